@@ -1,0 +1,65 @@
+"""Dense jump / flow operators of the appendix's Ito decomposition, for brute-force pins.
+
+State of one coordinate: v = (x_1..x_n, xt_1..xt_n, 1) in R^(2n+1).  Every event of the
+dynamic is an affine map of v, written as a (2n+1) x (2n+1) matrix:
+
+  flow over tau for worker w : identity except the 2x2 block on (w, n+w) = expm(tau * A),
+                               A = [[-eta, eta], [eta, -eta]]  (scipy's matrix exponential)
+  gossip on (i, j)           : x  <- (I - alpha E_ij) x,  xt <- xt - alpha_t E_ij x,
+                               E_ij = (e_i - e_j)(e_i - e_j)^T
+  gradient on i, g = s (x_i - c) + xi : x_i <- x_i - gamma g, xt_i <- xt_i - gamma g
+"""
+import numpy as np
+from scipy.linalg import expm
+
+
+def flow(n, w, eta, tau):
+    m = np.eye(2 * n + 1)
+    blk = expm(tau * np.array([[-eta, eta], [eta, -eta]]))
+    m[w, w], m[w, n + w], m[n + w, w], m[n + w, n + w] = blk[0, 0], blk[0, 1], blk[1, 0], blk[1, 1]
+    return m
+
+
+def gossip(n, i, j, alpha, alpha_t):
+    v = np.zeros(n); v[i] = 1.0; v[j] = -1.0
+    e = np.outer(v, v)
+    m = np.eye(2 * n + 1)
+    m[:n, :n] -= alpha * e
+    m[n:2 * n, :n] -= alpha_t * e
+    return m
+
+
+def gradient(n, i, gamma, s, c_k, xi_k):
+    m = np.eye(2 * n + 1)
+    for row in (i, n + i):
+        m[row, i] -= gamma * s
+        m[row, 2 * n] += gamma * s * c_k - gamma * xi_k
+    return m
+
+
+def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None):
+    """events: list of (t, kind, i, j).  c: (n, d) or None.  xi: list (per event) of d-vectors or None.
+    Returns (x, xt) after the events, every worker flowed to t_final if given."""
+    n, d = x0.shape
+    x = np.zeros((n, d)); xt = np.zeros((n, d))
+    for k in range(d):
+        v = np.concatenate([x0[:, k], xt0[:, k], [1.0]])
+        t = np.zeros(n)
+        total = np.eye(2 * n + 1)
+        for e, (te, kind, i, j) in enumerate(events):
+            ws = [i] if kind == 0 else [i, j]
+            for w in ws:
+                total = flow(n, w, eta, te - t[w]) @ total
+                t[w] = te
+            if kind == 0:
+                ck = 0.0 if c is None else c[i, k]
+                xk = 0.0 if xi is None or xi[e] is None else xi[e][k]
+                total = gradient(n, i, gamma[e], s[e], ck, xk) @ total
+            else:
+                total = gossip(n, i, j, alpha, alpha_t) @ total
+        if t_final is not None:
+            for w in range(n):
+                total = flow(n, w, eta, t_final - t[w]) @ total
+        v = total @ v
+        x[:, k], xt[:, k] = v[:n], v[n:2 * n]
+    return x, xt

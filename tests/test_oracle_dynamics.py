@@ -1,0 +1,279 @@
+"""Pins for the oracle's state update: mixing flow, gradient and gossip jumps (Eq. (1), Algorithm 1),
+the mean tracker (Eq. (2)), the consensus contraction of the appendix, and the observables."""
+import numpy as np
+import pytest
+from scipy.linalg import expm
+
+import dense_ops
+from oracle import core, graph
+
+
+def _events(n, edges, node_rate, edge_rate, seed, m):
+    return core.generate_events(n, [e[0] for e in edges], [e[1] for e in edges],
+                                np.broadcast_to(node_rate, (n,)).astype(float),
+                                np.broadcast_to(edge_rate, (len(edges),)).astype(float), seed, m)
+
+
+# ---------------------------------------------------------------- mixing flow
+@pytest.mark.parametrize("eta,tau", [(0.5, 0.3), (3.3, 1.7), (0.14, 12.0), (18.0, 0.01), (1.0, 0.0)])
+def test_mix_equals_matrix_exponential(eta, tau):
+    rng = np.random.default_rng(1)
+    x, xt = rng.normal(size=7), rng.normal(size=7)
+    mx, mxt = core.mix(x, xt, eta, tau)
+    big = expm(tau * np.array([[-eta, eta], [eta, -eta]]))
+    ref = big @ np.stack([x, xt])
+    assert np.allclose(mx, ref[0], rtol=1e-13, atol=1e-15)
+    assert np.allclose(mxt, ref[1], rtol=1e-13, atol=1e-15)
+
+
+def test_mix_semigroup_identity_limit_and_conservation():
+    rng = np.random.default_rng(2)
+    x, xt = rng.normal(size=50), rng.normal(size=50)
+    a1 = core.mix(*core.mix(x, xt, 0.8, 0.4), 0.8, 1.1)
+    a2 = core.mix(x, xt, 0.8, 1.5)
+    assert np.allclose(a1[0], a2[0], rtol=1e-14) and np.allclose(a1[1], a2[1], rtol=1e-14)
+    i0 = core.mix(x, xt, 0.0, 5.0)
+    assert np.array_equal(i0[0], x) and np.array_equal(i0[1], xt)
+    inf = core.mix(x, xt, 1.0, 1e3)
+    assert np.allclose(inf[0], (x + xt) / 2) and np.allclose(inf[1], (x + xt) / 2)
+    m = core.mix(x, xt, 2.0, 0.37)
+    assert np.allclose(m[0] + m[1], x + xt, rtol=1e-15)
+    assert np.allclose(m[0] - m[1], (x - xt) * np.exp(-2 * 2.0 * 0.37), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- whole path against dense operator products
+@pytest.mark.parametrize("n,d,topo,seed", [(2, 3, "complete", 0), (3, 8, "ring", 1), (4, 8, "complete", 2),
+                                           (4, 5, "ring", 3)])
+def test_event_loop_equals_product_of_dense_operators(n, d, topo, seed):
+    rng = np.random.default_rng(seed)
+    edges = getattr(graph, topo)(n)
+    ev = _events(n, edges, 1.0, 1.3, 100 + seed, 150)
+    eta, alpha, alpha_t = 0.7, 0.45, 1.3
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    c = rng.normal(size=(n, d))
+    m = len(ev)
+    gamma = rng.uniform(0.01, 0.2, m); s = rng.uniform(0.0, 1.5, m)
+    is_grad = ev.kind == 0
+    xi = rng.normal(size=(int(is_grad.sum()), d))
+    xi_row = np.full(m, -1, np.int64); xi_row[is_grad] = np.arange(is_grad.sum())
+    c_row = np.where(is_grad, ev.i, -1).astype(np.int64)
+
+    st = core.State(x0, xt0, eta, alpha, alpha_t).apply(ev, gamma, s, xi, xi_row, c, c_row)
+    T = ev.t[-1] + 0.25
+    ox, oxt = st.flushed(T)
+
+    evl = list(zip(ev.t, ev.kind, ev.i, ev.j))
+    xi_l = [xi[xi_row[e]] if xi_row[e] >= 0 else None for e in range(m)]
+    bx, bxt = dense_ops.run(x0, xt0, eta, alpha, alpha_t, evl, gamma, s, c, xi_l, t_final=T)
+    assert np.allclose(ox, bx, rtol=1e-10, atol=1e-12)
+    assert np.allclose(oxt, bxt, rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- gossip jump
+def test_gossip_half_is_exact_pairwise_average_and_conserves_sums():
+    rng = np.random.default_rng(3)
+    n, d = 5, 16
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    ev = core.Events([0.0], [1], [1], [3])     # at t=0 no flow has happened yet
+    st = core.State(x0, xt0, eta=0.9, alpha=0.5, alpha_t=2.0).apply(ev)
+    avg = (x0[1] + x0[3]) / 2
+    assert np.allclose(st.x[1], avg, rtol=1e-15) and np.allclose(st.x[3], avg, rtol=1e-15)
+    # the momentum buffer moves by alpha_tilde times the x difference (not the xt difference)
+    assert np.allclose(st.xt[1], xt0[1] - 2.0 * (x0[1] - x0[3]), rtol=1e-14)
+    assert np.allclose(st.xt[3], xt0[3] + 2.0 * (x0[1] - x0[3]), rtol=1e-14)
+    untouched = [0, 2, 4]
+    assert np.array_equal(st.x[untouched], x0[untouched]) and np.array_equal(st.xt[untouched], xt0[untouched])
+    assert np.allclose(st.x.sum(0), x0.sum(0), rtol=1e-14) and np.allclose(st.xt.sum(0), xt0.sum(0), rtol=1e-14)
+
+
+def test_gossip_stream_conserves_column_sums_after_flush():
+    # communication updates are orthogonal to 1; the flow conserves x_i + xt_i
+    rng = np.random.default_rng(4)
+    n, d = 8, 12
+    edges = graph.ring(n)
+    ev = _events(n, edges, 0.0, 1.0, 77, 400)
+    x0 = rng.normal(size=(n, d))
+    st = core.State(x0, None, eta=0.4, alpha=0.5, alpha_t=1.9).apply(ev)
+    x, xt = st.flushed(ev.t[-1])
+    assert np.allclose((x + xt).sum(0), 2 * x0.sum(0), rtol=1e-12)
+    # with xbar(0) = xtbar(0) the two means stay equal (sentence before Eq. (2))
+    assert np.allclose(x.sum(0), xt.sum(0), rtol=1e-10, atol=1e-12)
+
+
+# ---------------------------------------------------------------- gradient jump and the mean tracker
+def test_gradient_event_moves_both_buffers_by_the_same_amount():
+    rng = np.random.default_rng(5)
+    n, d = 3, 10
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d)); c = rng.normal(size=(n, d))
+    xi = rng.normal(size=(1, d))
+    ev = core.Events([0.0], [0], [2], [-1])
+    st = core.State(x0, xt0, eta=0.6).apply(ev, gamma=0.1, gscale=0.8, xi=xi, xi_row=[0], c=c, c_row=[2])
+    g = 0.8 * (x0[2] - c[2]) + xi[0]
+    assert np.allclose(st.x[2], x0[2] - 0.1 * g, rtol=1e-15)
+    assert np.allclose(st.xt[2], xt0[2] - 0.1 * g, rtol=1e-15)
+    assert np.array_equal(st.x[:2], x0[:2])
+    # after a flow of length tau the gradient is taken at the mixed point
+    ev = core.Events([0.9], [0], [2], [-1])
+    st = core.State(x0, xt0, eta=0.6).apply(ev, gamma=0.1, gscale=1.0, c=c, c_row=[2])
+    mx, mxt = core.mix(x0[2], xt0[2], 0.6, 0.9)
+    assert np.allclose(st.x[2], mx - 0.1 * (mx - c[2]), rtol=1e-14)
+    assert np.allclose(st.xt[2], mxt - 0.1 * (mx - c[2]), rtol=1e-14)
+    assert st.t[2] == 0.9 and st.t[0] == 0.0
+
+
+def test_mean_tracker_eq2():
+    # xbar(T) = xbar(0) - (1/n) sum_e gamma_e g_e  with g_e = xi_e here (gscale = 0), and xbar = xtbar
+    rng = np.random.default_rng(6)
+    n, d = 6, 9
+    edges = graph.exponential(n)
+    ev = _events(n, edges, 1.0, 1.0, 5, 600)
+    is_grad = ev.kind == 0
+    xi = rng.normal(size=(int(is_grad.sum()), d))
+    xi_row = np.full(len(ev), -1, np.int64); xi_row[is_grad] = np.arange(is_grad.sum())
+    gamma = rng.uniform(0.01, 0.1, len(ev))
+    x0 = rng.normal(size=(n, d))
+    p = graph.acid_params(n, edges, 1.0)
+    st = core.State(x0, None, p["eta"], p["alpha"], p["alpha_tilde"]).apply(ev, gamma, 0.0, xi, xi_row)
+    x, xt = st.flushed(ev.t[-1] + 1.0)
+    drift = (gamma[is_grad, None] * xi).sum(0)
+    assert np.allclose(x.sum(0), x0.sum(0) - drift, rtol=1e-10, atol=1e-10)
+    assert np.allclose(xt.sum(0), x0.sum(0) - drift, rtol=1e-10, atol=1e-10)
+
+
+# ---------------------------------------------------------------- baseline special case and contraction
+def test_eta_zero_is_textbook_pairwise_gossip_plus_sgd():
+    # eta = 0, alpha = 1/2 (Eq. (3)): randomized pairwise averaging (Boyd et al.) interleaved with SGD steps
+    rng = np.random.default_rng(7)
+    n, d = 7, 5
+    edges = graph.ring(n)
+    ev = _events(n, edges, 1.0, 2.0, 21, 500)
+    x0 = rng.normal(size=(n, d)); c = rng.normal(size=(n, d))
+    st = core.State(x0, None, 0.0, 0.5, 0.5).apply(ev, 0.1, 1.0, c=c, c_row=np.where(ev.kind == 0, ev.i, -1))
+    x = x0.copy()
+    for k, i, j in zip(ev.kind, ev.i, ev.j):
+        if k == 0:
+            x[i] = x[i] - 0.1 * (x[i] - c[i])
+        else:
+            x[i] = x[j] = (x[i] + x[j]) / 2
+    assert np.allclose(st.x, x, rtol=1e-12, atol=1e-14)
+
+
+def test_consensus_never_increases_under_plain_averaging():
+    # eta = 0, alpha = 1/2, communications only: every event is an orthogonal projection
+    rng = np.random.default_rng(8)
+    n, d = 16, 20
+    edges = graph.ring(n)
+    ev = _events(n, edges, 0.0, 1.0, 3, 300)
+    st = core.State(rng.normal(size=(n, d)), None, 0.0, 0.5, 0.5)
+    prev = st.stats(0.0)["consensus_x"]
+    for e in range(len(ev)):
+        st.apply(ev[e:e + 1])
+        cur = st.stats(ev.t[e])["consensus_x"]
+        assert cur <= prev * (1 + 1e-14)
+        prev = cur
+
+
+def test_expected_consensus_decay_rate():
+    # appendix, "Study of the ||pi x||_F^2 terms", alpha = 1/2, no gradients, eta = 0:
+    #   d/dt E||pi x||^2 = 2 alpha (alpha - 1) E||x||_Lambda^2 = -1/2 E||x||_Lambda^2 <= -(1/(2 chi_1)) E||pi x||^2.
+    # The second moment C = E[x x^T] of one coordinate obeys the linear ODE
+    #   dC/dt = sum_ij lambda_ij (W_ij C W_ij - C),  W_ij = I - E_ij / 2,
+    # solved here exactly with a Kronecker-product generator and scipy's expm; the oracle, averaged over
+    # clock seeds and coordinates, must reproduce tr(pi C_T) and respect the chi_1 bound.
+    rng = np.random.default_rng(9)
+    n, d, T = 8, 500, 6.0
+    edges = graph.ring(n)
+    lam = graph.laplacian(n, edges, 1.0)
+    c1 = graph.chi1(lam)
+    gen = np.zeros((n * n, n * n))
+    for i, j in edges:
+        v = np.zeros(n); v[i] = 1.0; v[j] = -1.0
+        w = np.eye(n) - 0.5 * np.outer(v, v)
+        gen += np.kron(w, w) - np.eye(n * n)
+    c_T = (expm(T * gen) @ np.eye(n).ravel()).reshape(n, n)      # C_0 = I: unit normal start
+    pi = np.eye(n) - np.ones((n, n)) / n
+    expect = d * np.trace(pi @ c_T)
+    start = d * np.trace(pi)
+    assert expect <= np.exp(-T / (2 * c1)) * start
+
+    x0 = rng.normal(size=(n, d))
+    vals = []
+    for seed in range(60):
+        ev = _events(n, edges, 0.0, 1.0, 1000 + seed, 400)
+        k = int(np.searchsorted(ev.t, T))
+        assert k < len(ev)
+        vals.append(core.State(x0, None, 0.0, 0.5, 0.5).apply(ev[:k]).stats(T)["consensus_x"])
+    # x0 is one draw: rescale the prediction by its actual starting consensus (expectation is linear in C_0,
+    # and pi x0 x0^T pi / d concentrates on pi for d = 500)
+    c0 = core.State(x0).stats(0.0)["consensus_x"]
+    predicted = expect * c0 / start
+    assert abs(np.mean(vals) - predicted) < 4 * np.std(vals) / np.sqrt(len(vals)) + 0.03 * predicted
+    assert np.mean(vals) <= np.exp(-T / (2 * c1)) * c0
+
+
+def test_acid_beats_baseline_on_the_ring():
+    # the paper's claim in miniature (ring, communications only): the accelerated parameters shrink the
+    # consensus distance faster than plain averaging at the same communication rate
+    rng = np.random.default_rng(10)
+    n, d = 16, 400
+    edges = graph.ring(n)
+    ev = _events(n, edges, 0.0, 1.0, 4, 16 * 60)
+    x0 = rng.normal(size=(n, d))
+    p = graph.acid_params(n, edges, 1.0)
+    T = ev.t[-1]
+    acc = core.State(x0, None, p["eta"], p["alpha"], p["alpha_tilde"]).apply(ev).stats(T)["consensus_x"]
+    base = core.State(x0, None, 0.0, 0.5, 0.5).apply(ev).stats(T)["consensus_x"]
+    assert acc < 0.2 * base
+
+
+def test_quadratic_objective_converges_near_mean_of_minimisers():
+    # config-1 style: f_i = 1/2 ||x - c_i||^2, no noise; the network average obeys Eq. (2) and settles around cbar
+    rng = np.random.default_rng(11)
+    n, d = 4, 50
+    edges = graph.complete(n)
+    ev = _events(n, edges, 1.0, 1.0, 12, 6000)
+    c = rng.normal(size=(n, d)); x0 = rng.normal(size=(n, d))
+    st = core.State(x0, None, 0.5, 0.5, 0.5).apply(ev, 0.05, 1.0, c=c, c_row=np.where(ev.kind == 0, ev.i, -1))
+    x, _ = st.flushed(ev.t[-1])
+    err0 = np.linalg.norm(x0.mean(0) - c.mean(0))
+    err = np.linalg.norm(x.mean(0) - c.mean(0))
+    assert err < 0.15 * err0
+
+
+# ---------------------------------------------------------------- observables
+def test_stats_against_library_variance_and_identities():
+    rng = np.random.default_rng(12)
+    n, d = 9, 33
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    st = core.State(x0, xt0, eta=0.0)
+    s = st.stats(0.0)
+    assert np.isclose(s["consensus_x"], n * np.var(x0, axis=0).sum(), rtol=1e-13)
+    assert np.isclose(s["consensus_xt"], (xt0 ** 2).sum() - n * (xt0.mean(0) ** 2).sum(), rtol=1e-12)
+    assert np.allclose(s["sum_x"], x0.sum(1)) and np.allclose(s["sum_xt"], xt0.sum(1))
+    same = core.State(np.tile(x0[:1], (n, 1))).stats(0.0)
+    assert same["consensus_x"] < 1e-25 and same["consensus_xt"] < 1e-25    # mean of n equal values rounds
+
+
+def test_stats_use_the_virtually_mixed_state_and_do_not_mutate():
+    rng = np.random.default_rng(13)
+    n, d = 4, 6
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    st = core.State(x0, xt0, eta=0.7)
+    st.t[:] = [0.0, 0.5, 1.0, 1.5]
+    s = st.stats(2.0)
+    fx, fxt = st.flushed(2.0)
+    assert np.isclose(s["consensus_x"], n * np.var(fx, axis=0).sum(), rtol=1e-13)
+    assert np.allclose(s["sum_xt"], fxt.sum(1), rtol=1e-13)
+    assert np.allclose(s["sum_x"] + s["sum_xt"], (x0 + xt0).sum(1), rtol=1e-13)   # flow conserves x_i + xt_i
+    assert np.array_equal(st.x, x0) and np.array_equal(st.xt, xt0)
+
+
+def test_malformed_events_are_rejected():
+    st = core.State(np.zeros((3, 2)))
+    with pytest.raises(ValueError):
+        st.apply(core.Events([1.0], [1], [0], [0]))          # self loop
+    with pytest.raises(ValueError):
+        st.apply(core.Events([1.0], [0], [5], [-1]))         # worker out of range
+    st.apply(core.Events([1.0], [0], [1], [-1]), 0.1, 0.0)
+    with pytest.raises(ValueError):
+        st.apply(core.Events([0.5], [1], [1], [2]))          # time runs backwards for worker 1
