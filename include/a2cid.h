@@ -1,0 +1,243 @@
+/*
+ * a2cid.h -- C ABI of the MI355X (gfx950) continuous-momentum gossip engine.
+ *
+ * The library applies the event-based dynamic of A2CiD2 (arXiv 2306.08289, Eq. (1),
+ * realised event by event as in Algorithm 1) to n simulated workers.  Worker i owns row i
+ * of two caller-provided device buffers: x (parameters) and xt (the momentum copy, written
+ * x-tilde in the paper), d fp32 values each, plus a host-side time stamp t_i at which the row
+ * was last brought up to date.  Three kinds of update exist:
+ *
+ *   mixing flow  (x_i, xt_i) <- exp((t - t_i) [[-eta, eta], [eta, -eta]]) (x_i, xt_i)
+ *                applied to a worker right before any jump that touches it (Algorithm 1);
+ *   gradient     x_i -= gamma g,  xt_i -= gamma g                  (Eq. (1), dN^i term)
+ *                with g = gscale * (x_i - c) + xi evaluated AFTER the mixing;
+ *   gossip       m = x_i - x_j;  x_i -= alpha m;  x_j += alpha m;
+ *                xt_i -= alpha_tilde m;  xt_j += alpha_tilde m     (Eq. (1), dM^ij term)
+ *                with m evaluated AFTER both workers have been mixed.
+ *
+ * Conventions
+ *   - "device pointer": memory of the GPU that is current when a2cid_create is called; "host
+ *     pointer": ordinary process memory.  The library never allocates, frees or reallocates
+ *     x, xt, xi or c; it owns only a small device scratch area (operation tables and
+ *     reduction partials) that lives as long as the context.
+ *   - All work is enqueued on the HIP stream given at creation.  a2cid_apply_events and
+ *     a2cid_flush return as soon as the work is enqueued; a2cid_stats waits for its result.
+ *   - Every function returns A2CID_OK (0) or a negative A2CID_E* code; on failure nothing has
+ *     been applied and a2cid_last_error() (thread-local) describes the cause.  No exception,
+ *     abort or signal crosses this boundary.
+ *   - A context must not be used from two threads at once.
+ */
+#ifndef A2CID_H
+#define A2CID_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define A2CID_OK          0
+#define A2CID_EINVAL     -1   /* null pointer, size out of range, non-finite parameter          */
+#define A2CID_EGRAPH     -2   /* edge list malformed (u >= v, duplicate, out of range, rate < 0) */
+#define A2CID_EORDER     -3   /* an event is earlier than its worker's current time stamp       */
+#define A2CID_EMATCHING  -4   /* two operations of one level share a worker, or bad level table  */
+#define A2CID_EALIGN     -5   /* pointer not 16-byte aligned or ld not a multiple of 4           */
+#define A2CID_EHIP       -6   /* a HIP runtime call failed (message holds the HIP error string) */
+#define A2CID_ENOMEM     -7   /* host allocation failed                                        */
+
+#define A2CID_KIND_GRADIENT 0
+#define A2CID_KIND_GOSSIP   1
+
+#define A2CID_MAX_WORKERS 1024
+
+typedef struct a2cid_ctx a2cid_ctx;
+typedef struct a2cid_sched a2cid_sched;
+
+/* Undirected communication graph with one Poisson rate per edge (Definition 3.1: the rates
+ * are the lambda^{ij} of the instantaneous expected Laplacian).  Host pointers, n_edges
+ * entries each, u[e] < v[e], no duplicates.  Borrowed for the duration of the call only. */
+typedef struct {
+    int32_t n_edges;
+    const int32_t *u;
+    const int32_t *v;
+    const double *rate;
+} a2cid_graph;
+
+/* The state buffers.  x and xt are device pointers to n rows of ld floats (row-major, row i =
+ * worker i, the first d entries of a row are used, the rest is never read or written).  Both
+ * must be 16-byte aligned and ld must be a multiple of 4, so that every row is 16-byte aligned.
+ * hip_stream is a hipStream_t (NULL: the default stream).  Owned by the caller and must outlive
+ * the context. */
+typedef struct {
+    float *x;
+    float *xt;
+    int64_t ld;
+    void *hip_stream;
+} a2cid_buffers;
+
+/* One event of the dynamic.
+ *   t       absolute time of the event (same clock for all workers).
+ *   kind    A2CID_KIND_GRADIENT (worker i; j ignored, conventionally -1) or
+ *           A2CID_KIND_GOSSIP (edge {i, j} of the graph, either orientation).
+ *   gamma   step size of a gradient event (Eq. (1)); ignored for gossip.
+ *   gscale  slope s of the affine gradient model g = s (x_i - c) + xi.  s = 0 with xi = the
+ *           gradient computed elsewhere is the general case; s = 1 with c = c_i is the
+ *           quadratic f_i = 1/2 ||x - c_i||^2.
+ *   xi, c   device pointers to d floats, 16-byte aligned, or NULL (treated as zeros).  Read
+ *           when the stream reaches the operation; the caller keeps them alive until then.
+ *   id      opaque to the library (the scheduler stores the serial event index here). */
+typedef struct {
+    double t;
+    int32_t kind;
+    int32_t i;
+    int32_t j;
+    float gamma;
+    float gscale;
+    int32_t reserved;
+    const float *xi;
+    const float *c;
+    int64_t id;
+} a2cid_op;
+
+/* A batch of events arranged in levels.  ops[level_off[l] .. level_off[l+1]) is level l;
+ * level_off has n_levels + 1 entries, level_off[0] = 0, level_off[n_levels] = n_ops.
+ * Operations of one level must touch pairwise distinct workers (a matching plus singletons);
+ * levels are applied in order, so each worker meets its events in the order given.  Times
+ * must be non-decreasing per worker (across batches too).  All host pointers, borrowed for
+ * the call.
+ *   t_sync  if finite: after its last operation in this batch every worker touched by the
+ *           batch is additionally mixed up to t_sync (fused into that operation's pass, the
+ *           "mix -> jump -> mix" form) and its time stamp becomes t_sync; must be >= every
+ *           event time of the batch.  NaN: no trailing mix. */
+typedef struct {
+    int64_t n_ops;
+    const a2cid_op *ops;
+    int32_t n_levels;
+    const int64_t *level_off;
+    double t_sync;
+} a2cid_event_batch;
+
+/* Observables (appendix "Notations": ||pi x||_F^2 = sum_i ||x_i - xbar||^2; Eq. (2) for the
+ * role of the sums).  sum_x and sum_xt are caller-allocated host arrays of n doubles. */
+typedef struct {
+    double consensus_x;
+    double consensus_xt;
+    double *sum_x;
+    double *sum_xt;
+} a2cid_stats_out;
+
+/* Per-operation coefficients produced by the host planner (exposed for testing and for
+ * callers that want to inspect a plan).  b = (1 - exp(-2 eta tau)) / 2 is the off-diagonal
+ * entry of exp(tau [[-eta, eta], [eta, -eta]]) = [[1 - b, b], [b, 1 - b]]. */
+typedef struct {
+    float b_pre_i, b_pre_j;    /* mixing to the event time, worker i / worker j (j: gossip only) */
+    float b_post_i, b_post_j;  /* trailing mixing to t_sync (0 when none)                        */
+} a2cid_coef;
+
+/* ---- hyper-parameters ----------------------------------------------------------------- */
+
+/* chi_1 = 1 / (smallest non-zero eigenvalue of the Laplacian), chi_2 = half the largest
+ * effective resistance over the edges (the two definitions after Definition 3.1), and the
+ * accelerated setting of Proposition 3.2: eta = 1 / (2 sqrt(chi_1 chi_2)),
+ * alpha_tilde = sqrt(chi_1 / chi_2) / 2 (alpha is 1/2).  Any output pointer may be NULL.
+ * A2CID_EGRAPH if the graph is malformed or not connected.  Host only. */
+int a2cid_graph_params(const a2cid_graph *graph, int32_t n,
+                       double *chi1, double *chi2, double *eta, double *alpha_tilde);
+
+/* ---- engine ---------------------------------------------------------------------------- */
+
+/* Creates a context for n workers (2 <= n <= A2CID_MAX_WORKERS) of d >= 1 parameters on the
+ * current HIP device.  eta >= 0, alpha, alpha_tilde finite (Eq. (1); "time-independent scalar
+ * hyper-parameters").  All t_i start at 0 (Algorithm 1, initialisation).  The graph is copied. */
+int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph,
+                 double eta, double alpha, double alpha_tilde, const a2cid_buffers *buf);
+
+/* Validates the batch, computes the mixing coefficients from the time stamps, advances the
+ * time stamps and enqueues the kernels (Algorithm 1, both threads, for every event of the
+ * batch).  On any error nothing is enqueued and no time stamp moves. */
+int a2cid_apply_events(a2cid_ctx *ctx, const a2cid_event_batch *batch);
+
+/* Consensus distances and per-worker sums of the state as it would be if every worker were
+ * mixed up to t_now (>= max_i t_i); x, xt and the time stamps are left untouched.  Blocks
+ * until the result is in *out. */
+int a2cid_stats(a2cid_ctx *ctx, double t_now, a2cid_stats_out *out);
+
+/* Mixes every worker up to t_now (>= max_i t_i) in place and sets all t_i = t_now: the state
+ * Algorithm 1 returns at its final time. */
+int a2cid_flush(a2cid_ctx *ctx, double t_now);
+
+/* Copies the n time stamps t_i into the host array t. */
+int a2cid_get_times(const a2cid_ctx *ctx, double *t);
+
+/* Replaces the n time stamps (resuming from a saved state). */
+int a2cid_set_times(a2cid_ctx *ctx, const double *t);
+
+/* Waits until everything enqueued so far has finished. */
+int a2cid_synchronize(a2cid_ctx *ctx);
+
+void a2cid_destroy(a2cid_ctx *ctx);
+
+/* ---- host-only planner (no GPU needed) -------------------------------------------------- */
+
+/* The validation and coefficient step of a2cid_apply_events as a pure host function:
+ * t (n doubles) is read and, on success, advanced; coef receives one entry per operation.
+ * Same error codes as a2cid_apply_events. */
+int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
+                     const a2cid_event_batch *batch, a2cid_coef *coef);
+
+/* ---- event scheduler (host only) ------------------------------------------------------- */
+
+/* Independent Poisson clocks (Assumption 3.1): one per worker (gradient events, rate
+ * node_rate[i] >= 0) and one per edge (gossip events, rate graph->rate[e] >= 0); a rate of 0
+ * never fires.  The k-th waiting time of clock c (workers first, then edges in list order)
+ * is -log1p(-u) / rate, u the 53-bit uniform built from the first two words of
+ * Philox4x32-10(counter = (k_lo, k_hi, c, 0x0A2C1D20), key = (seed_lo, seed_hi)); arrival
+ * times are running fp64 sums; simultaneous arrivals are ordered by clock id.  The merged
+ * stream is therefore a pure function of (n, graph, node_rate, seed). */
+int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
+                       const double *node_rate, uint64_t seed);
+
+/* Takes the next max_events events of the serial stream and packs them into levels: an
+ * event's level is one more than the highest level of an earlier event of this batch sharing
+ * a worker with it; inside a level events keep serial order.  The returned batch (ops,
+ * level_off) points into memory owned by the scheduler and stays valid until the next call
+ * on the same scheduler; the caller may fill in gamma, gscale, xi, c in place.  ops[k].id is
+ * the serial index of the event (0-based since creation); t_sync is NaN. */
+int a2cid_sched_next(a2cid_sched *s, int64_t max_events, a2cid_event_batch *out);
+
+/* Skips the next n_events events of the serial stream without producing them. */
+int a2cid_sched_skip(a2cid_sched *s, int64_t n_events);
+
+/* Number of events of each clock produced so far (n + n_edges entries): the communication
+ * history of the appendix "Uniform neighbor selection check" for the edge part. */
+int a2cid_sched_counts(const a2cid_sched *s, int64_t *counts);
+
+void a2cid_sched_destroy(a2cid_sched *s);
+
+/* ---- diagnostics and measurement ------------------------------------------------------- */
+
+/* Launch shape of the level kernel: unroll = 16-byte pieces per lane and row (1, 2, 4 or 8),
+ * nontemporal != 0 selects non-temporal loads and stores.  Results do not depend on it. */
+int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal);
+
+/* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
+ * and the algorithmic byte count (per event: 32 d for gossip; 16 d for a gradient event plus
+ * 4 d for each of xi and c that it reads; 16 d per worker mixed by a2cid_flush).  Any output
+ * pointer may be NULL. */
+int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
+                   double *algorithmic_bytes, int32_t reset);
+
+/* While enabled, every level-kernel launch is bracketed by a pair of HIP events on the
+ * context's stream.  a2cid_profile_read waits for the stream, returns the number of launches
+ * timed since the previous read and the sum of their durations in milliseconds, and forgets
+ * them. */
+int a2cid_profile(a2cid_ctx *ctx, int32_t enable);
+int a2cid_profile_read(a2cid_ctx *ctx, int64_t *n_launches, double *kernel_ms);
+
+const char *a2cid_last_error(void);
+const char *a2cid_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* A2CID_H */

@@ -1,0 +1,402 @@
+// Context, launch logic and the GPU half of the C ABI (see include/a2cid.h).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "a2cid_internal.h"
+#include "a2cid_kernels.hip.h"
+
+using namespace a2cid;
+
+#define A2CID_HIP(call)                                                                      \
+    do {                                                                                     \
+        hipError_t e_ = (call);                                                              \
+        if (e_ != hipSuccess)                                                                \
+            return fail(A2CID_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),    \
+                        __FILE__, __LINE__);                                                 \
+    } while (0)
+
+namespace {
+
+constexpr int kSlots = 4;               // operation-table staging buffers in flight
+constexpr int64_t kSlotOps = 16384;     // operations per staging buffer (1 MiB)
+constexpr int kStatsBlocks = 2048;      // workgroups of the observables kernel (grid-stride)
+constexpr int kStatsV = 2;              // float4 pieces per lane and row in the observables kernel
+
+struct Slot {
+    DevOp *host = nullptr;              // pinned
+    DevOp *dev = nullptr;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
+struct TimedLaunch {
+    hipEvent_t start, stop;
+};
+
+}  // namespace
+
+struct a2cid_ctx {
+    Graph g;
+    int32_t n = 0;
+    int64_t d = 0, ld = 0;
+    float *x = nullptr, *xt = nullptr;
+    hipStream_t stream = nullptr;
+    double eta = 0, alpha = 0, alpha_t = 0;
+    std::vector<double> t;
+    Plan plan;
+    PlanScratch scratch;
+    Slot slots[kSlots];
+    int next_slot = 0;
+    // launch shape of the level kernel (tunable through a2cid_set_tuning)
+    int unroll = 4;
+    int nontemporal = 0;
+    // observables scratch
+    float *b_host = nullptr, *b_dev = nullptr;
+    double *partials = nullptr, *out_dev = nullptr, *out_host = nullptr;
+    // counters since creation (or the last a2cid_counters_reset)
+    int64_t n_gossip = 0, n_grad = 0, n_launch = 0;
+    double alg_bytes = 0.0;
+    // optional per-launch timing
+    bool profiling = false;
+    std::vector<TimedLaunch> timed;
+    std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int acquire_slot(a2cid_ctx *c, Slot **out) {
+    Slot &s = c->slots[c->next_slot];
+    c->next_slot = (c->next_slot + 1) % kSlots;
+    if (s.in_flight) {
+        A2CID_HIP(hipEventSynchronize(s.done));
+        s.in_flight = false;
+    }
+    *out = &s;
+    return A2CID_OK;
+}
+
+int get_event(a2cid_ctx *c, hipEvent_t *e) {
+    if (!c->event_pool.empty()) {
+        *e = c->event_pool.back();
+        c->event_pool.pop_back();
+        return A2CID_OK;
+    }
+    A2CID_HIP(hipEventCreate(e));
+    return A2CID_OK;
+}
+
+template <int U, bool NT>
+void launch_level_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops) {
+    const int64_t n4 = c->d >> 2;
+    const int64_t per_block = (int64_t)U * kThreads;
+    int64_t blocks = (n4 + per_block - 1) / per_block;
+    if (blocks < 1) blocks = 1;   // the scalar tail lives in tile 0
+    dim3 grid((unsigned)blocks, (unsigned)n_ops);
+    hipLaunchKernelGGL((level_kernel<U, NT>), grid, dim3(kThreads), 0, c->stream, c->x, c->xt, c->ld, c->d,
+                       ops, (float)c->alpha, (float)c->alpha_t);
+}
+
+int launch_level(a2cid_ctx *c, const DevOp *ops, int32_t n_ops) {
+    TimedLaunch tl{};
+    if (c->profiling) {
+        if (int rc = get_event(c, &tl.start)) return rc;
+        if (int rc = get_event(c, &tl.stop)) return rc;
+        A2CID_HIP(hipEventRecord(tl.start, c->stream));
+    }
+    const bool nt = c->nontemporal != 0;
+    switch (c->unroll) {
+        case 1: nt ? launch_level_t<1, true>(c, ops, n_ops) : launch_level_t<1, false>(c, ops, n_ops); break;
+        case 2: nt ? launch_level_t<2, true>(c, ops, n_ops) : launch_level_t<2, false>(c, ops, n_ops); break;
+        case 8: nt ? launch_level_t<8, true>(c, ops, n_ops) : launch_level_t<8, false>(c, ops, n_ops); break;
+        default: nt ? launch_level_t<4, true>(c, ops, n_ops) : launch_level_t<4, false>(c, ops, n_ops); break;
+    }
+    A2CID_HIP(hipGetLastError());
+    if (c->profiling) {
+        A2CID_HIP(hipEventRecord(tl.stop, c->stream));
+        c->timed.push_back(tl);
+    }
+    ++c->n_launch;
+    return A2CID_OK;
+}
+
+// Mixing every worker whose coefficient is non-zero, as one level of mix-only operations.
+int enqueue_mix_all(a2cid_ctx *c, const std::vector<float> &b) {
+    int32_t done = 0;
+    while (done < c->n) {
+        Slot *s;
+        if (int rc = acquire_slot(c, &s)) return rc;
+        int32_t count = 0;
+        for (; done < c->n && count < kSlotOps; ++done) {
+            if (b[done] == 0.f) continue;
+            DevOp &o = s->host[count++];
+            std::memset(&o, 0, sizeof(o));
+            o.kind = kOpMixOnly;
+            o.row_i = done;
+            o.b_i = b[done];
+        }
+        if (count == 0) continue;
+        A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
+        if (int rc = launch_level(c, s->dev, count)) return rc;
+        A2CID_HIP(hipEventRecord(s->done, c->stream));
+        s->in_flight = true;
+        c->alg_bytes += 16.0 * (double)c->d * count;
+    }
+    return A2CID_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+void a2cid_destroy(a2cid_ctx *c) {
+    if (!c) return;
+    (void)hipStreamSynchronize(c->stream);
+    for (Slot &s : c->slots) {
+        if (s.host) (void)hipHostFree(s.host);
+        if (s.dev) (void)hipFree(s.dev);
+        if (s.done) (void)hipEventDestroy(s.done);
+    }
+    if (c->b_host) (void)hipHostFree(c->b_host);
+    if (c->b_dev) (void)hipFree(c->b_dev);
+    if (c->partials) (void)hipFree(c->partials);
+    if (c->out_dev) (void)hipFree(c->out_dev);
+    if (c->out_host) (void)hipHostFree(c->out_host);
+    for (TimedLaunch &tl : c->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
+    for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *graph, double eta,
+                       double alpha, double alpha_tilde, const a2cid_buffers *buf) {
+    if (int rc = load_graph(c->g, n, graph)) return rc;
+    if (d < 1) return fail(A2CID_EINVAL, "d = %lld must be >= 1", (long long)d);
+    if (!buf || !buf->x || !buf->xt) return fail(A2CID_EINVAL, "state buffers are NULL");
+    if (buf->x == buf->xt) return fail(A2CID_EINVAL, "x and xt must be distinct buffers");
+    if (buf->ld < d) return fail(A2CID_EINVAL, "ld = %lld is smaller than d = %lld", (long long)buf->ld, (long long)d);
+    if ((buf->ld & 3) || ((uintptr_t)buf->x & 15u) || ((uintptr_t)buf->xt & 15u))
+        return fail(A2CID_EALIGN, "x, xt must be 16-byte aligned and ld a multiple of 4");
+    if (!(eta >= 0.0) || !std::isfinite(eta) || !std::isfinite(alpha) || !std::isfinite(alpha_tilde))
+        return fail(A2CID_EINVAL, "eta must be finite and >= 0, alpha and alpha_tilde finite");
+    c->n = n; c->d = d; c->ld = buf->ld;
+    c->x = buf->x; c->xt = buf->xt;
+    c->stream = (hipStream_t)buf->hip_stream;
+    c->eta = eta; c->alpha = alpha; c->alpha_t = alpha_tilde;
+    c->t.assign(n, 0.0);
+    for (Slot &s : c->slots) {
+        A2CID_HIP(hipHostMalloc((void **)&s.host, sizeof(DevOp) * kSlotOps, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.dev, sizeof(DevOp) * kSlotOps));
+        A2CID_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
+    }
+    const size_t m = 2 * (size_t)n + 2;
+    A2CID_HIP(hipHostMalloc((void **)&c->b_host, sizeof(float) * n, hipHostMallocDefault));
+    A2CID_HIP(hipMalloc((void **)&c->b_dev, sizeof(float) * n));
+    A2CID_HIP(hipMalloc((void **)&c->partials, sizeof(double) * m * kStatsBlocks));
+    A2CID_HIP(hipMalloc((void **)&c->out_dev, sizeof(double) * m));
+    A2CID_HIP(hipHostMalloc((void **)&c->out_host, sizeof(double) * m, hipHostMallocDefault));
+    return A2CID_OK;
+}
+
+int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph, double eta,
+                 double alpha, double alpha_tilde, const a2cid_buffers *buf) {
+    clear_error();
+    if (!out) return fail(A2CID_EINVAL, "out is NULL");
+    *out = nullptr;
+    a2cid_ctx *c = new (std::nothrow) a2cid_ctx;
+    if (!c) return fail(A2CID_ENOMEM, "out of host memory");
+    int rc;
+    try {
+        rc = create_impl(c, n, d, graph, eta, alpha, alpha_tilde, buf);
+    } catch (const std::bad_alloc &) {
+        rc = fail(A2CID_ENOMEM, "out of host memory");
+    }
+    if (rc != A2CID_OK) {
+        // keep the message of the failure: a2cid_destroy makes HIP calls but never touches it
+        a2cid_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return A2CID_OK;
+}
+
+static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
+    if (int rc = plan_batch(c->g, c->eta, c->t.data(), batch, c->plan, c->scratch)) return rc;
+    int32_t l = 0;
+    while (l < batch->n_levels) {
+        // take as many whole levels as fit into one staging buffer
+        int32_t l_end = l;
+        int64_t count = 0;
+        while (l_end < batch->n_levels) {
+            const int64_t sz = batch->level_off[l_end + 1] - batch->level_off[l_end];
+            if (sz > kSlotOps) return fail(A2CID_EMATCHING, "level %d has %lld operations", l_end, (long long)sz);
+            if (count + sz > kSlotOps) break;
+            count += sz;
+            ++l_end;
+        }
+        if (count > 0) {
+            Slot *s;
+            if (int rc = acquire_slot(c, &s)) return rc;
+            const int64_t first = batch->level_off[l];
+            for (int64_t k = 0; k < count; ++k) {
+                const a2cid_op &op = batch->ops[first + k];
+                const a2cid_coef &cf = c->plan.coef[first + k];
+                DevOp &o = s->host[k];
+                o.kind = op.kind == A2CID_KIND_GOSSIP ? kOpGossip : kOpGradient;
+                o.row_i = op.i;
+                o.row_j = op.kind == A2CID_KIND_GOSSIP ? op.j : op.i;
+                o.b_i = cf.b_pre_i; o.b_j = cf.b_pre_j;
+                o.bp_i = cf.b_post_i; o.bp_j = cf.b_post_j;
+                o.gamma = op.gamma; o.gscale = op.gscale;
+                o.pad0 = 0;
+                o.xi = op.kind == A2CID_KIND_GRADIENT ? op.xi : nullptr;
+                o.c = op.kind == A2CID_KIND_GRADIENT ? op.c : nullptr;
+                o.pad1 = 0;
+            }
+            A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
+            for (int32_t ll = l; ll < l_end; ++ll) {
+                const int64_t lo = batch->level_off[ll] - first, sz = batch->level_off[ll + 1] - batch->level_off[ll];
+                if (sz == 0) continue;
+                if (int rc = launch_level(c, s->dev + lo, (int32_t)sz)) return rc;
+            }
+            A2CID_HIP(hipEventRecord(s->done, c->stream));
+            s->in_flight = true;
+        }
+        l = l_end;
+    }
+    c->t = c->plan.t_after;
+    c->n_gossip += c->plan.n_gossip;
+    c->n_grad += c->plan.n_grad;
+    c->alg_bytes += (double)c->d * (32.0 * c->plan.n_gossip + 16.0 * c->plan.n_grad +
+                                    4.0 * c->plan.n_grad_xi + 4.0 * c->plan.n_grad_c);
+    return A2CID_OK;
+}
+
+int a2cid_apply_events(a2cid_ctx *c, const a2cid_event_batch *batch) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    try {
+        return apply_impl(c, batch);
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+}
+
+int a2cid_flush(a2cid_ctx *c, double t_now) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    std::vector<float> b(c->n);
+    for (int32_t i = 0; i < c->n; ++i) {
+        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
+        b[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    }
+    if (int rc = enqueue_mix_all(c, b)) return rc;
+    std::fill(c->t.begin(), c->t.end(), t_now);
+    return A2CID_OK;
+}
+
+int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
+    clear_error();
+    if (!c || !out || !out->sum_x || !out->sum_xt) return fail(A2CID_EINVAL, "context / out is NULL");
+    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    for (int32_t i = 0; i < c->n; ++i)
+        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
+    // b_host is reused by every call: the previous call ended with a stream synchronisation
+    for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
+    const int64_t pieces = (c->d + 3) >> 2;
+    const int64_t per_tile = (int64_t)kStatsV * kThreads;
+    const int64_t n_tiles = (pieces + per_tile - 1) / per_tile;
+    const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, kStatsBlocks);
+    const int32_t m = 2 * c->n + 2;
+    const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
+    hipLaunchKernelGGL((stats_kernel<kStatsV>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt, c->ld,
+                       c->d, c->n, c->b_dev, c->partials, n_tiles);
+    A2CID_HIP(hipGetLastError());
+    hipLaunchKernelGGL(stats_final_kernel, dim3((m + kThreads - 1) / kThreads), dim3(kThreads), 0, c->stream,
+                       c->partials, blocks, m, c->out_dev);
+    A2CID_HIP(hipGetLastError());
+    A2CID_HIP(hipMemcpyAsync(c->out_host, c->out_dev, sizeof(double) * m, hipMemcpyDeviceToHost, c->stream));
+    A2CID_HIP(hipStreamSynchronize(c->stream));
+    std::memcpy(out->sum_x, c->out_host, sizeof(double) * c->n);
+    std::memcpy(out->sum_xt, c->out_host + c->n, sizeof(double) * c->n);
+    out->consensus_x = c->out_host[2 * c->n];
+    out->consensus_xt = c->out_host[2 * c->n + 1];
+    return A2CID_OK;
+}
+
+int a2cid_get_times(const a2cid_ctx *c, double *t) {
+    clear_error();
+    if (!c || !t) return fail(A2CID_EINVAL, "context / t is NULL");
+    std::copy(c->t.begin(), c->t.end(), t);
+    return A2CID_OK;
+}
+
+int a2cid_set_times(a2cid_ctx *c, const double *t) {
+    clear_error();
+    if (!c || !t) return fail(A2CID_EINVAL, "context / t is NULL");
+    for (int32_t i = 0; i < c->n; ++i)
+        if (!std::isfinite(t[i])) return fail(A2CID_EINVAL, "t[%d] is not finite", i);
+    c->t.assign(t, t + c->n);
+    return A2CID_OK;
+}
+
+int a2cid_synchronize(a2cid_ctx *c) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    A2CID_HIP(hipStreamSynchronize(c->stream));
+    return A2CID_OK;
+}
+
+int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8)
+        return fail(A2CID_EINVAL, "unroll must be 1, 2, 4 or 8");
+    c->unroll = unroll;
+    c->nontemporal = nontemporal ? 1 : 0;
+    return A2CID_OK;
+}
+
+int a2cid_counters(a2cid_ctx *c, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
+                   double *algorithmic_bytes, int32_t reset) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (n_gossip) *n_gossip = c->n_gossip;
+    if (n_gradient) *n_gradient = c->n_grad;
+    if (n_launches) *n_launches = c->n_launch;
+    if (algorithmic_bytes) *algorithmic_bytes = c->alg_bytes;
+    if (reset) { c->n_gossip = c->n_grad = c->n_launch = 0; c->alg_bytes = 0.0; }
+    return A2CID_OK;
+}
+
+int a2cid_profile(a2cid_ctx *c, int32_t enable) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    c->profiling = enable != 0;
+    return A2CID_OK;
+}
+
+int a2cid_profile_read(a2cid_ctx *c, int64_t *n_launches, double *kernel_ms) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    A2CID_HIP(hipStreamSynchronize(c->stream));
+    double total = 0.0;
+    for (TimedLaunch &tl : c->timed) {
+        float ms = 0.f;
+        A2CID_HIP(hipEventElapsedTime(&ms, tl.start, tl.stop));
+        total += ms;
+        c->event_pool.push_back(tl.start);
+        c->event_pool.push_back(tl.stop);
+    }
+    if (n_launches) *n_launches = (int64_t)c->timed.size();
+    if (kernel_ms) *kernel_ms = total;
+    c->timed.clear();
+    return A2CID_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,416 @@
+// Host side of the A2CiD2 engine: error reporting, graph quantities (Definition 3.1,
+// chi_1, chi_2, Proposition 3.2), the batch planner (validation + mixing coefficients of
+// Algorithm 1's matrix-exponential step) and the Poisson-clock event scheduler
+// (Assumption 3.1) with its level packing.  No GPU code in this file.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <limits>
+#include <new>
+#include <queue>
+#include <utility>
+
+#include "a2cid_internal.h"
+
+namespace a2cid {
+
+static thread_local char g_error[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_error, sizeof(g_error), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_error[0] = '\0'; }
+
+int load_graph(Graph &g, int32_t n, const a2cid_graph *src) {
+    if (n < 2 || n > A2CID_MAX_WORKERS)
+        return fail(A2CID_EINVAL, "n = %d outside [2, %d]", n, A2CID_MAX_WORKERS);
+    if (!src) return fail(A2CID_EINVAL, "graph is NULL");
+    if (src->n_edges < 0) return fail(A2CID_EGRAPH, "n_edges = %d is negative", src->n_edges);
+    if (src->n_edges > 0 && (!src->u || !src->v || !src->rate))
+        return fail(A2CID_EINVAL, "graph arrays are NULL");
+    g.n = n;
+    g.u.assign(src->u, src->u + src->n_edges);
+    g.v.assign(src->v, src->v + src->n_edges);
+    g.rate.assign(src->rate, src->rate + src->n_edges);
+    g.adj.assign((size_t)n * n, 0);
+    for (int32_t e = 0; e < src->n_edges; ++e) {
+        const int32_t a = g.u[e], b = g.v[e];
+        if (a < 0 || b >= n || a >= b)
+            return fail(A2CID_EGRAPH, "edge %d = (%d, %d) must satisfy 0 <= u < v < n", e, a, b);
+        if (!(g.rate[e] >= 0.0) || !std::isfinite(g.rate[e]))
+            return fail(A2CID_EGRAPH, "edge %d has rate %g (must be finite and >= 0)", e, g.rate[e]);
+        if (g.adj[(size_t)a * n + b]) return fail(A2CID_EGRAPH, "edge %d = (%d, %d) is a duplicate", e, a, b);
+        g.adj[(size_t)a * n + b] = g.adj[(size_t)b * n + a] = 1;
+    }
+    return A2CID_OK;
+}
+
+double mix_coefficient(double eta, double tau) {
+    // (1 - e^{-2 eta tau}) / 2 without cancellation for small eta * tau
+    return -0.5 * std::expm1(-2.0 * eta * tau);
+}
+
+// ------------------------------------------------------------------------------------------
+// Symmetric eigen-decomposition by cyclic Jacobi rotations (n <= A2CID_MAX_WORKERS; the
+// Laplacian is tiny next to the parameter vectors).  a is overwritten by its diagonal form,
+// v receives the eigenvectors as columns.
+// ------------------------------------------------------------------------------------------
+static void jacobi_eigen(int n, std::vector<double> &a, std::vector<double> &v) {
+    v.assign((size_t)n * n, 0.0);
+    for (int i = 0; i < n; ++i) v[(size_t)i * n + i] = 1.0;
+    for (int sweep = 0; sweep < 100; ++sweep) {
+        double off = 0.0, diag = 0.0;
+        for (int p = 0; p < n; ++p) {
+            diag += a[(size_t)p * n + p] * a[(size_t)p * n + p];
+            for (int q = p + 1; q < n; ++q) off += a[(size_t)p * n + q] * a[(size_t)p * n + q];
+        }
+        if (off <= 1e-30 * (diag + off)) break;
+        for (int p = 0; p < n - 1; ++p) {
+            for (int q = p + 1; q < n; ++q) {
+                const double apq = a[(size_t)p * n + q];
+                if (apq == 0.0) continue;
+                const double app = a[(size_t)p * n + p], aqq = a[(size_t)q * n + q];
+                const double theta = (aqq - app) / (2.0 * apq);
+                const double tt = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
+                const double c = 1.0 / std::sqrt(tt * tt + 1.0), s = tt * c;
+                for (int k = 0; k < n; ++k) {   // columns p, q of a
+                    const double akp = a[(size_t)k * n + p], akq = a[(size_t)k * n + q];
+                    a[(size_t)k * n + p] = c * akp - s * akq;
+                    a[(size_t)k * n + q] = s * akp + c * akq;
+                }
+                for (int k = 0; k < n; ++k) {   // rows p, q of a
+                    const double apk = a[(size_t)p * n + k], aqk = a[(size_t)q * n + k];
+                    a[(size_t)p * n + k] = c * apk - s * aqk;
+                    a[(size_t)q * n + k] = s * apk + c * aqk;
+                }
+                for (int k = 0; k < n; ++k) {
+                    const double vkp = v[(size_t)k * n + p], vkq = v[(size_t)k * n + q];
+                    v[(size_t)k * n + p] = c * vkp - s * vkq;
+                    v[(size_t)k * n + q] = s * vkp + c * vkq;
+                }
+            }
+        }
+    }
+}
+
+static bool connected(const Graph &g) {
+    std::vector<std::vector<int32_t>> nb(g.n);
+    for (size_t e = 0; e < g.u.size(); ++e)
+        if (g.rate[e] > 0.0) { nb[g.u[e]].push_back(g.v[e]); nb[g.v[e]].push_back(g.u[e]); }
+    std::vector<char> seen(g.n, 0);
+    std::vector<int32_t> stack{0};
+    seen[0] = 1;
+    int32_t count = 1;
+    while (!stack.empty()) {
+        const int32_t a = stack.back();
+        stack.pop_back();
+        for (int32_t b : nb[a])
+            if (!seen[b]) { seen[b] = 1; ++count; stack.push_back(b); }
+    }
+    return count == g.n;
+}
+
+// ------------------------------------------------------------------------------------------
+// Batch planner
+// ------------------------------------------------------------------------------------------
+int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
+               Plan &plan, PlanScratch &scratch) {
+    if (!batch) return fail(A2CID_EINVAL, "batch is NULL");
+    if (batch->n_ops < 0 || batch->n_levels < 0) return fail(A2CID_EINVAL, "negative batch size");
+    if (batch->n_ops > 0 && !batch->ops) return fail(A2CID_EINVAL, "batch->ops is NULL");
+    if (!batch->level_off) return fail(A2CID_EINVAL, "batch->level_off is NULL");
+    if (batch->level_off[0] != 0 || batch->level_off[batch->n_levels] != batch->n_ops)
+        return fail(A2CID_EMATCHING, "level_off must start at 0 and end at n_ops");
+    const int32_t n = g.n;
+    plan.coef.assign((size_t)batch->n_ops, a2cid_coef{0.f, 0.f, 0.f, 0.f});
+    plan.t_after.assign(t_now, t_now + n);
+    plan.n_gossip = plan.n_grad = plan.n_grad_xi = plan.n_grad_c = 0;
+    scratch.level_stamp.assign(n, 0);
+    scratch.last_op.assign(n, -1);
+    const bool sync = std::isfinite(batch->t_sync);
+    if (!sync && !std::isnan(batch->t_sync)) return fail(A2CID_EINVAL, "t_sync must be finite or NaN");
+
+    for (int32_t l = 0; l < batch->n_levels; ++l) {
+        const int64_t lo = batch->level_off[l], hi = batch->level_off[l + 1];
+        if (hi < lo || hi > batch->n_ops) return fail(A2CID_EMATCHING, "level_off not monotone at level %d", l);
+        for (int64_t k = lo; k < hi; ++k) {
+            const a2cid_op &op = batch->ops[k];
+            if (!std::isfinite(op.t)) return fail(A2CID_EINVAL, "op %lld: time is not finite", (long long)k);
+            if (op.i < 0 || op.i >= n) return fail(A2CID_EINVAL, "op %lld: worker i = %d out of range", (long long)k, op.i);
+            int32_t ends[2] = {op.i, -1};
+            if (op.kind == A2CID_KIND_GOSSIP) {
+                if (op.j < 0 || op.j >= n || op.j == op.i)
+                    return fail(A2CID_EINVAL, "op %lld: worker j = %d invalid", (long long)k, op.j);
+                if (!g.has_edge(op.i, op.j))
+                    return fail(A2CID_EGRAPH, "op %lld: (%d, %d) is not an edge of the graph", (long long)k, op.i, op.j);
+                ends[1] = op.j;
+                ++plan.n_gossip;
+            } else if (op.kind == A2CID_KIND_GRADIENT) {
+                if (!std::isfinite(op.gamma) || !std::isfinite(op.gscale))
+                    return fail(A2CID_EINVAL, "op %lld: gamma / gscale not finite", (long long)k);
+                if (((uintptr_t)op.xi | (uintptr_t)op.c) & 15u)
+                    return fail(A2CID_EALIGN, "op %lld: xi / c must be 16-byte aligned", (long long)k);
+                ++plan.n_grad;
+                if (op.xi) ++plan.n_grad_xi;
+                if (op.c && op.gscale != 0.f) ++plan.n_grad_c;
+            } else {
+                return fail(A2CID_EINVAL, "op %lld: unknown kind %d", (long long)k, op.kind);
+            }
+            if (sync && op.t > batch->t_sync)
+                return fail(A2CID_EORDER, "op %lld: time %.17g is after t_sync %.17g", (long long)k, op.t, batch->t_sync);
+            float *b_pre[2] = {&plan.coef[k].b_pre_i, &plan.coef[k].b_pre_j};
+            for (int s = 0; s < 2; ++s) {
+                const int32_t w = ends[s];
+                if (w < 0) continue;
+                if (scratch.level_stamp[w] == (int64_t)l + 1)
+                    return fail(A2CID_EMATCHING, "level %d: worker %d appears in two operations", l, w);
+                scratch.level_stamp[w] = (int64_t)l + 1;
+                const double tau = op.t - plan.t_after[w];
+                if (tau < 0.0)
+                    return fail(A2CID_EORDER, "op %lld: time %.17g is before worker %d's time %.17g",
+                                (long long)k, op.t, w, plan.t_after[w]);
+                *b_pre[s] = (float)mix_coefficient(eta, tau);
+                plan.t_after[w] = op.t;
+                scratch.last_op[w] = k;
+            }
+        }
+    }
+    if (sync) {
+        for (int32_t w = 0; w < n; ++w) {
+            const int64_t k = scratch.last_op[w];
+            if (k < 0) continue;
+            const float b = (float)mix_coefficient(eta, batch->t_sync - plan.t_after[w]);
+            if (batch->ops[k].i == w) plan.coef[k].b_post_i = b; else plan.coef[k].b_post_j = b;
+            plan.t_after[w] = batch->t_sync;
+        }
+    }
+    return A2CID_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Scheduler
+// ------------------------------------------------------------------------------------------
+static inline void philox4x32_10(uint32_t c[4], uint32_t k0, uint32_t k1) {
+    // Philox4x32-10 of Salmon et al. (SC'11): ten S-P rounds; the key follows a Weyl sequence.
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t lo = (uint64_t)M0 * c[0], hi = (uint64_t)M1 * c[2];
+        const uint32_t y0 = (uint32_t)(hi >> 32) ^ c[1] ^ k0;
+        const uint32_t y2 = (uint32_t)(lo >> 32) ^ c[3] ^ k1;
+        c[1] = (uint32_t)hi;
+        c[3] = (uint32_t)lo;
+        c[0] = y0;
+        c[2] = y2;
+        k0 += W0;
+        k1 += W1;
+    }
+}
+
+}  // namespace a2cid
+
+using namespace a2cid;
+
+struct a2cid_sched {
+    Graph g;
+    std::vector<double> rate;        // per clock: workers, then edges
+    std::vector<uint64_t> draws;     // waiting times drawn so far, per clock
+    std::vector<int64_t> fired;      // events produced so far, per clock
+    uint64_t seed = 0;
+    int64_t serial = 0;              // serial index of the next event
+    using Entry = std::pair<double, int32_t>;   // (arrival time, clock id): ties -> lower id first
+    std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
+    // storage behind the batch handed out by a2cid_sched_next
+    std::vector<a2cid_op> raw, ops;
+    std::vector<int32_t> level_of;
+    std::vector<int64_t> level_off, cursor;
+    std::vector<int32_t> last_level;
+
+    double waiting_time(int32_t clock) {
+        const uint64_t k = draws[clock]++;
+        uint32_t c[4] = {(uint32_t)k, (uint32_t)(k >> 32), (uint32_t)clock, 0x0A2C1D20u};
+        philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
+        const uint64_t mantissa = ((uint64_t)c[0] << 21) | (c[1] >> 11);
+        const double u = std::ldexp((double)mantissa, -53);
+        return -std::log1p(-u) / rate[clock];
+    }
+
+    bool pop(a2cid_op &op) {
+        if (heap.empty()) return false;
+        const Entry e = heap.top();
+        heap.pop();
+        const int32_t c = e.second;
+        std::memset(&op, 0, sizeof(op));
+        op.t = e.first;
+        if (c < g.n) { op.kind = A2CID_KIND_GRADIENT; op.i = c; op.j = -1; }
+        else { op.kind = A2CID_KIND_GOSSIP; op.i = g.u[c - g.n]; op.j = g.v[c - g.n]; }
+        op.id = serial++;
+        ++fired[c];
+        heap.emplace(e.first + waiting_time(c), c);
+        return true;
+    }
+};
+
+extern "C" {
+
+const char *a2cid_last_error(void) { return g_error; }
+const char *a2cid_version(void) { return "a2cid 0.1 (gfx950)"; }
+
+int a2cid_graph_params(const a2cid_graph *graph, int32_t n, double *chi1, double *chi2,
+                       double *eta, double *alpha_tilde) {
+    clear_error();
+    Graph g;
+    if (int rc = load_graph(g, n, graph)) return rc;
+    if (!connected(g)) return fail(A2CID_EGRAPH, "graph is not connected (chi_1 is infinite)");
+    std::vector<double> lap((size_t)n * n, 0.0), vec;
+    for (size_t e = 0; e < g.u.size(); ++e) {
+        const int32_t a = g.u[e], b = g.v[e];
+        lap[(size_t)a * n + a] += g.rate[e];
+        lap[(size_t)b * n + b] += g.rate[e];
+        lap[(size_t)a * n + b] -= g.rate[e];
+        lap[(size_t)b * n + a] -= g.rate[e];
+    }
+    jacobi_eigen(n, lap, vec);
+    std::vector<double> eig(n);
+    double top = 0.0;
+    for (int i = 0; i < n; ++i) { eig[i] = lap[(size_t)i * n + i]; top = std::max(top, eig[i]); }
+    // exactly one eigenvalue (the constant vector) is zero for a connected graph: drop the smallest
+    int zero = 0;
+    for (int i = 1; i < n; ++i) if (eig[i] < eig[zero]) zero = i;
+    double smallest = std::numeric_limits<double>::infinity();
+    for (int i = 0; i < n; ++i) if (i != zero) smallest = std::min(smallest, eig[i]);
+    if (!(smallest > 1e-13 * top)) return fail(A2CID_EGRAPH, "Laplacian has a second (near-)zero eigenvalue");
+    const double c1 = 1.0 / smallest;
+    double worst = 0.0;
+    for (size_t e = 0; e < g.u.size(); ++e) {
+        const int32_t a = g.u[e], b = g.v[e];
+        double r = 0.0;   // (e_a - e_b)^T pinv(Lambda) (e_a - e_b)
+        for (int k = 0; k < n; ++k) {
+            if (k == zero) continue;
+            const double diff = vec[(size_t)a * n + k] - vec[(size_t)b * n + k];
+            r += diff * diff / eig[k];
+        }
+        worst = std::max(worst, r);
+    }
+    const double c2 = 0.5 * worst;
+    if (chi1) *chi1 = c1;
+    if (chi2) *chi2 = c2;
+    if (eta) *eta = 0.5 / std::sqrt(c1 * c2);
+    if (alpha_tilde) *alpha_tilde = 0.5 * std::sqrt(c1 / c2);
+    return A2CID_OK;
+}
+
+int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
+                     const a2cid_event_batch *batch, a2cid_coef *coef) {
+    clear_error();
+    if (!t) return fail(A2CID_EINVAL, "t is NULL");
+    if (!(eta >= 0.0) || !std::isfinite(eta)) return fail(A2CID_EINVAL, "eta = %g must be finite and >= 0", eta);
+    try {
+        Graph g;
+        if (int rc = load_graph(g, n, graph)) return rc;
+        Plan plan;
+        PlanScratch scratch;
+        if (int rc = plan_batch(g, eta, t, batch, plan, scratch)) return rc;
+        if (coef && batch->n_ops > 0) std::memcpy(coef, plan.coef.data(), sizeof(a2cid_coef) * (size_t)batch->n_ops);
+        std::copy(plan.t_after.begin(), plan.t_after.end(), t);
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
+int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
+                       const double *node_rate, uint64_t seed) {
+    clear_error();
+    if (!out || !node_rate) return fail(A2CID_EINVAL, "out / node_rate is NULL");
+    *out = nullptr;
+    a2cid_sched *s = new (std::nothrow) a2cid_sched;
+    if (!s) return fail(A2CID_ENOMEM, "out of host memory");
+    try {
+        if (int rc = load_graph(s->g, n, graph)) { delete s; return rc; }
+        const int32_t clocks = n + (int32_t)s->g.u.size();
+        s->rate.resize(clocks);
+        for (int32_t i = 0; i < n; ++i) {
+            if (!(node_rate[i] >= 0.0) || !std::isfinite(node_rate[i])) {
+                delete s;
+                return fail(A2CID_EINVAL, "node_rate[%d] = %g must be finite and >= 0", i, node_rate[i]);
+            }
+            s->rate[i] = node_rate[i];
+        }
+        for (size_t e = 0; e < s->g.u.size(); ++e) s->rate[n + e] = s->g.rate[e];
+        s->draws.assign(clocks, 0);
+        s->fired.assign(clocks, 0);
+        s->seed = seed;
+        s->last_level.assign(n, -1);
+        for (int32_t c = 0; c < clocks; ++c)
+            if (s->rate[c] > 0.0) s->heap.emplace(s->waiting_time(c), c);
+    } catch (const std::bad_alloc &) {
+        delete s;
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    *out = s;
+    return A2CID_OK;
+}
+
+int a2cid_sched_next(a2cid_sched *s, int64_t max_events, a2cid_event_batch *out) {
+    clear_error();
+    if (!s || !out) return fail(A2CID_EINVAL, "scheduler / out is NULL");
+    if (max_events < 0) return fail(A2CID_EINVAL, "max_events is negative");
+    try {
+        s->raw.clear();
+        s->level_of.clear();
+        std::fill(s->last_level.begin(), s->last_level.end(), -1);
+        int32_t n_levels = 0;
+        a2cid_op op;
+        while ((int64_t)s->raw.size() < max_events && s->pop(op)) {
+            int32_t lev = s->last_level[op.i];
+            if (op.kind == A2CID_KIND_GOSSIP) lev = std::max(lev, s->last_level[op.j]);
+            ++lev;
+            s->last_level[op.i] = lev;
+            if (op.kind == A2CID_KIND_GOSSIP) s->last_level[op.j] = lev;
+            n_levels = std::max(n_levels, lev + 1);
+            s->raw.push_back(op);
+            s->level_of.push_back(lev);
+        }
+        // stable counting sort by level: serial order survives inside each level
+        s->level_off.assign((size_t)n_levels + 1, 0);
+        for (int32_t lev : s->level_of) ++s->level_off[(size_t)lev + 1];
+        for (int32_t l = 0; l < n_levels; ++l) s->level_off[(size_t)l + 1] += s->level_off[l];
+        s->cursor.assign(s->level_off.begin(), s->level_off.end() - (n_levels > 0 ? 1 : 0));
+        s->ops.resize(s->raw.size());
+        for (size_t k = 0; k < s->raw.size(); ++k) s->ops[(size_t)s->cursor[s->level_of[k]]++] = s->raw[k];
+        out->n_ops = (int64_t)s->ops.size();
+        out->ops = s->ops.data();
+        out->n_levels = n_levels;
+        out->level_off = s->level_off.data();
+        out->t_sync = std::numeric_limits<double>::quiet_NaN();
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
+int a2cid_sched_skip(a2cid_sched *s, int64_t n_events) {
+    clear_error();
+    if (!s || n_events < 0) return fail(A2CID_EINVAL, "scheduler is NULL or n_events negative");
+    a2cid_op op;
+    for (int64_t k = 0; k < n_events; ++k)
+        if (!s->pop(op)) break;
+    return A2CID_OK;
+}
+
+int a2cid_sched_counts(const a2cid_sched *s, int64_t *counts) {
+    clear_error();
+    if (!s || !counts) return fail(A2CID_EINVAL, "scheduler / counts is NULL");
+    std::copy(s->fired.begin(), s->fired.end(), counts);
+    return A2CID_OK;
+}
+
+void a2cid_sched_destroy(a2cid_sched *s) { delete s; }
+
+}  // extern "C"

@@ -1,0 +1,51 @@
+// Internal declarations shared by the host translation unit (planner, scheduler, graph
+// quantities) and the HIP translation unit (context, kernels).  Not part of the public ABI.
+#pragma once
+
+#include <cstdarg>
+#include <cstdint>
+#include <vector>
+
+#include "a2cid.h"
+
+namespace a2cid {
+
+// Sets the thread-local message returned by a2cid_last_error() and returns code.
+int fail(int code, const char *fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+// Undirected graph copied out of an a2cid_graph, with an n x n adjacency bitmap for
+// O(1) membership tests while validating gossip events.
+struct Graph {
+    int32_t n = 0;
+    std::vector<int32_t> u, v;
+    std::vector<double> rate;
+    std::vector<uint8_t> adj;   // n * n, adj[i * n + j] == 1 iff {i, j} is an edge
+
+    bool has_edge(int32_t i, int32_t j) const { return adj[(size_t)i * n + j] != 0; }
+};
+
+// Validates and copies.  Returns A2CID_OK / A2CID_EINVAL / A2CID_EGRAPH.
+int load_graph(Graph &g, int32_t n, const a2cid_graph *src);
+
+// Off-diagonal entry b of exp(tau [[-eta, eta], [eta, -eta]]) = [[1-b, b], [b, 1-b]]
+// (closed form of the mixing step of Algorithm 1): b = (1 - exp(-2 eta tau)) / 2.
+double mix_coefficient(double eta, double tau);
+
+// Result of planning one batch (the validation + coefficient step, S3 of the path).
+struct Plan {
+    std::vector<a2cid_coef> coef;   // one per op
+    std::vector<double> t_after;    // n time stamps after the batch
+    int64_t n_gossip = 0, n_grad = 0, n_grad_xi = 0, n_grad_c = 0;
+};
+
+// Pure host function behind a2cid_plan_batch and a2cid_apply_events.  scratch_* are
+// reusable work arrays (resized as needed) so that repeated calls do not allocate.
+struct PlanScratch {
+    std::vector<int64_t> level_stamp;   // per worker: 1 + index of the last level that touched it
+    std::vector<int64_t> last_op;       // per worker: index of its last op in the batch, or -1
+};
+int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
+               Plan &plan, PlanScratch &scratch);
+
+}  // namespace a2cid

@@ -1,0 +1,316 @@
+// Device code of the A2CiD2 engine for gfx950 (wave64).  Included only by a2cid_engine.hip.
+//
+// All three kernels are HBM streams (about 0.5 flop per byte), so there is no MFMA and no LDS
+// on the data path: each lane moves 128-bit pieces straight between global memory and
+// registers, and the design goal is simply "enough independent 16-byte loads in flight per CU".
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace a2cid {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+constexpr int kThreads = 256;           // 4 wavefronts per workgroup
+constexpr int kWaves = kThreads / 64;
+
+enum : int32_t { kOpGradient = 0, kOpGossip = 1, kOpMixOnly = 2 };
+
+// One operation of a level as the kernels see it (64 bytes).  Every field is uniform across
+// the workgroup that executes the operation, so the compiler keeps it in scalar registers.
+struct DevOp {
+    int32_t kind;
+    int32_t row_i, row_j;        // worker rows (row_j unused unless gossip)
+    float b_i, b_j;              // mixing to the event time: off-diagonal of exp(tau A)
+    float bp_i, bp_j;            // trailing mixing (0 = none)
+    float gamma, gscale;         // gradient step size and slope of the affine gradient model
+    int32_t pad0;
+    const float *xi;             // additive gradient term or nullptr
+    const float *c;              // centre of the affine gradient model or nullptr
+    int64_t pad1;
+};
+static_assert(sizeof(DevOp) == 64, "DevOp layout");
+
+// exp(tau A) (x, xt) in increment form: with b the off-diagonal entry, x += b (xt - x) and
+// xt -= b (xt - x).  x + xt is conserved exactly up to one rounding; b = 0 is the identity.
+template <typename T>
+__device__ __forceinline__ void mix(T &x, T &xt, float b) {
+    const T delta = b * (xt - x);
+    x += delta;
+    xt -= delta;
+}
+
+// Gossip jump of Eq. (1) for one pair, including the flows before and (optionally) after it.
+template <typename T>
+__device__ __forceinline__ void gossip_update(T &xi, T &xti, T &xj, T &xtj, const DevOp &op,
+                                              float alpha, float alpha_t) {
+    mix(xi, xti, op.b_i);
+    mix(xj, xtj, op.b_j);
+    const T m = xi - xj;
+    xi -= alpha * m;
+    xj += alpha * m;
+    xti -= alpha_t * m;
+    xtj += alpha_t * m;
+    mix(xi, xti, op.bp_i);
+    mix(xj, xtj, op.bp_j);
+}
+
+// Gradient jump of Eq. (1) with g = gscale (x - c) + xi, taken at the mixed point.
+template <typename T>
+__device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, const DevOp &op) {
+    mix(x, xt, op.b_i);
+    const T g = op.gscale * (x - c) + xi;
+    x -= op.gamma * g;
+    xt -= op.gamma * g;
+    mix(x, xt, op.bp_i);
+}
+
+template <bool NT>
+__device__ __forceinline__ v4f load4(const v4f *p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store4(v4f *p, v4f v) {
+    if constexpr (NT) __builtin_nontemporal_store(v, p);
+    else *p = v;
+}
+
+// ------------------------------------------------------------------------------------------
+// Level kernel: grid = (column tiles, operations of one level).  A workgroup applies ONE
+// operation to a tile of U * 256 float4 columns: every lane loads U 16-byte pieces of each
+// row the operation touches (coalesced: consecutive lanes, consecutive 16 bytes), updates them
+// in registers and stores them back in place.  Operations of a level touch disjoint rows, so
+// no two workgroups of a launch ever touch the same byte.
+//   gossip:   4 rows in, 4 rows out  (32 bytes per column)
+//   gradient: 2 rows (+ xi, + c) in, 2 rows out  (16 / 20 / 24 bytes per column)
+//   mix only: 2 rows in, 2 rows out
+// The d % 4 trailing columns of a row are handled by scalar code in the first tile.
+// ------------------------------------------------------------------------------------------
+template <int U, bool NT>
+__global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, float *__restrict__ xt,
+                                                         int64_t ld, int64_t d,
+                                                         const DevOp *__restrict__ ops,
+                                                         float alpha, float alpha_t) {
+    const DevOp op = ops[blockIdx.y];
+    const int64_t n4 = d >> 2;                                   // whole float4 pieces per row
+    const int64_t base = (int64_t)blockIdx.x * (U * kThreads) + threadIdx.x;
+    const bool full = (int64_t)(blockIdx.x + 1) * (U * kThreads) <= n4;
+
+    float *xi_row = x + (int64_t)op.row_i * ld;
+    float *xti_row = xt + (int64_t)op.row_i * ld;
+
+    if (op.kind == kOpGossip) {
+        float *xj_row = x + (int64_t)op.row_j * ld;
+        float *xtj_row = xt + (int64_t)op.row_j * ld;
+        v4f *pi = (v4f *)xi_row, *pti = (v4f *)xti_row, *pj = (v4f *)xj_row, *ptj = (v4f *)xtj_row;
+        v4f a[U], at[U], b[U], bt[U];
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
+                b[u] = load4<NT>(pj + k); bt[u] = load4<NT>(ptj + k);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
+                store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
+                store4<NT>(pj + k, b[u]); store4<NT>(ptj + k, bt[u]);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                if (k < n4) {
+                    a[u] = pi[k]; at[u] = pti[k]; b[u] = pj[k]; bt[u] = ptj[k];
+                    gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
+                    pi[k] = a[u]; pti[k] = at[u]; pj[k] = b[u]; ptj[k] = bt[u];
+                }
+            }
+        }
+        if (blockIdx.x == 0) {
+            const int64_t k = (n4 << 2) + threadIdx.x;
+            if (threadIdx.x < 4 && k < d) {
+                float s0 = xi_row[k], s1 = xti_row[k], s2 = xj_row[k], s3 = xtj_row[k];
+                gossip_update(s0, s1, s2, s3, op, alpha, alpha_t);
+                xi_row[k] = s0; xti_row[k] = s1; xj_row[k] = s2; xtj_row[k] = s3;
+            }
+        }
+    } else {
+        v4f *pi = (v4f *)xi_row, *pti = (v4f *)xti_row;
+        const bool grad = op.kind == kOpGradient;
+        const bool has_xi = grad && op.xi != nullptr;
+        const bool has_c = grad && op.c != nullptr && op.gscale != 0.f;
+        const v4f *pxi = (const v4f *)op.xi, *pc = (const v4f *)op.c;
+        const v4f zero = {0.f, 0.f, 0.f, 0.f};
+        v4f a[U], at[U], g[U], c[U];
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
+                g[u] = has_xi ? load4<NT>(pxi + k) : zero;
+                c[u] = has_c ? load4<NT>(pc + k) : zero;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                if (grad) gradient_update(a[u], at[u], g[u], c[u], op);
+                else mix(a[u], at[u], op.b_i);
+                store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t k = base + u * kThreads;
+                if (k < n4) {
+                    a[u] = pi[k]; at[u] = pti[k];
+                    g[u] = has_xi ? pxi[k] : zero;
+                    c[u] = has_c ? pc[k] : zero;
+                    if (grad) gradient_update(a[u], at[u], g[u], c[u], op);
+                    else mix(a[u], at[u], op.b_i);
+                    pi[k] = a[u]; pti[k] = at[u];
+                }
+            }
+        }
+        if (blockIdx.x == 0) {
+            const int64_t k = (n4 << 2) + threadIdx.x;
+            if (threadIdx.x < 4 && k < d) {
+                float s0 = xi_row[k], s1 = xti_row[k];
+                const float gk = has_xi ? op.xi[k] : 0.f, ck = has_c ? op.c[k] : 0.f;
+                if (grad) gradient_update(s0, s1, gk, ck, op);
+                else mix(s0, s1, op.b_i);
+                xi_row[k] = s0; xti_row[k] = s1;
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Observables.  One pass over x and xt (8 n d bytes).  A workgroup owns tiles of
+// V * 256 float4 columns and walks all n rows of a tile, so that for every column it sees the
+// n workers' values and can form the column's contribution to ||pi x||_F^2 without a second
+// pass: with the first row's (mixed) value p as pivot, D_i = v_i - p in fp64,
+//     sum_i (v_i - mean)^2 = sum_i D_i^2 - (sum_i D_i)^2 / n.
+// The pending mixing of each worker up to the observation time is applied in registers from
+// a per-worker coefficient table staged in LDS; nothing is written back to x or xt.
+// Per-worker coordinate sums: fp32 partial over the 4 V columns of a lane and the 64 lanes of
+// a wave (one partial = 256 V columns), then fp64 accumulation per wave in LDS.
+// Output: partials[block][0..n) row sums of x, [n..2n) of xt, [2n] consensus x, [2n+1] xt.
+// Dynamic LDS: kWaves * 2n doubles + n floats.
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+__device__ __forceinline__ v4f load4_guarded(const float *row, int64_t g, int64_t d) {
+    // float4 piece g of a row of d valid floats; pieces or components past the end read as 0
+    const int64_t k = g << 2;
+    if (k + 4 <= d) return *(const v4f *)(row + k);
+    v4f v = {0.f, 0.f, 0.f, 0.f};
+    if (k < d) v.x = row[k];
+    if (k + 1 < d) v.y = row[k + 1];
+    if (k + 2 < d) v.z = row[k + 2];
+    return v;
+}
+
+template <int V>
+__global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict__ x,
+                                                         const float *__restrict__ xt,
+                                                         int64_t ld, int64_t d, int32_t n,
+                                                         const float *__restrict__ bmix,
+                                                         double *__restrict__ partials,
+                                                         int64_t n_tiles) {
+    extern __shared__ double smem[];
+    double *srow = smem;                                  // [kWaves][2n]
+    float *sb = (float *)(smem + (size_t)kWaves * 2 * n); // [n]
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    for (int i = tid; i < n; i += kThreads) sb[i] = bmix[i];
+    for (int i = tid; i < kWaves * 2 * n; i += kThreads) srow[i] = 0.0;
+    __syncthreads();
+    double *my_row = srow + (size_t)wave * 2 * n;
+    const double inv_n = 1.0 / (double)n;
+    double cons_x = 0.0, cons_xt = 0.0;
+
+    for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const int64_t g0 = tile * (V * kThreads) + tid;
+        v4f px[V], pxt[V];
+        double sx[V][4], qx[V][4], sxt[V][4], qxt[V][4];
+#pragma unroll
+        for (int u = 0; u < V; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) sx[u][c] = qx[u][c] = sxt[u][c] = qxt[u][c] = 0.0;
+
+        for (int32_t i = 0; i < n; ++i) {
+            const float *xr = x + (int64_t)i * ld, *xtr = xt + (int64_t)i * ld;
+            const float b = sb[i];
+            v4f a[V], at[V];
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                a[u] = load4_guarded(xr, g0 + u * kThreads, d);
+                at[u] = load4_guarded(xtr, g0 + u * kThreads, d);
+            }
+            float rx = 0.f, rxt = 0.f;
+#pragma unroll
+            for (int u = 0; u < V; ++u) {
+                mix(a[u], at[u], b);
+                rx += (a[u].x + a[u].y) + (a[u].z + a[u].w);
+                rxt += (at[u].x + at[u].y) + (at[u].z + at[u].w);
+                if (i == 0) { px[u] = a[u]; pxt[u] = at[u]; }
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const double dx = (double)a[u][c] - (double)px[u][c];
+                    const double dxt = (double)at[u][c] - (double)pxt[u][c];
+                    sx[u][c] += dx; qx[u][c] += dx * dx;
+                    sxt[u][c] += dxt; qxt[u][c] += dxt * dxt;
+                }
+            }
+            rx = wave_sum(rx);
+            rxt = wave_sum(rxt);
+            if (lane == 0) { my_row[i] += (double)rx; my_row[n + i] += (double)rxt; }
+        }
+#pragma unroll
+        for (int u = 0; u < V; ++u)
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                cons_x += qx[u][c] - sx[u][c] * sx[u][c] * inv_n;
+                cons_xt += qxt[u][c] - sxt[u][c] * sxt[u][c] * inv_n;
+            }
+    }
+
+    // workgroup reduction of the two consensus partials (fixed order -> deterministic)
+    __shared__ double scons[2][kThreads];
+    scons[0][tid] = cons_x;
+    scons[1][tid] = cons_xt;
+    __syncthreads();
+    for (int s = kThreads / 2; s > 0; s >>= 1) {
+        if (tid < s) { scons[0][tid] += scons[0][tid + s]; scons[1][tid] += scons[1][tid + s]; }
+        __syncthreads();
+    }
+    double *out = partials + (size_t)blockIdx.x * (2 * (size_t)n + 2);
+    for (int i = tid; i < 2 * n; i += kThreads) {
+        double s = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) s += srow[(size_t)w * 2 * n + i];
+        out[i] = s;
+    }
+    if (tid == 0) { out[2 * n] = scons[0][0]; out[2 * n + 1] = scons[1][0]; }
+}
+
+// Sums the per-workgroup partials in block order (deterministic): out[j] = sum_b partials[b][j].
+__global__ __launch_bounds__(kThreads) void stats_final_kernel(const double *__restrict__ partials,
+                                                               int32_t n_blocks, int32_t m,
+                                                               double *__restrict__ out) {
+    const int j = blockIdx.x * kThreads + threadIdx.x;
+    if (j >= m) return;
+    double s = 0.0;
+    for (int32_t b = 0; b < n_blocks; ++b) s += partials[(size_t)b * m + j];
+    out[j] = s;
+}
+
+}  // namespace a2cid

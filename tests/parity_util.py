@@ -1,0 +1,68 @@
+"""CPU side of the GPU parity tests: runs the oracle on a column subset of a workload.
+
+Every step of the method is element-wise in the coordinate index (Eq. (1) couples workers, never
+coordinates), so following a subset of columns through the whole event stream is exact.
+Inputs come from the shared generator (synth.gen); events from the oracle's own clock code.
+"""
+import numpy as np
+
+from oracle import core, graph
+from synth import gen
+from paper_2306_08289_amd import workloads as wl
+
+TOL = 1e-5     # spec tolerance: max relative error, fp32, norm-wise per worker and buffer
+
+
+def sample_columns(d, count, seed=0):
+    """First and last 1024 columns (tile edges, ragged tail) plus seeded random ones."""
+    head = np.arange(min(d, 1024))
+    tail = np.arange(max(0, d - 1024), d)
+    rng = np.random.default_rng(seed)
+    mid = rng.integers(0, d, size=max(0, count - len(head) - len(tail)))
+    return np.unique(np.concatenate([head, tail, mid]))
+
+
+def oracle_params(cfg):
+    edges = getattr(graph, cfg.topology)(cfg.n)
+    node_rate, edge_rate = wl.clock_rates(cfg)
+    if cfg.accelerated:
+        p = graph.acid_params(cfg.n, edges, edge_rate)
+        eta, alpha_t = p["eta"], p["alpha_tilde"]
+    else:
+        eta, alpha_t = 0.0, 0.5
+    if cfg.eta is not None:
+        eta = cfg.eta
+    if cfg.alpha_tilde is not None:
+        alpha_t = cfg.alpha_tilde
+    return edges, node_rate, edge_rate, eta, 0.5, alpha_t
+
+
+def oracle_run(cfg, cols, n_events, t_final=None):
+    """Oracle state after the first n_events events of cfg, restricted to columns cols."""
+    edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg)
+    ev = core.generate_events(cfg.n, [e[0] for e in edges], [e[1] for e in edges], node_rate,
+                              np.full(len(edges), edge_rate), cfg.seed, n_events)
+    x0 = gen.normal_rows(cfg.seed, gen.DOMAIN_INIT, range(cfg.n), cols, cfg.init_sigma)
+    st = core.State(x0, None, eta, alpha, alpha_t)
+    is_grad = ev.kind == 0
+    m = len(ev)
+    c = c_row = xi = xi_row = None
+    if cfg.use_c:
+        c = gen.normal_rows(cfg.seed, gen.DOMAIN_C, range(cfg.n), cols, 1.0)
+        c_row = np.where(is_grad, ev.i, -1)
+    if cfg.xi_sigma > 0:
+        ids = np.nonzero(is_grad)[0]
+        xi = gen.normal_rows(cfg.seed, gen.DOMAIN_XI, ids, cols, cfg.xi_sigma)
+        xi_row = np.full(m, -1, np.int64)
+        xi_row[ids] = np.arange(len(ids))
+    # the engine receives gamma and gscale as fp32 values
+    st.apply(ev, float(np.float32(cfg.gamma)), float(np.float32(cfg.gscale)), xi, xi_row, c, c_row)
+    return st, ev
+
+
+def rel_err(got, want):
+    """Norm-wise relative error per row: max_k |got - want| / max_k |want|; returns the max over rows."""
+    got = np.asarray(got, np.float64); want = np.asarray(want, np.float64)
+    num = np.abs(got - want).max(axis=1)
+    den = np.maximum(np.abs(want).max(axis=1), 1e-30)
+    return float((num / den).max())

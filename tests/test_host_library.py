@@ -1,0 +1,201 @@
+"""CPU tests of the library's host side: exported symbols, graph quantities, scheduler, planner.
+No kernel is launched here."""
+import ctypes as C
+import math
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2306_08289_amd as a2
+from paper_2306_08289_amd import binding
+from oracle import core, graph, levels
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _uv(edges):
+    return [e[0] for e in edges], [e[1] for e in edges]
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "a2cid.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(a2cid_[a-z_]+)\s*\(", header))
+    assert len(declared) >= 20
+    lib = C.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.SIGNATURES), declared ^ set(binding.SIGNATURES)
+    assert b"gfx950" in a2.load().a2cid_version()
+
+
+@pytest.mark.parametrize("topo,n,rate", [("complete", 4, 1.0), ("ring", 16, 1.0), ("ring", 64, 2.0),
+                                         ("exponential", 64, 1.0), ("exponential", 16, 0.4),
+                                         ("complete", 64, 0.56)])
+def test_graph_params_match_oracle(topo, n, rate):
+    edges = getattr(graph, topo)(n)
+    u, v = _uv(edges)
+    got = a2.a2cid_graph_params(n, u, v, rate)
+    want = graph.acid_params(n, edges, rate)
+    for k in ("chi1", "chi2", "eta", "alpha_tilde"):
+        assert math.isclose(got[k], want[k], rel_tol=1e-9), k
+
+
+def test_graph_params_heterogeneous_rates_and_errors():
+    rng = np.random.default_rng(0)
+    n = 9
+    edges = sorted(set(graph.ring(n)) | {(0, 4), (2, 7), (1, 5)})
+    rates = rng.uniform(0.2, 2.0, len(edges))
+    u, v = _uv(edges)
+    got = a2.a2cid_graph_params(n, u, v, rates)
+    want = graph.acid_params(n, edges, rates)
+    assert math.isclose(got["chi1"], want["chi1"], rel_tol=1e-9)
+    assert math.isclose(got["chi2"], want["chi2"], rel_tol=1e-9)
+    with pytest.raises(a2.A2cidError) as e:
+        a2.a2cid_graph_params(4, [0, 2], [1, 3], 1.0)          # two components
+    assert e.value.code == binding.EGRAPH
+    with pytest.raises(a2.A2cidError) as e:
+        a2.a2cid_graph_params(4, [1], [0], 1.0)                # u >= v
+    assert e.value.code == binding.EGRAPH
+    with pytest.raises(a2.A2cidError) as e:
+        a2.a2cid_graph_params(4, [0, 0], [1, 1], 1.0)          # duplicate
+    assert e.value.code == binding.EGRAPH
+    with pytest.raises(a2.A2cidError) as e:
+        a2.a2cid_graph_params(1, [], [], 1.0)
+    assert e.value.code == binding.EINVAL
+
+
+# ------------------------------------------------------------------ scheduler
+@pytest.mark.parametrize("topo,n,node_rate,edge_rate,seed", [
+    ("complete", 4, 1.0, 1.0, 0xA2C1D2), ("ring", 16, 1.0, 1.0, 0xA2C1D3), ("ring", 64, 1.0, 2.0, 0xA2C1D4),
+    ("exponential", 64, 1.0, 1.0, (7 << 32) + 5), ("complete", 64, None, None, 0xA2C1D6)])
+def test_schedule_is_bit_identical_to_the_oracle_stream(topo, n, node_rate, edge_rate, seed):
+    edges = getattr(graph, topo)(n)
+    u, v = _uv(edges)
+    if node_rate is None:       # straggler clocks: log-normal node rates, edges at half their mean
+        node_rate = np.exp(0.5 * np.random.default_rng(1).normal(size=n))
+        edge_rate = 0.5 * node_rate.mean()
+    node_rate = np.broadcast_to(node_rate, (n,)).astype(float)
+    m = 20000
+    ref = core.generate_events(n, u, v, node_rate, np.full(len(edges), edge_rate), seed, m)
+    s = a2.Scheduler(n, u, v, edge_rate, node_rate, seed)
+    got = []
+    batch_size = 1024
+    while sum(len(b.ops) for b in got) < m:
+        got.append(s.next(min(batch_size, m - sum(len(b.ops) for b in got))))
+    ref_batches = levels.pack(ref.kind, ref.i, ref.j, batch_size)
+    assert len(got) == len(ref_batches)
+    for b, rb in zip(got, ref_batches):
+        order = [e for lev in rb for e in lev]
+        assert b.n_levels == len(rb)
+        assert list(b.level_off) == list(np.cumsum([0] + [len(lev) for lev in rb]))
+        assert np.array_equal(b.ops["id"], order)
+        assert np.array_equal(b.ops["t"], ref.t[order])          # bit-exact times
+        assert np.array_equal(b.ops["kind"], ref.kind[order])
+        assert np.array_equal(b.ops["i"], ref.i[order]) and np.array_equal(b.ops["j"], ref.j[order])
+        assert np.all(b.ops["xi"] == 0) and np.all(b.ops["c"] == 0) and math.isnan(b.t_sync)
+    counts = s.counts()
+    assert counts.sum() == m and np.array_equal(counts, np.bincount(ref.clock, minlength=n + len(edges)))
+
+
+def test_scheduler_skip_resumes_the_same_stream_and_dead_clocks():
+    n = 8
+    edges = graph.ring(n)
+    u, v = _uv(edges)
+    a = a2.Scheduler(n, u, v, 1.0, 1.0, 99)
+    whole = a.next(500)
+    b = a2.Scheduler(n, u, v, 1.0, 1.0, 99)
+    b.skip(200)
+    rest = b.next(300)
+    ids = np.sort(rest.ops["id"])
+    assert ids[0] == 200 and ids[-1] == 499
+    by_id = {int(o["id"]): o for o in whole.ops}
+    for o in rest.ops:
+        w = by_id[int(o["id"])]
+        assert o["t"] == w["t"] and o["i"] == w["i"] and o["j"] == w["j"] and o["kind"] == w["kind"]
+    dead = a2.Scheduler(n, u, v, 0.0, 0.0, 1)
+    assert len(dead.next(10).ops) == 0
+    comm_only = a2.Scheduler(n, u, v, 1.0, 0.0, 1).next(100)
+    assert np.all(comm_only.ops["kind"] == a2.KIND_GOSSIP)
+    assert len(a.next(0).ops) == 0
+
+
+# ------------------------------------------------------------------ planner
+def _batch(ops, level_off, t_sync=float("nan")):
+    arr = np.zeros(len(ops), a2.OP_DTYPE)
+    for k, o in enumerate(ops):
+        for key, val in o.items():
+            arr[k][key] = val
+    return a2.Batch(arr, level_off, t_sync)
+
+
+def test_planner_coefficients_and_time_stamps():
+    n, eta = 4, 0.7
+    u, v = _uv(graph.complete(n))
+    t0 = np.array([0.0, 0.5, 1.0, 0.25])
+    b = _batch([dict(t=1.5, kind=1, i=0, j=1), dict(t=1.25, kind=0, i=2, j=-1, gamma=0.1),
+                dict(t=2.0, kind=1, i=2, j=0), dict(t=2.5, kind=0, i=1, j=-1)], [0, 2, 4])
+    t1, coef = a2.a2cid_plan_batch(n, u, v, 1.0, eta, t0, b)
+    assert list(t1) == [2.0, 2.5, 2.0, 0.25]
+    bco = lambda tau: np.float32(0.5 * (1 - math.exp(-2 * eta * tau)))
+    assert coef["b_pre_i"][0] == bco(1.5) and coef["b_pre_j"][0] == bco(1.0)
+    assert coef["b_pre_i"][1] == bco(0.25) and coef["b_pre_j"][1] == 0
+    assert coef["b_pre_i"][2] == bco(0.75) and coef["b_pre_j"][2] == bco(0.5)
+    assert coef["b_pre_i"][3] == bco(1.0)
+    assert np.all(coef["b_post_i"] == 0) and np.all(coef["b_post_j"] == 0)
+    # the closed form against the matrix exponential (independent route)
+    from scipy.linalg import expm
+    assert math.isclose(float(coef["b_pre_i"][0]), expm(1.5 * np.array([[-eta, eta], [eta, -eta]]))[0, 1], rel_tol=1e-6)
+    # eta = 0: identity flow
+    _, c0 = a2.a2cid_plan_batch(n, u, v, 1.0, 0.0, t0, b)
+    assert np.all(c0["b_pre_i"] == 0) and np.all(c0["b_pre_j"] == 0)
+    # tiny eta * tau keeps relative accuracy (expm1 form)
+    t2, c2 = a2.a2cid_plan_batch(n, u, v, 1.0, 1e-9, np.zeros(n), _batch([dict(t=1e-3, kind=0, i=0, j=-1)], [0, 1]))
+    assert math.isclose(float(c2["b_pre_i"][0]), 1e-12, rel_tol=1e-6)
+
+
+def test_planner_trailing_mix_goes_to_each_workers_last_operation():
+    n, eta = 4, 0.3
+    u, v = _uv(graph.complete(n))
+    b = _batch([dict(t=1.0, kind=1, i=0, j=1), dict(t=2.0, kind=0, i=1, j=-1), dict(t=2.5, kind=1, i=2, j=0)],
+               [0, 1, 2, 3], t_sync=4.0)
+    t1, coef = a2.a2cid_plan_batch(n, u, v, 1.0, eta, np.zeros(n), b)
+    assert list(t1) == [4.0, 4.0, 4.0, 0.0]            # worker 3 is not touched by the batch
+    bco = lambda tau: np.float32(0.5 * (1 - math.exp(-2 * eta * tau)))
+    assert coef["b_post_i"][0] == 0 and coef["b_post_j"][0] == 0     # both have later operations
+    assert coef["b_post_i"][1] == bco(2.0)
+    assert coef["b_post_i"][2] == bco(1.5) and coef["b_post_j"][2] == bco(1.5)
+
+
+@pytest.mark.parametrize("ops,level_off,t_sync,code", [
+    ([dict(t=1.0, kind=1, i=0, j=1), dict(t=1.0, kind=0, i=1, j=-1)], [0, 2], float("nan"), binding.EMATCHING),
+    ([dict(t=1.0, kind=1, i=0, j=2)], [0, 1], float("nan"), binding.EGRAPH),           # not an edge of the ring
+    ([dict(t=0.4, kind=0, i=3, j=-1)], [0, 1], float("nan"), binding.EORDER),           # worker 3 is at t = 0.5
+    ([dict(t=1.0, kind=0, i=0, j=-1), dict(t=0.9, kind=0, i=0, j=-1)], [0, 1, 2], float("nan"), binding.EORDER),
+    ([dict(t=1.0, kind=7, i=0, j=-1)], [0, 1], float("nan"), binding.EINVAL),
+    ([dict(t=1.0, kind=0, i=9, j=-1)], [0, 1], float("nan"), binding.EINVAL),
+    ([dict(t=1.0, kind=1, i=1, j=1)], [0, 1], float("nan"), binding.EINVAL),
+    ([dict(t=float("inf"), kind=0, i=0, j=-1)], [0, 1], float("nan"), binding.EINVAL),
+    ([dict(t=1.0, kind=0, i=0, j=-1, gamma=float("nan"))], [0, 1], float("nan"), binding.EINVAL),
+    ([dict(t=1.0, kind=0, i=0, j=-1, xi=8)], [0, 1], float("nan"), binding.EALIGN),
+    ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 2], float("nan"), binding.EMATCHING),        # table does not end at n_ops
+    ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 1], 0.5, binding.EORDER),                    # t_sync before an event
+    ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 1], float("inf"), binding.EINVAL),
+])
+def test_planner_rejects_bad_batches_and_leaves_times_untouched(ops, level_off, t_sync, code):
+    n = 4
+    u, v = _uv(graph.ring(n))
+    t0 = np.array([0.0, 0.0, 0.0, 0.5])
+    with pytest.raises(a2.A2cidError) as e:
+        a2.a2cid_plan_batch(n, u, v, 1.0, 0.5, t0, _batch(ops, level_off, t_sync))
+    assert e.value.code == code, str(e.value)
+    assert list(t0) == [0.0, 0.0, 0.0, 0.5]
+
+
+def test_empty_batch_is_fine():
+    n = 4
+    u, v = _uv(graph.ring(n))
+    t1, coef = a2.a2cid_plan_batch(n, u, v, 1.0, 0.5, np.zeros(n), _batch([], [0]))
+    assert len(coef) == 0 and np.all(t1 == 0)
