@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the A2CiD2 hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic events: the scheduler draws
+and level-packs `--batch` events, the planner validates them and computes the mixing
+coefficients, the level kernels apply them to x and xt, and the observables kernel reads the
+state once.  Inputs (state, c_i, gradient-noise pool) are resident in HBM before timing starts;
+generating the per-event noise stands in for the gradient computation and is outside the path.
+
+Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move: 32 d per gossip
+event, 16 d + 4 d per gradient input per gradient event, 8 n d per observables call), events/s,
+the roofline of the dominant kernel measured with HIP events on its own stream, and the CPU oracle
+timed on a bounded sample on this machine's host cores.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
+
+# HBM traffic of the level kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
+# copy kernel of known size (profiles/): filled in by hand after such a run, null until then.
+MEASURED_TRAFFIC = {}
+
+
+def cpu_baseline(cfg, seconds_budget=20.0):
+    """The oracle as it stands, one host core, on a d-slice of the same workload (work is linear in d)."""
+    import numpy as np
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    import parity_util as pu
+    from oracle import core
+    d_slice, n_events = 250_000, 400
+    edges, node_rate, edge_rate, eta, alpha, alpha_t = pu.oracle_params(cfg)
+    ev = core.generate_events(cfg.n, [e[0] for e in edges], [e[1] for e in edges], node_rate,
+                              np.full(len(edges), edge_rate), cfg.seed, n_events)
+    rng = np.random.default_rng(0)
+    x0 = rng.normal(0.0, cfg.init_sigma, (cfg.n, d_slice))
+    is_grad = ev.kind == 0
+    m = len(ev)
+    c = c_row = xi = xi_row = None
+    if cfg.use_c:
+        c = rng.normal(size=(cfg.n, d_slice)); c_row = np.where(is_grad, ev.i, -1)
+    if cfg.xi_sigma > 0:
+        ids = np.nonzero(is_grad)[0]
+        xi = rng.normal(0.0, cfg.xi_sigma, (len(ids), d_slice))
+        xi_row = np.full(m, -1, np.int64); xi_row[ids] = np.arange(len(ids))
+    st = core.State(x0, None, eta, alpha, alpha_t)
+    n_goss, n_grad = int((~is_grad).sum()), int(is_grad.sum())
+    per_col = 32.0 * n_goss + (16.0 + (4.0 if xi is not None else 0.0) + (4.0 if c is not None else 0.0)) * n_grad
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        st.t[:] = 0.0
+        st.apply(ev, cfg.gamma, cfg.gscale, xi, xi_row, c, c_row)
+        st.stats(float(ev.t[-1]))
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > seconds_budget * 0.5 or reps >= 50:
+            break
+    per_col += 8.0 * cfg.n
+    gbs = per_col * d_slice * reps / el / 1e9
+    ev_s_full_d = m * reps / el * d_slice / cfg.d
+    return {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "events_per_s_at_full_d": ev_s_full_d,
+            "sample": f"first {m} events of {cfg.name} + one observables pass on a {d_slice}-column slice of "
+                      f"all {cfg.n} workers, fp64 state, repeated {reps}x ({el:.1f} s); bytes counted with the "
+                      f"same fp32 algorithmic formula as the GPU figure; host has {os.cpu_count()} cores"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4", help="C1..C5, C4-baseline")
+    ap.add_argument("--batch", type=int, default=1024, help="events per step")
+    ap.add_argument("--d", type=int, default=None, help="override the parameter count (debugging)")
+    ap.add_argument("--unroll", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true", help="do not bracket each kernel launch with HIP events")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU (workers are rows of one device buffer; "
+                 "no collectives exist) -- use --gpus 1")
+
+    import torch
+    from paper_2306_08289_amd import workloads as wl
+
+    cfg = wl.CONFIGS[args.workload]
+    if args.d:
+        cfg = wl.scaled(cfg, d=args.d)
+    torch.cuda.set_device(0)
+    w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True)
+    if args.unroll is not None or args.nontemporal is not None:
+        w.engine.set_tuning(args.unroll or 4, args.nontemporal or 0)
+    stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
+
+    def step():
+        b = w.step()
+        if not args.no_stats:
+            w.engine.stats(w.t_last)
+        return b
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    w.engine.counters(reset=True)
+    if not args.no_profile:
+        w.engine.profile(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    cnt = w.engine.counters()
+    launches, kernel_ms = (0, 0.0)
+    if not args.no_profile:
+        launches, kernel_ms = w.engine.profile_read()
+        w.engine.profile(False)
+
+    total_bytes = cnt["bytes"] + stats_bytes * args.steps
+    events = cnt["gossip"] + cnt["gradient"]
+    value = total_bytes / elapsed / 1e9
+    roofline = None
+    if launches:
+        achieved = cnt["bytes"] / (kernel_ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "level_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                    "traffic": MEASURED_TRAFFIC.get(args.workload),
+                    "launches": launches, "avg_launch_ms": kernel_ms / launches,
+                    "alg_bytes_per_launch": cnt["bytes"] / launches}
+    out = {
+        "metric": "achieved HBM GB/s (algorithmic bytes) on the event stream, 64 workers x 25.6M fp32 params"
+                  if cfg.n == 64 and cfg.d == 25_600_000 else f"achieved HBM GB/s (algorithmic bytes), {cfg.name}",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: n={cfg.n} {cfg.topology} graph, d={cfg.d} fp32, "
+                               f"{args.batch} events per step" + ("" if args.no_stats else " + one observables pass"),
+                   "eta": w.eta, "alpha": w.alpha, "alpha_tilde": w.alpha_tilde, "gamma": cfg.gamma,
+                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal},
+        "events_per_s": events / elapsed, "gossip_events_per_s": cnt["gossip"] / elapsed,
+        "gradient_events_per_s": cnt["gradient"] / elapsed,
+        "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "roofline": roofline,
+    }
+    w.close()
+    del w
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

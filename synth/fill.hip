@@ -38,7 +38,7 @@ __device__ __forceinline__ void box_muller(uint32_t w0, uint32_t w1, float &z0, 
     p = p * z + 1.0f;
     const float ln = (float)e * 0.693147182464599609375f + (s + s) * p;
     const float neg = -ln;
-    const float r = __fsqrt_rn(neg + neg);
+    const float r = sqrtf(neg + neg);   // correctly rounded (the _rn intrinsic is not)
 
     const uint32_t w = w1 >> 8;
     const uint32_t quad = w >> 22;
