@@ -23,9 +23,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
-# HBM traffic of the level kernel per launch, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs scaled by a
-# copy kernel of known size (profiles/): filled in by hand after such a run, null until then.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch of the dominant kernel in the default configuration, from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
+# size: profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the workload, batch size and kernel it names.
+MEASURED_TRAFFIC = {("C4", 1024, "walk_kernel"): 7.9222e11}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -82,6 +83,8 @@ def main():
     ap.add_argument("--d", type=int, default=None, help="override the parameter count (debugging)")
     ap.add_argument("--unroll", type=int, default=None)
     ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--threads", type=int, default=None)
+    ap.add_argument("--walk", type=int, default=None, help="1: one launch per batch (default), 0: one per level")
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket each kernel launch with HIP events")
@@ -91,15 +94,16 @@ def main():
                  "no collectives exist) -- use --gpus 1")
 
     import torch
-    from paper_2306_08289_amd import workloads as wl
+    from paper_2306_08289_amd import workloads as wl, a2cid_stream_probe
 
     cfg = wl.CONFIGS[args.workload]
     if args.d:
         cfg = wl.scaled(cfg, d=args.d)
     torch.cuda.set_device(0)
     w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True)
-    if args.unroll is not None or args.nontemporal is not None:
-        w.engine.set_tuning(args.unroll or 4, args.nontemporal or 0)
+    tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
+    if any(v is not None for v in tuning):
+        w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 1))])
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
 
     def step():
@@ -110,6 +114,22 @@ def main():
 
     for _ in range(args.warmup):
         step()
+    torch.cuda.synchronize()
+
+    # streaming ceiling of this machine: a plain copy of 1/4 of the state (>= 1.6 GB each way at full size)
+    rows = max(1, cfg.n // 4)
+    src, dst = w.x[:rows].reshape(-1), w.xt[cfg.n - rows:].reshape(-1)
+    keep = dst.clone()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a2cid_stream_probe(src, dst)
+    e0.record()
+    for _ in range(5):
+        a2cid_stream_probe(src, dst)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 8.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    dst.copy_(keep)
+    del keep
     torch.cuda.synchronize()
     w.engine.counters(reset=True)
     if not args.no_profile:
@@ -129,11 +149,12 @@ def main():
     events = cnt["gossip"] + cnt["gradient"]
     value = total_bytes / elapsed / 1e9
     roofline = None
+    kernel_name = "level_kernel" if args.walk == 0 else "walk_kernel"
     if launches:
         achieved = cnt["bytes"] / (kernel_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "level_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC.get(args.workload),
+                    "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if not args.d else None,
                     "launches": launches, "avg_launch_ms": kernel_ms / launches,
                     "alg_bytes_per_launch": cnt["bytes"] / launches}
     out = {
@@ -145,10 +166,12 @@ def main():
         "config": {"workload": f"{cfg.name}: n={cfg.n} {cfg.topology} graph, d={cfg.d} fp32, "
                                f"{args.batch} events per step" + ("" if args.no_stats else " + one observables pass"),
                    "eta": w.eta, "alpha": w.alpha, "alpha_tilde": w.alpha_tilde, "gamma": cfg.gamma,
-                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal},
+                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal, "threads": args.threads, "walk": args.walk},
         "events_per_s": events / elapsed, "gossip_events_per_s": cnt["gossip"] / elapsed,
         "gradient_events_per_s": cnt["gradient"] / elapsed,
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "copy_ceiling": {"value": copy_gbs, "unit": "GB/s",
+                         "what": f"plain device copy of {8.0 * src.numel() / 1e9:.2f} GB (read + write) on this machine"},
         "roofline": roofline,
     }
     w.close()

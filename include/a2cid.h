@@ -216,9 +216,19 @@ void a2cid_sched_destroy(a2cid_sched *s);
 
 /* ---- diagnostics and measurement ------------------------------------------------------- */
 
-/* Launch shape of the level kernel: unroll = 16-byte pieces per lane and row (1, 2, 4 or 8),
- * nontemporal != 0 selects non-temporal loads and stores.  Results do not depend on it. */
-int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal);
+/* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
+ * nontemporal != 0 selects non-temporal loads and stores, threads = workgroup size (64 ... 1024,
+ * a power of two), walk != 0 applies a whole batch with one launch in which every workgroup walks all
+ * operations for its own columns, walk == 0 uses one launch per level.  Default: 1, 0, 256, 1
+ * (tiles shrink automatically for short rows).
+ * Results do not depend on it. */
+int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t walk);
+
+/* Measurement aid, independent of any context: enqueues a plain copy of n floats (n a multiple
+ * of 4) from src to dst (device pointers, 16-byte aligned, non-overlapping) on hip_stream, with
+ * the same access shape as the event kernels.  It moves exactly 8 n bytes, which gives the
+ * practical streaming ceiling of the machine at hand and the scale of its HBM byte counters. */
+int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream);
 
 /* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
  * and the algorithmic byte count (per event: 32 d for gossip; 16 d for a gradient event plus
@@ -227,7 +237,7 @@ int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal);
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
                    double *algorithmic_bytes, int32_t reset);
 
-/* While enabled, every level-kernel launch is bracketed by a pair of HIP events on the
+/* While enabled, every event-kernel launch is bracketed by a pair of HIP events on the
  * context's stream.  a2cid_profile_read waits for the stream, returns the number of launches
  * timed since the previous read and the sum of their durations in milliseconds, and forgets
  * them. */

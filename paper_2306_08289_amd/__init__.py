@@ -5,4 +5,4 @@ this package is only the ctypes binding.  There is no CPU fallback: using the en
 built library raises ImportError.
 """
 from .binding import (A2cidError, Batch, Engine, Scheduler, OP_DTYPE, COEF_DTYPE, KIND_GOSSIP,  # noqa: F401
-                      KIND_GRADIENT, a2cid_graph_params, a2cid_plan_batch, load)
+                      KIND_GRADIENT, a2cid_graph_params, a2cid_plan_batch, a2cid_stream_probe, load)

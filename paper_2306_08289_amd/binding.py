@@ -78,7 +78,8 @@ SIGNATURES = {
     "a2cid_sched_skip": (C.c_int, [C.c_void_p, C.c_int64]),
     "a2cid_sched_counts": (C.c_int, [C.c_void_p, _P(C.c_int64)]),
     "a2cid_sched_destroy": (None, [C.c_void_p]),
-    "a2cid_set_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "a2cid_set_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "a2cid_stream_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
                                  C.c_int32]),
     "a2cid_profile": (C.c_int, [C.c_void_p, C.c_int32]),
@@ -113,6 +114,16 @@ def _check(rc):
 
 def _dptr(arr):
     return arr.ctypes.data_as(_P(C.c_double))
+
+
+def a2cid_stream_probe(src, dst, stream=None):
+    """Enqueues the copy probe dst <- src on two equally sized contiguous fp32 CUDA tensors."""
+    import torch
+    assert src.is_cuda and dst.is_cuda and src.dtype == dst.dtype == torch.float32
+    assert src.is_contiguous() and dst.is_contiguous() and src.numel() == dst.numel()
+    if stream is None:
+        stream = torch.cuda.current_stream(src.device)
+    _check(load().a2cid_stream_probe(src.data_ptr(), dst.data_ptr(), src.numel(), stream.cuda_stream))
 
 
 class _GraphArg:
@@ -249,8 +260,8 @@ class Engine:
     def synchronize(self):
         _check(load().a2cid_synchronize(self._h))
 
-    def set_tuning(self, unroll, nontemporal):
-        _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal))))
+    def set_tuning(self, unroll=1, nontemporal=0, threads=256, walk=1):
+        _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(bool(walk))))
 
     def counters(self, reset=False):
         g, gr, la = C.c_int64(), C.c_int64(), C.c_int64()

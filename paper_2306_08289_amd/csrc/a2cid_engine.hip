@@ -53,8 +53,10 @@ struct a2cid_ctx {
     Slot slots[kSlots];
     int next_slot = 0;
     // launch shape of the level kernel (tunable through a2cid_set_tuning)
-    int unroll = 4;
+    int unroll = 1;
     int nontemporal = 0;
+    int threads = 256;
+    int walk = 1;                       // 1: one walk launch per batch; 0: one launch per level
     // observables scratch
     float *b_host = nullptr, *b_dev = nullptr;
     double *partials = nullptr, *out_dev = nullptr, *out_host = nullptr;
@@ -90,18 +92,36 @@ int get_event(a2cid_ctx *c, hipEvent_t *e) {
     return A2CID_OK;
 }
 
-template <int U, bool NT>
-void launch_level_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops) {
+template <int U, bool NT, int TPB>
+void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
     const int64_t n4 = c->d >> 2;
-    const int64_t per_block = (int64_t)U * kThreads;
+    const int64_t per_block = (int64_t)U * TPB;
     int64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;   // the scalar tail lives in tile 0
-    dim3 grid((unsigned)blocks, (unsigned)n_ops);
-    hipLaunchKernelGGL((level_kernel<U, NT>), grid, dim3(kThreads), 0, c->stream, c->x, c->xt, c->ld, c->d,
-                       ops, (float)c->alpha, (float)c->alpha_t);
+    if (walk) {
+        hipLaunchKernelGGL((walk_kernel<U, NT, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
+                           c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
+    } else {
+        hipLaunchKernelGGL((level_kernel<U, NT, TPB>), dim3((unsigned)blocks, (unsigned)n_ops), dim3(TPB), 0,
+                           c->stream, c->x, c->xt, c->ld, c->d, ops, (float)c->alpha, (float)c->alpha_t);
+    }
 }
 
-int launch_level(a2cid_ctx *c, const DevOp *ops, int32_t n_ops) {
+template <int U, bool NT>
+void launch_u(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
+    int threads = c->threads;
+    while (threads > 64 && (c->d >> 2) / ((int64_t)U * threads) < 2048) threads >>= 1;
+    switch (threads) {
+        case 64: launch_t<U, NT, 64>(c, ops, n_ops, walk); break;
+        case 128: launch_t<U, NT, 128>(c, ops, n_ops, walk); break;
+        case 512: launch_t<U, NT, 512>(c, ops, n_ops, walk); break;
+        case 1024: launch_t<U, NT, 1024>(c, ops, n_ops, walk); break;
+        default: launch_t<U, NT, 256>(c, ops, n_ops, walk); break;
+    }
+}
+
+// Enqueues n_ops operations: as one level (they must touch disjoint rows) or as a walk in order.
+int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
     TimedLaunch tl{};
     if (c->profiling) {
         if (int rc = get_event(c, &tl.start)) return rc;
@@ -109,11 +129,13 @@ int launch_level(a2cid_ctx *c, const DevOp *ops, int32_t n_ops) {
         A2CID_HIP(hipEventRecord(tl.start, c->stream));
     }
     const bool nt = c->nontemporal != 0;
-    switch (c->unroll) {
-        case 1: nt ? launch_level_t<1, true>(c, ops, n_ops) : launch_level_t<1, false>(c, ops, n_ops); break;
-        case 2: nt ? launch_level_t<2, true>(c, ops, n_ops) : launch_level_t<2, false>(c, ops, n_ops); break;
-        case 8: nt ? launch_level_t<8, true>(c, ops, n_ops) : launch_level_t<8, false>(c, ops, n_ops); break;
-        default: nt ? launch_level_t<4, true>(c, ops, n_ops) : launch_level_t<4, false>(c, ops, n_ops); break;
+    // short rows: shrink the tile so that the grid still has a few thousand workgroups
+    int unroll = c->unroll;
+    while (unroll > 1 && (c->d >> 2) / ((int64_t)unroll * c->threads) < 2048) unroll >>= 1;
+    switch (unroll) {
+        case 1: nt ? launch_u<1, true>(c, ops, n_ops, walk) : launch_u<1, false>(c, ops, n_ops, walk); break;
+        case 2: nt ? launch_u<2, true>(c, ops, n_ops, walk) : launch_u<2, false>(c, ops, n_ops, walk); break;
+        default: nt ? launch_u<4, true>(c, ops, n_ops, walk) : launch_u<4, false>(c, ops, n_ops, walk); break;
     }
     A2CID_HIP(hipGetLastError());
     if (c->profiling) {
@@ -141,7 +163,7 @@ int enqueue_mix_all(a2cid_ctx *c, const std::vector<float> &b) {
         }
         if (count == 0) continue;
         A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
-        if (int rc = launch_level(c, s->dev, count)) return rc;
+        if (int rc = launch_ops(c, s->dev, count, false)) return rc;
         A2CID_HIP(hipEventRecord(s->done, c->stream));
         s->in_flight = true;
         c->alg_bytes += 16.0 * (double)c->d * count;
@@ -257,10 +279,14 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 o.pad1 = 0;
             }
             A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
-            for (int32_t ll = l; ll < l_end; ++ll) {
-                const int64_t lo = batch->level_off[ll] - first, sz = batch->level_off[ll + 1] - batch->level_off[ll];
-                if (sz == 0) continue;
-                if (int rc = launch_level(c, s->dev + lo, (int32_t)sz)) return rc;
+            if (c->walk) {
+                if (int rc = launch_ops(c, s->dev, (int32_t)count, true)) return rc;
+            } else {
+                for (int32_t ll = l; ll < l_end; ++ll) {
+                    const int64_t lo = batch->level_off[ll] - first, sz = batch->level_off[ll + 1] - batch->level_off[ll];
+                    if (sz == 0) continue;
+                    if (int rc = launch_ops(c, s->dev + lo, (int32_t)sz, false)) return rc;
+                }
             }
             A2CID_HIP(hipEventRecord(s->done, c->stream));
             s->in_flight = true;
@@ -317,8 +343,7 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     hipLaunchKernelGGL((stats_kernel<kStatsV>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt, c->ld,
                        c->d, c->n, c->b_dev, c->partials, n_tiles);
     A2CID_HIP(hipGetLastError());
-    hipLaunchKernelGGL(stats_final_kernel, dim3((m + kThreads - 1) / kThreads), dim3(kThreads), 0, c->stream,
-                       c->partials, blocks, m, c->out_dev);
+    hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, c->partials, blocks, m, c->out_dev);
     A2CID_HIP(hipGetLastError());
     A2CID_HIP(hipMemcpyAsync(c->out_host, c->out_dev, sizeof(double) * m, hipMemcpyDeviceToHost, c->stream));
     A2CID_HIP(hipStreamSynchronize(c->stream));
@@ -352,13 +377,27 @@ int a2cid_synchronize(a2cid_ctx *c) {
     return A2CID_OK;
 }
 
-int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal) {
+int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t walk) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
-    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8)
-        return fail(A2CID_EINVAL, "unroll must be 1, 2, 4 or 8");
+    if (unroll != 1 && unroll != 2 && unroll != 4) return fail(A2CID_EINVAL, "unroll must be 1, 2 or 4");
+    if (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024)
+        return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
     c->unroll = unroll;
     c->nontemporal = nontemporal ? 1 : 0;
+    c->threads = threads;
+    c->walk = walk ? 1 : 0;
+    return A2CID_OK;
+}
+
+int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream) {
+    clear_error();
+    if (!src || !dst || n < 4 || (n & 3)) return fail(A2CID_EINVAL, "src / dst NULL or n not a positive multiple of 4");
+    if (((uintptr_t)src | (uintptr_t)dst) & 15u) return fail(A2CID_EALIGN, "src and dst must be 16-byte aligned");
+    const int64_t n4 = n >> 2;
+    hipLaunchKernelGGL(copy_probe_kernel, dim3((unsigned)((n4 + 1023) / 1024)), dim3(256), 0, (hipStream_t)hip_stream,
+                       (const v4f *)src, (v4f *)dst, n4);
+    A2CID_HIP(hipGetLastError());
     return A2CID_OK;
 }
 

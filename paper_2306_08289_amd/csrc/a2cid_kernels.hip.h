@@ -78,25 +78,21 @@ __device__ __forceinline__ void store4(v4f *p, v4f v) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Level kernel: grid = (column tiles, operations of one level).  A workgroup applies ONE
-// operation to a tile of U * 256 float4 columns: every lane loads U 16-byte pieces of each
-// row the operation touches (coalesced: consecutive lanes, consecutive 16 bytes), updates them
-// in registers and stores them back in place.  Operations of a level touch disjoint rows, so
-// no two workgroups of a launch ever touch the same byte.
+// One operation applied to one tile of U * TPB float4 columns by a workgroup of TPB lanes:
+// every lane loads U 16-byte pieces of each row the operation touches (coalesced: consecutive
+// lanes, consecutive 16 bytes), updates them in registers and stores them back in place.
 //   gossip:   4 rows in, 4 rows out  (32 bytes per column)
 //   gradient: 2 rows (+ xi, + c) in, 2 rows out  (16 / 20 / 24 bytes per column)
 //   mix only: 2 rows in, 2 rows out
-// The d % 4 trailing columns of a row are handled by scalar code in the first tile.
+// The d % 4 trailing columns of a row are handled by scalar code in tile 0.
 // ------------------------------------------------------------------------------------------
-template <int U, bool NT>
-__global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, float *__restrict__ xt,
-                                                         int64_t ld, int64_t d,
-                                                         const DevOp *__restrict__ ops,
-                                                         float alpha, float alpha_t) {
-    const DevOp op = ops[blockIdx.y];
+template <int U, bool NT, int TPB>
+__device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
+                                              int64_t d, const DevOp &op, int64_t tile,
+                                              float alpha, float alpha_t) {
     const int64_t n4 = d >> 2;                                   // whole float4 pieces per row
-    const int64_t base = (int64_t)blockIdx.x * (U * kThreads) + threadIdx.x;
-    const bool full = (int64_t)(blockIdx.x + 1) * (U * kThreads) <= n4;
+    const int64_t base = (int64_t)tile * (U * TPB) + threadIdx.x;
+    const bool full = (int64_t)(tile + 1) * (U * TPB) <= n4;
 
     float *xi_row = x + (int64_t)op.row_i * ld;
     float *xti_row = xt + (int64_t)op.row_i * ld;
@@ -109,13 +105,13 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
         if (full) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
                 b[u] = load4<NT>(pj + k); bt[u] = load4<NT>(ptj + k);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
                 store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
                 store4<NT>(pj + k, b[u]); store4<NT>(ptj + k, bt[u]);
@@ -123,7 +119,7 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 if (k < n4) {
                     a[u] = pi[k]; at[u] = pti[k]; b[u] = pj[k]; bt[u] = ptj[k];
                     gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
@@ -131,7 +127,7 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
                 }
             }
         }
-        if (blockIdx.x == 0) {
+        if (tile == 0) {
             const int64_t k = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && k < d) {
                 float s0 = xi_row[k], s1 = xti_row[k], s2 = xj_row[k], s3 = xtj_row[k];
@@ -150,14 +146,14 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
         if (full) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
                 g[u] = has_xi ? load4<NT>(pxi + k) : zero;
                 c[u] = has_c ? load4<NT>(pc + k) : zero;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 if (grad) gradient_update(a[u], at[u], g[u], c[u], op);
                 else mix(a[u], at[u], op.b_i);
                 store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
@@ -165,7 +161,7 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
         } else {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int64_t k = base + u * kThreads;
+                const int64_t k = base + u * TPB;
                 if (k < n4) {
                     a[u] = pi[k]; at[u] = pti[k];
                     g[u] = has_xi ? pxi[k] : zero;
@@ -176,7 +172,7 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
                 }
             }
         }
-        if (blockIdx.x == 0) {
+        if (tile == 0) {
             const int64_t k = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && k < d) {
                 float s0 = xi_row[k], s1 = xti_row[k];
@@ -186,6 +182,64 @@ __global__ __launch_bounds__(kThreads) void level_kernel(float *__restrict__ x, 
                 xi_row[k] = s0; xti_row[k] = s1;
             }
         }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Level kernel: grid = (column tiles, operations of one level); one launch per level.
+// Operations of a level touch disjoint rows, so no two workgroups of a launch ever touch the
+// same byte, and the launch boundary orders consecutive levels.
+// ------------------------------------------------------------------------------------------
+template <int U, bool NT, int TPB>
+__global__ __launch_bounds__(TPB) void level_kernel(float *__restrict__ x, float *__restrict__ xt,
+                                                    int64_t ld, int64_t d, const DevOp *__restrict__ ops,
+                                                    float alpha, float alpha_t) {
+    const DevOp op = ops[blockIdx.y];
+    apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, (int64_t)blockIdx.x, alpha, alpha_t);
+}
+
+// ------------------------------------------------------------------------------------------
+// Walk kernel: grid = column tiles; one launch per batch.  Eq. (1) couples workers but never
+// coordinates, so a workgroup that owns a tile of columns can apply EVERY operation of the batch
+// to that tile, in the batch's (level-sorted, hence per-worker serial) order, without
+// synchronising with any other workgroup: all accesses of a lane hit the lane's own columns and
+// a wave's accesses to one address are performed in program order.  Compared with one launch
+// per level this removes the drain/fill bubble between levels, which matters because most levels
+// of a greedily packed batch hold far fewer than n/2 operations.  Every operation still reads and
+// writes its rows from and to memory (the tiles of all resident workgroups together exceed the
+// caches by far), so the traffic is the same 32 d / 16-24 d bytes per event.
+// Operation records are uniform per workgroup and are fetched with scalar loads.
+// Measured fastest on MI355X with TPB = 256, U = 1 and ordinary (temporal) accesses.
+// ------------------------------------------------------------------------------------------
+template <int U, bool NT, int TPB>
+__global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float *__restrict__ xt,
+                                                   int64_t ld, int64_t d, const DevOp *__restrict__ ops,
+                                                   int32_t n_ops, float alpha, float alpha_t) {
+    const int64_t tile = blockIdx.x;
+    for (int32_t k = 0; k < n_ops; ++k) {
+        const DevOp op = ops[k];
+        apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Plain device copy of n4 float4 pieces with the event kernels' access shape (4 pieces per lane,
+// 256 lanes, non-temporal).  A measurement aid: it moves a known number of bytes, which gives
+// the practical streaming ceiling of the machine at hand and the scale of the HBM counters.
+// ------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void copy_probe_kernel(const v4f *__restrict__ src, v4f *__restrict__ dst,
+                                                         int64_t n4) {
+    const int64_t base = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    v4f r[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t k = base + u * 256;
+        if (k < n4) r[u] = __builtin_nontemporal_load(src + k);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t k = base + u * 256;
+        if (k < n4) __builtin_nontemporal_store(r[u], dst + k);
     }
 }
 
@@ -302,15 +356,22 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict
     if (tid == 0) { out[2 * n] = scons[0][0]; out[2 * n + 1] = scons[1][0]; }
 }
 
-// Sums the per-workgroup partials in block order (deterministic): out[j] = sum_b partials[b][j].
+// Sums the per-workgroup partials: workgroup j produces out[j] = sum_b partials[b][j].  Lane t adds
+// blocks t, t + 256, ... in order, then a fixed-shape tree combines the 256 lanes (deterministic).
 __global__ __launch_bounds__(kThreads) void stats_final_kernel(const double *__restrict__ partials,
                                                                int32_t n_blocks, int32_t m,
                                                                double *__restrict__ out) {
-    const int j = blockIdx.x * kThreads + threadIdx.x;
-    if (j >= m) return;
+    __shared__ double acc[kThreads];
+    const int j = blockIdx.x, tid = threadIdx.x;
     double s = 0.0;
-    for (int32_t b = 0; b < n_blocks; ++b) s += partials[(size_t)b * m + j];
-    out[j] = s;
+    for (int32_t b = tid; b < n_blocks; b += kThreads) s += partials[(size_t)b * m + j];
+    acc[tid] = s;
+    __syncthreads();
+    for (int w = kThreads / 2; w > 0; w >>= 1) {
+        if (tid < w) acc[tid] += acc[tid + w];
+        __syncthreads();
+    }
+    if (tid == 0) out[j] = acc[0];
 }
 
 }  // namespace a2cid

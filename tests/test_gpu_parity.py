@@ -79,9 +79,13 @@ def test_small_configs_match_oracle_everywhere(name, d, events, batch):
     _compare(wl.scaled(wl.CONFIGS[name], d=d, events=events), events, batch)
 
 
-@pytest.mark.parametrize("unroll,nt", [(1, 0), (2, 1), (4, 1), (8, 0), (8, 1)])
-def test_launch_shapes_give_the_same_answer(unroll, nt):
-    _compare(wl.scaled(wl.CONFIGS["C2"], d=2 * 8 * 1024 + 517, events=1500), 1500, 500, tuning=(unroll, nt))
+@pytest.mark.parametrize("unroll,nt,threads,walk", [(1, 0, 64, 0), (2, 1, 128, 0), (4, 1, 256, 1), (4, 0, 64, 0),
+                                                   (2, 0, 512, 1), (1, 1, 128, 1), (4, 1, 64, 0),
+                                                   (1, 0, 1024, 1), (2, 1, 1024, 0)])
+def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
+    # rows long enough that the engine keeps the requested unroll (it shrinks tiles for short rows)
+    cfg = wl.scaled(wl.CONFIGS["C2"], d=2048 * 1024 * 4 * 4 + 517, events=600)
+    _compare(cfg, 600, 300, cols=pu.sample_columns(cfg.d, 4096, seed=2), tuning=(unroll, nt, threads, walk))
 
 
 @pytest.mark.parametrize("name,events,batch", [("C2", 3000, 1024), ("C3", 600, 512), ("C4", 400, 400),
