@@ -224,6 +224,11 @@ void a2cid_sched_destroy(a2cid_sched *s);
  * Results do not depend on it. */
 int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t walk);
 
+/* Launch shape of the observables kernel: pieces = 16-byte pieces per lane and row (1 or 2), rows =
+ * rows whose loads are issued together (1, 2 or 4), blocks = workgroups (grid-stride over column
+ * tiles, 1 ... 8192).  Default: 2, 2, 2048.  Changes the summation order, hence the last bits. */
+int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t blocks);
+
 /* Measurement aid, independent of any context: enqueues a plain copy of n floats (n a multiple
  * of 4) from src to dst (device pointers, 16-byte aligned, non-overlapping) on hip_stream, with
  * the same access shape as the event kernels.  It moves exactly 8 n bytes, which gives the

@@ -79,6 +79,7 @@ SIGNATURES = {
     "a2cid_sched_counts": (C.c_int, [C.c_void_p, _P(C.c_int64)]),
     "a2cid_sched_destroy": (None, [C.c_void_p]),
     "a2cid_set_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "a2cid_set_stats_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
     "a2cid_stream_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
                                  C.c_int32]),
@@ -262,6 +263,9 @@ class Engine:
 
     def set_tuning(self, unroll=1, nontemporal=0, threads=256, walk=1):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(bool(walk))))
+
+    def set_stats_tuning(self, pieces=2, rows=2, blocks=2048):
+        _check(load().a2cid_set_stats_tuning(self._h, int(pieces), int(rows), int(blocks)))
 
     def counters(self, reset=False):
         g, gr, la = C.c_int64(), C.c_int64(), C.c_int64()

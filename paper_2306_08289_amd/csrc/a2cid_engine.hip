@@ -24,8 +24,7 @@ namespace {
 
 constexpr int kSlots = 4;               // operation-table staging buffers in flight
 constexpr int64_t kSlotOps = 16384;     // operations per staging buffer (1 MiB)
-constexpr int kStatsBlocks = 2048;      // workgroups of the observables kernel (grid-stride)
-constexpr int kStatsV = 2;              // float4 pieces per lane and row in the observables kernel
+constexpr int kStatsBlocksMax = 8192;   // upper bound on workgroups of the observables kernel (grid-stride)
 
 struct Slot {
     DevOp *host = nullptr;              // pinned
@@ -57,6 +56,7 @@ struct a2cid_ctx {
     int nontemporal = 0;
     int threads = 256;
     int walk = 1;                       // 1: one walk launch per batch; 0: one launch per level
+    int stats_v = 2, stats_r = 2, stats_blocks = 2048;   // launch shape of the observables kernel
     // observables scratch
     float *b_host = nullptr, *b_dev = nullptr;
     double *partials = nullptr, *out_dev = nullptr, *out_host = nullptr;
@@ -217,7 +217,7 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     const size_t m = 2 * (size_t)n + 2;
     A2CID_HIP(hipHostMalloc((void **)&c->b_host, sizeof(float) * n, hipHostMallocDefault));
     A2CID_HIP(hipMalloc((void **)&c->b_dev, sizeof(float) * n));
-    A2CID_HIP(hipMalloc((void **)&c->partials, sizeof(double) * m * kStatsBlocks));
+    A2CID_HIP(hipMalloc((void **)&c->partials, sizeof(double) * m * kStatsBlocksMax));
     A2CID_HIP(hipMalloc((void **)&c->out_dev, sizeof(double) * m));
     A2CID_HIP(hipHostMalloc((void **)&c->out_host, sizeof(double) * m, hipHostMallocDefault));
     return A2CID_OK;
@@ -335,13 +335,22 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
     A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
     const int64_t pieces = (c->d + 3) >> 2;
-    const int64_t per_tile = (int64_t)kStatsV * kThreads;
+    const int v = c->stats_v, r = c->stats_r;
+    const int64_t per_tile = (int64_t)v * kThreads;
     const int64_t n_tiles = (pieces + per_tile - 1) / per_tile;
-    const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, kStatsBlocks);
+    const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, c->stats_blocks);
     const int32_t m = 2 * c->n + 2;
     const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
-    hipLaunchKernelGGL((stats_kernel<kStatsV>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt, c->ld,
-                       c->d, c->n, c->b_dev, c->partials, n_tiles);
+#define A2CID_STATS_LAUNCH(V, R)                                                                               \
+    hipLaunchKernelGGL((stats_kernel<V, R>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt, c->ld, \
+                       c->d, c->n, c->b_dev, c->partials, n_tiles)
+    if (v == 1 && r == 1) A2CID_STATS_LAUNCH(1, 1);
+    else if (v == 1 && r == 2) A2CID_STATS_LAUNCH(1, 2);
+    else if (v == 1 && r == 4) A2CID_STATS_LAUNCH(1, 4);
+    else if (v == 2 && r == 1) A2CID_STATS_LAUNCH(2, 1);
+    else if (v == 2 && r == 4) A2CID_STATS_LAUNCH(2, 4);
+    else A2CID_STATS_LAUNCH(2, 2);
+#undef A2CID_STATS_LAUNCH
     A2CID_HIP(hipGetLastError());
     hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, c->partials, blocks, m, c->out_dev);
     A2CID_HIP(hipGetLastError());
@@ -387,6 +396,16 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     c->nontemporal = nontemporal ? 1 : 0;
     c->threads = threads;
     c->walk = walk ? 1 : 0;
+    return A2CID_OK;
+}
+
+int a2cid_set_stats_tuning(a2cid_ctx *c, int32_t pieces, int32_t rows, int32_t blocks) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if ((pieces != 1 && pieces != 2) || (rows != 1 && rows != 2 && rows != 4))
+        return fail(A2CID_EINVAL, "pieces must be 1 or 2 and rows 1, 2 or 4");
+    if (blocks < 1 || blocks > kStatsBlocksMax) return fail(A2CID_EINVAL, "blocks must be in [1, %d]", kStatsBlocksMax);
+    c->stats_v = pieces; c->stats_r = rows; c->stats_blocks = blocks;
     return A2CID_OK;
 }
 

@@ -273,7 +273,39 @@ __device__ __forceinline__ v4f load4_guarded(const float *row, int64_t g, int64_
     return v;
 }
 
+// Column accumulators of one lane: sum and sum of squares of the pivot-shifted values.
 template <int V>
+struct ColumnAcc {
+    v4f px[V], pxt[V];
+    double sx[V][4], qx[V][4], sxt[V][4], qxt[V][4];
+};
+
+// One row of a tile: mix, per-row partial sums into the wave's LDS slab, column accumulators.
+template <int V>
+__device__ __forceinline__ void stats_row(ColumnAcc<V> &acc, v4f (&a)[V], v4f (&at)[V], float b, bool first,
+                                          double *my_row, int32_t i, int32_t n, int lane) {
+    float rx = 0.f, rxt = 0.f;
+#pragma unroll
+    for (int u = 0; u < V; ++u) {
+        mix(a[u], at[u], b);
+        rx += (a[u].x + a[u].y) + (a[u].z + a[u].w);
+        rxt += (at[u].x + at[u].y) + (at[u].z + at[u].w);
+        if (first) { acc.px[u] = a[u]; acc.pxt[u] = at[u]; }
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const double dx = (double)a[u][c] - (double)acc.px[u][c];
+            const double dxt = (double)at[u][c] - (double)acc.pxt[u][c];
+            acc.sx[u][c] += dx; acc.qx[u][c] += dx * dx;
+            acc.sxt[u][c] += dxt; acc.qxt[u][c] += dxt * dxt;
+        }
+    }
+    rx = wave_sum(rx);
+    rxt = wave_sum(rxt);
+    if (lane == 0) { my_row[i] += (double)rx; my_row[n + i] += (double)rxt; }
+}
+
+// V: float4 pieces per lane and row; R: rows whose loads are issued together (memory-level parallelism).
+template <int V, int R>
 __global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict__ x,
                                                          const float *__restrict__ xt,
                                                          int64_t ld, int64_t d, int32_t n,
@@ -289,51 +321,50 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict
     __syncthreads();
     double *my_row = srow + (size_t)wave * 2 * n;
     const double inv_n = 1.0 / (double)n;
+    const int64_t n4 = d >> 2;
     double cons_x = 0.0, cons_xt = 0.0;
 
     for (int64_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const int64_t g0 = tile * (V * kThreads) + tid;
-        v4f px[V], pxt[V];
-        double sx[V][4], qx[V][4], sxt[V][4], qxt[V][4];
+        const bool full = (tile + 1) * (V * kThreads) <= n4;   // every piece of the tile is a whole float4
+        ColumnAcc<V> acc;
 #pragma unroll
         for (int u = 0; u < V; ++u)
 #pragma unroll
-            for (int c = 0; c < 4; ++c) sx[u][c] = qx[u][c] = sxt[u][c] = qxt[u][c] = 0.0;
+            for (int c = 0; c < 4; ++c) acc.sx[u][c] = acc.qx[u][c] = acc.sxt[u][c] = acc.qxt[u][c] = 0.0;
 
-        for (int32_t i = 0; i < n; ++i) {
+        int32_t i = 0;
+        if (full) {
+            for (; i + R <= n; i += R) {
+                v4f a[R][V], at[R][V];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    const v4f *xr = (const v4f *)(x + (int64_t)(i + r) * ld) + g0;
+                    const v4f *xtr = (const v4f *)(xt + (int64_t)(i + r) * ld) + g0;
+#pragma unroll
+                    for (int u = 0; u < V; ++u) { a[r][u] = xr[u * kThreads]; at[r][u] = xtr[u * kThreads]; }
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    stats_row<V>(acc, a[r], at[r], sb[i + r], i + r == 0, my_row, i + r, n, lane);
+            }
+        }
+        for (; i < n; ++i) {
             const float *xr = x + (int64_t)i * ld, *xtr = xt + (int64_t)i * ld;
-            const float b = sb[i];
             v4f a[V], at[V];
 #pragma unroll
             for (int u = 0; u < V; ++u) {
                 a[u] = load4_guarded(xr, g0 + u * kThreads, d);
                 at[u] = load4_guarded(xtr, g0 + u * kThreads, d);
             }
-            float rx = 0.f, rxt = 0.f;
-#pragma unroll
-            for (int u = 0; u < V; ++u) {
-                mix(a[u], at[u], b);
-                rx += (a[u].x + a[u].y) + (a[u].z + a[u].w);
-                rxt += (at[u].x + at[u].y) + (at[u].z + at[u].w);
-                if (i == 0) { px[u] = a[u]; pxt[u] = at[u]; }
-#pragma unroll
-                for (int c = 0; c < 4; ++c) {
-                    const double dx = (double)a[u][c] - (double)px[u][c];
-                    const double dxt = (double)at[u][c] - (double)pxt[u][c];
-                    sx[u][c] += dx; qx[u][c] += dx * dx;
-                    sxt[u][c] += dxt; qxt[u][c] += dxt * dxt;
-                }
-            }
-            rx = wave_sum(rx);
-            rxt = wave_sum(rxt);
-            if (lane == 0) { my_row[i] += (double)rx; my_row[n + i] += (double)rxt; }
+            stats_row<V>(acc, a, at, sb[i], i == 0, my_row, i, n, lane);
         }
 #pragma unroll
         for (int u = 0; u < V; ++u)
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
-                cons_x += qx[u][c] - sx[u][c] * sx[u][c] * inv_n;
-                cons_xt += qxt[u][c] - sxt[u][c] * sxt[u][c] * inv_n;
+                cons_x += acc.qx[u][c] - acc.sx[u][c] * acc.sx[u][c] * inv_n;
+                cons_xt += acc.qxt[u][c] - acc.sxt[u][c] * acc.sxt[u][c] * inv_n;
             }
     }
 

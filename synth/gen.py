@@ -119,6 +119,40 @@ def normal(seed, domain, row, cols, sigma=1.0, mean=0.0):
 
 
 def normal_rows(seed, domain, rows, cols, sigma=1.0, mean=0.0):
-    """(len(rows), len(cols)) fp32 matrix: one generator row per entry of rows."""
+    """(len(rows), len(cols)) fp32 matrix: one generator row per entry of rows (numpy implementation)."""
     return np.stack([normal(seed, domain, r, cols, sigma, mean) for r in rows]) if len(rows) else \
         np.zeros((0, len(cols)), np.float32)
+
+
+_clib = None
+
+
+def _c_library():
+    """gen_c.c compiled on first use (gcc, -ffp-contract=off): the same definition, ~100x faster."""
+    global _clib
+    if _clib is None:
+        import ctypes as C
+        import os
+        import subprocess
+        here = os.path.dirname(os.path.abspath(__file__))
+        src, lib = os.path.join(here, "gen_c.c"), os.path.join(here, "libsynth_gen.so")
+        if not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+            subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-std=c11", "-shared", "-fPIC",
+                            src, "-o", lib, "-lm"], check=True)
+        _clib = C.CDLL(lib)
+        i64 = np.ctypeslib.ndpointer(np.int64, flags="C_CONTIGUOUS")
+        _clib.synth_normal_rows.argtypes = [C.c_uint64, C.c_uint32, i64, C.c_int64, i64, C.c_int64, C.c_float,
+                                            C.c_float, np.ctypeslib.ndpointer(np.float32, flags="C_CONTIGUOUS")]
+        _clib.synth_normal_rows.restype = None
+    return _clib
+
+
+def normal_rows_fast(seed, domain, rows, cols, sigma=1.0, mean=0.0):
+    """Same values as normal_rows, computed by the C implementation of the same definition."""
+    rows = np.ascontiguousarray(rows, np.int64)
+    cols = np.ascontiguousarray(cols, np.int64)
+    out = np.zeros((len(rows), len(cols)), np.float32)
+    if out.size:
+        _c_library().synth_normal_rows(int(seed), int(domain), rows, len(rows), cols, len(cols),
+                                       float(sigma), float(mean), out)
+    return out

@@ -37,27 +37,52 @@ def oracle_params(cfg):
     return edges, node_rate, edge_rate, eta, 0.5, alpha_t
 
 
-def oracle_run(cfg, cols, n_events, t_final=None):
+class OracleStream:
+    """The oracle following columns `cols` of a workload, fed with the serial stream chunk by chunk."""
+
+    def __init__(self, cfg, cols):
+        self.cfg, self.cols = cfg, np.asarray(cols, np.int64)
+        edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg)
+        self.edges, self.node_rate, self.edge_rate = edges, node_rate, edge_rate
+        x0 = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_INIT, np.arange(cfg.n), self.cols, cfg.init_sigma)
+        self.state = core.State(x0, None, eta, alpha, alpha_t)
+        self.c = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_C, np.arange(cfg.n), self.cols, 1.0) if cfg.use_c else None
+        self.events = None
+        self.done = 0
+
+    def generate(self, n_events):
+        """The first n_events events of the stream (the oracle's own clock code, from time 0)."""
+        self.events = core.generate_events(self.cfg.n, [e[0] for e in self.edges], [e[1] for e in self.edges],
+                                           self.node_rate, np.full(len(self.edges), self.edge_rate), self.cfg.seed,
+                                           n_events)
+        return self.events
+
+    def advance(self, upto):
+        """Applies events [done, upto) of the generated stream."""
+        cfg, ev = self.cfg, self.events[self.done:upto]
+        is_grad = ev.kind == 0
+        m = len(ev)
+        c_row = xi = xi_row = None
+        if self.c is not None:
+            c_row = np.where(is_grad, ev.i, -1)
+        if cfg.xi_sigma > 0:
+            ids = np.nonzero(is_grad)[0]
+            xi = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_XI, ids + self.done, self.cols, cfg.xi_sigma)
+            xi_row = np.full(m, -1, np.int64)
+            xi_row[ids] = np.arange(len(ids))
+        # the engine receives gamma and gscale as fp32 values
+        self.state.apply(ev, float(np.float32(cfg.gamma)), float(np.float32(cfg.gscale)), xi, xi_row, self.c, c_row)
+        self.done = upto
+        return self.state
+
+
+def oracle_run(cfg, cols, n_events, chunk=20000):
     """Oracle state after the first n_events events of cfg, restricted to columns cols."""
-    edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg)
-    ev = core.generate_events(cfg.n, [e[0] for e in edges], [e[1] for e in edges], node_rate,
-                              np.full(len(edges), edge_rate), cfg.seed, n_events)
-    x0 = gen.normal_rows(cfg.seed, gen.DOMAIN_INIT, range(cfg.n), cols, cfg.init_sigma)
-    st = core.State(x0, None, eta, alpha, alpha_t)
-    is_grad = ev.kind == 0
-    m = len(ev)
-    c = c_row = xi = xi_row = None
-    if cfg.use_c:
-        c = gen.normal_rows(cfg.seed, gen.DOMAIN_C, range(cfg.n), cols, 1.0)
-        c_row = np.where(is_grad, ev.i, -1)
-    if cfg.xi_sigma > 0:
-        ids = np.nonzero(is_grad)[0]
-        xi = gen.normal_rows(cfg.seed, gen.DOMAIN_XI, ids, cols, cfg.xi_sigma)
-        xi_row = np.full(m, -1, np.int64)
-        xi_row[ids] = np.arange(len(ids))
-    # the engine receives gamma and gscale as fp32 values
-    st.apply(ev, float(np.float32(cfg.gamma)), float(np.float32(cfg.gscale)), xi, xi_row, c, c_row)
-    return st, ev
+    o = OracleStream(cfg, cols)
+    ev = o.generate(n_events)
+    for lo in range(0, len(ev), chunk):
+        o.advance(min(len(ev), lo + chunk))
+    return o.state, ev
 
 
 def rel_err(got, want):

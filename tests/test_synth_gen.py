@@ -40,3 +40,16 @@ def test_normal_is_a_pure_function_of_its_coordinates():
     shifted = gen.normal(9, gen.DOMAIN_XI, 1, np.arange(64), sigma=2.0, mean=3.0)
     base = gen.normal(9, gen.DOMAIN_XI, 1, np.arange(64))
     assert np.array_equal(shifted, np.float32(3.0) + np.float32(2.0) * base)
+
+
+def test_c_implementation_is_bit_identical_to_numpy():
+    rng = np.random.default_rng(0)
+    cols = np.unique(np.concatenate([np.arange(40), rng.integers(0, 25_600_000, 3000)]))
+    rows = [0, 1, 63, 999_999, (1 << 33) + 5]
+    for domain, sigma, mean in [(gen.DOMAIN_INIT, 1.0, 0.0), (gen.DOMAIN_XI, 1e-3, 0.0), (gen.DOMAIN_C, 2.0, -0.5)]:
+        a = gen.normal_rows(0xA2C1D2 + (3 << 32), domain, rows, cols, sigma, mean)
+        b = gen.normal_rows_fast(0xA2C1D2 + (3 << 32), domain, rows, cols, sigma, mean)
+        assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    big = gen.normal_rows_fast(1, gen.DOMAIN_INIT, [0], np.arange(2_000_000))[0]
+    assert np.array_equal(big[:5000], gen.normal(1, gen.DOMAIN_INIT, 0, np.arange(5000)))
+    assert abs(big.astype(np.float64).std() - 1) < 0.005
