@@ -218,16 +218,24 @@ void a2cid_sched_destroy(a2cid_sched *s);
 
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores, threads = workgroup size (64 ... 1024,
- * a power of two), walk != 0 applies a whole batch with one launch in which every workgroup walks all
- * operations for its own columns, walk == 0 uses one launch per level.  Default: 1, 0, 256, 1
- * (tiles shrink automatically for short rows).
- * Results do not depend on it. */
-int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t walk);
+ * a power of two), mode = 0: one launch per level; 1: one launch per batch in which every
+ * workgroup walks all operations for its own columns, each operation reading and writing its rows
+ * in device memory (default); 2: as 1, but the workgroup keeps its columns of all touched rows
+ * in LDS for the whole batch, so the state is read and written once per batch instead of once per
+ * event (at most 112 workers; requires every gradient input of a batch to be final when the batch
+ * is submitted).  Default: 1, 0, 256, 1 (tiles shrink automatically for short rows).  All modes
+ * compute the same operations in the same per-worker order. */
+int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t mode);
+
+/* Mode 2 only: waves per workgroup, i.e. how many operations of one level a column tile
+ * processes concurrently (1, 2, 4 or 8; default 8). */
+int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group);
 
 /* Launch shape of the observables kernel: pieces = 16-byte pieces per lane and row (1 or 2), rows =
  * rows whose loads are issued together (1, 2 or 4), blocks = workgroups (grid-stride over column
- * tiles, 1 ... 8192).  Default: 2, 2, 2048.  Changes the summation order, hence the last bits. */
-int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t blocks);
+ * tiles, 1 ... 8192), nontemporal != 0 selects non-temporal loads.  Default: 2, 2, 2048, 1.  The
+ * first three change the summation order, hence the last bits of the results. */
+int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t blocks, int32_t nontemporal);
 
 /* Measurement aid, independent of any context: enqueues a plain copy of n floats (n a multiple
  * of 4) from src to dst (device pointers, 16-byte aligned, non-overlapping) on hip_stream, with
@@ -236,11 +244,12 @@ int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t
 int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream);
 
 /* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
- * and the algorithmic byte count (per event: 32 d for gossip; 16 d for a gradient event plus
- * 4 d for each of xi and c that it reads; 16 d per worker mixed by a2cid_flush).  Any output
- * pointer may be NULL. */
+ * the algorithmic byte count (per event: 32 d for gossip; 16 d for a gradient event plus 4 d for
+ * each of xi and c that it reads; 16 d per worker mixed by a2cid_flush), and, for mode 2, the state
+ * bytes its launches really move (16 d per touched row and launch).  Any output pointer may be
+ * NULL. */
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
-                   double *algorithmic_bytes, int32_t reset);
+                   double *algorithmic_bytes, double *resident_state_bytes, int32_t reset);
 
 /* While enabled, every event-kernel launch is bracketed by a pair of HIP events on the
  * context's stream.  a2cid_profile_read waits for the stream, returns the number of launches

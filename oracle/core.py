@@ -134,6 +134,13 @@ class State:
         assert rc == 0
         return {"consensus_x": cx.value, "consensus_xt": cxt.value, "sum_x": sx, "sum_xt": sxt}
 
+    def mix_workers(self, workers, t_now):
+        """Applies the mixing flow up to t_now to the listed workers in place (and moves their time stamps)."""
+        for i in workers:
+            lib().a2o_mix_row(self.x[i], self.xt[i], self.d, self.eta, float(t_now) - self.t[i])
+            self.t[i] = float(t_now)
+        return self
+
     def flushed(self, t_now):
         """Copy of (x, xt) with every worker mixed up to t_now (what Algorithm 1 returns at T)."""
         x = self.x.copy(); xt = self.xt.copy()

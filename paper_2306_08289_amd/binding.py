@@ -79,10 +79,11 @@ SIGNATURES = {
     "a2cid_sched_counts": (C.c_int, [C.c_void_p, _P(C.c_int64)]),
     "a2cid_sched_destroy": (None, [C.c_void_p]),
     "a2cid_set_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
-    "a2cid_set_stats_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32]),
+    "a2cid_set_stats_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "a2cid_stream_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
-                                 C.c_int32]),
+                                 _P(C.c_double), C.c_int32]),
+    "a2cid_set_resident_group": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_profile": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_profile_read": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_double)]),
     "a2cid_last_error": (C.c_char_p, []),
@@ -261,17 +262,22 @@ class Engine:
     def synchronize(self):
         _check(load().a2cid_synchronize(self._h))
 
-    def set_tuning(self, unroll=1, nontemporal=0, threads=256, walk=1):
-        _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(bool(walk))))
+    def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=1):
+        _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))
 
-    def set_stats_tuning(self, pieces=2, rows=2, blocks=2048):
-        _check(load().a2cid_set_stats_tuning(self._h, int(pieces), int(rows), int(blocks)))
+    def set_resident_group(self, group=8):
+        _check(load().a2cid_set_resident_group(self._h, int(group)))
+
+    def set_stats_tuning(self, pieces=2, rows=2, blocks=2048, nontemporal=1):
+        _check(load().a2cid_set_stats_tuning(self._h, int(pieces), int(rows), int(blocks), int(bool(nontemporal))))
 
     def counters(self, reset=False):
         g, gr, la = C.c_int64(), C.c_int64(), C.c_int64()
-        by = C.c_double()
-        _check(load().a2cid_counters(self._h, C.byref(g), C.byref(gr), C.byref(la), C.byref(by), int(reset)))
-        return {"gossip": g.value, "gradient": gr.value, "launches": la.value, "bytes": by.value}
+        by, rb = C.c_double(), C.c_double()
+        _check(load().a2cid_counters(self._h, C.byref(g), C.byref(gr), C.byref(la), C.byref(by), C.byref(rb),
+                                     int(reset)))
+        return {"gossip": g.value, "gradient": gr.value, "launches": la.value, "bytes": by.value,
+                "resident_state_bytes": rb.value}
 
     def profile(self, enable):
         _check(load().a2cid_profile(self._h, int(bool(enable))))

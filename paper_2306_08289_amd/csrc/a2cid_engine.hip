@@ -29,6 +29,10 @@ constexpr int kStatsBlocksMax = 8192;   // upper bound on workgroups of the obse
 struct Slot {
     DevOp *host = nullptr;              // pinned
     DevOp *dev = nullptr;
+    // resident kernel only: rows touched, compact operation records, gradient inputs in order
+    int32_t *rows_host = nullptr, *rows_dev = nullptr;   // A2CID_MAX_WORKERS entries
+    ResOp *res_host = nullptr, *res_dev = nullptr;       // kSlotOps entries
+    GradIn *gin_host = nullptr, *gin_dev = nullptr;      // kSlotOps entries
     hipEvent_t done = nullptr;
     bool in_flight = false;
 };
@@ -55,14 +59,18 @@ struct a2cid_ctx {
     int unroll = 1;
     int nontemporal = 0;
     int threads = 256;
-    int walk = 1;                       // 1: one walk launch per batch; 0: one launch per level
-    int stats_v = 2, stats_r = 2, stats_blocks = 2048;   // launch shape of the observables kernel
+    int walk = 1;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident
+    int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
+    float *zero_dev = nullptr;          // one zero float: stands in for absent gradient inputs
+    std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
+    int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     // observables scratch
     float *b_host = nullptr, *b_dev = nullptr;
     double *partials = nullptr, *out_dev = nullptr, *out_host = nullptr;
     // counters since creation (or the last a2cid_counters_reset)
     int64_t n_gossip = 0, n_grad = 0, n_launch = 0;
     double alg_bytes = 0.0;
+    double resident_bytes = 0.0;        // state bytes actually moved by resident launches (16 d per touched row)
     // optional per-launch timing
     bool profiling = false;
     std::vector<TimedLaunch> timed;
@@ -146,6 +154,37 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
     return A2CID_OK;
 }
 
+constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row and workgroup + staging: 64 KiB at most
+
+int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, int32_t n_rows) {
+    TimedLaunch tl{};
+    if (c->profiling) {
+        if (int rc = get_event(c, &tl.start)) return rc;
+        if (int rc = get_event(c, &tl.stop)) return rc;
+        A2CID_HIP(hipEventRecord(tl.start, c->stream));
+    }
+    const unsigned blocks = (unsigned)((c->d + 63) / 64);
+    const size_t lds = sizeof(Pair) * 64 * ((size_t)n_rows + kStage);
+#define A2CID_RESIDENT(W)                                                                                      \
+    hipLaunchKernelGGL((resident_kernel<W>), dim3(blocks), dim3(64 * W), lds, c->stream, c->x, c->xt, c->ld,   \
+                       c->d, s->res_dev, n_ops, s->gin_dev, n_grad, s->rows_dev, n_rows, (float)c->alpha,       \
+                       (float)c->alpha_t)
+    switch (c->group) {
+        case 1: A2CID_RESIDENT(1); break;
+        case 2: A2CID_RESIDENT(2); break;
+        case 4: A2CID_RESIDENT(4); break;
+        default: A2CID_RESIDENT(8); break;
+    }
+#undef A2CID_RESIDENT
+    A2CID_HIP(hipGetLastError());
+    if (c->profiling) {
+        A2CID_HIP(hipEventRecord(tl.stop, c->stream));
+        c->timed.push_back(tl);
+    }
+    ++c->n_launch;
+    return A2CID_OK;
+}
+
 // Mixing every worker whose coefficient is non-zero, as one level of mix-only operations.
 int enqueue_mix_all(a2cid_ctx *c, const std::vector<float> &b) {
     int32_t done = 0;
@@ -181,6 +220,12 @@ void a2cid_destroy(a2cid_ctx *c) {
     for (Slot &s : c->slots) {
         if (s.host) (void)hipHostFree(s.host);
         if (s.dev) (void)hipFree(s.dev);
+        if (s.rows_host) (void)hipHostFree(s.rows_host);
+        if (s.rows_dev) (void)hipFree(s.rows_dev);
+        if (s.res_host) (void)hipHostFree(s.res_host);
+        if (s.res_dev) (void)hipFree(s.res_dev);
+        if (s.gin_host) (void)hipHostFree(s.gin_host);
+        if (s.gin_dev) (void)hipFree(s.gin_dev);
         if (s.done) (void)hipEventDestroy(s.done);
     }
     if (c->b_host) (void)hipHostFree(c->b_host);
@@ -188,6 +233,7 @@ void a2cid_destroy(a2cid_ctx *c) {
     if (c->partials) (void)hipFree(c->partials);
     if (c->out_dev) (void)hipFree(c->out_dev);
     if (c->out_host) (void)hipHostFree(c->out_host);
+    if (c->zero_dev) (void)hipFree(c->zero_dev);
     for (TimedLaunch &tl : c->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
     for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     delete c;
@@ -212,6 +258,12 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     for (Slot &s : c->slots) {
         A2CID_HIP(hipHostMalloc((void **)&s.host, sizeof(DevOp) * kSlotOps, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.dev, sizeof(DevOp) * kSlotOps));
+        A2CID_HIP(hipHostMalloc((void **)&s.rows_host, sizeof(int32_t) * A2CID_MAX_WORKERS, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.rows_dev, sizeof(int32_t) * A2CID_MAX_WORKERS));
+        A2CID_HIP(hipHostMalloc((void **)&s.res_host, sizeof(ResOp) * kSlotOps, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.res_dev, sizeof(ResOp) * kSlotOps));
+        A2CID_HIP(hipHostMalloc((void **)&s.gin_host, sizeof(GradIn) * kSlotOps, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.gin_dev, sizeof(GradIn) * kSlotOps));
         A2CID_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
     }
     const size_t m = 2 * (size_t)n + 2;
@@ -220,6 +272,8 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     A2CID_HIP(hipMalloc((void **)&c->partials, sizeof(double) * m * kStatsBlocksMax));
     A2CID_HIP(hipMalloc((void **)&c->out_dev, sizeof(double) * m));
     A2CID_HIP(hipHostMalloc((void **)&c->out_host, sizeof(double) * m, hipHostMallocDefault));
+    A2CID_HIP(hipMalloc((void **)&c->zero_dev, 256));
+    A2CID_HIP(hipMemset(c->zero_dev, 0, 256));
     return A2CID_OK;
 }
 
@@ -278,8 +332,59 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 o.c = op.kind == A2CID_KIND_GRADIENT ? op.c : nullptr;
                 o.pad1 = 0;
             }
+            if (c->walk == 2) {
+                // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
+                // cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring)
+                int32_t n_rows = 0, n_grad = 0;
+                const uintptr_t zero = (uintptr_t)c->zero_dev | 1u;
+                c->slot_of.assign(c->n, -1);
+                for (int32_t ll = l; ll < l_end; ++ll) {
+                    const int64_t lo = batch->level_off[ll] - first, hi = batch->level_off[ll + 1] - first;
+                    int64_t sub = lo;                       // first record of the current sub-level
+                    int32_t g_before = n_grad;
+                    auto close_sub = [&](int64_t end) {
+                        for (int64_t k = sub; k < end; ++k) {
+                            s->res_host[k].w0 |= (uint32_t)(end - k) << 24;
+                            s->res_host[k].g = (uint32_t)g_before | ((uint32_t)n_grad << 16);
+                        }
+                        sub = end;
+                        g_before = n_grad;
+                    };
+                    for (int64_t k = lo; k < hi; ++k) {
+                        const DevOp &o = s->host[k];
+                        if (o.kind == kOpGradient && n_grad - g_before == kStage) close_sub(k);
+                        if (k - sub == 255) close_sub(k);
+                        if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
+                        if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
+                        ResOp &r = s->res_host[k];
+                        r.w0 = (uint32_t)o.kind | ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
+                        r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
+                        r.gamma = o.gamma; r.gscale = o.gscale;
+                        if (o.kind == kOpGradient) {
+                            r.gidx = (uint32_t)n_grad;
+                            s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
+                            s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
+                            ++n_grad;
+                        }
+                    }
+                    close_sub(hi);
+                }
+                A2CID_HIP(hipMemcpyAsync(s->rows_dev, s->rows_host, sizeof(int32_t) * (size_t)n_rows,
+                                         hipMemcpyHostToDevice, c->stream));
+                A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResOp) * (size_t)count,
+                                         hipMemcpyHostToDevice, c->stream));
+                if (n_grad > 0)
+                    A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad,
+                                             hipMemcpyHostToDevice, c->stream));
+                c->resident_bytes += (double)c->d * 16.0 * n_rows;
+                if (int rc = launch_resident(c, s, (int32_t)count, n_grad, n_rows)) return rc;
+                A2CID_HIP(hipEventRecord(s->done, c->stream));
+                s->in_flight = true;
+                l = l_end;
+                continue;
+            }
             A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
-            if (c->walk) {
+            if (c->walk == 1) {
                 if (int rc = launch_ops(c, s->dev, (int32_t)count, true)) return rc;
             } else {
                 for (int32_t ll = l; ll < l_end; ++ll) {
@@ -341,15 +446,16 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, c->stats_blocks);
     const int32_t m = 2 * c->n + 2;
     const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
-#define A2CID_STATS_LAUNCH(V, R)                                                                               \
-    hipLaunchKernelGGL((stats_kernel<V, R>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt, c->ld, \
-                       c->d, c->n, c->b_dev, c->partials, n_tiles)
-    if (v == 1 && r == 1) A2CID_STATS_LAUNCH(1, 1);
-    else if (v == 1 && r == 2) A2CID_STATS_LAUNCH(1, 2);
-    else if (v == 1 && r == 4) A2CID_STATS_LAUNCH(1, 4);
-    else if (v == 2 && r == 1) A2CID_STATS_LAUNCH(2, 1);
-    else if (v == 2 && r == 4) A2CID_STATS_LAUNCH(2, 4);
-    else A2CID_STATS_LAUNCH(2, 2);
+#define A2CID_STATS_LAUNCH(V, R, NT)                                                                            \
+    hipLaunchKernelGGL((stats_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt,       \
+                       c->ld, c->d, c->n, c->b_dev, c->partials, n_tiles)
+    const bool snt = c->stats_nt != 0;
+    if (v == 1 && r == 1) { if (snt) A2CID_STATS_LAUNCH(1, 1, true); else A2CID_STATS_LAUNCH(1, 1, false); }
+    else if (v == 1 && r == 2) { if (snt) A2CID_STATS_LAUNCH(1, 2, true); else A2CID_STATS_LAUNCH(1, 2, false); }
+    else if (v == 1 && r == 4) { if (snt) A2CID_STATS_LAUNCH(1, 4, true); else A2CID_STATS_LAUNCH(1, 4, false); }
+    else if (v == 2 && r == 1) { if (snt) A2CID_STATS_LAUNCH(2, 1, true); else A2CID_STATS_LAUNCH(2, 1, false); }
+    else if (v == 2 && r == 4) { if (snt) A2CID_STATS_LAUNCH(2, 4, true); else A2CID_STATS_LAUNCH(2, 4, false); }
+    else { if (snt) A2CID_STATS_LAUNCH(2, 2, true); else A2CID_STATS_LAUNCH(2, 2, false); }
 #undef A2CID_STATS_LAUNCH
     A2CID_HIP(hipGetLastError());
     hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, c->partials, blocks, m, c->out_dev);
@@ -386,26 +492,37 @@ int a2cid_synchronize(a2cid_ctx *c) {
     return A2CID_OK;
 }
 
-int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t walk) {
+int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t mode) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (unroll != 1 && unroll != 2 && unroll != 4) return fail(A2CID_EINVAL, "unroll must be 1, 2 or 4");
     if (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024)
         return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
+    if (mode < 0 || mode > 2) return fail(A2CID_EINVAL, "mode must be 0 (levels), 1 (walk) or 2 (resident)");
+    if (mode == 2 && c->n > kResidentMaxRows)
+        return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
     c->unroll = unroll;
     c->nontemporal = nontemporal ? 1 : 0;
     c->threads = threads;
-    c->walk = walk ? 1 : 0;
+    c->walk = mode;
     return A2CID_OK;
 }
 
-int a2cid_set_stats_tuning(a2cid_ctx *c, int32_t pieces, int32_t rows, int32_t blocks) {
+int a2cid_set_resident_group(a2cid_ctx *c, int32_t group) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (group != 1 && group != 2 && group != 4 && group != 8) return fail(A2CID_EINVAL, "group must be 1, 2, 4 or 8");
+    c->group = group;
+    return A2CID_OK;
+}
+
+int a2cid_set_stats_tuning(a2cid_ctx *c, int32_t pieces, int32_t rows, int32_t blocks, int32_t nontemporal) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if ((pieces != 1 && pieces != 2) || (rows != 1 && rows != 2 && rows != 4))
         return fail(A2CID_EINVAL, "pieces must be 1 or 2 and rows 1, 2 or 4");
     if (blocks < 1 || blocks > kStatsBlocksMax) return fail(A2CID_EINVAL, "blocks must be in [1, %d]", kStatsBlocksMax);
-    c->stats_v = pieces; c->stats_r = rows; c->stats_blocks = blocks;
+    c->stats_v = pieces; c->stats_r = rows; c->stats_blocks = blocks; c->stats_nt = nontemporal ? 1 : 0;
     return A2CID_OK;
 }
 
@@ -421,14 +538,15 @@ int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream
 }
 
 int a2cid_counters(a2cid_ctx *c, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
-                   double *algorithmic_bytes, int32_t reset) {
+                   double *algorithmic_bytes, double *resident_state_bytes, int32_t reset) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (n_gossip) *n_gossip = c->n_gossip;
     if (n_gradient) *n_gradient = c->n_grad;
     if (n_launches) *n_launches = c->n_launch;
     if (algorithmic_bytes) *algorithmic_bytes = c->alg_bytes;
-    if (reset) { c->n_gossip = c->n_grad = c->n_launch = 0; c->alg_bytes = 0.0; }
+    if (resident_state_bytes) *resident_state_bytes = c->resident_bytes;
+    if (reset) { c->n_gossip = c->n_grad = c->n_launch = 0; c->alg_bytes = c->resident_bytes = 0.0; }
     return A2CID_OK;
 }
 

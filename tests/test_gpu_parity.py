@@ -81,7 +81,7 @@ def test_small_configs_match_oracle_everywhere(name, d, events, batch):
 
 @pytest.mark.parametrize("unroll,nt,threads,walk", [(1, 0, 64, 0), (2, 1, 128, 0), (4, 1, 256, 1), (4, 0, 64, 0),
                                                    (2, 0, 512, 1), (1, 1, 128, 1), (4, 1, 64, 0),
-                                                   (1, 0, 1024, 1), (2, 1, 1024, 0)])
+                                                   (1, 0, 1024, 1), (2, 1, 1024, 0), (1, 0, 256, 2)])
 def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
     # rows long enough that the engine keeps the requested unroll (it shrinks tiles for short rows)
     cfg = wl.scaled(wl.CONFIGS["C2"], d=2048 * 1024 * 4 * 4 + 517, events=600)
@@ -93,3 +93,162 @@ def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
 def test_full_size_configs_on_sampled_columns(name, events, batch):
     cfg = wl.scaled(wl.CONFIGS[name], events=events)
     _compare(cfg, events, batch, cols=pu.sample_columns(cfg.d, 4096, seed=1))
+
+
+def test_trailing_mix_is_fused_into_each_workers_last_operation():
+    # t_sync: every worker touched by the batch ends mixed to t_sync, the others stay where they were
+    cfg = wl.scaled(wl.CONFIGS["C4"], d=4 * 1024 * 2 + 3, events=40)
+    _say(f"t_sync {cfg.name} d={cfg.d}")
+    w = wl.Workload(cfg, batch_events=40)
+    b = w.next_batch(40)
+    t_sync = float(b.ops["t"].max()) + 0.75
+    b.t_sync = t_sync
+    w.engine.apply_events(b)
+    cols = np.arange(cfg.d)
+    st, ev = pu.oracle_run(cfg, cols, 40)
+    touched = sorted(set(ev.i.tolist()) | set(ev.j[ev.kind == 1].tolist()))
+    assert 0 < len(touched) < cfg.n                      # the case is only interesting if somebody is left out
+    st.mix_workers(touched, t_sync)
+    gx, gxt = w.columns(cols)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    w.close()
+
+
+def test_rejected_batches_leave_state_and_times_untouched():
+    from paper_2306_08289_amd import A2cidError, binding
+    cfg = wl.scaled(wl.CONFIGS["C2"], d=5000, events=200)
+    w = wl.Workload(cfg, batch_events=100)
+    w.run(100)
+    x0, xt0 = w.columns(np.arange(cfg.d))
+    t0 = w.engine.times()
+    good = w.next_batch(100)
+    for name, mutate, code in [
+        ("time runs backwards", lambda o: o["t"].__setitem__(len(o) - 1, 0.0), binding.EORDER),
+        ("not an edge", lambda o: (o["kind"].__setitem__(0, 1), o["i"].__setitem__(0, 0), o["j"].__setitem__(0, 8)),
+         binding.EGRAPH),
+        ("worker out of range", lambda o: o["i"].__setitem__(3, 99), binding.EINVAL),
+    ]:
+        _say(f"reject: {name}")
+        bad = type(good)(good.ops.copy(), good.level_off.copy(), good.t_sync)
+        mutate(bad.ops)
+        with pytest.raises(A2cidError) as e:
+            w.engine.apply_events(bad)
+        assert e.value.code == code, str(e.value)
+    # two operations of one level on the same worker
+    bad = type(good)(good.ops.copy(), np.array([0, len(good.ops)], np.int64), good.t_sync)
+    with pytest.raises(A2cidError) as e:
+        w.engine.apply_events(bad)
+    assert e.value.code == binding.EMATCHING
+    x1, xt1 = w.columns(np.arange(cfg.d))
+    assert np.array_equal(x0, x1) and np.array_equal(xt0, xt1) and np.array_equal(t0, w.engine.times())
+    with pytest.raises(A2cidError):
+        w.engine.stats(float(t0.max()) - 1.0)            # observation time before a worker's time stamp
+    with pytest.raises(A2cidError):
+        w.engine.flush(float(t0.max()) - 1.0)
+    w.engine.apply_events(good)                           # the untouched good batch still applies
+    st, _ = pu.oracle_run(cfg, np.arange(cfg.d), 200)
+    gx, gxt = w.columns(np.arange(cfg.d))
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    w.close()
+
+
+def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit():
+    # every operation performs the same arithmetic whatever batch it lands in and whichever kernel runs it
+    cfg = wl.scaled(wl.CONFIGS["C5"], d=70001, events=900)
+    cols = np.arange(cfg.d)
+    results = []
+    for batch, tuning in [(900, None), (128, None), (300, (4, 1, 64, 0)), (77, (2, 0, 128, 1)), (450, (1, 0, 256, 2))]:
+        _say(f"batching {batch} tuning {tuning}")
+        w = wl.Workload(cfg, batch_events=batch)
+        if tuning:
+            w.engine.set_tuning(*tuning)
+        w.run(900)
+        results.append(w.columns(cols) + (w.engine.times(),))
+        w.close()
+    for r in results[1:]:
+        assert all(np.array_equal(a, b) for a, b in zip(results[0], r))
+
+
+def test_resume_from_saved_state_continues_the_same_trajectory():
+    cfg = wl.scaled(wl.CONFIGS["C3"], d=30011, events=1200)
+    cols = np.arange(cfg.d)
+    a = wl.Workload(cfg, batch_events=400)
+    a.run(1200)
+    whole = a.columns(cols)
+    b = wl.Workload(cfg, batch_events=400)
+    b.run(800)
+    saved_x, saved_xt, saved_t = b.x.clone(), b.xt.clone(), b.engine.times()
+    b.close()
+    c = wl.Workload(cfg, batch_events=400)               # fresh context: restore buffers, times, stream position
+    c.x.copy_(saved_x); c.xt.copy_(saved_xt)
+    c.engine.set_times(saved_t)
+    c.sched.skip(800)
+    c.run(400)
+    resumed = c.columns(cols)
+    assert np.array_equal(whole[0], resumed[0]) and np.array_equal(whole[1], resumed[1])
+    assert np.array_equal(a.engine.times(), c.engine.times())
+    a.close(); c.close()
+
+
+def test_observables_at_full_size_against_library_reductions():
+    # 64 x 25.6M: the oracle cannot hold this; torch reductions in fp64 are the independent reference
+    cfg = wl.scaled(wl.CONFIGS["C5"], events=300)
+    _say(f"stats full size {cfg.name}")
+    w = wl.Workload(cfg, batch_events=300)
+    w.run(300)
+    t_now = w.t_last + 0.3
+    s1 = w.engine.stats(t_now)
+    s2 = w.engine.stats(t_now + 5.0)
+    # the flow conserves x_i + xt_i for every worker
+    l1 = float(w.x[:, :cfg.d].abs().sum(dtype=torch.float64)) / cfg.n
+    assert np.all(np.abs((s1["sum_x"] + s1["sum_xt"]) - (s2["sum_x"] + s2["sum_xt"])) <= 1e-5 * l1)
+    w.engine.flush(t_now)
+    w.engine.synchronize()
+    cons = {"x": 0.0, "xt": 0.0}
+    sums = {"x": np.zeros(cfg.n), "xt": np.zeros(cfg.n)}
+    for name, buf in (("x", w.x), ("xt", w.xt)):
+        for lo in range(0, cfg.d, 1 << 21):
+            blk = buf[:, lo:min(cfg.d, lo + (1 << 21))].double()
+            cons[name] += float(((blk - blk.mean(0, keepdim=True)) ** 2).sum())
+            sums[name] += blk.sum(1).cpu().numpy()
+    assert math.isclose(s1["consensus_x"], cons["x"], rel_tol=1e-6)
+    assert math.isclose(s1["consensus_xt"], cons["xt"], rel_tol=1e-6)
+    assert np.all(np.abs(s1["sum_x"] - sums["x"]) <= 1e-6 * l1) and np.all(np.abs(s1["sum_xt"] - sums["xt"]) <= 1e-6 * l1)
+    s3 = w.engine.stats(t_now)                            # after the flush nothing is pending: same numbers
+    assert math.isclose(s3["consensus_x"], s1["consensus_x"], rel_tol=1e-6)
+    w.close()
+
+
+@pytest.mark.parametrize("name,d,events,batch,group", [("C1", 1000, 3000, 512, 4), ("C2", 64 * 37 + 5, 3000, 1000, 1),
+                                                       ("C3", 9001, 3000, 1024, 2), ("C4", 12345, 4000, 1024, 8),
+                                                       ("C5", 8191, 4000, 700, 4)])
+def test_resident_kernel_matches_oracle(name, d, events, batch, group):
+    cfg = wl.scaled(wl.CONFIGS[name], d=d, events=events)
+    _say(f"resident {name} d={d} group={group}")
+    w = wl.Workload(cfg, batch_events=batch)
+    w.engine.set_tuning(1, 0, 256, 2)
+    w.engine.set_resident_group(group)
+    w.run(events)
+    cols = np.arange(cfg.d)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, events)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    if w.ld != cfg.d:
+        assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
+    w.close()
+
+
+def test_resident_kernel_at_full_size_on_sampled_columns():
+    cfg = wl.scaled(wl.CONFIGS["C4"], events=2048)
+    _say("resident C4 full size")
+    w = wl.Workload(cfg, batch_events=1024)
+    w.engine.set_tuning(1, 0, 256, 2)
+    w.run(2048)
+    cols = pu.sample_columns(cfg.d, 4096, seed=3)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, 2048)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    w.close()
