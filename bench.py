@@ -86,7 +86,8 @@ def main():
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--walk", type=int, default=None,
                     help="event kernel: 1 = one launch per batch (default), 0 = one per level, 2 = LDS-resident")
-    ap.add_argument("--group", type=int, default=None, help="resident kernel: operations issued together")
+    ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
+    ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -107,8 +108,8 @@ def main():
     tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
     if any(v is not None for v in tuning):
         w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 1))])
-    if args.group is not None:
-        w.engine.set_resident_group(args.group)
+    if args.group is not None or args.cols is not None:
+        w.engine.set_resident_group(args.group or 8, args.cols or 1)
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
 
     def step():

@@ -227,9 +227,11 @@ void a2cid_sched_destroy(a2cid_sched *s);
  * compute the same operations in the same per-worker order. */
 int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t mode);
 
-/* Mode 2 only: waves per workgroup, i.e. how many operations of one level a column tile
- * processes concurrently (1, 2, 4 or 8; default 8). */
-int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group);
+/* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
+ * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
+ * columns wide and needs 512 * cols * (workers + 16) bytes of the CU's 160 KiB of LDS).
+ * Default: 8, 1. */
+int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
 
 /* Launch shape of the observables kernel: pieces = 16-byte pieces per lane and row (1 or 2), rows =
  * rows whose loads are issued together (1, 2 or 4), blocks = workgroups (grid-stride over column

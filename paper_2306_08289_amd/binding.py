@@ -83,7 +83,7 @@ SIGNATURES = {
     "a2cid_stream_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
                                  _P(C.c_double), C.c_int32]),
-    "a2cid_set_resident_group": (C.c_int, [C.c_void_p, C.c_int32]),
+    "a2cid_set_resident_group": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
     "a2cid_profile": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_profile_read": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_double)]),
     "a2cid_last_error": (C.c_char_p, []),
@@ -265,8 +265,8 @@ class Engine:
     def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=1):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))
 
-    def set_resident_group(self, group=8):
-        _check(load().a2cid_set_resident_group(self._h, int(group)))
+    def set_resident_group(self, group=8, cols=1):
+        _check(load().a2cid_set_resident_group(self._h, int(group), int(cols)))
 
     def set_stats_tuning(self, pieces=2, rows=2, blocks=2048, nontemporal=1):
         _check(load().a2cid_set_stats_tuning(self._h, int(pieces), int(rows), int(blocks), int(bool(nontemporal))))

@@ -62,6 +62,7 @@ struct a2cid_ctx {
     int walk = 1;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident
     int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
     float *zero_dev = nullptr;          // one zero float: stands in for absent gradient inputs
+    int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     // observables scratch
@@ -154,7 +155,7 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
     return A2CID_OK;
 }
 
-constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row and workgroup + staging: 64 KiB at most
+constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row, column-per-lane and workgroup, plus staging
 
 int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, int32_t n_rows) {
     TimedLaunch tl{};
@@ -163,17 +164,30 @@ int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, 
         if (int rc = get_event(c, &tl.stop)) return rc;
         A2CID_HIP(hipEventRecord(tl.start, c->stream));
     }
-    const unsigned blocks = (unsigned)((c->d + 63) / 64);
-    const size_t lds = sizeof(Pair) * 64 * ((size_t)n_rows + kStage);
-#define A2CID_RESIDENT(W)                                                                                      \
-    hipLaunchKernelGGL((resident_kernel<W>), dim3(blocks), dim3(64 * W), lds, c->stream, c->x, c->xt, c->ld,   \
-                       c->d, s->res_dev, n_ops, s->gin_dev, n_grad, s->rows_dev, n_rows, (float)c->alpha,       \
-                       (float)c->alpha_t)
-    switch (c->group) {
-        case 1: A2CID_RESIDENT(1); break;
-        case 2: A2CID_RESIDENT(2); break;
-        case 4: A2CID_RESIDENT(4); break;
-        default: A2CID_RESIDENT(8); break;
+    const int cols = c->resident_cols;
+    const unsigned blocks = (unsigned)((c->d + 64 * cols - 1) / (64 * cols));
+    const size_t lds = sizeof(Pair) * 64 * cols * ((size_t)n_rows + kStage);
+#define A2CID_RESIDENT(W, C)                                                                                     \
+    do {                                                                                                         \
+        if (lds > 65536)                                                                                         \
+            A2CID_HIP(hipFuncSetAttribute((const void *)resident_kernel<W, C>,                                   \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
+        hipLaunchKernelGGL((resident_kernel<W, C>), dim3(blocks), dim3(64 * W), lds, c->stream, c->x, c->xt,     \
+                           c->ld, c->d, s->res_dev, n_ops, s->gin_dev, n_grad, s->rows_dev, n_rows,              \
+                           (float)c->alpha, (float)c->alpha_t);                                                  \
+    } while (0)
+    const int key = c->group * 10 + cols;
+    switch (key) {
+        case 11: A2CID_RESIDENT(1, 1); break;
+        case 21: A2CID_RESIDENT(2, 1); break;
+        case 41: A2CID_RESIDENT(4, 1); break;
+        case 161: A2CID_RESIDENT(16, 1); break;
+        case 42: A2CID_RESIDENT(4, 2); break;
+        case 82: A2CID_RESIDENT(8, 2); break;
+        case 162: A2CID_RESIDENT(16, 2); break;
+        case 84: A2CID_RESIDENT(8, 4); break;
+        case 164: A2CID_RESIDENT(16, 4); break;
+        default: A2CID_RESIDENT(8, 1); break;
     }
 #undef A2CID_RESIDENT
     A2CID_HIP(hipGetLastError());
@@ -357,7 +371,8 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                         if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
                         if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
                         ResOp &r = s->res_host[k];
-                        r.w0 = (uint32_t)o.kind | ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
+                        r.w0 = (uint32_t)o.kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) |
+                               ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
                         r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
                         r.gamma = o.gamma; r.gscale = o.gscale;
                         if (o.kind == kOpGradient) {
@@ -508,11 +523,18 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     return A2CID_OK;
 }
 
-int a2cid_set_resident_group(a2cid_ctx *c, int32_t group) {
+int a2cid_set_resident_group(a2cid_ctx *c, int32_t group, int32_t cols) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
-    if (group != 1 && group != 2 && group != 4 && group != 8) return fail(A2CID_EINVAL, "group must be 1, 2, 4 or 8");
+    if (group != 1 && group != 2 && group != 4 && group != 8 && group != 16)
+        return fail(A2CID_EINVAL, "group must be 1, 2, 4, 8 or 16");
+    if (cols != 1 && cols != 2 && cols != 4) return fail(A2CID_EINVAL, "cols must be 1, 2 or 4");
+    if ((cols == 2 && group < 4) || (cols == 4 && group < 8))
+        return fail(A2CID_EINVAL, "cols = 2 needs group >= 4 and cols = 4 needs group >= 8");
+    if (sizeof(Pair) * 64 * (size_t)cols * ((size_t)c->n + kStage) > 160 * 1024)
+        return fail(A2CID_EINVAL, "%d workers x %d columns per lane do not fit into 160 KiB of LDS", c->n, cols);
     c->group = group;
+    c->resident_cols = cols;
     return A2CID_OK;
 }
 

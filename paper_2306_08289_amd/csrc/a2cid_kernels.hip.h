@@ -230,9 +230,10 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
 // LDS copy, and finally writes the rows back.  State traffic per batch drops from 32 d bytes per
 // gossip event to 16 d bytes per touched row; gradient inputs are still read once per event.
 //
-// LDS capacity allows only four such tiles per CU, so the W waves of a workgroup share one tile:
-// lane l of every wave stands for column l of the tile, the operations of a level (which touch
-// disjoint rows) are dealt round-robin to the waves, and a workgroup barrier separates levels.
+// LDS capacity allows only a few such tiles per CU, so the W waves of a workgroup share one tile of
+// 64 * C columns: lane l of every wave stands for columns l*C .. l*C+C-1 of the tile, the operations
+// of a level (which touch disjoint rows) are dealt round-robin to the waves, and a workgroup barrier
+// separates levels.  C > 1 spreads the scalar bookkeeping of an operation over more columns.
 //   - operation records (32 bytes) are fetched 64 at a time, one record per lane, with vector
 //     loads, and a record's fields are broadcast with v_readlane: no memory access per operation;
 //   - gradient inputs (xi, c at the lane's column) go through a ring of kStage LDS slots indexed by
@@ -247,7 +248,8 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
 struct Pair { float x, xt; };
 
 struct ResOp {                   // 32 bytes
-    uint32_t w0;                 // kind | slot_i << 8 | slot_j << 16 | operations left in the (sub-)level << 24
+    uint32_t w0;                 // kind | (a trailing mix is non-zero) << 2 | slot_i << 8 | slot_j << 16 |
+                                 // operations left in the (sub-)level << 24
     uint32_t g;                  // gradient events before this (sub-)level | gradient events up to its end << 16
     float b_i;
     union { float b_j; uint32_t gidx; };   // gossip: mixing coefficient of worker j; gradient: ordinal of the event
@@ -272,34 +274,89 @@ __device__ __forceinline__ float grad_input(uintptr_t p, int64_t col) {
     return *(global_f32)addr;
 }
 
-template <int W>
+// C consecutive floats of a row starting at column col (col is a multiple of C, rows are 16-byte aligned);
+// columns at or beyond d read as 0 and are never written.
+template <int C>
+struct Cols { float v[C]; };
+
+template <int C>
+__device__ __forceinline__ Cols<C> load_cols(const float *p, int64_t col, int64_t d) {
+    typedef float vec __attribute__((ext_vector_type(C)));
+    Cols<C> r;
+    if (col + C <= d) {
+        if constexpr (C == 1) r.v[0] = p[col];
+        else { const vec t = *(const vec *)(p + col);
+#pragma unroll
+               for (int c = 0; c < C; ++c) r.v[c] = t[c]; }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c) r.v[c] = col + c < d ? p[col + c] : 0.f;
+    }
+    return r;
+}
+
+template <int C>
+__device__ __forceinline__ void store_cols(float *p, int64_t col, int64_t d, const Cols<C> &r) {
+    typedef float vec __attribute__((ext_vector_type(C)));
+    if (col + C <= d) {
+        if constexpr (C == 1) p[col] = r.v[0];
+        else { vec t;
+#pragma unroll
+               for (int c = 0; c < C; ++c) t[c] = r.v[c];
+               *(vec *)(p + col) = t; }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c) if (col + c < d) p[col + c] = r.v[c];
+    }
+}
+
+template <int C>
+__device__ __forceinline__ Cols<C> grad_input_cols(uintptr_t p, int64_t col, int64_t d) {
+    if (p & 1) {                                          // a single zero float stands for the whole row
+        Cols<C> r;
+        const float z = *(global_f32)(p & ~(uintptr_t)1);
+#pragma unroll
+        for (int c = 0; c < C; ++c) r.v[c] = z;
+        return r;
+    }
+    return load_cols<C>((const float *)p, col, d);
+}
+
+// W waves share a tile of 64 * C columns; lane l of every wave stands for columns l*C .. l*C + C-1 of the tile.
+template <int C>
+struct TileCell { Pair p[C]; };
+
+template <int W, int C>
 __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x, float *__restrict__ xt,
                                                           int64_t ld, int64_t d, const ResOp *__restrict__ ops,
                                                           int32_t n_ops, const GradIn *__restrict__ gin,
                                                           int32_t n_grad, const int32_t *__restrict__ rows,
                                                           int32_t n_rows, float alpha, float alpha_t) {
-    extern __shared__ Pair lds[];
-    Pair *tile = lds;                                    // [n_rows][64]
-    Pair *gstage = lds + (size_t)n_rows * 64;            // [kStage][64]: (xi, c) of staged gradient events
+    extern __shared__ unsigned char lds_raw[];
+    TileCell<C> *tile = (TileCell<C> *)lds_raw;          // [n_rows][64]
+    TileCell<C> *gstage = tile + (size_t)n_rows * 64;    // [kStage][64]: (xi, c) of staged gradient events
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t col = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * C;
     const bool valid = col < d;
 
-    // rows wave, wave + W, ... of the slot list, eight loads of each buffer in flight per wave
-    for (int32_t s0 = wave; s0 < n_rows; s0 += 8 * W) {
-        Pair v[8];
+    // rows wave, wave + W, ... of the slot list, four loads of each buffer in flight per wave
+    for (int32_t s0 = wave; s0 < n_rows; s0 += 4 * W) {
+        TileCell<C> v[4];
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < 4; ++q) {
             const int32_t s = s0 + q * W;
-            v[q].x = 0.f; v[q].xt = 0.f;
+#pragma unroll
+            for (int c = 0; c < C; ++c) { v[q].p[c].x = 0.f; v[q].p[c].xt = 0.f; }
             if (s < n_rows && valid) {
-                const int64_t off = (int64_t)rows[s] * ld + col;
-                v[q].x = x[off]; v[q].xt = xt[off];
+                const int64_t off = (int64_t)rows[s] * ld;
+                const Cols<C> a = load_cols<C>(x + off, col, d), at = load_cols<C>(xt + off, col, d);
+#pragma unroll
+                for (int c = 0; c < C; ++c) { v[q].p[c].x = a.v[c]; v[q].p[c].xt = at.v[c]; }
             }
         }
 #pragma unroll
-        for (int q = 0; q < 8; ++q) {
+        for (int q = 0; q < 4; ++q) {
             const int32_t s = s0 + q * W;
             if (s < n_rows) tile[s * 64 + lane] = v[q];
         }
@@ -327,14 +384,19 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             // fill the ring: everything up to g_before + kStage (older ordinals are consumed)
             int32_t hi = g_before + kStage;
             if (hi > n_grad) hi = n_grad;
-            Pair gv[kStage / W + 1];
+            TileCell<C> gv[kStage / W + 1];
 #pragma unroll
             for (int u = 0; u < kStage / W + 1; ++u) {
                 const int32_t o = staged_hi + wave + u * W;
-                gv[u].x = 0.f; gv[u].xt = 0.f;
+#pragma unroll
+                for (int c = 0; c < C; ++c) { gv[u].p[c].x = 0.f; gv[u].p[c].xt = 0.f; }
                 if (o < hi) {
                     const GradIn in = gin[o];
-                    if (valid) { gv[u].x = grad_input(in.xi, col); gv[u].xt = grad_input(in.c, col); }
+                    if (valid) {
+                        const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d);
+#pragma unroll
+                        for (int c = 0; c < C; ++c) { gv[u].p[c].x = a.v[c]; gv[u].p[c].xt = cc.v[c]; }
+                    }
                 }
             }
 #pragma unroll
@@ -356,22 +418,43 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             const int l = idx - k0;
             const uint32_t w0 = lane_u32(ra.x, l);
             const uint32_t kind = w0 & 3u;
-            Pair *pi = tile + ((w0 >> 8) & 255u) * 64 + lane;
-            OpCoef oc;
-            oc.b_i = lane_f32(ra.z, l); oc.bp_i = lane_f32(rb.x, l);
-            Pair vi = *pi;
+            const bool trailing = (w0 & 4u) != 0;        // some trailing mix is non-zero (rare: only with t_sync)
+            TileCell<C> *pi = tile + ((w0 >> 8) & 255u) * 64 + lane;
+            const float b_i = lane_f32(ra.z, l);
+            TileCell<C> vi = *pi;
             if (kind == (uint32_t)kOpGossip) {
-                Pair *pj = tile + ((w0 >> 16) & 255u) * 64 + lane;
-                oc.b_j = lane_f32(ra.w, l); oc.bp_j = lane_f32(rb.y, l);
-                Pair vj = *pj;
-                gossip_update(vi.x, vi.xt, vj.x, vj.xt, oc, alpha, alpha_t);
+                TileCell<C> *pj = tile + ((w0 >> 16) & 255u) * 64 + lane;
+                const float b_j = lane_f32(ra.w, l);
+                TileCell<C> vj = *pj;
+#pragma unroll
+                for (int c = 0; c < C; ++c) {
+                    mix(vi.p[c].x, vi.p[c].xt, b_i);
+                    mix(vj.p[c].x, vj.p[c].xt, b_j);
+                    const float m = vi.p[c].x - vj.p[c].x;
+                    vi.p[c].x -= alpha * m; vj.p[c].x += alpha * m;
+                    vi.p[c].xt -= alpha_t * m; vj.p[c].xt += alpha_t * m;
+                }
+                if (trailing) {
+                    const float bp_i = lane_f32(rb.x, l), bp_j = lane_f32(rb.y, l);
+#pragma unroll
+                    for (int c = 0; c < C; ++c) { mix(vi.p[c].x, vi.p[c].xt, bp_i); mix(vj.p[c].x, vj.p[c].xt, bp_j); }
+                }
                 *pj = vj;
             } else if (kind == (uint32_t)kOpGradient) {
+                OpCoef oc;
+                oc.b_i = b_i; oc.bp_i = 0.f;
                 oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
-                const Pair in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
-                gradient_update(vi.x, vi.xt, in.x, in.xt, oc);
+                const TileCell<C> in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
+#pragma unroll
+                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.p[c].x, in.p[c].xt, oc);
+                if (trailing) {
+                    const float bp_i = lane_f32(rb.x, l);
+#pragma unroll
+                    for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, bp_i);
+                }
             } else {
-                mix(vi.x, vi.xt, oc.b_i);
+#pragma unroll
+                for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, b_i);
             }
             *pi = vi;
         }
@@ -381,9 +464,13 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 
     if (valid) {
         for (int32_t s = wave; s < n_rows; s += W) {
-            const Pair v = tile[s * 64 + lane];
-            const int64_t off = (int64_t)rows[s] * ld + col;
-            x[off] = v.x; xt[off] = v.xt;
+            const TileCell<C> v = tile[s * 64 + lane];
+            const int64_t off = (int64_t)rows[s] * ld;
+            Cols<C> a, at;
+#pragma unroll
+            for (int c = 0; c < C; ++c) { a.v[c] = v.p[c].x; at.v[c] = v.p[c].xt; }
+            store_cols<C>(x + off, col, d, a);
+            store_cols<C>(xt + off, col, d, at);
         }
     }
 }

@@ -220,15 +220,16 @@ def test_observables_at_full_size_against_library_reductions():
     w.close()
 
 
-@pytest.mark.parametrize("name,d,events,batch,group", [("C1", 1000, 3000, 512, 4), ("C2", 64 * 37 + 5, 3000, 1000, 1),
-                                                       ("C3", 9001, 3000, 1024, 2), ("C4", 12345, 4000, 1024, 8),
-                                                       ("C5", 8191, 4000, 700, 4)])
-def test_resident_kernel_matches_oracle(name, d, events, batch, group):
+@pytest.mark.parametrize("name,d,events,batch,group,cols", [
+    ("C1", 1000, 3000, 512, 4, 1), ("C2", 64 * 37 + 5, 3000, 1000, 1, 1), ("C3", 9001, 3000, 1024, 2, 1),
+    ("C4", 12345, 4000, 1024, 8, 1), ("C5", 8191, 4000, 700, 4, 2), ("C4", 12347, 3000, 1024, 8, 2),
+    ("C3", 9001, 3000, 1024, 16, 4), ("C2", 1027, 3000, 1000, 8, 4), ("C1", 3, 500, 100, 16, 2)])
+def test_resident_kernel_matches_oracle(name, d, events, batch, group, cols):
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=events)
-    _say(f"resident {name} d={d} group={group}")
+    _say(f"resident {name} d={d} group={group} cols={cols}")
     w = wl.Workload(cfg, batch_events=batch)
     w.engine.set_tuning(1, 0, 256, 2)
-    w.engine.set_resident_group(group)
+    w.engine.set_resident_group(group, cols)
     w.run(events)
     cols = np.arange(cfg.d)
     gx, gxt = w.columns(cols)
