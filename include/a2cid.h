@@ -50,6 +50,9 @@ extern "C" {
 
 #define A2CID_MAX_WORKERS 1024
 
+#define A2CID_ORDER_EQ1     0   /* jumps evaluated after the mixing: Eq. (1) (default)          */
+#define A2CID_ORDER_LISTING 1   /* jumps evaluated before it: the line order of Algorithm 1     */
+
 typedef struct a2cid_ctx a2cid_ctx;
 typedef struct a2cid_sched a2cid_sched;
 
@@ -157,6 +160,14 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
  * batch).  On any error nothing is enqueued and no time stamp moves. */
 int a2cid_apply_events(a2cid_ctx *ctx, const a2cid_event_batch *batch);
 
+/* Chooses from which values a jump is formed, for all later batches.  A2CID_ORDER_EQ1: the
+ * gradient g and the difference m = x_i - x_j are evaluated after the workers have been mixed to
+ * the event time, as Eq. (1) prescribes (its jump terms act on x_t).  A2CID_ORDER_LISTING: they
+ * are evaluated from the stored values, then the workers are mixed, then the jump is applied --
+ * the order in which Algorithm 1 lists its lines, where g is as stale as the mixing it skipped.
+ * The two coincide when eta = 0. */
+int a2cid_set_order(a2cid_ctx *ctx, int32_t order);
+
 /* Consensus distances and per-worker sums of the state as it would be if every worker were
  * mixed up to t_now (>= max_i t_i); x, xt and the time stamps are left untouched.  Blocks
  * until the result is in *out. */
@@ -165,6 +176,13 @@ int a2cid_stats(a2cid_ctx *ctx, double t_now, a2cid_stats_out *out);
 /* Mixes every worker up to t_now (>= max_i t_i) in place and sets all t_i = t_now: the state
  * Algorithm 1 returns at its final time. */
 int a2cid_flush(a2cid_ctx *ctx, double t_now);
+
+/* Consensus step of the experimental protocol ("one All-Reduce averaging is performed before and
+ * after the training", section "Experimental Setup"): mixes every worker up to t_now
+ * (>= max_i t_i), then replaces every x_i by the mean of the x_j and every xt_i by the mean of the
+ * xt_j, and sets all t_i = t_now.  Both means, hence Eq. (2)'s tracker, are unchanged by it; the
+ * consensus distances become 0.  Asynchronous like a2cid_flush (16 n d bytes). */
+int a2cid_average(a2cid_ctx *ctx, double t_now);
 
 /* Copies the n time stamps t_i into the host array t. */
 int a2cid_get_times(const a2cid_ctx *ctx, double *t);

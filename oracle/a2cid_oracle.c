@@ -90,9 +90,55 @@ void a2o_gossip_event(double *x_i, double *xt_i, double *t_i,
 }
 
 /* ------------------------------------------------------------------------- */
+/* The same two jumps in the order in which Algorithm 1 LISTS its lines: the     */
+/* gradient g (resp. the difference m_ij) is formed from the stored, not yet    */
+/* mixed values, then the worker is mixed to te, then the jump is applied.  In   */
+/* a real system g takes a whole forward/backward pass and is stale in exactly   */
+/* this way.  Kept as a variant; the default reading is the one above.           */
+/* ------------------------------------------------------------------------- */
+void a2o_gradient_event_listing(double *x_i, double *xt_i, double *t_i, int64_t d,
+                                double eta, double te, double gamma, double gscale,
+                                const double *c, const double *xi)
+{
+    double *g = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int64_t k = 0; k < d; ++k) {
+        g[k] = gscale * (x_i[k] - (c ? c[k] : 0.0));
+        if (xi) g[k] += xi[k];
+    }
+    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    *t_i = te;
+    for (int64_t k = 0; k < d; ++k) {
+        x_i[k] -= gamma * g[k];
+        xt_i[k] -= gamma * g[k];
+    }
+    free(g);
+}
+
+void a2o_gossip_event_listing(double *x_i, double *xt_i, double *t_i,
+                              double *x_j, double *xt_j, double *t_j, int64_t d,
+                              double eta, double te, double alpha, double alpha_t)
+{
+    double *m = (double *)malloc(sizeof(double) * (size_t)d);
+    for (int64_t k = 0; k < d; ++k) m[k] = x_i[k] - x_j[k];
+    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    *t_i = te;
+    a2o_mix_row(x_j, xt_j, d, eta, te - *t_j);
+    *t_j = te;
+    for (int64_t k = 0; k < d; ++k) {
+        x_i[k] -= alpha * m[k];
+        x_j[k] += alpha * m[k];
+        xt_i[k] -= alpha_t * m[k];
+        xt_j[k] += alpha_t * m[k];
+    }
+    free(m);
+}
+
+/* ------------------------------------------------------------------------- */
 /* Serial event loop.  x, xt are n x d row-major, t has n entries.              */
 /* kind[e] == 0: gradient on worker wi[e]; kind[e] == 1: gossip on (wi, wj).    */
 /* xi_row[e] / c_row[e] index rows of the dense matrices xi / c (or -1: none).  */
+/* order 0: jumps evaluated after the mixing (Eq. (1)); order 1: Algorithm 1's    */
+/* listing order (see above).                                                   */
 /* Returns 0, or -(e+1) for the first malformed event (nothing after it runs).  */
 /* ------------------------------------------------------------------------- */
 int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
@@ -101,7 +147,7 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
                          const int32_t *wi, const int32_t *wj,
                          const double *gamma, const double *gscale,
                          const int64_t *xi_row, const double *xi,
-                         const int64_t *c_row, const double *c)
+                         const int64_t *c_row, const double *c, int32_t order)
 {
     for (int64_t e = 0; e < n_events; ++e) {
         const int32_t i = wi[e];
@@ -110,15 +156,15 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
             if (te[e] < t[i]) return -(e + 1);
             const double *ce = (c_row && c_row[e] >= 0) ? c + c_row[e] * d : NULL;
             const double *xe = (xi_row && xi_row[e] >= 0) ? xi + xi_row[e] * d : NULL;
-            a2o_gradient_event(x + (int64_t)i * d, xt + (int64_t)i * d, t + i, d,
-                               eta, te[e], gamma[e], gscale[e], ce, xe);
+            (order ? a2o_gradient_event_listing : a2o_gradient_event)(
+                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, d, eta, te[e], gamma[e], gscale[e], ce, xe);
         } else if (kind[e] == 1) {
             const int32_t j = wj[e];
             if (j < 0 || j >= n || j == i) return -(e + 1);
             if (te[e] < t[i] || te[e] < t[j]) return -(e + 1);
-            a2o_gossip_event(x + (int64_t)i * d, xt + (int64_t)i * d, t + i,
-                             x + (int64_t)j * d, xt + (int64_t)j * d, t + j, d,
-                             eta, te[e], alpha, alpha_t);
+            (order ? a2o_gossip_event_listing : a2o_gossip_event)(
+                x + (int64_t)i * d, xt + (int64_t)i * d, t + i,
+                x + (int64_t)j * d, xt + (int64_t)j * d, t + j, d, eta, te[e], alpha, alpha_t);
         } else {
             return -(e + 1);
         }

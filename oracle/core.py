@@ -25,7 +25,7 @@ def lib():
         _lib.a2o_apply_events.argtypes = [
             C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double, C.c_double,
             C.c_int64, d_p, i32_p, i32_p, i32_p, d_p, d_p,
-            i64_p, C.c_void_p, i64_p, C.c_void_p]
+            i64_p, C.c_void_p, i64_p, C.c_void_p, C.c_int32]
         _lib.a2o_apply_events.restype = C.c_int64
         _lib.a2o_stats.argtypes = [C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double,
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), d_p, d_p]
@@ -88,13 +88,14 @@ def generate_events(n, edges_u, edges_v, node_rate, edge_rate, seed, n_events):
 class State:
     """x, xt (n x d, fp64) and the per-worker last-update times t (Algorithm 1, initialisation)."""
 
-    def __init__(self, x0, xt0=None, eta=0.0, alpha=0.5, alpha_t=0.5):
+    def __init__(self, x0, xt0=None, eta=0.0, alpha=0.5, alpha_t=0.5, order=0):
         self.x = np.array(x0, dtype=np.float64, order="C")
         self.xt = self.x.copy() if xt0 is None else np.array(xt0, dtype=np.float64, order="C")
         assert self.x.ndim == 2 and self.x.shape == self.xt.shape
         self.n, self.d = self.x.shape
         self.t = np.zeros(self.n, np.float64)
         self.eta, self.alpha, self.alpha_t = float(eta), float(alpha), float(alpha_t)
+        self.order = int(order)      # 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
 
     def apply(self, ev, gamma=None, gscale=None, xi=None, xi_row=None, c=None, c_row=None):
         """Run the serial event loop over ev.
@@ -121,7 +122,7 @@ class State:
         rc = lib().a2o_apply_events(self.n, self.d, self.x, self.xt, self.t,
                                     self.eta, self.alpha, self.alpha_t, m,
                                     ev.t, ev.kind, ev.i, ev.j, gamma, gscale,
-                                    xi_r, xi_p, c_r, c_p)
+                                    xi_r, xi_p, c_r, c_p, self.order)
         if rc != 0:
             raise ValueError(f"malformed event at position {-rc - 1}")
         return self
@@ -139,6 +140,14 @@ class State:
         for i in workers:
             lib().a2o_mix_row(self.x[i], self.xt[i], self.d, self.eta, float(t_now) - self.t[i])
             self.t[i] = float(t_now)
+        return self
+
+    def average(self, t_now):
+        """Every worker mixed to t_now, then every row replaced by the mean over workers (x and xt): the
+        All-Reduce averaging the experimental protocol performs before and after training."""
+        self.mix_workers(range(self.n), t_now)
+        self.x[:] = self.x.mean(axis=0, keepdims=True)
+        self.xt[:] = self.xt.mean(axis=0, keepdims=True)
         return self
 
     def flushed(self, t_now):

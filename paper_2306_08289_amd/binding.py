@@ -67,6 +67,8 @@ SIGNATURES = {
     "a2cid_apply_events": (C.c_int, [C.c_void_p, _P(a2cid_event_batch)]),
     "a2cid_stats": (C.c_int, [C.c_void_p, C.c_double, _P(a2cid_stats_out)]),
     "a2cid_flush": (C.c_int, [C.c_void_p, C.c_double]),
+    "a2cid_set_order": (C.c_int, [C.c_void_p, C.c_int32]),
+    "a2cid_average": (C.c_int, [C.c_void_p, C.c_double]),
     "a2cid_get_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
     "a2cid_set_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
     "a2cid_synchronize": (C.c_int, [C.c_void_p]),
@@ -246,8 +248,14 @@ class Engine:
         _check(load().a2cid_stats(self._h, float(t_now), C.byref(out)))
         return {"consensus_x": out.consensus_x, "consensus_xt": out.consensus_xt, "sum_x": sx, "sum_xt": sxt}
 
+    def set_order(self, order):
+        _check(load().a2cid_set_order(self._h, int(order)))
+
     def flush(self, t_now):
         _check(load().a2cid_flush(self._h, float(t_now)))
+
+    def average(self, t_now):
+        _check(load().a2cid_average(self._h, float(t_now)))
 
     def times(self):
         t = np.zeros(self.n)

@@ -63,6 +63,7 @@ struct a2cid_ctx {
     int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
     float *zero_dev = nullptr;          // one zero float: stands in for absent gradient inputs
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
+    int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     // observables scratch
@@ -341,7 +342,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 o.b_i = cf.b_pre_i; o.b_j = cf.b_pre_j;
                 o.bp_i = cf.b_post_i; o.bp_j = cf.b_post_j;
                 o.gamma = op.gamma; o.gscale = op.gscale;
-                o.pad0 = 0;
+                o.flags = c->order;
                 o.xi = op.kind == A2CID_KIND_GRADIENT ? op.xi : nullptr;
                 o.c = op.kind == A2CID_KIND_GRADIENT ? op.c : nullptr;
                 o.pad1 = 0;
@@ -371,7 +372,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                         if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
                         if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
                         ResOp &r = s->res_host[k];
-                        r.w0 = (uint32_t)o.kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) |
+                        r.w0 = (uint32_t)o.kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) | (c->order ? 8u : 0u) |
                                ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
                         r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
                         r.gamma = o.gamma; r.gscale = o.gscale;
@@ -484,6 +485,25 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     return A2CID_OK;
 }
 
+int a2cid_average(a2cid_ctx *c, double t_now) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    for (int32_t i = 0; i < c->n; ++i)
+        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
+    // b_host may still be read by an earlier asynchronous upload: wait for the stream first
+    A2CID_HIP(hipStreamSynchronize(c->stream));
+    for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
+    const int64_t pieces = (c->d + 3) >> 2;
+    hipLaunchKernelGGL(average_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads)), dim3(kThreads),
+                       sizeof(float) * (size_t)c->n, c->stream, c->x, c->xt, c->ld, c->d, c->n, c->b_dev);
+    A2CID_HIP(hipGetLastError());
+    std::fill(c->t.begin(), c->t.end(), t_now);
+    c->alg_bytes += 16.0 * (double)c->n * (double)c->d;
+    return A2CID_OK;
+}
+
 int a2cid_get_times(const a2cid_ctx *c, double *t) {
     clear_error();
     if (!c || !t) return fail(A2CID_EINVAL, "context / t is NULL");
@@ -520,6 +540,14 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     c->nontemporal = nontemporal ? 1 : 0;
     c->threads = threads;
     c->walk = mode;
+    return A2CID_OK;
+}
+
+int a2cid_set_order(a2cid_ctx *c, int32_t order) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (order != A2CID_ORDER_EQ1 && order != A2CID_ORDER_LISTING) return fail(A2CID_EINVAL, "unknown order %d", order);
+    c->order = order;
     return A2CID_OK;
 }
 

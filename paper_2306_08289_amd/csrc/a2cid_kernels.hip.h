@@ -25,7 +25,7 @@ struct DevOp {
     float b_i, b_j;              // mixing to the event time: off-diagonal of exp(tau A)
     float bp_i, bp_j;            // trailing mixing (0 = none)
     float gamma, gscale;         // gradient step size and slope of the affine gradient model
-    int32_t pad0;
+    int32_t flags;               // bit 0: jumps from the stored (pre-mix) values, Algorithm 1's listing order
     const float *xi;             // additive gradient term or nullptr
     const float *c;              // centre of the affine gradient model or nullptr
     int64_t pad1;
@@ -42,12 +42,15 @@ __device__ __forceinline__ void mix(T &x, T &xt, float b) {
 }
 
 // Gossip jump of Eq. (1) for one pair, including the flows before and (optionally) after it.
+// pre = false: the difference m is taken after both workers are mixed (Eq. (1));
+// pre = true:  m is taken from the stored values, before the mixing (Algorithm 1 as listed).
 template <typename T, typename Op>
 __device__ __forceinline__ void gossip_update(T &xi, T &xti, T &xj, T &xtj, const Op &op,
-                                              float alpha, float alpha_t) {
+                                              float alpha, float alpha_t, bool pre) {
+    const T m_stored = xi - xj;
     mix(xi, xti, op.b_i);
     mix(xj, xtj, op.b_j);
-    const T m = xi - xj;
+    const T m = pre ? m_stored : xi - xj;
     xi -= alpha * m;
     xj += alpha * m;
     xti -= alpha_t * m;
@@ -56,11 +59,13 @@ __device__ __forceinline__ void gossip_update(T &xi, T &xti, T &xj, T &xtj, cons
     mix(xj, xtj, op.bp_j);
 }
 
-// Gradient jump of Eq. (1) with g = gscale (x - c) + xi, taken at the mixed point.
+// Gradient jump of Eq. (1) with g = gscale (x - c) + xi, taken at the mixed point (pre = false) or
+// at the stored point (pre = true, Algorithm 1 as listed).
 template <typename T, typename Op>
-__device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, const Op &op) {
+__device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, const Op &op, bool pre) {
+    const T g_stored = op.gscale * (x - c) + xi;
     mix(x, xt, op.b_i);
-    const T g = op.gscale * (x - c) + xi;
+    const T g = pre ? g_stored : op.gscale * (x - c) + xi;
     x -= op.gamma * g;
     xt -= op.gamma * g;
     mix(x, xt, op.bp_i);
@@ -91,6 +96,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                                               int64_t d, const DevOp &op, int64_t tile,
                                               float alpha, float alpha_t) {
     const int64_t n4 = d >> 2;                                   // whole float4 pieces per row
+    const bool pre = (op.flags & 1) != 0;
     const int64_t base = (int64_t)tile * (U * TPB) + threadIdx.x;
     const bool full = (int64_t)(tile + 1) * (U * TPB) <= n4;
 
@@ -112,7 +118,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t k = base + u * TPB;
-                gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
+                gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t, pre);
                 store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
                 store4<NT>(pj + k, b[u]); store4<NT>(ptj + k, bt[u]);
             }
@@ -122,7 +128,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                 const int64_t k = base + u * TPB;
                 if (k < n4) {
                     a[u] = pi[k]; at[u] = pti[k]; b[u] = pj[k]; bt[u] = ptj[k];
-                    gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t);
+                    gossip_update(a[u], at[u], b[u], bt[u], op, alpha, alpha_t, pre);
                     pi[k] = a[u]; pti[k] = at[u]; pj[k] = b[u]; ptj[k] = bt[u];
                 }
             }
@@ -131,7 +137,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
             const int64_t k = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && k < d) {
                 float s0 = xi_row[k], s1 = xti_row[k], s2 = xj_row[k], s3 = xtj_row[k];
-                gossip_update(s0, s1, s2, s3, op, alpha, alpha_t);
+                gossip_update(s0, s1, s2, s3, op, alpha, alpha_t, pre);
                 xi_row[k] = s0; xti_row[k] = s1; xj_row[k] = s2; xtj_row[k] = s3;
             }
         }
@@ -154,7 +160,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t k = base + u * TPB;
-                if (grad) gradient_update(a[u], at[u], g[u], c[u], op);
+                if (grad) gradient_update(a[u], at[u], g[u], c[u], op, pre);
                 else mix(a[u], at[u], op.b_i);
                 store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
             }
@@ -166,7 +172,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                     a[u] = pi[k]; at[u] = pti[k];
                     g[u] = has_xi ? pxi[k] : zero;
                     c[u] = has_c ? pc[k] : zero;
-                    if (grad) gradient_update(a[u], at[u], g[u], c[u], op);
+                    if (grad) gradient_update(a[u], at[u], g[u], c[u], op, pre);
                     else mix(a[u], at[u], op.b_i);
                     pi[k] = a[u]; pti[k] = at[u];
                 }
@@ -177,7 +183,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
             if (threadIdx.x < 4 && k < d) {
                 float s0 = xi_row[k], s1 = xti_row[k];
                 const float gk = has_xi ? op.xi[k] : 0.f, ck = has_c ? op.c[k] : 0.f;
-                if (grad) gradient_update(s0, s1, gk, ck, op);
+                if (grad) gradient_update(s0, s1, gk, ck, op, pre);
                 else mix(s0, s1, op.b_i);
                 xi_row[k] = s0; xti_row[k] = s1;
             }
@@ -248,7 +254,7 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
 struct Pair { float x, xt; };
 
 struct ResOp {                   // 32 bytes
-    uint32_t w0;                 // kind | (a trailing mix is non-zero) << 2 | slot_i << 8 | slot_j << 16 |
+    uint32_t w0;                 // kind | (a trailing mix is non-zero) << 2 | (listing order) << 3 | slot_i << 8 | slot_j << 16 |
                                  // operations left in the (sub-)level << 24
     uint32_t g;                  // gradient events before this (sub-)level | gradient events up to its end << 16
     float b_i;
@@ -419,6 +425,7 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             const uint32_t w0 = lane_u32(ra.x, l);
             const uint32_t kind = w0 & 3u;
             const bool trailing = (w0 & 4u) != 0;        // some trailing mix is non-zero (rare: only with t_sync)
+            const bool pre = (w0 & 8u) != 0;             // jumps from the stored values (Algorithm 1 as listed)
             TileCell<C> *pi = tile + ((w0 >> 8) & 255u) * 64 + lane;
             const float b_i = lane_f32(ra.z, l);
             TileCell<C> vi = *pi;
@@ -428,9 +435,10 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
                 TileCell<C> vj = *pj;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
+                    const float m_stored = vi.p[c].x - vj.p[c].x;
                     mix(vi.p[c].x, vi.p[c].xt, b_i);
                     mix(vj.p[c].x, vj.p[c].xt, b_j);
-                    const float m = vi.p[c].x - vj.p[c].x;
+                    const float m = pre ? m_stored : vi.p[c].x - vj.p[c].x;
                     vi.p[c].x -= alpha * m; vj.p[c].x += alpha * m;
                     vi.p[c].xt -= alpha_t * m; vj.p[c].xt += alpha_t * m;
                 }
@@ -446,7 +454,7 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
                 oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
                 const TileCell<C> in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
 #pragma unroll
-                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.p[c].x, in.p[c].xt, oc);
+                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.p[c].x, in.p[c].xt, oc, pre);
                 if (trailing) {
                     const float bp_i = lane_f32(rb.x, l);
 #pragma unroll
@@ -638,6 +646,36 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict
         out[i] = s;
     }
     if (tid == 0) { out[2 * n] = scons[0][0]; out[2 * n + 1] = scons[1][0]; }
+}
+
+// Consensus step: every worker's (virtually mixed) row is replaced by the mean over workers, in x and in xt.
+// One pass: a lane reads its float4 of all n rows (fp64 column sums), then writes the mean n times.
+// 8 n d bytes in, 8 n d bytes out.  Dynamic LDS: n floats (pending mixing coefficients).
+__global__ __launch_bounds__(kThreads) void average_kernel(float *__restrict__ x, float *__restrict__ xt,
+                                                           int64_t ld, int64_t d, int32_t n,
+                                                           const float *__restrict__ bmix) {
+    extern __shared__ float sbm[];
+    for (int i = threadIdx.x; i < n; i += kThreads) sbm[i] = bmix[i];
+    __syncthreads();
+    const int64_t g = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    const int64_t k = g << 2;
+    if (k >= d) return;
+    const bool whole = k + 4 <= d;
+    double sx[4] = {0.0, 0.0, 0.0, 0.0}, sxt[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int32_t i = 0; i < n; ++i) {
+        v4f a = load4_guarded(x + (int64_t)i * ld, g, d), at = load4_guarded(xt + (int64_t)i * ld, g, d);
+        mix(a, at, sbm[i]);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { sx[c] += (double)a[c]; sxt[c] += (double)at[c]; }
+    }
+    v4f mx, mxt;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) { mx[c] = (float)(sx[c] / (double)n); mxt[c] = (float)(sxt[c] / (double)n); }
+    for (int32_t i = 0; i < n; ++i) {
+        float *xr = x + (int64_t)i * ld + k, *xtr = xt + (int64_t)i * ld + k;
+        if (whole) { *(v4f *)xr = mx; *(v4f *)xtr = mxt; }
+        else for (int c = 0; c < 4 && k + c < d; ++c) { xr[c] = mx[c]; xtr[c] = mxt[c]; }
+    }
 }
 
 // Sums the per-workgroup partials: workgroup j produces out[j] = sum_b partials[b][j].  Lane t adds

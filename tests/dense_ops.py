@@ -37,8 +37,10 @@ def gradient(n, i, gamma, s, c_k, xi_k):
     return m
 
 
-def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None):
+def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, order=0):
     """events: list of (t, kind, i, j).  c: (n, d) or None.  xi: list (per event) of d-vectors or None.
+    order 0: v <- J F v (flow, then the jump evaluated at the flowed state, Eq. (1));
+    order 1: v <- F v + (J - I) v (the jump evaluated at the stored state, Algorithm 1's listing order).
     Returns (x, xt) after the events, every worker flowed to t_final if given."""
     n, d = x0.shape
     x = np.zeros((n, d)); xt = np.zeros((n, d))
@@ -48,15 +50,18 @@ def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None):
         total = np.eye(2 * n + 1)
         for e, (te, kind, i, j) in enumerate(events):
             ws = [i] if kind == 0 else [i, j]
+            f = np.eye(2 * n + 1)
             for w in ws:
-                total = flow(n, w, eta, te - t[w]) @ total
+                f = flow(n, w, eta, te - t[w]) @ f
                 t[w] = te
             if kind == 0:
                 ck = 0.0 if c is None else c[i, k]
                 xk = 0.0 if xi is None or xi[e] is None else xi[e][k]
-                total = gradient(n, i, gamma[e], s[e], ck, xk) @ total
+                jump = gradient(n, i, gamma[e], s[e], ck, xk)
             else:
-                total = gossip(n, i, j, alpha, alpha_t) @ total
+                jump = gossip(n, i, j, alpha, alpha_t)
+            step = jump @ f if order == 0 else f + jump - np.eye(2 * n + 1)
+            total = step @ total
         if t_final is not None:
             for w in range(n):
                 total = flow(n, w, eta, t_final - t[w]) @ total

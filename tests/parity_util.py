@@ -40,12 +40,12 @@ def oracle_params(cfg):
 class OracleStream:
     """The oracle following columns `cols` of a workload, fed with the serial stream chunk by chunk."""
 
-    def __init__(self, cfg, cols):
+    def __init__(self, cfg, cols, order=0):
         self.cfg, self.cols = cfg, np.asarray(cols, np.int64)
         edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg)
         self.edges, self.node_rate, self.edge_rate = edges, node_rate, edge_rate
         x0 = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_INIT, np.arange(cfg.n), self.cols, cfg.init_sigma)
-        self.state = core.State(x0, None, eta, alpha, alpha_t)
+        self.state = core.State(x0, None, eta, alpha, alpha_t, order=order)
         self.c = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_C, np.arange(cfg.n), self.cols, 1.0) if cfg.use_c else None
         self.events = None
         self.done = 0
@@ -76,9 +76,9 @@ class OracleStream:
         return self.state
 
 
-def oracle_run(cfg, cols, n_events, chunk=20000):
+def oracle_run(cfg, cols, n_events, chunk=20000, order=0):
     """Oracle state after the first n_events events of cfg, restricted to columns cols."""
-    o = OracleStream(cfg, cols)
+    o = OracleStream(cfg, cols, order)
     ev = o.generate(n_events)
     for lo in range(0, len(ev), chunk):
         o.advance(min(len(ev), lo + chunk))

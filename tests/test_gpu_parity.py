@@ -253,3 +253,44 @@ def test_resident_kernel_at_full_size_on_sampled_columns():
     assert np.array_equal(w.engine.times(), st.t)
     assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
     w.close()
+
+
+@pytest.mark.parametrize("name,d,mode", [("C2", 4 * 1024 + 7, 1), ("C4", 9001, 0), ("C5", 5003, 2), ("C3", 3333, 1)])
+def test_listing_order_variant_matches_oracle(name, d, mode):
+    # Algorithm 1 as listed: g and m from the stored values, then the mixing, then the jump
+    cfg = wl.scaled(wl.CONFIGS[name], d=d, events=2500)
+    _say(f"listing order {name} d={d} mode={mode}")
+    w = wl.Workload(cfg, batch_events=500)
+    w.engine.set_tuning(1, 0, 256, mode)
+    w.engine.set_order(1)
+    w.run(2500)
+    cols = np.arange(cfg.d)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, 2500, order=1)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    st0, _ = pu.oracle_run(cfg, cols, 2500, order=0)
+    if w.eta > 0 and cfg.name != "C5":                  # the variants really differ (not on C5, where xt = x)
+        assert pu.rel_err(gx, st0.x) > 10 * pu.TOL
+    w.close()
+
+
+@pytest.mark.parametrize("name,d", [("C2", 4 * 256 * 3 + 2), ("C4", 7), ("C5", 40001)])
+def test_average_matches_oracle(name, d):
+    cfg = wl.scaled(wl.CONFIGS[name], d=d, events=700)
+    _say(f"average {name} d={d}")
+    w = wl.Workload(cfg, batch_events=350)
+    w.run(700)
+    cols = np.arange(cfg.d)
+    st, ev = pu.oracle_run(cfg, cols, 700)
+    t_now = float(ev.t[-1]) + 0.4
+    w.engine.average(t_now)
+    st.average(t_now)
+    gx, gxt = w.columns(cols)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    assert np.all(w.engine.times() == t_now)
+    assert np.array_equal(gx, np.tile(gx[:1], (cfg.n, 1)))      # exact consensus: all rows identical
+    if w.ld != cfg.d:
+        assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
+    s = w.engine.stats(t_now)
+    assert s["consensus_x"] == 0.0 and s["consensus_xt"] == 0.0
+    w.close()

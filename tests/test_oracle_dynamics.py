@@ -277,3 +277,54 @@ def test_malformed_events_are_rejected():
     st.apply(core.Events([1.0], [0], [1], [-1]), 0.1, 0.0)
     with pytest.raises(ValueError):
         st.apply(core.Events([0.5], [1], [1], [2]))          # time runs backwards for worker 1
+
+
+@pytest.mark.parametrize("n,d,topo,seed", [(3, 4, "ring", 5), (4, 6, "complete", 6)])
+def test_listing_order_variant_equals_its_dense_operator_product(n, d, topo, seed):
+    # Algorithm 1 as listed: g and m_ij from the stored values, then the mixing, then the jump
+    rng = np.random.default_rng(seed)
+    edges = getattr(graph, topo)(n)
+    ev = _events(n, edges, 1.0, 1.3, 200 + seed, 120)
+    eta, alpha, alpha_t = 0.9, 0.5, 1.4
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d)); c = rng.normal(size=(n, d))
+    m = len(ev)
+    gamma = rng.uniform(0.01, 0.2, m); s = rng.uniform(0.0, 1.5, m)
+    is_grad = ev.kind == 0
+    xi = rng.normal(size=(int(is_grad.sum()), d))
+    xi_row = np.full(m, -1, np.int64); xi_row[is_grad] = np.arange(is_grad.sum())
+    c_row = np.where(is_grad, ev.i, -1).astype(np.int64)
+    st = core.State(x0, xt0, eta, alpha, alpha_t, order=1).apply(ev, gamma, s, xi, xi_row, c, c_row)
+    T = ev.t[-1] + 0.5
+    ox, oxt = st.flushed(T)
+    evl = list(zip(ev.t, ev.kind, ev.i, ev.j))
+    xi_l = [xi[xi_row[e]] if xi_row[e] >= 0 else None for e in range(m)]
+    bx, bxt = dense_ops.run(x0, xt0, eta, alpha, alpha_t, evl, gamma, s, c, xi_l, t_final=T, order=1)
+    assert np.allclose(ox, bx, rtol=1e-10, atol=1e-12) and np.allclose(oxt, bxt, rtol=1e-10, atol=1e-12)
+    # the two orders differ (unless eta = 0, where there is no flow to be stale against) ...
+    st0 = core.State(x0, xt0, eta, alpha, alpha_t, order=0).apply(ev, gamma, s, xi, xi_row, c, c_row)
+    assert not np.allclose(st0.x, st.x, rtol=1e-6)
+    a = core.State(x0, xt0, 0.0, alpha, alpha_t, order=0).apply(ev, gamma, s, xi, xi_row, c, c_row)
+    b = core.State(x0, xt0, 0.0, alpha, alpha_t, order=1).apply(ev, gamma, s, xi, xi_row, c, c_row)
+    assert np.allclose(a.x, b.x, rtol=1e-13) and np.allclose(a.xt, b.xt, rtol=1e-13)
+    # ... and both keep the invariants: column sums of x + xt move only by the gradient steps
+    comm_only = _events(n, edges, 0.0, 1.0, 9, 80)
+    s1 = core.State(x0, None, eta, alpha, alpha_t, order=1).apply(comm_only)
+    fx, fxt = s1.flushed(comm_only.t[-1])
+    assert np.allclose((fx + fxt).sum(0), 2 * x0.sum(0), rtol=1e-12)
+
+
+def test_average_reaches_consensus_and_keeps_the_means():
+    rng = np.random.default_rng(14)
+    n, d = 6, 11
+    edges = graph.ring(n)
+    ev = _events(n, edges, 1.0, 1.0, 31, 200)
+    x0 = rng.normal(size=(n, d))
+    st = core.State(x0, None, 0.6, 0.5, 1.2).apply(ev, 0.05, 0.0, rng.normal(size=(int((ev.kind == 0).sum()), d)),
+                                                   np.where(ev.kind == 0, np.cumsum(ev.kind == 0) - 1, -1))
+    T = ev.t[-1] + 0.3
+    fx, fxt = st.flushed(T)
+    st.average(T)
+    assert np.allclose(st.x, fx.mean(0, keepdims=True), rtol=1e-14) and np.allclose(st.xt, fxt.mean(0), rtol=1e-14)
+    s = st.stats(T)
+    assert s["consensus_x"] < 1e-25 and s["consensus_xt"] < 1e-25 and np.all(st.t == T)
+    assert np.allclose(st.x.sum(0), fx.sum(0), rtol=1e-13)
