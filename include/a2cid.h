@@ -215,6 +215,21 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
 int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
                        const double *node_rate, uint64_t seed);
 
+/* The event source of the paper's implementation instead of Assumption 3.1's clocks (section
+ * "Practical implementation of the dynamic"; appendix "Uniform neighbor selection check"):
+ * every worker computes gradient steps back to back (the k-th step of worker i lasts
+ * (1 / node_rate[i]) (1 + jitter (2u - 1)), u uniform; its end is a gradient event) and at each
+ * step's end adds a Poisson(comm_per_grad) number of p2p averagings to do; a worker that is not
+ * inside an averaging and still has some to do is available and joins the tail of one queue; the
+ * coordinator pairs the oldest available worker with its oldest available graph neighbour as long
+ * as such pairs exist (a gossip event at that moment; both partners are then busy for comm_time).
+ * Simultaneous completions are ordered (time, averaging-end before step-end, worker).  The graph's
+ * rates are ignored.  Streams: Philox4x32-10 as for a2cid_sched_create with counter tags
+ * 0x0A2C1D21 (durations) and 0x0A2C1D22 (Poisson counts, product-of-uniforms method).  The
+ * returned scheduler is used with a2cid_sched_next / skip / counts / destroy like any other. */
+int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *graph, const double *node_rate,
+                           double comm_per_grad, double comm_time, double jitter, uint64_t seed);
+
 /* Takes the next max_events events of the serial stream and packs them into levels: an
  * event's level is one more than the highest level of an earlier event of this batch sharing
  * a worker with it; inside a level events keep serial order.  The returned batch (ops,

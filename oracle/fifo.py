@@ -1,0 +1,111 @@
+"""The paper's practical event source (test infrastructure): gradient steps back to back, a Poisson
+number of p2p averagings per gradient step, partners found first-in-first-out among available
+neighbours (section "Practical implementation of the dynamic"; appendix "Uniform neighbor selection
+check").  Plain Python, one event at a time.
+
+Reading used (the paper describes the mechanism in prose only):
+  * worker i finishes gradient steps back to back; the k-th step lasts (1 / rate_i) * (1 + jitter * (2u - 1)),
+    u uniform in [0, 1); its completion at time t is the gradient event (t, i);
+  * at each completion the worker draws K ~ Poisson(comm_per_grad) and adds K to the averagings it still
+    has to do;
+  * a worker is AVAILABLE when it is not inside an averaging and still has averagings to do; when it
+    becomes available it joins the tail of one global queue;
+  * whenever the queue changes, the coordinator scans it from the head and pairs the first worker with
+    the first later worker that is its neighbour in the graph, as long as such pairs exist; a pairing at
+    time t is the gossip event (t, i, j), costs each partner one of its pending averagings and keeps both
+    busy until t + comm_time;
+  * simultaneous completions are handled in order (time, communication-end before gradient-end, worker id).
+
+Random numbers: Philox4x32-10, key = (seed_lo, seed_hi), counter = (draw_lo, draw_hi, worker, tag) with
+tag 0x0A2C1D21 for step durations and 0x0A2C1D22 for the Poisson counts; a uniform is the 53-bit value
+built from words 0 and 1.  The Poisson count multiplies uniforms until the product drops to exp(-mean) or
+below (Knuth).
+"""
+import heapq
+import math
+
+import numpy as np
+
+from . import core
+
+TAG_DURATION = 0x0A2C1D21
+TAG_POISSON = 0x0A2C1D22
+
+
+class _Uniforms:
+    def __init__(self, seed, worker, tag):
+        self.key = [seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF]
+        self.worker, self.tag, self.k = worker, tag, 0
+
+    def next(self):
+        w = core.philox4x32_10([self.k & 0xFFFFFFFF, self.k >> 32, self.worker, self.tag], self.key)
+        self.k += 1
+        return ((int(w[0]) << 21) | (int(w[1]) >> 11)) * 2.0 ** -53
+
+
+def _poisson(stream, mean):
+    limit = math.exp(-mean)
+    k, p = 0, 1.0
+    while True:
+        k += 1
+        p *= stream.next()
+        if not p > limit:
+            return k - 1
+
+
+def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_events):
+    """Returns core.Events (clock = worker for gradient events, n + edge index for gossip events)."""
+    edge_index = {}
+    for e, (a, b) in enumerate(edges):
+        edge_index[(a, b)] = e
+        edge_index[(b, a)] = e
+    dur = [_Uniforms(seed, i, TAG_DURATION) for i in range(n)]
+    cnt = [_Uniforms(seed, i, TAG_POISSON) for i in range(n)]
+    todo = [0] * n
+    busy = [False] * n
+    queue = []                                   # available workers, oldest first
+    heap = []                                    # (time, kind: 0 communication end / 1 gradient end, worker)
+    for i in range(n):
+        if node_rate[i] > 0:
+            heapq.heappush(heap, ((1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0)), 1, i))
+    out_t, out_kind, out_i, out_j, out_clock = [], [], [], [], []
+
+    def join(i):
+        if not busy[i] and todo[i] > 0 and i not in queue:
+            queue.append(i)
+
+    def match(t):
+        while True:
+            found = None
+            for pa in range(len(queue)):
+                for pb in range(pa + 1, len(queue)):
+                    if (queue[pa], queue[pb]) in edge_index:
+                        found = (pa, pb)
+                        break
+                if found:
+                    break
+            if not found or len(out_t) >= n_events:
+                return
+            a, b = queue[found[0]], queue[found[1]]
+            del queue[found[1]]
+            del queue[found[0]]
+            e = edge_index[(a, b)]
+            out_t.append(t); out_kind.append(1); out_i.append(edges[e][0]); out_j.append(edges[e][1])
+            out_clock.append(n + e)
+            for w in (a, b):
+                todo[w] -= 1
+                busy[w] = True
+                heapq.heappush(heap, (t + comm_time, 0, w))
+
+    while heap and len(out_t) < n_events:
+        t, kind, i = heapq.heappop(heap)
+        if kind == 0:
+            busy[i] = False
+        else:
+            out_t.append(t); out_kind.append(0); out_i.append(i); out_j.append(-1); out_clock.append(i)
+            todo[i] += _poisson(cnt[i], comm_per_grad)
+            heapq.heappush(heap, (t + (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0)), 1, i))
+        join(i)
+        match(t)
+    return core.Events(np.array(out_t), np.array(out_kind, np.int32), np.array(out_i, np.int32),
+                       np.array(out_j, np.int32), np.array(out_clock, np.int32))

@@ -8,7 +8,9 @@
 #include <cstring>
 #include <limits>
 #include <new>
+#include <deque>
 #include <queue>
+#include <tuple>
 #include <utility>
 
 #include "a2cid_internal.h"
@@ -231,16 +233,102 @@ struct a2cid_sched {
     std::vector<int64_t> level_off, cursor;
     std::vector<int32_t> last_level;
 
-    double waiting_time(int32_t clock) {
-        const uint64_t k = draws[clock]++;
-        uint32_t c[4] = {(uint32_t)k, (uint32_t)(k >> 32), (uint32_t)clock, 0x0A2C1D20u};
+    // ---- first-in-first-out pairing source (a2cid_sched_create_fifo) -------------------------------
+    bool fifo = false;
+    double comm_per_grad = 0.0, comm_time = 0.0, jitter = 0.0;
+    std::vector<uint64_t> count_draws;           // uniforms used so far for the Poisson counts, per worker
+    std::vector<int64_t> todo;                   // averagings a worker still has to do
+    std::vector<char> busy, queued;
+    std::vector<int32_t> waiting;                // available workers, oldest first
+    std::vector<int32_t> edge_of;                // n x n: index of edge {a, b}, or -1
+    using Completion = std::tuple<double, int32_t, int32_t>;   // (time, 0 averaging ends / 1 step ends, worker)
+    std::priority_queue<Completion, std::vector<Completion>, std::greater<Completion>> completions;
+    std::deque<a2cid_op> emitted;                // events produced by the last completion, not yet handed out
+
+    double uniform(uint64_t k, uint32_t stream, uint32_t tag) const {
+        uint32_t c[4] = {(uint32_t)k, (uint32_t)(k >> 32), stream, tag};
         philox4x32_10(c, (uint32_t)seed, (uint32_t)(seed >> 32));
         const uint64_t mantissa = ((uint64_t)c[0] << 21) | (c[1] >> 11);
-        const double u = std::ldexp((double)mantissa, -53);
+        return std::ldexp((double)mantissa, -53);
+    }
+
+    double waiting_time(int32_t clock) {
+        const double u = uniform(draws[clock]++, (uint32_t)clock, 0x0A2C1D20u);
         return -std::log1p(-u) / rate[clock];
     }
 
+    // duration of worker w's next gradient step: mean 1 / rate, uniform within +- jitter of it
+    double step_time(int32_t w) {
+        const double u = uniform(draws[w]++, (uint32_t)w, 0x0A2C1D21u);
+        return (1.0 / rate[w]) * (1.0 + jitter * (2.0 * u - 1.0));
+    }
+
+    // Poisson(comm_per_grad) by multiplying uniforms until the product reaches exp(-mean) (Knuth)
+    int64_t comm_count(int32_t w) {
+        const double limit = std::exp(-comm_per_grad);
+        int64_t k = 0;
+        double p = 1.0;
+        do {
+            ++k;
+            p *= uniform(count_draws[w]++, (uint32_t)w, 0x0A2C1D22u);
+        } while (p > limit);
+        return k - 1;
+    }
+
+    void emit(double t, int32_t kind, int32_t i, int32_t j, int32_t clock) {
+        a2cid_op op;
+        std::memset(&op, 0, sizeof(op));
+        op.t = t; op.kind = kind; op.i = i; op.j = j;
+        op.id = serial++;
+        ++fired[clock];
+        emitted.push_back(op);
+    }
+
+    // one completion of the FIFO source: may emit a gradient event and any number of pairings
+    bool advance_fifo() {
+        if (completions.empty()) return false;
+        const auto [t, what, w] = completions.top();
+        completions.pop();
+        if (what == 0) {
+            busy[w] = 0;
+        } else {
+            emit(t, A2CID_KIND_GRADIENT, w, -1, w);
+            todo[w] += comm_count(w);
+            completions.emplace(t + step_time(w), 1, w);
+        }
+        if (!busy[w] && todo[w] > 0 && !queued[w]) { waiting.push_back(w); queued[w] = 1; }
+        // the coordinator: oldest available worker first, with the oldest available neighbour of it
+        for (;;) {
+            size_t pa = 0, pb = 0;
+            bool found = false;
+            for (pa = 0; pa < waiting.size() && !found; ++pa)
+                for (pb = pa + 1; pb < waiting.size(); ++pb)
+                    if (edge_of[(size_t)waiting[pa] * g.n + waiting[pb]] >= 0) { found = true; break; }
+            if (!found) break;
+            --pa;   // the outer loop stepped once more after the hit
+            const int32_t a = waiting[pa], b = waiting[pb];
+            waiting.erase(waiting.begin() + (ptrdiff_t)pb);
+            waiting.erase(waiting.begin() + (ptrdiff_t)pa);
+            const int32_t e = edge_of[(size_t)a * g.n + b];
+            emit(t, A2CID_KIND_GOSSIP, g.u[e], g.v[e], g.n + e);
+            for (int32_t m : {a, b}) {
+                --todo[m];
+                busy[m] = 1;
+                queued[m] = 0;
+                completions.emplace(t + comm_time, 0, m);
+            }
+        }
+        return true;
+    }
+
     bool pop(a2cid_op &op) {
+        if (fifo) {
+            while (emitted.empty())
+                if (!advance_fifo()) return false;
+            op = emitted.front();
+            emitted.pop_front();
+            return true;
+        }
         if (heap.empty()) return false;
         const Entry e = heap.top();
         heap.pop();
@@ -349,6 +437,53 @@ int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
         s->last_level.assign(n, -1);
         for (int32_t c = 0; c < clocks; ++c)
             if (s->rate[c] > 0.0) s->heap.emplace(s->waiting_time(c), c);
+    } catch (const std::bad_alloc &) {
+        delete s;
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    *out = s;
+    return A2CID_OK;
+}
+
+int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *graph, const double *node_rate,
+                           double comm_per_grad, double comm_time, double jitter, uint64_t seed) {
+    clear_error();
+    if (!out || !node_rate) return fail(A2CID_EINVAL, "out / node_rate is NULL");
+    *out = nullptr;
+    if (!(comm_per_grad >= 0.0) || !std::isfinite(comm_per_grad) || comm_per_grad > 700.0)
+        return fail(A2CID_EINVAL, "comm_per_grad = %g must be in [0, 700]", comm_per_grad);
+    if (!(comm_time >= 0.0) || !std::isfinite(comm_time)) return fail(A2CID_EINVAL, "comm_time = %g must be >= 0", comm_time);
+    if (!(jitter >= 0.0) || jitter >= 1.0) return fail(A2CID_EINVAL, "jitter = %g must be in [0, 1)", jitter);
+    a2cid_sched *s = new (std::nothrow) a2cid_sched;
+    if (!s) return fail(A2CID_ENOMEM, "out of host memory");
+    try {
+        if (int rc = load_graph(s->g, n, graph)) { delete s; return rc; }
+        const int32_t clocks = n + (int32_t)s->g.u.size();
+        s->fifo = true;
+        s->comm_per_grad = comm_per_grad; s->comm_time = comm_time; s->jitter = jitter;
+        s->rate.assign(clocks, 0.0);
+        for (int32_t i = 0; i < n; ++i) {
+            if (!(node_rate[i] >= 0.0) || !std::isfinite(node_rate[i])) {
+                delete s;
+                return fail(A2CID_EINVAL, "node_rate[%d] = %g must be finite and >= 0", i, node_rate[i]);
+            }
+            s->rate[i] = node_rate[i];
+        }
+        s->draws.assign(clocks, 0);
+        s->fired.assign(clocks, 0);
+        s->count_draws.assign(n, 0);
+        s->todo.assign(n, 0);
+        s->busy.assign(n, 0);
+        s->queued.assign(n, 0);
+        s->seed = seed;
+        s->last_level.assign(n, -1);
+        s->edge_of.assign((size_t)n * n, -1);
+        for (size_t e = 0; e < s->g.u.size(); ++e) {
+            s->edge_of[(size_t)s->g.u[e] * n + s->g.v[e]] = (int32_t)e;
+            s->edge_of[(size_t)s->g.v[e] * n + s->g.u[e]] = (int32_t)e;
+        }
+        for (int32_t i = 0; i < n; ++i)
+            if (s->rate[i] > 0.0) s->completions.emplace(s->step_time(i), 1, i);
     } catch (const std::bad_alloc &) {
         delete s;
         return fail(A2CID_ENOMEM, "out of host memory");

@@ -82,6 +82,13 @@ def clock_rates(cfg):
     return np.ones(cfg.n), float(cfg.edge_rate)
 
 
+def fifo_edge_rate(cfg, fifo):
+    """Per-edge rate equivalent to every worker doing comm_per_grad averagings per gradient step with peers chosen
+    uniformly among its neighbours: n * comm_per_grad * mean(node rate) / 2 communications per unit time."""
+    node, _ = clock_rates(cfg)
+    return cfg.n * fifo["comm_per_grad"] * float(node.mean()) / 2.0 / len(edge_list(cfg.topology, cfg.n))
+
+
 def grad_fraction(cfg):
     node, er = clock_rates(cfg)
     ne = len(edge_list(cfg.topology, cfg.n))
@@ -96,7 +103,10 @@ def scaled(cfg, d=None, events=None):
 class Workload:
     """Device-side instance of a config: state, gradient inputs, scheduler and engine."""
 
-    def __init__(self, cfg, device="cuda:0", batch_events=1024, xi_slots=None, reuse_xi=False):
+    def __init__(self, cfg, device="cuda:0", batch_events=1024, xi_slots=None, reuse_xi=False, fifo=None):
+        """fifo = dict(comm_per_grad, comm_time, jitter) replaces the Poisson clocks by the first-in-first-out
+        pairing source; the edge rate that enters chi_1, chi_2 is then comm_per_grad spread evenly over the edges
+        (uniform pairing among neighbours, as the paper assumes when it computes them)."""
         import torch
         from . import binding
         from synth import fill
@@ -110,6 +120,8 @@ class Workload:
         self.u = [e[0] for e in edges]
         self.v = [e[1] for e in edges]
         self.node_rate, self.edge_rate = clock_rates(cfg)
+        if fifo is not None:
+            self.edge_rate = fifo_edge_rate(cfg, fifo)
         if cfg.accelerated:
             p = binding.a2cid_graph_params(n, self.u, self.v, self.edge_rate)
             eta, alpha_t = p["eta"], p["alpha_tilde"]
@@ -137,7 +149,7 @@ class Workload:
             self.xi = None
             if cfg.xi_sigma > 0:
                 if xi_slots is None:
-                    frac = grad_fraction(cfg)
+                    frac = grad_fraction(cfg) if fifo is None else 1.0 / (1.0 + 0.5 * fifo["comm_per_grad"])
                     xi_slots = min(self.batch_events, int(self.batch_events * frac * 1.5) + 16)
                 self.xi = torch.empty((int(xi_slots), self.ld), dtype=torch.float32, device=self.device)
                 if self.reuse_xi:
@@ -145,7 +157,7 @@ class Workload:
                         fill.fill_normal(self.xi[s, :d], cfg.seed, gen.DOMAIN_XI, s, cfg.xi_sigma)
             self.engine = binding.Engine(self.x, self.xt, d, self.u, self.v, self.edge_rate, self.eta,
                                          self.alpha, self.alpha_tilde)
-        self.sched = binding.Scheduler(n, self.u, self.v, self.edge_rate, self.node_rate, cfg.seed)
+        self.sched = binding.Scheduler(n, self.u, self.v, self.edge_rate, self.node_rate, cfg.seed, fifo=fifo)
         self.events_done = 0
         self.t_last = 0.0
 

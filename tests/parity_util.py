@@ -22,9 +22,11 @@ def sample_columns(d, count, seed=0):
     return np.unique(np.concatenate([head, tail, mid]))
 
 
-def oracle_params(cfg):
+def oracle_params(cfg, fifo=None):
     edges = getattr(graph, cfg.topology)(cfg.n)
     node_rate, edge_rate = wl.clock_rates(cfg)
+    if fifo is not None:
+        edge_rate = graph.per_worker_to_edge_rate(cfg.n, edges, fifo["comm_per_grad"] * float(node_rate.mean()))
     if cfg.accelerated:
         p = graph.acid_params(cfg.n, edges, edge_rate)
         eta, alpha_t = p["eta"], p["alpha_tilde"]
@@ -40,9 +42,9 @@ def oracle_params(cfg):
 class OracleStream:
     """The oracle following columns `cols` of a workload, fed with the serial stream chunk by chunk."""
 
-    def __init__(self, cfg, cols, order=0):
-        self.cfg, self.cols = cfg, np.asarray(cols, np.int64)
-        edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg)
+    def __init__(self, cfg, cols, order=0, fifo=None):
+        self.cfg, self.cols, self.fifo = cfg, np.asarray(cols, np.int64), fifo
+        edges, node_rate, edge_rate, eta, alpha, alpha_t = oracle_params(cfg, fifo)
         self.edges, self.node_rate, self.edge_rate = edges, node_rate, edge_rate
         x0 = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_INIT, np.arange(cfg.n), self.cols, cfg.init_sigma)
         self.state = core.State(x0, None, eta, alpha, alpha_t, order=order)
@@ -52,6 +54,11 @@ class OracleStream:
 
     def generate(self, n_events):
         """The first n_events events of the stream (the oracle's own clock code, from time 0)."""
+        if self.fifo is not None:
+            from oracle import fifo as fifo_source
+            self.events = fifo_source.generate(self.cfg.n, self.edges, self.node_rate, self.fifo["comm_per_grad"],
+                                               self.fifo["comm_time"], self.fifo["jitter"], self.cfg.seed, n_events)
+            return self.events
         self.events = core.generate_events(self.cfg.n, [e[0] for e in self.edges], [e[1] for e in self.edges],
                                            self.node_rate, np.full(len(self.edges), self.edge_rate), self.cfg.seed,
                                            n_events)
@@ -76,9 +83,9 @@ class OracleStream:
         return self.state
 
 
-def oracle_run(cfg, cols, n_events, chunk=20000, order=0):
+def oracle_run(cfg, cols, n_events, chunk=20000, order=0, fifo=None):
     """Oracle state after the first n_events events of cfg, restricted to columns cols."""
-    o = OracleStream(cfg, cols, order)
+    o = OracleStream(cfg, cols, order, fifo)
     ev = o.generate(n_events)
     for lo in range(0, len(ev), chunk):
         o.advance(min(len(ev), lo + chunk))

@@ -294,3 +294,22 @@ def test_average_matches_oracle(name, d):
     s = w.engine.stats(t_now)
     assert s["consensus_x"] == 0.0 and s["consensus_xt"] == 0.0
     w.close()
+
+
+@pytest.mark.parametrize("name,d,mode", [("C3", 6001, 1), ("C4", 5000, 2), ("C5", 4099, 1)])
+def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode):
+    # the paper's practical event source: Poisson count per gradient step + first-in-first-out pairing
+    fifo = dict(comm_per_grad=2.0 if name == "C3" else 1.0, comm_time=0.03, jitter=0.25)
+    cfg = wl.scaled(wl.CONFIGS[name], d=d, events=3000)
+    _say(f"fifo source {name} d={d} mode={mode}")
+    w = wl.Workload(cfg, batch_events=750, fifo=fifo)
+    w.engine.set_tuning(1, 0, 256, mode)
+    w.run(3000)
+    cols = np.arange(cfg.d)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, 3000, fifo=fifo)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    counts = w.sched.counts()
+    assert counts.sum() == 3000 and np.array_equal(counts, np.bincount(ev.clock, minlength=len(counts)))
+    w.close()

@@ -199,3 +199,36 @@ def test_empty_batch_is_fine():
     u, v = _uv(graph.ring(n))
     t1, coef = a2.a2cid_plan_batch(n, u, v, 1.0, 0.5, np.zeros(n), _batch([], [0]))
     assert len(coef) == 0 and np.all(t1 == 0)
+
+
+# ------------------------------------------------------------------ first-in-first-out pairing source
+@pytest.mark.parametrize("topo,n,rho,comm_time,jitter,seed", [
+    ("ring", 16, 1.0, 0.05, 0.2, 3), ("exponential", 64, 1.0, 0.02, 0.1, (5 << 32) + 1),
+    ("complete", 8, 2.0, 0.0, 0.0, 7), ("ring", 64, 2.0, 0.01, 0.5, 11)])
+def test_fifo_schedule_is_bit_identical_to_the_oracle_stream(topo, n, rho, comm_time, jitter, seed):
+    from oracle import fifo
+    edges = getattr(graph, topo)(n)
+    u, v = _uv(edges)
+    rate = np.exp(0.3 * np.random.default_rng(2).normal(size=n)) if jitter > 0 else np.ones(n)
+    m = 6000
+    ref = fifo.generate(n, edges, rate, rho, comm_time, jitter, seed, m)
+    s = a2.Scheduler(n, u, v, 1.0, rate, seed, fifo=dict(comm_per_grad=rho, comm_time=comm_time, jitter=jitter))
+    got = [s.next(1500) for _ in range(4)]
+    ref_batches = levels.pack(ref.kind, ref.i, ref.j, 1500)
+    for b, rb in zip(got, ref_batches):
+        order = [e for lev in rb for e in lev]
+        assert list(b.level_off) == list(np.cumsum([0] + [len(lev) for lev in rb]))
+        assert np.array_equal(b.ops["id"], order)
+        assert np.array_equal(b.ops["t"], ref.t[order])
+        assert np.array_equal(b.ops["kind"], ref.kind[order])
+        assert np.array_equal(b.ops["i"], ref.i[order]) and np.array_equal(b.ops["j"], ref.j[order])
+    assert np.array_equal(s.counts(), np.bincount(ref.clock, minlength=n + len(edges)))
+
+
+def test_fifo_scheduler_rejects_bad_parameters():
+    u, v = _uv(graph.ring(4))
+    for kw in (dict(comm_per_grad=-1.0, comm_time=0.0, jitter=0.0), dict(comm_per_grad=1.0, comm_time=-0.1, jitter=0.0),
+               dict(comm_per_grad=1.0, comm_time=0.0, jitter=1.0), dict(comm_per_grad=float("nan"), comm_time=0.0, jitter=0.0)):
+        with pytest.raises(a2.A2cidError) as e:
+            a2.Scheduler(4, u, v, 1.0, 1.0, 1, fifo=kw)
+        assert e.value.code == binding.EINVAL
