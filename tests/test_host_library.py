@@ -232,3 +232,31 @@ def test_fifo_scheduler_rejects_bad_parameters():
         with pytest.raises(a2.A2cidError) as e:
             a2.Scheduler(4, u, v, 1.0, 1.0, 1, fifo=kw)
         assert e.value.code == binding.EINVAL
+
+
+def test_engine_entry_points_fail_cleanly_without_touching_memory():
+    # argument checks come before any GPU call, so these run on a machine without a GPU
+    lib = a2.load()
+    g = binding._GraphArg([0, 1], [1, 2], 1.0)
+    h = C.c_void_p()
+    for buf, code in [(binding.a2cid_buffers(0x1004, 0x2000, 8, None), binding.EALIGN),
+                      (binding.a2cid_buffers(0x1000, 0x2000, 6, None), binding.EINVAL),       # ld < d
+                      (binding.a2cid_buffers(0x1000, 0x2000, 10, None), binding.EALIGN),      # ld % 4 != 0
+                      (binding.a2cid_buffers(0x1000, 0x1000, 8, None), binding.EINVAL),       # x == xt
+                      (binding.a2cid_buffers(0, 0x2000, 8, None), binding.EINVAL)]:
+        assert lib.a2cid_create(C.byref(h), 3, 8, C.byref(g.struct), 0.5, 0.5, 0.5, C.byref(buf)) == code
+        assert h.value is None and len(lib.a2cid_last_error()) > 0
+    good = binding.a2cid_buffers(0x1000, 0x2000, 8, None)
+    assert lib.a2cid_create(C.byref(h), 3, 0, C.byref(g.struct), 0.5, 0.5, 0.5, C.byref(good)) == binding.EINVAL
+    assert lib.a2cid_create(C.byref(h), 3, 8, C.byref(g.struct), -1.0, 0.5, 0.5, C.byref(good)) == binding.EINVAL
+    assert lib.a2cid_create(C.byref(h), 3, 8, C.byref(g.struct), 0.5, float("nan"), 0.5, C.byref(good)) == binding.EINVAL
+    assert lib.a2cid_create(C.byref(h), 3, 8, None, 0.5, 0.5, 0.5, C.byref(good)) == binding.EINVAL
+    assert lib.a2cid_create(C.byref(h), 3, 8, C.byref(g.struct), 0.5, 0.5, 0.5, None) == binding.EINVAL
+    assert lib.a2cid_apply_events(None, None) == binding.EINVAL
+    assert lib.a2cid_stats(None, 0.0, None) == binding.EINVAL
+    assert lib.a2cid_flush(None, 0.0) == binding.EINVAL and lib.a2cid_average(None, 0.0) == binding.EINVAL
+    assert lib.a2cid_stream_probe(None, None, 16, None) == binding.EINVAL
+    assert lib.a2cid_stream_probe(0x1000, 0x2000, 18, None) == binding.EINVAL
+    assert lib.a2cid_stream_probe(0x1004, 0x2000, 16, None) == binding.EALIGN
+    lib.a2cid_destroy(None)
+    lib.a2cid_sched_destroy(None)
