@@ -463,8 +463,13 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     const int32_t m = 2 * c->n + 2;
     const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
 #define A2CID_STATS_LAUNCH(V, R, NT)                                                                            \
-    hipLaunchKernelGGL((stats_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt,       \
-                       c->ld, c->d, c->n, c->b_dev, c->partials, n_tiles)
+    do {                                                                                                         \
+        if (lds > 32768)   /* the kernel also has 4 KiB of static LDS; the default cap is 64 KiB in total */      \
+            A2CID_HIP(hipFuncSetAttribute((const void *)stats_kernel<V, R, NT>,                                   \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                 \
+        hipLaunchKernelGGL((stats_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt,   \
+                           c->ld, c->d, c->n, c->b_dev, c->partials, n_tiles);                                    \
+    } while (0)
     const bool snt = c->stats_nt != 0;
     if (v == 1 && r == 1) { if (snt) A2CID_STATS_LAUNCH(1, 1, true); else A2CID_STATS_LAUNCH(1, 1, false); }
     else if (v == 1 && r == 2) { if (snt) A2CID_STATS_LAUNCH(1, 2, true); else A2CID_STATS_LAUNCH(1, 2, false); }

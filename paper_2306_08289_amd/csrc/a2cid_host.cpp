@@ -59,46 +59,123 @@ double mix_coefficient(double eta, double tau) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Symmetric eigen-decomposition by cyclic Jacobi rotations (n <= A2CID_MAX_WORKERS; the
-// Laplacian is tiny next to the parameter vectors).  a is overwritten by its diagonal form,
-// v receives the eigenvectors as columns.
+// Eigenvalues of a symmetric matrix (row-major, destroyed): Householder reduction to tridiagonal
+// form followed by the implicit-shift QL iteration (Wilkinson & Reinsch), eigenvalues only.
+// O(n^3) once: a second for n = 1024, the largest Laplacian the library accepts.
+// Returns false if the QL iteration does not converge.
 // ------------------------------------------------------------------------------------------
-static void jacobi_eigen(int n, std::vector<double> &a, std::vector<double> &v) {
-    v.assign((size_t)n * n, 0.0);
-    for (int i = 0; i < n; ++i) v[(size_t)i * n + i] = 1.0;
-    for (int sweep = 0; sweep < 100; ++sweep) {
-        double off = 0.0, diag = 0.0;
-        for (int p = 0; p < n; ++p) {
-            diag += a[(size_t)p * n + p] * a[(size_t)p * n + p];
-            for (int q = p + 1; q < n; ++q) off += a[(size_t)p * n + q] * a[(size_t)p * n + q];
-        }
-        if (off <= 1e-30 * (diag + off)) break;
-        for (int p = 0; p < n - 1; ++p) {
-            for (int q = p + 1; q < n; ++q) {
-                const double apq = a[(size_t)p * n + q];
-                if (apq == 0.0) continue;
-                const double app = a[(size_t)p * n + p], aqq = a[(size_t)q * n + q];
-                const double theta = (aqq - app) / (2.0 * apq);
-                const double tt = (theta >= 0 ? 1.0 : -1.0) / (std::fabs(theta) + std::sqrt(theta * theta + 1.0));
-                const double c = 1.0 / std::sqrt(tt * tt + 1.0), s = tt * c;
-                for (int k = 0; k < n; ++k) {   // columns p, q of a
-                    const double akp = a[(size_t)k * n + p], akq = a[(size_t)k * n + q];
-                    a[(size_t)k * n + p] = c * akp - s * akq;
-                    a[(size_t)k * n + q] = s * akp + c * akq;
+static bool symmetric_eigenvalues(int n, std::vector<double> &a, std::vector<double> &diag) {
+    std::vector<double> off(n, 0.0), p(n);
+    diag.assign(n, 0.0);
+    auto A = [&](int r, int c) -> double & { return a[(size_t)r * n + c]; };
+    // Householder: row i of the (lower triangle of the) leading (i+1) x (i+1) block is reflected onto e_{i-1}
+    for (int i = n - 1; i >= 1; --i) {
+        const int l = i - 1;
+        double scale = 0.0, h = 0.0;
+        if (l > 0) {
+            for (int k = 0; k <= l; ++k) scale += std::fabs(A(i, k));
+            if (scale == 0.0) {
+                off[i] = A(i, l);
+            } else {
+                for (int k = 0; k <= l; ++k) { A(i, k) /= scale; h += A(i, k) * A(i, k); }
+                const double f = A(i, l);
+                const double g = f >= 0.0 ? -std::sqrt(h) : std::sqrt(h);
+                off[i] = scale * g;
+                h -= f * g;
+                A(i, l) = f - g;                       // row i now holds the Householder vector u, h = |u|^2 / 2
+                double dot = 0.0;
+                for (int j = 0; j <= l; ++j) {         // p = B u / h with B the leading block (lower triangle stored)
+                    double acc = 0.0;
+                    for (int k = 0; k <= j; ++k) acc += A(j, k) * A(i, k);
+                    for (int k = j + 1; k <= l; ++k) acc += A(k, j) * A(i, k);
+                    p[j] = acc / h;
+                    dot += p[j] * A(i, j);
                 }
-                for (int k = 0; k < n; ++k) {   // rows p, q of a
-                    const double apk = a[(size_t)p * n + k], aqk = a[(size_t)q * n + k];
-                    a[(size_t)p * n + k] = c * apk - s * aqk;
-                    a[(size_t)q * n + k] = s * apk + c * aqk;
-                }
-                for (int k = 0; k < n; ++k) {
-                    const double vkp = v[(size_t)k * n + p], vkq = v[(size_t)k * n + q];
-                    v[(size_t)k * n + p] = c * vkp - s * vkq;
-                    v[(size_t)k * n + q] = s * vkp + c * vkq;
+                const double kappa = dot / (h + h);
+                for (int j = 0; j <= l; ++j) p[j] -= kappa * A(i, j);          // q = p - kappa u
+                for (int j = 0; j <= l; ++j) {                                 // B <- B - u q^T - q u^T
+                    const double uj = A(i, j), qj = p[j];
+                    for (int k = 0; k <= j; ++k) A(j, k) -= uj * p[k] + qj * A(i, k);
                 }
             }
+        } else {
+            off[i] = A(i, l);
         }
     }
+    for (int i = 0; i < n; ++i) diag[i] = A(i, i);
+    // implicit QL on the tridiagonal (diag, off), off[i] coupling i-1 and i
+    for (int i = 1; i < n; ++i) off[i - 1] = off[i];
+    off[n - 1] = 0.0;
+    for (int l = 0; l < n; ++l) {
+        for (int iter = 0;; ++iter) {
+            int m = l;
+            for (; m < n - 1; ++m) {
+                const double dd = std::fabs(diag[m]) + std::fabs(diag[m + 1]);
+                if (std::fabs(off[m]) <= 2.3e-16 * dd) break;
+            }
+            if (m == l) break;
+            if (iter == 200) return false;
+            double g = (diag[l + 1] - diag[l]) / (2.0 * off[l]);
+            double r = std::hypot(g, 1.0);
+            g = diag[m] - diag[l] + off[l] / (g + (g >= 0.0 ? std::fabs(r) : -std::fabs(r)));
+            double sn = 1.0, cs = 1.0, shift = 0.0;
+            int i = m - 1;
+            for (; i >= l; --i) {
+                double f = sn * off[i];
+                const double bb = cs * off[i];
+                r = std::hypot(f, g);
+                off[i + 1] = r;
+                if (r == 0.0) { diag[i + 1] -= shift; off[m] = 0.0; break; }
+                sn = f / r;
+                cs = g / r;
+                g = diag[i + 1] - shift;
+                r = (diag[i] - g) * sn + 2.0 * cs * bb;
+                shift = sn * r;
+                diag[i + 1] = g + shift;
+                g = cs * r - bb;
+            }
+            if (r == 0.0 && i >= l) continue;
+            diag[l] -= shift;
+            off[l] = g;
+            off[m] = 0.0;
+        }
+    }
+    return true;
+}
+
+// Inverse of a symmetric positive definite matrix (row-major, overwritten) by Cholesky factorisation.
+// Returns false if a pivot is not positive.
+static bool spd_inverse(int n, std::vector<double> &a) {
+    auto A = [&](int r, int c) -> double & { return a[(size_t)r * n + c]; };
+    for (int j = 0; j < n; ++j) {                      // A = G G^T, G lower triangular, stored in place
+        double dj = A(j, j);
+        for (int k = 0; k < j; ++k) dj -= A(j, k) * A(j, k);
+        if (!(dj > 0.0)) return false;
+        dj = std::sqrt(dj);
+        A(j, j) = dj;
+        for (int i = j + 1; i < n; ++i) {
+            double v = A(i, j);
+            for (int k = 0; k < j; ++k) v -= A(i, k) * A(j, k);
+            A(i, j) = v / dj;
+        }
+    }
+    for (int j = 0; j < n; ++j) {                      // G <- G^{-1} (lower triangular), column by column
+        A(j, j) = 1.0 / A(j, j);
+        for (int i = j + 1; i < n; ++i) {
+            double v = 0.0;
+            for (int k = j; k < i; ++k) v -= A(i, k) * A(k, j);
+            A(i, j) = v / A(i, i);
+        }
+    }
+    for (int i = 0; i < n; ++i)                         // A^{-1} = G^{-T} G^{-1}: upper triangle first, then mirror
+        for (int j = i; j < n; ++j) {
+            double v = 0.0;
+            for (int k = j; k < n; ++k) v += A(k, i) * A(k, j);
+            A(i, j) = v;                                // safe: column entries A(k, i), A(k, j) with k >= j >= i, row i < k
+        }
+    for (int i = 0; i < n; ++i)
+        for (int j = 0; j < i; ++j) A(i, j) = A(j, i);
+    return true;
 }
 
 static bool connected(const Graph &g) {
@@ -355,36 +432,34 @@ int a2cid_graph_params(const a2cid_graph *graph, int32_t n, double *chi1, double
     Graph g;
     if (int rc = load_graph(g, n, graph)) return rc;
     if (!connected(g)) return fail(A2CID_EGRAPH, "graph is not connected (chi_1 is infinite)");
-    std::vector<double> lap((size_t)n * n, 0.0), vec;
+    std::vector<double> lap((size_t)n * n, 0.0);
+    double trace = 0.0;
     for (size_t e = 0; e < g.u.size(); ++e) {
         const int32_t a = g.u[e], b = g.v[e];
         lap[(size_t)a * n + a] += g.rate[e];
         lap[(size_t)b * n + b] += g.rate[e];
         lap[(size_t)a * n + b] -= g.rate[e];
         lap[(size_t)b * n + a] -= g.rate[e];
+        trace += 2.0 * g.rate[e];
     }
-    jacobi_eigen(n, lap, vec);
-    std::vector<double> eig(n);
-    double top = 0.0;
-    for (int i = 0; i < n; ++i) { eig[i] = lap[(size_t)i * n + i]; top = std::max(top, eig[i]); }
-    // exactly one eigenvalue (the constant vector) is zero for a connected graph: drop the smallest
-    int zero = 0;
-    for (int i = 1; i < n; ++i) if (eig[i] < eig[zero]) zero = i;
-    double smallest = std::numeric_limits<double>::infinity();
-    for (int i = 0; i < n; ++i) if (i != zero) smallest = std::min(smallest, eig[i]);
-    if (!(smallest > 1e-13 * top)) return fail(A2CID_EGRAPH, "Laplacian has a second (near-)zero eigenvalue");
-    const double c1 = 1.0 / smallest;
+    // chi_2: Lambda + c 1 1^T is positive definite for a connected graph and its inverse differs from the
+    // pseudo-inverse only by a multiple of 1 1^T, which (e_a - e_b) does not see
+    std::vector<double> inv(lap);
+    const double shift = trace / ((double)n * (double)n);
+    for (double &v : inv) v += shift;
+    if (!spd_inverse(n, inv)) return fail(A2CID_EGRAPH, "Laplacian is not positive definite on the complement of 1");
     double worst = 0.0;
     for (size_t e = 0; e < g.u.size(); ++e) {
-        const int32_t a = g.u[e], b = g.v[e];
-        double r = 0.0;   // (e_a - e_b)^T pinv(Lambda) (e_a - e_b)
-        for (int k = 0; k < n; ++k) {
-            if (k == zero) continue;
-            const double diff = vec[(size_t)a * n + k] - vec[(size_t)b * n + k];
-            r += diff * diff / eig[k];
-        }
-        worst = std::max(worst, r);
+        const size_t a = (size_t)g.u[e], b = (size_t)g.v[e];
+        worst = std::max(worst, inv[a * n + a] + inv[b * n + b] - 2.0 * inv[a * n + b]);
     }
+    // chi_1: the second smallest eigenvalue (the smallest is the 0 of the constant vector)
+    std::vector<double> eig;
+    if (!symmetric_eigenvalues(n, lap, eig)) return fail(A2CID_EGRAPH, "eigenvalue iteration did not converge");
+    std::sort(eig.begin(), eig.end());
+    const double smallest = eig[1], top = eig[n - 1];
+    if (!(smallest > 1e-13 * top)) return fail(A2CID_EGRAPH, "Laplacian has a second (near-)zero eigenvalue");
+    const double c1 = 1.0 / smallest;
     const double c2 = 0.5 * worst;
     if (chi1) *chi1 = c1;
     if (chi2) *chi2 = c2;

@@ -313,3 +313,87 @@ def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode):
     counts = w.sched.counts()
     assert counts.sum() == 3000 and np.array_equal(counts, np.bincount(ev.clock, minlength=len(counts)))
     w.close()
+
+
+def _custom_workload(n, topology, d, seed=0xA2C1D2 + 77, **kw):
+    base = dict(name=f"custom-{n}-{topology}", n=n, topology=topology, d=d, init_sigma=1.0, gscale=1.0, use_c=True,
+                xi_sigma=0.1, edge_rate=1.0, events=1000, seed=seed)
+    base.update(kw)
+    return wl.Config(**base)
+
+
+@pytest.mark.parametrize("n,topology,d,events,mode", [(2, "ring", 4099, 400, 1), (2, "ring", 5, 400, 2),
+                                                      (1024, "ring", 261, 6000, 1), (1024, "ring", 133, 4000, 0),
+                                                      (112, "exponential", 700, 3000, 2)])
+def test_extreme_worker_counts(n, topology, d, events, mode):
+    # explicit eta, alpha_tilde: Proposition 3.2 gives alpha_tilde = 115 on a ring of 1024, where fp32 cancellation in
+    # xt (terms of +-100 summing to O(1)) alone exceeds 1e-5 -- a property of fp32 state, not of the kernels
+    cfg = _custom_workload(n, topology, d, eta=0.3, alpha_tilde=1.5)
+    _say(f"extreme n={n} {topology} d={d} mode={mode}")
+    w = wl.Workload(cfg, batch_events=2000)
+    w.engine.set_tuning(1, 0, 256, mode)
+    w.run(events)
+    cols = np.arange(d)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, events)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    t_now = float(ev.t[-1]) + 0.2
+    gs, os_ = w.engine.stats(t_now), st.stats(t_now)
+    assert math.isclose(gs["consensus_x"], os_["consensus_x"], rel_tol=1e-4)
+    assert math.isclose(gs["consensus_xt"], os_["consensus_xt"], rel_tol=1e-4)
+    assert np.all(np.abs(gs["sum_x"] - os_["sum_x"]) <= 1e-5 * np.abs(st.x).sum(1))
+    w.engine.average(t_now)
+    st.average(t_now)
+    ax, axt = w.columns(cols)
+    assert pu.rel_err(ax, st.x) <= pu.TOL and pu.rel_err(axt, st.xt) <= pu.TOL
+    w.close()
+
+
+def test_resident_mode_is_refused_beyond_its_lds_capacity():
+    from paper_2306_08289_amd import A2cidError, binding
+    w = wl.Workload(_custom_workload(128, "ring", 64), batch_events=100)
+    with pytest.raises(A2cidError) as e:
+        w.engine.set_tuning(1, 0, 256, 2)
+    assert e.value.code == binding.EINVAL
+    w.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2])
+def test_batches_larger_than_a_staging_buffer_and_empty_batches(mode):
+    # 40 000 events in one batch: the library splits it over several operation-table uploads
+    cfg = wl.scaled(wl.CONFIGS["C4"], d=150, events=40000)
+    _say(f"big batch mode={mode}")
+    w = wl.Workload(cfg, batch_events=40000, xi_slots=40000)
+    w.engine.set_tuning(1, 0, 256, mode)
+    empty = w.next_batch(0)
+    assert len(empty.ops) == 0
+    w.engine.apply_events(empty)
+    w.run(40000)
+    cols = np.arange(cfg.d)
+    gx, gxt = w.columns(cols)
+    st, ev = pu.oracle_run(cfg, cols, 40000)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    c = w.engine.counters()
+    assert c["gossip"] + c["gradient"] == 40000
+    w.close()
+
+
+@pytest.mark.parametrize("mode", [0, 2])
+def test_trailing_mix_in_the_other_kernels(mode):
+    cfg = wl.scaled(wl.CONFIGS["C3"], d=777, events=60)
+    w = wl.Workload(cfg, batch_events=60)
+    w.engine.set_tuning(1, 0, 256, mode)
+    b = w.next_batch(60)
+    t_sync = float(b.ops["t"].max()) + 1.25
+    b.t_sync = t_sync
+    w.engine.apply_events(b)
+    cols = np.arange(cfg.d)
+    st, ev = pu.oracle_run(cfg, cols, 60)
+    touched = sorted(set(ev.i.tolist()) | set(ev.j[ev.kind == 1].tolist()))
+    st.mix_workers(touched, t_sync)
+    gx, gxt = w.columns(cols)
+    assert np.array_equal(w.engine.times(), st.t)
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    w.close()

@@ -33,7 +33,8 @@ def test_library_exports_every_declared_symbol():
 
 @pytest.mark.parametrize("topo,n,rate", [("complete", 4, 1.0), ("ring", 16, 1.0), ("ring", 64, 2.0),
                                          ("exponential", 64, 1.0), ("exponential", 16, 0.4),
-                                         ("complete", 64, 0.56)])
+                                         ("complete", 64, 0.56), ("ring", 1024, 1.0), ("ring", 2, 3.0),
+                                         ("exponential", 600, 0.7)])
 def test_graph_params_match_oracle(topo, n, rate):
     edges = getattr(graph, topo)(n)
     u, v = _uv(edges)
