@@ -452,7 +452,8 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
     for (int32_t i = 0; i < c->n; ++i)
         if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
-    // b_host is reused by every call: the previous call ended with a stream synchronisation
+    // b_host is reused by every call and an earlier asynchronous upload (a2cid_average) may still be reading it
+    A2CID_HIP(hipStreamSynchronize(c->stream));
     for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
     A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
     const int64_t pieces = (c->d + 3) >> 2;

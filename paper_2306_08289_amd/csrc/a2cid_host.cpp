@@ -4,6 +4,7 @@
 // (Assumption 3.1) with its level packing.  No GPU code in this file.
 #include <algorithm>
 #include <cmath>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <limits>
@@ -384,8 +385,8 @@ struct a2cid_sched {
             if (!found) break;
             --pa;   // the outer loop stepped once more after the hit
             const int32_t a = waiting[pa], b = waiting[pb];
-            waiting.erase(waiting.begin() + (ptrdiff_t)pb);
-            waiting.erase(waiting.begin() + (ptrdiff_t)pa);
+            waiting.erase(waiting.begin() + (std::ptrdiff_t)pb);
+            waiting.erase(waiting.begin() + (std::ptrdiff_t)pa);
             const int32_t e = edge_of[(size_t)a * g.n + b];
             emit(t, A2CID_KIND_GOSSIP, g.u[e], g.v[e], g.n + e);
             for (int32_t m : {a, b}) {

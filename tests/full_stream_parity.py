@@ -23,17 +23,19 @@ import parity_util as pu                                  # noqa: E402
 from paper_2306_08289_amd import workloads as wl          # noqa: E402
 
 
-def run(name, events, check_every, batch):
+def run(name, events, check_every, batch, mode=1, order=0, fifo=None):
     cfg = wl.CONFIGS[name]
     events = events or cfg.events
     cols = pu.sample_columns(cfg.d, 4096, seed=7)
     print(f"[{name}] n={cfg.n} d={cfg.d} events={events} sampled columns={len(cols)}", flush=True)
     t0 = time.perf_counter()
-    o = pu.OracleStream(cfg, cols)
+    o = pu.OracleStream(cfg, cols, order=order, fifo=fifo)
     ev = o.generate(events)
     print(f"[{name}] oracle stream generated in {time.perf_counter() - t0:.1f} s, T = {ev.t[-1]:.3f}", flush=True)
-    w = wl.Workload(cfg, batch_events=batch)
-    rec = {"config": name, "n": cfg.n, "d": cfg.d, "events": events, "eta": w.eta, "alpha_tilde": w.alpha_tilde,
+    w = wl.Workload(cfg, batch_events=batch, fifo=fifo)
+    w.engine.set_tuning(1, 0, 256, mode)
+    w.engine.set_order(order)
+    rec = {"config": name, "mode": mode, "order": order, "fifo": fifo, "n": cfg.n, "d": cfg.d, "events": events, "eta": w.eta, "alpha_tilde": w.alpha_tilde,
            "checks": [], "trace": []}
     gpu_s = 0.0
     done = 0
@@ -78,6 +80,10 @@ def main():
     ap.add_argument("--events", type=int, default=None)
     ap.add_argument("--check-every", type=int, default=100000)
     ap.add_argument("--batch", type=int, default=1024)
+    ap.add_argument("--mode", type=int, default=1, help="event kernel: 0 levels, 1 walk (default), 2 LDS-resident")
+    ap.add_argument("--order", type=int, default=0, help="0: Eq. (1) order (default); 1: Algorithm 1's listing order")
+    ap.add_argument("--fifo", type=float, default=None,
+                    help="use the first-in-first-out pairing source with this many averagings per gradient step")
     ap.add_argument("--out", default=os.path.join(ROOT, "gpurun_out", "full_stream.json"))
     args = ap.parse_args()
     results = []
@@ -85,8 +91,10 @@ def main():
         results = json.load(open(args.out))
     ok = True
     for name in args.configs:
-        rec = run(name, args.events, args.check_every, args.batch)
-        results = [r for r in results if r["config"] != name] + [rec]
+        fifo = None if args.fifo is None else dict(comm_per_grad=args.fifo, comm_time=0.02, jitter=0.2)
+        rec = run(name, args.events, args.check_every, args.batch, args.mode, args.order, fifo)
+        results = [r for r in results if (r["config"], r.get("mode", 1), r.get("order", 0), bool(r.get("fifo"))) !=
+                   (name, args.mode, args.order, fifo is not None)] + [rec]
         os.makedirs(os.path.dirname(args.out), exist_ok=True)
         json.dump(results, open(args.out, "w"), indent=1)
         ok = ok and rec["pass"]
