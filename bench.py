@@ -73,6 +73,38 @@ def cpu_baseline(cfg, seconds_budget=20.0):
                       f"same fp32 algorithmic formula as the GPU figure; host has {os.cpu_count()} cores"}
 
 
+def short_run(name, batch, steps=6, warmup=2):
+    """A few steps of one configuration with the default (walk) kernel, then with the LDS-resident one."""
+    import torch
+    from paper_2306_08289_amd import workloads as wl
+    cfg = wl.CONFIGS[name]
+    w = wl.Workload(cfg, device="cuda:0", batch_events=batch, xi_slots=32, reuse_xi=True)
+    stats_bytes = 8.0 * cfg.n * cfg.d
+    res = {"workload": name, "n": cfg.n, "topology": cfg.topology, "d": cfg.d, "events_per_step": batch,
+           "state_bytes": 8.0 * cfg.n * cfg.d,
+           "note": "state fits the 256 MB last-level cache: not an HBM figure" if 8.0 * cfg.n * cfg.d < 3e8 else ""}
+    for mode, key in ((1, "walk"), (2, "resident")):
+        w.engine.set_tuning(1, 0, 256, mode)
+        for _ in range(warmup):
+            w.step(); w.engine.stats(w.t_last)
+        torch.cuda.synchronize()
+        w.engine.counters(reset=True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            w.step(); w.engine.stats(w.t_last)
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        c = w.engine.counters()
+        ev = c["gossip"] + c["gradient"]
+        res[key] = {"events_per_s": ev / el, "gossip_events_per_s": c["gossip"] / el,
+                    "algorithmic_GBs": (c["bytes"] + stats_bytes * steps) / el / 1e9,
+                    "frac_of_hbm_peak": (c["bytes"] + stats_bytes * steps) / el / 1e9 / HBM_PEAK_GBS if mode == 1 else None}
+    w.close()
+    del w
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -89,6 +121,8 @@ def main():
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="append a short measurement of every configuration (C1..C5) to the JSON line")
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket each kernel launch with HIP events")
@@ -207,6 +241,9 @@ def main():
             "speedup_vs_one_pass_per_event": (r_events / r_el) / (events / elapsed)}
     w.close()
     del w
+    torch.cuda.empty_cache()
+    if args.all_configs:
+        out["all_configs"] = [short_run(name, args.batch) for name in ("C1", "C2", "C3", "C4", "C4-baseline", "C5")]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))
