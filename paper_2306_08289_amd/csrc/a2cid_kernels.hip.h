@@ -224,11 +224,9 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
     const int64_t tile = blockIdx.x;
     // the record of operation k + 1 is requested before operation k's rows are, so that its scalar-load
     // latency hides behind the vector loads instead of preceding them
-    DevOp op = ops[0];
     for (int32_t k = 0; k < n_ops; ++k) {
-        const DevOp next = ops[k + 1 < n_ops ? k + 1 : k];
+        const DevOp op = ops[k];
         apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);
-        op = next;
     }
 }
 
