@@ -121,6 +121,7 @@ def main():
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
+    ap.add_argument("--ld-pad", type=int, default=0, help="extra row pitch in units of 4 floats (layout experiments)")
     ap.add_argument("--all-configs", action="store_true",
                     help="append a short measurement of every configuration (C1..C5) to the JSON line")
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
@@ -138,7 +139,7 @@ def main():
     if args.d:
         cfg = wl.scaled(cfg, d=args.d)
     torch.cuda.set_device(0)
-    w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True)
+    w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True, ld_pad=args.ld_pad)
     tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
     if any(v is not None for v in tuning):
         w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 1))])

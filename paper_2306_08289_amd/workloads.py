@@ -103,7 +103,7 @@ def scaled(cfg, d=None, events=None):
 class Workload:
     """Device-side instance of a config: state, gradient inputs, scheduler and engine."""
 
-    def __init__(self, cfg, device="cuda:0", batch_events=1024, xi_slots=None, reuse_xi=False, fifo=None):
+    def __init__(self, cfg, device="cuda:0", batch_events=1024, xi_slots=None, reuse_xi=False, fifo=None, ld_pad=0):
         """fifo = dict(comm_per_grad, comm_time, jitter) replaces the Poisson clocks by the first-in-first-out
         pairing source; the edge rate that enters chi_1, chi_2 is then comm_per_grad spread evenly over the edges
         (uniform pairing among neighbours, as the paper assumes when it computes them)."""
@@ -115,7 +115,7 @@ class Workload:
         self.batch_events = int(batch_events)
         self.reuse_xi = bool(reuse_xi)
         n, d = cfg.n, cfg.d
-        self.ld = (d + 3) // 4 * 4
+        self.ld = (d + 3) // 4 * 4 + 4 * int(ld_pad)      # row pitch in floats (a multiple of 4)
         edges = edge_list(cfg.topology, n)
         self.u = [e[0] for e in edges]
         self.v = [e[1] for e in edges]
