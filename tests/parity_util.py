@@ -8,7 +8,7 @@ import numpy as np
 
 from oracle import core, graph
 from synth import gen
-from paper_2306_08289_amd import workloads as wl
+from synth import configs as wl          # configurations and clock rates: shared inputs, no product code
 
 TOL = 1e-5     # spec tolerance: max relative error, fp32, norm-wise per worker and buffer
 
