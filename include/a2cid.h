@@ -150,14 +150,17 @@ int a2cid_graph_params(const a2cid_graph *graph, int32_t n,
 /* ---- engine ---------------------------------------------------------------------------- */
 
 /* Creates a context for n workers (2 <= n <= A2CID_MAX_WORKERS) of d >= 1 parameters on the
- * current HIP device.  eta >= 0, alpha, alpha_tilde finite (Eq. (1); "time-independent scalar
+ * current HIP device, which must own x and xt (checked: a2cid_check_device_span).  eta >= 0, alpha, alpha_tilde finite (Eq. (1); "time-independent scalar
  * hyper-parameters").  All t_i start at 0 (Algorithm 1, initialisation).  The graph is copied. */
 int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph,
                  double eta, double alpha, double alpha_tilde, const a2cid_buffers *buf);
 
-/* Validates the batch, computes the mixing coefficients from the time stamps, advances the
- * time stamps and enqueues the kernels (Algorithm 1, both threads, for every event of the
- * batch).  On any error nothing is enqueued and no time stamp moves. */
+/* Validates the batch (levels, edges, time order, alignment, and that every xi and c it will read
+ * is d floats of device memory: see a2cid_check_device_span), computes the mixing coefficients from
+ * the time stamps, advances the time stamps and enqueues the kernels (Algorithm 1, both threads, for
+ * every event of the batch).  When validation fails nothing is enqueued and no time stamp moves.
+ * The device that was current at a2cid_create must be current (A2CID_EINVAL otherwise); the same
+ * holds for a2cid_flush, a2cid_stats and a2cid_average. */
 int a2cid_apply_events(a2cid_ctx *ctx, const a2cid_event_batch *batch);
 
 /* Chooses from which values a jump is formed, for all later batches.  A2CID_ORDER_EQ1: the
@@ -271,6 +274,13 @@ int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
  * tiles, 1 ... 8192), nontemporal != 0 selects non-temporal loads.  Default: 2, 2, 2048, 1.  The
  * first three change the summation order, hence the last bits of the results. */
 int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t blocks, int32_t nontemporal);
+
+/* The check the library applies to x and xt at creation and to every xi and c a batch will read:
+ * A2CID_OK if [p, p + bytes) is device (or managed) memory of the context's GPU that does not run
+ * past the end of its allocation, A2CID_EINVAL otherwise (a host pointer, another GPU's memory, a
+ * span longer than what was allocated).  It sees allocations, not tensors: a span inside a
+ * larger allocation, such as a caching allocator's segment, passes.  Launches nothing. */
+int a2cid_check_device_span(a2cid_ctx *ctx, const void *p, int64_t bytes);
 
 /* Measurement aid, independent of any context: enqueues a plain copy of n floats (n a multiple
  * of 4) from src to dst (device pointers, 16-byte aligned, non-overlapping) on hip_stream, with

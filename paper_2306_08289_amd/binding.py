@@ -84,6 +84,7 @@ SIGNATURES = {
     "a2cid_sched_destroy": (None, [C.c_void_p]),
     "a2cid_set_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
     "a2cid_set_stats_tuning": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
+    "a2cid_check_device_span": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64]),
     "a2cid_stream_probe": (C.c_int, [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]),
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
                                  _P(C.c_double), C.c_int32]),
@@ -247,24 +248,33 @@ class Engine:
             _check(load().a2cid_create(C.byref(self._h), self.n, self.d, C.byref(self._g.struct), float(eta),
                                        float(alpha), float(alpha_tilde), C.byref(buf)))
 
+    def _device(self):
+        """The library requires the device of creation to be current on every call that touches the GPU."""
+        import torch
+        return torch.cuda.device(self.x.device)
+
     def apply_events(self, batch):
         bs = batch.struct()
-        _check(load().a2cid_apply_events(self._h, C.byref(bs)))
+        with self._device():
+            _check(load().a2cid_apply_events(self._h, C.byref(bs)))
 
     def stats(self, t_now):
         sx = np.zeros(self.n); sxt = np.zeros(self.n)
         out = a2cid_stats_out(0.0, 0.0, _dptr(sx), _dptr(sxt))
-        _check(load().a2cid_stats(self._h, float(t_now), C.byref(out)))
+        with self._device():
+            _check(load().a2cid_stats(self._h, float(t_now), C.byref(out)))
         return {"consensus_x": out.consensus_x, "consensus_xt": out.consensus_xt, "sum_x": sx, "sum_xt": sxt}
 
     def set_order(self, order):
         _check(load().a2cid_set_order(self._h, int(order)))
 
     def flush(self, t_now):
-        _check(load().a2cid_flush(self._h, float(t_now)))
+        with self._device():
+            _check(load().a2cid_flush(self._h, float(t_now)))
 
     def average(self, t_now):
-        _check(load().a2cid_average(self._h, float(t_now)))
+        with self._device():
+            _check(load().a2cid_average(self._h, float(t_now)))
 
     def times(self):
         t = np.zeros(self.n)
@@ -278,6 +288,10 @@ class Engine:
 
     def synchronize(self):
         _check(load().a2cid_synchronize(self._h))
+
+    def check_device_span(self, address, nbytes):
+        """Raises A2cidError unless [address, address + nbytes) is device memory the kernels may touch."""
+        _check(load().a2cid_check_device_span(self._h, C.c_void_p(int(address)), int(nbytes)))
 
     def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=1):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))

@@ -41,6 +41,11 @@ struct TimedLaunch {
     hipEvent_t start, stop;
 };
 
+struct DevSpan {
+    uintptr_t lo, hi;                   // one device allocation, [lo, hi)
+};
+constexpr size_t kKnownSpans = 64;
+
 }  // namespace
 
 struct a2cid_ctx {
@@ -49,6 +54,8 @@ struct a2cid_ctx {
     int64_t d = 0, ld = 0;
     float *x = nullptr, *xt = nullptr;
     hipStream_t stream = nullptr;
+    int device = -1;                    // the GPU that was current at creation and owns x, xt and the scratch
+    std::vector<DevSpan> known;         // device allocations that passed check_device_span (a cache)
     double eta = 0, alpha = 0, alpha_t = 0;
     std::vector<double> t;
     Plan plan;
@@ -80,6 +87,51 @@ struct a2cid_ctx {
 };
 
 namespace {
+
+// Every call that touches the GPU must run with the context's device current: the scratch lives there and a
+// launch on another device would hand its kernels pointers that device cannot reach.
+int enter(const a2cid_ctx *c) {
+    int dev = -1;
+    A2CID_HIP(hipGetDevice(&dev));
+    if (dev != c->device)
+        return fail(A2CID_EINVAL, "the context belongs to HIP device %d but device %d is current", c->device, dev);
+    return A2CID_OK;
+}
+
+// Turns a pointer that the kernels would fault on into an error: [p, p + bytes) has to be device (or managed)
+// memory of the context's GPU and must not run past the end of its allocation.  Allocations that passed are
+// remembered, so the runtime is asked once per allocation, not once per operation.  The check sees allocations,
+// not tensors: a span that stays inside a larger allocation (a caching allocator's segment) passes.
+int check_device_span(a2cid_ctx *c, const void *p, size_t bytes, const char *what) {
+    const uintptr_t lo = (uintptr_t)p, hi = lo + bytes;
+    if (hi < lo) return fail(A2CID_EINVAL, "%s: %zu bytes from %p wrap the address space", what, bytes, p);
+    for (const DevSpan &k : c->known)
+        if (k.lo <= lo && hi <= k.hi) return A2CID_OK;
+    hipPointerAttribute_t attr;
+    std::memset(&attr, 0, sizeof(attr));
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(A2CID_EINVAL, "%s: %p is not memory known to the HIP runtime (a host pointer?)", what, p);
+    }
+    if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged)
+        return fail(A2CID_EINVAL, "%s: %p is not device memory", what, p);
+    if (attr.type == hipMemoryTypeDevice && attr.device != c->device)
+        return fail(A2CID_EINVAL, "%s: %p belongs to HIP device %d, the context to device %d", what, p, attr.device,
+                    c->device);
+    hipDeviceptr_t base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, (hipDeviceptr_t)p) != hipSuccess) {
+        (void)hipGetLastError();
+        return A2CID_OK;                // the runtime knows the pointer but not its extent: nothing more to check
+    }
+    const uintptr_t blo = (uintptr_t)base, bhi = blo + size;
+    if (lo < blo || hi > bhi)
+        return fail(A2CID_EINVAL, "%s: %zu bytes from %p run past the end of the allocation (%zu bytes at %p)", what,
+                    bytes, p, size, (void *)base);
+    if (c->known.size() >= kKnownSpans) c->known.clear();
+    c->known.push_back({blo, bhi});
+    return A2CID_OK;
+}
 
 int acquire_slot(a2cid_ctx *c, Slot **out) {
     Slot &s = c->slots[c->next_slot];
@@ -266,6 +318,10 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     if (!(eta >= 0.0) || !std::isfinite(eta) || !std::isfinite(alpha) || !std::isfinite(alpha_tilde))
         return fail(A2CID_EINVAL, "eta must be finite and >= 0, alpha and alpha_tilde finite");
     c->n = n; c->d = d; c->ld = buf->ld;
+    A2CID_HIP(hipGetDevice(&c->device));
+    const size_t state_bytes = sizeof(float) * ((size_t)(n - 1) * (size_t)buf->ld + (size_t)d);
+    if (int rc = check_device_span(c, buf->x, state_bytes, "x")) return rc;
+    if (int rc = check_device_span(c, buf->xt, state_bytes, "xt")) return rc;
     c->x = buf->x; c->xt = buf->xt;
     c->stream = (hipStream_t)buf->hip_stream;
     c->eta = eta; c->alpha = alpha; c->alpha_t = alpha_tilde;
@@ -315,7 +371,17 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 }
 
 static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
+    if (int rc = enter(c)) return rc;
     if (int rc = plan_batch(c->g, c->eta, c->t.data(), batch, c->plan, c->scratch)) return rc;
+    // gradient inputs the kernels will read: d floats each, inside one device allocation
+    for (int64_t k = 0; k < batch->n_ops; ++k) {
+        const a2cid_op &op = batch->ops[k];
+        if (op.kind != A2CID_KIND_GRADIENT) continue;
+        if (op.xi)
+            if (int rc = check_device_span(c, op.xi, sizeof(float) * (size_t)c->d, "xi of a gradient event")) return rc;
+        if (op.c && op.gscale != 0.f)
+            if (int rc = check_device_span(c, op.c, sizeof(float) * (size_t)c->d, "c of a gradient event")) return rc;
+    }
     int32_t l = 0;
     while (l < batch->n_levels) {
         // take as many whole levels as fit into one staging buffer
@@ -436,6 +502,7 @@ int a2cid_flush(a2cid_ctx *c, double t_now) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    if (int rc = enter(c)) return rc;
     std::vector<float> b(c->n);
     for (int32_t i = 0; i < c->n; ++i) {
         if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
@@ -450,6 +517,7 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     clear_error();
     if (!c || !out || !out->sum_x || !out->sum_xt) return fail(A2CID_EINVAL, "context / out is NULL");
     if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    if (int rc = enter(c)) return rc;
     for (int32_t i = 0; i < c->n; ++i)
         if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
     // b_host is reused by every call and an earlier asynchronous upload (a2cid_average) may still be reading it
@@ -495,6 +563,7 @@ int a2cid_average(a2cid_ctx *c, double t_now) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    if (int rc = enter(c)) return rc;
     for (int32_t i = 0; i < c->n; ++i)
         if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
     // b_host may still be read by an earlier asynchronous upload: wait for the stream first
@@ -580,6 +649,12 @@ int a2cid_set_stats_tuning(a2cid_ctx *c, int32_t pieces, int32_t rows, int32_t b
     if (blocks < 1 || blocks > kStatsBlocksMax) return fail(A2CID_EINVAL, "blocks must be in [1, %d]", kStatsBlocksMax);
     c->stats_v = pieces; c->stats_r = rows; c->stats_blocks = blocks; c->stats_nt = nontemporal ? 1 : 0;
     return A2CID_OK;
+}
+
+int a2cid_check_device_span(a2cid_ctx *c, const void *p, int64_t bytes) {
+    clear_error();
+    if (!c || !p || bytes < 1) return fail(A2CID_EINVAL, "context / pointer NULL or bytes < 1");
+    return check_device_span(c, p, (size_t)bytes, "span");
 }
 
 int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream) {

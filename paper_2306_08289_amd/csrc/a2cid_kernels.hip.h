@@ -1,8 +1,10 @@
 // Device code of the A2CiD2 engine for gfx950 (wave64).  Included only by a2cid_engine.hip.
 //
-// All three kernels are HBM streams (about 0.5 flop per byte), so there is no MFMA and no LDS
-// on the data path: each lane moves 128-bit pieces straight between global memory and
-// registers, and the design goal is simply "enough independent 16-byte loads in flight per CU".
+// The event kernels (level, walk) and the observables kernel are HBM streams (about 0.5 flop per
+// byte), so there is no MFMA and no LDS on their data path: each lane moves 128-bit pieces straight
+// between global memory and registers, and the design goal is simply "enough independent 16-byte
+// loads in flight per CU".  The opt-in resident kernel is the exception: it keeps a column tile of
+// every touched row in LDS for the length of a batch.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -222,8 +224,6 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
                                                    int64_t ld, int64_t d, const DevOp *__restrict__ ops,
                                                    int32_t n_ops, float alpha, float alpha_t) {
     const int64_t tile = blockIdx.x;
-    // the record of operation k + 1 is requested before operation k's rows are, so that its scalar-load
-    // latency hides behind the vector loads instead of preceding them
     for (int32_t k = 0; k < n_ops; ++k) {
         const DevOp op = ops[k];
         apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);

@@ -153,6 +153,58 @@ def test_rejected_batches_leave_state_and_times_untouched():
     w.close()
 
 
+def test_pointers_the_kernels_would_fault_on_are_rejected_on_the_host():
+    """Host-side checks only: every bad case must come back as an error before anything is launched.  The batch
+    with a bad pointer is submitted only after the span check itself has been seen to classify that pointer."""
+    from paper_2306_08289_amd import A2cidError, binding
+    cfg = wl.scaled(wl.CONFIGS["C2"], d=5000, events=200)
+    w = wl.Workload(cfg, batch_events=100)
+    eng = w.engine
+    row_bytes = 4 * cfg.d
+    eng.check_device_span(w.x.data_ptr(), w.x.numel() * 4)
+    eng.check_device_span(w.c.data_ptr() + 3 * w.ld * 4, row_bytes)
+    host = np.zeros(cfg.d + 8, np.float32)
+    host_ptr = (host.ctypes.data + 15) & ~15
+    pinned = torch.zeros(cfg.d, dtype=torch.float32).pin_memory()
+    for what, ptr, nbytes in [("pageable host memory", host_ptr, row_bytes),
+                              ("pinned host memory", pinned.data_ptr(), row_bytes),
+                              ("past the end of the allocation", w.x.data_ptr(), 1 << 44),
+                              ("null", 0, row_bytes)]:
+        _say(f"span check: {what}")
+        with pytest.raises(A2cidError) as e:
+            eng.check_device_span(ptr, nbytes)
+        assert e.value.code == binding.EINVAL, str(e.value)
+    w.run(100)
+    x0, xt0 = w.columns(np.arange(cfg.d))
+    t0 = eng.times()
+    good = w.next_batch(100)
+    grad = np.nonzero(good.ops["kind"] == 0)[0]
+    for field in ("xi", "c"):
+        _say(f"batch with a host pointer as {field}")
+        bad = type(good)(good.ops.copy(), good.level_off.copy(), good.t_sync)
+        bad.ops[field][grad[-1]] = host_ptr
+        with pytest.raises(A2cidError) as e:
+            eng.apply_events(bad)
+        assert e.value.code == binding.EINVAL, str(e.value)
+    x1, xt1 = w.columns(np.arange(cfg.d))
+    assert np.array_equal(x0, x1) and np.array_equal(xt0, xt1) and np.array_equal(t0, eng.times())
+    # creation applies the same check to the state buffers
+    _say("create with a host buffer as x")
+    import ctypes
+    hx = torch.zeros((cfg.n, w.ld), dtype=torch.float32).pin_memory()
+    graph = binding._GraphArg(w.u, w.v, w.edge_rate)
+    buf = binding.a2cid_buffers(hx.data_ptr(), w.xt.data_ptr(), w.ld, eng.stream.cuda_stream)
+    handle = ctypes.c_void_p()
+    rc = binding.load().a2cid_create(ctypes.byref(handle), cfg.n, cfg.d, ctypes.byref(graph.struct), w.eta, w.alpha,
+                                     w.alpha_tilde, ctypes.byref(buf))
+    assert rc == binding.EINVAL and not handle.value, binding.load().a2cid_last_error()
+    eng.apply_events(good)
+    st, _ = pu.oracle_run(cfg, np.arange(cfg.d), 200)
+    gx, gxt = w.columns(np.arange(cfg.d))
+    assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
+    w.close()
+
+
 def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit():
     # every operation performs the same arithmetic whatever batch it lands in and whichever kernel runs it
     cfg = wl.scaled(wl.CONFIGS["C5"], d=70001, events=900)
