@@ -3,14 +3,16 @@
 
 A step is one pass of the whole path over one batch of synthetic events: the scheduler draws
 and level-packs `--batch` events, the planner validates them and computes the mixing
-coefficients, the level kernels apply them to x and xt, and the observables kernel reads the
-state once.  Inputs (state, c_i, gradient-noise pool) are resident in HBM before timing starts;
+coefficients and the chain order, the event kernel applies them to x and xt, and the observables
+kernel reads the state once.  Inputs (state, c_i, gradient-noise pool) are resident in HBM before timing starts;
 generating the per-event noise stands in for the gradient computation and is outside the path.
 
-Prints ONE JSON line: throughput in algorithmic GB/s (bytes the method must move: 32 d per gossip
-event, 16 d + 4 d per gradient input per gradient event, 8 n d per observables call), events/s,
-the roofline of the dominant kernel measured with HIP events on its own stream, and the CPU oracle
-timed on a bounded sample on this machine's host cores.
+Prints ONE JSON line: throughput in GB/s of the bytes the kernels move (per gossip event 32 d, less
+8 d for each row the chain kernel carries in registers from or to a neighbouring operation; per
+gradient event 16 d + 4 d per gradient input, less the same; 8 n d per observables call), the same
+work priced at one full pass per event (one_pass_equivalent_GBs), events/s, the roofline of the
+dominant kernel measured with HIP events on its own stream, and the CPU oracle timed on a bounded
+sample on this machine's host cores.
 """
 import argparse
 import json
@@ -27,6 +29,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
 # size: profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the workload, batch size and kernel it names.
 MEASURED_TRAFFIC = {("C4", 1024, "walk_kernel"): 7.9222e11}
+
+MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -69,12 +73,13 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     return {"value": gbs, "unit": "GB/s", "cores": 1, "kind": "oracle",
             "events_per_s_at_full_d": ev_s_full_d,
             "sample": f"first {m} events of {cfg.name} + one observables pass on a {d_slice}-column slice of "
-                      f"all {cfg.n} workers, fp64 state, repeated {reps}x ({el:.1f} s); bytes counted with the "
-                      f"same fp32 algorithmic formula as the GPU figure; host has {os.cpu_count()} cores"}
+                      f"all {cfg.n} workers, fp64 state, repeated {reps}x ({el:.1f} s); bytes counted as one fp32 "
+                      f"pass per event (compare with one_pass_equivalent_GBs, or events_per_s_at_full_d with "
+                      f"events_per_s); host has {os.cpu_count()} cores"}
 
 
 def short_run(name, batch, steps=6, warmup=2):
-    """A few steps of one configuration with the default (walk) kernel, then with the LDS-resident one."""
+    """A few steps of one configuration with the walk, chain (default) and LDS-resident kernels."""
     import torch
     from paper_2306_08289_amd import workloads as wl
     cfg = wl.CONFIGS[name]
@@ -83,7 +88,7 @@ def short_run(name, batch, steps=6, warmup=2):
     res = {"workload": name, "n": cfg.n, "topology": cfg.topology, "d": cfg.d, "events_per_step": batch,
            "state_bytes": 8.0 * cfg.n * cfg.d,
            "note": "state fits the 256 MB last-level cache: not an HBM figure" if 8.0 * cfg.n * cfg.d < 3e8 else ""}
-    for mode, key in ((1, "walk"), (2, "resident")):
+    for mode, key in ((1, "walk"), (3, "chain"), (2, "resident")):
         w.engine.set_tuning(1, 0, 256, mode)
         for _ in range(warmup):
             w.step(); w.engine.stats(w.t_last)
@@ -97,8 +102,9 @@ def short_run(name, batch, steps=6, warmup=2):
         c = w.engine.counters()
         ev = c["gossip"] + c["gradient"]
         res[key] = {"events_per_s": ev / el, "gossip_events_per_s": c["gossip"] / el,
-                    "algorithmic_GBs": (c["bytes"] + stats_bytes * steps) / el / 1e9,
-                    "frac_of_hbm_peak": (c["bytes"] + stats_bytes * steps) / el / 1e9 / HBM_PEAK_GBS if mode == 1 else None}
+                    "hbm_GBs": (c["moved_bytes"] + stats_bytes * steps) / el / 1e9,
+                    "frac_of_hbm_peak": (c["moved_bytes"] + stats_bytes * steps) / el / 1e9 / HBM_PEAK_GBS,
+                    "one_pass_equivalent_GBs": (c["bytes"] + stats_bytes * steps) / el / 1e9}
     w.close()
     del w
     torch.cuda.empty_cache()
@@ -117,7 +123,8 @@ def main():
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--walk", type=int, default=None,
-                    help="event kernel: 1 = one launch per batch (default), 0 = one per level, 2 = LDS-resident")
+                    help="event kernel: 3 = chain (default), 1 = walk in level order, 0 = one launch per level, "
+                         "2 = LDS-resident")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
@@ -142,7 +149,7 @@ def main():
     w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True, ld_pad=args.ld_pad)
     tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
     if any(v is not None for v in tuning):
-        w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 1))])
+        w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 3))])
     if args.group is not None or args.cols is not None:
         w.engine.set_resident_group(args.group or 8, args.cols or 1)
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
@@ -186,18 +193,23 @@ def main():
         launches, kernel_ms = w.engine.profile_read()
         w.engine.profile(False)
 
-    total_bytes = cnt["bytes"] + stats_bytes * args.steps
+    # bytes: what the launched kernels move by construction (for the chain kernel less than one pass per event,
+    # because a worker shared by consecutive operations stays in registers); one_pass: 32 d per gossip event etc.
+    total_bytes = cnt["moved_bytes"] + stats_bytes * args.steps
+    one_pass_bytes = cnt["bytes"] + stats_bytes * args.steps
     events = cnt["gossip"] + cnt["gradient"]
     value = total_bytes / elapsed / 1e9
     roofline = None
-    kernel_name = {0: "level_kernel", 2: "resident_kernel"}.get(args.walk, "walk_kernel")
+    kernel_name = MODE_NAMES[3 if args.walk is None else args.walk]
     if launches:
-        achieved = cnt["bytes"] / (kernel_ms * 1e-3) / 1e9
+        achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                     "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if not args.d else None,
                     "launches": launches, "avg_launch_ms": kernel_ms / launches,
-                    "alg_bytes_per_launch": cnt["bytes"] / launches}
+                    "alg_bytes_per_launch": cnt["moved_bytes"] / launches,
+                    "one_pass_bytes_per_launch": cnt["bytes"] / launches,
+                    "one_pass_equivalent_GBs": cnt["bytes"] / (kernel_ms * 1e-3) / 1e9}
     out = {
         "metric": "achieved HBM GB/s and gossip events/s, 64 workers \u00d7 25.6M fp32 params"
                   if cfg.n == 64 and cfg.d == 25_600_000 else f"achieved HBM GB/s and gossip events/s, {cfg.name}",
@@ -211,13 +223,14 @@ def main():
         "events_per_s": events / elapsed, "gossip_events_per_s": cnt["gossip"] / elapsed,
         "gradient_events_per_s": cnt["gradient"] / elapsed,
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
+        "one_pass_equivalent_GBs": one_pass_bytes / elapsed / 1e9,
         "copy_ceiling": {"value": copy_gbs, "unit": "GB/s",
                          "what": f"plain device copy of {8.0 * src.numel() / 1e9:.2f} GB (read + write) on this machine"},
         "roofline": roofline,
     }
-    # separate line: the LDS-resident variant moves fewer bytes than the algorithmic count, so its rate is quoted
-    # in events/s and real state bytes, never as a fraction of the HBM roofline
-    if not args.no_resident_leg and args.walk != 2 and cfg.n <= 128:
+    # separate line: the LDS-resident variant is bound by LDS latency and instruction issue, not by HBM, so its
+    # rate is quoted in events/s and bytes moved, never as a fraction of the HBM roofline
+    if not args.no_resident_leg and args.walk != 2 and cfg.n <= 112:
         w.engine.set_tuning(1, 0, 256, 2)
         for _ in range(2):
             step()
@@ -231,15 +244,13 @@ def main():
         r_el = time.perf_counter() - t0
         rc = w.engine.counters()
         r_events = rc["gossip"] + rc["gradient"]
-        grad_inputs = rc["bytes"] - cfg.d * (32.0 * rc["gossip"] + 16.0 * rc["gradient"])
         out["resident_variant"] = {
-            "what": "same steps with the LDS-resident kernel (state read and written once per batch); "
-                    "valid only when gradient inputs do not depend on the evolving state",
+            "what": "same steps with the LDS-resident kernel (state read and written once per batch)",
             "events_per_s": r_events / r_el, "gossip_events_per_s": rc["gossip"] / r_el,
             "ms_per_step": r_el / r_steps * 1e3, "steps": r_steps,
-            "hbm_bytes_per_step_by_construction": (rc["resident_state_bytes"] + grad_inputs) / r_steps + stats_bytes,
-            "algorithmic_bytes_per_step": rc["bytes"] / r_steps + stats_bytes,
-            "speedup_vs_one_pass_per_event": (r_events / r_el) / (events / elapsed)}
+            "hbm_bytes_per_step_by_construction": rc["moved_bytes"] / r_steps + stats_bytes,
+            "one_pass_bytes_per_step": rc["bytes"] / r_steps + stats_bytes,
+            "speedup_vs_headline": (r_events / r_el) / (events / elapsed)}
     w.close()
     del w
     torch.cuda.empty_cache()

@@ -206,6 +206,17 @@ void a2cid_destroy(a2cid_ctx *ctx);
 int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
                      const a2cid_event_batch *batch, a2cid_coef *coef);
 
+/* The order in which the chain kernel (a2cid_set_tuning, mode 3) applies a batch, as a pure host
+ * function.  Eq. (1) lets operations on disjoint workers commute, so any order that keeps every
+ * worker's own operations in sequence yields the same state bit for bit; the library picks one in
+ * which an operation shares a worker with its predecessor as often as it can, and keeps that
+ * worker's columns in registers from the one to the other.  order[k] (n_ops entries) is the index
+ * into batch->ops of the k-th operation applied; shared[k] is the worker carried from position k
+ * to position k + 1, or -1 (shared[n_ops - 1] is always -1).  Either output may be NULL.  Only
+ * kinds and worker indices of the operations are read (the level table is not).  A batch of more
+ * than 16384 operations is ordered by a2cid_apply_events in pieces of whole levels. */
+int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t *order, int32_t *shared);
+
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 
 /* Independent Poisson clocks (Assumption 3.1): one per worker (gradient events, rate
@@ -253,14 +264,22 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* ---- diagnostics and measurement ------------------------------------------------------- */
 
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
- * nontemporal != 0 selects non-temporal loads and stores, threads = workgroup size (64 ... 1024,
- * a power of two), mode = 0: one launch per level; 1: one launch per batch in which every
- * workgroup walks all operations for its own columns, each operation reading and writing its rows
- * in device memory (default); 2: as 1, but the workgroup keeps its columns of all touched rows
- * in LDS for the whole batch, so the state is read and written once per batch instead of once per
- * event (at most 112 workers; requires every gradient input of a batch to be final when the batch
- * is submitted).  Default: 1, 0, 256, 1 (tiles shrink automatically for short rows).  All modes
- * compute the same operations in the same per-worker order. */
+ * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
+ * workgroup size (64 ... 1024, a power of two), mode =
+ *   0: one launch per level;
+ *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
+ *      own columns, each operation reading and writing its rows in device memory (32 d bytes per
+ *      gossip event);
+ *   3: as 1, but in the order of a2cid_plan_chain, a worker shared by consecutive operations
+ *      staying in registers (16 d bytes for a gossip event that inherits a worker and hands one on;
+ *      default);
+ *   2: as 1, but the workgroup keeps its columns of all touched rows in LDS for the whole batch, so
+ *      the state is read and written once per batch instead of once per event (at most 112
+ *      workers).
+ * Default: 1, 0, 256, 3 (tiles shrink automatically for short rows).  All modes compute the same
+ * operations in the same per-worker order and give the same state bit for bit.  In every mode the
+ * gradient inputs of a batch must hold their final values, in stream order, before
+ * a2cid_apply_events is called. */
 int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t mode);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
@@ -289,12 +308,13 @@ int a2cid_check_device_span(a2cid_ctx *ctx, const void *p, int64_t bytes);
 int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream);
 
 /* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
- * the algorithmic byte count (per event: 32 d for gossip; 16 d for a gradient event plus 4 d for
- * each of xi and c that it reads; 16 d per worker mixed by a2cid_flush), and, for mode 2, the state
- * bytes its launches really move (16 d per touched row and launch).  Any output pointer may be
- * NULL. */
+ * the byte count of one pass per event (32 d for a gossip event; 16 d for a gradient event plus
+ * 4 d for each of xi and c that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
+ * a2cid_average), and the bytes the launched kernels move by construction: the same for modes 0
+ * and 1; for mode 3, 8 d less for every row carried in and for every row kept; for mode 2, 16 d
+ * per touched row and launch plus the gradient inputs.  Any output pointer may be NULL. */
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
-                   double *algorithmic_bytes, double *resident_state_bytes, int32_t reset);
+                   double *one_pass_bytes, double *moved_bytes, int32_t reset);
 
 /* While enabled, every event-kernel launch is bracketed by a pair of HIP events on the
  * context's stream.  a2cid_profile_read waits for the stream, returns the number of launches

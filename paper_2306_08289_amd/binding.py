@@ -73,6 +73,7 @@ SIGNATURES = {
     "a2cid_set_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
     "a2cid_synchronize": (C.c_int, [C.c_void_p]),
     "a2cid_destroy": (None, [C.c_void_p]),
+    "a2cid_plan_chain": (C.c_int, [C.c_int32, _P(a2cid_event_batch), _P(C.c_int32), _P(C.c_int32)]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
     "a2cid_sched_create": (C.c_int, [_P(C.c_void_p), C.c_int32, _P(a2cid_graph), _P(C.c_double), C.c_uint64]),
@@ -177,6 +178,18 @@ def a2cid_plan_batch(n, u, v, rate, eta, t, batch):
     bs = batch.struct()
     _check(load().a2cid_plan_batch(n, C.byref(g.struct), float(eta), _dptr(t), C.byref(bs), coef.ctypes.data))
     return t, coef
+
+
+def a2cid_plan_chain(n, batch):
+    """Returns (order, shared): the order in which the chain kernel applies the batch and the worker carried
+    from each position to the next (-1: none)."""
+    m = len(batch.ops)
+    order = np.zeros(m, np.int32)
+    shared = np.zeros(m, np.int32)
+    bs = batch.struct()
+    _check(load().a2cid_plan_chain(int(n), C.byref(bs), order.ctypes.data_as(_P(C.c_int32)),
+                                   shared.ctypes.data_as(_P(C.c_int32))))
+    return order, shared
 
 
 class Scheduler:
@@ -293,7 +306,7 @@ class Engine:
         """Raises A2cidError unless [address, address + nbytes) is device memory the kernels may touch."""
         _check(load().a2cid_check_device_span(self._h, C.c_void_p(int(address)), int(nbytes)))
 
-    def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=1):
+    def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=3):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))
 
     def set_resident_group(self, group=8, cols=1):
@@ -308,7 +321,7 @@ class Engine:
         _check(load().a2cid_counters(self._h, C.byref(g), C.byref(gr), C.byref(la), C.byref(by), C.byref(rb),
                                      int(reset)))
         return {"gossip": g.value, "gradient": gr.value, "launches": la.value, "bytes": by.value,
-                "resident_state_bytes": rb.value}
+                "moved_bytes": rb.value}
 
     def profile(self, enable):
         _check(load().a2cid_profile(self._h, int(bool(enable))))

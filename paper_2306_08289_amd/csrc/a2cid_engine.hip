@@ -66,7 +66,7 @@ struct a2cid_ctx {
     int unroll = 1;
     int nontemporal = 0;
     int threads = 256;
-    int walk = 1;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident
+    int walk = 3;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident; 3: chain
     int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
     float *zero_dev = nullptr;          // one zero float: stands in for absent gradient inputs
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
@@ -79,7 +79,8 @@ struct a2cid_ctx {
     // counters since creation (or the last a2cid_counters_reset)
     int64_t n_gossip = 0, n_grad = 0, n_launch = 0;
     double alg_bytes = 0.0;
-    double resident_bytes = 0.0;        // state bytes actually moved by resident launches (16 d per touched row)
+    double moved_bytes = 0.0;           // bytes the launched kernels move by construction (<= alg_bytes)
+    ChainPlan chain;
     // optional per-launch timing
     bool profiling = false;
     std::vector<TimedLaunch> timed;
@@ -154,13 +155,18 @@ int get_event(a2cid_ctx *c, hipEvent_t *e) {
     return A2CID_OK;
 }
 
+enum LaunchKind { kLaunchLevel = 0, kLaunchWalk = 1, kLaunchChain = 3 };
+
 template <int U, bool NT, int TPB>
-void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
+void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
     const int64_t n4 = c->d >> 2;
     const int64_t per_block = (int64_t)U * TPB;
     int64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;   // the scalar tail lives in tile 0
-    if (walk) {
+    if (walk == kLaunchChain) {
+        hipLaunchKernelGGL((chain_kernel<U, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
+                           c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
+    } else if (walk == kLaunchWalk) {
         hipLaunchKernelGGL((walk_kernel<U, NT, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
                            c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
     } else {
@@ -170,7 +176,7 @@ void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
 }
 
 template <int U, bool NT>
-void launch_u(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
+void launch_u(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
     int threads = c->threads;
     while (threads > 64 && (c->d >> 2) / ((int64_t)U * threads) < 2048) threads >>= 1;
     switch (threads) {
@@ -183,14 +189,14 @@ void launch_u(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
 }
 
 // Enqueues n_ops operations: as one level (they must touch disjoint rows) or as a walk in order.
-int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
+int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
     TimedLaunch tl{};
     if (c->profiling) {
         if (int rc = get_event(c, &tl.start)) return rc;
         if (int rc = get_event(c, &tl.stop)) return rc;
         A2CID_HIP(hipEventRecord(tl.start, c->stream));
     }
-    const bool nt = c->nontemporal != 0;
+    const bool nt = c->nontemporal != 0 && walk != kLaunchChain;   // the chain kernel has one access policy
     // short rows: shrink the tile so that the grid still has a few thousand workgroups
     int unroll = c->unroll;
     while (unroll > 1 && (c->d >> 2) / ((int64_t)unroll * c->threads) < 2048) unroll >>= 1;
@@ -206,6 +212,34 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, bool walk) {
     }
     ++c->n_launch;
     return A2CID_OK;
+}
+
+
+// Marks the carried workers of a chain-ordered operation table: neighbours that share the planned worker keep
+// its columns in registers (kFlagKeepI/J on the first, kFlagCarryIn on the second, which is turned so that the
+// shared worker is its row_i).  Returns the bytes per column that the launch moves.
+double mark_carries(DevOp *ops, int64_t count, const std::vector<int32_t> &shared) {
+    for (int64_t k = 0; k + 1 < count; ++k) {
+        if (shared[k] < 0) continue;
+        DevOp &p = ops[k], &q = ops[k + 1];
+        p.flags |= shared[k] == p.row_i ? kFlagKeepI : kFlagKeepJ;
+        if (q.row_i != shared[k]) {      // only a gossip operation can have the shared worker as row_j
+            std::swap(q.row_i, q.row_j);
+            std::swap(q.b_i, q.b_j);
+            std::swap(q.bp_i, q.bp_j);
+        }
+        q.flags |= kFlagCarryIn;
+    }
+    double per_column = 0.0;
+    for (int64_t k = 0; k < count; ++k) {
+        const DevOp &o = ops[k];
+        const bool kept = (o.flags & (kFlagKeepI | kFlagKeepJ)) != 0;
+        per_column += (o.flags & kFlagCarryIn) ? 0.0 : 8.0;                  // row_i in
+        per_column += kept && o.kind != kOpGossip ? 0.0 : 8.0;               // one row out unless the only row is kept
+        if (o.kind == kOpGossip) per_column += 8.0 + (kept ? 0.0 : 8.0);     // row_j in, second row out unless one is kept
+        if (o.kind == kOpGradient) per_column += (o.xi ? 4.0 : 0.0) + ((o.c && o.gscale != 0.f) ? 4.0 : 0.0);
+    }
+    return per_column;
 }
 
 constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row, column-per-lane and workgroup, plus staging
@@ -269,10 +303,11 @@ int enqueue_mix_all(a2cid_ctx *c, const std::vector<float> &b) {
         }
         if (count == 0) continue;
         A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
-        if (int rc = launch_ops(c, s->dev, count, false)) return rc;
+        if (int rc = launch_ops(c, s->dev, count, kLaunchLevel)) return rc;
         A2CID_HIP(hipEventRecord(s->done, c->stream));
         s->in_flight = true;
         c->alg_bytes += 16.0 * (double)c->d * count;
+        c->moved_bytes += 16.0 * (double)c->d * count;
     }
     return A2CID_OK;
 }
@@ -398,9 +433,11 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
             Slot *s;
             if (int rc = acquire_slot(c, &s)) return rc;
             const int64_t first = batch->level_off[l];
+            if (c->walk == 3) plan_chain(c->n, batch->ops + first, count, c->chain);
             for (int64_t k = 0; k < count; ++k) {
-                const a2cid_op &op = batch->ops[first + k];
-                const a2cid_coef &cf = c->plan.coef[first + k];
+                const int64_t src = first + (c->walk == 3 ? c->chain.order[k] : k);
+                const a2cid_op &op = batch->ops[src];
+                const a2cid_coef &cf = c->plan.coef[src];
                 DevOp &o = s->host[k];
                 o.kind = op.kind == A2CID_KIND_GOSSIP ? kOpGossip : kOpGradient;
                 o.row_i = op.i;
@@ -416,7 +453,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
             if (c->walk == 2) {
                 // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
                 // cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring)
-                int32_t n_rows = 0, n_grad = 0;
+                int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0;
                 const uintptr_t zero = (uintptr_t)c->zero_dev | 1u;
                 c->slot_of.assign(c->n, -1);
                 for (int32_t ll = l; ll < l_end; ++ll) {
@@ -446,6 +483,8 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                             r.gidx = (uint32_t)n_grad;
                             s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
                             s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
+                            n_xi += o.xi != nullptr;
+                            n_c += o.c && o.gscale != 0.f;
                             ++n_grad;
                         }
                     }
@@ -458,21 +497,33 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 if (n_grad > 0)
                     A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad,
                                              hipMemcpyHostToDevice, c->stream));
-                c->resident_bytes += (double)c->d * 16.0 * n_rows;
+                c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c));
                 if (int rc = launch_resident(c, s, (int32_t)count, n_grad, n_rows)) return rc;
                 A2CID_HIP(hipEventRecord(s->done, c->stream));
                 s->in_flight = true;
                 l = l_end;
                 continue;
             }
+            double moved = 0.0;             // bytes per column that this chunk's launches move
+            if (c->walk == 3) {
+                moved = mark_carries(s->host, count, c->chain.shared);
+            } else {
+                for (int64_t k = 0; k < count; ++k) {
+                    const DevOp &o = s->host[k];
+                    moved += o.kind == kOpGossip ? 32.0 : 16.0 + (o.xi ? 4.0 : 0.0) + ((o.c && o.gscale != 0.f) ? 4.0 : 0.0);
+                }
+            }
+            c->moved_bytes += moved * (double)c->d;
             A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
-            if (c->walk == 1) {
-                if (int rc = launch_ops(c, s->dev, (int32_t)count, true)) return rc;
+            if (c->walk == 3) {
+                if (int rc = launch_ops(c, s->dev, (int32_t)count, kLaunchChain)) return rc;
+            } else if (c->walk == 1) {
+                if (int rc = launch_ops(c, s->dev, (int32_t)count, kLaunchWalk)) return rc;
             } else {
                 for (int32_t ll = l; ll < l_end; ++ll) {
                     const int64_t lo = batch->level_off[ll] - first, sz = batch->level_off[ll + 1] - batch->level_off[ll];
                     if (sz == 0) continue;
-                    if (int rc = launch_ops(c, s->dev + lo, (int32_t)sz, false)) return rc;
+                    if (int rc = launch_ops(c, s->dev + lo, (int32_t)sz, kLaunchLevel)) return rc;
                 }
             }
             A2CID_HIP(hipEventRecord(s->done, c->stream));
@@ -576,6 +627,7 @@ int a2cid_average(a2cid_ctx *c, double t_now) {
     A2CID_HIP(hipGetLastError());
     std::fill(c->t.begin(), c->t.end(), t_now);
     c->alg_bytes += 16.0 * (double)c->n * (double)c->d;
+    c->moved_bytes += 16.0 * (double)c->n * (double)c->d;
     return A2CID_OK;
 }
 
@@ -608,7 +660,7 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     if (unroll != 1 && unroll != 2 && unroll != 4) return fail(A2CID_EINVAL, "unroll must be 1, 2 or 4");
     if (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024)
         return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
-    if (mode < 0 || mode > 2) return fail(A2CID_EINVAL, "mode must be 0 (levels), 1 (walk) or 2 (resident)");
+    if (mode < 0 || mode > 3) return fail(A2CID_EINVAL, "mode must be 0 (levels), 1 (walk), 2 (resident) or 3 (chain)");
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
     c->unroll = unroll;
@@ -669,15 +721,15 @@ int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream
 }
 
 int a2cid_counters(a2cid_ctx *c, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
-                   double *algorithmic_bytes, double *resident_state_bytes, int32_t reset) {
+                   double *one_pass_bytes, double *moved_bytes, int32_t reset) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (n_gossip) *n_gossip = c->n_gossip;
     if (n_gradient) *n_gradient = c->n_grad;
     if (n_launches) *n_launches = c->n_launch;
-    if (algorithmic_bytes) *algorithmic_bytes = c->alg_bytes;
-    if (resident_state_bytes) *resident_state_bytes = c->resident_bytes;
-    if (reset) { c->n_gossip = c->n_grad = c->n_launch = 0; c->alg_bytes = c->resident_bytes = 0.0; }
+    if (one_pass_bytes) *one_pass_bytes = c->alg_bytes;
+    if (moved_bytes) *moved_bytes = c->moved_bytes;
+    if (reset) { c->n_gossip = c->n_grad = c->n_launch = 0; c->alg_bytes = c->moved_bytes = 0.0; }
     return A2CID_OK;
 }
 

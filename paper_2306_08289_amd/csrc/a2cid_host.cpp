@@ -4,6 +4,7 @@
 // (Assumption 3.1) with its level packing.  No GPU code in this file.
 #include <algorithm>
 #include <cmath>
+#include <cstdint>
 #include <cstddef>
 #include <cstdio>
 #include <cstring>
@@ -422,6 +423,73 @@ struct a2cid_sched {
     }
 };
 
+namespace a2cid {
+
+static inline int op_endpoints(const a2cid_op &o, int32_t (&w)[2]) {
+    w[0] = o.i;
+    w[1] = o.j;
+    return o.kind == A2CID_KIND_GOSSIP ? 2 : 1;
+}
+
+void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &s) {
+    s.order.resize((size_t)count);
+    s.shared.assign((size_t)count, -1);
+    s.next_op.assign(2 * (size_t)count, -1);
+    s.waiting.assign((size_t)count, 0);
+    s.emitted.assign((size_t)count, 0);
+    s.head.assign(n, -1);
+    s.last.assign(n, -1);
+    s.recent.clear();
+    int32_t w[2];
+    for (int64_t k = 0; k < count; ++k) {
+        const int ne = op_endpoints(ops[k], w);
+        for (int e = 0; e < ne; ++e) {
+            const int32_t p = s.last[w[e]];
+            if (p >= 0) {
+                s.next_op[2 * (size_t)p + (ops[p].i == w[e] ? 0 : 1)] = (int32_t)k;
+                ++s.waiting[k];
+            } else {
+                s.head[w[e]] = (int32_t)k;
+            }
+            s.last[w[e]] = (int32_t)k;
+        }
+    }
+    int64_t scan = 0;
+    for (int64_t out = 0; out < count; ++out) {
+        int32_t pick = -1;
+        for (size_t r = 0; r < s.recent.size() && pick < 0; ++r) {
+            const int32_t k = s.head[s.recent[r]];
+            if (k >= 0 && s.waiting[k] == 0) pick = k;
+        }
+        if (pick < 0) {
+            // the earliest operation not yet emitted: everything it waits for has a smaller index, so it is free
+            while (s.emitted[scan]) ++scan;
+            pick = (int32_t)scan;
+        }
+        s.order[out] = pick;
+        s.emitted[pick] = 1;
+        const int ne = op_endpoints(ops[pick], w);
+        for (int e = 0; e < ne; ++e) {
+            const int32_t nx = s.next_op[2 * (size_t)pick + e];
+            s.head[w[e]] = nx;
+            if (nx >= 0) --s.waiting[nx];
+            auto it = std::find(s.recent.begin(), s.recent.end(), w[e]);
+            if (it != s.recent.end()) s.recent.erase(it);
+            s.recent.insert(s.recent.begin(), w[e]);
+        }
+        if (s.recent.size() > kChainRecent) s.recent.resize(kChainRecent);
+    }
+    for (int64_t k = 0; k + 1 < count; ++k) {
+        int32_t pw[2], qw[2];
+        const int np = op_endpoints(ops[s.order[k]], pw), nq = op_endpoints(ops[s.order[k + 1]], qw);
+        for (int e = 0; e < np && s.shared[k] < 0; ++e)
+            for (int f = 0; f < nq; ++f)
+                if (pw[e] == qw[f]) { s.shared[k] = pw[e]; break; }
+    }
+}
+
+}  // namespace a2cid
+
 extern "C" {
 
 const char *a2cid_last_error(void) { return g_error; }
@@ -482,6 +550,28 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
         if (int rc = plan_batch(g, eta, t, batch, plan, scratch)) return rc;
         if (coef && batch->n_ops > 0) std::memcpy(coef, plan.coef.data(), sizeof(a2cid_coef) * (size_t)batch->n_ops);
         std::copy(plan.t_after.begin(), plan.t_after.end(), t);
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
+int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t *order, int32_t *shared) {
+    clear_error();
+    if (n < 1 || n > A2CID_MAX_WORKERS) return fail(A2CID_EINVAL, "n = %d out of range", n);
+    if (!batch || batch->n_ops < 0 || (batch->n_ops > 0 && !batch->ops)) return fail(A2CID_EINVAL, "batch is NULL or malformed");
+    if (batch->n_ops > INT32_MAX) return fail(A2CID_EINVAL, "too many operations");
+    for (int64_t k = 0; k < batch->n_ops; ++k) {
+        const a2cid_op &o = batch->ops[k];
+        const bool gossip = o.kind == A2CID_KIND_GOSSIP;
+        if ((!gossip && o.kind != A2CID_KIND_GRADIENT) || o.i < 0 || o.i >= n || (gossip && (o.j < 0 || o.j >= n || o.j == o.i)))
+            return fail(A2CID_EINVAL, "op %lld: bad kind or worker index", (long long)k);
+    }
+    try {
+        ChainPlan plan;
+        plan_chain(n, batch->ops, batch->n_ops, plan);
+        if (order) std::copy(plan.order.begin(), plan.order.end(), order);
+        if (shared) std::copy(plan.shared.begin(), plan.shared.end(), shared);
     } catch (const std::bad_alloc &) {
         return fail(A2CID_ENOMEM, "out of host memory");
     }

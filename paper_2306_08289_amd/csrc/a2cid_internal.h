@@ -48,4 +48,26 @@ struct PlanScratch {
 int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
                Plan &plan, PlanScratch &scratch);
 
+// The order in which the chain kernel applies the operations of one launch, and which worker stays in
+// registers between neighbours of that order.  Any linear extension of the per-worker orders gives the same
+// result bit for bit (operations on disjoint rows commute exactly); this one is built greedily so that an
+// operation shares a worker with its predecessor as often as possible: the next operation is the pending
+// operation of the most recently used worker whose other endpoint is free too, and when none of the
+// kChainRecent last used workers has one, the earliest operation not yet emitted (always free when the
+// input is sorted by level).
+struct ChainPlan {
+    std::vector<int32_t> order;         // order[k]: index of the k-th operation applied
+    std::vector<int32_t> shared;        // shared[k]: worker common to positions k and k + 1 that is carried, or -1
+    // work arrays
+    std::vector<int32_t> next_op;       // [2 k + e]: the next operation of operation k's endpoint e, or -1
+    std::vector<int32_t> waiting;       // endpoints of operation k whose previous operation has not been emitted
+    std::vector<int32_t> head;          // per worker: its first operation not yet emitted, or -1
+    std::vector<int32_t> last;
+    std::vector<int32_t> recent;        // workers in order of last use, most recent first
+    std::vector<char> emitted;
+};
+constexpr size_t kChainRecent = 4;
+// ops[0 .. count) must hold valid worker indices (0 <= i, j < n) and each worker's operations in its order.
+void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &plan);
+
 }  // namespace a2cid

@@ -27,12 +27,20 @@ struct DevOp {
     float b_i, b_j;              // mixing to the event time: off-diagonal of exp(tau A)
     float bp_i, bp_j;            // trailing mixing (0 = none)
     float gamma, gscale;         // gradient step size and slope of the affine gradient model
-    int32_t flags;               // bit 0: jumps from the stored (pre-mix) values, Algorithm 1's listing order
+    int32_t flags;               // kFlag* bits
     const float *xi;             // additive gradient term or nullptr
     const float *c;              // centre of the affine gradient model or nullptr
     int64_t pad1;
 };
 static_assert(sizeof(DevOp) == 64, "DevOp layout");
+
+enum : int32_t {
+    kFlagListing = 1,            // jumps from the stored (pre-mix) values, Algorithm 1's listing order
+    // chain kernel only: a workgroup keeps one worker's columns in registers from one operation to the next
+    kFlagCarryIn = 2,            // row_i's columns are already in the carry registers: do not load them
+    kFlagKeepI = 4,              // row_i's columns stay in the carry registers: do not store them
+    kFlagKeepJ = 8,              // row_j's columns move to the carry registers and are not stored (gossip only)
+};
 
 // exp(tau A) (x, xt) in increment form: with b the off-diagonal entry, x += b (xt - x) and
 // xt -= b (xt - x).  x + xt is conserved exactly up to one rounding; b = 0 is the identity.
@@ -91,6 +99,9 @@ __device__ __forceinline__ void store4(v4f *p, v4f v) {
 //   gossip:   4 rows in, 4 rows out  (32 bytes per column)
 //   gradient: 2 rows (+ xi, + c) in, 2 rows out  (16 / 20 / 24 bytes per column)
 //   mix only: 2 rows in, 2 rows out
+// Gradient inputs are read once and never written, so their loads are always non-temporal: kept out
+// of the caches they leave more room for state lines (measured +5 % on the ring workload, where a
+// third of the events are gradient events; neutral elsewhere).  For the state rows NT selects the policy.
 // The d % 4 trailing columns of a row are handled by scalar code in tile 0.
 // ------------------------------------------------------------------------------------------
 template <int U, bool NT, int TPB>
@@ -98,7 +109,7 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                                               int64_t d, const DevOp &op, int64_t tile,
                                               float alpha, float alpha_t) {
     const int64_t n4 = d >> 2;                                   // whole float4 pieces per row
-    const bool pre = (op.flags & 1) != 0;
+    const bool pre = (op.flags & kFlagListing) != 0;
     const int64_t base = (int64_t)tile * (U * TPB) + threadIdx.x;
     const bool full = (int64_t)(tile + 1) * (U * TPB) <= n4;
 
@@ -156,8 +167,8 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
             for (int u = 0; u < U; ++u) {
                 const int64_t k = base + u * TPB;
                 a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
-                g[u] = has_xi ? load4<NT>(pxi + k) : zero;
-                c[u] = has_c ? load4<NT>(pc + k) : zero;
+                g[u] = has_xi ? load4<true>(pxi + k) : zero;
+                c[u] = has_c ? load4<true>(pc + k) : zero;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -227,6 +238,140 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
     for (int32_t k = 0; k < n_ops; ++k) {
         const DevOp op = ops[k];
         apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);
+    }
+}
+
+
+// The d % 4 trailing columns of the rows of one operation, by lanes 0..3 of the calling workgroup, always
+// through memory (no carry).
+__device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__restrict__ xt, int64_t ld, int64_t d,
+                                              const DevOp &op, float alpha, float alpha_t) {
+    const int64_t k = ((d >> 2) << 2) + threadIdx.x;
+    if (threadIdx.x >= 4 || k >= d) return;
+    const bool pre = (op.flags & kFlagListing) != 0;
+    float *xi_row = x + (int64_t)op.row_i * ld, *xti_row = xt + (int64_t)op.row_i * ld;
+    float s0 = xi_row[k], s1 = xti_row[k];
+    if (op.kind == kOpGossip) {
+        float *xj_row = x + (int64_t)op.row_j * ld, *xtj_row = xt + (int64_t)op.row_j * ld;
+        float s2 = xj_row[k], s3 = xtj_row[k];
+        gossip_update(s0, s1, s2, s3, op, alpha, alpha_t, pre);
+        xj_row[k] = s2; xtj_row[k] = s3;
+    } else if (op.kind == kOpGradient) {
+        const float gk = op.xi != nullptr ? op.xi[k] : 0.f;
+        const float ck = (op.c != nullptr && op.gscale != 0.f) ? op.c[k] : 0.f;
+        gradient_update(s0, s1, gk, ck, op, pre);
+    } else {
+        mix(s0, s1, op.b_i);
+    }
+    xi_row[k] = s0; xti_row[k] = s1;
+}
+
+// ------------------------------------------------------------------------------------------
+// Chain kernel: the walk, on a batch the host has re-ordered and annotated.  Any linear extension of
+// the per-worker orders gives the same result bit for bit (operations on disjoint rows commute
+// exactly), so the host picks one in which an operation shares a worker with its predecessor as
+// often as possible (70-80 % of the operations on the paper's graphs) and marks the shared worker: its
+// columns stay in the workgroup's registers instead of being stored by one operation and loaded again
+// by the next.  A carried gossip operation moves 16 bytes per column instead of 32, a carried gradient
+// operation 8 (+ inputs) instead of 16; the carried worker is always presented as row_i (swapping
+// the two ends of a gossip operation negates m, which changes no bit of the result).
+// The last operation of a launch keeps nothing, so memory is complete when the launch ends.
+// ------------------------------------------------------------------------------------------
+// What an operation reads besides row_i: the other worker's columns (gossip) or the gradient inputs.
+struct Partner { v4f p0, p1; };
+
+template <int U>
+__device__ __forceinline__ void load_partner(Partner (&p)[U], const DevOp &op, v4f *xs, v4f *xts, int64_t ld4,
+                                             int64_t tile0, const uint32_t (&lp)[U], const bool (&act)[U]) {
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int u = 0; u < U; ++u) { p[u].p0 = zero; p[u].p1 = zero; }
+    if (op.kind == kOpGossip) {
+        const v4f *pj = xs + (int64_t)op.row_j * ld4, *ptj = xts + (int64_t)op.row_j * ld4;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (act[u]) { p[u].p0 = pj[lp[u]]; p[u].p1 = ptj[lp[u]]; }
+    } else if (op.kind == kOpGradient) {
+        const bool has_xi = op.xi != nullptr;
+        const bool has_c = op.c != nullptr && op.gscale != 0.f;
+        const v4f *pxi = (const v4f *)op.xi + tile0, *pc = (const v4f *)op.c + tile0;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (has_xi && act[u]) p[u].p0 = load4<true>(pxi + lp[u]);
+            if (has_c && act[u]) p[u].p1 = load4<true>(pc + lp[u]);
+        }
+    }
+}
+
+template <int U, int TPB>
+__global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
+                                                    int64_t d, const DevOp *__restrict__ ops, int32_t n_ops,
+                                                    float alpha, float alpha_t) {
+    // a row's pieces of this tile are at (row base + tile0, a workgroup-uniform address) + lane-dependent
+    // 32-bit offsets: scalar base plus vector offset, no 64-bit address arithmetic per lane
+    const int64_t tile0 = (int64_t)blockIdx.x * (U * TPB);          // first float4 piece of the tile
+    const int64_t left = (d >> 2) - tile0;                          // whole pieces from there to the row's end
+    uint32_t lp[U];
+    bool act[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        lp[u] = (uint32_t)(u * TPB) + threadIdx.x;
+        act[u] = (int64_t)lp[u] < left;
+    }
+    v4f *const xs = (v4f *)x + tile0, *const xts = (v4f *)xt + tile0;
+    const int64_t ld4 = ld >> 2;
+    const v4f zero = {0.f, 0.f, 0.f, 0.f};
+    v4f a[U], at[U];                                     // the carried worker's columns
+#pragma unroll
+    for (int u = 0; u < U; ++u) { a[u] = zero; at[u] = zero; }
+
+    for (int32_t k = 0; k < n_ops; ++k) {
+        const DevOp op = ops[k];
+        const bool pre = (op.flags & kFlagListing) != 0;
+        v4f *pi = xs + (int64_t)op.row_i * ld4, *pti = xts + (int64_t)op.row_i * ld4;
+        if (!(op.flags & kFlagCarryIn)) {
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (act[u]) { a[u] = pi[lp[u]]; at[u] = pti[lp[u]]; }
+        }
+        Partner p[U];
+        load_partner<U>(p, op, xs, xts, ld4, tile0, lp, act);
+
+        if (op.kind == kOpGossip) {
+            v4f *pj = xs + (int64_t)op.row_j * ld4, *ptj = xts + (int64_t)op.row_j * ld4;
+#pragma unroll
+            for (int u = 0; u < U; ++u) gossip_update(a[u], at[u], p[u].p0, p[u].p1, op, alpha, alpha_t, pre);
+            if (op.flags & kFlagKeepJ) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
+                    a[u] = p[u].p0; at[u] = p[u].p1;
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (act[u]) { pj[lp[u]] = p[u].p0; ptj[lp[u]] = p[u].p1; }
+                if (!(op.flags & kFlagKeepI)) {
+#pragma unroll
+                    for (int u = 0; u < U; ++u)
+                        if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
+                }
+            }
+        } else {
+            if (op.kind == kOpGradient) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) gradient_update(a[u], at[u], p[u].p0, p[u].p1, op, pre);
+            } else {
+#pragma unroll
+                for (int u = 0; u < U; ++u) mix(a[u], at[u], op.b_i);
+            }
+            if (!(op.flags & kFlagKeepI)) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
+            }
+        }
+        if (blockIdx.x == 0) apply_op_tail(x, xt, ld, d, op, alpha, alpha_t);
     }
 }
 

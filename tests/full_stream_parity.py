@@ -23,7 +23,7 @@ import parity_util as pu                                  # noqa: E402
 from paper_2306_08289_amd import workloads as wl          # noqa: E402
 
 
-def run(name, events, check_every, batch, mode=1, order=0, fifo=None):
+def run(name, events, check_every, batch, mode=3, order=0, fifo=None):
     cfg = wl.CONFIGS[name]
     events = events or cfg.events
     cols = pu.sample_columns(cfg.d, 4096, seed=7)
@@ -80,7 +80,8 @@ def main():
     ap.add_argument("--events", type=int, default=None)
     ap.add_argument("--check-every", type=int, default=100000)
     ap.add_argument("--batch", type=int, default=1024)
-    ap.add_argument("--mode", type=int, default=1, help="event kernel: 0 levels, 1 walk (default), 2 LDS-resident")
+    ap.add_argument("--mode", type=int, default=3,
+                    help="event kernel: 0 levels, 1 walk, 2 LDS-resident, 3 chain (default)")
     ap.add_argument("--order", type=int, default=0, help="0: Eq. (1) order (default); 1: Algorithm 1's listing order")
     ap.add_argument("--fifo", type=float, default=None,
                     help="use the first-in-first-out pairing source with this many averagings per gradient step")
@@ -93,7 +94,7 @@ def main():
     for name in args.configs:
         fifo = None if args.fifo is None else dict(comm_per_grad=args.fifo, comm_time=0.02, jitter=0.2)
         rec = run(name, args.events, args.check_every, args.batch, args.mode, args.order, fifo)
-        results = [r for r in results if (r["config"], r.get("mode", 1), r.get("order", 0), bool(r.get("fifo"))) !=
+        results = [r for r in results if (r["config"], r.get("mode", 3), r.get("order", 0), bool(r.get("fifo"))) !=
                    (name, args.mode, args.order, fifo is not None)] + [rec]
         os.makedirs(os.path.dirname(args.out), exist_ok=True)
         json.dump(results, open(args.out, "w"), indent=1)

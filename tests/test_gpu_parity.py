@@ -81,7 +81,8 @@ def test_small_configs_match_oracle_everywhere(name, d, events, batch):
 
 @pytest.mark.parametrize("unroll,nt,threads,walk", [(1, 0, 64, 0), (2, 1, 128, 0), (4, 1, 256, 1), (4, 0, 64, 0),
                                                    (2, 0, 512, 1), (1, 1, 128, 1), (4, 1, 64, 0),
-                                                   (1, 0, 1024, 1), (2, 1, 1024, 0), (1, 0, 256, 2)])
+                                                   (1, 0, 1024, 1), (2, 1, 1024, 0), (1, 0, 256, 2),
+                                                   (1, 0, 256, 3), (2, 0, 128, 3), (4, 0, 64, 3), (1, 0, 1024, 3)])
 def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
     # rows long enough that the engine keeps the requested unroll (it shrinks tiles for short rows)
     cfg = wl.scaled(wl.CONFIGS["C2"], d=2048 * 1024 * 4 * 4 + 517, events=600)
@@ -210,7 +211,8 @@ def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit():
     cfg = wl.scaled(wl.CONFIGS["C5"], d=70001, events=900)
     cols = np.arange(cfg.d)
     results = []
-    for batch, tuning in [(900, None), (128, None), (300, (4, 1, 64, 0)), (77, (2, 0, 128, 1)), (450, (1, 0, 256, 2))]:
+    for batch, tuning in [(900, None), (128, None), (512, (1, 0, 256, 1)), (300, (4, 1, 64, 0)), (77, (2, 0, 128, 1)), (450, (1, 0, 256, 2)),
+                          (900, (1, 0, 256, 3)), (211, (2, 0, 64, 3))]:
         _say(f"batching {batch} tuning {tuning}")
         w = wl.Workload(cfg, batch_events=batch)
         if tuning:
@@ -307,7 +309,8 @@ def test_resident_kernel_at_full_size_on_sampled_columns():
     w.close()
 
 
-@pytest.mark.parametrize("name,d,mode", [("C2", 4 * 1024 + 7, 1), ("C4", 9001, 0), ("C5", 5003, 2), ("C3", 3333, 1)])
+@pytest.mark.parametrize("name,d,mode", [("C2", 4 * 1024 + 7, 1), ("C4", 9001, 0), ("C5", 5003, 2), ("C3", 3333, 1),
+                                         ("C4", 4 * 256 * 2 + 3, 3), ("C3", 2049, 3)])
 def test_listing_order_variant_matches_oracle(name, d, mode):
     # Algorithm 1 as listed: g and m from the stored values, then the mixing, then the jump
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=2500)
@@ -348,7 +351,7 @@ def test_average_matches_oracle(name, d):
     w.close()
 
 
-@pytest.mark.parametrize("name,d,mode", [("C3", 6001, 1), ("C4", 5000, 2), ("C5", 4099, 1)])
+@pytest.mark.parametrize("name,d,mode", [("C3", 6001, 1), ("C4", 5000, 2), ("C5", 4099, 1), ("C4", 4100, 3)])
 def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode):
     # the paper's practical event source: Poisson count per gradient step + first-in-first-out pairing
     fifo = dict(comm_per_grad=2.0 if name == "C3" else 1.0, comm_time=0.03, jitter=0.25)
@@ -376,7 +379,8 @@ def _custom_workload(n, topology, d, seed=0xA2C1D2 + 77, **kw):
 
 @pytest.mark.parametrize("n,topology,d,events,mode", [(2, "ring", 4099, 400, 1), (2, "ring", 5, 400, 2),
                                                       (1024, "ring", 261, 6000, 1), (1024, "ring", 133, 4000, 0),
-                                                      (112, "exponential", 700, 3000, 2)])
+                                                      (112, "exponential", 700, 3000, 2), (2, "ring", 1031, 400, 3),
+                                                      (1024, "ring", 259, 6000, 3)])
 def test_extreme_worker_counts(n, topology, d, events, mode):
     # explicit eta, alpha_tilde: Proposition 3.2 gives alpha_tilde = 115 on a ring of 1024, where fp32 cancellation in
     # xt (terms of +-100 summing to O(1)) alone exceeds 1e-5 -- a property of fp32 state, not of the kernels
@@ -411,7 +415,7 @@ def test_resident_mode_is_refused_beyond_its_lds_capacity():
     w.close()
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 def test_batches_larger_than_a_staging_buffer_and_empty_batches(mode):
     # 40 000 events in one batch: the library splits it over several operation-table uploads
     cfg = wl.scaled(wl.CONFIGS["C4"], d=150, events=40000)
@@ -432,7 +436,7 @@ def test_batches_larger_than_a_staging_buffer_and_empty_batches(mode):
     w.close()
 
 
-@pytest.mark.parametrize("mode", [0, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2])
 def test_trailing_mix_in_the_other_kernels(mode):
     cfg = wl.scaled(wl.CONFIGS["C3"], d=777, events=60)
     w = wl.Workload(cfg, batch_events=60)

@@ -261,3 +261,75 @@ def test_engine_entry_points_fail_cleanly_without_touching_memory():
     assert lib.a2cid_stream_probe(0x1004, 0x2000, 16, None) == binding.EALIGN
     lib.a2cid_destroy(None)
     lib.a2cid_sched_destroy(None)
+
+
+# ---- chain order (the linear extension the chain kernel applies) -----------------------------------
+
+def _check_chain_plan(n, ops, order, shared):
+    m = len(ops)
+    assert sorted(order.tolist()) == list(range(m))                       # a permutation
+    ends = [({int(o["i"]), int(o["j"])} if o["kind"] == binding.KIND_GOSSIP else {int(o["i"])}) for o in ops]
+    seen = {}
+    for pos, k in enumerate(order):                                       # every worker sees its operations in order
+        for w in ends[k]:
+            assert seen.get(w, -1) < k, (w, pos)
+            seen[w] = int(k)
+    for pos in range(m):
+        common = ends[order[pos]] & ends[order[pos + 1]] if pos + 1 < m else set()
+        if common:
+            assert int(shared[pos]) in common                            # whenever neighbours share a worker it is carried
+        else:
+            assert shared[pos] == -1
+
+
+def _random_ops(rng, n, m, p_grad):
+    ops = np.zeros(m, binding.OP_DTYPE)
+    for k in range(m):
+        if rng.random() < p_grad or n < 2:
+            ops["kind"][k], ops["i"][k], ops["j"][k] = binding.KIND_GRADIENT, rng.integers(n), -1
+        else:
+            i, j = rng.choice(n, 2, replace=False)
+            ops["kind"][k], ops["i"][k], ops["j"][k] = binding.KIND_GOSSIP, i, j
+    return ops
+
+
+@pytest.mark.parametrize("n,m,p_grad,seed", [(2, 50, 0.3, 0), (3, 200, 0.0, 1), (5, 300, 0.5, 2), (64, 1024, 0.15, 3),
+                                             (64, 5000, 1.0, 4), (1024, 3000, 0.2, 5), (1, 10, 1.0, 6)])
+def test_chain_order_is_a_linear_extension_with_consistent_carries(n, m, p_grad, seed):
+    ops = _random_ops(np.random.default_rng(seed), n, m, p_grad)
+    batch = binding.Batch(ops, [0, m])
+    order, shared = binding.a2cid_plan_chain(n, batch)
+    _check_chain_plan(n, ops, order, shared)
+
+
+@pytest.mark.parametrize("topo,n,edge_rate,floor", [("ring", 64, 2.0, 0.75), ("exponential", 64, 1.0, 0.65),
+                                                    ("complete", 64, 0.56, 0.62)])
+def test_chain_order_on_scheduler_batches(topo, n, edge_rate, floor):
+    """On the paper's topologies most operations inherit a worker from their predecessor: the fraction is what the
+    chain kernel's traffic saving rests on, so a regression of the greedy order shows here."""
+    edges = getattr(graph, topo)(n)
+    u, v = _uv(edges)
+    s = binding.Scheduler(n, u, v, edge_rate, 1.0, 11)
+    for size in (1, 7, 1024, 4096):
+        b = s.next(size)
+        order, shared = binding.a2cid_plan_chain(n, b)
+        _check_chain_plan(n, b.ops, order, shared)
+        if size >= 1024:
+            assert (shared >= 0).mean() >= floor, (topo, size, (shared >= 0).mean())
+    s.close()
+
+
+def test_chain_order_rejects_malformed_batches_and_accepts_empty_ones():
+    empty = binding.Batch(np.zeros(0, binding.OP_DTYPE), [0])
+    order, shared = binding.a2cid_plan_chain(4, empty)
+    assert len(order) == 0 and len(shared) == 0
+    for field, value in (("i", 4), ("i", -1), ("j", 9), ("kind", 7)):
+        ops = _random_ops(np.random.default_rng(0), 4, 20, 0.0)
+        ops[field][11] = value
+        with pytest.raises(a2.A2cidError) as e:
+            binding.a2cid_plan_chain(4, binding.Batch(ops, [0, 20]))
+        assert e.value.code == binding.EINVAL
+    ops = _random_ops(np.random.default_rng(0), 4, 20, 0.0)
+    ops["j"][3] = ops["i"][3]                                             # a worker cannot gossip with itself
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_plan_chain(4, binding.Batch(ops, [0, 20]))
