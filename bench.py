@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
 # HBM bytes per launch of the dominant kernel in the default configuration, from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
-# size: profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the workload, batch size and kernel it names.
-MEASURED_TRAFFIC = {("C4", 1024, "walk_kernel"): 7.9222e11}
+# size: profiles/chain_kernel_C4_hbm_counters.md and profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the
+# workload, batch size and kernel it names.
+MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 4.8261e11, ("C4", 1024, "walk_kernel"): 7.9200e11}
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 
