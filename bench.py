@@ -126,6 +126,7 @@ def main():
     ap.add_argument("--walk", type=int, default=None,
                     help="event kernel: 3 = chain (default), 1 = walk in level order, 0 = one launch per level, "
                          "2 = LDS-resident")
+    ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
@@ -149,6 +150,8 @@ def main():
     torch.cuda.set_device(0)
     w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True, ld_pad=args.ld_pad)
     tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
+    if args.slots is not None:
+        w.engine.set_chain_slots(args.slots)
     if any(v is not None for v in tuning):
         w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 3))])
     if args.group is not None or args.cols is not None:
@@ -220,7 +223,8 @@ def main():
         "config": {"workload": f"{cfg.name}: n={cfg.n} {cfg.topology} graph, d={cfg.d} fp32, "
                                f"{args.batch} events per step" + ("" if args.no_stats else " + one observables pass"),
                    "eta": w.eta, "alpha": w.alpha, "alpha_tilde": w.alpha_tilde, "gamma": cfg.gamma,
-                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal, "threads": args.threads, "walk": args.walk},
+                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal, "threads": args.threads, "walk": args.walk,
+                   "slots": args.slots},
         "events_per_s": events / elapsed, "gossip_events_per_s": cnt["gossip"] / elapsed,
         "gradient_events_per_s": cnt["gradient"] / elapsed,
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,

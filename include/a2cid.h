@@ -206,16 +206,31 @@ void a2cid_destroy(a2cid_ctx *ctx);
 int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
                      const a2cid_event_batch *batch, a2cid_coef *coef);
 
-/* The order in which the chain kernel (a2cid_set_tuning, mode 3) applies a batch, as a pure host
+/* The programme the chain kernel (a2cid_set_tuning, mode 3) runs for a batch, as a pure host
  * function.  Eq. (1) lets operations on disjoint workers commute, so any order that keeps every
  * worker's own operations in sequence yields the same state bit for bit; the library picks one in
- * which an operation shares a worker with its predecessor as often as it can, and keeps that
- * worker's columns in registers from the one to the other.  order[k] (n_ops entries) is the index
- * into batch->ops of the k-th operation applied; shared[k] is the worker carried from position k
- * to position k + 1, or -1 (shared[n_ops - 1] is always -1).  Either output may be NULL.  Only
- * kinds and worker indices of the operations are read (the level table is not).  A batch of more
- * than 16384 operations is ordered by a2cid_apply_events in pieces of whole levels. */
-int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t *order, int32_t *shared);
+ * which an operation finds its workers' columns close by as often as it can: in the workgroup's
+ * carry registers (A2CID_LOC_CARRY: handed from one operation to the very next) or parked in one of
+ * lds_slots LDS slots (A2CID_LOC_SLOT0 + s), instead of device memory (A2CID_LOC_MEMORY).
+ * A step with op >= 0 applies batch->ops[op] with its workers presented as (row_i, row_j) (row_j = -1
+ * for a gradient event; the carried worker is always row_i), reads them from src_i / src_j and leaves
+ * them in dst_i / dst_j.  A step with op = -1 writes the worker row_i parked in slot src_i back to
+ * memory.  After the last step every worker's columns are in memory.
+ * steps (capacity entries; 3 n_ops + lds_slots always suffice) may be NULL to query *n_steps only;
+ * *bytes_per_column (may be NULL) receives what the launch moves per column: 8 per row read from or
+ * written to memory, 4 per gradient input read.  Only kinds, worker indices and the xi / c / gscale
+ * fields of the operations are read (the level table is not).  0 <= lds_slots <= 16.
+ * a2cid_apply_events plans pieces of at most 5461 operations (whole levels) independently. */
+#define A2CID_LOC_MEMORY 0
+#define A2CID_LOC_CARRY  1
+#define A2CID_LOC_SLOT0  2
+typedef struct a2cid_chain_step {
+    int32_t op;
+    int32_t row_i, row_j;
+    uint8_t src_i, src_j, dst_i, dst_j;
+} a2cid_chain_step;
+int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t lds_slots, a2cid_chain_step *steps,
+                     int64_t capacity, int64_t *n_steps, double *bytes_per_column);
 
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 
@@ -270,9 +285,9 @@ void a2cid_sched_destroy(a2cid_sched *s);
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
  *      own columns, each operation reading and writing its rows in device memory (32 d bytes per
  *      gossip event);
- *   3: as 1, but in the order of a2cid_plan_chain, a worker shared by consecutive operations
- *      staying in registers (16 d bytes for a gossip event that inherits a worker and hands one on;
- *      default);
+ *   3: as 1, but following the programme of a2cid_plan_chain: a worker shared by consecutive
+ *      operations stays in registers and workers that come back soon are parked in LDS (16 d bytes
+ *      for a gossip event that finds one worker there and leaves one there; default);
  *   2: as 1, but the workgroup keeps its columns of all touched rows in LDS for the whole batch, so
  *      the state is read and written once per batch instead of once per event (at most 112
  *      workers).
@@ -281,6 +296,12 @@ void a2cid_sched_destroy(a2cid_sched *s);
  * gradient inputs of a batch must hold their final values, in stream order, before
  * a2cid_apply_events is called. */
 int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_t threads, int32_t mode);
+
+/* Mode 3 only: LDS slots in which a workgroup parks workers between operations (0 ... 16; each
+ * takes unroll x threads x 32 bytes of the CU's 160 KiB of LDS per resident workgroup, so 5 leaves
+ * room for four workgroups of 256 lanes on a CU: more slots save more traffic but leave fewer
+ * columns in flight).  0: only the carry registers are used.  Default: 5. */
+int a2cid_set_chain_slots(a2cid_ctx *ctx, int32_t slots);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
  * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
@@ -311,7 +332,8 @@ int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream
  * the byte count of one pass per event (32 d for a gossip event; 16 d for a gradient event plus
  * 4 d for each of xi and c that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
  * a2cid_average), and the bytes the launched kernels move by construction: the same for modes 0
- * and 1; for mode 3, 8 d less for every row carried in and for every row kept; for mode 2, 16 d
+ * and 1; for mode 3, 8 d for every row read from or written to memory (a2cid_plan_chain) plus the
+ * gradient inputs; for mode 2, 16 d
  * per touched row and launch plus the gradient inputs.  Any output pointer may be NULL. */
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
                    double *one_pass_bytes, double *moved_bytes, int32_t reset);

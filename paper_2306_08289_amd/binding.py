@@ -73,7 +73,9 @@ SIGNATURES = {
     "a2cid_set_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
     "a2cid_synchronize": (C.c_int, [C.c_void_p]),
     "a2cid_destroy": (None, [C.c_void_p]),
-    "a2cid_plan_chain": (C.c_int, [C.c_int32, _P(a2cid_event_batch), _P(C.c_int32), _P(C.c_int32)]),
+    "a2cid_plan_chain": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_int32, C.c_void_p, C.c_int64,
+                                   _P(C.c_int64), _P(C.c_double)]),
+    "a2cid_set_chain_slots": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
     "a2cid_sched_create": (C.c_int, [_P(C.c_void_p), C.c_int32, _P(a2cid_graph), _P(C.c_double), C.c_uint64]),
@@ -180,16 +182,20 @@ def a2cid_plan_batch(n, u, v, rate, eta, t, batch):
     return t, coef
 
 
-def a2cid_plan_chain(n, batch):
-    """Returns (order, shared): the order in which the chain kernel applies the batch and the worker carried
-    from each position to the next (-1: none)."""
+STEP_DTYPE = np.dtype([("op", "<i4"), ("row_i", "<i4"), ("row_j", "<i4"), ("src_i", "u1"), ("src_j", "u1"),
+                       ("dst_i", "u1"), ("dst_j", "u1")])
+LOC_MEMORY, LOC_CARRY, LOC_SLOT0 = 0, 1, 2
+
+
+def a2cid_plan_chain(n, batch, lds_slots=5):
+    """Returns (steps, bytes_per_column): the chain kernel's programme for the batch as a STEP_DTYPE array."""
     m = len(batch.ops)
-    order = np.zeros(m, np.int32)
-    shared = np.zeros(m, np.int32)
+    steps = np.zeros(3 * m + int(lds_slots), STEP_DTYPE)
+    count, per_col = C.c_int64(), C.c_double()
     bs = batch.struct()
-    _check(load().a2cid_plan_chain(int(n), C.byref(bs), order.ctypes.data_as(_P(C.c_int32)),
-                                   shared.ctypes.data_as(_P(C.c_int32))))
-    return order, shared
+    _check(load().a2cid_plan_chain(int(n), C.byref(bs), int(lds_slots), steps.ctypes.data, len(steps),
+                                   C.byref(count), C.byref(per_col)))
+    return steps[:count.value], per_col.value
 
 
 class Scheduler:
@@ -308,6 +314,9 @@ class Engine:
 
     def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=3):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))
+
+    def set_chain_slots(self, slots=5):
+        _check(load().a2cid_set_chain_slots(self._h, int(slots)))
 
     def set_resident_group(self, group=8, cols=1):
         _check(load().a2cid_set_resident_group(self._h, int(group), int(cols)))

@@ -81,6 +81,7 @@ struct a2cid_ctx {
     double alg_bytes = 0.0;
     double moved_bytes = 0.0;           // bytes the launched kernels move by construction (<= alg_bytes)
     ChainPlan chain;
+    int chain_slots = 5;                // chain kernel: LDS slots for parked workers
     // optional per-launch timing
     bool profiling = false;
     std::vector<TimedLaunch> timed;
@@ -164,7 +165,11 @@ void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
     int64_t blocks = (n4 + per_block - 1) / per_block;
     if (blocks < 1) blocks = 1;   // the scalar tail lives in tile 0
     if (walk == kLaunchChain) {
-        hipLaunchKernelGGL((chain_kernel<U, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
+        const size_t lds = (size_t)c->chain_slots * U * TPB * 2 * sizeof(v4f);
+        if (lds > 65536)
+            (void)hipFuncSetAttribute((const void *)chain_kernel<U, TPB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)lds);      // a failure shows as the launch error that follows
+        hipLaunchKernelGGL((chain_kernel<U, TPB>), dim3((unsigned)blocks), dim3(TPB), lds, c->stream, c->x,
                            c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
     } else if (walk == kLaunchWalk) {
         hipLaunchKernelGGL((walk_kernel<U, NT, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
@@ -214,33 +219,6 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
     return A2CID_OK;
 }
 
-
-// Marks the carried workers of a chain-ordered operation table: neighbours that share the planned worker keep
-// its columns in registers (kFlagKeepI/J on the first, kFlagCarryIn on the second, which is turned so that the
-// shared worker is its row_i).  Returns the bytes per column that the launch moves.
-double mark_carries(DevOp *ops, int64_t count, const std::vector<int32_t> &shared) {
-    for (int64_t k = 0; k + 1 < count; ++k) {
-        if (shared[k] < 0) continue;
-        DevOp &p = ops[k], &q = ops[k + 1];
-        p.flags |= shared[k] == p.row_i ? kFlagKeepI : kFlagKeepJ;
-        if (q.row_i != shared[k]) {      // only a gossip operation can have the shared worker as row_j
-            std::swap(q.row_i, q.row_j);
-            std::swap(q.b_i, q.b_j);
-            std::swap(q.bp_i, q.bp_j);
-        }
-        q.flags |= kFlagCarryIn;
-    }
-    double per_column = 0.0;
-    for (int64_t k = 0; k < count; ++k) {
-        const DevOp &o = ops[k];
-        const bool kept = (o.flags & (kFlagKeepI | kFlagKeepJ)) != 0;
-        per_column += (o.flags & kFlagCarryIn) ? 0.0 : 8.0;                  // row_i in
-        per_column += kept && o.kind != kOpGossip ? 0.0 : 8.0;               // one row out unless the only row is kept
-        if (o.kind == kOpGossip) per_column += 8.0 + (kept ? 0.0 : 8.0);     // row_j in, second row out unless one is kept
-        if (o.kind == kOpGradient) per_column += (o.xi ? 4.0 : 0.0) + ((o.c && o.gscale != 0.f) ? 4.0 : 0.0);
-    }
-    return per_column;
-}
 
 constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row, column-per-lane and workgroup, plus staging
 
@@ -417,6 +395,8 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
         if (op.c && op.gscale != 0.f)
             if (int rc = check_device_span(c, op.c, sizeof(float) * (size_t)c->d, "c of a gradient event")) return rc;
     }
+    // the chain programme of k operations has at most 3 k + slots steps (every spill makes room for a parking)
+    const int64_t cap = c->walk == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps;
     int32_t l = 0;
     while (l < batch->n_levels) {
         // take as many whole levels as fit into one staging buffer
@@ -424,8 +404,8 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
         int64_t count = 0;
         while (l_end < batch->n_levels) {
             const int64_t sz = batch->level_off[l_end + 1] - batch->level_off[l_end];
-            if (sz > kSlotOps) return fail(A2CID_EMATCHING, "level %d has %lld operations", l_end, (long long)sz);
-            if (count + sz > kSlotOps) break;
+            if (sz > cap) return fail(A2CID_EMATCHING, "level %d has %lld operations", l_end, (long long)sz);
+            if (count + sz > cap) break;
             count += sz;
             ++l_end;
         }
@@ -433,12 +413,9 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
             Slot *s;
             if (int rc = acquire_slot(c, &s)) return rc;
             const int64_t first = batch->level_off[l];
-            if (c->walk == 3) plan_chain(c->n, batch->ops + first, count, c->chain);
-            for (int64_t k = 0; k < count; ++k) {
-                const int64_t src = first + (c->walk == 3 ? c->chain.order[k] : k);
+            auto fill = [&](DevOp &o, int64_t src) {
                 const a2cid_op &op = batch->ops[src];
                 const a2cid_coef &cf = c->plan.coef[src];
-                DevOp &o = s->host[k];
                 o.kind = op.kind == A2CID_KIND_GOSSIP ? kOpGossip : kOpGradient;
                 o.row_i = op.i;
                 o.row_j = op.kind == A2CID_KIND_GOSSIP ? op.j : op.i;
@@ -448,7 +425,37 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 o.flags = c->order;
                 o.xi = op.kind == A2CID_KIND_GRADIENT ? op.xi : nullptr;
                 o.c = op.kind == A2CID_KIND_GRADIENT ? op.c : nullptr;
+                o.loc = 0;                  // every row from and to memory
                 o.pad1 = 0;
+            };
+            int64_t n_dev = count;          // records of the device table
+            if (c->walk == 3) {
+                plan_chain(c->n, batch->ops + first, count, c->chain_slots, c->chain);
+                n_dev = (int64_t)c->chain.steps.size();
+                if (n_dev > kSlotOps) return fail(A2CID_EINVAL, "internal: chain programme of %lld steps", (long long)n_dev);
+                for (int64_t k = 0; k < n_dev; ++k) {
+                    const a2cid_chain_step &st = c->chain.steps[k];
+                    DevOp &o = s->host[k];
+                    const uint32_t top = kLocSlot0 + (uint32_t)c->chain_slots;
+                    if (st.src_i >= top || st.src_j >= top || st.dst_i >= top || st.dst_j >= top)
+                        return fail(A2CID_EINVAL, "internal: chain step %lld names a slot that does not exist", (long long)k);
+                    if (st.op < 0) {
+                        std::memset(&o, 0, sizeof(o));
+                        o.kind = kOpSpill;
+                        o.row_i = o.row_j = st.row_i;
+                        o.loc = st.src_i;
+                        continue;
+                    }
+                    fill(o, first + st.op);
+                    if (o.row_i != st.row_i) {       // a gossip operation turned so that the carried worker is row_i
+                        std::swap(o.row_i, o.row_j);
+                        std::swap(o.b_i, o.b_j);
+                        std::swap(o.bp_i, o.bp_j);
+                    }
+                    o.loc = (uint32_t)st.src_i | (uint32_t)st.src_j << 8 | (uint32_t)st.dst_i << 16 | (uint32_t)st.dst_j << 24;
+                }
+            } else {
+                for (int64_t k = 0; k < count; ++k) fill(s->host[k], first + k);
             }
             if (c->walk == 2) {
                 // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
@@ -506,7 +513,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
             }
             double moved = 0.0;             // bytes per column that this chunk's launches move
             if (c->walk == 3) {
-                moved = mark_carries(s->host, count, c->chain.shared);
+                moved = c->chain.bytes_per_column;
             } else {
                 for (int64_t k = 0; k < count; ++k) {
                     const DevOp &o = s->host[k];
@@ -514,9 +521,9 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 }
             }
             c->moved_bytes += moved * (double)c->d;
-            A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)count, hipMemcpyHostToDevice, c->stream));
+            A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)n_dev, hipMemcpyHostToDevice, c->stream));
             if (c->walk == 3) {
-                if (int rc = launch_ops(c, s->dev, (int32_t)count, kLaunchChain)) return rc;
+                if (int rc = launch_ops(c, s->dev, (int32_t)n_dev, kLaunchChain)) return rc;
             } else if (c->walk == 1) {
                 if (int rc = launch_ops(c, s->dev, (int32_t)count, kLaunchWalk)) return rc;
             } else {
@@ -663,6 +670,9 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     if (mode < 0 || mode > 3) return fail(A2CID_EINVAL, "mode must be 0 (levels), 1 (walk), 2 (resident) or 3 (chain)");
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
+    if (mode == 3 && (size_t)c->chain_slots * unroll * threads * 32 > 160 * 1024)
+        return fail(A2CID_EINVAL, "%d slots of %d x %d lanes x 32 bytes do not fit into 160 KiB of LDS "
+                    "(a2cid_set_chain_slots lowers the slots)", c->chain_slots, unroll, threads);
     c->unroll = unroll;
     c->nontemporal = nontemporal ? 1 : 0;
     c->threads = threads;
@@ -675,6 +685,17 @@ int a2cid_set_order(a2cid_ctx *c, int32_t order) {
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
     if (order != A2CID_ORDER_EQ1 && order != A2CID_ORDER_LISTING) return fail(A2CID_EINVAL, "unknown order %d", order);
     c->order = order;
+    return A2CID_OK;
+}
+
+int a2cid_set_chain_slots(a2cid_ctx *c, int32_t slots) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (slots < 0 || slots > kChainMaxSlots) return fail(A2CID_EINVAL, "slots must be in [0, %d]", kChainMaxSlots);
+    if ((size_t)slots * c->unroll * c->threads * 32 > 160 * 1024)
+        return fail(A2CID_EINVAL, "%d slots of %d x %d lanes x 32 bytes do not fit into 160 KiB of LDS", slots, c->unroll,
+                    c->threads);
+    c->chain_slots = slots;
     return A2CID_OK;
 }
 

@@ -431,14 +431,17 @@ static inline int op_endpoints(const a2cid_op &o, int32_t (&w)[2]) {
     return o.kind == A2CID_KIND_GOSSIP ? 2 : 1;
 }
 
-void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &s) {
-    s.order.resize((size_t)count);
-    s.shared.assign((size_t)count, -1);
+void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots, ChainPlan &s) {
+    s.steps.clear();
+    s.steps.reserve((size_t)count + (size_t)count / 2 + (size_t)lds_slots);
+    s.bytes_per_column = 0.0;
     s.next_op.assign(2 * (size_t)count, -1);
     s.waiting.assign((size_t)count, 0);
     s.emitted.assign((size_t)count, 0);
     s.head.assign(n, -1);
     s.last.assign(n, -1);
+    s.where.assign(n, A2CID_LOC_MEMORY);
+    s.owner.assign(lds_slots, -1);
     s.recent.clear();
     int32_t w[2];
     for (int64_t k = 0; k < count; ++k) {
@@ -454,21 +457,114 @@ void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &s) {
             s.last[w[e]] = (int32_t)k;
         }
     }
+    const int32_t never = INT32_MAX;
+    auto next_use = [&](int32_t worker) { return s.head[worker] >= 0 ? s.head[worker] : never; };
+
     int64_t scan = 0;
-    for (int64_t out = 0; out < count; ++out) {
-        int32_t pick = -1;
-        for (size_t r = 0; r < s.recent.size() && pick < 0; ++r) {
-            const int32_t k = s.head[s.recent[r]];
-            if (k >= 0 && s.waiting[k] == 0) pick = k;
+    int64_t prev = -1;                  // index into steps of the last operation step; its dst_* are still open
+    int32_t pw[2] = {-1, -1};           // its workers, as (row_i, row_j)
+    int npw = 0;
+
+    // Closes the previous operation's step: where its workers' columns go, given the workers of the next one.
+    auto close_prev = [&](const int32_t *nw, int nn) {
+        if (prev < 0) return;
+        auto used_next = [&](int32_t worker) { return (nn > 0 && nw[0] == worker) || (nn > 1 && nw[1] == worker); };
+        int32_t carried = -1;
+        for (int e = 0; e < npw && carried < 0; ++e)
+            if (used_next(pw[e])) carried = pw[e];
+        for (int e = 0; e < npw; ++e) {
+            const int32_t worker = pw[e];
+            const uint8_t at = s.where[worker];             // where the operation found it
+            uint8_t dst = A2CID_LOC_MEMORY;
+            if (worker == carried) {
+                dst = A2CID_LOC_CARRY;
+            } else if (next_use(worker) != never) {
+                if (at >= A2CID_LOC_SLOT0) {
+                    dst = at;                               // stays in its slot
+                } else {
+                    int32_t slot = -1;
+                    for (int32_t q = 0; q < lds_slots && slot < 0; ++q)
+                        if (s.owner[q] < 0) slot = q;
+                    if (slot < 0) {
+                        // the parked worker whose next operation is farthest away makes room if it is farther
+                        // than this worker's; workers of the previous and of the next operation stay
+                        int32_t far = -1;
+                        for (int32_t q = 0; q < lds_slots; ++q) {
+                            const int32_t v = s.owner[q];
+                            if (v == pw[0] || (npw > 1 && v == pw[1]) || used_next(v)) continue;
+                            if (far < 0 || next_use(v) > next_use(s.owner[far])) far = q;
+                        }
+                        if (far >= 0 && next_use(s.owner[far]) > next_use(worker)) {
+                            a2cid_chain_step spill{};
+                            spill.op = -1;
+                            spill.row_i = s.owner[far];
+                            spill.row_j = -1;
+                            spill.src_i = (uint8_t)(A2CID_LOC_SLOT0 + far);
+                            s.steps.insert(s.steps.begin() + prev, spill);   // before the step that re-uses the slot
+                            ++prev;
+                            s.bytes_per_column += 8.0;
+                            s.where[s.owner[far]] = A2CID_LOC_MEMORY;
+                            s.owner[far] = -1;
+                            slot = far;
+                        }
+                    }
+                    if (slot >= 0) {
+                        dst = (uint8_t)(A2CID_LOC_SLOT0 + slot);
+                        s.owner[slot] = worker;
+                    }
+                }
+            }
+            if (at >= A2CID_LOC_SLOT0 && dst != at) s.owner[at - A2CID_LOC_SLOT0] = -1;
+            if (dst == A2CID_LOC_MEMORY) s.bytes_per_column += 8.0;
+            s.where[worker] = dst;
+            (e == 0 ? s.steps[prev].dst_i : s.steps[prev].dst_j) = dst;
         }
+    };
+
+    for (int64_t out = 0; out < count; ++out) {
+        // candidates: pending operations of nearby workers, fewest rows to fetch from memory first
+        int32_t pick = -1, pick_miss = 3;
+        auto near_by = [&](int32_t worker) {
+            return s.where[worker] != A2CID_LOC_MEMORY || (npw > 0 && pw[0] == worker) || (npw > 1 && pw[1] == worker);
+        };
+        auto consider = [&](int32_t worker) {
+            const int32_t k = s.head[worker];
+            if (k < 0 || s.waiting[k] != 0) return;
+            int32_t v[2];
+            const int ne = op_endpoints(ops[k], v);
+            int32_t miss = 0;
+            for (int e = 0; e < ne; ++e) miss += near_by(v[e]) ? 0 : 1;
+            if (miss < pick_miss) { pick = k; pick_miss = miss; }
+        };
+        for (int e = 0; e < npw; ++e) consider(pw[e]);
+        for (size_t r = 0; r < s.recent.size(); ++r) consider(s.recent[r]);
+        for (int32_t q = 0; q < lds_slots; ++q)
+            if (s.owner[q] >= 0) consider(s.owner[q]);
         if (pick < 0) {
             // the earliest operation not yet emitted: everything it waits for has a smaller index, so it is free
             while (s.emitted[scan]) ++scan;
             pick = (int32_t)scan;
         }
-        s.order[out] = pick;
         s.emitted[pick] = 1;
         const int ne = op_endpoints(ops[pick], w);
+        close_prev(w, ne);
+
+        a2cid_chain_step step{};
+        step.op = pick;
+        // the worker that sits in the carry registers, if any, is presented as row_i
+        const bool turn = ne == 2 && s.where[w[1]] == A2CID_LOC_CARRY;
+        step.row_i = turn ? w[1] : w[0];
+        step.row_j = ne == 2 ? (turn ? w[0] : w[1]) : -1;
+        step.src_i = s.where[step.row_i];
+        step.src_j = ne == 2 ? s.where[step.row_j] : (uint8_t)A2CID_LOC_MEMORY;
+        if (step.src_i == A2CID_LOC_MEMORY) s.bytes_per_column += 8.0;
+        if (ne == 2 && step.src_j == A2CID_LOC_MEMORY) s.bytes_per_column += 8.0;
+        if (ops[pick].kind == A2CID_KIND_GRADIENT)
+            s.bytes_per_column += (ops[pick].xi ? 4.0 : 0.0) + ((ops[pick].c && ops[pick].gscale != 0.f) ? 4.0 : 0.0);
+        prev = (int64_t)s.steps.size();
+        s.steps.push_back(step);
+        pw[0] = step.row_i; pw[1] = step.row_j; npw = ne;
+
         for (int e = 0; e < ne; ++e) {
             const int32_t nx = s.next_op[2 * (size_t)pick + e];
             s.head[w[e]] = nx;
@@ -479,12 +575,18 @@ void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &s) {
         }
         if (s.recent.size() > kChainRecent) s.recent.resize(kChainRecent);
     }
-    for (int64_t k = 0; k + 1 < count; ++k) {
-        int32_t pw[2], qw[2];
-        const int np = op_endpoints(ops[s.order[k]], pw), nq = op_endpoints(ops[s.order[k + 1]], qw);
-        for (int e = 0; e < np && s.shared[k] < 0; ++e)
-            for (int f = 0; f < nq; ++f)
-                if (pw[e] == qw[f]) { s.shared[k] = pw[e]; break; }
+    close_prev(nullptr, 0);
+    for (int32_t q = 0; q < lds_slots; ++q) {
+        if (s.owner[q] < 0) continue;
+        a2cid_chain_step spill{};
+        spill.op = -1;
+        spill.row_i = s.owner[q];
+        spill.row_j = -1;
+        spill.src_i = (uint8_t)(A2CID_LOC_SLOT0 + q);
+        s.steps.push_back(spill);
+        s.bytes_per_column += 8.0;
+        s.where[s.owner[q]] = A2CID_LOC_MEMORY;
+        s.owner[q] = -1;
     }
 }
 
@@ -556,11 +658,14 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
     return A2CID_OK;
 }
 
-int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t *order, int32_t *shared) {
+int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t lds_slots, a2cid_chain_step *steps,
+                     int64_t capacity, int64_t *n_steps, double *bytes_per_column) {
     clear_error();
     if (n < 1 || n > A2CID_MAX_WORKERS) return fail(A2CID_EINVAL, "n = %d out of range", n);
+    if (lds_slots < 0 || lds_slots > kChainMaxSlots) return fail(A2CID_EINVAL, "lds_slots must be in [0, %d]", kChainMaxSlots);
     if (!batch || batch->n_ops < 0 || (batch->n_ops > 0 && !batch->ops)) return fail(A2CID_EINVAL, "batch is NULL or malformed");
-    if (batch->n_ops > INT32_MAX) return fail(A2CID_EINVAL, "too many operations");
+    if (batch->n_ops > INT32_MAX / 4) return fail(A2CID_EINVAL, "too many operations");
+    if (!n_steps) return fail(A2CID_EINVAL, "n_steps is NULL");
     for (int64_t k = 0; k < batch->n_ops; ++k) {
         const a2cid_op &o = batch->ops[k];
         const bool gossip = o.kind == A2CID_KIND_GOSSIP;
@@ -569,9 +674,14 @@ int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t *order, 
     }
     try {
         ChainPlan plan;
-        plan_chain(n, batch->ops, batch->n_ops, plan);
-        if (order) std::copy(plan.order.begin(), plan.order.end(), order);
-        if (shared) std::copy(plan.shared.begin(), plan.shared.end(), shared);
+        plan_chain(n, batch->ops, batch->n_ops, lds_slots, plan);
+        *n_steps = (int64_t)plan.steps.size();
+        if (bytes_per_column) *bytes_per_column = plan.bytes_per_column;
+        if (steps) {
+            if ((int64_t)plan.steps.size() > capacity)
+                return fail(A2CID_EINVAL, "%zu steps do not fit into %lld entries", plan.steps.size(), (long long)capacity);
+            std::copy(plan.steps.begin(), plan.steps.end(), steps);
+        }
     } catch (const std::bad_alloc &) {
         return fail(A2CID_ENOMEM, "out of host memory");
     }

@@ -48,26 +48,34 @@ struct PlanScratch {
 int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
                Plan &plan, PlanScratch &scratch);
 
-// The order in which the chain kernel applies the operations of one launch, and which worker stays in
-// registers between neighbours of that order.  Any linear extension of the per-worker orders gives the same
+// The chain kernel's programme for one launch: the order in which the operations are applied and where every
+// touched worker's columns come from and go to.  Any linear extension of the per-worker orders gives the same
 // result bit for bit (operations on disjoint rows commute exactly); this one is built greedily so that an
-// operation shares a worker with its predecessor as often as possible: the next operation is the pending
-// operation of the most recently used worker whose other endpoint is free too, and when none of the
-// kChainRecent last used workers has one, the earliest operation not yet emitted (always free when the
-// input is sorted by level).
+// operation finds its workers close by as often as possible.  A worker's columns can be in device memory, in the
+// workgroup's carry registers (from one operation to the very next), or parked in one of lds_slots LDS slots:
+//   - next comes the free pending operation of a worker used by the previous operation, of one of the
+//     kChainRecent last used workers, or of a parked worker, whichever misses the fewest rows (ties: in that
+//     order); when there is none, the earliest operation not yet emitted (always free in a level-sorted batch);
+//   - a worker that the next operation uses stays in the carry registers; another worker with a pending
+//     operation is parked if a slot is free or holds a worker whose next operation comes later in the batch
+//     (that worker is written back first: a spill step); everything else goes to memory;
+//   - after the last operation every parked worker is written back, so memory is complete when the launch ends.
 struct ChainPlan {
-    std::vector<int32_t> order;         // order[k]: index of the k-th operation applied
-    std::vector<int32_t> shared;        // shared[k]: worker common to positions k and k + 1 that is carried, or -1
+    std::vector<a2cid_chain_step> steps;
+    double bytes_per_column = 0.0;      // what the launch moves: 8 per row read from or written to memory, 4 per input
     // work arrays
     std::vector<int32_t> next_op;       // [2 k + e]: the next operation of operation k's endpoint e, or -1
     std::vector<int32_t> waiting;       // endpoints of operation k whose previous operation has not been emitted
     std::vector<int32_t> head;          // per worker: its first operation not yet emitted, or -1
     std::vector<int32_t> last;
     std::vector<int32_t> recent;        // workers in order of last use, most recent first
+    std::vector<int32_t> owner;         // per LDS slot: the parked worker or -1
+    std::vector<uint8_t> where;         // per worker: A2CID_LOC_* of its current columns
     std::vector<char> emitted;
 };
 constexpr size_t kChainRecent = 4;
-// ops[0 .. count) must hold valid worker indices (0 <= i, j < n) and each worker's operations in its order.
-void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, ChainPlan &plan);
+constexpr int32_t kChainMaxSlots = 16;
+// ops[0 .. count) must hold valid worker indices (0 <= i, j < n, i != j for gossip); 0 <= lds_slots <= kChainMaxSlots.
+void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots, ChainPlan &plan);
 
 }  // namespace a2cid

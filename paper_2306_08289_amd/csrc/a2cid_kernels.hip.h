@@ -17,7 +17,7 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 constexpr int kThreads = 256;           // 4 wavefronts per workgroup
 constexpr int kWaves = kThreads / 64;
 
-enum : int32_t { kOpGradient = 0, kOpGossip = 1, kOpMixOnly = 2 };
+enum : int32_t { kOpGradient = 0, kOpGossip = 1, kOpMixOnly = 2, kOpSpill = 3 };
 
 // One operation of a level as the kernels see it (64 bytes).  Every field is uniform across
 // the workgroup that executes the operation, so the compiler keeps it in scalar registers.
@@ -30,16 +30,22 @@ struct DevOp {
     int32_t flags;               // kFlag* bits
     const float *xi;             // additive gradient term or nullptr
     const float *c;              // centre of the affine gradient model or nullptr
-    int64_t pad1;
+    uint32_t loc;                // chain kernel: where the rows come from and go to, one kLoc* code per byte:
+                                 // src_i | src_j << 8 | dst_i << 16 | dst_j << 24 (32-bit fields only: the
+                                 // record then stays in scalar registers)
+    int32_t pad1;
 };
 static_assert(sizeof(DevOp) == 64, "DevOp layout");
 
 enum : int32_t {
     kFlagListing = 1,            // jumps from the stored (pre-mix) values, Algorithm 1's listing order
-    // chain kernel only: a workgroup keeps one worker's columns in registers from one operation to the next
-    kFlagCarryIn = 2,            // row_i's columns are already in the carry registers: do not load them
-    kFlagKeepI = 4,              // row_i's columns stay in the carry registers: do not store them
-    kFlagKeepJ = 8,              // row_j's columns move to the carry registers and are not stored (gossip only)
+};
+
+// Chain kernel: where a worker's columns of the workgroup's tile are.
+enum : uint32_t {
+    kLocMemory = 0,              // the row in device memory
+    kLocCarry = 1,               // the workgroup's carry registers (from one operation to the very next)
+    kLocSlot0 = 2,               // kLocSlot0 + s: parked in LDS slot s
 };
 
 // exp(tau A) (x, xt) in increment form: with b the off-diagonal entry, x += b (xt - x) and
@@ -242,12 +248,15 @@ __global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float 
 }
 
 
+// The coefficients of one operation, as the update functions read them.
+struct OpCoef { float b_i, b_j, bp_i, bp_j, gamma, gscale; };
+
 // The d % 4 trailing columns of the rows of one operation, by lanes 0..3 of the calling workgroup, always
 // through memory (no carry).
 __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__restrict__ xt, int64_t ld, int64_t d,
                                               const DevOp &op, float alpha, float alpha_t) {
     const int64_t k = ((d >> 2) << 2) + threadIdx.x;
-    if (threadIdx.x >= 4 || k >= d) return;
+    if (threadIdx.x >= 4 || k >= d || op.kind == kOpSpill) return;
     const bool pre = (op.flags & kFlagListing) != 0;
     float *xi_row = x + (int64_t)op.row_i * ld, *xti_row = xt + (int64_t)op.row_i * ld;
     float s0 = xi_row[k], s1 = xti_row[k];
@@ -267,39 +276,52 @@ __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__re
 }
 
 // ------------------------------------------------------------------------------------------
-// Chain kernel: the walk, on a batch the host has re-ordered and annotated.  Any linear extension of
-// the per-worker orders gives the same result bit for bit (operations on disjoint rows commute
-// exactly), so the host picks one in which an operation shares a worker with its predecessor as
-// often as possible (70-80 % of the operations on the paper's graphs) and marks the shared worker: its
-// columns stay in the workgroup's registers instead of being stored by one operation and loaded again
-// by the next.  A carried gossip operation moves 16 bytes per column instead of 32, a carried gradient
-// operation 8 (+ inputs) instead of 16; the carried worker is always presented as row_i (swapping
-// the two ends of a gossip operation negates m, which changes no bit of the result).
-// The last operation of a launch keeps nothing, so memory is complete when the launch ends.
+// Chain kernel: the walk, on a programme the host has ordered and annotated (plan_chain).  Any linear
+// extension of the per-worker orders gives the same result bit for bit (operations on disjoint rows
+// commute exactly), so the host picks one in which an operation finds its workers' columns close by
+// as often as possible, and tells the kernel where each row comes from and goes to:
+//   - the carry registers: a worker shared by two consecutive operations is neither stored by the
+//     first nor loaded by the second (70-80 % of the operations on the paper's graphs).  The carried
+//     worker is always presented as row_i; swapping the two ends of a gossip operation negates m,
+//     which changes no bit of the result;
+//   - an LDS slot: a worker with a pending operation is parked (2 x 16 bytes per lane and slot) instead
+//     of stored, and read back from there; a spill pseudo-operation writes a parked worker to memory
+//     when its slot is needed for a worker that comes back sooner, and at the end of the launch;
+//   - device memory otherwise.
+// A lane only ever touches its own LDS cells, so there is no barrier.  A gossip operation that gets
+// one worker from the registers and hands one on moves 16 bytes per column instead of 32.
+// Dynamic LDS: slots * U * TPB * 32 bytes.  The d % 4 trailing columns always go through memory.
 // ------------------------------------------------------------------------------------------
-// What an operation reads besides row_i: the other worker's columns (gossip) or the gradient inputs.
-struct Partner { v4f p0, p1; };
-
-template <int U>
-__device__ __forceinline__ void load_partner(Partner (&p)[U], const DevOp &op, v4f *xs, v4f *xts, int64_t ld4,
-                                             int64_t tile0, const uint32_t (&lp)[U], const bool (&act)[U]) {
-    const v4f zero = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int u = 0; u < U; ++u) { p[u].p0 = zero; p[u].p1 = zero; }
-    if (op.kind == kOpGossip) {
-        const v4f *pj = xs + (int64_t)op.row_j * ld4, *ptj = xts + (int64_t)op.row_j * ld4;
+// The two rows (x, xt) of a worker at location loc, memory or an LDS slot, for the lanes' pieces of the tile.
+template <int U, int TPB>
+__device__ __forceinline__ void chain_fetch(uint32_t loc, int32_t row, v4f (&v)[U], v4f (&vt)[U], const v4f *xs,
+                                            const v4f *xts, int64_t ld4, const v4f *parked, const uint32_t (&lp)[U],
+                                            const bool (&act)[U]) {
+    if (loc == kLocMemory) {
+        const v4f *p = xs + (int64_t)row * ld4, *pt = xts + (int64_t)row * ld4;
 #pragma unroll
         for (int u = 0; u < U; ++u)
-            if (act[u]) { p[u].p0 = pj[lp[u]]; p[u].p1 = ptj[lp[u]]; }
-    } else if (op.kind == kOpGradient) {
-        const bool has_xi = op.xi != nullptr;
-        const bool has_c = op.c != nullptr && op.gscale != 0.f;
-        const v4f *pxi = (const v4f *)op.xi + tile0, *pc = (const v4f *)op.c + tile0;
+            if (act[u]) { v[u] = p[lp[u]]; vt[u] = pt[lp[u]]; }
+    } else {
+        const v4f *s = parked + (size_t)(loc - kLocSlot0) * (2 * U * TPB);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (has_xi && act[u]) p[u].p0 = load4<true>(pxi + lp[u]);
-            if (has_c && act[u]) p[u].p1 = load4<true>(pc + lp[u]);
-        }
+        for (int u = 0; u < U; ++u) { v[u] = s[lp[u]]; vt[u] = s[U * TPB + lp[u]]; }
+    }
+}
+
+template <int U, int TPB>
+__device__ __forceinline__ void chain_put(uint32_t loc, int32_t row, const v4f (&v)[U], const v4f (&vt)[U], v4f *xs,
+                                          v4f *xts, int64_t ld4, v4f *parked, const uint32_t (&lp)[U],
+                                          const bool (&act)[U]) {
+    if (loc == kLocMemory) {
+        v4f *p = xs + (int64_t)row * ld4, *pt = xts + (int64_t)row * ld4;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (act[u]) { p[lp[u]] = v[u]; pt[lp[u]] = vt[u]; }
+    } else {
+        v4f *s = parked + (size_t)(loc - kLocSlot0) * (2 * U * TPB);
+#pragma unroll
+        for (int u = 0; u < U; ++u) { s[lp[u]] = v[u]; s[U * TPB + lp[u]] = vt[u]; }
     }
 }
 
@@ -307,6 +329,7 @@ template <int U, int TPB>
 __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
                                                     int64_t d, const DevOp *__restrict__ ops, int32_t n_ops,
                                                     float alpha, float alpha_t) {
+    extern __shared__ v4f parked[];                      // [slot][x | xt][U][TPB]
     // a row's pieces of this tile are at (row base + tile0, a workgroup-uniform address) + lane-dependent
     // 32-bit offsets: scalar base plus vector offset, no 64-bit address arithmetic per lane
     const int64_t tile0 = (int64_t)blockIdx.x * (U * TPB);          // first float4 piece of the tile
@@ -321,57 +344,61 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
     v4f *const xs = (v4f *)x + tile0, *const xts = (v4f *)xt + tile0;
     const int64_t ld4 = ld >> 2;
     const v4f zero = {0.f, 0.f, 0.f, 0.f};
-    v4f a[U], at[U];                                     // the carried worker's columns
+    v4f a[U], at[U];                                     // row_i's columns; the carry registers between operations
 #pragma unroll
     for (int u = 0; u < U; ++u) { a[u] = zero; at[u] = zero; }
 
     for (int32_t k = 0; k < n_ops; ++k) {
-        const DevOp op = ops[k];
-        const bool pre = (op.flags & kFlagListing) != 0;
-        v4f *pi = xs + (int64_t)op.row_i * ld4, *pti = xts + (int64_t)op.row_i * ld4;
-        if (!(op.flags & kFlagCarryIn)) {
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-                if (act[u]) { a[u] = pi[lp[u]]; at[u] = pti[lp[u]]; }
+        // field by field: the record stays in scalar registers
+        const DevOp *rec = ops + k;
+        const int32_t kind = rec->kind, row_i = rec->row_i, row_j = rec->row_j;
+        const uint32_t loc = rec->loc;
+        const uint32_t src_i = loc & 255u, src_j = (loc >> 8) & 255u, dst_i = (loc >> 16) & 255u, dst_j = loc >> 24;
+        if (kind == kOpSpill) {                          // a parked worker goes back to memory
+            v4f b[U], bt[U];
+            chain_fetch<U, TPB>(src_i, row_i, b, bt, xs, xts, ld4, parked, lp, act);
+            chain_put<U, TPB>(kLocMemory, row_i, b, bt, xs, xts, ld4, parked, lp, act);
+            continue;
         }
-        Partner p[U];
-        load_partner<U>(p, op, xs, xts, ld4, tile0, lp, act);
-
-        if (op.kind == kOpGossip) {
-            v4f *pj = xs + (int64_t)op.row_j * ld4, *ptj = xts + (int64_t)op.row_j * ld4;
+        const bool pre = (rec->flags & kFlagListing) != 0;
+        const OpCoef oc = {rec->b_i, rec->b_j, rec->bp_i, rec->bp_j, rec->gamma, rec->gscale};
+        if (src_i != kLocCarry) chain_fetch<U, TPB>(src_i, row_i, a, at, xs, xts, ld4, parked, lp, act);
+        if (kind == kOpGossip) {
+            v4f b[U], bt[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) gossip_update(a[u], at[u], p[u].p0, p[u].p1, op, alpha, alpha_t, pre);
-            if (op.flags & kFlagKeepJ) {
+            for (int u = 0; u < U; ++u) { b[u] = zero; bt[u] = zero; }
+            chain_fetch<U, TPB>(src_j, row_j, b, bt, xs, xts, ld4, parked, lp, act);
 #pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
-                    a[u] = p[u].p0; at[u] = p[u].p1;
-                }
+            for (int u = 0; u < U; ++u) gossip_update(a[u], at[u], b[u], bt[u], oc, alpha, alpha_t, pre);
+            if (dst_j == kLocCarry) {
+                chain_put<U, TPB>(dst_i, row_i, a, at, xs, xts, ld4, parked, lp, act);   // never the registers as well
+#pragma unroll
+                for (int u = 0; u < U; ++u) { a[u] = b[u]; at[u] = bt[u]; }
             } else {
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (act[u]) { pj[lp[u]] = p[u].p0; ptj[lp[u]] = p[u].p1; }
-                if (!(op.flags & kFlagKeepI)) {
-#pragma unroll
-                    for (int u = 0; u < U; ++u)
-                        if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
-                }
+                chain_put<U, TPB>(dst_j, row_j, b, bt, xs, xts, ld4, parked, lp, act);
+                if (dst_i != kLocCarry) chain_put<U, TPB>(dst_i, row_i, a, at, xs, xts, ld4, parked, lp, act);
             }
         } else {
-            if (op.kind == kOpGradient) {
+            if (kind == kOpGradient) {
+                const float *xi = rec->xi, *cc = rec->c;
+                const bool has_xi = xi != nullptr;
+                const bool has_c = cc != nullptr && oc.gscale != 0.f;
+                const v4f *pxi = (const v4f *)xi + tile0, *pc = (const v4f *)cc + tile0;
+                v4f g[U], c[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) gradient_update(a[u], at[u], p[u].p0, p[u].p1, op, pre);
+                for (int u = 0; u < U; ++u) {
+                    g[u] = (has_xi && act[u]) ? load4<true>(pxi + lp[u]) : zero;
+                    c[u] = (has_c && act[u]) ? load4<true>(pc + lp[u]) : zero;
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) gradient_update(a[u], at[u], g[u], c[u], oc, pre);
             } else {
 #pragma unroll
-                for (int u = 0; u < U; ++u) mix(a[u], at[u], op.b_i);
+                for (int u = 0; u < U; ++u) mix(a[u], at[u], oc.b_i);
             }
-            if (!(op.flags & kFlagKeepI)) {
-#pragma unroll
-                for (int u = 0; u < U; ++u)
-                    if (act[u]) { pi[lp[u]] = a[u]; pti[lp[u]] = at[u]; }
-            }
+            if (dst_i != kLocCarry) chain_put<U, TPB>(dst_i, row_i, a, at, xs, xts, ld4, parked, lp, act);
         }
-        if (blockIdx.x == 0) apply_op_tail(x, xt, ld, d, op, alpha, alpha_t);
+        if (blockIdx.x == 0) apply_op_tail(x, xt, ld, d, *rec, alpha, alpha_t);
     }
 }
 
@@ -413,8 +440,6 @@ static_assert(sizeof(ResOp) == 32, "ResOp layout");
 // Gradient inputs of the launch's gradient events, in order.  A pointer with bit 0 set addresses a
 // single float (a zero) that every column reads; otherwise column k is at pointer + k.
 struct GradIn { uintptr_t xi, c; };
-
-struct OpCoef { float b_i, b_j, bp_i, bp_j, gamma, gscale; };
 
 constexpr int kStage = 16;       // LDS ring slots for gradient inputs
 

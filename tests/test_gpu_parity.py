@@ -89,6 +89,46 @@ def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
     _compare(cfg, 600, 300, cols=pu.sample_columns(cfg.d, 4096, seed=2), tuning=(unroll, nt, threads, walk))
 
 
+@pytest.mark.parametrize("name,d,slots,threads,unroll", [("C3", 4 * 256 * 5 + 2, 0, 256, 1), ("C4", 4 * 256 * 3 + 1, 1, 256, 1),
+                                                         ("C5", 4 * 128 * 7, 3, 128, 1), ("C4", 4 * 64 * 9 + 3, 16, 64, 1),
+                                                         ("C2", 4 * 512 * 4 * 2100 + 5, 2, 512, 4),
+                                                         ("C4", 4 * 1024 * 2 * 2100, 2, 1024, 2)])
+def test_chain_kernel_with_any_number_of_parking_slots(name, d, slots, threads, unroll):
+    cfg = wl.scaled(wl.CONFIGS[name], d=d, events=1500)
+    _say(f"chain slots {name} d={d} slots={slots} threads={threads} unroll={unroll}")
+    w = wl.Workload(cfg, batch_events=700)
+    w.engine.set_chain_slots(min(slots, 1))            # each call checks slots x unroll x threads x 32 B against the LDS
+    w.engine.set_tuning(unroll, 0, threads, 3)
+    w.engine.set_chain_slots(slots)
+    w.run(1500)
+    cols = np.arange(cfg.d) if cfg.d < 100000 else pu.sample_columns(cfg.d, 4096, seed=5)
+    gx, gxt = w.columns(cols)
+    st, _ = pu.oracle_run(cfg, cols, 1500)
+    assert np.array_equal(w.engine.times(), st.t)
+    ex, ext = pu.rel_err(gx, st.x), pu.rel_err(gxt, st.xt)
+    _say(f"  rel err x {ex:.3g} xt {ext:.3g}")
+    assert ex <= pu.TOL and ext <= pu.TOL
+    if w.ld != cfg.d:
+        assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
+    w.close()
+
+
+def test_chain_slots_beyond_the_lds_are_refused():
+    from paper_2306_08289_amd import A2cidError
+    cfg = wl.scaled(wl.CONFIGS["C1"], events=10)
+    w = wl.Workload(cfg)
+    with pytest.raises(A2cidError):
+        w.engine.set_chain_slots(17)
+    w.engine.set_chain_slots(16)
+    with pytest.raises(A2cidError):
+        w.engine.set_tuning(4, 0, 1024, 3)             # 16 slots x 4 x 1024 lanes x 32 B = 2 MiB of LDS
+    w.engine.set_chain_slots(1)
+    w.engine.set_tuning(4, 0, 1024, 3)                  # 128 KiB: allowed
+    with pytest.raises(A2cidError):
+        w.engine.set_chain_slots(2)                     # 256 KiB with the shape just set
+    w.close()
+
+
 @pytest.mark.parametrize("name,events,batch", [("C2", 3000, 1024), ("C3", 600, 512), ("C4", 400, 400),
                                                ("C5", 400, 400)])
 def test_full_size_configs_on_sampled_columns(name, events, batch):
@@ -211,12 +251,15 @@ def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit():
     cfg = wl.scaled(wl.CONFIGS["C5"], d=70001, events=900)
     cols = np.arange(cfg.d)
     results = []
-    for batch, tuning in [(900, None), (128, None), (512, (1, 0, 256, 1)), (300, (4, 1, 64, 0)), (77, (2, 0, 128, 1)), (450, (1, 0, 256, 2)),
-                          (900, (1, 0, 256, 3)), (211, (2, 0, 64, 3))]:
-        _say(f"batching {batch} tuning {tuning}")
+    for batch, tuning, slots in [(900, None, None), (128, None, None), (512, (1, 0, 256, 1), None),
+                                 (300, (4, 1, 64, 0), None), (77, (2, 0, 128, 1), None), (450, (1, 0, 256, 2), None),
+                                 (900, (1, 0, 256, 3), 0), (211, (2, 0, 64, 3), 5), (640, (1, 0, 128, 3), 1)]:
+        _say(f"batching {batch} tuning {tuning} slots {slots}")
         w = wl.Workload(cfg, batch_events=batch)
         if tuning:
             w.engine.set_tuning(*tuning)
+        if slots is not None:
+            w.engine.set_chain_slots(slots)
         w.run(900)
         results.append(w.columns(cols) + (w.engine.times(),))
         w.close()
