@@ -29,7 +29,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
 # size: profiles/chain_kernel_C4_hbm_counters.md and profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the
 # workload, batch size and kernel it names.
-MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 4.8261e11, ("C4", 1024, "walk_kernel"): 7.9200e11}
+MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 3.2186e11, ("C4", 1024, "walk_kernel"): 7.9200e11}
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 
@@ -205,11 +205,14 @@ def main():
     value = total_bytes / elapsed / 1e9
     roofline = None
     kernel_name = MODE_NAMES[3 if args.walk is None else args.walk]
+    # the stored counter readings belong to the default launch shape of their kernel
+    default_shape = (not args.d and args.unroll in (None, 1) and args.threads in (None, 256) and
+                     args.nontemporal in (None, 0) and args.slots in (None, 5) and not args.ld_pad)
     if launches:
         achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if not args.d else None,
+                    "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if default_shape else None,
                     "launches": launches, "avg_launch_ms": kernel_ms / launches,
                     "alg_bytes_per_launch": cnt["moved_bytes"] / launches,
                     "one_pass_bytes_per_launch": cnt["bytes"] / launches,
