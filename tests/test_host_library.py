@@ -397,3 +397,33 @@ def test_chain_programme_rejects_malformed_batches_and_accepts_empty_ones():
         binding.a2cid_plan_chain(4, binding.Batch(ops, [0, 20]))
     with pytest.raises(a2.A2cidError):
         binding.a2cid_plan_chain(4, binding.Batch(ops, [0, 20]), lds_slots=17)
+
+
+def test_chain_programme_on_arbitrary_small_batches():
+    """Property test: whatever the batch, the programme is executable and leaves memory complete."""
+    hyp = pytest.importorskip("hypothesis")
+    from hypothesis import strategies as st
+
+    @st.composite
+    def batches(draw):
+        n = draw(st.integers(1, 9))
+        m = draw(st.integers(0, 40))
+        ops = np.zeros(m, binding.OP_DTYPE)
+        for k in range(m):
+            i = draw(st.integers(0, n - 1))
+            if n == 1 or draw(st.booleans()):
+                ops["kind"][k], ops["i"][k], ops["j"][k] = binding.KIND_GRADIENT, i, -1
+                ops["xi"][k] = draw(st.sampled_from([0, 4096]))
+            else:
+                j = draw(st.integers(0, n - 2))
+                ops["kind"][k], ops["i"][k], ops["j"][k] = binding.KIND_GOSSIP, i, j + (j >= i)
+        return n, ops, draw(st.integers(0, 6))
+
+    @hyp.settings(max_examples=300, deadline=None)
+    @hyp.given(batches())
+    def check(case):
+        n, ops, slots = case
+        steps, per_col = binding.a2cid_plan_chain(n, binding.Batch(ops, [0, len(ops)]), slots)
+        assert _run_chain_programme(n, ops, steps, slots) == per_col
+
+    check()
