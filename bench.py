@@ -3,16 +3,19 @@
 
 A step is one pass of the whole path over one batch of synthetic events: the scheduler draws
 and level-packs `--batch` events, the planner validates them and computes the mixing
-coefficients and the chain order, the event kernel applies them to x and xt, and the observables
-kernel reads the state once.  Inputs (state, c_i, gradient-noise pool) are resident in HBM before timing starts;
+coefficients, the event kernel applies them to x and xt, and the observables kernel reads the
+state once.  Inputs (state, c_i, gradient-noise pool) are resident in HBM before timing starts;
 generating the per-event noise stands in for the gradient computation and is outside the path.
 
-Prints ONE JSON line: throughput in GB/s of the bytes the kernels move (per gossip event 32 d, less
-8 d for each row the chain kernel carries in registers from or to a neighbouring operation; per
-gradient event 16 d + 4 d per gradient input, less the same; 8 n d per observables call), the same
-work priced at one full pass per event (one_pass_equivalent_GBs), events/s, the roofline of the
-dominant kernel measured with HIP events on its own stream, and the CPU oracle timed on a bounded
-sample on this machine's host cores.
+Prints ONE JSON line.  The headline figures (value, roofline) belong to the walk kernel, which
+makes one full pass over the touched rows per event, so that its traffic IS the algorithmic byte
+count of the method: 32 d per gossip event, 16 d + 4 d per gradient input per gradient event
+(+ 8 n d per observables call in `value`).  The kernels that keep workers on the chip between
+events -- the chain kernel, which is the library's default, and the LDS-resident kernel -- move
+fewer bytes for the same events; they are timed on the same steps and reported as separate lines
+(`chain_variant`, `resident_variant`: events/s up, HBM GB/s down, with the bytes they move by
+construction and the same work priced at one pass per event).  Also: the copy ceiling of the
+machine, and the CPU oracle timed on a bounded sample on this machine's host cores.
 """
 import argparse
 import json
@@ -29,9 +32,15 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
 # size: profiles/chain_kernel_C4_hbm_counters.md and profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the
 # workload, batch size and kernel it names.
-MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 3.2186e11, ("C4", 1024, "walk_kernel"): 7.9200e11}
+MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 3.2738e11, ("C4", 1024, "walk_kernel"): 7.9201e11}
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
+MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
+             1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
+             2: "resident_kernel: every touched row stays in LDS for the whole batch (state read and written once "
+                "per batch)",
+             3: "chain_kernel (the library's default): events re-ordered so that a worker's columns are found in "
+                "registers or parked in LDS as often as possible"}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -124,12 +133,14 @@ def main():
     ap.add_argument("--nontemporal", type=int, default=None)
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--walk", type=int, default=None,
-                    help="event kernel: 3 = chain (default), 1 = walk in level order, 0 = one launch per level, "
-                         "2 = LDS-resident")
+                    help="event kernel of the headline line: 1 = walk, one full pass per event (default: the kernel "
+                         "whose traffic is the algorithmic byte count), 3 = chain (the library's default), "
+                         "0 = one launch per level, 2 = LDS-resident")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
+    ap.add_argument("--no-chain-leg", action="store_true", help="skip the separate chain-kernel measurement")
     ap.add_argument("--ld-pad", type=int, default=0, help="extra row pitch in units of 4 floats (layout experiments)")
     ap.add_argument("--all-configs", action="store_true",
                     help="append a short measurement of every configuration (C1..C5) to the JSON line")
@@ -149,11 +160,10 @@ def main():
         cfg = wl.scaled(cfg, d=args.d)
     torch.cuda.set_device(0)
     w = wl.Workload(cfg, device="cuda:0", batch_events=args.batch, xi_slots=32, reuse_xi=True, ld_pad=args.ld_pad)
-    tuning = (args.unroll, args.nontemporal, args.threads, args.walk)
+    mode = 1 if args.walk is None else args.walk
     if args.slots is not None:
         w.engine.set_chain_slots(args.slots)
-    if any(v is not None for v in tuning):
-        w.engine.set_tuning(*[dflt if v is None else v for v, dflt in zip(tuning, (1, 0, 256, 3))])
+    w.engine.set_tuning(args.unroll or 1, args.nontemporal or 0, args.threads or 256, mode)
     if args.group is not None or args.cols is not None:
         w.engine.set_resident_group(args.group or 8, args.cols or 1)
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
@@ -183,40 +193,50 @@ def main():
     dst.copy_(keep)
     del keep
     torch.cuda.synchronize()
-    w.engine.counters(reset=True)
-    if not args.no_profile:
-        w.engine.profile(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    cnt = w.engine.counters()
-    launches, kernel_ms = (0, 0.0)
-    if not args.no_profile:
-        launches, kernel_ms = w.engine.profile_read()
-        w.engine.profile(False)
+    # the stored counter readings belong to the default launch shape of their kernel
+    default_shape = (not args.d and args.unroll in (None, 1) and args.threads in (None, 256) and
+                     args.nontemporal in (None, 0) and args.slots in (None, 5) and not args.ld_pad)
 
-    # bytes: what the launched kernels move by construction (for the chain kernel less than one pass per event,
-    # because a worker shared by consecutive operations stays in registers); one_pass: 32 d per gossip event etc.
+    def measure(steps):
+        """Times `steps` steps with the kernel mode currently set; returns wall time, counters and, with profiling
+        on, the summed duration of the event-kernel launches (HIP events on the engine's stream)."""
+        w.engine.counters(reset=True)
+        if not args.no_profile:
+            w.engine.profile(True)
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        el = time.perf_counter() - t0
+        cnt = w.engine.counters()
+        launches, kernel_ms = (0, 0.0)
+        if not args.no_profile:
+            launches, kernel_ms = w.engine.profile_read()
+            w.engine.profile(False)
+        return el, cnt, launches, kernel_ms
+
+    def kernel_line(kernel_name, cnt, launches, kernel_ms):
+        """Roofline figures of the event kernel of one leg: bytes it moves by construction over its launch time."""
+        if not launches:
+            return None
+        achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
+        bound = "hbm" if kernel_name != "resident_kernel" else "instruction issue and LDS latency (not HBM: see frac)"
+        return {"bound": bound, "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if default_shape else None,
+                "launches": launches, "avg_launch_ms": kernel_ms / launches,
+                "alg_bytes_per_launch": cnt["moved_bytes"] / launches,
+                "one_pass_bytes_per_launch": cnt["bytes"] / launches,
+                "one_pass_equivalent_GBs": cnt["bytes"] / (kernel_ms * 1e-3) / 1e9}
+
+    elapsed, cnt, launches, kernel_ms = measure(args.steps)
+    # bytes: what the launched kernels move by construction; for the headline (walk) kernel that is one full pass
+    # per event: 32 d per gossip event, 16 d + 4 d per input per gradient event
     total_bytes = cnt["moved_bytes"] + stats_bytes * args.steps
     one_pass_bytes = cnt["bytes"] + stats_bytes * args.steps
     events = cnt["gossip"] + cnt["gradient"]
     value = total_bytes / elapsed / 1e9
-    roofline = None
-    kernel_name = MODE_NAMES[3 if args.walk is None else args.walk]
-    # the stored counter readings belong to the default launch shape of their kernel
-    default_shape = (not args.d and args.unroll in (None, 1) and args.threads in (None, 256) and
-                     args.nontemporal in (None, 0) and args.slots in (None, 5) and not args.ld_pad)
-    if launches:
-        achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                    "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                    "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if default_shape else None,
-                    "launches": launches, "avg_launch_ms": kernel_ms / launches,
-                    "alg_bytes_per_launch": cnt["moved_bytes"] / launches,
-                    "one_pass_bytes_per_launch": cnt["bytes"] / launches,
-                    "one_pass_equivalent_GBs": cnt["bytes"] / (kernel_ms * 1e-3) / 1e9}
+    roofline = kernel_line(MODE_NAMES[mode], cnt, launches, kernel_ms)
     out = {
         "metric": "achieved HBM GB/s and gossip events/s, 64 workers \u00d7 25.6M fp32 params"
                   if cfg.n == 64 and cfg.d == 25_600_000 else f"achieved HBM GB/s and gossip events/s, {cfg.name}",
@@ -225,9 +245,10 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: n={cfg.n} {cfg.topology} graph, d={cfg.d} fp32, "
                                f"{args.batch} events per step" + ("" if args.no_stats else " + one observables pass"),
+                   "kernel": MODE_WHAT[mode],
                    "eta": w.eta, "alpha": w.alpha, "alpha_tilde": w.alpha_tilde, "gamma": cfg.gamma,
-                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal, "threads": args.threads, "walk": args.walk,
-                   "slots": args.slots},
+                   "edge_rate": w.edge_rate, "unroll": args.unroll, "nontemporal": args.nontemporal,
+                   "threads": args.threads, "walk": args.walk, "slots": args.slots},
         "events_per_s": events / elapsed, "gossip_events_per_s": cnt["gossip"] / elapsed,
         "gradient_events_per_s": cnt["gradient"] / elapsed,
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
@@ -236,29 +257,32 @@ def main():
                          "what": f"plain device copy of {8.0 * src.numel() / 1e9:.2f} GB (read + write) on this machine"},
         "roofline": roofline,
     }
-    # separate line: the LDS-resident variant is bound by LDS latency and instruction issue, not by HBM, so its
-    # rate is quoted in events/s and bytes moved, never as a fraction of the HBM roofline
-    if not args.no_resident_leg and args.walk != 2 and cfg.n <= 112:
-        w.engine.set_tuning(1, 0, 256, 2)
+    # separate lines: the kernels that keep workers on the chip between events move fewer bytes than one pass per
+    # event, so their events/s go up while their HBM GB/s go down; they are never mixed into the headline figure
+    variants = []
+    if not args.no_chain_leg and mode != 3:
+        variants.append((3, "chain_variant"))
+    if not args.no_resident_leg and mode != 2 and cfg.n <= 112:
+        variants.append((2, "resident_variant"))
+    for v_mode, key in variants:
+        w.engine.set_tuning(1, 0, 256, v_mode)
         for _ in range(2):
             step()
         torch.cuda.synchronize()
-        w.engine.counters(reset=True)
-        r_steps = max(3, args.steps // 2)
-        t0 = time.perf_counter()
-        for _ in range(r_steps):
-            step()
-        torch.cuda.synchronize()
-        r_el = time.perf_counter() - t0
-        rc = w.engine.counters()
-        r_events = rc["gossip"] + rc["gradient"]
-        out["resident_variant"] = {
-            "what": "same steps with the LDS-resident kernel (state read and written once per batch)",
-            "events_per_s": r_events / r_el, "gossip_events_per_s": rc["gossip"] / r_el,
-            "ms_per_step": r_el / r_steps * 1e3, "steps": r_steps,
-            "hbm_bytes_per_step_by_construction": rc["moved_bytes"] / r_steps + stats_bytes,
-            "one_pass_bytes_per_step": rc["bytes"] / r_steps + stats_bytes,
-            "speedup_vs_headline": (r_events / r_el) / (events / elapsed)}
+        v_steps = max(3, args.steps // 2)
+        v_el, vc, v_launches, v_ms = measure(v_steps)
+        v_events = vc["gossip"] + vc["gradient"]
+        out[key] = {
+            "what": "same steps with " + MODE_WHAT[v_mode],
+            "events_per_s": v_events / v_el, "gossip_events_per_s": vc["gossip"] / v_el,
+            "ms_per_step": v_el / v_steps * 1e3, "steps": v_steps,
+            "hbm_GBs": (vc["moved_bytes"] + stats_bytes * v_steps) / v_el / 1e9,
+            "frac_of_hbm_peak": (vc["moved_bytes"] + stats_bytes * v_steps) / v_el / 1e9 / HBM_PEAK_GBS,
+            "one_pass_equivalent_GBs": (vc["bytes"] + stats_bytes * v_steps) / v_el / 1e9,
+            "hbm_bytes_per_step_by_construction": vc["moved_bytes"] / v_steps + stats_bytes,
+            "one_pass_bytes_per_step": vc["bytes"] / v_steps + stats_bytes,
+            "kernel": kernel_line(MODE_NAMES[v_mode], vc, v_launches, v_ms),
+            "speedup_vs_headline": (v_events / v_el) / (events / elapsed)}
     w.close()
     del w
     torch.cuda.empty_cache()

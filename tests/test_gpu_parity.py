@@ -129,11 +129,13 @@ def test_chain_slots_beyond_the_lds_are_refused():
     w.close()
 
 
-@pytest.mark.parametrize("name,events,batch", [("C2", 3000, 1024), ("C3", 600, 512), ("C4", 400, 400),
-                                               ("C5", 400, 400)])
-def test_full_size_configs_on_sampled_columns(name, events, batch):
+@pytest.mark.parametrize("name,events,batch,mode", [("C2", 3000, 1024, 3), ("C3", 600, 512, 3), ("C4", 400, 400, 3),
+                                                    ("C5", 400, 400, 3), ("C4", 2048, 1024, 1), ("C4", 2048, 1024, 3),
+                                                    ("C3", 1024, 1024, 1)])
+def test_full_size_configs_on_sampled_columns(name, events, batch, mode):
+    # the launch shapes the benchmark times: 1024 events per batch, walk (mode 1) and chain (mode 3) kernels
     cfg = wl.scaled(wl.CONFIGS[name], events=events)
-    _compare(cfg, events, batch, cols=pu.sample_columns(cfg.d, 4096, seed=1))
+    _compare(cfg, events, batch, cols=pu.sample_columns(cfg.d, 4096, seed=1), tuning=(1, 0, 256, mode))
 
 
 def test_trailing_mix_is_fused_into_each_workers_last_operation():
