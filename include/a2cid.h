@@ -104,9 +104,11 @@ typedef struct {
 
 /* A batch of events arranged in levels.  ops[level_off[l] .. level_off[l+1]) is level l;
  * level_off has n_levels + 1 entries, level_off[0] = 0, level_off[n_levels] = n_ops.
- * Operations of one level must touch pairwise distinct workers (a matching plus singletons);
- * levels are applied in order, so each worker meets its events in the order given.  Times
- * must be non-decreasing per worker (across batches too).  All host pointers, borrowed for
+ * Operations of one level must touch pairwise distinct workers (a matching plus singletons).
+ * Every worker meets its events in the order given; operations on distinct workers commute
+ * exactly, and the library is free to interleave them in any order that respects this (mode 0
+ * applies level after level, the other modes walk the batch per column tile: a2cid_set_tuning).
+ * Times must be non-decreasing per worker (across batches too).  All host pointers, borrowed for
  * the call.
  *   t_sync  if finite: after its last operation in this batch every worker touched by the
  *           batch is additionally mixed up to t_sync (fused into that operation's pass, the
