@@ -256,10 +256,17 @@ int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
  * as such pairs exist (a gossip event at that moment; both partners are then busy for comm_time).
  * Simultaneous completions are ordered (time, averaging-end before step-end, worker).  The graph's
  * rates are ignored.  Streams: Philox4x32-10 as for a2cid_sched_create with counter tags
- * 0x0A2C1D21 (durations) and 0x0A2C1D22 (Poisson counts, product-of-uniforms method).  The
+ * 0x0A2C1D21 (durations) and 0x0A2C1D22 (Poisson counts, product-of-uniforms method).
+ * normalize != 0 stamps the events with normalised time instead of real time, as the same section
+ * describes (a running average of the duration of the previous gradient steps normalises time, so
+ * that a gradient step takes one unit as the analysis assumes): the stamp advances by (real time
+ * elapsed) / (average duration of all gradient steps completed so far, by any worker; before the
+ * first completion: the mean of 1 / node_rate[i]); a step's duration enters the average after the
+ * events of its own completion are stamped.  Durations and comm_time stay in real time.  The
  * returned scheduler is used with a2cid_sched_next / skip / counts / destroy like any other. */
 int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *graph, const double *node_rate,
-                           double comm_per_grad, double comm_time, double jitter, uint64_t seed);
+                           double comm_per_grad, double comm_time, double jitter, int32_t normalize,
+                           uint64_t seed);
 
 /* Takes the next max_events events of the serial stream and packs them into levels: an
  * event's level is one more than the highest level of an earlier event of this batch sharing

@@ -14,7 +14,13 @@ Reading used (the paper describes the mechanism in prose only):
     the first later worker that is its neighbour in the graph, as long as such pairs exist; a pairing at
     time t is the gossip event (t, i, j), costs each partner one of its pending averagings and keeps both
     busy until t + comm_time;
-  * simultaneous completions are handled in order (time, communication-end before gradient-end, worker id).
+  * simultaneous completions are handled in order (time, communication-end before gradient-end, worker id);
+  * normalize=True (the same section: a running average of the duration of the previous gradient steps
+    normalises time, so that a gradient step takes one unit as the analysis assumes): events are stamped with
+    the normalised time T, which advances by (real time elapsed) / (average duration of all gradient steps
+    completed so far, by any worker); before the first completion the average is the mean of 1 / rate_i.  A
+    step's duration enters the average after the events of its own completion are stamped.  Durations and
+    communication times stay in real time; only the stamps change.
 
 Random numbers: Philox4x32-10, key = (seed_lo, seed_hi), counter = (draw_lo, draw_hi, worker, tag) with
 tag 0x0A2C1D21 for step durations and 0x0A2C1D22 for the Poisson counts; a uniform is the 53-bit value
@@ -53,7 +59,7 @@ def _poisson(stream, mean):
             return k - 1
 
 
-def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_events):
+def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_events, normalize=False):
     """Returns core.Events (clock = worker for gradient events, n + edge index for gossip events)."""
     edge_index = {}
     for e, (a, b) in enumerate(edges):
@@ -65,10 +71,16 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
     busy = [False] * n
     queue = []                                   # available workers, oldest first
     heap = []                                    # (time, kind: 0 communication end / 1 gradient end, worker)
+    running = [0.0] * n                          # duration of the gradient step each worker is in
     for i in range(n):
         if node_rate[i] > 0:
-            heapq.heappush(heap, ((1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0)), 1, i))
+            running[i] = (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0))
+            heapq.heappush(heap, (running[i], 1, i))
     out_t, out_kind, out_i, out_j, out_clock = [], [], [], [], []
+    active = [1.0 / node_rate[i] for i in range(n) if node_rate[i] > 0]
+    unit = sum(active) / len(active) if active else 1.0      # average gradient-step duration so far
+    dur_sum, dur_n = 0.0, 0
+    t_norm, real_last = 0.0, 0.0
 
     def join(i):
         if not busy[i] and todo[i] > 0 and i not in queue:
@@ -90,22 +102,33 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
             del queue[found[1]]
             del queue[found[0]]
             e = edge_index[(a, b)]
-            out_t.append(t); out_kind.append(1); out_i.append(edges[e][0]); out_j.append(edges[e][1])
+            out_t.append(stamp(t)); out_kind.append(1); out_i.append(edges[e][0]); out_j.append(edges[e][1])
             out_clock.append(n + e)
             for w in (a, b):
                 todo[w] -= 1
                 busy[w] = True
                 heapq.heappush(heap, (t + comm_time, 0, w))
 
+    def stamp(t):
+        return t_norm if normalize else t
+
     while heap and len(out_t) < n_events:
         t, kind, i = heapq.heappop(heap)
+        t_norm += (t - real_last) / unit
+        real_last = t
         if kind == 0:
             busy[i] = False
         else:
-            out_t.append(t); out_kind.append(0); out_i.append(i); out_j.append(-1); out_clock.append(i)
+            out_t.append(stamp(t)); out_kind.append(0); out_i.append(i); out_j.append(-1); out_clock.append(i)
             todo[i] += _poisson(cnt[i], comm_per_grad)
-            heapq.heappush(heap, (t + (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0)), 1, i))
+            finished = running[i]
+            running[i] = (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0))
+            heapq.heappush(heap, (t + running[i], 1, i))
         join(i)
         match(t)
+        if kind == 1:                            # the finished step counts from the next interval on
+            dur_sum += finished
+            dur_n += 1
+            unit = dur_sum / dur_n
     return core.Events(np.array(out_t), np.array(out_kind, np.int32), np.array(out_i, np.int32),
                        np.array(out_j, np.int32), np.array(out_clock, np.int32))

@@ -80,7 +80,7 @@ SIGNATURES = {
                                    _P(a2cid_event_batch), C.c_void_p]),
     "a2cid_sched_create": (C.c_int, [_P(C.c_void_p), C.c_int32, _P(a2cid_graph), _P(C.c_double), C.c_uint64]),
     "a2cid_sched_create_fifo": (C.c_int, [_P(C.c_void_p), C.c_int32, _P(a2cid_graph), _P(C.c_double), C.c_double,
-                                          C.c_double, C.c_double, C.c_uint64]),
+                                          C.c_double, C.c_double, C.c_int32, C.c_uint64]),
     "a2cid_sched_next": (C.c_int, [C.c_void_p, C.c_int64, _P(a2cid_event_batch)]),
     "a2cid_sched_skip": (C.c_int, [C.c_void_p, C.c_int64]),
     "a2cid_sched_counts": (C.c_int, [C.c_void_p, _P(C.c_int64)]),
@@ -202,7 +202,7 @@ class Scheduler:
     """a2cid_sched_*: seeded Poisson clocks -> serial stream -> level-packed batches."""
 
     def __init__(self, n, u, v, edge_rate, node_rate, seed, fifo=None):
-        """fifo = None: Poisson clocks per node and edge; fifo = dict(comm_per_grad, comm_time, jitter): the
+        """fifo = None: Poisson clocks per node and edge; fifo = dict(comm_per_grad, comm_time, jitter[, normalize]): the
         first-in-first-out pairing source (edge rates are then ignored)."""
         self._g = _GraphArg(u, v, edge_rate)
         self.n = n
@@ -214,7 +214,8 @@ class Scheduler:
         else:
             _check(load().a2cid_sched_create_fifo(C.byref(self._h), n, C.byref(self._g.struct), _dptr(nr),
                                                   float(fifo["comm_per_grad"]), float(fifo["comm_time"]),
-                                                  float(fifo["jitter"]), int(seed)))
+                                                  float(fifo["jitter"]), int(bool(fifo.get("normalize", False))),
+                                                  int(seed)))
 
     def next(self, max_events):
         """Next batch as a `Batch` (copied out of the scheduler's storage)."""

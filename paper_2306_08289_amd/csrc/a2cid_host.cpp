@@ -323,6 +323,12 @@ struct a2cid_sched {
     using Completion = std::tuple<double, int32_t, int32_t>;   // (time, 0 averaging ends / 1 step ends, worker)
     std::priority_queue<Completion, std::vector<Completion>, std::greater<Completion>> completions;
     std::deque<a2cid_op> emitted;                // events produced by the last completion, not yet handed out
+    // normalised clock: time advances by (real time elapsed) / (average duration of the gradient steps completed
+    // so far), so that a gradient step takes one unit of it
+    bool normalize = false;
+    double unit = 1.0, dur_sum = 0.0, t_norm = 0.0, real_last = 0.0;
+    int64_t dur_n = 0;
+    std::vector<double> running;                 // duration of the gradient step each worker is in
 
     double uniform(uint64_t k, uint32_t stream, uint32_t tag) const {
         uint32_t c[4] = {(uint32_t)k, (uint32_t)(k >> 32), stream, tag};
@@ -368,12 +374,18 @@ struct a2cid_sched {
         if (completions.empty()) return false;
         const auto [t, what, w] = completions.top();
         completions.pop();
+        t_norm += (t - real_last) / unit;
+        real_last = t;
+        const double stamp = normalize ? t_norm : t;
+        double finished = 0.0;
         if (what == 0) {
             busy[w] = 0;
         } else {
-            emit(t, A2CID_KIND_GRADIENT, w, -1, w);
+            emit(stamp, A2CID_KIND_GRADIENT, w, -1, w);
             todo[w] += comm_count(w);
-            completions.emplace(t + step_time(w), 1, w);
+            finished = running[w];
+            running[w] = step_time(w);
+            completions.emplace(t + running[w], 1, w);
         }
         if (!busy[w] && todo[w] > 0 && !queued[w]) { waiting.push_back(w); queued[w] = 1; }
         // the coordinator: oldest available worker first, with the oldest available neighbour of it
@@ -389,13 +401,18 @@ struct a2cid_sched {
             waiting.erase(waiting.begin() + (std::ptrdiff_t)pb);
             waiting.erase(waiting.begin() + (std::ptrdiff_t)pa);
             const int32_t e = edge_of[(size_t)a * g.n + b];
-            emit(t, A2CID_KIND_GOSSIP, g.u[e], g.v[e], g.n + e);
+            emit(stamp, A2CID_KIND_GOSSIP, g.u[e], g.v[e], g.n + e);
             for (int32_t m : {a, b}) {
                 --todo[m];
                 busy[m] = 1;
                 queued[m] = 0;
                 completions.emplace(t + comm_time, 0, m);
             }
+        }
+        if (what == 1) {                         // the finished step counts from the next interval on
+            dur_sum += finished;
+            ++dur_n;
+            unit = dur_sum / (double)dur_n;
         }
         return true;
     }
@@ -722,7 +739,7 @@ int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
 }
 
 int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *graph, const double *node_rate,
-                           double comm_per_grad, double comm_time, double jitter, uint64_t seed) {
+                           double comm_per_grad, double comm_time, double jitter, int32_t normalize, uint64_t seed) {
     clear_error();
     if (!out || !node_rate) return fail(A2CID_EINVAL, "out / node_rate is NULL");
     *out = nullptr;
@@ -758,8 +775,18 @@ int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *gra
             s->edge_of[(size_t)s->g.u[e] * n + s->g.v[e]] = (int32_t)e;
             s->edge_of[(size_t)s->g.v[e] * n + s->g.u[e]] = (int32_t)e;
         }
-        for (int32_t i = 0; i < n; ++i)
-            if (s->rate[i] > 0.0) s->completions.emplace(s->step_time(i), 1, i);
+        s->normalize = normalize != 0;
+        s->running.assign(n, 0.0);
+        double nominal = 0.0;
+        int32_t active = 0;
+        for (int32_t i = 0; i < n; ++i) {
+            if (!(s->rate[i] > 0.0)) continue;
+            s->running[i] = s->step_time(i);
+            s->completions.emplace(s->running[i], 1, i);
+            nominal += 1.0 / s->rate[i];
+            ++active;
+        }
+        s->unit = active > 0 ? nominal / (double)active : 1.0;
     } catch (const std::bad_alloc &) {
         delete s;
         return fail(A2CID_ENOMEM, "out of host memory");

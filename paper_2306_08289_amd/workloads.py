@@ -37,9 +37,11 @@ def edge_list(topology, n):
 
 def fifo_edge_rate(cfg, fifo):
     """Per-edge rate equivalent to every worker doing comm_per_grad averagings per gradient step with peers chosen
-    uniformly among its neighbours: n * comm_per_grad * mean(node rate) / 2 communications per unit time."""
+    uniformly among its neighbours: n * comm_per_grad * (gradient steps per worker and unit time) / 2 communications
+    per unit time.  With the normalised clock a worker makes one gradient step per unit time."""
     node, _ = clock_rates(cfg)
-    return cfg.n * fifo["comm_per_grad"] * float(node.mean()) / 2.0 / len(edge_list(cfg.topology, cfg.n))
+    steps_per_unit_time = 1.0 if fifo.get("normalize") else float(node.mean())
+    return cfg.n * fifo["comm_per_grad"] * steps_per_unit_time / 2.0 / len(edge_list(cfg.topology, cfg.n))
 
 
 def grad_fraction(cfg):

@@ -26,7 +26,8 @@ def oracle_params(cfg, fifo=None):
     edges = getattr(graph, cfg.topology)(cfg.n)
     node_rate, edge_rate = wl.clock_rates(cfg)
     if fifo is not None:
-        edge_rate = graph.per_worker_to_edge_rate(cfg.n, edges, fifo["comm_per_grad"] * float(node_rate.mean()))
+        steps_per_unit_time = 1.0 if fifo.get("normalize") else float(node_rate.mean())
+        edge_rate = graph.per_worker_to_edge_rate(cfg.n, edges, fifo["comm_per_grad"] * steps_per_unit_time)
     if cfg.accelerated:
         p = graph.acid_params(cfg.n, edges, edge_rate)
         eta, alpha_t = p["eta"], p["alpha_tilde"]
@@ -57,7 +58,8 @@ class OracleStream:
         if self.fifo is not None:
             from oracle import fifo as fifo_source
             self.events = fifo_source.generate(self.cfg.n, self.edges, self.node_rate, self.fifo["comm_per_grad"],
-                                               self.fifo["comm_time"], self.fifo["jitter"], self.cfg.seed, n_events)
+                                               self.fifo["comm_time"], self.fifo["jitter"], self.cfg.seed, n_events,
+                                               normalize=bool(self.fifo.get("normalize", False)))
             return self.events
         self.events = core.generate_events(self.cfg.n, [e[0] for e in self.edges], [e[1] for e in self.edges],
                                            self.node_rate, np.full(len(self.edges), self.edge_rate), self.cfg.seed,

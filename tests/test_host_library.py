@@ -203,17 +203,19 @@ def test_empty_batch_is_fine():
 
 
 # ------------------------------------------------------------------ first-in-first-out pairing source
+@pytest.mark.parametrize("normalize", [False, True])
 @pytest.mark.parametrize("topo,n,rho,comm_time,jitter,seed", [
     ("ring", 16, 1.0, 0.05, 0.2, 3), ("exponential", 64, 1.0, 0.02, 0.1, (5 << 32) + 1),
     ("complete", 8, 2.0, 0.0, 0.0, 7), ("ring", 64, 2.0, 0.01, 0.5, 11)])
-def test_fifo_schedule_is_bit_identical_to_the_oracle_stream(topo, n, rho, comm_time, jitter, seed):
+def test_fifo_schedule_is_bit_identical_to_the_oracle_stream(topo, n, rho, comm_time, jitter, seed, normalize):
     from oracle import fifo
     edges = getattr(graph, topo)(n)
     u, v = _uv(edges)
     rate = np.exp(0.3 * np.random.default_rng(2).normal(size=n)) if jitter > 0 else np.ones(n)
     m = 6000
-    ref = fifo.generate(n, edges, rate, rho, comm_time, jitter, seed, m)
-    s = a2.Scheduler(n, u, v, 1.0, rate, seed, fifo=dict(comm_per_grad=rho, comm_time=comm_time, jitter=jitter))
+    ref = fifo.generate(n, edges, rate, rho, comm_time, jitter, seed, m, normalize=normalize)
+    s = a2.Scheduler(n, u, v, 1.0, rate, seed, fifo=dict(comm_per_grad=rho, comm_time=comm_time, jitter=jitter,
+                                                         normalize=normalize))
     got = [s.next(1500) for _ in range(4)]
     ref_batches = levels.pack(ref.kind, ref.i, ref.j, 1500)
     for b, rb in zip(got, ref_batches):

@@ -80,3 +80,52 @@ def test_prefix_and_seed():
     _, c = _run(8, "ring", 1.0, 1.0, 0.05, 0.2, 8, 1000)
     assert np.array_equal(a.t[:1000], b.t) and np.array_equal(a.clock[:1000], b.clock)
     assert not np.array_equal(b.t, c.t)
+
+
+# ---- normalised clock (a running average of the gradient-step durations normalises time) -----------
+
+def test_normalised_clock_is_a_reparametrisation_with_one_gradient_step_per_unit_time():
+    n, edges = 8, graph.ring(8)
+    # identical workers, no jitter: every step lasts 1 / r, so normalised time is exactly r x real time and the
+    # k-th gradient step of every worker ends at k, whatever r is (the unit-time gradient process of the analysis)
+    for r in (0.25, 2.0, 7.0):
+        real = fifo.generate(n, edges, np.full(n, r), 1.5, 0.01 / r, 0.0, 3, 3000)
+        norm = fifo.generate(n, edges, np.full(n, r), 1.5, 0.01 / r, 0.0, 3, 3000, normalize=True)
+        assert np.array_equal(real.kind, norm.kind) and np.array_equal(real.i, norm.i) and np.array_equal(real.j, norm.j)
+        assert np.allclose(norm.t, r * real.t, rtol=1e-12, atol=0)
+        for w in range(n):
+            ends = norm.t[(norm.kind == 0) & (norm.i == w)]
+            assert np.allclose(ends, np.arange(1, len(ends) + 1), rtol=1e-9)
+    # the stream does not depend on the time unit at all: scaling every rate and comm_time scales real time only
+    a = fifo.generate(n, edges, np.full(n, 0.25), 1.5, 0.04, 0.0, 3, 3000, normalize=True)
+    b = fifo.generate(n, edges, np.full(n, 2.0), 1.5, 0.005, 0.0, 3, 3000, normalize=True)
+    assert np.array_equal(a.kind, b.kind) and np.array_equal(a.i, b.i) and np.allclose(a.t, b.t, rtol=1e-12)
+
+
+def test_normalised_clock_with_unequal_workers():
+    n, edges = 12, graph.exponential(12)
+    rate = np.array([0.4, 0.7, 1.0, 1.0, 1.3, 2.0, 2.5, 3.0, 0.9, 1.1, 1.6, 0.5])
+    real = fifo.generate(n, edges, rate, 1.0, 0.02, 0.3, 9, 30000)
+    norm = fifo.generate(n, edges, rate, 1.0, 0.02, 0.3, 9, 30000, normalize=True)
+    # only the stamps change: same events in the same order, stamps non-decreasing, equal real times stay equal
+    assert np.array_equal(real.kind, norm.kind) and np.array_equal(real.i, norm.i) and np.array_equal(real.j, norm.j)
+    assert np.all(np.diff(norm.t) >= 0)
+    assert np.array_equal(np.diff(real.t) == 0, np.diff(norm.t) == 0)
+    # in normalised time the workers together complete one gradient step per worker and unit time
+    grads = (norm.kind == 0).sum()
+    assert abs(grads / (n * norm.t[-1]) - 1.0) < 0.01
+    # before the first completion the unit is the mean nominal duration; afterwards the running average: recompute
+    # the first few stamps by hand from the real stream
+    unit = np.mean(1.0 / rate)
+    done, t_norm, last = [], 0.0, 0.0
+    step_start = np.zeros(n)
+    for k in range(200):
+        t_norm += (real.t[k] - last) / unit
+        last = real.t[k]
+        assert np.isclose(norm.t[k], t_norm, rtol=1e-12)
+        if real.kind[k] == 0:
+            done.append(real.t[k] - step_start[real.i[k]])
+            step_start[real.i[k]] = real.t[k]
+            # averaging ends between events move the clock too but never change the unit, so applying the new unit
+            # from this event on is the same thing
+            unit = np.mean(done)
