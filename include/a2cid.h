@@ -217,8 +217,9 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
  * A step with op >= 0 applies batch->ops[op] with its workers presented as (row_i, row_j) (row_j = -1
  * for a gradient event; the carried worker is always row_i), reads them from src_i / src_j and leaves
  * them in dst_i / dst_j.  A step with op = -1 writes the worker row_i parked in slot src_i back to
- * memory.  After the last step every worker's columns are in memory.
- * steps (capacity entries; 3 n_ops + lds_slots always suffice) may be NULL to query *n_steps only;
+ * memory.  After the last step every worker's columns are in memory (a worker's last operation
+ * of the batch always leaves it there).
+ * steps (capacity entries; 3 n_ops always suffice) may be NULL to query *n_steps only;
  * *bytes_per_column (may be NULL) receives what the launch moves per column: 8 per row read from or
  * written to memory, 4 per gradient input read.  Only kinds, worker indices and the xi / c / gscale
  * fields of the operations are read (the level table is not).  0 <= lds_slots <= 16.

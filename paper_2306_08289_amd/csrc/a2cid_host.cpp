@@ -593,9 +593,10 @@ void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots
         if (s.recent.size() > kChainRecent) s.recent.resize(kChainRecent);
     }
     close_prev(nullptr, 0);
+    // a worker is parked only while an operation of it is pending, and by now none is: the slots are empty
     for (int32_t q = 0; q < lds_slots; ++q) {
         if (s.owner[q] < 0) continue;
-        a2cid_chain_step spill{};
+        a2cid_chain_step spill{};                // guard: never reached
         spill.op = -1;
         spill.row_i = s.owner[q];
         spill.row_j = -1;

@@ -59,7 +59,8 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
 //   - a worker that the next operation uses stays in the carry registers; another worker with a pending
 //     operation is parked if a slot is free or holds a worker whose next operation comes later in the batch
 //     (that worker is written back first: a spill step); everything else goes to memory;
-//   - after the last operation every parked worker is written back, so memory is complete when the launch ends.
+//   - a worker is parked only while it has a pending operation and goes to memory after its last one, so
+//     memory is complete when the launch ends.
 struct ChainPlan {
     std::vector<a2cid_chain_step> steps;
     double bytes_per_column = 0.0;      // what the launch moves: 8 per row read from or written to memory, 4 per input

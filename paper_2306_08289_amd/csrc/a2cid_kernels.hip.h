@@ -286,7 +286,8 @@ __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__re
 //     which changes no bit of the result;
 //   - an LDS slot: a worker with a pending operation is parked (2 x 16 bytes per lane and slot) instead
 //     of stored, and read back from there; a spill pseudo-operation writes a parked worker to memory
-//     when its slot is needed for a worker that comes back sooner, and at the end of the launch;
+//     when its slot is needed for a worker that comes back sooner (a worker's last operation of the
+//     launch always leaves it in memory);
 //   - device memory otherwise.
 // A lane only ever touches its own LDS cells, so there is no barrier.  A gossip operation that gets
 // one worker from the registers and hands one on moves 16 bytes per column instead of 32.
