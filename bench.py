@@ -49,7 +49,7 @@ def cpu_baseline(cfg, seconds_budget=20.0):
     sys.path.insert(0, os.path.join(ROOT, "tests"))
     import parity_util as pu
     from oracle import core
-    d_slice, n_events = 250_000, 400
+    d_slice, n_events = min(250_000, cfg.d), 400
     edges, node_rate, edge_rate, eta, alpha, alpha_t = pu.oracle_params(cfg)
     ev = core.generate_events(cfg.n, [e[0] for e in edges], [e[1] for e in edges], node_rate,
                               np.full(len(edges), edge_rate), cfg.seed, n_events)
@@ -118,6 +118,7 @@ def short_run(name, batch, steps=6, warmup=2):
     w.close()
     del w
     torch.cuda.empty_cache()
+    res["cpu_oracle"] = cpu_baseline(cfg, seconds_budget=6.0)
     return res
 
 
