@@ -22,9 +22,14 @@
  *     reduction partials) that lives as long as the context.
  *   - All work is enqueued on the HIP stream given at creation.  a2cid_apply_events and
  *     a2cid_flush return as soon as the work is enqueued; a2cid_stats waits for its result.
- *   - Every function returns A2CID_OK (0) or a negative A2CID_E* code; on failure nothing has
- *     been applied and a2cid_last_error() (thread-local) describes the cause.  No exception,
- *     abort or signal crosses this boundary.
+ *   - Every function returns A2CID_OK (0) or a negative A2CID_E* code and a2cid_last_error()
+ *     (thread-local) describes the cause.  Everything a call can check -- arguments, batch
+ *     structure, time order, pointers, sizes -- is checked before the call enqueues anything or
+ *     moves a time stamp, so a call that fails one of these checks has applied nothing.  If a HIP
+ *     call fails after that point, part of the work may already be in the stream while the time
+ *     stamps were not advanced: the context is then marked unusable and every later
+ *     a2cid_apply_events / flush / stats / average on it returns A2CID_EHIP.  No exception, abort
+ *     or signal crosses this boundary.
  *   - A context must not be used from two threads at once.
  */
 #ifndef A2CID_H
@@ -152,8 +157,9 @@ int a2cid_graph_params(const a2cid_graph *graph, int32_t n,
 /* ---- engine ---------------------------------------------------------------------------- */
 
 /* Creates a context for n workers (2 <= n <= A2CID_MAX_WORKERS) of d >= 1 parameters on the
- * current HIP device, which must own x and xt (checked: a2cid_check_device_span).  eta >= 0, alpha, alpha_tilde finite (Eq. (1); "time-independent scalar
- * hyper-parameters").  All t_i start at 0 (Algorithm 1, initialisation).  The graph is copied. */
+ * current HIP device, which must own x and xt (checked: a2cid_check_device_span).  eta >= 0,
+ * alpha and alpha_tilde finite: the three constants of Eq. (1), fixed for the life of the context.
+ * All t_i start at 0 (Algorithm 1, initialisation).  The graph is copied. */
 int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph,
                  double eta, double alpha, double alpha_tilde, const a2cid_buffers *buf);
 
@@ -182,8 +188,8 @@ int a2cid_stats(a2cid_ctx *ctx, double t_now, a2cid_stats_out *out);
  * Algorithm 1 returns at its final time. */
 int a2cid_flush(a2cid_ctx *ctx, double t_now);
 
-/* Consensus step of the experimental protocol ("one All-Reduce averaging is performed before and
- * after the training", section "Experimental Setup"): mixes every worker up to t_now
+/* Consensus step of the experimental protocol (section "Experimental Setup": the workers are
+ * averaged once before and once after training): mixes every worker up to t_now
  * (>= max_i t_i), then replaces every x_i by the mean of the x_j and every xt_i by the mean of the
  * xt_j, and sets all t_i = t_now.  Both means, hence Eq. (2)'s tracker, are unchanged by it; the
  * consensus distances become 0.  Asynchronous like a2cid_flush (16 n d bytes). */
@@ -223,7 +229,7 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
  * *bytes_per_column (may be NULL) receives what the launch moves per column: 8 per row read from or
  * written to memory, 4 per gradient input read.  Only kinds, worker indices and the xi / c / gscale
  * fields of the operations are read (the level table is not).  0 <= lds_slots <= 16.
- * a2cid_apply_events plans pieces of at most 5461 operations (whole levels) independently. */
+ * a2cid_apply_events plans pieces of at most 5456 operations (whole levels) independently. */
 #define A2CID_LOC_MEMORY 0
 #define A2CID_LOC_CARRY  1
 #define A2CID_LOC_SLOT0  2
@@ -329,7 +335,8 @@ int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t
  * A2CID_OK if [p, p + bytes) is device (or managed) memory of the context's GPU that does not run
  * past the end of its allocation, A2CID_EINVAL otherwise (a host pointer, another GPU's memory, a
  * span longer than what was allocated).  It sees allocations, not tensors: a span inside a
- * larger allocation, such as a caching allocator's segment, passes.  Launches nothing. */
+ * larger allocation, such as a caching allocator's segment, passes.  The runtime is asked on every
+ * call (a2cid_apply_events asks once per allocation and batch).  Launches nothing. */
 int a2cid_check_device_span(a2cid_ctx *ctx, const void *p, int64_t bytes);
 
 /* Measurement aid, independent of any context: enqueues a plain copy of n floats (n a multiple

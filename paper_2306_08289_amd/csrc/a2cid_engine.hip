@@ -37,6 +37,14 @@ struct Slot {
     bool in_flight = false;
 };
 
+// Pinned staging for the n pending mixing coefficients that a2cid_stats and a2cid_average upload: two buffers, each
+// guarded by an event, so that a call never has to wait for the stream before it may write the next set.
+struct CoefStage {
+    float *host = nullptr;              // pinned, n floats
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+
 struct TimedLaunch {
     hipEvent_t start, stop;
 };
@@ -73,8 +81,11 @@ struct a2cid_ctx {
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
+    bool failed = false;                // an enqueueing step failed half-way: device state and time stamps disagree
     // observables scratch
-    float *b_host = nullptr, *b_dev = nullptr;
+    CoefStage coef_stage[2];
+    int next_coef_stage = 0;
+    float *b_dev = nullptr;
     double *partials = nullptr, *out_dev = nullptr, *out_host = nullptr;
     // counters since creation (or the last a2cid_counters_reset)
     int64_t n_gossip = 0, n_grad = 0, n_launch = 0;
@@ -100,15 +111,21 @@ int enter(const a2cid_ctx *c) {
     return A2CID_OK;
 }
 
+int unusable(const a2cid_ctx *c) {
+    if (!c->failed) return A2CID_OK;
+    return fail(A2CID_EHIP, "the context is unusable: an earlier call failed after part of its work had been enqueued, "
+                "so the device state and the time stamps no longer belong together");
+}
+
 // Turns a pointer that the kernels would fault on into an error: [p, p + bytes) has to be device (or managed)
-// memory of the context's GPU and must not run past the end of its allocation.  Allocations that passed are
-// remembered, so the runtime is asked once per allocation, not once per operation.  The check sees allocations,
-// not tensors: a span that stays inside a larger allocation (a caching allocator's segment) passes.
-int check_device_span(a2cid_ctx *c, const void *p, size_t bytes, const char *what) {
+// memory of the context's GPU and must not run past the end of its allocation.  Asks the runtime; allocates
+// nothing.  On success *span (may be NULL) receives the extent of the allocation, or an empty span when the
+// runtime knows the pointer but not its extent.  The check sees allocations, not tensors: a span that stays
+// inside a larger allocation (a caching allocator's segment) passes.
+int query_device_span(const a2cid_ctx *c, const void *p, size_t bytes, const char *what, DevSpan *span) {
     const uintptr_t lo = (uintptr_t)p, hi = lo + bytes;
+    if (span) *span = DevSpan{0, 0};
     if (hi < lo) return fail(A2CID_EINVAL, "%s: %zu bytes from %p wrap the address space", what, bytes, p);
-    for (const DevSpan &k : c->known)
-        if (k.lo <= lo && hi <= k.hi) return A2CID_OK;
     hipPointerAttribute_t attr;
     std::memset(&attr, 0, sizeof(attr));
     if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
@@ -130,8 +147,34 @@ int check_device_span(a2cid_ctx *c, const void *p, size_t bytes, const char *wha
     if (lo < blo || hi > bhi)
         return fail(A2CID_EINVAL, "%s: %zu bytes from %p run past the end of the allocation (%zu bytes at %p)", what,
                     bytes, p, size, (void *)base);
-    if (c->known.size() >= kKnownSpans) c->known.clear();
-    c->known.push_back({blo, bhi});
+    if (span) *span = DevSpan{blo, bhi};
+    return A2CID_OK;
+}
+
+// The same check with a memory: allocations that passed are remembered, so the runtime is asked once per
+// allocation, not once per operation.  The memory lasts for one call of the library only (the caller of this
+// function clears c->known first): an allocation freed and replaced between two calls is looked at again.
+int check_device_span(a2cid_ctx *c, const void *p, size_t bytes, const char *what) {
+    const uintptr_t lo = (uintptr_t)p, hi = lo + bytes;
+    for (const DevSpan &k : c->known)
+        if (k.lo <= lo && lo <= hi && hi <= k.hi) return A2CID_OK;
+    DevSpan span;
+    if (int rc = query_device_span(c, p, bytes, what, &span)) return rc;
+    if (span.hi > span.lo) {
+        if (c->known.size() >= kKnownSpans) c->known.clear();
+        c->known.push_back(span);
+    }
+    return A2CID_OK;
+}
+
+int acquire_coef_stage(a2cid_ctx *c, CoefStage **out) {
+    CoefStage &s = c->coef_stage[c->next_coef_stage];
+    c->next_coef_stage ^= 1;
+    if (s.in_flight) {
+        A2CID_HIP(hipEventSynchronize(s.done));
+        s.in_flight = false;
+    }
+    *out = &s;
     return A2CID_OK;
 }
 
@@ -308,7 +351,10 @@ void a2cid_destroy(a2cid_ctx *c) {
         if (s.gin_dev) (void)hipFree(s.gin_dev);
         if (s.done) (void)hipEventDestroy(s.done);
     }
-    if (c->b_host) (void)hipHostFree(c->b_host);
+    for (CoefStage &cs : c->coef_stage) {
+        if (cs.host) (void)hipHostFree(cs.host);
+        if (cs.done) (void)hipEventDestroy(cs.done);
+    }
     if (c->b_dev) (void)hipFree(c->b_dev);
     if (c->partials) (void)hipFree(c->partials);
     if (c->out_dev) (void)hipFree(c->out_dev);
@@ -351,7 +397,10 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
         A2CID_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
     }
     const size_t m = 2 * (size_t)n + 2;
-    A2CID_HIP(hipHostMalloc((void **)&c->b_host, sizeof(float) * n, hipHostMallocDefault));
+    for (CoefStage &cs : c->coef_stage) {
+        A2CID_HIP(hipHostMalloc((void **)&cs.host, sizeof(float) * n, hipHostMallocDefault));
+        A2CID_HIP(hipEventCreateWithFlags(&cs.done, hipEventDisableTiming));
+    }
     A2CID_HIP(hipMalloc((void **)&c->b_dev, sizeof(float) * n));
     A2CID_HIP(hipMalloc((void **)&c->partials, sizeof(double) * m * kStatsBlocksMax));
     A2CID_HIP(hipMalloc((void **)&c->out_dev, sizeof(double) * m));
@@ -383,10 +432,18 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
     return A2CID_OK;
 }
 
+// The chain programme of k operations has at most 3 k + slots steps (every spill makes room for a parking).
+static int64_t piece_capacity(const a2cid_ctx *c) { return c->walk == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps; }
+
+static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch);
+
 static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
     if (int rc = enter(c)) return rc;
+    if (int rc = unusable(c)) return rc;
+    // ---- validation: nothing is enqueued and no time stamp moves before all of it has passed ----
     if (int rc = plan_batch(c->g, c->eta, c->t.data(), batch, c->plan, c->scratch)) return rc;
     // gradient inputs the kernels will read: d floats each, inside one device allocation
+    c->known.clear();
     for (int64_t k = 0; k < batch->n_ops; ++k) {
         const a2cid_op &op = batch->ops[k];
         if (op.kind != A2CID_KIND_GRADIENT) continue;
@@ -395,11 +452,29 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
         if (op.c && op.gscale != 0.f)
             if (int rc = check_device_span(c, op.c, sizeof(float) * (size_t)c->d, "c of a gradient event")) return rc;
     }
-    // the chain programme of k operations has at most 3 k + slots steps (every spill makes room for a parking)
-    const int64_t cap = c->walk == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps;
+    const int64_t cap = piece_capacity(c);
+    for (int32_t l = 0; l < batch->n_levels; ++l) {
+        const int64_t sz = batch->level_off[l + 1] - batch->level_off[l];
+        if (sz > cap) return fail(A2CID_EMATCHING, "level %d has %lld operations", l, (long long)sz);
+    }
+    // ---- enqueueing: a failure from here on leaves kernels in the stream whose time stamps were not committed ----
+    if (int rc = enqueue_batch(c, batch)) {
+        c->failed = true;
+        return rc;
+    }
+    c->t = c->plan.t_after;
+    c->n_gossip += c->plan.n_gossip;
+    c->n_grad += c->plan.n_grad;
+    c->alg_bytes += (double)c->d * (32.0 * c->plan.n_gossip + 16.0 * c->plan.n_grad +
+                                    4.0 * c->plan.n_grad_xi + 4.0 * c->plan.n_grad_c);
+    return A2CID_OK;
+}
+
+static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
+    const int64_t cap = piece_capacity(c);
     int32_t l = 0;
     while (l < batch->n_levels) {
-        // take as many whole levels as fit into one staging buffer
+        // take as many whole levels as fit into one staging buffer (apply_impl has checked that every level does)
         int32_t l_end = l;
         int64_t count = 0;
         while (l_end < batch->n_levels) {
@@ -538,11 +613,6 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
         }
         l = l_end;
     }
-    c->t = c->plan.t_after;
-    c->n_gossip += c->plan.n_gossip;
-    c->n_grad += c->plan.n_grad;
-    c->alg_bytes += (double)c->d * (32.0 * c->plan.n_gossip + 16.0 * c->plan.n_grad +
-                                    4.0 * c->plan.n_grad_xi + 4.0 * c->plan.n_grad_c);
     return A2CID_OK;
 }
 
@@ -556,46 +626,69 @@ int a2cid_apply_events(a2cid_ctx *c, const a2cid_event_batch *batch) {
     }
 }
 
+// Checks shared by the calls that bring every worker to a common time t_now.
+static int check_common_time(const a2cid_ctx *c, double t_now) {
+    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
+    if (int rc = enter(c)) return rc;
+    if (int rc = unusable(c)) return rc;
+    for (int32_t i = 0; i < c->n; ++i)
+        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
+    return A2CID_OK;
+}
+
+// Uploads the n pending mixing coefficients for t_now into b_dev (stream-ordered after every earlier reader of it).
+static int upload_coefficients(a2cid_ctx *c, double t_now) {
+    CoefStage *cs;
+    if (int rc = acquire_coef_stage(c, &cs)) return rc;
+    for (int32_t i = 0; i < c->n; ++i) cs->host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    A2CID_HIP(hipMemcpyAsync(c->b_dev, cs->host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
+    A2CID_HIP(hipEventRecord(cs->done, c->stream));
+    cs->in_flight = true;
+    return A2CID_OK;
+}
+
 int a2cid_flush(a2cid_ctx *c, double t_now) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
-    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
-    if (int rc = enter(c)) return rc;
-    std::vector<float> b(c->n);
-    for (int32_t i = 0; i < c->n; ++i) {
-        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
-        b[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    if (int rc = check_common_time(c, t_now)) return rc;
+    try {
+        std::vector<float> b(c->n);
+        for (int32_t i = 0; i < c->n; ++i) b[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+        if (int rc = enqueue_mix_all(c, b)) {
+            c->failed = true;
+            return rc;
+        }
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
     }
-    if (int rc = enqueue_mix_all(c, b)) return rc;
     std::fill(c->t.begin(), c->t.end(), t_now);
     return A2CID_OK;
 }
 
-int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
-    clear_error();
-    if (!c || !out || !out->sum_x || !out->sum_xt) return fail(A2CID_EINVAL, "context / out is NULL");
-    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
-    if (int rc = enter(c)) return rc;
-    for (int32_t i = 0; i < c->n; ++i)
-        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
-    // b_host is reused by every call and an earlier asynchronous upload (a2cid_average) may still be reading it
-    A2CID_HIP(hipStreamSynchronize(c->stream));
-    for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
-    A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
+// The observables pass: per-workgroup partials into `partials` (blocks x (2n + 2) doubles), then their sums into
+// `out` (2n + 2 doubles: sums of x, sums of xt, the two consensus distances).  The coefficients come from the
+// device table b_dev, or, when args is not NULL, from the kernel's argument block.
+static int launch_stats(a2cid_ctx *c, const float *b_dev, const MixArgs *args, double *partials, int32_t max_blocks,
+                        double *out) {
     const int64_t pieces = (c->d + 3) >> 2;
     const int v = c->stats_v, r = c->stats_r;
     const int64_t per_tile = (int64_t)v * kThreads;
     const int64_t n_tiles = (pieces + per_tile - 1) / per_tile;
-    const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, c->stats_blocks);
+    const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, max_blocks);
     const int32_t m = 2 * c->n + 2;
     const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
-#define A2CID_STATS_LAUNCH(V, R, NT)                                                                            \
+#define A2CID_STATS_LAUNCH(V, R, NT)                                                                             \
     do {                                                                                                         \
-        if (lds > 32768)   /* the kernel also has 4 KiB of static LDS; the default cap is 64 KiB in total */      \
-            A2CID_HIP(hipFuncSetAttribute((const void *)stats_kernel<V, R, NT>,                                   \
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                 \
-        hipLaunchKernelGGL((stats_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, c->xt,   \
-                           c->ld, c->d, c->n, c->b_dev, c->partials, n_tiles);                                    \
+        if (args) {      /* at most kMixArgsMax workers: the dynamic LDS stays below the default cap */            \
+            hipLaunchKernelGGL((stats_args_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x, \
+                               c->xt, c->ld, c->d, c->n, *args, partials, n_tiles);                               \
+        } else {                                                                                                 \
+            if (lds > 32768)   /* the kernel also has 4 KiB of static LDS; the default cap is 64 KiB in total */  \
+                A2CID_HIP(hipFuncSetAttribute((const void *)stats_kernel<V, R, NT>,                               \
+                                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));             \
+            hipLaunchKernelGGL((stats_kernel<V, R, NT>), dim3(blocks), dim3(kThreads), lds, c->stream, c->x,      \
+                               c->xt, c->ld, c->d, c->n, b_dev, partials, n_tiles);                               \
+        }                                                                                                        \
     } while (0)
     const bool snt = c->stats_nt != 0;
     if (v == 1 && r == 1) { if (snt) A2CID_STATS_LAUNCH(1, 1, true); else A2CID_STATS_LAUNCH(1, 1, false); }
@@ -606,10 +699,28 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     else { if (snt) A2CID_STATS_LAUNCH(2, 2, true); else A2CID_STATS_LAUNCH(2, 2, false); }
 #undef A2CID_STATS_LAUNCH
     A2CID_HIP(hipGetLastError());
-    hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, c->partials, blocks, m, c->out_dev);
+    hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, partials, blocks, m, out);
     A2CID_HIP(hipGetLastError());
+    return A2CID_OK;
+}
+
+static int stats_impl(a2cid_ctx *c, double t_now) {
+    if (int rc = upload_coefficients(c, t_now)) return rc;
+    if (int rc = launch_stats(c, c->b_dev, nullptr, c->partials, c->stats_blocks, c->out_dev)) return rc;
+    const int32_t m = 2 * c->n + 2;
     A2CID_HIP(hipMemcpyAsync(c->out_host, c->out_dev, sizeof(double) * m, hipMemcpyDeviceToHost, c->stream));
     A2CID_HIP(hipStreamSynchronize(c->stream));
+    return A2CID_OK;
+}
+
+int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
+    clear_error();
+    if (!c || !out || !out->sum_x || !out->sum_xt) return fail(A2CID_EINVAL, "context / out is NULL");
+    if (int rc = check_common_time(c, t_now)) return rc;
+    if (int rc = stats_impl(c, t_now)) {
+        c->failed = true;
+        return rc;
+    }
     std::memcpy(out->sum_x, c->out_host, sizeof(double) * c->n);
     std::memcpy(out->sum_xt, c->out_host + c->n, sizeof(double) * c->n);
     out->consensus_x = c->out_host[2 * c->n];
@@ -617,21 +728,23 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     return A2CID_OK;
 }
 
-int a2cid_average(a2cid_ctx *c, double t_now) {
-    clear_error();
-    if (!c) return fail(A2CID_EINVAL, "context is NULL");
-    if (!std::isfinite(t_now)) return fail(A2CID_EINVAL, "t_now is not finite");
-    if (int rc = enter(c)) return rc;
-    for (int32_t i = 0; i < c->n; ++i)
-        if (t_now < c->t[i]) return fail(A2CID_EORDER, "t_now %.17g is before worker %d's time %.17g", t_now, i, c->t[i]);
-    // b_host may still be read by an earlier asynchronous upload: wait for the stream first
-    A2CID_HIP(hipStreamSynchronize(c->stream));
-    for (int32_t i = 0; i < c->n; ++i) c->b_host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
-    A2CID_HIP(hipMemcpyAsync(c->b_dev, c->b_host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
+static int average_impl(a2cid_ctx *c, double t_now) {
+    if (int rc = upload_coefficients(c, t_now)) return rc;
     const int64_t pieces = (c->d + 3) >> 2;
     hipLaunchKernelGGL(average_kernel, dim3((unsigned)((pieces + kThreads - 1) / kThreads)), dim3(kThreads),
                        sizeof(float) * (size_t)c->n, c->stream, c->x, c->xt, c->ld, c->d, c->n, c->b_dev);
     A2CID_HIP(hipGetLastError());
+    return A2CID_OK;
+}
+
+int a2cid_average(a2cid_ctx *c, double t_now) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (int rc = check_common_time(c, t_now)) return rc;
+    if (int rc = average_impl(c, t_now)) {
+        c->failed = true;
+        return rc;
+    }
     std::fill(c->t.begin(), c->t.end(), t_now);
     c->alg_bytes += 16.0 * (double)c->n * (double)c->d;
     c->moved_bytes += 16.0 * (double)c->n * (double)c->d;
@@ -727,7 +840,7 @@ int a2cid_set_stats_tuning(a2cid_ctx *c, int32_t pieces, int32_t rows, int32_t b
 int a2cid_check_device_span(a2cid_ctx *c, const void *p, int64_t bytes) {
     clear_error();
     if (!c || !p || bytes < 1) return fail(A2CID_EINVAL, "context / pointer NULL or bytes < 1");
-    return check_device_span(c, p, (size_t)bytes, "span");
+    return query_device_span(c, p, (size_t)bytes, "span", nullptr);
 }
 
 int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream) {

@@ -738,19 +738,28 @@ __device__ __forceinline__ void stats_row(ColumnAcc<V> &acc, v4f (&a)[V], v4f (&
     if (lane == 0) { my_row[i] += (double)rx; my_row[n + i] += (double)rxt; }
 }
 
+// Where the observables kernel finds the pending mixing coefficient of each worker: a device table (NULL: nothing
+// is pending, every coefficient is 0) or the kernel's own argument block (no upload, nothing to keep alive).
+struct MixTable {
+    const float *p;
+    __device__ __forceinline__ float at(int i) const { return p ? p[i] : 0.f; }
+};
+constexpr int kMixArgsMax = 256;         // workers whose coefficients fit into the argument block (1 KiB)
+struct MixArgs {
+    float b[kMixArgsMax];
+    __device__ __forceinline__ float at(int i) const { return b[i]; }
+};
+
 // V: float4 pieces per lane and row; R: rows whose loads are issued together (memory-level parallelism).
-template <int V, int R, bool NT>
-__global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict__ x,
-                                                         const float *__restrict__ xt,
-                                                         int64_t ld, int64_t d, int32_t n,
-                                                         const float *__restrict__ bmix,
-                                                         double *__restrict__ partials,
-                                                         int64_t n_tiles) {
+template <int V, int R, bool NT, typename B>
+__device__ __forceinline__ void stats_body(const float *__restrict__ x, const float *__restrict__ xt, int64_t ld,
+                                           int64_t d, int32_t n, const B &bmix, double *__restrict__ partials,
+                                           int64_t n_tiles) {
     extern __shared__ double smem[];
     double *srow = smem;                                  // [kWaves][2n]
     float *sb = (float *)(smem + (size_t)kWaves * 2 * n); // [n]
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    for (int i = tid; i < n; i += kThreads) sb[i] = bmix[i];
+    for (int i = tid; i < n; i += kThreads) sb[i] = bmix.at(i);
     for (int i = tid; i < kWaves * 2 * n; i += kThreads) srow[i] = 0.0;
     __syncthreads();
     double *my_row = srow + (size_t)wave * 2 * n;
@@ -819,6 +828,27 @@ __global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict
         out[i] = s;
     }
     if (tid == 0) { out[2 * n] = scons[0][0]; out[2 * n + 1] = scons[1][0]; }
+}
+
+template <int V, int R, bool NT>
+__global__ __launch_bounds__(kThreads) void stats_kernel(const float *__restrict__ x,
+                                                         const float *__restrict__ xt,
+                                                         int64_t ld, int64_t d, int32_t n,
+                                                         const float *__restrict__ bmix,
+                                                         double *__restrict__ partials,
+                                                         int64_t n_tiles) {
+    stats_body<V, R, NT>(x, xt, ld, d, n, MixTable{bmix}, partials, n_tiles);
+}
+
+// The same pass with the coefficients in the argument block (n <= kMixArgsMax).
+template <int V, int R, bool NT>
+__global__ __launch_bounds__(kThreads) void stats_args_kernel(const float *__restrict__ x,
+                                                              const float *__restrict__ xt,
+                                                              int64_t ld, int64_t d, int32_t n,
+                                                              const MixArgs bmix,
+                                                              double *__restrict__ partials,
+                                                              int64_t n_tiles) {
+    stats_body<V, R, NT>(x, xt, ld, d, n, bmix, partials, n_tiles);
 }
 
 // Consensus step: every worker's (virtually mixed) row is replaced by the mean over workers, in x and in xt.

@@ -45,22 +45,10 @@ def _compare(cfg, n_events, batch_events, cols=None, tuning=None):
     assert ex <= pu.TOL and ext <= pu.TOL
     if w.ld != cfg.d:                                           # padding columns were never written
         assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
-    # observables at a common later time, against the oracle's on the same columns when complete
-    t_now = float(ev.t[-1]) + 0.5
-    gs = w.engine.stats(t_now)
-    if len(cols) == cfg.d:
-        os_ = st.stats(t_now)
-        for k in ("consensus_x", "consensus_xt"):
-            assert math.isclose(gs[k], os_[k], rel_tol=1e-4), (k, gs[k], os_[k])
-        l1x = np.abs(st.x).sum(1); l1xt = np.abs(st.xt).sum(1)
-        assert np.all(np.abs(gs["sum_x"] - os_["sum_x"]) <= 1e-5 * l1x)
-        assert np.all(np.abs(gs["sum_xt"] - os_["sum_xt"]) <= 1e-5 * l1xt)
-    # flush, then the same columns once more
-    w.engine.flush(t_now)
-    fx, fxt = w.columns(cols)
-    ox, oxt = st.flushed(t_now)
-    assert pu.rel_err(fx, ox) <= pu.TOL and pu.rel_err(fxt, oxt) <= pu.TOL
-    assert np.all(w.engine.times() == t_now)
+    # observables at a common later time and the flushed state
+    pu.check_observables(w, st, float(ev.t[-1]) + 0.5, cols)
+    if w.ld != cfg.d:
+        assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
     w.close()
     return w
 
@@ -311,11 +299,13 @@ def test_observables_at_full_size_against_library_reductions():
             blk = buf[:, lo:min(cfg.d, lo + (1 << 21))].double()
             cons[name] += float(((blk - blk.mean(0, keepdim=True)) ** 2).sum())
             sums[name] += blk.sum(1).cpu().numpy()
-    assert math.isclose(s1["consensus_x"], cons["x"], rel_tol=1e-6)
-    assert math.isclose(s1["consensus_xt"], cons["xt"], rel_tol=1e-6)
+    # fp64 accumulation on both sides: 1e-9; the per-worker sums pass through fp32 partial sums of 512 values
+    # (at most 9 roundings of 2^-24 each): 1e-6 of the mean L1 norm of a row
+    assert math.isclose(s1["consensus_x"], cons["x"], rel_tol=1e-9)
+    assert math.isclose(s1["consensus_xt"], cons["xt"], rel_tol=1e-9)
     assert np.all(np.abs(s1["sum_x"] - sums["x"]) <= 1e-6 * l1) and np.all(np.abs(s1["sum_xt"] - sums["xt"]) <= 1e-6 * l1)
     s3 = w.engine.stats(t_now)                            # after the flush nothing is pending: same numbers
-    assert math.isclose(s3["consensus_x"], s1["consensus_x"], rel_tol=1e-6)
+    assert math.isclose(s3["consensus_x"], s1["consensus_x"], rel_tol=1e-9)
     w.close()
 
 
@@ -441,10 +431,7 @@ def test_extreme_worker_counts(n, topology, d, events, mode):
     assert np.array_equal(w.engine.times(), st.t)
     assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
     t_now = float(ev.t[-1]) + 0.2
-    gs, os_ = w.engine.stats(t_now), st.stats(t_now)
-    assert math.isclose(gs["consensus_x"], os_["consensus_x"], rel_tol=1e-4)
-    assert math.isclose(gs["consensus_xt"], os_["consensus_xt"], rel_tol=1e-4)
-    assert np.all(np.abs(gs["sum_x"] - os_["sum_x"]) <= 1e-5 * np.abs(st.x).sum(1))
+    pu.check_observables(w, st, t_now, cols)
     w.engine.average(t_now)
     st.average(t_now)
     ax, axt = w.columns(cols)
@@ -513,9 +500,12 @@ def test_acceleration_shows_on_the_device_path():
         w.run(c.events)
         st, ev = pu.oracle_run(c, np.arange(c.d), c.events)
         t_end = float(ev.t[-1])
-        got, ref = w.engine.stats(t_end)["consensus_x"], st.stats(t_end)["consensus_x"]
-        _say(f"{label}: eta={w.eta:.4g} alpha_tilde={w.alpha_tilde:.4g} consensus gpu {got:.6g} oracle {ref:.6g}")
-        assert math.isclose(got, ref, rel_tol=1e-3)
+        ref = st.stats(t_end)["consensus_x"]
+        # the workers are close to consensus here (||pi x||^2 << ||x||^2), where the observable amplifies the
+        # state error: the comparison allows exactly what the measured state error can cause, no more
+        got = pu.check_observables(w, st, t_end, np.arange(c.d))["consensus_x"]
+        _say(f"{label}: eta={w.eta:.4g} alpha_tilde={w.alpha_tilde:.4g} consensus gpu {got:.6g} oracle {ref:.6g} "
+             f"rel diff {abs(got - ref) / ref:.2e}")
         consensus[label] = got
         w.close()
     assert consensus["accelerated"] < 0.1 * consensus["baseline"]
