@@ -184,6 +184,23 @@ int a2cid_set_order(a2cid_ctx *ctx, int32_t order);
  * until the result is in *out. */
 int a2cid_stats(a2cid_ctx *ctx, double t_now, a2cid_stats_out *out);
 
+/* a2cid_stats for callers that cannot allocate device memory or wait for the stream (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same observables of
+ * the same virtually mixed state, written to caller-provided DEVICE memory, asynchronously on the
+ * context's stream, by the same kernels.  out: 2 n + 2 doubles, 8-byte aligned, device memory of
+ * the context's GPU: [0, n) the sums of x_i, [n, 2n) the sums of xt_i, [2n] and [2n + 1] the
+ * consensus distances of x and xt.  The call makes no hipMalloc / hipFree and no host allocation,
+ * uploads nothing (the n pending mixing coefficients travel in the kernel's argument block) and
+ * does not synchronise.  Its only scratch, the per-workgroup partial sums, is a fixed array of
+ * 2 129 920 bytes inside the library's code object: every GPU the library runs on holds one copy
+ * until the process ends, and all calls on a GPU share it.  Each call rewrites every entry it later
+ * reads, so nothing has to be cleared between calls, but two calls that overlap on one GPU (two
+ * contexts or streams) race on it: serialise them.  At most A2CID_STATS_STATIC_MAX_WORKERS workers
+ * (A2CID_EINVAL beyond); for more than 64 workers fewer workgroups than a2cid_stats would use share
+ * the scratch, which changes the summation order (last bits) but not the result otherwise. */
+#define A2CID_STATS_STATIC_MAX_WORKERS 256
+int a2cid_stats_static(a2cid_ctx *ctx, double t_now, double *out);
+
 /* Mixes every worker up to t_now (>= max_i t_i) in place and sets all t_i = t_now: the state
  * Algorithm 1 returns at its final time. */
 int a2cid_flush(a2cid_ctx *ctx, double t_now);

@@ -14,6 +14,7 @@ LIB_PATH = os.path.join(HERE, "liba2cid.so")
 
 OK, EINVAL, EGRAPH, EORDER, EMATCHING, EALIGN, EHIP, ENOMEM = 0, -1, -2, -3, -4, -5, -6, -7
 KIND_GRADIENT, KIND_GOSSIP = 0, 1
+STATS_STATIC_MAX_WORKERS = 256        # A2CID_STATS_STATIC_MAX_WORKERS
 ERROR_NAMES = {EINVAL: "A2CID_EINVAL", EGRAPH: "A2CID_EGRAPH", EORDER: "A2CID_EORDER",
                EMATCHING: "A2CID_EMATCHING", EALIGN: "A2CID_EALIGN", EHIP: "A2CID_EHIP",
                ENOMEM: "A2CID_ENOMEM"}
@@ -66,6 +67,7 @@ SIGNATURES = {
                                C.c_double, _P(a2cid_buffers)]),
     "a2cid_apply_events": (C.c_int, [C.c_void_p, _P(a2cid_event_batch)]),
     "a2cid_stats": (C.c_int, [C.c_void_p, C.c_double, _P(a2cid_stats_out)]),
+    "a2cid_stats_static": (C.c_int, [C.c_void_p, C.c_double, C.c_void_p]),
     "a2cid_flush": (C.c_int, [C.c_void_p, C.c_double]),
     "a2cid_set_order": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_average": (C.c_int, [C.c_void_p, C.c_double]),
@@ -284,6 +286,14 @@ class Engine:
         with self._device():
             _check(load().a2cid_stats(self._h, float(t_now), C.byref(out)))
         return {"consensus_x": out.consensus_x, "consensus_xt": out.consensus_xt, "sum_x": sx, "sum_xt": sxt}
+
+    def stats_static(self, t_now, out):
+        """a2cid_stats_static: the observables into `out`, a contiguous fp64 CUDA tensor of 2 n + 2 elements
+        (sums of x, sums of xt, consensus distances); asynchronous, nothing is allocated."""
+        import torch
+        assert out.is_cuda and out.dtype == torch.float64 and out.is_contiguous() and out.numel() == 2 * self.n + 2
+        with self._device():
+            _check(load().a2cid_stats_static(self._h, float(t_now), C.c_void_p(out.data_ptr())))
 
     def set_order(self, order):
         _check(load().a2cid_set_order(self._h, int(order)))

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -19,6 +20,13 @@ using namespace a2cid;
             return fail(A2CID_EHIP, "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),    \
                         __FILE__, __LINE__);                                                 \
     } while (0)
+
+// Scratch of a2cid_stats_static: per-workgroup partial sums of the observables kernel, for callers that cannot
+// allocate.  Every GPU the library runs on holds its own copy of this array, at its own address, until the process
+// ends.  In host code the name below is only a handle: the address a kernel may use comes from hipGetSymbolAddress
+// (static_scratch()), once per device.
+constexpr size_t kStaticDoubles = 2048 * (2 * 64 + 2);      // 2048 workgroups x 64 workers: 2 129 920 bytes
+static __device__ __align__(256) double scratch[kStaticDoubles];
 
 namespace {
 
@@ -164,6 +172,24 @@ int check_device_span(a2cid_ctx *c, const void *p, size_t bytes, const char *wha
         if (c->known.size() >= kKnownSpans) c->known.clear();
         c->known.push_back(span);
     }
+    return A2CID_OK;
+}
+
+// The address of this device's copy of the static scratch array.  Looked up once per device, with that device
+// current (every caller has made sure of that), and kept.
+constexpr int kMaxDevices = 64;
+int static_scratch(int device, double **out) {
+    static std::mutex guard;
+    static double *address[kMaxDevices] = {};
+    if (device < 0 || device >= kMaxDevices) return fail(A2CID_EINVAL, "HIP device %d out of range", device);
+    std::lock_guard<std::mutex> lock(guard);
+    if (!address[device]) {
+        double *p = nullptr;
+        A2CID_HIP(hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(A2CID_EHIP, "hipGetSymbolAddress returned a null address for the static scratch");
+        address[device] = p;
+    }
+    *out = address[device];
     return A2CID_OK;
 }
 
@@ -407,6 +433,8 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     A2CID_HIP(hipHostMalloc((void **)&c->out_host, sizeof(double) * m, hipHostMallocDefault));
     A2CID_HIP(hipMalloc((void **)&c->zero_dev, 256));
     A2CID_HIP(hipMemset(c->zero_dev, 0, 256));
+    double *static_ptr = nullptr;       // resolved here so that a2cid_stats_static never has to look it up
+    if (int rc = static_scratch(c->device, &static_ptr)) return rc;
     return A2CID_OK;
 }
 
@@ -725,6 +753,30 @@ int a2cid_stats(a2cid_ctx *c, double t_now, a2cid_stats_out *out) {
     std::memcpy(out->sum_xt, c->out_host + c->n, sizeof(double) * c->n);
     out->consensus_x = c->out_host[2 * c->n];
     out->consensus_xt = c->out_host[2 * c->n + 1];
+    return A2CID_OK;
+}
+
+int a2cid_stats_static(a2cid_ctx *c, double t_now, double *out) {
+    clear_error();
+    if (!c || !out) return fail(A2CID_EINVAL, "context / out is NULL");
+    if (c->n > A2CID_STATS_STATIC_MAX_WORKERS)
+        return fail(A2CID_EINVAL, "a2cid_stats_static handles at most %d workers (the context has %d): its scratch is "
+                    "a fixed array of %zu bytes and its coefficients travel in the kernel arguments",
+                    A2CID_STATS_STATIC_MAX_WORKERS, c->n, sizeof(double) * kStaticDoubles);
+    if ((uintptr_t)out & 7u) return fail(A2CID_EALIGN, "out must be 8-byte aligned");
+    if (int rc = check_common_time(c, t_now)) return rc;
+    const int32_t m = 2 * c->n + 2;
+    if (int rc = query_device_span(c, out, sizeof(double) * (size_t)m, "out", nullptr)) return rc;
+    double *partials = nullptr;
+    if (int rc = static_scratch(c->device, &partials)) return rc;
+    MixArgs args;
+    for (int32_t i = 0; i < kMixArgsMax; ++i)
+        args.b[i] = i < c->n ? (float)mix_coefficient(c->eta, t_now - c->t[i]) : 0.f;
+    const int32_t max_blocks = (int32_t)std::min<size_t>((size_t)c->stats_blocks, kStaticDoubles / (size_t)m);
+    if (int rc = launch_stats(c, nullptr, &args, partials, max_blocks, out)) {
+        c->failed = true;
+        return rc;
+    }
     return A2CID_OK;
 }
 
