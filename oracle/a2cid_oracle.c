@@ -49,19 +49,29 @@ void a2o_mix_row(double *x, double *xt, int64_t d, double eta, double tau)
 
 /* ------------------------------------------------------------------------- */
 /* Gradient jump of Eq. (1) / gradient thread of Algorithm 1 for worker i at    */
-/* time te: mix to te, g = gscale * (x_i - c) + xi, then the SAME gamma * g is  */
-/* subtracted from x_i and from xt_i.  c and xi may be NULL (treated as zero;   */
-/* with c == NULL the affine part is gscale * x_i).                            */
+/* time te: mix to te, g = gscale * h .* (x_i - c) + xi, then the SAME          */
+/* gamma * g is subtracted from x_i and from xt_i.  This g is the gradient of   */
+/* the local objective f_i(x) = gscale/2 sum_k h_k (x_k - c_k)^2 plus the noise */
+/* xi of a stochastic oracle: mu-strongly convex and L-smooth with              */
+/* mu = gscale min h, L = gscale max h (the first setting of Proposition 3.2).  */
+/* c, xi and h may be NULL (c, xi: zeros; h: ones, i.e. a scalar curvature).    */
 /* ------------------------------------------------------------------------- */
+static double a2o_local_gradient(double x, int64_t k, double gscale,
+                                 const double *c, const double *xi, const double *h)
+{
+    double g = gscale * (h ? h[k] : 1.0) * (x - (c ? c[k] : 0.0));
+    if (xi) g += xi[k];
+    return g;
+}
+
 void a2o_gradient_event(double *x_i, double *xt_i, double *t_i, int64_t d,
                         double eta, double te, double gamma, double gscale,
-                        const double *c, const double *xi)
+                        const double *c, const double *xi, const double *h)
 {
     a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
     *t_i = te;
     for (int64_t k = 0; k < d; ++k) {
-        double g = gscale * (x_i[k] - (c ? c[k] : 0.0));
-        if (xi) g += xi[k];
+        const double g = a2o_local_gradient(x_i[k], k, gscale, c, xi, h);
         x_i[k] -= gamma * g;
         xt_i[k] -= gamma * g;
     }
@@ -98,13 +108,10 @@ void a2o_gossip_event(double *x_i, double *xt_i, double *t_i,
 /* ------------------------------------------------------------------------- */
 void a2o_gradient_event_listing(double *x_i, double *xt_i, double *t_i, int64_t d,
                                 double eta, double te, double gamma, double gscale,
-                                const double *c, const double *xi)
+                                const double *c, const double *xi, const double *h)
 {
     double *g = (double *)malloc(sizeof(double) * (size_t)d);
-    for (int64_t k = 0; k < d; ++k) {
-        g[k] = gscale * (x_i[k] - (c ? c[k] : 0.0));
-        if (xi) g[k] += xi[k];
-    }
+    for (int64_t k = 0; k < d; ++k) g[k] = a2o_local_gradient(x_i[k], k, gscale, c, xi, h);
     a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
     *t_i = te;
     for (int64_t k = 0; k < d; ++k) {
@@ -136,7 +143,8 @@ void a2o_gossip_event_listing(double *x_i, double *xt_i, double *t_i,
 /* ------------------------------------------------------------------------- */
 /* Serial event loop.  x, xt are n x d row-major, t has n entries.              */
 /* kind[e] == 0: gradient on worker wi[e]; kind[e] == 1: gossip on (wi, wj).    */
-/* xi_row[e] / c_row[e] index rows of the dense matrices xi / c (or -1: none).  */
+/* xi_row[e] / c_row[e] / h_row[e] index rows of the dense matrices xi / c / h  */
+/* (or -1: none; the row arrays themselves may be NULL).                        */
 /* order 0: jumps evaluated after the mixing (Eq. (1)); order 1: Algorithm 1's    */
 /* listing order (see above).                                                   */
 /* Returns 0, or -(e+1) for the first malformed event (nothing after it runs).  */
@@ -147,7 +155,8 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
                          const int32_t *wi, const int32_t *wj,
                          const double *gamma, const double *gscale,
                          const int64_t *xi_row, const double *xi,
-                         const int64_t *c_row, const double *c, int32_t order)
+                         const int64_t *c_row, const double *c,
+                         const int64_t *h_row, const double *h, int32_t order)
 {
     for (int64_t e = 0; e < n_events; ++e) {
         const int32_t i = wi[e];
@@ -156,8 +165,9 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
             if (te[e] < t[i]) return -(e + 1);
             const double *ce = (c_row && c_row[e] >= 0) ? c + c_row[e] * d : NULL;
             const double *xe = (xi_row && xi_row[e] >= 0) ? xi + xi_row[e] * d : NULL;
+            const double *he = (h_row && h_row[e] >= 0) ? h + h_row[e] * d : NULL;
             (order ? a2o_gradient_event_listing : a2o_gradient_event)(
-                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, d, eta, te[e], gamma[e], gscale[e], ce, xe);
+                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, d, eta, te[e], gamma[e], gscale[e], ce, xe, he);
         } else if (kind[e] == 1) {
             const int32_t j = wj[e];
             if (j < 0 || j >= n || j == i) return -(e + 1);

@@ -25,7 +25,7 @@ def lib():
         _lib.a2o_apply_events.argtypes = [
             C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double, C.c_double,
             C.c_int64, d_p, i32_p, i32_p, i32_p, d_p, d_p,
-            i64_p, C.c_void_p, i64_p, C.c_void_p, C.c_int32]
+            i64_p, C.c_void_p, i64_p, C.c_void_p, i64_p, C.c_void_p, C.c_int32]
         _lib.a2o_apply_events.restype = C.c_int64
         _lib.a2o_stats.argtypes = [C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double,
                                    C.POINTER(C.c_double), C.POINTER(C.c_double), d_p, d_p]
@@ -97,11 +97,12 @@ class State:
         self.eta, self.alpha, self.alpha_t = float(eta), float(alpha), float(alpha_t)
         self.order = int(order)      # 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
 
-    def apply(self, ev, gamma=None, gscale=None, xi=None, xi_row=None, c=None, c_row=None):
+    def apply(self, ev, gamma=None, gscale=None, xi=None, xi_row=None, c=None, c_row=None, h=None, h_row=None):
         """Run the serial event loop over ev.
 
         gamma, gscale: per-event arrays (scalars broadcast).  xi: (m, d) matrix of additive
-        gradient terms, xi_row[e] the row used by event e (-1: none); same for c, c_row.
+        gradient terms, xi_row[e] the row used by event e (-1: none); same for c, c_row (centres) and
+        h, h_row (per-coordinate curvatures: g = gscale * h .* (x - c) + xi; none: h = 1).
         """
         m = len(ev)
         gamma = np.ascontiguousarray(np.broadcast_to(0.0 if gamma is None else gamma, (m,)), np.float64)
@@ -119,10 +120,11 @@ class State:
 
         xi_m, xi_r, xi_p = prep(xi, xi_row)
         c_m, c_r, c_p = prep(c, c_row)
+        h_m, h_r, h_p = prep(h, h_row)
         rc = lib().a2o_apply_events(self.n, self.d, self.x, self.xt, self.t,
                                     self.eta, self.alpha, self.alpha_t, m,
                                     ev.t, ev.kind, ev.i, ev.j, gamma, gscale,
-                                    xi_r, xi_p, c_r, c_p, self.order)
+                                    xi_r, xi_p, c_r, c_p, h_r, h_p, self.order)
         if rc != 0:
             raise ValueError(f"malformed event at position {-rc - 1}")
         return self

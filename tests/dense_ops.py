@@ -7,7 +7,8 @@ dynamic is an affine map of v, written as a (2n+1) x (2n+1) matrix:
                                A = [[-eta, eta], [eta, -eta]]  (scipy's matrix exponential)
   gossip on (i, j)           : x  <- (I - alpha E_ij) x,  xt <- xt - alpha_t E_ij x,
                                E_ij = (e_i - e_j)(e_i - e_j)^T
-  gradient on i, g = s (x_i - c) + xi : x_i <- x_i - gamma g, xt_i <- xt_i - gamma g
+  gradient on i, g = s h (x_i - c) + xi : x_i <- x_i - gamma g, xt_i <- xt_i - gamma g
+                               (h: the coordinate's curvature, 1 when none is given)
 """
 import numpy as np
 from scipy.linalg import expm
@@ -37,8 +38,9 @@ def gradient(n, i, gamma, s, c_k, xi_k):
     return m
 
 
-def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, order=0):
+def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, order=0, h=None):
     """events: list of (t, kind, i, j).  c: (n, d) or None.  xi: list (per event) of d-vectors or None.
+    h: (n, d) per-worker, per-coordinate curvatures or None.
     order 0: v <- J F v (flow, then the jump evaluated at the flowed state, Eq. (1));
     order 1: v <- F v + (J - I) v (the jump evaluated at the stored state, Algorithm 1's listing order).
     Returns (x, xt) after the events, every worker flowed to t_final if given."""
@@ -57,7 +59,8 @@ def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, ord
             if kind == 0:
                 ck = 0.0 if c is None else c[i, k]
                 xk = 0.0 if xi is None or xi[e] is None else xi[e][k]
-                jump = gradient(n, i, gamma[e], s[e], ck, xk)
+                hk = 1.0 if h is None else h[i, k]
+                jump = gradient(n, i, gamma[e], s[e] * hk, ck, xk)
             else:
                 jump = gossip(n, i, j, alpha, alpha_t)
             step = jump @ f if order == 0 else f + jump - np.eye(2 * n + 1)

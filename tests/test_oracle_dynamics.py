@@ -328,3 +328,119 @@ def test_average_reaches_consensus_and_keeps_the_means():
     s = st.stats(T)
     assert s["consensus_x"] < 1e-25 and s["consensus_xt"] < 1e-25 and np.all(st.t == T)
     assert np.allclose(st.x.sum(0), fx.sum(0), rtol=1e-13)
+
+
+# ---------------------------------------------------------------- strongly convex local objectives (curvature h)
+def _diag_quadratics(rng, n, d, h_lo=0.5, h_hi=2.0):
+    """f_i(x) = 1/2 sum_k h_ik (x_k - c_ik)^2: centres, curvatures and the minimiser of sum_i f_i."""
+    c = rng.normal(size=(n, d))
+    h = rng.uniform(h_lo, h_hi, size=(n, d))
+    return c, h, (h * c).sum(0) / h.sum(0)
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_event_loop_with_per_coordinate_curvature_equals_dense_operator_product(order):
+    rng = np.random.default_rng(20 + order)
+    n, d = 4, 7
+    edges = graph.ring(n)
+    ev = _events(n, edges, 1.0, 1.1, 300 + order, 140)
+    eta, alpha, alpha_t = 0.8, 0.5, 1.2
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    c, h, _ = _diag_quadratics(rng, n, d, 0.1, 3.0)
+    m = len(ev)
+    gamma = rng.uniform(0.01, 0.2, m); s = rng.uniform(0.2, 1.5, m)
+    is_grad = ev.kind == 0
+    xi = rng.normal(size=(int(is_grad.sum()), d))
+    xi_row = np.full(m, -1, np.int64); xi_row[is_grad] = np.arange(is_grad.sum())
+    row = np.where(is_grad, ev.i, -1).astype(np.int64)
+    st = core.State(x0, xt0, eta, alpha, alpha_t, order=order).apply(ev, gamma, s, xi, xi_row, c, row, h, row)
+    T = ev.t[-1] + 0.3
+    ox, oxt = st.flushed(T)
+    evl = list(zip(ev.t, ev.kind, ev.i, ev.j))
+    xi_l = [xi[xi_row[e]] if xi_row[e] >= 0 else None for e in range(m)]
+    bx, bxt = dense_ops.run(x0, xt0, eta, alpha, alpha_t, evl, gamma, s, c, xi_l, t_final=T, order=order, h=h)
+    assert np.allclose(ox, bx, rtol=1e-10, atol=1e-12) and np.allclose(oxt, bxt, rtol=1e-10, atol=1e-12)
+    # the curvature matters: the same run with h = 1 ends elsewhere
+    flat = core.State(x0, xt0, eta, alpha, alpha_t, order=order).apply(ev, gamma, s, xi, xi_row, c, row)
+    assert not np.allclose(flat.x, st.x, rtol=1e-3)
+
+
+def test_repeated_gradient_steps_on_a_diagonal_quadratic_follow_the_textbook_closed_form():
+    # one worker, eta = 0 (no flow), N gradient events with constant step: gradient descent on
+    # f(x) = s/2 sum_k h_k (x_k - c_k)^2 gives x_k(N) = c_k + (1 - gamma s h_k)^N (x_k(0) - c_k), coordinate by
+    # coordinate; xt receives the same increments
+    rng = np.random.default_rng(22)
+    n, d, N, gamma, s = 3, 12, 40, 0.15, 0.7
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    c, h, _ = _diag_quadratics(rng, n, d, 0.1, 4.0)
+    ev = core.Events(np.arange(1, N + 1, dtype=float), np.zeros(N, np.int32), np.full(N, 1, np.int32),
+                     np.full(N, -1, np.int32))
+    row = np.full(N, 1, np.int64)
+    st = core.State(x0, xt0, eta=0.0).apply(ev, gamma, s, c=c, c_row=row, h=h, h_row=row)
+    want = c[1] + (1.0 - gamma * s * h[1]) ** N * (x0[1] - c[1])
+    assert np.allclose(st.x[1], want, rtol=1e-12, atol=1e-14)
+    assert np.allclose(st.xt[1] - xt0[1], want - x0[1], rtol=1e-11, atol=1e-13)
+    assert np.array_equal(st.x[[0, 2]], x0[[0, 2]])
+    # a curvature row of another worker may be attached to the event: the row index is what counts
+    other = core.State(x0, xt0, eta=0.0).apply(ev, gamma, s, c=c, c_row=row, h=h, h_row=np.full(N, 2, np.int64))
+    assert np.allclose(other.x[1], c[1] + (1.0 - gamma * s * h[2]) ** N * (x0[1] - c[1]), rtol=1e-12, atol=1e-14)
+
+
+def test_network_mean_is_stationary_exactly_at_the_minimiser_of_the_sum_of_local_objectives():
+    # all workers at x* = argmin sum_i f_i = (sum_i h_i c_i) / (sum_i h_i), x = xt (so the flow moves nothing): one
+    # gradient event per worker, at any times, leaves the network mean where it is because sum_i grad f_i(x*) = 0
+    # (Eq. (2) with a vanishing right-hand side); from the mean of the centres instead, the mean moves
+    rng = np.random.default_rng(23)
+    n, d, gamma = 6, 9, 0.1
+    c, h, x_star = _diag_quadratics(rng, n, d)
+    order = rng.permutation(n).astype(np.int32)
+    ev = core.Events(np.sort(rng.uniform(0.1, 2.0, n)), np.zeros(n, np.int32), order, np.full(n, -1, np.int32))
+    row = order.astype(np.int64)
+    at_opt = core.State(np.tile(x_star, (n, 1)), None, 0.4, 0.5, 1.3).apply(ev, gamma, 1.0, c=c, c_row=row, h=h, h_row=row)
+    x, xt = at_opt.flushed(3.0)
+    assert np.allclose(x.mean(0), x_star, rtol=1e-13, atol=1e-14) and np.allclose(xt.mean(0), x_star, rtol=1e-13, atol=1e-14)
+    off = core.State(np.tile(c.mean(0), (n, 1)), None, 0.4, 0.5, 1.3).apply(ev, gamma, 1.0, c=c, c_row=row, h=h, h_row=row)
+    assert np.abs(off.flushed(3.0)[0].mean(0) - c.mean(0)).max() > 1e-3
+
+
+def test_workers_settle_around_the_minimiser_of_the_sum_not_around_the_mean_of_the_centres():
+    rng = np.random.default_rng(24)
+    n, d, gamma = 4, 16, 0.025
+    edges = graph.complete(n)
+    ev = _events(n, edges, 1.0, 10.0, 77, 120000)
+    c, h, x_star = _diag_quadratics(rng, n, d)
+    x0 = 3.0 * rng.normal(size=(n, d))
+    p = graph.acid_params(n, edges, 10.0)
+    row = np.where(ev.kind == 0, ev.i, -1).astype(np.int64)
+    st = core.State(x0, None, p["eta"], p["alpha"], p["alpha_tilde"]).apply(ev, gamma, 1.0, c=c, c_row=row, h=h, h_row=row)
+    x, xt = st.flushed(ev.t[-1])
+    err, err0 = np.abs(x - x_star).max(), np.abs(x0 - x_star).max()
+    assert err < 0.03 * err0                                  # a neighbourhood of size O(gamma) of the minimiser
+    assert err < 0.5 * np.abs(x - c.mean(0)).max()            # ... and not of the mean of the centres
+    assert np.allclose(x.sum(0), xt.sum(0), rtol=1e-10, atol=1e-10)     # Eq. (2): the two means stay together
+
+
+def test_accelerated_parameters_reach_a_tighter_neighbourhood_of_the_optimum_on_the_ring():
+    # Proposition 3.2, strongly convex case: the heterogeneity of the local objectives enters the bound with a
+    # factor (1 + chi): chi_1 = 6.6 for plain averaging on the ring of 16, sqrt(chi_1 chi_2) = 1.8 with the
+    # accelerated parameters.  Same events, same objectives: the distance to the optimum levels off lower.
+    rng = np.random.default_rng(25)
+    n, d, gamma = 16, 64, 0.05
+    edges = graph.ring(n)
+    ev = _events(n, edges, 1.0, 1.0, 77, 20000)
+    c, h, x_star = _diag_quadratics(rng, n, d, 0.2, 2.0)
+    x0 = np.tile(3.0 * rng.normal(size=d), (n, 1))            # the workers start in consensus, as in the paper
+    p = graph.acid_params(n, edges, 1.0)
+    row = np.where(ev.kind == 0, ev.i, -1).astype(np.int64)
+    level = {}
+    for label, (eta, alpha_t) in {"accelerated": (p["eta"], p["alpha_tilde"]), "baseline": (0.0, 0.5)}.items():
+        st = core.State(x0, None, eta, 0.5, alpha_t)
+        dist = []
+        for lo in range(0, len(ev), 2000):
+            part = ev[lo:lo + 2000]
+            st.apply(part, gamma, 1.0, c=c, c_row=row[lo:lo + 2000], h=h, h_row=row[lo:lo + 2000])
+            x, _ = st.flushed(part.t[-1])
+            dist.append(np.sqrt(((x - x_star) ** 2).sum(1).mean()))
+        assert dist[0] < 0.5 * np.sqrt(((x0 - x_star) ** 2).sum(1).mean())     # the transient is over early
+        level[label] = np.mean(dist[2:])
+    assert level["accelerated"] < 0.8 * level["baseline"]
