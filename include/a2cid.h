@@ -10,7 +10,7 @@
  *   mixing flow  (x_i, xt_i) <- exp((t - t_i) [[-eta, eta], [eta, -eta]]) (x_i, xt_i)
  *                applied to a worker right before any jump that touches it (Algorithm 1);
  *   gradient     x_i -= gamma g,  xt_i -= gamma g                  (Eq. (1), dN^i term)
- *                with g = gscale * (x_i - c) + xi evaluated AFTER the mixing;
+ *                with g = gscale * h .* (x_i - c) + xi evaluated AFTER the mixing;
  *   gossip       m = x_i - x_j;  x_i -= alpha m;  x_j += alpha m;
  *                xt_i -= alpha_tilde m;  xt_j += alpha_tilde m     (Eq. (1), dM^ij term)
  *                with m evaluated AFTER both workers have been mixed.
@@ -88,11 +88,14 @@ typedef struct {
  *   kind    A2CID_KIND_GRADIENT (worker i; j ignored, conventionally -1) or
  *           A2CID_KIND_GOSSIP (edge {i, j} of the graph, either orientation).
  *   gamma   step size of a gradient event (Eq. (1)); ignored for gossip.
- *   gscale  slope s of the affine gradient model g = s (x_i - c) + xi.  s = 0 with xi = the
+ *   gscale  slope s of the affine gradient model g = s h .* (x_i - c) + xi.  s = 0 with xi = the
  *           gradient computed elsewhere is the general case; s = 1 with c = c_i is the
- *           quadratic f_i = 1/2 ||x - c_i||^2.
- *   xi, c   device pointers to d floats, 16-byte aligned, or NULL (treated as zeros).  Read
- *           when the stream reaches the operation; the caller keeps them alive until then.
+ *           quadratic f_i = 1/2 ||x - c_i||^2; with a curvature vector h it is the gradient of
+ *           f_i(x) = s/2 sum_k h_k (x_k - c_k)^2, which is (s min h)-strongly convex and
+ *           (s max h)-smooth: the first setting of Proposition 3.2.
+ *   xi, c, h  device pointers to d floats, 16-byte aligned, or NULL (xi, c: zeros; h: ones).
+ *           Read when the stream reaches the operation; the caller keeps them alive until
+ *           then.  c and h are not read when gscale = 0.
  *   id      opaque to the library (the scheduler stores the serial event index here). */
 typedef struct {
     double t;
@@ -104,6 +107,7 @@ typedef struct {
     int32_t reserved;
     const float *xi;
     const float *c;
+    const float *h;
     int64_t id;
 } a2cid_op;
 
@@ -163,7 +167,7 @@ int a2cid_graph_params(const a2cid_graph *graph, int32_t n,
 int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph,
                  double eta, double alpha, double alpha_tilde, const a2cid_buffers *buf);
 
-/* Validates the batch (levels, edges, time order, alignment, and that every xi and c it will read
+/* Validates the batch (levels, edges, time order, alignment, and that every xi, c and h it will read
  * is d floats of device memory: see a2cid_check_device_span), computes the mixing coefficients from
  * the time stamps, advances the time stamps and enqueues the kernels (Algorithm 1, both threads, for
  * every event of the batch).  When validation fails nothing is enqueued and no time stamp moves.
@@ -244,7 +248,7 @@ int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
  * of the batch always leaves it there).
  * steps (capacity entries; 3 n_ops always suffice) may be NULL to query *n_steps only;
  * *bytes_per_column (may be NULL) receives what the launch moves per column: 8 per row read from or
- * written to memory, 4 per gradient input read.  Only kinds, worker indices and the xi / c / gscale
+ * written to memory, 4 per gradient input read.  Only kinds, worker indices and the xi / c / h / gscale
  * fields of the operations are read (the level table is not).  0 <= lds_slots <= 16.
  * a2cid_apply_events plans pieces of at most 5456 operations (whole levels) independently. */
 #define A2CID_LOC_MEMORY 0
@@ -338,7 +342,7 @@ int a2cid_set_chain_slots(a2cid_ctx *ctx, int32_t slots);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
  * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
- * columns wide and needs 512 * cols * (workers + 16) bytes of the CU's 160 KiB of LDS).
+ * columns wide and needs 512 * cols * workers + 12 288 * cols bytes of the CU's 160 KiB of LDS).
  * Default: 8, 1. */
 int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
 
@@ -348,7 +352,7 @@ int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
  * first three change the summation order, hence the last bits of the results. */
 int a2cid_set_stats_tuning(a2cid_ctx *ctx, int32_t pieces, int32_t rows, int32_t blocks, int32_t nontemporal);
 
-/* The check the library applies to x and xt at creation and to every xi and c a batch will read:
+/* The check the library applies to x and xt at creation and to every xi, c and h a batch will read:
  * A2CID_OK if [p, p + bytes) is device (or managed) memory of the context's GPU that does not run
  * past the end of its allocation, A2CID_EINVAL otherwise (a host pointer, another GPU's memory, a
  * span longer than what was allocated).  It sees allocations, not tensors: a span inside a
@@ -364,7 +368,7 @@ int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream
 
 /* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
  * the byte count of one pass per event (32 d for a gossip event; 16 d for a gradient event plus
- * 4 d for each of xi and c that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
+ * 4 d for each of xi, c and h that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
  * a2cid_average), and the bytes the launched kernels move by construction: the same for modes 0
  * and 1; for mode 3, 8 d for every row read from or written to memory (a2cid_plan_chain) plus the
  * gradient inputs; for mode 2, 16 d

@@ -38,12 +38,12 @@ class a2cid_buffers(C.Structure):
 class a2cid_op(C.Structure):
     _fields_ = [("t", C.c_double), ("kind", C.c_int32), ("i", C.c_int32), ("j", C.c_int32),
                 ("gamma", C.c_float), ("gscale", C.c_float), ("reserved", C.c_int32),
-                ("xi", C.c_void_p), ("c", C.c_void_p), ("id", C.c_int64)]
+                ("xi", C.c_void_p), ("c", C.c_void_p), ("h", C.c_void_p), ("id", C.c_int64)]
 
 
 OP_DTYPE = np.dtype([("t", "<f8"), ("kind", "<i4"), ("i", "<i4"), ("j", "<i4"), ("gamma", "<f4"),
-                     ("gscale", "<f4"), ("reserved", "<i4"), ("xi", "<u8"), ("c", "<u8"), ("id", "<i8")])
-assert OP_DTYPE.itemsize == C.sizeof(a2cid_op) == 56
+                     ("gscale", "<f4"), ("reserved", "<i4"), ("xi", "<u8"), ("c", "<u8"), ("h", "<u8"), ("id", "<i8")])
+assert OP_DTYPE.itemsize == C.sizeof(a2cid_op) == 64
 
 
 class a2cid_event_batch(C.Structure):

@@ -84,7 +84,7 @@ struct a2cid_ctx {
     int threads = 256;
     int walk = 3;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident; 3: chain
     int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
-    float *zero_dev = nullptr;          // one zero float: stands in for absent gradient inputs
+    float *zero_dev = nullptr;          // a zero float and, behind it, a one: stand in for absent gradient inputs
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
@@ -300,7 +300,7 @@ int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, 
     }
     const int cols = c->resident_cols;
     const unsigned blocks = (unsigned)((c->d + 64 * cols - 1) / (64 * cols));
-    const size_t lds = sizeof(Pair) * 64 * cols * ((size_t)n_rows + kStage);
+    const size_t lds = resident_lds_bytes(cols, n_rows);
 #define A2CID_RESIDENT(W, C)                                                                                     \
     do {                                                                                                         \
         if (lds > 65536)                                                                                         \
@@ -433,6 +433,8 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     A2CID_HIP(hipHostMalloc((void **)&c->out_host, sizeof(double) * m, hipHostMallocDefault));
     A2CID_HIP(hipMalloc((void **)&c->zero_dev, 256));
     A2CID_HIP(hipMemset(c->zero_dev, 0, 256));
+    const float one = 1.f;
+    A2CID_HIP(hipMemcpy(c->zero_dev + 1, &one, sizeof(one), hipMemcpyHostToDevice));
     double *static_ptr = nullptr;       // resolved here so that a2cid_stats_static never has to look it up
     if (int rc = static_scratch(c->device, &static_ptr)) return rc;
     return A2CID_OK;
@@ -479,6 +481,8 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
             if (int rc = check_device_span(c, op.xi, sizeof(float) * (size_t)c->d, "xi of a gradient event")) return rc;
         if (op.c && op.gscale != 0.f)
             if (int rc = check_device_span(c, op.c, sizeof(float) * (size_t)c->d, "c of a gradient event")) return rc;
+        if (op.h && op.gscale != 0.f)
+            if (int rc = check_device_span(c, op.h, sizeof(float) * (size_t)c->d, "h of a gradient event")) return rc;
     }
     const int64_t cap = piece_capacity(c);
     for (int32_t l = 0; l < batch->n_levels; ++l) {
@@ -494,7 +498,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
     c->n_gossip += c->plan.n_gossip;
     c->n_grad += c->plan.n_grad;
     c->alg_bytes += (double)c->d * (32.0 * c->plan.n_gossip + 16.0 * c->plan.n_grad +
-                                    4.0 * c->plan.n_grad_xi + 4.0 * c->plan.n_grad_c);
+                                    4.0 * (c->plan.n_grad_xi + c->plan.n_grad_c + c->plan.n_grad_h));
     return A2CID_OK;
 }
 
@@ -519,17 +523,16 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             auto fill = [&](DevOp &o, int64_t src) {
                 const a2cid_op &op = batch->ops[src];
                 const a2cid_coef &cf = c->plan.coef[src];
-                o.kind = op.kind == A2CID_KIND_GOSSIP ? kOpGossip : kOpGradient;
+                o.kind = (op.kind == A2CID_KIND_GOSSIP ? kOpGossip : kOpGradient) | (c->order ? kFlagListing << 8 : 0);
                 o.row_i = op.i;
                 o.row_j = op.kind == A2CID_KIND_GOSSIP ? op.j : op.i;
                 o.b_i = cf.b_pre_i; o.b_j = cf.b_pre_j;
                 o.bp_i = cf.b_post_i; o.bp_j = cf.b_post_j;
                 o.gamma = op.gamma; o.gscale = op.gscale;
-                o.flags = c->order;
                 o.xi = op.kind == A2CID_KIND_GRADIENT ? op.xi : nullptr;
                 o.c = op.kind == A2CID_KIND_GRADIENT ? op.c : nullptr;
+                o.h = op.kind == A2CID_KIND_GRADIENT ? op.h : nullptr;
                 o.loc = 0;                  // every row from and to memory
-                o.pad1 = 0;
             };
             int64_t n_dev = count;          // records of the device table
             if (c->walk == 3) {
@@ -563,8 +566,8 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             if (c->walk == 2) {
                 // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
                 // cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring)
-                int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0;
-                const uintptr_t zero = (uintptr_t)c->zero_dev | 1u;
+                int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
+                const uintptr_t zero = (uintptr_t)c->zero_dev | 1u, one = (uintptr_t)(c->zero_dev + 1) | 1u;
                 c->slot_of.assign(c->n, -1);
                 for (int32_t ll = l; ll < l_end; ++ll) {
                     const int64_t lo = batch->level_off[ll] - first, hi = batch->level_off[ll + 1] - first;
@@ -580,21 +583,24 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                     };
                     for (int64_t k = lo; k < hi; ++k) {
                         const DevOp &o = s->host[k];
-                        if (o.kind == kOpGradient && n_grad - g_before == kStage) close_sub(k);
+                        const int32_t kind = op_kind(o.kind);
+                        if (kind == kOpGradient && n_grad - g_before == kStage) close_sub(k);
                         if (k - sub == 255) close_sub(k);
                         if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
                         if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
                         ResOp &r = s->res_host[k];
-                        r.w0 = (uint32_t)o.kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) | (c->order ? 8u : 0u) |
+                        r.w0 = (uint32_t)kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) | (c->order ? 8u : 0u) |
                                ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
                         r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
                         r.gamma = o.gamma; r.gscale = o.gscale;
-                        if (o.kind == kOpGradient) {
+                        if (kind == kOpGradient) {
                             r.gidx = (uint32_t)n_grad;
                             s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
                             s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
+                            s->gin_host[n_grad].h = (o.h && o.gscale != 0.f) ? (uintptr_t)o.h : one;
                             n_xi += o.xi != nullptr;
                             n_c += o.c && o.gscale != 0.f;
+                            n_h += o.h && o.gscale != 0.f;
                             ++n_grad;
                         }
                     }
@@ -607,7 +613,7 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 if (n_grad > 0)
                     A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad,
                                              hipMemcpyHostToDevice, c->stream));
-                c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c));
+                c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c + n_h));
                 if (int rc = launch_resident(c, s, (int32_t)count, n_grad, n_rows)) return rc;
                 A2CID_HIP(hipEventRecord(s->done, c->stream));
                 s->in_flight = true;
@@ -620,7 +626,8 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             } else {
                 for (int64_t k = 0; k < count; ++k) {
                     const DevOp &o = s->host[k];
-                    moved += o.kind == kOpGossip ? 32.0 : 16.0 + (o.xi ? 4.0 : 0.0) + ((o.c && o.gscale != 0.f) ? 4.0 : 0.0);
+                    moved += op_kind(o.kind) == kOpGossip ? 32.0 : 16.0 + (o.xi ? 4.0 : 0.0) +
+                             ((o.c && o.gscale != 0.f) ? 4.0 : 0.0) + ((o.h && o.gscale != 0.f) ? 4.0 : 0.0);
                 }
             }
             c->moved_bytes += moved * (double)c->d;
@@ -872,7 +879,7 @@ int a2cid_set_resident_group(a2cid_ctx *c, int32_t group, int32_t cols) {
     if (cols != 1 && cols != 2 && cols != 4) return fail(A2CID_EINVAL, "cols must be 1, 2 or 4");
     if ((cols == 2 && group < 4) || (cols == 4 && group < 8))
         return fail(A2CID_EINVAL, "cols = 2 needs group >= 4 and cols = 4 needs group >= 8");
-    if (sizeof(Pair) * 64 * (size_t)cols * ((size_t)c->n + kStage) > 160 * 1024)
+    if (resident_lds_bytes(cols, c->n) > 160 * 1024)
         return fail(A2CID_EINVAL, "%d workers x %d columns per lane do not fit into 160 KiB of LDS", c->n, cols);
     c->group = group;
     c->resident_cols = cols;

@@ -211,7 +211,7 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
     const int32_t n = g.n;
     plan.coef.assign((size_t)batch->n_ops, a2cid_coef{0.f, 0.f, 0.f, 0.f});
     plan.t_after.assign(t_now, t_now + n);
-    plan.n_gossip = plan.n_grad = plan.n_grad_xi = plan.n_grad_c = 0;
+    plan.n_gossip = plan.n_grad = plan.n_grad_xi = plan.n_grad_c = plan.n_grad_h = 0;
     scratch.level_stamp.assign(n, 0);
     scratch.last_op.assign(n, -1);
     const bool sync = std::isfinite(batch->t_sync);
@@ -235,11 +235,12 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
             } else if (op.kind == A2CID_KIND_GRADIENT) {
                 if (!std::isfinite(op.gamma) || !std::isfinite(op.gscale))
                     return fail(A2CID_EINVAL, "op %lld: gamma / gscale not finite", (long long)k);
-                if (((uintptr_t)op.xi | (uintptr_t)op.c) & 15u)
-                    return fail(A2CID_EALIGN, "op %lld: xi / c must be 16-byte aligned", (long long)k);
+                if (((uintptr_t)op.xi | (uintptr_t)op.c | (uintptr_t)op.h) & 15u)
+                    return fail(A2CID_EALIGN, "op %lld: xi / c / h must be 16-byte aligned", (long long)k);
                 ++plan.n_grad;
                 if (op.xi) ++plan.n_grad_xi;
                 if (op.c && op.gscale != 0.f) ++plan.n_grad_c;
+                if (op.h && op.gscale != 0.f) ++plan.n_grad_h;
             } else {
                 return fail(A2CID_EINVAL, "op %lld: unknown kind %d", (long long)k, op.kind);
             }
@@ -577,7 +578,8 @@ void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots
         if (step.src_i == A2CID_LOC_MEMORY) s.bytes_per_column += 8.0;
         if (ne == 2 && step.src_j == A2CID_LOC_MEMORY) s.bytes_per_column += 8.0;
         if (ops[pick].kind == A2CID_KIND_GRADIENT)
-            s.bytes_per_column += (ops[pick].xi ? 4.0 : 0.0) + ((ops[pick].c && ops[pick].gscale != 0.f) ? 4.0 : 0.0);
+            s.bytes_per_column += (ops[pick].xi ? 4.0 : 0.0) + ((ops[pick].c && ops[pick].gscale != 0.f) ? 4.0 : 0.0) +
+                                  ((ops[pick].h && ops[pick].gscale != 0.f) ? 4.0 : 0.0);
         prev = (int64_t)s.steps.size();
         s.steps.push_back(step);
         pw[0] = step.row_i; pw[1] = step.row_j; npw = ne;

@@ -36,7 +36,7 @@ double mix_coefficient(double eta, double tau);
 struct Plan {
     std::vector<a2cid_coef> coef;   // one per op
     std::vector<double> t_after;    // n time stamps after the batch
-    int64_t n_gossip = 0, n_grad = 0, n_grad_xi = 0, n_grad_c = 0;
+    int64_t n_gossip = 0, n_grad = 0, n_grad_xi = 0, n_grad_c = 0, n_grad_h = 0;
 };
 
 // Pure host function behind a2cid_plan_batch and a2cid_apply_events.  scratch_* are

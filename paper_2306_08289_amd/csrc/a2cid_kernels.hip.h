@@ -22,24 +22,25 @@ enum : int32_t { kOpGradient = 0, kOpGossip = 1, kOpMixOnly = 2, kOpSpill = 3 };
 // One operation of a level as the kernels see it (64 bytes).  Every field is uniform across
 // the workgroup that executes the operation, so the compiler keeps it in scalar registers.
 struct DevOp {
-    int32_t kind;
+    int32_t kind;                // kOp* in the low byte, kFlag* bits above it (op_kind, op_flags)
     int32_t row_i, row_j;        // worker rows (row_j unused unless gossip)
     float b_i, b_j;              // mixing to the event time: off-diagonal of exp(tau A)
     float bp_i, bp_j;            // trailing mixing (0 = none)
     float gamma, gscale;         // gradient step size and slope of the affine gradient model
-    int32_t flags;               // kFlag* bits
-    const float *xi;             // additive gradient term or nullptr
-    const float *c;              // centre of the affine gradient model or nullptr
     uint32_t loc;                // chain kernel: where the rows come from and go to, one kLoc* code per byte:
                                  // src_i | src_j << 8 | dst_i << 16 | dst_j << 24 (32-bit fields only: the
                                  // record then stays in scalar registers)
-    int32_t pad1;
+    const float *xi;             // additive gradient term or nullptr
+    const float *c;              // centre of the affine gradient model or nullptr
+    const float *h;              // per-coordinate curvature of the gradient model or nullptr (ones)
 };
 static_assert(sizeof(DevOp) == 64, "DevOp layout");
 
 enum : int32_t {
     kFlagListing = 1,            // jumps from the stored (pre-mix) values, Algorithm 1's listing order
 };
+__host__ __device__ __forceinline__ int32_t op_kind(int32_t word) { return word & 255; }
+__host__ __device__ __forceinline__ int32_t op_flags(int32_t word) { return word >> 8; }
 
 // Chain kernel: where a worker's columns of the workgroup's tile are.
 enum : uint32_t {
@@ -75,13 +76,15 @@ __device__ __forceinline__ void gossip_update(T &xi, T &xti, T &xj, T &xtj, cons
     mix(xj, xtj, op.bp_j);
 }
 
-// Gradient jump of Eq. (1) with g = gscale (x - c) + xi, taken at the mixed point (pre = false) or
-// at the stored point (pre = true, Algorithm 1 as listed).
+// Gradient jump of Eq. (1) with g = gscale h (x - c) + xi (h: the coordinate's curvature, 1 when the event
+// carries none: gscale * 1 is exact, so such events compute what they always did), taken at the mixed point
+// (pre = false) or at the stored point (pre = true, Algorithm 1 as listed).
 template <typename T, typename Op>
-__device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, const Op &op, bool pre) {
-    const T g_stored = op.gscale * (x - c) + xi;
+__device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, T h, const Op &op, bool pre) {
+    const T slope = op.gscale * h;
+    const T g_stored = slope * (x - c) + xi;
     mix(x, xt, op.b_i);
-    const T g = pre ? g_stored : op.gscale * (x - c) + xi;
+    const T g = pre ? g_stored : slope * (x - c) + xi;
     x -= op.gamma * g;
     xt -= op.gamma * g;
     mix(x, xt, op.bp_i);
@@ -115,14 +118,15 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                                               int64_t d, const DevOp &op, int64_t tile,
                                               float alpha, float alpha_t) {
     const int64_t n4 = d >> 2;                                   // whole float4 pieces per row
-    const bool pre = (op.flags & kFlagListing) != 0;
+    const bool pre = (op_flags(op.kind) & kFlagListing) != 0;
+    const int32_t kind = op_kind(op.kind);
     const int64_t base = (int64_t)tile * (U * TPB) + threadIdx.x;
     const bool full = (int64_t)(tile + 1) * (U * TPB) <= n4;
 
     float *xi_row = x + (int64_t)op.row_i * ld;
     float *xti_row = xt + (int64_t)op.row_i * ld;
 
-    if (op.kind == kOpGossip) {
+    if (kind == kOpGossip) {
         float *xj_row = x + (int64_t)op.row_j * ld;
         float *xtj_row = xt + (int64_t)op.row_j * ld;
         v4f *pi = (v4f *)xi_row, *pti = (v4f *)xti_row, *pj = (v4f *)xj_row, *ptj = (v4f *)xtj_row;
@@ -162,12 +166,13 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
         }
     } else {
         v4f *pi = (v4f *)xi_row, *pti = (v4f *)xti_row;
-        const bool grad = op.kind == kOpGradient;
+        const bool grad = kind == kOpGradient;
         const bool has_xi = grad && op.xi != nullptr;
         const bool has_c = grad && op.c != nullptr && op.gscale != 0.f;
-        const v4f *pxi = (const v4f *)op.xi, *pc = (const v4f *)op.c;
-        const v4f zero = {0.f, 0.f, 0.f, 0.f};
-        v4f a[U], at[U], g[U], c[U];
+        const bool has_h = grad && op.h != nullptr && op.gscale != 0.f;
+        const v4f *pxi = (const v4f *)op.xi, *pc = (const v4f *)op.c, *ph = (const v4f *)op.h;
+        const v4f zero = {0.f, 0.f, 0.f, 0.f}, one = {1.f, 1.f, 1.f, 1.f};
+        v4f a[U], at[U], g[U], c[U], h[U];
         if (full) {
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -175,11 +180,12 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                 a[u] = load4<NT>(pi + k); at[u] = load4<NT>(pti + k);
                 g[u] = has_xi ? load4<true>(pxi + k) : zero;
                 c[u] = has_c ? load4<true>(pc + k) : zero;
+                h[u] = has_h ? load4<true>(ph + k) : one;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const int64_t k = base + u * TPB;
-                if (grad) gradient_update(a[u], at[u], g[u], c[u], op, pre);
+                if (grad) gradient_update(a[u], at[u], g[u], c[u], h[u], op, pre);
                 else mix(a[u], at[u], op.b_i);
                 store4<NT>(pi + k, a[u]); store4<NT>(pti + k, at[u]);
             }
@@ -191,7 +197,8 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
                     a[u] = pi[k]; at[u] = pti[k];
                     g[u] = has_xi ? pxi[k] : zero;
                     c[u] = has_c ? pc[k] : zero;
-                    if (grad) gradient_update(a[u], at[u], g[u], c[u], op, pre);
+                    h[u] = has_h ? ph[k] : one;
+                    if (grad) gradient_update(a[u], at[u], g[u], c[u], h[u], op, pre);
                     else mix(a[u], at[u], op.b_i);
                     pi[k] = a[u]; pti[k] = at[u];
                 }
@@ -201,8 +208,8 @@ __device__ __forceinline__ void apply_op_tile(float *__restrict__ x, float *__re
             const int64_t k = (n4 << 2) + threadIdx.x;
             if (threadIdx.x < 4 && k < d) {
                 float s0 = xi_row[k], s1 = xti_row[k];
-                const float gk = has_xi ? op.xi[k] : 0.f, ck = has_c ? op.c[k] : 0.f;
-                if (grad) gradient_update(s0, s1, gk, ck, op, pre);
+                const float gk = has_xi ? op.xi[k] : 0.f, ck = has_c ? op.c[k] : 0.f, hk = has_h ? op.h[k] : 1.f;
+                if (grad) gradient_update(s0, s1, gk, ck, hk, op, pre);
                 else mix(s0, s1, op.b_i);
                 xi_row[k] = s0; xti_row[k] = s1;
             }
@@ -256,19 +263,21 @@ struct OpCoef { float b_i, b_j, bp_i, bp_j, gamma, gscale; };
 __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__restrict__ xt, int64_t ld, int64_t d,
                                               const DevOp &op, float alpha, float alpha_t) {
     const int64_t k = ((d >> 2) << 2) + threadIdx.x;
-    if (threadIdx.x >= 4 || k >= d || op.kind == kOpSpill) return;
-    const bool pre = (op.flags & kFlagListing) != 0;
+    const int32_t kind = op_kind(op.kind);
+    if (threadIdx.x >= 4 || k >= d || kind == kOpSpill) return;
+    const bool pre = (op_flags(op.kind) & kFlagListing) != 0;
     float *xi_row = x + (int64_t)op.row_i * ld, *xti_row = xt + (int64_t)op.row_i * ld;
     float s0 = xi_row[k], s1 = xti_row[k];
-    if (op.kind == kOpGossip) {
+    if (kind == kOpGossip) {
         float *xj_row = x + (int64_t)op.row_j * ld, *xtj_row = xt + (int64_t)op.row_j * ld;
         float s2 = xj_row[k], s3 = xtj_row[k];
         gossip_update(s0, s1, s2, s3, op, alpha, alpha_t, pre);
         xj_row[k] = s2; xtj_row[k] = s3;
-    } else if (op.kind == kOpGradient) {
+    } else if (kind == kOpGradient) {
         const float gk = op.xi != nullptr ? op.xi[k] : 0.f;
         const float ck = (op.c != nullptr && op.gscale != 0.f) ? op.c[k] : 0.f;
-        gradient_update(s0, s1, gk, ck, op, pre);
+        const float hk = (op.h != nullptr && op.gscale != 0.f) ? op.h[k] : 1.f;
+        gradient_update(s0, s1, gk, ck, hk, op, pre);
     } else {
         mix(s0, s1, op.b_i);
     }
@@ -352,7 +361,8 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
     for (int32_t k = 0; k < n_ops; ++k) {
         // field by field: the record stays in scalar registers
         const DevOp *rec = ops + k;
-        const int32_t kind = rec->kind, row_i = rec->row_i, row_j = rec->row_j;
+        const int32_t word = rec->kind, row_i = rec->row_i, row_j = rec->row_j;
+        const int32_t kind = op_kind(word);
         const uint32_t loc = rec->loc;
         const uint32_t src_i = loc & 255u, src_j = (loc >> 8) & 255u, dst_i = (loc >> 16) & 255u, dst_j = loc >> 24;
         if (kind == kOpSpill) {                          // a parked worker goes back to memory
@@ -361,7 +371,7 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
             chain_put<U, TPB>(kLocMemory, row_i, b, bt, xs, xts, ld4, parked, lp, act);
             continue;
         }
-        const bool pre = (rec->flags & kFlagListing) != 0;
+        const bool pre = (op_flags(word) & kFlagListing) != 0;
         const OpCoef oc = {rec->b_i, rec->b_j, rec->bp_i, rec->bp_j, rec->gamma, rec->gscale};
         if (src_i != kLocCarry) chain_fetch<U, TPB>(src_i, row_i, a, at, xs, xts, ld4, parked, lp, act);
         if (kind == kOpGossip) {
@@ -381,18 +391,21 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
             }
         } else {
             if (kind == kOpGradient) {
-                const float *xi = rec->xi, *cc = rec->c;
+                const float *xi = rec->xi, *cc = rec->c, *hh = rec->h;
                 const bool has_xi = xi != nullptr;
                 const bool has_c = cc != nullptr && oc.gscale != 0.f;
-                const v4f *pxi = (const v4f *)xi + tile0, *pc = (const v4f *)cc + tile0;
-                v4f g[U], c[U];
+                const bool has_h = hh != nullptr && oc.gscale != 0.f;
+                const v4f *pxi = (const v4f *)xi + tile0, *pc = (const v4f *)cc + tile0, *ph = (const v4f *)hh + tile0;
+                const v4f one = {1.f, 1.f, 1.f, 1.f};
+                v4f g[U], c[U], h[U];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     g[u] = (has_xi && act[u]) ? load4<true>(pxi + lp[u]) : zero;
                     c[u] = (has_c && act[u]) ? load4<true>(pc + lp[u]) : zero;
+                    h[u] = (has_h && act[u]) ? load4<true>(ph + lp[u]) : one;
                 }
 #pragma unroll
-                for (int u = 0; u < U; ++u) gradient_update(a[u], at[u], g[u], c[u], oc, pre);
+                for (int u = 0; u < U; ++u) gradient_update(a[u], at[u], g[u], c[u], h[u], oc, pre);
             } else {
 #pragma unroll
                 for (int u = 0; u < U; ++u) mix(a[u], at[u], oc.b_i);
@@ -439,8 +452,8 @@ struct ResOp {                   // 32 bytes
 static_assert(sizeof(ResOp) == 32, "ResOp layout");
 
 // Gradient inputs of the launch's gradient events, in order.  A pointer with bit 0 set addresses a
-// single float (a zero) that every column reads; otherwise column k is at pointer + k.
-struct GradIn { uintptr_t xi, c; };
+// single float (a zero for xi and c, a one for h) that every column reads; otherwise column k is at pointer + k.
+struct GradIn { uintptr_t xi, c, h; };
 
 constexpr int kStage = 16;       // LDS ring slots for gradient inputs
 
@@ -505,6 +518,15 @@ __device__ __forceinline__ Cols<C> grad_input_cols(uintptr_t p, int64_t col, int
 template <int C>
 struct TileCell { Pair p[C]; };
 
+// The staged inputs of one gradient event at a lane's columns.
+template <int C>
+struct StageCell { float xi[C], c[C], h[C]; };
+
+// Dynamic LDS of the resident kernel: the tile rows, then the ring of staged gradient inputs.
+constexpr size_t resident_lds_bytes(int cols, int n_rows) {
+    return (sizeof(Pair) * (size_t)n_rows + 3 * sizeof(float) * (size_t)kStage) * 64 * (size_t)cols;
+}
+
 template <int W, int C>
 __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x, float *__restrict__ xt,
                                                           int64_t ld, int64_t d, const ResOp *__restrict__ ops,
@@ -513,7 +535,7 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
                                                           int32_t n_rows, float alpha, float alpha_t) {
     extern __shared__ unsigned char lds_raw[];
     TileCell<C> *tile = (TileCell<C> *)lds_raw;          // [n_rows][64]
-    TileCell<C> *gstage = tile + (size_t)n_rows * 64;    // [kStage][64]: (xi, c) of staged gradient events
+    StageCell<C> *gstage = (StageCell<C> *)(tile + (size_t)n_rows * 64);   // [kStage][64]: inputs of staged gradient events
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * C;
@@ -563,18 +585,19 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             // fill the ring: everything up to g_before + kStage (older ordinals are consumed)
             int32_t hi = g_before + kStage;
             if (hi > n_grad) hi = n_grad;
-            TileCell<C> gv[kStage / W + 1];
+            StageCell<C> gv[kStage / W + 1];
 #pragma unroll
             for (int u = 0; u < kStage / W + 1; ++u) {
                 const int32_t o = staged_hi + wave + u * W;
 #pragma unroll
-                for (int c = 0; c < C; ++c) { gv[u].p[c].x = 0.f; gv[u].p[c].xt = 0.f; }
+                for (int c = 0; c < C; ++c) { gv[u].xi[c] = 0.f; gv[u].c[c] = 0.f; gv[u].h[c] = 1.f; }
                 if (o < hi) {
                     const GradIn in = gin[o];
                     if (valid) {
-                        const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d);
+                        const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d),
+                                      hh = grad_input_cols<C>(in.h, col, d);
 #pragma unroll
-                        for (int c = 0; c < C; ++c) { gv[u].p[c].x = a.v[c]; gv[u].p[c].xt = cc.v[c]; }
+                        for (int c = 0; c < C; ++c) { gv[u].xi[c] = a.v[c]; gv[u].c[c] = cc.v[c]; gv[u].h[c] = hh.v[c]; }
                     }
                 }
             }
@@ -625,9 +648,9 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
                 OpCoef oc;
                 oc.b_i = b_i; oc.bp_i = 0.f;
                 oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
-                const TileCell<C> in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
+                const StageCell<C> in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
 #pragma unroll
-                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.p[c].x, in.p[c].xt, oc, pre);
+                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.xi[c], in.c[c], in.h[c], oc, pre);
                 if (trailing) {
                     const float bp_i = lane_f32(rb.x, l);
 #pragma unroll

@@ -96,6 +96,13 @@ class Workload:
                 self.c = torch.empty((n, self.ld), dtype=torch.float32, device=self.device)
                 for i in range(n):
                     fill.fill_normal(self.c[i, :d], cfg.seed, gen.DOMAIN_C, i, 1.0)
+            self.h = None
+            if cfg.curvature:
+                self.h = torch.empty((n, self.ld), dtype=torch.float32, device=self.device)
+                for i in range(n):
+                    row = self.h[i, :d]
+                    fill.fill_normal(row, cfg.seed, gen.DOMAIN_H, i, 1.0)
+                    row.mul_(row).clamp_(max=4.0).mul_(0.75).add_(0.25)      # synth.gen.curvature, step by step
             self.xi = None
             if cfg.xi_sigma > 0:
                 if xi_slots is None:
@@ -123,6 +130,8 @@ class Workload:
         row_bytes = self.ld * 4
         if self.c is not None:
             ops["c"][grad] = self.c.data_ptr() + ops["i"][grad].astype(np.uint64) * np.uint64(row_bytes)
+        if self.h is not None:
+            ops["h"][grad] = self.h.data_ptr() + ops["i"][grad].astype(np.uint64) * np.uint64(row_bytes)
         if self.xi is not None:
             slots = self.xi.shape[0]
             if not self.reuse_xi and len(grad) > slots:

@@ -32,6 +32,7 @@ class Config:
     eta: float = None                # explicit override (config 1 fixes eta = 0.5)
     alpha_tilde: float = None        # explicit override
     gamma: float = GAMMA
+    curvature: bool = False          # per-worker, per-coordinate curvatures h_i (strongly convex local quadratics)
     extra: dict = field(default_factory=dict)
 
 

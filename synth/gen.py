@@ -27,6 +27,7 @@ import numpy as np
 DOMAIN_INIT = 1   # row = worker index: initial parameters x_i(0)
 DOMAIN_C = 2      # row = worker index: minimiser c_i of the local quadratic
 DOMAIN_XI = 3     # row = serial event index: additive gradient noise of that event
+DOMAIN_H = 5      # row = worker index: the normals behind the curvatures h_i of the local quadratic (4: straggler rates)
 
 _M32 = np.uint64(0xFFFFFFFF)
 _f = np.float32
@@ -156,3 +157,10 @@ def normal_rows_fast(seed, domain, rows, cols, sigma=1.0, mean=0.0):
         _c_library().synth_normal_rows(int(seed), int(domain), rows, len(rows), cols, len(cols),
                                        float(sigma), float(mean), out)
     return out
+
+
+def curvature(z):
+    """Curvatures of a local quadratic from standard normals: h = 0.25 + 0.75 min(z^2, 4), in [0.25, 3.25] with mean
+    about 0.96, every step an individually rounded fp32 operation (the device harness does the same three steps)."""
+    z = np.asarray(z, np.float32)
+    return (np.minimum(z * z, _f(4.0)) * _f(0.75) + _f(0.25)).astype(np.float32)

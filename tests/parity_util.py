@@ -53,6 +53,8 @@ class OracleStream:
         x0 = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_INIT, np.arange(cfg.n), self.cols, cfg.init_sigma)
         self.state = core.State(x0, None, eta, alpha, alpha_t, order=order)
         self.c = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_C, np.arange(cfg.n), self.cols, 1.0) if cfg.use_c else None
+        self.h = gen.curvature(gen.normal_rows_fast(cfg.seed, gen.DOMAIN_H, np.arange(cfg.n), self.cols, 1.0)) \
+            if cfg.curvature else None
         self.events = None
         self.done = 0
 
@@ -74,16 +76,19 @@ class OracleStream:
         cfg, ev = self.cfg, self.events[self.done:upto]
         is_grad = ev.kind == 0
         m = len(ev)
-        c_row = xi = xi_row = None
+        c_row = xi = xi_row = h_row = None
         if self.c is not None:
             c_row = np.where(is_grad, ev.i, -1)
+        if self.h is not None:
+            h_row = np.where(is_grad, ev.i, -1)
         if cfg.xi_sigma > 0:
             ids = np.nonzero(is_grad)[0]
             xi = gen.normal_rows_fast(cfg.seed, gen.DOMAIN_XI, ids + self.done, self.cols, cfg.xi_sigma)
             xi_row = np.full(m, -1, np.int64)
             xi_row[ids] = np.arange(len(ids))
         # the engine receives gamma and gscale as fp32 values
-        self.state.apply(ev, float(np.float32(cfg.gamma)), float(np.float32(cfg.gscale)), xi, xi_row, self.c, c_row)
+        self.state.apply(ev, float(np.float32(cfg.gamma)), float(np.float32(cfg.gscale)), xi, xi_row, self.c, c_row,
+                         self.h, h_row)
         self.done = upto
         return self.state
 

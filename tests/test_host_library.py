@@ -181,6 +181,7 @@ def test_planner_trailing_mix_goes_to_each_workers_last_operation():
     ([dict(t=float("inf"), kind=0, i=0, j=-1)], [0, 1], float("nan"), binding.EINVAL),
     ([dict(t=1.0, kind=0, i=0, j=-1, gamma=float("nan"))], [0, 1], float("nan"), binding.EINVAL),
     ([dict(t=1.0, kind=0, i=0, j=-1, xi=8)], [0, 1], float("nan"), binding.EALIGN),
+    ([dict(t=1.0, kind=0, i=0, j=-1, h=4100)], [0, 1], float("nan"), binding.EALIGN),
     ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 2], float("nan"), binding.EMATCHING),        # table does not end at n_ops
     ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 1], 0.5, binding.EORDER),                    # t_sync before an event
     ([dict(t=1.0, kind=0, i=0, j=-1)], [0, 1], float("inf"), binding.EINVAL),
@@ -305,7 +306,8 @@ def _run_chain_programme(n, ops, steps, slots):
             else:
                 assert 0 <= src - binding.LOC_SLOT0 < slots and parked[src - binding.LOC_SLOT0] == (w, version[w]), k
         if ops[k]["kind"] == binding.KIND_GRADIENT:
-            moved += (4 if ops[k]["xi"] else 0) + (4 if ops[k]["c"] and ops[k]["gscale"] != 0 else 0)
+            moved += (4 if ops[k]["xi"] else 0) + (4 if ops[k]["c"] and ops[k]["gscale"] != 0 else 0) + \
+                     (4 if ops[k]["h"] and ops[k]["gscale"] != 0 else 0)
         for w in ws:
             version[w] += 1
         for w, src, dst in zip(ws, srcs, dsts):                           # a slot that is left becomes free
@@ -336,6 +338,7 @@ def _random_ops(rng, n, m, p_grad):
             ops["kind"][k], ops["i"][k], ops["j"][k] = binding.KIND_GRADIENT, rng.integers(n), -1
             ops["xi"][k] = 4096 if rng.random() < 0.7 else 0
             ops["c"][k] = 8192 if rng.random() < 0.5 else 0
+            ops["h"][k] = 12288 if rng.random() < 0.4 else 0
             ops["gscale"][k] = 1.0 if rng.random() < 0.8 else 0.0
         else:
             i, j = rng.choice(n, 2, replace=False)
