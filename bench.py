@@ -28,11 +28,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 
-# HBM bytes per launch of the dominant kernel in the default configuration, from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of known
-# size: profiles/chain_kernel_C4_hbm_counters.md and profiles/walk_kernel_C4_hbm_counters.md.  Only valid for the
-# workload, batch size and kernel it names.
-MEASURED_TRAFFIC = {("C4", 1024, "chain_kernel"): 3.2738e11, ("C4", 1024, "walk_kernel"): 7.9201e11}
+# Bytes per launch that crossed the L2 <-> memory-fabric boundary, from two rocprofv3 --pmc runs of this same
+# command (FETCH_SIZE, then WRITE_SIZE), each scaled by what the same counter reads for the library's copy probe of
+# known size.  NOT a reading of the run that prints the line: `traffic_source` names the committed summary the
+# figure comes from.  Only valid for the workload, batch size, kernel and launch shape it names.  The counters sit
+# between the L2 and the fabric: bytes served by the 256 MB last-level cache behind it count as traffic here.
+MEASURED_TRAFFIC = {
+    ("C4", 1024, "chain_kernel"): (3.2738e11, "profiles/chain_kernel_C4_hbm_counters.md"),
+    ("C4", 1024, "walk_kernel"): (7.9201e11, "profiles/walk_kernel_C4_hbm_counters.md"),
+}
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
@@ -138,6 +142,7 @@ def main():
                          "whose traffic is the algorithmic byte count), 3 = chain (the library's default), "
                          "0 = one launch per level, 2 = LDS-resident")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
+    ap.add_argument("--walk-occupancy", type=int, default=None, help="walk kernel: at most this many workgroups per CU")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
@@ -147,6 +152,7 @@ def main():
                     help="append a short measurement of every configuration (C1..C5) to the JSON line")
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-inplace-probe", action="store_true", help="skip the in-place streaming ceilings")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket each kernel launch with HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -165,6 +171,8 @@ def main():
     if args.slots is not None:
         w.engine.set_chain_slots(args.slots)
     w.engine.set_tuning(args.unroll or 1, args.nontemporal or 0, args.threads or 256, mode)
+    if args.walk_occupancy is not None:
+        w.engine.set_walk_occupancy(args.walk_occupancy)
     if args.group is not None or args.cols is not None:
         w.engine.set_resident_group(args.group or 8, args.cols or 1)
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
@@ -222,15 +230,43 @@ def main():
             return None
         achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
         bound = "hbm" if kernel_name != "resident_kernel" else "instruction issue and LDS latency (not HBM: see frac)"
+        traffic, source = MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name), (None, None)) \
+            if default_shape else (None, None)
         return {"bound": bound, "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name)) if default_shape else None,
+                "traffic": traffic,
+                "traffic_source": None if traffic is None else
+                f"{source}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, scaled by the "
+                "copy probe; bytes between L2 and fabric, per launch; not measured by the run that printed this line",
                 "launches": launches, "avg_launch_ms": kernel_ms / launches,
                 "alg_bytes_per_launch": cnt["moved_bytes"] / launches,
                 "one_pass_bytes_per_launch": cnt["bytes"] / launches,
                 "one_pass_equivalent_GBs": cnt["bytes"] / (kernel_ms * 1e-3) / 1e9}
 
     elapsed, cnt, launches, kernel_ms = measure(args.steps)
+    stats_launches, stats_ms = (0, 0.0) if (args.no_profile or args.no_stats) else w.engine.profile_read_stats()
+
+    # in-place streaming ceilings of this machine on the whole state, with the walk kernel's access shape and a reuse
+    # distance (n / rows_per_op passes of every resident workgroup) far beyond the caches
+    def inplace(rows_per_op, n_ops):
+        w.engine.inplace_probe(rows_per_op, n_ops)                 # warm-up
+        p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        p0.record()
+        moved = sum(w.engine.inplace_probe(rows_per_op, n_ops) for _ in range(3))
+        p1.record()
+        torch.cuda.synchronize()
+        ms = p0.elapsed_time(p1)
+        return {"value": moved / (ms * 1e-3) / 1e9, "unit": "GB/s", "bytes_per_launch": moved / 3,
+                "avg_launch_ms": ms / 3, "passes_per_launch": n_ops}
+    inplace_ceiling = None
+    if not args.no_inplace_probe and cfg.d >= 4:
+        per_pass = 64.0 * (cfg.d // 4)
+        inplace_ceiling = {
+            "what": "in-place pass over the whole state (x and xt of all workers in turn) with the walk kernel's tile and "
+                    "access shape, values multiplied by 1; a row is touched again only after n / rows passes of every "
+                    "workgroup, so nothing is served from a cache when the state is far larger than 256 MB",
+            "gossip_shape": inplace(2, max(8, min(256, int(2.5e10 / per_pass)))),
+            "mixing_shape": inplace(1, max(8, min(512, int(2.5e10 / per_pass))))}
     # bytes: what the launched kernels move by construction; for the headline (walk) kernel that is one full pass
     # per event: 32 d per gossip event, 16 d + 4 d per input per gradient event
     total_bytes = cnt["moved_bytes"] + stats_bytes * args.steps
@@ -255,8 +291,16 @@ def main():
         "frac_of_hbm_peak": value / HBM_PEAK_GBS,
         "one_pass_equivalent_GBs": one_pass_bytes / elapsed / 1e9,
         "copy_ceiling": {"value": copy_gbs, "unit": "GB/s",
-                         "what": f"plain device copy of {8.0 * src.numel() / 1e9:.2f} GB (read + write) on this machine"},
+                         "what": f"plain out-of-place, non-temporal device copy of {8.0 * src.numel() / 1e9:.2f} GB "
+                                 "(read + write) on this machine; also the scale of the HBM byte counters"},
+        "inplace_ceiling": inplace_ceiling,
         "roofline": roofline,
+        "stats_kernel": None if not stats_launches else {
+            "bound": "hbm", "kernel": "stats_kernel", "achieved": stats_bytes * stats_launches / (stats_ms * 1e-3) / 1e9,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": stats_bytes * stats_launches / (stats_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "launches": stats_launches, "avg_launch_ms": stats_ms / stats_launches,
+            "alg_bytes_per_launch": stats_bytes},
     }
     # separate lines: the kernels that keep workers on the chip between events move fewer bytes than one pass per
     # event, so their events/s go up while their HBM GB/s go down; they are never mixed into the headline figure
@@ -272,6 +316,8 @@ def main():
         torch.cuda.synchronize()
         v_steps = max(3, args.steps // 2)
         v_el, vc, v_launches, v_ms = measure(v_steps)
+        if not (args.no_profile or args.no_stats):
+            w.engine.profile_read_stats()
         v_events = vc["gossip"] + vc["gradient"]
         out[key] = {
             "what": "same steps with " + MODE_WHAT[v_mode],
@@ -289,6 +335,8 @@ def main():
     torch.cuda.empty_cache()
     if args.all_configs:
         out["all_configs"] = [short_run(name, args.batch) for name in ("C1", "C2", "C3", "C4", "C4-baseline", "C5")]
+        # the two cache-resident configurations again with batches long enough to amortise launch and host cost
+        out["all_configs"] += [short_run(name, 16384, steps=4, warmup=1) for name in ("C1", "C2")]
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(out))

@@ -318,17 +318,19 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
  * workgroup size (64 ... 1024, a power of two), mode =
+ *  -1: chosen per batch: 3, except for rows so short (d <= 4096) that a launch has a handful of
+ *      workgroups and the host-side planning of mode 3 costs more than it saves: then 1 (default);
  *   0: one launch per level;
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
  *      own columns, each operation reading and writing its rows in device memory (32 d bytes per
  *      gossip event);
  *   3: as 1, but following the programme of a2cid_plan_chain: a worker shared by consecutive
  *      operations stays in registers and workers that come back soon are parked in LDS (16 d bytes
- *      for a gossip event that finds one worker there and leaves one there; default);
+ *      for a gossip event that finds one worker there and leaves one there);
  *   2: as 1, but the workgroup keeps its columns of all touched rows in LDS for the whole batch, so
  *      the state is read and written once per batch instead of once per event (at most 112
  *      workers).
- * Default: 1, 0, 256, 3 (tiles shrink automatically for short rows).  All modes compute the same
+ * Default: 1, 0, 256, -1 (tiles shrink automatically for short rows).  All modes compute the same
  * operations in the same per-worker order and give the same state bit for bit.  In every mode the
  * gradient inputs of a batch must hold their final values, in stream order, before
  * a2cid_apply_events is called. */
@@ -339,6 +341,13 @@ int a2cid_set_tuning(a2cid_ctx *ctx, int32_t unroll, int32_t nontemporal, int32_
  * room for four workgroups of 256 lanes on a CU: more slots save more traffic but leave fewer
  * columns in flight).  0: only the carry registers are used.  Default: 5. */
 int a2cid_set_chain_slots(a2cid_ctx *ctx, int32_t slots);
+
+/* Mode 1 only: at most workgroups_per_cu workgroups of the walk kernel share a compute unit (0, the
+ * default: as many as fit, 8 of 256 lanes).  Fewer resident workgroups mean fewer columns in flight
+ * and a smaller memory footprint per operation, so that a row written by one operation is more often
+ * still in the last-level cache when a later operation reads it; which effect wins depends on how soon
+ * rows come back in the event stream. */
+int a2cid_set_walk_occupancy(a2cid_ctx *ctx, int32_t workgroups_per_cu);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
  * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
@@ -366,6 +375,16 @@ int a2cid_check_device_span(a2cid_ctx *ctx, const void *p, int64_t bytes);
  * practical streaming ceiling of the machine at hand and the scale of its HBM byte counters. */
 int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream);
 
+/* Measurement aid: an in-place pass over the context's own state with the walk kernel's access shape and
+ * (next to) no arithmetic.  n_ops times, every column tile reads the pieces of rows_per_op (1 or 2) consecutive
+ * workers from x and xt, multiplies them by 1 and stores them back, the workers advancing cyclically, so that
+ * a row comes back only after n / rows_per_op passes, beyond the reach of the chip's caches for the state sizes
+ * this is meant for: the rate it reaches is the in-place HBM streaming rate of the machine at hand for the
+ * shape of a gossip event (rows_per_op = 2: four row pieces in, four out) or of a mixing pass (1).  The state
+ * is left unchanged bit for bit.  Asynchronous on the context's stream; *bytes (may be NULL) receives the
+ * bytes the launch moves: n_ops * rows_per_op * 64 * floor(d / 4).  Needs 2 <= n, 1 <= n_ops. */
+int a2cid_inplace_probe(a2cid_ctx *ctx, int32_t rows_per_op, int32_t n_ops, double *bytes);
+
 /* Work enqueued since creation or the last reset: gossip and gradient events, kernel launches,
  * the byte count of one pass per event (32 d for a gossip event; 16 d for a gradient event plus
  * 4 d for each of xi, c and h that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
@@ -376,12 +395,15 @@ int a2cid_stream_probe(const float *src, float *dst, int64_t n, void *hip_stream
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
                    double *one_pass_bytes, double *moved_bytes, int32_t reset);
 
-/* While enabled, every event-kernel launch is bracketed by a pair of HIP events on the
- * context's stream.  a2cid_profile_read waits for the stream, returns the number of launches
- * timed since the previous read and the sum of their durations in milliseconds, and forgets
- * them. */
+/* While enabled, every event-kernel launch and every observables-kernel launch (a2cid_stats,
+ * a2cid_stats_static) is bracketed by a pair of HIP events on the context's stream.
+ * a2cid_profile_read waits for the stream, returns the number of event-kernel launches timed
+ * since the previous read and the sum of their durations in milliseconds, and forgets them;
+ * a2cid_profile_read_stats does the same for the observables kernel (the pass over x and xt, not
+ * the small kernel that adds the partial sums). */
 int a2cid_profile(a2cid_ctx *ctx, int32_t enable);
 int a2cid_profile_read(a2cid_ctx *ctx, int64_t *n_launches, double *kernel_ms);
+int a2cid_profile_read_stats(a2cid_ctx *ctx, int64_t *n_launches, double *kernel_ms);
 
 const char *a2cid_last_error(void);
 const char *a2cid_version(void);

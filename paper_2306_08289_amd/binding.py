@@ -94,8 +94,11 @@ SIGNATURES = {
     "a2cid_counters": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_int64), _P(C.c_int64), _P(C.c_double),
                                  _P(C.c_double), C.c_int32]),
     "a2cid_set_resident_group": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32]),
+    "a2cid_set_walk_occupancy": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_profile": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_profile_read": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_double)]),
+    "a2cid_profile_read_stats": (C.c_int, [C.c_void_p, _P(C.c_int64), _P(C.c_double)]),
+    "a2cid_inplace_probe": (C.c_int, [C.c_void_p, C.c_int32, C.c_int32, _P(C.c_double)]),
     "a2cid_last_error": (C.c_char_p, []),
     "a2cid_version": (C.c_char_p, []),
 }
@@ -323,11 +326,14 @@ class Engine:
         """Raises A2cidError unless [address, address + nbytes) is device memory the kernels may touch."""
         _check(load().a2cid_check_device_span(self._h, C.c_void_p(int(address)), int(nbytes)))
 
-    def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=3):
+    def set_tuning(self, unroll=1, nontemporal=0, threads=256, mode=-1):
         _check(load().a2cid_set_tuning(self._h, int(unroll), int(bool(nontemporal)), int(threads), int(mode)))
 
     def set_chain_slots(self, slots=5):
         _check(load().a2cid_set_chain_slots(self._h, int(slots)))
+
+    def set_walk_occupancy(self, workgroups_per_cu=0):
+        _check(load().a2cid_set_walk_occupancy(self._h, int(workgroups_per_cu)))
 
     def set_resident_group(self, group=8, cols=1):
         _check(load().a2cid_set_resident_group(self._h, int(group), int(cols)))
@@ -350,6 +356,18 @@ class Engine:
         nl, ms = C.c_int64(), C.c_double()
         _check(load().a2cid_profile_read(self._h, C.byref(nl), C.byref(ms)))
         return nl.value, ms.value
+
+    def profile_read_stats(self):
+        nl, ms = C.c_int64(), C.c_double()
+        _check(load().a2cid_profile_read_stats(self._h, C.byref(nl), C.byref(ms)))
+        return nl.value, ms.value
+
+    def inplace_probe(self, rows_per_op, n_ops):
+        """Enqueues the in-place streaming probe on the state; returns the bytes the launch moves."""
+        moved = C.c_double()
+        with self._device():
+            _check(load().a2cid_inplace_probe(self._h, int(rows_per_op), int(n_ops), C.byref(moved)))
+        return moved.value
 
     def close(self):
         if self._h:

@@ -82,7 +82,8 @@ struct a2cid_ctx {
     int unroll = 1;
     int nontemporal = 0;
     int threads = 256;
-    int walk = 3;                       // 0: one launch per level; 1: one walk launch per batch; 2: resident; 3: chain
+    int walk = -1;                      // 0: one launch per level; 1: one walk launch per batch; 2: resident; 3: chain;
+                                        // -1: 3, except 1 for very short rows (event_mode())
     int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
     float *zero_dev = nullptr;          // a zero float and, behind it, a one: stand in for absent gradient inputs
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
@@ -101,9 +102,11 @@ struct a2cid_ctx {
     double moved_bytes = 0.0;           // bytes the launched kernels move by construction (<= alg_bytes)
     ChainPlan chain;
     int chain_slots = 5;                // chain kernel: LDS slots for parked workers
+    int walk_wg_per_cu = 0;             // walk kernel: at most this many workgroups per CU (0: whatever fits)
     // optional per-launch timing
     bool profiling = false;
     std::vector<TimedLaunch> timed;
+    std::vector<TimedLaunch> timed_stats;   // the observables kernel, kept apart from the event kernels
     std::vector<hipEvent_t> event_pool;
 };
 
@@ -241,7 +244,12 @@ void launch_t(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
         hipLaunchKernelGGL((chain_kernel<U, TPB>), dim3((unsigned)blocks), dim3(TPB), lds, c->stream, c->x,
                            c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
     } else if (walk == kLaunchWalk) {
-        hipLaunchKernelGGL((walk_kernel<U, NT, TPB>), dim3((unsigned)blocks), dim3(TPB), 0, c->stream, c->x,
+        // the kernel uses no LDS: asking for 1 / k of the CU's 160 KiB keeps at most k workgroups on a CU
+        const size_t lds = c->walk_wg_per_cu > 0 ? (size_t)(160 * 1024) / c->walk_wg_per_cu - 256 : 0;
+        if (lds > 65536)
+            (void)hipFuncSetAttribute((const void *)walk_kernel<U, NT, TPB>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)lds);      // a failure shows as the launch error that follows
+        hipLaunchKernelGGL((walk_kernel<U, NT, TPB>), dim3((unsigned)blocks), dim3(TPB), lds, c->stream, c->x,
                            c->xt, c->ld, c->d, ops, n_ops, (float)c->alpha, (float)c->alpha_t);
     } else {
         hipLaunchKernelGGL((level_kernel<U, NT, TPB>), dim3((unsigned)blocks, (unsigned)n_ops), dim3(TPB), 0,
@@ -387,6 +395,7 @@ void a2cid_destroy(a2cid_ctx *c) {
     if (c->out_host) (void)hipHostFree(c->out_host);
     if (c->zero_dev) (void)hipFree(c->zero_dev);
     for (TimedLaunch &tl : c->timed) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
+    for (TimedLaunch &tl : c->timed_stats) { (void)hipEventDestroy(tl.start); (void)hipEventDestroy(tl.stop); }
     for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     delete c;
 }
@@ -463,7 +472,12 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 }
 
 // The chain programme of k operations has at most 3 k + slots steps (every spill makes room for a parking).
-static int64_t piece_capacity(const a2cid_ctx *c) { return c->walk == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps; }
+// The event kernel of the next batch.  Left to the library, rows of at most 4096 parameters (a launch of a handful of
+// workgroups, bound by launch and host cost) go to the walk kernel, which needs no programme from the host; everything
+// longer to the chain kernel.
+constexpr int64_t kShortRow = 4096;
+static int event_mode(const a2cid_ctx *c) { return c->walk >= 0 ? c->walk : (c->d <= kShortRow ? 1 : 3); }
+static int64_t piece_capacity(const a2cid_ctx *c) { return event_mode(c) == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps; }
 
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch);
 
@@ -504,6 +518,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
 
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
     const int64_t cap = piece_capacity(c);
+    const int mode = event_mode(c);
     int32_t l = 0;
     while (l < batch->n_levels) {
         // take as many whole levels as fit into one staging buffer (apply_impl has checked that every level does)
@@ -535,7 +550,7 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 o.loc = 0;                  // every row from and to memory
             };
             int64_t n_dev = count;          // records of the device table
-            if (c->walk == 3) {
+            if (mode == 3) {
                 plan_chain(c->n, batch->ops + first, count, c->chain_slots, c->chain);
                 n_dev = (int64_t)c->chain.steps.size();
                 if (n_dev > kSlotOps) return fail(A2CID_EINVAL, "internal: chain programme of %lld steps", (long long)n_dev);
@@ -563,7 +578,7 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             } else {
                 for (int64_t k = 0; k < count; ++k) fill(s->host[k], first + k);
             }
-            if (c->walk == 2) {
+            if (mode == 2) {
                 // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
                 // cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring)
                 int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
@@ -621,7 +636,7 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 continue;
             }
             double moved = 0.0;             // bytes per column that this chunk's launches move
-            if (c->walk == 3) {
+            if (mode == 3) {
                 moved = c->chain.bytes_per_column;
             } else {
                 for (int64_t k = 0; k < count; ++k) {
@@ -632,9 +647,9 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             }
             c->moved_bytes += moved * (double)c->d;
             A2CID_HIP(hipMemcpyAsync(s->dev, s->host, sizeof(DevOp) * (size_t)n_dev, hipMemcpyHostToDevice, c->stream));
-            if (c->walk == 3) {
+            if (mode == 3) {
                 if (int rc = launch_ops(c, s->dev, (int32_t)n_dev, kLaunchChain)) return rc;
-            } else if (c->walk == 1) {
+            } else if (mode == 1) {
                 if (int rc = launch_ops(c, s->dev, (int32_t)count, kLaunchWalk)) return rc;
             } else {
                 for (int32_t ll = l; ll < l_end; ++ll) {
@@ -712,6 +727,14 @@ static int launch_stats(a2cid_ctx *c, const float *b_dev, const MixArgs *args, d
     const int32_t blocks = (int32_t)std::min<int64_t>(n_tiles, max_blocks);
     const int32_t m = 2 * c->n + 2;
     const size_t lds = sizeof(double) * kWaves * 2 * (size_t)c->n + sizeof(float) * (size_t)c->n;
+    // timing is a measurement aid of the allocating entry point only: a2cid_stats_static (args != NULL) takes no events
+    TimedLaunch tl{};
+    const bool timing = c->profiling && !args;
+    if (timing) {
+        if (int rc = get_event(c, &tl.start)) return rc;
+        if (int rc = get_event(c, &tl.stop)) return rc;
+        A2CID_HIP(hipEventRecord(tl.start, c->stream));
+    }
 #define A2CID_STATS_LAUNCH(V, R, NT)                                                                             \
     do {                                                                                                         \
         if (args) {      /* at most kMixArgsMax workers: the dynamic LDS stays below the default cap */            \
@@ -734,6 +757,10 @@ static int launch_stats(a2cid_ctx *c, const float *b_dev, const MixArgs *args, d
     else { if (snt) A2CID_STATS_LAUNCH(2, 2, true); else A2CID_STATS_LAUNCH(2, 2, false); }
 #undef A2CID_STATS_LAUNCH
     A2CID_HIP(hipGetLastError());
+    if (timing) {
+        A2CID_HIP(hipEventRecord(tl.stop, c->stream));
+        c->timed_stats.push_back(tl);
+    }
     hipLaunchKernelGGL(stats_final_kernel, dim3(m), dim3(kThreads), 0, c->stream, partials, blocks, m, out);
     A2CID_HIP(hipGetLastError());
     return A2CID_OK;
@@ -839,10 +866,11 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     if (unroll != 1 && unroll != 2 && unroll != 4) return fail(A2CID_EINVAL, "unroll must be 1, 2 or 4");
     if (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024)
         return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
-    if (mode < 0 || mode > 3) return fail(A2CID_EINVAL, "mode must be 0 (levels), 1 (walk), 2 (resident) or 3 (chain)");
+    if (mode < -1 || mode > 3)
+        return fail(A2CID_EINVAL, "mode must be -1 (automatic), 0 (levels), 1 (walk), 2 (resident) or 3 (chain)");
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
-    if (mode == 3 && (size_t)c->chain_slots * unroll * threads * 32 > 160 * 1024)
+    if ((mode == 3 || mode == -1) && (size_t)c->chain_slots * unroll * threads * 32 > 160 * 1024)
         return fail(A2CID_EINVAL, "%d slots of %d x %d lanes x 32 bytes do not fit into 160 KiB of LDS "
                     "(a2cid_set_chain_slots lowers the slots)", c->chain_slots, unroll, threads);
     c->unroll = unroll;
@@ -868,6 +896,14 @@ int a2cid_set_chain_slots(a2cid_ctx *c, int32_t slots) {
         return fail(A2CID_EINVAL, "%d slots of %d x %d lanes x 32 bytes do not fit into 160 KiB of LDS", slots, c->unroll,
                     c->threads);
     c->chain_slots = slots;
+    return A2CID_OK;
+}
+
+int a2cid_set_walk_occupancy(a2cid_ctx *c, int32_t workgroups_per_cu) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (workgroups_per_cu < 0 || workgroups_per_cu > 32) return fail(A2CID_EINVAL, "workgroups_per_cu must be in [0, 32]");
+    c->walk_wg_per_cu = workgroups_per_cu;
     return A2CID_OK;
 }
 
@@ -933,21 +969,52 @@ int a2cid_profile(a2cid_ctx *c, int32_t enable) {
     return A2CID_OK;
 }
 
-int a2cid_profile_read(a2cid_ctx *c, int64_t *n_launches, double *kernel_ms) {
-    clear_error();
-    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+static int read_timed(a2cid_ctx *c, std::vector<TimedLaunch> &timed, int64_t *n_launches, double *kernel_ms) {
     A2CID_HIP(hipStreamSynchronize(c->stream));
     double total = 0.0;
-    for (TimedLaunch &tl : c->timed) {
+    for (TimedLaunch &tl : timed) {
         float ms = 0.f;
         A2CID_HIP(hipEventElapsedTime(&ms, tl.start, tl.stop));
         total += ms;
         c->event_pool.push_back(tl.start);
         c->event_pool.push_back(tl.stop);
     }
-    if (n_launches) *n_launches = (int64_t)c->timed.size();
+    if (n_launches) *n_launches = (int64_t)timed.size();
     if (kernel_ms) *kernel_ms = total;
-    c->timed.clear();
+    timed.clear();
+    return A2CID_OK;
+}
+
+int a2cid_profile_read(a2cid_ctx *c, int64_t *n_launches, double *kernel_ms) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    return read_timed(c, c->timed, n_launches, kernel_ms);
+}
+
+int a2cid_profile_read_stats(a2cid_ctx *c, int64_t *n_launches, double *kernel_ms) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    return read_timed(c, c->timed_stats, n_launches, kernel_ms);
+}
+
+int a2cid_inplace_probe(a2cid_ctx *c, int32_t rows_per_op, int32_t n_ops, double *bytes) {
+    clear_error();
+    if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (rows_per_op != 1 && rows_per_op != 2) return fail(A2CID_EINVAL, "rows_per_op must be 1 or 2");
+    if (n_ops < 1) return fail(A2CID_EINVAL, "n_ops must be >= 1");
+    if (int rc = enter(c)) return rc;
+    if (int rc = unusable(c)) return rc;
+    const int64_t n4 = c->d >> 2;
+    if (bytes) *bytes = (double)n_ops * rows_per_op * 64.0 * (double)n4;
+    if (n4 == 0) return A2CID_OK;
+    const dim3 grid((unsigned)((n4 + kThreads - 1) / kThreads)), block(kThreads);
+    if (rows_per_op == 2)
+        hipLaunchKernelGGL((inplace_probe_kernel<2, kThreads>), grid, block, 0, c->stream, c->x, c->xt, c->ld, c->d, c->n,
+                           n_ops, 1.0f);
+    else
+        hipLaunchKernelGGL((inplace_probe_kernel<1, kThreads>), grid, block, 0, c->stream, c->x, c->xt, c->ld, c->d, c->n,
+                           n_ops, 1.0f);
+    A2CID_HIP(hipGetLastError());
     return A2CID_OK;
 }
 

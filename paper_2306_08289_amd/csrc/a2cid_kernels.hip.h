@@ -230,34 +230,6 @@ __global__ __launch_bounds__(TPB) void level_kernel(float *__restrict__ x, float
     apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, (int64_t)blockIdx.x, alpha, alpha_t);
 }
 
-// ------------------------------------------------------------------------------------------
-// Walk kernel: grid = column tiles; one launch per batch.  Eq. (1) couples workers but never
-// coordinates, so a workgroup that owns a tile of columns can apply EVERY operation of the batch
-// to that tile, in the batch's (level-sorted, hence per-worker serial) order, without
-// synchronising with any other workgroup: all accesses of a lane hit the lane's own columns and
-// a wave's accesses to one address are performed in program order.  Compared with one launch
-// per level this removes the drain/fill bubble between levels, which matters because most levels
-// of a greedily packed batch hold far fewer than n/2 operations.  Every operation still reads and
-// writes its rows from and to memory (the tiles of all resident workgroups together exceed the
-// caches by far), so the traffic is the same 32 d / 16-24 d bytes per event.
-// Operation records are uniform per workgroup and are fetched with scalar loads.
-// Measured fastest on MI355X with TPB = 256, U = 1 and ordinary (temporal) accesses.
-// ------------------------------------------------------------------------------------------
-template <int U, bool NT, int TPB>
-__global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float *__restrict__ xt,
-                                                   int64_t ld, int64_t d, const DevOp *__restrict__ ops,
-                                                   int32_t n_ops, float alpha, float alpha_t) {
-    const int64_t tile = blockIdx.x;
-    for (int32_t k = 0; k < n_ops; ++k) {
-        const DevOp op = ops[k];
-        apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);
-    }
-}
-
-
-// The coefficients of one operation, as the update functions read them.
-struct OpCoef { float b_i, b_j, bp_i, bp_j, gamma, gscale; };
-
 // The d % 4 trailing columns of the rows of one operation, by lanes 0..3 of the calling workgroup, always
 // through memory (no carry).
 __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__restrict__ xt, int64_t ld, int64_t d,
@@ -283,6 +255,38 @@ __device__ __forceinline__ void apply_op_tail(float *__restrict__ x, float *__re
     }
     xi_row[k] = s0; xti_row[k] = s1;
 }
+
+// ------------------------------------------------------------------------------------------
+// Walk kernel: grid = column tiles; one launch per batch.  Eq. (1) couples workers but never
+// coordinates, so a workgroup that owns a tile of columns can apply EVERY operation of the batch
+// to that tile, in the batch's (level-sorted, hence per-worker serial) order, without
+// synchronising with any other workgroup: all accesses of a lane hit the lane's own columns and
+// a wave's accesses to one address are performed in program order.  Compared with one launch
+// per level this removes the drain/fill bubble between levels, which matters because most levels
+// of a greedily packed batch hold far fewer than n/2 operations.  Every operation still reads and
+// writes its rows from and to memory (the tiles of all resident workgroups together exceed the
+// caches by far), so the traffic is the same 32 d / 16-24 d bytes per event.
+// Operation records are uniform per workgroup and are fetched with scalar loads.
+// Measured fastest on MI355X with TPB = 256, U = 1 and ordinary (temporal) accesses.  Applying two operations on
+// disjoint workers in one pass, with the loads of both in flight together, was measured as well and gains nothing on
+// the event streams (ring: +-0 %, exponential and complete graph: -1 to -3 %), although a plain in-place pass over
+// four rows at a time streams faster than one over two.
+// ------------------------------------------------------------------------------------------
+template <int U, bool NT, int TPB>
+__global__ __launch_bounds__(TPB) void walk_kernel(float *__restrict__ x, float *__restrict__ xt,
+                                                   int64_t ld, int64_t d, const DevOp *__restrict__ ops,
+                                                   int32_t n_ops, float alpha, float alpha_t) {
+    extern __shared__ unsigned char occupancy_ballast[];     // never touched: its size limits the workgroups per CU
+    const int64_t tile = blockIdx.x;
+    for (int32_t k = 0; k < n_ops; ++k) {
+        const DevOp op = ops[k];
+        apply_op_tile<U, NT, TPB>(x, xt, ld, d, op, tile, alpha, alpha_t);
+    }
+}
+
+
+// The coefficients of one operation, as the update functions read them.
+struct OpCoef { float b_i, b_j, bp_i, bp_j, gamma, gscale; };
 
 // ------------------------------------------------------------------------------------------
 // Chain kernel: the walk, on a programme the host has ordered and annotated (plan_chain).  Any linear
@@ -697,6 +701,43 @@ __global__ __launch_bounds__(256) void copy_probe_kernel(const v4f *__restrict__
     for (int u = 0; u < 4; ++u) {
         const int64_t k = base + u * 256;
         if (k < n4) __builtin_nontemporal_store(r[u], dst + k);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// In-place streaming probe with the walk kernel's access shape: grid = column tiles of TPB float4 pieces; every
+// workgroup makes n_ops passes, pass k reading ROWS consecutive workers' pieces of x and xt (2 ROWS loads of 16
+// bytes per lane, all issued before the first use), multiplying them by `scale` and storing them back in place
+// (ordinary, temporal accesses).  The workers advance cyclically by ROWS per pass, so a row comes back after
+// n / ROWS passes: with 64 workers and thousands of resident workgroups that is hundreds of megabytes later, beyond
+// every cache of the chip, which makes the probe's rate the machine's in-place HBM streaming rate at this shape.
+// ROWS = 2 is the shape of a gossip event (4 row pieces in, 4 out), ROWS = 1 that of a gradient event without
+// inputs or of a pure mixing pass.  With scale = 1 the state is unchanged bit for bit (the host passes it at run
+// time, so the arithmetic cannot be folded away).  Moves n_ops * ROWS * 64 bytes per whole float4 column.
+// ------------------------------------------------------------------------------------------
+template <int ROWS, int TPB>
+__global__ __launch_bounds__(TPB) void inplace_probe_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
+                                                            int64_t d, int32_t n, int32_t n_ops, float scale) {
+    const int64_t k = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (k >= (d >> 2)) return;
+    const int64_t ld4 = ld >> 2;
+    v4f *const px = (v4f *)x + k, *const pxt = (v4f *)xt + k;
+    int32_t w = 0;
+    for (int32_t op = 0; op < n_ops; ++op) {
+        v4f a[ROWS], at[ROWS];
+        int32_t row[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            row[r] = w + r < n ? w + r : w + r - n;
+            a[r] = px[(int64_t)row[r] * ld4];
+            at[r] = pxt[(int64_t)row[r] * ld4];
+        }
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            px[(int64_t)row[r] * ld4] = a[r] * scale;
+            pxt[(int64_t)row[r] * ld4] = at[r] * scale;
+        }
+        w = w + ROWS < n ? w + ROWS : w + ROWS - n;
     }
 }
 

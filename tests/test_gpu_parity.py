@@ -257,6 +257,44 @@ def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit():
         assert all(np.array_equal(a, b) for a, b in zip(results[0], r))
 
 
+def test_measurement_aids_leave_the_state_alone_and_occupancy_changes_no_bit():
+    from paper_2306_08289_amd import A2cidError
+    cfg = wl.scaled(wl.CONFIGS["C4"], d=4 * 256 * 9 + 2, events=600)
+    cols = np.arange(cfg.d)
+    w = wl.Workload(cfg, batch_events=300)
+    w.engine.set_tuning(1, 0, 256, 1)
+    w.run(300)
+    before = w.columns(cols)
+    for rows_per_op, n_ops in ((2, 70), (1, 130)):           # more passes than workers: the cycle wraps around
+        moved = w.engine.inplace_probe(rows_per_op, n_ops)
+        assert moved == n_ops * rows_per_op * 64.0 * (cfg.d // 4)
+    after = w.columns(cols)
+    assert np.array_equal(before[0].view(np.uint32), after[0].view(np.uint32))
+    assert np.array_equal(before[1].view(np.uint32), after[1].view(np.uint32))
+    assert torch.isnan(w.x[:, cfg.d:]).all() and torch.isnan(w.xt[:, cfg.d:]).all()
+    for bad in ((0, 8), (3, 8), (2, 0)):
+        with pytest.raises(A2cidError):
+            w.engine.inplace_probe(*bad)
+    w.engine.profile(True)
+    w.engine.stats(w.t_last)
+    w.engine.stats(w.t_last + 1.0)
+    launches, ms = w.engine.profile_read_stats()
+    assert launches == 2 and ms > 0.0 and w.engine.profile_read_stats()[0] == 0
+    w.engine.profile(False)
+    w.engine.set_walk_occupancy(3)                            # fewer workgroups per CU: the same bits
+    w.run(300)
+    limited = w.columns(cols)
+    w.close()
+    ref = wl.Workload(cfg, batch_events=300)
+    ref.engine.set_tuning(1, 0, 256, 1)
+    ref.run(600)
+    whole = ref.columns(cols)
+    assert np.array_equal(limited[0], whole[0]) and np.array_equal(limited[1], whole[1])
+    with pytest.raises(A2cidError):
+        ref.engine.set_walk_occupancy(33)
+    ref.close()
+
+
 def test_resume_from_saved_state_continues_the_same_trajectory():
     cfg = wl.scaled(wl.CONFIGS["C3"], d=30011, events=1200)
     cols = np.arange(cfg.d)
