@@ -351,7 +351,7 @@ int a2cid_set_walk_occupancy(a2cid_ctx *ctx, int32_t workgroups_per_cu);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
  * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
- * columns wide and needs 512 * cols * workers + 12 288 * cols bytes of the CU's 160 KiB of LDS).
+ * columns wide and needs 512 * cols * workers + 6 144 * cols bytes of the CU's 160 KiB of LDS).
  * Default: 8, 1. */
 int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
 

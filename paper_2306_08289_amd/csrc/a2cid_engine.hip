@@ -32,6 +32,7 @@ namespace {
 
 constexpr int kSlots = 4;               // operation-table staging buffers in flight
 constexpr int64_t kSlotOps = 16384;     // operations per staging buffer (1 MiB)
+constexpr int64_t kResRecords = 131072; // records of the resident kernel's per-wave programmes per staging buffer (4 MiB)
 constexpr int kStatsBlocksMax = 8192;   // upper bound on workgroups of the observables kernel (grid-stride)
 
 struct Slot {
@@ -39,7 +40,7 @@ struct Slot {
     DevOp *dev = nullptr;
     // resident kernel only: rows touched, compact operation records, gradient inputs in order
     int32_t *rows_host = nullptr, *rows_dev = nullptr;   // A2CID_MAX_WORKERS entries
-    ResOp *res_host = nullptr, *res_dev = nullptr;       // kSlotOps entries
+    ResOp *res_host = nullptr, *res_dev = nullptr;       // kResRecords entries
     GradIn *gin_host = nullptr, *gin_dev = nullptr;      // kSlotOps entries
     hipEvent_t done = nullptr;
     bool in_flight = false;
@@ -89,6 +90,7 @@ struct a2cid_ctx {
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
+    std::vector<std::vector<ResOp>> programme;   // resident kernel: the per-wave programmes being written
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     bool failed = false;                // an enqueueing step failed half-way: device state and time stamps disagree
     // observables scratch
@@ -299,7 +301,7 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
 
 constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row, column-per-lane and workgroup, plus staging
 
-int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, int32_t n_rows) {
+int launch_resident(a2cid_ctx *c, const Slot *s, int32_t stride, int32_t n_rows, bool trailing) {
     TimedLaunch tl{};
     if (c->profiling) {
         if (int rc = get_event(c, &tl.start)) return rc;
@@ -309,14 +311,19 @@ int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, 
     const int cols = c->resident_cols;
     const unsigned blocks = (unsigned)((c->d + 64 * cols - 1) / (64 * cols));
     const size_t lds = resident_lds_bytes(cols, n_rows);
-#define A2CID_RESIDENT(W, C)                                                                                     \
+#define A2CID_RESIDENT_K(W, C, PRE, TRAIL)                                                                       \
     do {                                                                                                         \
         if (lds > 65536)                                                                                         \
-            A2CID_HIP(hipFuncSetAttribute((const void *)resident_kernel<W, C>,                                   \
+            A2CID_HIP(hipFuncSetAttribute((const void *)resident_kernel<W, C, PRE, TRAIL>,                       \
                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
-        hipLaunchKernelGGL((resident_kernel<W, C>), dim3(blocks), dim3(64 * W), lds, c->stream, c->x, c->xt,     \
-                           c->ld, c->d, s->res_dev, n_ops, s->gin_dev, n_grad, s->rows_dev, n_rows,              \
+        hipLaunchKernelGGL((resident_kernel<W, C, PRE, TRAIL>), dim3(blocks), dim3(64 * W), lds, c->stream,      \
+                           c->x, c->xt, c->ld, c->d, s->res_dev, stride, s->gin_dev, s->rows_dev, n_rows,        \
                            (float)c->alpha, (float)c->alpha_t);                                                  \
+    } while (0)
+#define A2CID_RESIDENT(W, C)                                                                                     \
+    do {                                                                                                         \
+        if (c->order) { if (trailing) A2CID_RESIDENT_K(W, C, true, true); else A2CID_RESIDENT_K(W, C, true, false); }   \
+        else { if (trailing) A2CID_RESIDENT_K(W, C, false, true); else A2CID_RESIDENT_K(W, C, false, false); }   \
     } while (0)
     const int key = c->group * 10 + cols;
     switch (key) {
@@ -332,6 +339,7 @@ int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_ops, int32_t n_grad, 
         default: A2CID_RESIDENT(8, 1); break;
     }
 #undef A2CID_RESIDENT
+#undef A2CID_RESIDENT_K
     A2CID_HIP(hipGetLastError());
     if (c->profiling) {
         A2CID_HIP(hipEventRecord(tl.stop, c->stream));
@@ -425,8 +433,8 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
         A2CID_HIP(hipMalloc((void **)&s.dev, sizeof(DevOp) * kSlotOps));
         A2CID_HIP(hipHostMalloc((void **)&s.rows_host, sizeof(int32_t) * A2CID_MAX_WORKERS, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.rows_dev, sizeof(int32_t) * A2CID_MAX_WORKERS));
-        A2CID_HIP(hipHostMalloc((void **)&s.res_host, sizeof(ResOp) * kSlotOps, hipHostMallocDefault));
-        A2CID_HIP(hipMalloc((void **)&s.res_dev, sizeof(ResOp) * kSlotOps));
+        A2CID_HIP(hipHostMalloc((void **)&s.res_host, sizeof(ResOp) * kResRecords, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.res_dev, sizeof(ResOp) * kResRecords));
         A2CID_HIP(hipHostMalloc((void **)&s.gin_host, sizeof(GradIn) * kSlotOps, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.gin_dev, sizeof(GradIn) * kSlotOps));
         A2CID_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
@@ -471,13 +479,21 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
     return A2CID_OK;
 }
 
-// The chain programme of k operations has at most 3 k + slots steps (every spill makes room for a parking).
 // The event kernel of the next batch.  Left to the library, rows of at most 4096 parameters (a launch of a handful of
 // workgroups, bound by launch and host cost) go to the walk kernel, which needs no programme from the host; everything
 // longer to the chain kernel.
 constexpr int64_t kShortRow = 4096;
 static int event_mode(const a2cid_ctx *c) { return c->walk >= 0 ? c->walk : (c->d <= kShortRow ? 1 : 3); }
-static int64_t piece_capacity(const a2cid_ctx *c) { return event_mode(c) == 3 ? (kSlotOps - kChainMaxSlots) / 3 : kSlotOps; }
+// Operations per launch: the chain programme of k operations has at most 3 k + slots steps (every spill makes room for
+// a parking); each of the resident kernel's W programmes holds at most k barrier records (a (sub-)level per operation
+// at worst), at most k operation records (all dealt to the same wave then) and an end record, in whole chunks of 64.
+static int64_t piece_capacity(const a2cid_ctx *c) {
+    switch (event_mode(c)) {
+        case 3: return (kSlotOps - kChainMaxSlots) / 3;
+        case 2: return std::min<int64_t>(kSlotOps, (kResRecords / c->group - 64) / 2);
+        default: return kSlotOps;
+    }
+}
 
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch);
 
@@ -579,57 +595,105 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 for (int64_t k = 0; k < count; ++k) fill(s->host[k], first + k);
             }
             if (mode == 2) {
-                // compact records: LDS slots in order of first use, gradient inputs in order of use, and levels
-                // cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring)
+                // One programme per wave: LDS slots in order of first use, gradient inputs in order of use, every
+                // level cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring),
+                // every sub-level opened by a barrier record (in all programmes) that names its gradient events,
+                // its operations dealt to the waves in turn.
+                const int W = c->group;
                 int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
+                bool trailing = false;
                 const uintptr_t zero = (uintptr_t)c->zero_dev | 1u, one = (uintptr_t)(c->zero_dev + 1) | 1u;
                 c->slot_of.assign(c->n, -1);
+                c->programme.resize(W);
+                for (auto &prog : c->programme) prog.clear();
+                ResOp bar;
+                std::memset(&bar, 0, sizeof(bar));
+                bar.w0 = kResBarrier;
+                auto open_sub = [&](int32_t g_lo, int32_t g_hi, int64_t ops_in_sub) {
+                    bar.g_lo = (uint32_t)g_lo;
+                    bar.g_hi = (uint32_t)g_hi;
+                    for (int w = 0; w < W; ++w) {           // operation k of the sub-level goes to wave k mod W
+                        bar.n_mine = (uint32_t)((ops_in_sub + W - 1 - w) / W);
+                        c->programme[(size_t)w].push_back(bar);
+                    }
+                };
+                // gradient ordinals of the piece, so that a fill can reach beyond its own sub-level
+                int32_t total_grad = 0;
+                for (int64_t k = 0; k < count; ++k) total_grad += op_kind(s->host[k].kind) == kOpGradient;
+                int32_t staged_hi = 0;                      // ordinals below this are in the ring or consumed
                 for (int32_t ll = l; ll < l_end; ++ll) {
                     const int64_t lo = batch->level_off[ll] - first, hi = batch->level_off[ll + 1] - first;
-                    int64_t sub = lo;                       // first record of the current sub-level
-                    int32_t g_before = n_grad;
-                    auto close_sub = [&](int64_t end) {
+                    int64_t sub = lo;
+                    while (sub < hi) {
+                        // the sub-level [sub, end): as far as the level goes with at most kStage gradient events
+                        int64_t end = sub;
+                        int32_t grads = 0;
+                        while (end < hi) {
+                            const bool is_grad = op_kind(s->host[end].kind) == kOpGradient;
+                            if (is_grad && grads == kStage) break;
+                            grads += is_grad;
+                            ++end;
+                        }
+                        // Everything before ordinal n_grad is consumed when this sub-level starts, so the ring can
+                        // take ordinals up to n_grad + kStage: when the sub-level needs one that is not staged yet,
+                        // the waves fetch as far ahead as the ring allows (few fills, each hiding one memory latency).
+                        int32_t fill_lo = 0, fill_hi = 0;
+                        if (n_grad + grads > staged_hi) {
+                            fill_lo = staged_hi;
+                            fill_hi = std::min(total_grad, n_grad + kStage);
+                            staged_hi = fill_hi;
+                        }
+                        open_sub(fill_lo, fill_hi, end - sub);
                         for (int64_t k = sub; k < end; ++k) {
-                            s->res_host[k].w0 |= (uint32_t)(end - k) << 24;
-                            s->res_host[k].g = (uint32_t)g_before | ((uint32_t)n_grad << 16);
+                            const DevOp &o = s->host[k];
+                            const int32_t kind = op_kind(o.kind);
+                            if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
+                            if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
+                            ResOp r;
+                            std::memset(&r, 0, sizeof(r));
+                            r.w0 = (kind == kOpGossip ? kResGossip : kResGradient) |
+                                   ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
+                            r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
+                            r.gamma = o.gamma; r.gscale = o.gscale;
+                            trailing = trailing || o.bp_i != 0.f || o.bp_j != 0.f;
+                            if (kind == kOpGradient) {
+                                r.gidx = (uint32_t)n_grad;
+                                s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
+                                s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
+                                s->gin_host[n_grad].h = (o.h && o.gscale != 0.f) ? (uintptr_t)o.h : one;
+                                n_xi += o.xi != nullptr;
+                                n_c += o.c && o.gscale != 0.f;
+                                n_h += o.h && o.gscale != 0.f;
+                                ++n_grad;
+                            }
+                            c->programme[(size_t)((k - sub) % W)].push_back(r);
                         }
                         sub = end;
-                        g_before = n_grad;
-                    };
-                    for (int64_t k = lo; k < hi; ++k) {
-                        const DevOp &o = s->host[k];
-                        const int32_t kind = op_kind(o.kind);
-                        if (kind == kOpGradient && n_grad - g_before == kStage) close_sub(k);
-                        if (k - sub == 255) close_sub(k);
-                        if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
-                        if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
-                        ResOp &r = s->res_host[k];
-                        r.w0 = (uint32_t)kind | ((o.bp_i != 0.f || o.bp_j != 0.f) ? 4u : 0u) | (c->order ? 8u : 0u) |
-                               ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
-                        r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
-                        r.gamma = o.gamma; r.gscale = o.gscale;
-                        if (kind == kOpGradient) {
-                            r.gidx = (uint32_t)n_grad;
-                            s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
-                            s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
-                            s->gin_host[n_grad].h = (o.h && o.gscale != 0.f) ? (uintptr_t)o.h : one;
-                            n_xi += o.xi != nullptr;
-                            n_c += o.c && o.gscale != 0.f;
-                            n_h += o.h && o.gscale != 0.f;
-                            ++n_grad;
-                        }
                     }
-                    close_sub(hi);
+                }
+                size_t longest = 0;
+                for (const auto &prog : c->programme) longest = std::max(longest, prog.size());
+                const size_t stride = (longest + 1 + 63) / 64 * 64;          // at least one end record, whole chunks
+                if ((int64_t)(stride * (size_t)W) > kResRecords)
+                    return fail(A2CID_EINVAL, "internal: resident programmes of %zu records", stride * (size_t)W);
+                ResOp end_rec;
+                std::memset(&end_rec, 0, sizeof(end_rec));
+                end_rec.w0 = kResEnd;
+                for (int w = 0; w < W; ++w) {
+                    ResOp *dst = s->res_host + (size_t)w * stride;
+                    const auto &prog = c->programme[(size_t)w];
+                    std::copy(prog.begin(), prog.end(), dst);
+                    std::fill(dst + prog.size(), dst + stride, end_rec);
                 }
                 A2CID_HIP(hipMemcpyAsync(s->rows_dev, s->rows_host, sizeof(int32_t) * (size_t)n_rows,
                                          hipMemcpyHostToDevice, c->stream));
-                A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResOp) * (size_t)count,
+                A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResOp) * stride * (size_t)W,
                                          hipMemcpyHostToDevice, c->stream));
                 if (n_grad > 0)
                     A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad,
                                              hipMemcpyHostToDevice, c->stream));
                 c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c + n_h));
-                if (int rc = launch_resident(c, s, (int32_t)count, n_grad, n_rows)) return rc;
+                if (int rc = launch_resident(c, s, (int32_t)stride, n_rows, trailing)) return rc;
                 A2CID_HIP(hipEventRecord(s->done, c->stream));
                 s->in_flight = true;
                 l = l_end;

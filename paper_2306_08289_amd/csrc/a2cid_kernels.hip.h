@@ -421,36 +421,44 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
 }
 
 // ------------------------------------------------------------------------------------------
-// Resident kernel: grid = tiles of 64 columns, W waves per workgroup, one launch per batch.
+// Resident kernel: grid = tiles of 64 * C columns, W waves per workgroup, one launch per batch.
 // The same ownership argument as for the walk kernel, taken one step further: the workgroup
-// first copies its 64 columns of every row the batch touches into LDS (slot s holds row
-// rows[s] as (x, xt) pairs, 512 bytes per slot), then applies all operations of the batch to the
-// LDS copy, and finally writes the rows back.  State traffic per batch drops from 32 d bytes per
-// gossip event to 16 d bytes per touched row; gradient inputs are still read once per event.
+// first copies its columns of every row the batch touches into LDS (slot s holds row rows[s] as
+// (x, xt) pairs, 512 * C bytes per slot), then applies all operations of the batch to the LDS copy,
+// and finally writes the rows back.  State traffic per batch drops from 32 d bytes per gossip
+// event to 16 d bytes per touched row; gradient inputs are still read once per event.
 //
-// LDS capacity allows only a few such tiles per CU, so the W waves of a workgroup share one tile of
-// 64 * C columns: lane l of every wave stands for columns l*C .. l*C+C-1 of the tile, the operations
-// of a level (which touch disjoint rows) are dealt round-robin to the waves, and a workgroup barrier
-// separates levels.  C > 1 spreads the scalar bookkeeping of an operation over more columns.
-//   - operation records (32 bytes) are fetched 64 at a time, one record per lane, with vector
-//     loads, and a record's fields are broadcast with v_readlane: no memory access per operation;
-//   - gradient inputs (xi, c at the lane's column) go through a ring of kStage LDS slots indexed by
-//     the event's ordinal among the gradient events of the launch; before a level starts, the waves
-//     together fetch as many upcoming events as the ring can take.  The host splits levels so that
-//     none holds more than kStage gradient events.
+// LDS capacity allows only a few such tiles per CU, so the W waves of a workgroup share one tile:
+// lane l of every wave stands for columns l*C .. l*C+C-1 of the tile, the operations of a level
+// (which touch disjoint rows) are dealt to the waves, and a workgroup barrier separates levels.
+// The kernel is bound by instruction issue, not by memory, so everything a wave can be spared is
+// done on the host: it writes one linear programme per wave (ResOp records, W * stride of them,
+// every programme padded with end records to the common length, a multiple of 64):
+//   - a barrier record before each (sub-)level, the same number of them in every programme; it says
+//     how many operation records of this programme follow it, and it may name a range of gradient
+//     events (by their ordinal in the launch) whose inputs (xi, c, h at the lane's columns) the waves
+//     fetch together, between two barriers, into a ring of kStage LDS slots (slot = ordinal mod
+//     kStage): the host lets a fill reach as far ahead as the ring allows, so that fills are few;
+//   - an operation record (gossip or gradient event) for each operation dealt to the wave;
+//   - end records.
+// A wave fetches its records 64 at a time, one per lane, and broadcasts the fields of the current one
+// with v_readlane: no memory access and no level bookkeeping per operation.  Whether jumps are taken
+// from the stored values (PRE: Algorithm 1 as listed) and whether any operation of the launch carries a
+// trailing mix (TRAIL) are compile-time cases, so the common path (neither) carries no test for them.
 // Valid only while every gradient input of the batch is final when the batch is submitted (true
 // for the affine gradient model; a real network's gradient at x_i is not), which is why this path
 // is opt-in and its throughput is reported apart from the roofline of the one-pass-per-event
 // kernels.
 // ------------------------------------------------------------------------------------------
-struct Pair { float x, xt; };
+struct alignas(8) Pair { float x, xt; };
+
+enum : uint32_t { kResGradient = 0, kResGossip = 1, kResBarrier = 3, kResEnd = 4 };
 
 struct ResOp {                   // 32 bytes
-    uint32_t w0;                 // kind | (a trailing mix is non-zero) << 2 | (listing order) << 3 | slot_i << 8 | slot_j << 16 |
-                                 // operations left in the (sub-)level << 24
-    uint32_t g;                  // gradient events before this (sub-)level | gradient events up to its end << 16
-    float b_i;
-    union { float b_j; uint32_t gidx; };   // gossip: mixing coefficient of worker j; gradient: ordinal of the event
+    uint32_t w0;                 // kRes* kind | slot_i << 8 | slot_j << 16
+    union { uint32_t gidx; uint32_t g_lo; };   // gradient: ordinal of the event; barrier: first ordinal to stage
+    union { float b_i; uint32_t n_mine; };     // barrier: operation records of this programme up to the next barrier
+    union { float b_j; uint32_t g_hi; };       // gossip: mixing coefficient of worker j; barrier: one past the last ordinal
     float bp_i, bp_j, gamma, gscale;
 };
 static_assert(sizeof(ResOp) == 32, "ResOp layout");
@@ -459,16 +467,13 @@ static_assert(sizeof(ResOp) == 32, "ResOp layout");
 // single float (a zero for xi and c, a one for h) that every column reads; otherwise column k is at pointer + k.
 struct GradIn { uintptr_t xi, c, h; };
 
-constexpr int kStage = 16;       // LDS ring slots for gradient inputs
+constexpr int kStage = 8;        // LDS ring slots for gradient inputs: with 64 workers a tile then takes 38 KiB, which lets
+                                 // four workgroups share a CU (16 slots: three, measured 18 % slower)
 
 typedef const __attribute__((address_space(1))) float *global_f32;
 
 __device__ __forceinline__ uint32_t lane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
 __device__ __forceinline__ float lane_f32(uint32_t v, int l) { return __int_as_float(__builtin_amdgcn_readlane((int)v, l)); }
-__device__ __forceinline__ float grad_input(uintptr_t p, int64_t col) {
-    const uintptr_t addr = (p & ~(uintptr_t)1) + ((p & 1) ? 0 : (uintptr_t)col * 4);
-    return *(global_f32)addr;
-}
 
 // C consecutive floats of a row starting at column col (col is a multiple of C, rows are 16-byte aligned);
 // columns at or beyond d read as 0 and are never written.
@@ -508,7 +513,7 @@ __device__ __forceinline__ void store_cols(float *p, int64_t col, int64_t d, con
 
 template <int C>
 __device__ __forceinline__ Cols<C> grad_input_cols(uintptr_t p, int64_t col, int64_t d) {
-    if (p & 1) {                                          // a single zero float stands for the whole row
+    if (p & 1) {                                          // a single float stands for the whole row
         Cols<C> r;
         const float z = *(global_f32)(p & ~(uintptr_t)1);
 #pragma unroll
@@ -520,7 +525,7 @@ __device__ __forceinline__ Cols<C> grad_input_cols(uintptr_t p, int64_t col, int
 
 // W waves share a tile of 64 * C columns; lane l of every wave stands for columns l*C .. l*C + C-1 of the tile.
 template <int C>
-struct TileCell { Pair p[C]; };
+struct alignas(8) TileCell { Pair p[C]; };
 
 // The staged inputs of one gradient event at a lane's columns.
 template <int C>
@@ -531,12 +536,12 @@ constexpr size_t resident_lds_bytes(int cols, int n_rows) {
     return (sizeof(Pair) * (size_t)n_rows + 3 * sizeof(float) * (size_t)kStage) * 64 * (size_t)cols;
 }
 
-template <int W, int C>
+template <int W, int C, bool PRE, bool TRAIL>
 __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x, float *__restrict__ xt,
-                                                          int64_t ld, int64_t d, const ResOp *__restrict__ ops,
-                                                          int32_t n_ops, const GradIn *__restrict__ gin,
-                                                          int32_t n_grad, const int32_t *__restrict__ rows,
-                                                          int32_t n_rows, float alpha, float alpha_t) {
+                                                          int64_t ld, int64_t d, const ResOp *__restrict__ recs,
+                                                          int32_t stride, const GradIn *__restrict__ gin,
+                                                          const int32_t *__restrict__ rows, int32_t n_rows,
+                                                          float alpha, float alpha_t) {
     extern __shared__ unsigned char lds_raw[];
     TileCell<C> *tile = (TileCell<C> *)lds_raw;          // [n_rows][64]
     StageCell<C> *gstage = (StageCell<C> *)(tile + (size_t)n_rows * 64);   // [kStage][64]: inputs of staged gradient events
@@ -566,109 +571,96 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             if (s < n_rows) tile[s * 64 + lane] = v[q];
         }
     }
-    __syncthreads();
+    // no barrier here: every programme starts with a barrier record
 
-    int32_t staged_hi = 0;                               // gradient ordinals < staged_hi are in the ring or consumed
-    int32_t k0 = -64;                                    // first record of the chunk held in (ra, rb)
+    const ResOp *mine = recs + (size_t)wave * stride;
+    TileCell<C> *const my_cell = tile + lane;            // slot s of this lane: my_cell + 64 s
     uint4 ra = {0u, 0u, 0u, 0u}, rb = {0u, 0u, 0u, 0u};
-    int32_t k = 0;                                       // first operation of the current (sub-)level
-    while (k < n_ops) {
-        if (k >= k0 + 64) {
-            k0 = k & ~63;
-            if (k0 + lane < n_ops) {
-                const uint4 *p = (const uint4 *)(ops + k0 + lane);
-                ra = p[0]; rb = p[1];
-            }
+    int32_t pos = 0;                                     // next record of this wave's programme
+    for (;;) {
+        // a barrier record opens a (sub-)level; anything else (an end record) closes the programme
+        if ((pos & 63) == 0) {                           // the next 64 records, one per lane
+            const uint4 *p = (const uint4 *)(mine + pos + lane);
+            ra = p[0]; rb = p[1];
         }
-        const uint32_t head = lane_u32(ra.x, k - k0);
-        int32_t run = (int32_t)(head >> 24);
-        if (run < 1) run = 1;                            // a malformed record must not stall the walk
-        const uint32_t gw = lane_u32(ra.y, k - k0);
-        const int32_t g_before = (int32_t)(gw & 0xffffu), g_after = (int32_t)(gw >> 16);
-        if (g_after > staged_hi) {
-            // fill the ring: everything up to g_before + kStage (older ordinals are consumed)
-            int32_t hi = g_before + kStage;
-            if (hi > n_grad) hi = n_grad;
-            StageCell<C> gv[kStage / W + 1];
+        const int lb = pos & 63;
+        if ((lane_u32(ra.x, lb) & 7u) != kResBarrier) break;
+        const int32_t g_lo = (int32_t)lane_u32(ra.y, lb), g_hi = (int32_t)lane_u32(ra.w, lb);
+        const int32_t n_mine = (int32_t)lane_u32(ra.z, lb);
+        ++pos;
+        // the previous (sub-)level is complete and its staged inputs are consumed; stage those of this one
+        __syncthreads();
+        if (g_hi > g_lo) {
+            for (int32_t o = g_lo + wave; o < g_hi; o += W) {
+                const GradIn in = gin[o];
+                StageCell<C> gv;
 #pragma unroll
-            for (int u = 0; u < kStage / W + 1; ++u) {
-                const int32_t o = staged_hi + wave + u * W;
+                for (int c = 0; c < C; ++c) { gv.xi[c] = 0.f; gv.c[c] = 0.f; gv.h[c] = 1.f; }
+                if (valid) {
+                    const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d),
+                                  hh = grad_input_cols<C>(in.h, col, d);
 #pragma unroll
-                for (int c = 0; c < C; ++c) { gv[u].xi[c] = 0.f; gv[u].c[c] = 0.f; gv[u].h[c] = 1.f; }
-                if (o < hi) {
-                    const GradIn in = gin[o];
-                    if (valid) {
-                        const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d),
-                                      hh = grad_input_cols<C>(in.h, col, d);
-#pragma unroll
-                        for (int c = 0; c < C; ++c) { gv[u].xi[c] = a.v[c]; gv[u].c[c] = cc.v[c]; gv[u].h[c] = hh.v[c]; }
-                    }
+                    for (int c = 0; c < C; ++c) { gv.xi[c] = a.v[c]; gv.c[c] = cc.v[c]; gv.h[c] = hh.v[c]; }
                 }
+                gstage[(o % kStage) * 64 + lane] = gv;
             }
-#pragma unroll
-            for (int u = 0; u < kStage / W + 1; ++u) {
-                const int32_t o = staged_hi + wave + u * W;
-                if (o < hi) gstage[(o % kStage) * 64 + lane] = gv[u];
-            }
-            staged_hi = hi;
             __syncthreads();
         }
-        for (int32_t idx = k + wave; idx < k + run; idx += W) {
-            if (idx >= k0 + 64) {
-                k0 = idx & ~63;
-                if (k0 + lane < n_ops) {
-                    const uint4 *p = (const uint4 *)(ops + k0 + lane);
-                    ra = p[0]; rb = p[1];
-                }
+        // this wave's operations of the (sub-)level
+        for (int32_t t = 0; t < n_mine; ++t, ++pos) {
+            if ((pos & 63) == 0) {
+                const uint4 *p = (const uint4 *)(mine + pos + lane);
+                ra = p[0]; rb = p[1];
             }
-            const int l = idx - k0;
+            const int l = pos & 63;
             const uint32_t w0 = lane_u32(ra.x, l);
-            const uint32_t kind = w0 & 3u;
-            const bool trailing = (w0 & 4u) != 0;        // some trailing mix is non-zero (rare: only with t_sync)
-            const bool pre = (w0 & 8u) != 0;             // jumps from the stored values (Algorithm 1 as listed)
-            TileCell<C> *pi = tile + ((w0 >> 8) & 255u) * 64 + lane;
+            // both rows are requested before the first use (slot_j = slot_i in a gradient record, so the second read is
+            // always a valid one); the empty asm statement keeps the compiler from moving it behind the branch, where
+            // every gossip operation would pay two LDS round trips in a row instead of one
+            TileCell<C> *pi = my_cell + ((w0 >> 8) & 255u) * 64, *pj = my_cell + ((w0 >> 16) & 255u) * 64;
+            TileCell<C> vi = *pi, vj = *pj;
+#pragma unroll
+            for (int c = 0; c < C; ++c) asm volatile("" : "+v"(vj.p[c].x), "+v"(vj.p[c].xt));
             const float b_i = lane_f32(ra.z, l);
-            TileCell<C> vi = *pi;
-            if (kind == (uint32_t)kOpGossip) {
-                TileCell<C> *pj = tile + ((w0 >> 16) & 255u) * 64 + lane;
+            if ((w0 & 7u) == kResGossip) {
                 const float b_j = lane_f32(ra.w, l);
-                TileCell<C> vj = *pj;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
                     const float m_stored = vi.p[c].x - vj.p[c].x;
                     mix(vi.p[c].x, vi.p[c].xt, b_i);
                     mix(vj.p[c].x, vj.p[c].xt, b_j);
-                    const float m = pre ? m_stored : vi.p[c].x - vj.p[c].x;
+                    const float m = PRE ? m_stored : vi.p[c].x - vj.p[c].x;
                     vi.p[c].x -= alpha * m; vj.p[c].x += alpha * m;
                     vi.p[c].xt -= alpha_t * m; vj.p[c].xt += alpha_t * m;
                 }
-                if (trailing) {
-                    const float bp_i = lane_f32(rb.x, l), bp_j = lane_f32(rb.y, l);
+                if (TRAIL) {
+                    const float bp_j = lane_f32(rb.y, l);
 #pragma unroll
-                    for (int c = 0; c < C; ++c) { mix(vi.p[c].x, vi.p[c].xt, bp_i); mix(vj.p[c].x, vj.p[c].xt, bp_j); }
+                    for (int c = 0; c < C; ++c) mix(vj.p[c].x, vj.p[c].xt, bp_j);
                 }
                 *pj = vj;
-            } else if (kind == (uint32_t)kOpGradient) {
-                OpCoef oc;
-                oc.b_i = b_i; oc.bp_i = 0.f;
-                oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
-                const StageCell<C> in = gstage[(lane_u32(ra.w, l) % kStage) * 64 + lane];
+            } else {                                     // a gradient event
+                const StageCell<C> in = gstage[(lane_u32(ra.y, l) % kStage) * 64 + lane];
+                const float gamma = lane_f32(rb.z, l), slope0 = lane_f32(rb.w, l);
 #pragma unroll
-                for (int c = 0; c < C; ++c) gradient_update(vi.p[c].x, vi.p[c].xt, in.xi[c], in.c[c], in.h[c], oc, pre);
-                if (trailing) {
-                    const float bp_i = lane_f32(rb.x, l);
-#pragma unroll
-                    for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, bp_i);
+                for (int c = 0; c < C; ++c) {
+                    const float slope = slope0 * in.h[c];
+                    const float g_stored = slope * (vi.p[c].x - in.c[c]) + in.xi[c];
+                    mix(vi.p[c].x, vi.p[c].xt, b_i);
+                    const float g = PRE ? g_stored : slope * (vi.p[c].x - in.c[c]) + in.xi[c];
+                    vi.p[c].x -= gamma * g;
+                    vi.p[c].xt -= gamma * g;
                 }
-            } else {
+            }
+            if (TRAIL) {
+                const float bp_i = lane_f32(rb.x, l);
 #pragma unroll
-                for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, b_i);
+                for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, bp_i);
             }
             *pi = vi;
         }
-        k += run;
-        __syncthreads();
     }
+    __syncthreads();
 
     if (valid) {
         for (int32_t s = wave; s < n_rows; s += W) {
