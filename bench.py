@@ -11,7 +11,7 @@ Prints ONE JSON line.  The headline figures (value, roofline) belong to the walk
 makes one full pass over the touched rows per event, so that its traffic IS the algorithmic byte
 count of the method: 32 d per gossip event, 16 d + 4 d per gradient input per gradient event
 (+ 8 n d per observables call in `value`).  The kernels that keep workers on the chip between
-events -- the chain kernel, which is the library's default, and the LDS-resident kernel -- move
+events -- the chain kernel and the LDS-resident kernel, between which the library chooses by shape -- move
 fewer bytes for the same events; they are timed on the same steps and reported as separate lines
 (`chain_variant`, `resident_variant`: events/s up, HBM GB/s down, with the bytes they move by
 construction and the same work priced at one pass per event).  Also: the copy ceiling of the
@@ -41,10 +41,10 @@ MEASURED_TRAFFIC = {
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
-             2: "resident_kernel: every touched row stays in LDS for the whole batch (state read and written once "
-                "per batch)",
-             3: "chain_kernel (the library's default): events re-ordered so that a worker's columns are found in "
-                "registers or parked in LDS as often as possible"}
+             2: "resident_kernel (the library's choice for 32 to 112 workers): every touched row stays in LDS for the "
+                "whole batch (state read and written once per batch)",
+             3: "chain_kernel (the library's choice for fewer than 32 or more than 112 workers): events re-ordered so "
+                "that a worker's columns are found in registers or parked in LDS as often as possible"}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -93,7 +93,7 @@ def cpu_baseline(cfg, seconds_budget=20.0):
 
 
 def short_run(name, batch, steps=6, warmup=2):
-    """A few steps of one configuration with the walk, chain (default) and LDS-resident kernels."""
+    """A few steps of one configuration with the walk, chain and LDS-resident kernels."""
     import torch
     from paper_2306_08289_amd import workloads as wl
     cfg = wl.CONFIGS[name]

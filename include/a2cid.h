@@ -318,8 +318,9 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
  * workgroup size (64 ... 1024, a power of two), mode =
- *  -1: chosen per batch: 3, except for rows so short (d <= 4096) that a launch has a handful of
- *      workgroups and the host-side planning of mode 3 costs more than it saves: then 1 (default);
+ *  -1: chosen by the library from the shape (default): 2 where its tile fits the LDS and a level holds
+ *      enough operations to occupy its waves (32 ... 112 workers) and for rows of at most 4096
+ *      parameters; 1 for such short rows otherwise; 3 for everything else;
  *   0: one launch per level;
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
  *      own columns, each operation reading and writing its rows in device memory (32 d bytes per

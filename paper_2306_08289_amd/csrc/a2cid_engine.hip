@@ -299,7 +299,6 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
 }
 
 
-constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row, column-per-lane and workgroup, plus staging
 
 int launch_resident(a2cid_ctx *c, const Slot *s, int32_t stride, int32_t n_rows, bool trailing) {
     TimedLaunch tl{};
@@ -479,11 +478,20 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
     return A2CID_OK;
 }
 
-// The event kernel of the next batch.  Left to the library, rows of at most 4096 parameters (a launch of a handful of
-// workgroups, bound by launch and host cost) go to the walk kernel, which needs no programme from the host; everything
-// longer to the chain kernel.
+// The event kernel of the next batch when the choice is left to the library, from measurements on the five
+// configurations (events per second, 1024 events per batch): the LDS-resident kernel wherever its tile fits the LDS and
+// a level has enough operations to occupy its waves (32 ... 112 workers: 1.1 to 2 times the chain kernel), and for
+// rows so short (at most 4096 parameters) that every other kernel launches a handful of workgroups; the walk kernel
+// for short rows otherwise (it needs no programme from the host); the chain kernel for the rest (16 workers: 1.3 times
+// the resident kernel; more than 112 workers).
 constexpr int64_t kShortRow = 4096;
-static int event_mode(const a2cid_ctx *c) { return c->walk >= 0 ? c->walk : (c->d <= kShortRow ? 1 : 3); }
+constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row and column-per-lane, plus the input ring
+static int event_mode(const a2cid_ctx *c) {
+    if (c->walk >= 0) return c->walk;
+    const bool short_row = c->d <= kShortRow;
+    if (c->n <= kResidentMaxRows && (short_row || c->n >= 32)) return 2;
+    return short_row ? 1 : 3;
+}
 // Operations per launch: the chain programme of k operations has at most 3 k + slots steps (every spill makes room for
 // a parking); each of the resident kernel's W programmes holds at most k barrier records (a (sub-)level per operation
 // at worst), at most k operation records (all dealt to the same wave then) and an end record, in whole chunks of 64.
