@@ -49,13 +49,24 @@ enum : uint32_t {
     kLocSlot0 = 2,               // kLocSlot0 + s: parked in LDS slot s
 };
 
-// exp(tau A) (x, xt) in increment form: with b the off-diagonal entry, x += b (xt - x) and
-// xt -= b (xt - x).  x + xt is conserved exactly up to one rounding; b = 0 is the identity.
+// The arithmetic of the three updates is written with explicit fused multiply-adds, so that every kernel performs
+// the same sequence of individually rounded IEEE operations whatever the compiler would have chosen to contract in
+// its context: this is what makes the kernels agree bit for bit.
+__device__ __forceinline__ float fma_s(float s, float a, float c) { return __builtin_fmaf(s, a, c); }
+__device__ __forceinline__ v4f fma_s(float s, v4f a, v4f c) {
+    const v4f sv = {s, s, s, s};
+    return __builtin_elementwise_fma(sv, a, c);
+}
+__device__ __forceinline__ float fma_t(float s, float a, float c) { return __builtin_fmaf(s, a, c); }
+__device__ __forceinline__ v4f fma_t(v4f s, v4f a, v4f c) { return __builtin_elementwise_fma(s, a, c); }
+
+// exp(tau A) (x, xt) in increment form: with b the off-diagonal entry and delta = xt - x, x <- x + b delta and
+// xt <- xt - b delta (one rounding each).  x + xt is conserved up to rounding; b = 0 is the identity.
 template <typename T>
 __device__ __forceinline__ void mix(T &x, T &xt, float b) {
-    const T delta = b * (xt - x);
-    x += delta;
-    xt -= delta;
+    const T delta = xt - x;
+    x = fma_s(b, delta, x);
+    xt = fma_s(-b, delta, xt);
 }
 
 // Gossip jump of Eq. (1) for one pair, including the flows before and (optionally) after it.
@@ -68,26 +79,54 @@ __device__ __forceinline__ void gossip_update(T &xi, T &xti, T &xj, T &xtj, cons
     mix(xi, xti, op.b_i);
     mix(xj, xtj, op.b_j);
     const T m = pre ? m_stored : xi - xj;
-    xi -= alpha * m;
-    xj += alpha * m;
-    xti -= alpha_t * m;
-    xtj += alpha_t * m;
+    xi = fma_s(-alpha, m, xi);
+    xj = fma_s(alpha, m, xj);
+    xti = fma_s(-alpha_t, m, xti);
+    xtj = fma_s(alpha_t, m, xtj);
     mix(xi, xti, op.bp_i);
     mix(xj, xtj, op.bp_j);
 }
 
 // Gradient jump of Eq. (1) with g = gscale h (x - c) + xi (h: the coordinate's curvature, 1 when the event
-// carries none: gscale * 1 is exact, so such events compute what they always did), taken at the mixed point
-// (pre = false) or at the stored point (pre = true, Algorithm 1 as listed).
+// carries none: gscale * 1 is exact), taken at the mixed point (pre = false) or at the stored point (pre = true,
+// Algorithm 1 as listed).
 template <typename T, typename Op>
 __device__ __forceinline__ void gradient_update(T &x, T &xt, T xi, T c, T h, const Op &op, bool pre) {
     const T slope = op.gscale * h;
-    const T g_stored = slope * (x - c) + xi;
+    const T g_stored = fma_t(slope, x - c, xi);
     mix(x, xt, op.b_i);
-    const T g = pre ? g_stored : slope * (x - c) + xi;
-    x -= op.gamma * g;
-    xt -= op.gamma * g;
+    const T g = pre ? g_stored : fma_t(slope, x - c, xi);
+    x = fma_s(-op.gamma, g, x);
+    xt = fma_s(-op.gamma, g, xt);
     mix(x, xt, op.bp_i);
+}
+
+// The same two jumps with the trailing mix as a compile-time case: a mix with b = 0 is the identity (the fused
+// multiply-add of 0 * delta onto x returns x; only a negative zero would come back positive), so without a trailing
+// mix its instructions are simply left out.
+template <bool TRAIL, typename T, typename Op>
+__device__ __forceinline__ void gossip_jump(T &xi, T &xti, T &xj, T &xtj, const Op &op, float alpha, float alpha_t,
+                                            bool pre) {
+    const T m_stored = xi - xj;
+    mix(xi, xti, op.b_i);
+    mix(xj, xtj, op.b_j);
+    const T m = pre ? m_stored : xi - xj;
+    xi = fma_s(-alpha, m, xi);
+    xj = fma_s(alpha, m, xj);
+    xti = fma_s(-alpha_t, m, xti);
+    xtj = fma_s(alpha_t, m, xtj);
+    if (TRAIL) { mix(xi, xti, op.bp_i); mix(xj, xtj, op.bp_j); }
+}
+
+template <bool TRAIL, typename T, typename Op>
+__device__ __forceinline__ void gradient_jump(T &x, T &xt, T xi, T c, T h, const Op &op, bool pre) {
+    const T slope = op.gscale * h;
+    const T g_stored = fma_t(slope, x - c, xi);
+    mix(x, xt, op.b_i);
+    const T g = pre ? g_stored : fma_t(slope, x - c, xi);
+    x = fma_s(-op.gamma, g, x);
+    xt = fma_s(-op.gamma, g, xt);
+    if (TRAIL) mix(x, xt, op.bp_i);
 }
 
 template <bool NT>
@@ -623,39 +662,23 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             for (int c = 0; c < C; ++c) asm volatile("" : "+v"(vj.p[c].x), "+v"(vj.p[c].xt));
             const float b_i = lane_f32(ra.z, l);
             if ((w0 & 7u) == kResGossip) {
-                const float b_j = lane_f32(ra.w, l);
+                OpCoef oc;
+                oc.b_i = b_i; oc.b_j = lane_f32(ra.w, l);
+                oc.bp_i = TRAIL ? lane_f32(rb.x, l) : 0.f;
+                oc.bp_j = TRAIL ? lane_f32(rb.y, l) : 0.f;
 #pragma unroll
                 for (int c = 0; c < C; ++c) {
-                    const float m_stored = vi.p[c].x - vj.p[c].x;
-                    mix(vi.p[c].x, vi.p[c].xt, b_i);
-                    mix(vj.p[c].x, vj.p[c].xt, b_j);
-                    const float m = PRE ? m_stored : vi.p[c].x - vj.p[c].x;
-                    vi.p[c].x -= alpha * m; vj.p[c].x += alpha * m;
-                    vi.p[c].xt -= alpha_t * m; vj.p[c].xt += alpha_t * m;
-                }
-                if (TRAIL) {
-                    const float bp_j = lane_f32(rb.y, l);
-#pragma unroll
-                    for (int c = 0; c < C; ++c) mix(vj.p[c].x, vj.p[c].xt, bp_j);
+                    gossip_jump<TRAIL>(vi.p[c].x, vi.p[c].xt, vj.p[c].x, vj.p[c].xt, oc, alpha, alpha_t, PRE);
                 }
                 *pj = vj;
             } else {                                     // a gradient event
                 const StageCell<C> in = gstage[(lane_u32(ra.y, l) % kStage) * 64 + lane];
-                const float gamma = lane_f32(rb.z, l), slope0 = lane_f32(rb.w, l);
+                OpCoef oc;
+                oc.b_i = b_i; oc.bp_i = TRAIL ? lane_f32(rb.x, l) : 0.f;
+                oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
 #pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    const float slope = slope0 * in.h[c];
-                    const float g_stored = slope * (vi.p[c].x - in.c[c]) + in.xi[c];
-                    mix(vi.p[c].x, vi.p[c].xt, b_i);
-                    const float g = PRE ? g_stored : slope * (vi.p[c].x - in.c[c]) + in.xi[c];
-                    vi.p[c].x -= gamma * g;
-                    vi.p[c].xt -= gamma * g;
-                }
-            }
-            if (TRAIL) {
-                const float bp_i = lane_f32(rb.x, l);
-#pragma unroll
-                for (int c = 0; c < C; ++c) mix(vi.p[c].x, vi.p[c].xt, bp_i);
+                for (int c = 0; c < C; ++c)
+                    gradient_jump<TRAIL>(vi.p[c].x, vi.p[c].xt, in.xi[c], in.c[c], in.h[c], oc, PRE);
             }
             *pi = vi;
         }
