@@ -34,8 +34,15 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # figure comes from.  Only valid for the workload, batch size, kernel and launch shape it names.  The counters sit
 # between the L2 and the fabric: bytes served by the 256 MB last-level cache behind it count as traffic here.
 MEASURED_TRAFFIC = {
-    ("C4", 1024, "chain_kernel"): (3.2738e11, "profiles/chain_kernel_C4_hbm_counters.md"),
-    ("C4", 1024, "walk_kernel"): (7.9201e11, "profiles/walk_kernel_C4_hbm_counters.md"),
+    ("C4", 1024, "walk_kernel"): (7.9189e11, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "chain_kernel"): (3.2501e11, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "resident_kernel"): (2.9906e10, "profiles/bench_C4_hbm_counters.md"),
+    ("C3", 1024, "walk_kernel"): (3.3678e11, "profiles/bench_C3_hbm_counters.md"),
+    ("C3", 1024, "chain_kernel"): (7.2097e10, "profiles/bench_C3_hbm_counters.md"),
+    ("C3", 1024, "resident_kernel"): (1.3529e10, "profiles/bench_C3_hbm_counters.md"),
+    ("C5", 1024, "walk_kernel"): (8.2851e11, "profiles/bench_C5_hbm_counters.md"),
+    ("C5", 1024, "chain_kernel"): (3.7700e11, "profiles/bench_C5_hbm_counters.md"),
+    ("C5", 1024, "resident_kernel"): (3.6357e10, "profiles/bench_C5_hbm_counters.md"),
 }
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
@@ -126,6 +133,50 @@ def short_run(name, batch, steps=6, warmup=2):
     return res
 
 
+def reuse_sweep(name, batch):
+    """Walk kernel against the distance at which a row comes back: gossip-only batches that cycle over k disjoint
+    pairs (0,1), (2,3), ... of the configuration's workers, so that every row is read again k operations after it was
+    written.  Needs a graph that has these edges (the complete graph of C5).  With about 2000 resident workgroups of
+    16 KB each an operation's footprint is 32 MB: the curve shows which reuse distances the on-chip caches (L2, then
+    the 256 MB last-level cache) still serve, and what is left when none does."""
+    import numpy as np
+    import torch
+    from paper_2306_08289_amd import binding, workloads as wl
+    cfg = wl.CONFIGS[name]
+    w = wl.Workload(cfg, device="cuda:0", batch_events=batch, xi_slots=1, reuse_xi=True)
+    eng = w.engine
+    eng.set_tuning(1, 0, 256, 1)
+    now = [0.0]
+
+    def cyclic_batch(k):
+        ops = np.zeros(batch, binding.OP_DTYPE)
+        pair = np.arange(batch) % k
+        ops["kind"], ops["i"], ops["j"] = binding.KIND_GOSSIP, 2 * pair, 2 * pair + 1
+        ops["t"] = now[0] + 1e-3 * (np.arange(batch) // k + 1)
+        now[0] = float(ops["t"][-1])
+        off = np.arange(0, batch + 1, k, dtype=np.int64)
+        return binding.Batch(ops, off if off[-1] == batch else np.append(off, batch))
+
+    rows = []
+    k = 1
+    while 2 * k <= cfg.n:
+        for _ in range(2):
+            eng.apply_events(cyclic_batch(k))
+        torch.cuda.synchronize()
+        eng.counters(reset=True)
+        eng.profile(True)
+        for _ in range(4):
+            eng.apply_events(cyclic_batch(k))
+        launches, ms = eng.profile_read()
+        eng.profile(False)
+        moved = eng.counters()["moved_bytes"]
+        rows.append({"reuse_distance_ops": k, "workers_in_cycle": 2 * k, "GBs": moved / (ms * 1e-3) / 1e9,
+                     "avg_launch_ms": ms / launches, "alg_bytes_per_launch": moved / launches})
+        k *= 2
+    w.close()
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +204,9 @@ def main():
     ap.add_argument("--no-stats", action="store_true", help="leave the observables pass out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-inplace-probe", action="store_true", help="skip the in-place streaming ceilings")
+    ap.add_argument("--reuse-sweep", action="store_true",
+                    help="instead of the benchmark: the walk kernel's rate against the reuse distance of a row "
+                         "(synthetic gossip-only batches on --workload, which needs the complete graph: C5)")
     ap.add_argument("--no-profile", action="store_true", help="do not bracket each kernel launch with HIP events")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -162,6 +216,11 @@ def main():
     import torch
     from paper_2306_08289_amd import workloads as wl, a2cid_stream_probe
 
+    if args.reuse_sweep:
+        torch.cuda.set_device(0)
+        print(json.dumps({"reuse_sweep": {"workload": args.workload, "kernel": MODE_WHAT[1], "events_per_launch": args.batch,
+                                          "rows": reuse_sweep(args.workload, args.batch)}}))
+        return
     cfg = wl.CONFIGS[args.workload]
     if args.d:
         cfg = wl.scaled(cfg, d=args.d)
