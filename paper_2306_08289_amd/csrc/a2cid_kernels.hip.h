@@ -3,7 +3,7 @@
 // The event kernels (level, walk) and the observables kernel are HBM streams (about 0.5 flop per
 // byte), so there is no MFMA and no LDS on their data path: each lane moves 128-bit pieces straight
 // between global memory and registers, and the design goal is simply "enough independent 16-byte
-// loads in flight per CU".  The opt-in resident kernel is the exception: it keeps a column tile of
+// loads in flight per CU".  The resident kernel is the exception: it keeps a column tile of
 // every touched row in LDS for the length of a batch.
 #pragma once
 
@@ -485,9 +485,8 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
 // from the stored values (PRE: Algorithm 1 as listed) and whether any operation of the launch carries a
 // trailing mix (TRAIL) are compile-time cases, so the common path (neither) carries no test for them.
 // Valid only while every gradient input of the batch is final when the batch is submitted (true
-// for the affine gradient model; a real network's gradient at x_i is not), which is why this path
-// is opt-in and its throughput is reported apart from the roofline of the one-pass-per-event
-// kernels.
+// for the affine gradient model; a real network's gradient at x_i is not).  Its throughput is
+// reported apart from the roofline of the one-pass-per-event kernels: it is not bound by memory.
 // ------------------------------------------------------------------------------------------
 struct alignas(8) Pair { float x, xt; };
 
