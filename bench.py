@@ -194,7 +194,7 @@ def main():
                          "0 = one launch per level, 2 = LDS-resident")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--walk-occupancy", type=int, default=None, help="walk kernel: at most this many workgroups per CU")
-    ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup")
+    ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup (default: chosen per batch)")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
     ap.add_argument("--no-chain-leg", action="store_true", help="skip the separate chain-kernel measurement")
@@ -233,7 +233,7 @@ def main():
     if args.walk_occupancy is not None:
         w.engine.set_walk_occupancy(args.walk_occupancy)
     if args.group is not None or args.cols is not None:
-        w.engine.set_resident_group(args.group or 8, args.cols or 1)
+        w.engine.set_resident_group(args.group or 0, args.cols or 1)
     stats_bytes = 0.0 if args.no_stats else 8.0 * cfg.n * cfg.d
 
     def step():

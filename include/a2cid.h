@@ -351,9 +351,10 @@ int a2cid_set_chain_slots(a2cid_ctx *ctx, int32_t slots);
 int a2cid_set_walk_occupancy(a2cid_ctx *ctx, int32_t workgroups_per_cu);
 
 /* Mode 2 only: group = waves per workgroup, i.e. how many operations of one level a column tile
- * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4: a tile is 64 * cols
- * columns wide and needs 512 * cols * workers + 6 144 * cols bytes of the CU's 160 KiB of LDS).
- * Default: 8, 1. */
+ * processes concurrently (1, 2, 4, 8 or 16); cols = columns per lane (1, 2 or 4; group = 1 goes with
+ * cols = 1 only): a tile is 64 * cols columns wide and needs 512 * cols bytes of the CU's 160 KiB of
+ * LDS per worker.  group = 0 (the default; cols is then ignored): the library chooses both for every
+ * batch from the average number of operations per level and the number of workers. */
 int a2cid_set_resident_group(a2cid_ctx *ctx, int32_t group, int32_t cols);
 
 /* Launch shape of the observables kernel: pieces = 16-byte pieces per lane and row (1 or 2), rows =

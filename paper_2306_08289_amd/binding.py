@@ -335,7 +335,7 @@ class Engine:
     def set_walk_occupancy(self, workgroups_per_cu=0):
         _check(load().a2cid_set_walk_occupancy(self._h, int(workgroups_per_cu)))
 
-    def set_resident_group(self, group=8, cols=1):
+    def set_resident_group(self, group=0, cols=1):
         _check(load().a2cid_set_resident_group(self._h, int(group), int(cols)))
 
     def set_stats_tuning(self, pieces=2, rows=2, blocks=2048, nontemporal=1):

@@ -32,7 +32,7 @@ namespace {
 
 constexpr int kSlots = 4;               // operation-table staging buffers in flight
 constexpr int64_t kSlotOps = 16384;     // operations per staging buffer (1 MiB)
-constexpr int64_t kResRecords = 131072; // records of the resident kernel's per-wave programmes per staging buffer (4 MiB)
+constexpr int64_t kResRecords = 8192;   // slots of the resident kernel's per-wave programmes per staging buffer (16 waves x 512)
 constexpr int kStatsBlocksMax = 8192;   // upper bound on workgroups of the observables kernel (grid-stride)
 
 struct Slot {
@@ -40,7 +40,7 @@ struct Slot {
     DevOp *dev = nullptr;
     // resident kernel only: rows touched, compact operation records, gradient inputs in order
     int32_t *rows_host = nullptr, *rows_dev = nullptr;   // A2CID_MAX_WORKERS entries
-    ResOp *res_host = nullptr, *res_dev = nullptr;       // kResRecords entries
+    ResSlot *res_host = nullptr, *res_dev = nullptr;     // kResRecords entries
     GradIn *gin_host = nullptr, *gin_dev = nullptr;      // kSlotOps entries
     hipEvent_t done = nullptr;
     bool in_flight = false;
@@ -85,12 +85,18 @@ struct a2cid_ctx {
     int threads = 256;
     int walk = -1;                      // 0: one launch per level; 1: one walk launch per batch; 2: resident; 3: chain;
                                         // -1: 3, except 1 for very short rows (event_mode())
-    int group = 8;                      // resident kernel: waves per workgroup (sharing one 64-column tile)
+    int group = 0;                      // resident kernel: waves per workgroup (sharing one tile); 0: chosen per batch
+    int group_now = 8, cols_now = 1;    // the shape of the launch being written
     float *zero_dev = nullptr;          // a zero float and, behind it, a one: stand in for absent gradient inputs
-    int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4)
+    int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4) when group != 0
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
-    std::vector<std::vector<ResOp>> programme;   // resident kernel: the per-wave programmes being written
+    std::vector<std::vector<ResSlot>> programme; // resident kernel: the per-wave programmes being written
+    std::vector<int32_t> wave_slots;             // per wave: slots of the operations dealt to it in the current (sub-)level
+    std::vector<int64_t> last_grad_rec;          // per wave: index of its latest gradient record in programme (-1: none)
+    std::vector<int32_t> last_grad_level;        // per wave: (sub-)level of its latest gradient event
+    std::vector<int32_t> wave_load;              // per wave: operations dealt to it in the current (sub-)level
+    std::vector<int32_t> wave_of;                // per operation of the current (sub-)level: its wave
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     bool failed = false;                // an enqueueing step failed half-way: device state and time stamps disagree
     // observables scratch
@@ -300,51 +306,230 @@ int launch_ops(a2cid_ctx *c, const DevOp *ops, int32_t n_ops, LaunchKind walk) {
 
 
 
-int launch_resident(a2cid_ctx *c, const Slot *s, int32_t stride, int32_t n_rows, bool trailing) {
+// The resident kernel: flags of the launch are template cases.
+template <int W, int C>
+void launch_resident_wc(a2cid_ctx *c, const Slot *s, int32_t n_rows, unsigned blocks, size_t lds, bool pre,
+                         bool trail, bool hc, bool hh, hipError_t *err) {
+    *err = hipSuccess;
+#define A2CID_RES(PRE, TRAIL, HC, HH)                                                                                    \
+    do {                                                                                                             \
+        if (lds > 65536)                                                                                             \
+            *err = hipFuncSetAttribute((const void *)resident_kernel<W, C, PRE, TRAIL, HC, HH>,                    \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                        \
+        if (*err == hipSuccess)                                                                                      \
+            hipLaunchKernelGGL((resident_kernel<W, C, PRE, TRAIL, HC, HH>), dim3(blocks), dim3(64 * W), lds,       \
+                               c->stream, c->x, c->xt, c->ld, c->d, s->res_dev, s->gin_dev,          \
+                               s->rows_dev, n_rows, (float)c->alpha, (float)c->alpha_t);                             \
+    } while (0)
+    const int key = (pre ? 8 : 0) | (trail ? 4 : 0) | (hc ? 2 : 0) | (hh ? 1 : 0);
+    switch (key) {
+        case 0: A2CID_RES(false, false, false, false); break;
+        case 1: A2CID_RES(false, false, false, true); break;
+        case 2: A2CID_RES(false, false, true, false); break;
+        case 3: A2CID_RES(false, false, true, true); break;
+        case 4: A2CID_RES(false, true, false, false); break;
+        case 5: A2CID_RES(false, true, false, true); break;
+        case 6: A2CID_RES(false, true, true, false); break;
+        case 7: A2CID_RES(false, true, true, true); break;
+        case 8: A2CID_RES(true, false, false, false); break;
+        case 9: A2CID_RES(true, false, false, true); break;
+        case 10: A2CID_RES(true, false, true, false); break;
+        case 11: A2CID_RES(true, false, true, true); break;
+        case 12: A2CID_RES(true, true, false, false); break;
+        case 13: A2CID_RES(true, true, false, true); break;
+        case 14: A2CID_RES(true, true, true, false); break;
+        default: A2CID_RES(true, true, true, true); break;
+    }
+#undef A2CID_RES
+}
+
+int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_rows, bool trailing, bool has_c, bool has_h) {
     TimedLaunch tl{};
     if (c->profiling) {
         if (int rc = get_event(c, &tl.start)) return rc;
         if (int rc = get_event(c, &tl.stop)) return rc;
         A2CID_HIP(hipEventRecord(tl.start, c->stream));
     }
-    const int cols = c->resident_cols;
+    const int cols = c->cols_now;
     const unsigned blocks = (unsigned)((c->d + 64 * cols - 1) / (64 * cols));
     const size_t lds = resident_lds_bytes(cols, n_rows);
-#define A2CID_RESIDENT_K(W, C, PRE, TRAIL)                                                                       \
-    do {                                                                                                         \
-        if (lds > 65536)                                                                                         \
-            A2CID_HIP(hipFuncSetAttribute((const void *)resident_kernel<W, C, PRE, TRAIL>,                       \
-                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));                \
-        hipLaunchKernelGGL((resident_kernel<W, C, PRE, TRAIL>), dim3(blocks), dim3(64 * W), lds, c->stream,      \
-                           c->x, c->xt, c->ld, c->d, s->res_dev, stride, s->gin_dev, s->rows_dev, n_rows,        \
-                           (float)c->alpha, (float)c->alpha_t);                                                  \
-    } while (0)
-#define A2CID_RESIDENT(W, C)                                                                                     \
-    do {                                                                                                         \
-        if (c->order) { if (trailing) A2CID_RESIDENT_K(W, C, true, true); else A2CID_RESIDENT_K(W, C, true, false); }   \
-        else { if (trailing) A2CID_RESIDENT_K(W, C, false, true); else A2CID_RESIDENT_K(W, C, false, false); }   \
-    } while (0)
-    const int key = c->group * 10 + cols;
-    switch (key) {
-        case 11: A2CID_RESIDENT(1, 1); break;
-        case 21: A2CID_RESIDENT(2, 1); break;
-        case 41: A2CID_RESIDENT(4, 1); break;
-        case 161: A2CID_RESIDENT(16, 1); break;
-        case 42: A2CID_RESIDENT(4, 2); break;
-        case 82: A2CID_RESIDENT(8, 2); break;
-        case 162: A2CID_RESIDENT(16, 2); break;
-        case 84: A2CID_RESIDENT(8, 4); break;
-        case 164: A2CID_RESIDENT(16, 4); break;
-        default: A2CID_RESIDENT(8, 1); break;
+    if (lds > 160 * 1024) return fail(A2CID_EINVAL, "internal: %d rows x %d columns per lane exceed the LDS", n_rows, cols);
+    hipError_t err = hipSuccess;
+    const bool pre = c->order != 0;
+    switch (c->group_now * 10 + cols) {
+        case 11: launch_resident_wc<1, 1>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 21: launch_resident_wc<2, 1>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 22: launch_resident_wc<2, 2>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 24: launch_resident_wc<2, 4>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 41: launch_resident_wc<4, 1>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 42: launch_resident_wc<4, 2>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 44: launch_resident_wc<4, 4>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 81: launch_resident_wc<8, 1>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 82: launch_resident_wc<8, 2>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 84: launch_resident_wc<8, 4>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 161: launch_resident_wc<16, 1>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 162: launch_resident_wc<16, 2>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        case 164: launch_resident_wc<16, 4>(c, s, n_rows, blocks, lds, pre, trailing, has_c, has_h, &err); break;
+        default: return fail(A2CID_EINVAL, "no resident kernel for %d waves and %d columns per lane", c->group_now, cols);
     }
-#undef A2CID_RESIDENT
-#undef A2CID_RESIDENT_K
+    A2CID_HIP(err);
     A2CID_HIP(hipGetLastError());
     if (c->profiling) {
         A2CID_HIP(hipEventRecord(tl.stop, c->stream));
         c->timed.push_back(tl);
     }
     ++c->n_launch;
+    return A2CID_OK;
+}
+
+// One launch of resident_kernel: writes the per-wave programmes for the operations of the batch from operation *k
+// on (which lies in level *l), as many whole (sub-)levels as the programmes hold, uploads them and launches the kernel.
+// On return *l, *k name the first operation not included.  trailing: gossip operations take two slots.
+int enqueue_resident(a2cid_ctx *c, const a2cid_event_batch *batch, int32_t *l, int64_t *k, bool trailing) {
+    Slot *s;
+    if (int rc = acquire_slot(c, &s)) return rc;
+    const int W = c->group_now;
+    const size_t n_slots = (size_t)resident_slots(W);      // of one wave's programme
+    const uint32_t row_bytes = resident_row_bytes(c->cols_now);
+    const uintptr_t zero = 1u, one = 3u;        // odd values: no pointer, a constant row
+    const int64_t sub_max = 31 * (int64_t)W;    // at most 31 operations (62 slots) per wave between two control slots
+    int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
+    c->slot_of.assign(c->n, -1);
+    c->programme.resize(W);
+    for (auto &prog : c->programme) prog.clear();
+    c->last_grad_rec.assign(W, -1);
+    c->last_grad_level.assign(W, -1);
+    c->wave_load.assign(W, 0);
+    c->wave_slots.assign(W, 0);
+    const ResSlot blank = {0u, 0u, 0u, 0u};
+    auto f2u = [](float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; };
+    const uint32_t gossip_slots = trailing ? 2u : 1u;
+    int32_t sub_index = 0;                      // running number of the (sub-)levels of this launch
+    bool full = false;
+    while (!full && *l < batch->n_levels) {
+        const int64_t hi = batch->level_off[*l + 1];
+        if (*k >= hi) { ++*l; continue; }
+        const int64_t sub = *k, end = std::min(hi, sub + sub_max);
+        // Deal the operations to the waves: gradient events first, each to the least loaded wave whose previous
+        // gradient event lies furthest back (its inputs are requested when that one is done); then the gossip
+        // events to the least loaded waves.
+        std::fill(c->wave_load.begin(), c->wave_load.end(), 0);
+        std::fill(c->wave_slots.begin(), c->wave_slots.end(), 0);
+        c->wave_of.assign((size_t)(end - sub), 0);
+        for (int pass = 0; pass < 2; ++pass)
+            for (int64_t q = sub; q < end; ++q) {
+                const bool is_grad = batch->ops[q].kind == A2CID_KIND_GRADIENT;
+                if (is_grad != (pass == 0)) continue;
+                int best = 0;
+                for (int w = 1; w < W; ++w) {
+                    if (c->wave_load[w] != c->wave_load[best]) {
+                        if (c->wave_load[w] < c->wave_load[best]) best = w;
+                    } else if (is_grad && c->last_grad_level[w] < c->last_grad_level[best]) {
+                        best = w;
+                    }
+                }
+                c->wave_of[(size_t)(q - sub)] = best;
+                ++c->wave_load[best];
+                c->wave_slots[best] += is_grad ? 2 : (int32_t)gossip_slots;
+                if (is_grad) c->last_grad_level[best] = sub_index;
+            }
+        // does every wave's programme take the (sub-)level (and still an end slot after it)?
+        for (int w = 0; w < W && !full; ++w) {
+            size_t at = c->programme[(size_t)w].size();
+            const size_t need = 1 + (size_t)c->wave_slots[w];
+            if ((at & 63) + need > 63) at = (at + 64) & ~(size_t)63;      // a jump slot, then the next set
+            if (at + need + 1 > n_slots) full = true;
+        }
+        if (full) break;
+        // per wave: control slot, gossip operations, gradient operations; never across a set of 64 slots
+        for (int w = 0; w < W; ++w) {
+            auto &prog = c->programme[(size_t)w];
+            const size_t need = 1 + (size_t)c->wave_slots[w];
+            if ((prog.size() & 63) + need > 63) {
+                ResSlot jump = blank;
+                jump.x = kResJump;
+                prog.push_back(jump);
+                ResSlot pad = blank;
+                pad.x = kResEnd;
+                while (prog.size() & 63) prog.push_back(pad);
+            }
+            ResSlot ctl = blank;
+            ctl.y = kResNone;
+            const size_t ctl_at = prog.size();
+            prog.push_back(ctl);
+            uint32_t n_gos_w = 0, n_grad_w = 0;
+            for (int pass = 0; pass < 2; ++pass)
+                for (int64_t q = sub; q < end; ++q) {
+                    if (c->wave_of[(size_t)(q - sub)] != w) continue;
+                    const a2cid_op &op = batch->ops[q];
+                    const a2cid_coef &cf = c->plan.coef[q];
+                    const bool is_grad = op.kind == A2CID_KIND_GRADIENT;
+                    if (is_grad != (pass == 1)) continue;
+                    const int32_t row_i = op.i, row_j = is_grad ? op.i : op.j;
+                    if (c->slot_of[row_i] < 0) { c->slot_of[row_i] = n_rows; s->rows_host[n_rows++] = row_i; }
+                    if (c->slot_of[row_j] < 0) { c->slot_of[row_j] = n_rows; s->rows_host[n_rows++] = row_j; }
+                    ResSlot r = blank;
+                    r.x = (uint32_t)c->slot_of[row_i] * row_bytes;
+                    if (!is_grad) {
+                        r.y = (uint32_t)c->slot_of[row_j] * row_bytes;
+                        r.z = f2u(cf.b_pre_i); r.w = f2u(cf.b_pre_j);
+                        prog.push_back(r);
+                        if (trailing) {
+                            ResSlot r2 = blank;
+                            r2.x = f2u(cf.b_post_i); r2.y = f2u(cf.b_post_j);
+                            prog.push_back(r2);
+                        }
+                        ++n_gos_w;
+                    } else {
+                        r.y = f2u(cf.b_pre_i); r.z = f2u(op.gamma); r.w = f2u(op.gscale);
+                        const bool use_c = op.c && op.gscale != 0.f, use_h = op.h && op.gscale != 0.f;
+                        const uintptr_t xi = op.xi ? (uintptr_t)op.xi : zero;
+                        s->gin_host[n_grad].xi = xi;
+                        s->gin_host[n_grad].c = use_c ? (uintptr_t)op.c : zero;
+                        s->gin_host[n_grad].h = use_h ? (uintptr_t)op.h : one;
+                        n_xi += op.xi != nullptr; n_c += use_c; n_h += use_h;
+                        // the slot that names this event: the second slot of the wave's previous gradient
+                        // operation, or the first slot of its programme
+                        ResSlot &from = c->last_grad_rec[w] < 0 ? prog[0] : prog[(size_t)c->last_grad_rec[w]];
+                        if (c->last_grad_rec[w] < 0) from.y = (uint32_t)n_grad;
+                        else from.x = (uint32_t)n_grad;
+                        from.z = (uint32_t)(xi & 0xffffffffu);
+                        from.w = (uint32_t)((uint64_t)xi >> 32);
+                        prog.push_back(r);
+                        ResSlot r2 = blank;
+                        r2.x = kResNone;
+                        r2.y = f2u(cf.b_post_i);
+                        c->last_grad_rec[w] = (int64_t)prog.size();
+                        prog.push_back(r2);
+                        ++n_grad;
+                        ++n_grad_w;
+                    }
+                }
+            prog[ctl_at].x = kResLevel | n_gos_w << 8 | n_grad_w << 16;
+        }
+        ++sub_index;
+        *k = end;
+    }
+    if (sub_index == 0) return fail(A2CID_EINVAL, "internal: a level does not fit an empty resident programme");
+    ResSlot end_slot = blank;
+    end_slot.x = kResEnd;
+    ResSlot *host = s->res_host;
+    for (int w = 0; w < W; ++w) {
+        ResSlot *dst = host + (size_t)w * n_slots;
+        const auto &prog = c->programme[(size_t)w];
+        if (prog.size() + 1 > n_slots) return fail(A2CID_EINVAL, "internal: resident programme of %zu slots", prog.size());
+        std::copy(prog.begin(), prog.end(), dst);
+        std::fill(dst + prog.size(), dst + n_slots, end_slot);
+    }
+    A2CID_HIP(hipMemcpyAsync(s->rows_dev, s->rows_host, sizeof(int32_t) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
+    A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * n_slots * (size_t)W, hipMemcpyHostToDevice,
+                             c->stream));
+    if (n_grad > 0)
+        A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad, hipMemcpyHostToDevice, c->stream));
+    c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c + n_h));
+    if (int rc = launch_resident(c, s, n_rows, trailing, n_c > 0, n_h > 0)) return rc;
+    A2CID_HIP(hipEventRecord(s->done, c->stream));
+    s->in_flight = true;
     return A2CID_OK;
 }
 
@@ -432,8 +617,8 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
         A2CID_HIP(hipMalloc((void **)&s.dev, sizeof(DevOp) * kSlotOps));
         A2CID_HIP(hipHostMalloc((void **)&s.rows_host, sizeof(int32_t) * A2CID_MAX_WORKERS, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.rows_dev, sizeof(int32_t) * A2CID_MAX_WORKERS));
-        A2CID_HIP(hipHostMalloc((void **)&s.res_host, sizeof(ResOp) * kResRecords, hipHostMallocDefault));
-        A2CID_HIP(hipMalloc((void **)&s.res_dev, sizeof(ResOp) * kResRecords));
+        A2CID_HIP(hipHostMalloc((void **)&s.res_host, sizeof(ResSlot) * kResRecords, hipHostMallocDefault));
+        A2CID_HIP(hipMalloc((void **)&s.res_dev, sizeof(ResSlot) * kResRecords));
         A2CID_HIP(hipHostMalloc((void **)&s.gin_host, sizeof(GradIn) * kSlotOps, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.gin_dev, sizeof(GradIn) * kSlotOps));
         A2CID_HIP(hipEventCreateWithFlags(&s.done, hipEventDisableTiming));
@@ -479,18 +664,18 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 }
 
 // The event kernel of the next batch when the choice is left to the library, from measurements on the five
-// configurations (events per second, 1024 events per batch): the LDS-resident kernel wherever its tile fits the LDS and
-// a level has enough operations to occupy its waves (32 ... 112 workers: 1.1 to 2 times the chain kernel), and for
-// rows so short (at most 4096 parameters) that every other kernel launches a handful of workgroups; the walk kernel
-// for short rows otherwise (it needs no programme from the host); the chain kernel for the rest (16 workers: 1.3 times
-// the resident kernel; more than 112 workers).
+// configurations (events per second, 1024 events per batch): the LDS-resident kernel for up to 112 workers (4 workers:
+// 2.2 times, 16: 1.25 times, 64: 1.7 to 2.6 times the chain kernel) and for rows so short (at most 4096 parameters) that
+// every other kernel launches a handful of workgroups; beyond that the chain kernel, or, for short rows, the walk kernel
+// (it needs no programme from the host).  The resident kernel itself takes up to kResidentMaxRows workers (512 bytes
+// of LDS per row and column-per-lane).
 constexpr int64_t kShortRow = 4096;
-constexpr int32_t kResidentMaxRows = 112;   // 512 bytes of LDS per row and column-per-lane, plus the input ring
+constexpr int32_t kResidentAutoRows = 112;
+constexpr int32_t kResidentMaxRows = 320;
 static int event_mode(const a2cid_ctx *c) {
     if (c->walk >= 0) return c->walk;
-    const bool short_row = c->d <= kShortRow;
-    if (c->n <= kResidentMaxRows && (short_row || c->n >= 32)) return 2;
-    return short_row ? 1 : 3;
+    if (c->n <= kResidentAutoRows) return 2;
+    return c->d <= kShortRow ? 1 : 3;
 }
 // Operations per launch: the chain programme of k operations has at most 3 k + slots steps (every spill makes room for
 // a parking); each of the resident kernel's W programmes holds at most k barrier records (a (sub-)level per operation
@@ -498,12 +683,35 @@ static int event_mode(const a2cid_ctx *c) {
 static int64_t piece_capacity(const a2cid_ctx *c) {
     switch (event_mode(c)) {
         case 3: return (kSlotOps - kChainMaxSlots) / 3;
-        case 2: return std::min<int64_t>(kSlotOps, (kResRecords / c->group - 64) / 2);
+        case 2: return kSlotOps;        // cut into launches on the way (enqueue_resident)
         default: return kSlotOps;
     }
 }
 
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch);
+
+// Launch shape of the resident kernel for a batch, unless the caller has fixed it.  Waves per tile: the largest power
+// of two that does not exceed the average number of operations of a level (more waves than operations only add
+// waves that pass the barrier with nothing to do; fewer make a level as long as several operations).  Columns per
+// lane: as many as still let 32 / waves workgroups share a CU's 160 KiB of LDS (32 waves per CU is the hardware limit),
+// at 512 bytes per row and column-per-lane.  Measured on the 64-worker configurations (events per second, 1024 events
+// per batch): ring, 17.5 operations per level: 16 waves x 2 columns 108 k, 8 x 1 94 k; exponential graph, 11.5: 8 x 1
+// 46.8 k, 16 x 2 44.6 k; complete graph, 10.1: 8 x 1 44.8 k, 16 x 2 41.6 k; 16 workers on a ring, 5.7: 4 x 2 766 k,
+// 8 x 2 699 k.
+static void resident_shape(a2cid_ctx *c, const a2cid_event_batch *batch) {
+    if (c->group != 0) {
+        c->group_now = c->group;
+        c->cols_now = c->resident_cols;
+        return;
+    }
+    const double per_level = batch->n_levels > 0 ? (double)batch->n_ops / (double)batch->n_levels : 1.0;
+    int waves = 2;
+    while (waves < 16 && 2 * waves <= per_level) waves *= 2;
+    int cols = 4;
+    while (cols > 1 && (size_t)c->n * 512 * cols * (32 / waves) > 160 * 1024) cols /= 2;
+    c->group_now = waves;
+    c->cols_now = cols;
+}
 
 static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
     if (int rc = enter(c)) return rc;
@@ -543,6 +751,20 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
     const int64_t cap = piece_capacity(c);
     const int mode = event_mode(c);
+    if (mode == 2) {
+        resident_shape(c, batch);
+        // as many launches as the programmes need (each holds resident_slots slots per wave)
+        bool trailing = false;
+        for (int64_t k = 0; k < batch->n_ops && !trailing; ++k)
+            trailing = c->plan.coef[k].b_post_i != 0.f || c->plan.coef[k].b_post_j != 0.f;
+        int32_t l = 0;
+        int64_t k = 0;
+        while (l < batch->n_levels) {
+            if (k >= batch->level_off[l + 1]) { ++l; continue; }
+            if (int rc = enqueue_resident(c, batch, &l, &k, trailing)) return rc;
+        }
+        return A2CID_OK;
+    }
     int32_t l = 0;
     while (l < batch->n_levels) {
         // take as many whole levels as fit into one staging buffer (apply_impl has checked that every level does)
@@ -601,111 +823,6 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
                 }
             } else {
                 for (int64_t k = 0; k < count; ++k) fill(s->host[k], first + k);
-            }
-            if (mode == 2) {
-                // One programme per wave: LDS slots in order of first use, gradient inputs in order of use, every
-                // level cut into sub-levels of at most kStage gradient events (the size of the kernel's input ring),
-                // every sub-level opened by a barrier record (in all programmes) that names its gradient events,
-                // its operations dealt to the waves in turn.
-                const int W = c->group;
-                int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
-                bool trailing = false;
-                const uintptr_t zero = (uintptr_t)c->zero_dev | 1u, one = (uintptr_t)(c->zero_dev + 1) | 1u;
-                c->slot_of.assign(c->n, -1);
-                c->programme.resize(W);
-                for (auto &prog : c->programme) prog.clear();
-                ResOp bar;
-                std::memset(&bar, 0, sizeof(bar));
-                bar.w0 = kResBarrier;
-                auto open_sub = [&](int32_t g_lo, int32_t g_hi, int64_t ops_in_sub) {
-                    bar.g_lo = (uint32_t)g_lo;
-                    bar.g_hi = (uint32_t)g_hi;
-                    for (int w = 0; w < W; ++w) {           // operation k of the sub-level goes to wave k mod W
-                        bar.n_mine = (uint32_t)((ops_in_sub + W - 1 - w) / W);
-                        c->programme[(size_t)w].push_back(bar);
-                    }
-                };
-                // gradient ordinals of the piece, so that a fill can reach beyond its own sub-level
-                int32_t total_grad = 0;
-                for (int64_t k = 0; k < count; ++k) total_grad += op_kind(s->host[k].kind) == kOpGradient;
-                int32_t staged_hi = 0;                      // ordinals below this are in the ring or consumed
-                for (int32_t ll = l; ll < l_end; ++ll) {
-                    const int64_t lo = batch->level_off[ll] - first, hi = batch->level_off[ll + 1] - first;
-                    int64_t sub = lo;
-                    while (sub < hi) {
-                        // the sub-level [sub, end): as far as the level goes with at most kStage gradient events
-                        int64_t end = sub;
-                        int32_t grads = 0;
-                        while (end < hi) {
-                            const bool is_grad = op_kind(s->host[end].kind) == kOpGradient;
-                            if (is_grad && grads == kStage) break;
-                            grads += is_grad;
-                            ++end;
-                        }
-                        // Everything before ordinal n_grad is consumed when this sub-level starts, so the ring can
-                        // take ordinals up to n_grad + kStage: when the sub-level needs one that is not staged yet,
-                        // the waves fetch as far ahead as the ring allows (few fills, each hiding one memory latency).
-                        int32_t fill_lo = 0, fill_hi = 0;
-                        if (n_grad + grads > staged_hi) {
-                            fill_lo = staged_hi;
-                            fill_hi = std::min(total_grad, n_grad + kStage);
-                            staged_hi = fill_hi;
-                        }
-                        open_sub(fill_lo, fill_hi, end - sub);
-                        for (int64_t k = sub; k < end; ++k) {
-                            const DevOp &o = s->host[k];
-                            const int32_t kind = op_kind(o.kind);
-                            if (c->slot_of[o.row_i] < 0) { c->slot_of[o.row_i] = n_rows; s->rows_host[n_rows++] = o.row_i; }
-                            if (c->slot_of[o.row_j] < 0) { c->slot_of[o.row_j] = n_rows; s->rows_host[n_rows++] = o.row_j; }
-                            ResOp r;
-                            std::memset(&r, 0, sizeof(r));
-                            r.w0 = (kind == kOpGossip ? kResGossip : kResGradient) |
-                                   ((uint32_t)c->slot_of[o.row_i] << 8) | ((uint32_t)c->slot_of[o.row_j] << 16);
-                            r.b_i = o.b_i; r.b_j = o.b_j; r.bp_i = o.bp_i; r.bp_j = o.bp_j;
-                            r.gamma = o.gamma; r.gscale = o.gscale;
-                            trailing = trailing || o.bp_i != 0.f || o.bp_j != 0.f;
-                            if (kind == kOpGradient) {
-                                r.gidx = (uint32_t)n_grad;
-                                s->gin_host[n_grad].xi = o.xi ? (uintptr_t)o.xi : zero;
-                                s->gin_host[n_grad].c = (o.c && o.gscale != 0.f) ? (uintptr_t)o.c : zero;
-                                s->gin_host[n_grad].h = (o.h && o.gscale != 0.f) ? (uintptr_t)o.h : one;
-                                n_xi += o.xi != nullptr;
-                                n_c += o.c && o.gscale != 0.f;
-                                n_h += o.h && o.gscale != 0.f;
-                                ++n_grad;
-                            }
-                            c->programme[(size_t)((k - sub) % W)].push_back(r);
-                        }
-                        sub = end;
-                    }
-                }
-                size_t longest = 0;
-                for (const auto &prog : c->programme) longest = std::max(longest, prog.size());
-                const size_t stride = (longest + 1 + 63) / 64 * 64;          // at least one end record, whole chunks
-                if ((int64_t)(stride * (size_t)W) > kResRecords)
-                    return fail(A2CID_EINVAL, "internal: resident programmes of %zu records", stride * (size_t)W);
-                ResOp end_rec;
-                std::memset(&end_rec, 0, sizeof(end_rec));
-                end_rec.w0 = kResEnd;
-                for (int w = 0; w < W; ++w) {
-                    ResOp *dst = s->res_host + (size_t)w * stride;
-                    const auto &prog = c->programme[(size_t)w];
-                    std::copy(prog.begin(), prog.end(), dst);
-                    std::fill(dst + prog.size(), dst + stride, end_rec);
-                }
-                A2CID_HIP(hipMemcpyAsync(s->rows_dev, s->rows_host, sizeof(int32_t) * (size_t)n_rows,
-                                         hipMemcpyHostToDevice, c->stream));
-                A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResOp) * stride * (size_t)W,
-                                         hipMemcpyHostToDevice, c->stream));
-                if (n_grad > 0)
-                    A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad,
-                                             hipMemcpyHostToDevice, c->stream));
-                c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c + n_h));
-                if (int rc = launch_resident(c, s, (int32_t)stride, n_rows, trailing)) return rc;
-                A2CID_HIP(hipEventRecord(s->done, c->stream));
-                s->in_flight = true;
-                l = l_end;
-                continue;
             }
             double moved = 0.0;             // bytes per column that this chunk's launches move
             if (mode == 3) {
@@ -982,11 +1099,14 @@ int a2cid_set_walk_occupancy(a2cid_ctx *c, int32_t workgroups_per_cu) {
 int a2cid_set_resident_group(a2cid_ctx *c, int32_t group, int32_t cols) {
     clear_error();
     if (!c) return fail(A2CID_EINVAL, "context is NULL");
+    if (group == 0) {                   // back to the choice per batch
+        c->group = 0;
+        return A2CID_OK;
+    }
     if (group != 1 && group != 2 && group != 4 && group != 8 && group != 16)
-        return fail(A2CID_EINVAL, "group must be 1, 2, 4, 8 or 16");
+        return fail(A2CID_EINVAL, "group must be 0 (chosen per batch), 1, 2, 4, 8 or 16");
     if (cols != 1 && cols != 2 && cols != 4) return fail(A2CID_EINVAL, "cols must be 1, 2 or 4");
-    if ((cols == 2 && group < 4) || (cols == 4 && group < 8))
-        return fail(A2CID_EINVAL, "cols = 2 needs group >= 4 and cols = 4 needs group >= 8");
+    if (group == 1 && cols != 1) return fail(A2CID_EINVAL, "group = 1 goes with cols = 1 only");
     if (resident_lds_bytes(cols, c->n) > 160 * 1024)
         return fail(A2CID_EINVAL, "%d workers x %d columns per lane do not fit into 160 KiB of LDS", c->n, cols);
     c->group = group;

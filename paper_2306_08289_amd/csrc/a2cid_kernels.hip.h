@@ -459,54 +459,9 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
     }
 }
 
-// ------------------------------------------------------------------------------------------
-// Resident kernel: grid = tiles of 64 * C columns, W waves per workgroup, one launch per batch.
-// The same ownership argument as for the walk kernel, taken one step further: the workgroup
-// first copies its columns of every row the batch touches into LDS (slot s holds row rows[s] as
-// (x, xt) pairs, 512 * C bytes per slot), then applies all operations of the batch to the LDS copy,
-// and finally writes the rows back.  State traffic per batch drops from 32 d bytes per gossip
-// event to 16 d bytes per touched row; gradient inputs are still read once per event.
-//
-// LDS capacity allows only a few such tiles per CU, so the W waves of a workgroup share one tile:
-// lane l of every wave stands for columns l*C .. l*C+C-1 of the tile, the operations of a level
-// (which touch disjoint rows) are dealt to the waves, and a workgroup barrier separates levels.
-// The kernel is bound by instruction issue, not by memory, so everything a wave can be spared is
-// done on the host: it writes one linear programme per wave (ResOp records, W * stride of them,
-// every programme padded with end records to the common length, a multiple of 64):
-//   - a barrier record before each (sub-)level, the same number of them in every programme; it says
-//     how many operation records of this programme follow it, and it may name a range of gradient
-//     events (by their ordinal in the launch) whose inputs (xi, c, h at the lane's columns) the waves
-//     fetch together, between two barriers, into a ring of kStage LDS slots (slot = ordinal mod
-//     kStage): the host lets a fill reach as far ahead as the ring allows, so that fills are few;
-//   - an operation record (gossip or gradient event) for each operation dealt to the wave;
-//   - end records.
-// A wave fetches its records 64 at a time, one per lane, and broadcasts the fields of the current one
-// with v_readlane: no memory access and no level bookkeeping per operation.  Whether jumps are taken
-// from the stored values (PRE: Algorithm 1 as listed) and whether any operation of the launch carries a
-// trailing mix (TRAIL) are compile-time cases, so the common path (neither) carries no test for them.
-// Valid only while every gradient input of the batch is final when the batch is submitted (true
-// for the affine gradient model; a real network's gradient at x_i is not).  Its throughput is
-// reported apart from the roofline of the one-pass-per-event kernels: it is not bound by memory.
-// ------------------------------------------------------------------------------------------
-struct alignas(8) Pair { float x, xt; };
-
-enum : uint32_t { kResGradient = 0, kResGossip = 1, kResBarrier = 3, kResEnd = 4 };
-
-struct ResOp {                   // 32 bytes
-    uint32_t w0;                 // kRes* kind | slot_i << 8 | slot_j << 16
-    union { uint32_t gidx; uint32_t g_lo; };   // gradient: ordinal of the event; barrier: first ordinal to stage
-    union { float b_i; uint32_t n_mine; };     // barrier: operation records of this programme up to the next barrier
-    union { float b_j; uint32_t g_hi; };       // gossip: mixing coefficient of worker j; barrier: one past the last ordinal
-    float bp_i, bp_j, gamma, gscale;
-};
-static_assert(sizeof(ResOp) == 32, "ResOp layout");
-
-// Gradient inputs of the launch's gradient events, in order.  A pointer with bit 0 set addresses a
-// single float (a zero for xi and c, a one for h) that every column reads; otherwise column k is at pointer + k.
+// Gradient inputs of a launch's gradient events, in order: device pointers to the row (column k at pointer + k), or an
+// odd value, which is no pointer but stands for a constant row: 1 for zeros, 3 for ones.
 struct GradIn { uintptr_t xi, c, h; };
-
-constexpr int kStage = 8;        // LDS ring slots for gradient inputs: with 64 workers a tile then takes 38 KiB, which lets
-                                 // four workgroups share a CU (16 slots: three, measured 18 % slower)
 
 typedef const __attribute__((address_space(1))) float *global_f32;
 
@@ -549,148 +504,275 @@ __device__ __forceinline__ void store_cols(float *p, int64_t col, int64_t d, con
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Resident kernel: grid = tiles of 64 * C columns, W waves per workgroup, one launch per batch (or per piece of
+// a batch).  The same ownership argument as for the walk kernel, taken one step further: the workgroup first
+// copies its columns of every row the launch touches into LDS, then applies all operations of the launch to the
+// LDS copy, and finally writes the rows back.  State traffic per launch drops from 32 d bytes per gossip event to
+// 16 d bytes per touched row; gradient inputs are still read once per event.
+//
+// LDS capacity allows only a few such tiles per CU, so the W waves of a workgroup share one tile: lane l of every
+// wave stands for columns l*C .. l*C+C-1 of the tile, the operations of a level (which touch disjoint rows) are
+// dealt to the waves, and a workgroup barrier separates levels.  The kernel is bound by instruction issue, not
+// by memory or LDS bandwidth, so everything a wave can be spared is done on the host, which writes one linear
+// programme per wave:
+//   - the programme is typed by position: a control slot says how many gossip operations and then how many
+//     gradient operations follow, so the operation loops test no kind, and operations carry ready-made LDS
+//     byte offsets of their rows;
+//   - a programme is at most 256 or 512 slots of 16 bytes (resident_slots), and a wave holds all of it in
+//     registers from the start (four or eight slots per lane): the operation loops read their operands with
+//     v_readlane and never touch memory for them.  The host cuts a batch into launches whose programmes fit, and
+//     never lets a level straddle a set of 64 slots (it closes a set early with a jump slot), so the loops over
+//     one set are plain;
+//   - gradient inputs do not pass through LDS and need no barrier of their own: every gradient operation names
+//     the wave's NEXT gradient event (its xi pointer in the slot, c and h through the gin table), and the wave
+//     requests those inputs into registers as soon as it has used the current ones; the host deals the
+//     gradient events of a level to the waves whose last one lies furthest back, so a request has several
+//     levels' time to arrive.  The very first ones are named by the programme's first control slot.
+// Whether jumps are taken from the stored values (PRE: Algorithm 1 as listed), whether any operation of the
+// launch carries a trailing mix (TRAIL) and whether any gradient event has a centre c (HC) or a curvature h (HH)
+// are compile-time cases, so the common path carries no test and no load for them.
+// Valid only while every gradient input of the batch is final when the batch is submitted (true for the affine
+// gradient model; a real network's gradient at x_i is not).  Its throughput is reported apart from the roofline
+// of the one-pass-per-event kernels: it is not bound by memory.
+// LDS: n_rows * 64 * 8 C bytes (C = 1: (x, xt) pairs; C = 2, 4: planes of 16-byte cells holding two columns).
+// ------------------------------------------------------------------------------------------
+enum : uint32_t { kResLevel = 1, kResJump = 2, kResEnd = 3 };
+constexpr uint32_t kResNone = 0xffffffffu;
+// Slots of one wave's programme: sets of 64, one slot per lane and set.  Four sets (16 registers) when 16 waves share
+// the operations of a level, eight otherwise (a wave then has twice the operations, and registers to spare).
+constexpr int resident_sets(int waves) { return waves >= 16 ? 4 : 8; }
+constexpr int resident_slots(int waves) { return 64 * resident_sets(waves); }
+constexpr int kResSetMax = 62;            // operation slots of one wave between two control slots
+
+// control:   x = kRes* | gossip operations << 8 | gradient operations << 16; in the first slot of a programme also
+//            y = ordinal of the wave's first gradient event (kResNone: it has none), z/w = that event's xi
+// gossip:    x = LDS offset of row i, y = of row j, z = b_i, w = b_j; with trailing mixes (TRAIL) a second slot
+//            follows: x = bp_i, y = bp_j
+// gradient:  two slots: x = LDS offset of the row, y = b_i, z = gamma, w = gscale; then x = ordinal of the wave's
+//            next gradient event or kResNone, y = bp_i, z/w = xi of that next event (low, high; an odd value is no
+//            pointer but stands for a constant row: 1 for zeros, 3 for ones; so are c and h in the gin table)
+struct ResSlot { uint32_t x, y, z, w; };
+static_assert(sizeof(ResSlot) == 16, "ResSlot layout");
+
+constexpr size_t resident_lds_bytes(int cols, int n_rows) { return (size_t)n_rows * 64 * 8 * (size_t)cols; }
+constexpr uint32_t resident_row_bytes(int cols) { return 64u * 8u * (uint32_t)cols; }
+
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// The lane's C columns of a row (x and xt) to and from its cell(s) at LDS byte offset off (which already includes
+// the lane's own offset): C = 1: one (x, xt) pair; C = 2, 4: cells (x, xt, x', xt') of two columns, one per plane.
 template <int C>
-__device__ __forceinline__ Cols<C> grad_input_cols(uintptr_t p, int64_t col, int64_t d) {
-    if (p & 1) {                                          // a single float stands for the whole row
-        Cols<C> r;
-        const float z = *(global_f32)(p & ~(uintptr_t)1);
+__device__ __forceinline__ void res_put(unsigned char *lds, uint32_t off, const Cols<C> &a, const Cols<C> &at) {
+    if constexpr (C == 1) {
+        const v2f t = {a.v[0], at.v[0]};
+        *(v2f *)(lds + off) = t;
+    } else {
 #pragma unroll
-        for (int c = 0; c < C; ++c) r.v[c] = z;
-        return r;
+        for (int h = 0; h < C / 2; ++h) {
+            const v4f t = {a.v[2 * h], at.v[2 * h], a.v[2 * h + 1], at.v[2 * h + 1]};
+            *(v4f *)(lds + off + h * 1024) = t;
+        }
     }
-    return load_cols<C>((const float *)p, col, d);
 }
 
-// W waves share a tile of 64 * C columns; lane l of every wave stands for columns l*C .. l*C + C-1 of the tile.
 template <int C>
-struct alignas(8) TileCell { Pair p[C]; };
-
-// The staged inputs of one gradient event at a lane's columns.
-template <int C>
-struct StageCell { float xi[C], c[C], h[C]; };
-
-// Dynamic LDS of the resident kernel: the tile rows, then the ring of staged gradient inputs.
-constexpr size_t resident_lds_bytes(int cols, int n_rows) {
-    return (sizeof(Pair) * (size_t)n_rows + 3 * sizeof(float) * (size_t)kStage) * 64 * (size_t)cols;
+__device__ __forceinline__ void res_get(const unsigned char *lds, uint32_t off, Cols<C> &a, Cols<C> &at) {
+    if constexpr (C == 1) {
+        const v2f t = *(const v2f *)(lds + off);
+        a.v[0] = t.x; at.v[0] = t.y;
+    } else {
+#pragma unroll
+        for (int h = 0; h < C / 2; ++h) {
+            const v4f t = *(const v4f *)(lds + off + h * 1024);
+            a.v[2 * h] = t.x; at.v[2 * h] = t.y; a.v[2 * h + 1] = t.z; at.v[2 * h + 1] = t.w;
+        }
+    }
 }
 
-template <int W, int C, bool PRE, bool TRAIL>
-__global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x, float *__restrict__ xt,
-                                                          int64_t ld, int64_t d, const ResOp *__restrict__ recs,
-                                                          int32_t stride, const GradIn *__restrict__ gin,
-                                                          const int32_t *__restrict__ rows, int32_t n_rows,
-                                                          float alpha, float alpha_t) {
-    extern __shared__ unsigned char lds_raw[];
-    TileCell<C> *tile = (TileCell<C> *)lds_raw;          // [n_rows][64]
-    StageCell<C> *gstage = (StageCell<C> *)(tile + (size_t)n_rows * 64);   // [kStage][64]: inputs of staged gradient events
+// Columns col0 + lane_c .. + C - 1 of one gradient input.  whole: every lane of the tile has C columns below d.
+// The input is addressed as global memory (a generic pointer would make these loads count as possible LDS
+// accesses, and every LDS access of the operation loops would then wait for them).
+template <int C>
+__device__ __forceinline__ void res_input(float (&out)[C], uintptr_t p, int64_t col0, uint32_t lane_c, int64_t d,
+                                         bool whole, float absent) {
+    typedef float vec __attribute__((ext_vector_type(C)));
+    typedef const __attribute__((address_space(1))) vec *global_vec;
+    if (p & 1) {                                          // no row: the constant 0 (tag 1) or 1 (tag 3) for every column
+        const float z = (p & 2) ? 1.f : 0.f;
+#pragma unroll
+        for (int c = 0; c < C; ++c) out[c] = z;
+        return;
+    }
+    const global_f32 base = (global_f32)p + col0;         // uniform; the lane adds a 32-bit offset
+    if (whole) {
+        if constexpr (C == 1) out[0] = __builtin_nontemporal_load(base + lane_c);
+        else {
+            const vec t = __builtin_nontemporal_load((global_vec)(base + lane_c));
+#pragma unroll
+            for (int c = 0; c < C; ++c) out[c] = t[c];
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < C; ++c) out[c] = col0 + lane_c + c < d ? base[lane_c + c] : absent;
+    }
+}
+
+template <int C, bool HC, bool HH>
+__device__ __forceinline__ void res_request(float (&gx)[C], float (&gc)[C], float (&gh)[C], uint32_t xi_lo,
+                                           uint32_t xi_hi, const GradIn *__restrict__ gin, uint32_t g, int64_t col0,
+                                           uint32_t lane_c, int64_t d, bool whole) {
+    res_input<C>(gx, (uintptr_t)xi_lo | (uintptr_t)xi_hi << 32, col0, lane_c, d, whole, 0.f);
+    if constexpr (HC) res_input<C>(gc, gin[g].c, col0, lane_c, d, whole, 0.f);
+    if constexpr (HH) res_input<C>(gh, gin[g].h, col0, lane_c, d, whole, 1.f);
+}
+
+template <int W, int C, bool PRE, bool TRAIL, bool HC, bool HH>
+__global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
+                                                           int64_t d, const ResSlot *__restrict__ recs,
+                                                           const GradIn *__restrict__ gin,
+                                                           const int32_t *__restrict__ rows, int32_t n_rows,
+                                                           float alpha, float alpha_t) {
+    extern __shared__ unsigned char lds[];
+    constexpr uint32_t kCell = C == 1 ? 8 : 16;
+    constexpr uint32_t kRow = resident_row_bytes(C);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int64_t col = ((int64_t)blockIdx.x * 64 + lane) * C;
+    const int64_t col0 = (int64_t)blockIdx.x * (64 * C);            // first column of the tile (uniform)
+    const uint32_t lane_c = (uint32_t)lane * C;
+    const int64_t col = col0 + lane_c;
     const bool valid = col < d;
+    const bool whole = col0 + 64 * C <= d;
+    const uint32_t lane_off = (uint32_t)lane * kCell;
 
-    // rows wave, wave + W, ... of the slot list, four loads of each buffer in flight per wave
+    // this wave's whole programme: slot 64 k + lane in set k
+    constexpr int kSets = resident_sets(W);
+    const uint4 *prog = (const uint4 *)recs + (size_t)wave * (64 * kSets) + lane;
+    uint4 set[kSets];
+#pragma unroll
+    for (int k = 0; k < kSets; ++k) set[k] = prog[64 * k];
+
+    // the wave's first gradient inputs
+    float gx[C], gc[C], gh[C];
+#pragma unroll
+    for (int c = 0; c < C; ++c) { gx[c] = 0.f; gc[c] = 0.f; gh[c] = 1.f; }
+    {
+        const uint32_t g0 = lane_u32(set[0].y, 0);
+        if (g0 != kResNone)
+            res_request<C, HC, HH>(gx, gc, gh, lane_u32(set[0].z, 0), lane_u32(set[0].w, 0), gin, g0, col0, lane_c, d, whole);
+    }
+
+    // rows wave, wave + W, ... of the slot list into LDS, four rows' loads in flight per wave
     for (int32_t s0 = wave; s0 < n_rows; s0 += 4 * W) {
-        TileCell<C> v[4];
+        Cols<C> a[4], at[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int32_t s = s0 + q * W;
 #pragma unroll
-            for (int c = 0; c < C; ++c) { v[q].p[c].x = 0.f; v[q].p[c].xt = 0.f; }
+            for (int c = 0; c < C; ++c) { a[q].v[c] = 0.f; at[q].v[c] = 0.f; }
             if (s < n_rows && valid) {
                 const int64_t off = (int64_t)rows[s] * ld;
-                const Cols<C> a = load_cols<C>(x + off, col, d), at = load_cols<C>(xt + off, col, d);
-#pragma unroll
-                for (int c = 0; c < C; ++c) { v[q].p[c].x = a.v[c]; v[q].p[c].xt = at.v[c]; }
+                a[q] = load_cols<C>(x + off, col, d);
+                at[q] = load_cols<C>(xt + off, col, d);
             }
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int32_t s = s0 + q * W;
-            if (s < n_rows) tile[s * 64 + lane] = v[q];
+            if (s < n_rows) res_put<C>(lds, (uint32_t)s * kRow + lane_off, a[q], at[q]);
         }
     }
-    // no barrier here: every programme starts with a barrier record
+    // no barrier here: every programme starts with a level slot, which brings one
 
-    const ResOp *mine = recs + (size_t)wave * stride;
-    TileCell<C> *const my_cell = tile + lane;            // slot s of this lane: my_cell + 64 s
-    uint4 ra = {0u, 0u, 0u, 0u}, rb = {0u, 0u, 0u, 0u};
-    int32_t pos = 0;                                     // next record of this wave's programme
-    for (;;) {
-        // a barrier record opens a (sub-)level; anything else (an end record) closes the programme
-        if ((pos & 63) == 0) {                           // the next 64 records, one per lane
-            const uint4 *p = (const uint4 *)(mine + pos + lane);
-            ra = p[0]; rb = p[1];
-        }
-        const int lb = pos & 63;
-        if ((lane_u32(ra.x, lb) & 7u) != kResBarrier) break;
-        const int32_t g_lo = (int32_t)lane_u32(ra.y, lb), g_hi = (int32_t)lane_u32(ra.w, lb);
-        const int32_t n_mine = (int32_t)lane_u32(ra.z, lb);
-        ++pos;
-        // the previous (sub-)level is complete and its staged inputs are consumed; stage those of this one
-        __syncthreads();
-        if (g_hi > g_lo) {
-            for (int32_t o = g_lo + wave; o < g_hi; o += W) {
-                const GradIn in = gin[o];
-                StageCell<C> gv;
-#pragma unroll
-                for (int c = 0; c < C; ++c) { gv.xi[c] = 0.f; gv.c[c] = 0.f; gv.h[c] = 1.f; }
-                if (valid) {
-                    const Cols<C> a = grad_input_cols<C>(in.xi, col, d), cc = grad_input_cols<C>(in.c, col, d),
-                                  hh = grad_input_cols<C>(in.h, col, d);
-#pragma unroll
-                    for (int c = 0; c < C; ++c) { gv.xi[c] = a.v[c]; gv.c[c] = cc.v[c]; gv.h[c] = hh.v[c]; }
-                }
-                gstage[(o % kStage) * 64 + lane] = gv;
-            }
-            __syncthreads();
-        }
-        // this wave's operations of the (sub-)level
-        for (int32_t t = 0; t < n_mine; ++t, ++pos) {
-            if ((pos & 63) == 0) {
-                const uint4 *p = (const uint4 *)(mine + pos + lane);
-                ra = p[0]; rb = p[1];
-            }
-            const int l = pos & 63;
-            const uint32_t w0 = lane_u32(ra.x, l);
-            // both rows are requested before the first use (slot_j = slot_i in a gradient record, so the second read is
-            // always a valid one); the empty asm statement keeps the compiler from moving it behind the branch, where
-            // every gossip operation would pay two LDS round trips in a row instead of one
-            TileCell<C> *pi = my_cell + ((w0 >> 8) & 255u) * 64, *pj = my_cell + ((w0 >> 16) & 255u) * 64;
-            TileCell<C> vi = *pi, vj = *pj;
-#pragma unroll
-            for (int c = 0; c < C; ++c) asm volatile("" : "+v"(vj.p[c].x), "+v"(vj.p[c].xt));
-            const float b_i = lane_f32(ra.z, l);
-            if ((w0 & 7u) == kResGossip) {
+    // The slots of one set, from its first to a jump slot (returns false) or to the end of the programme (true).
+    auto run_set = [&](const uint4 &r) __attribute__((always_inline)) -> bool {
+        int32_t pos = 0;                                 // lane that holds the next slot
+        for (;;) {
+            const uint32_t w0 = lane_u32(r.x, pos);
+            const uint32_t kind = w0 & 7u;
+            if (kind != kResLevel) return kind != kResJump;
+            const int32_t n_gossip = (int32_t)((w0 >> 8) & 255u), n_grad = (int32_t)((w0 >> 16) & 255u);
+            ++pos;
+            __syncthreads();                             // the previous level is complete in LDS
+            for (int32_t t = 0; t < n_gossip; ++t, pos += TRAIL ? 2 : 1) {
+                const uint32_t oi = lane_u32(r.x, pos) + lane_off, oj = lane_u32(r.y, pos) + lane_off;
                 OpCoef oc;
-                oc.b_i = b_i; oc.b_j = lane_f32(ra.w, l);
-                oc.bp_i = TRAIL ? lane_f32(rb.x, l) : 0.f;
-                oc.bp_j = TRAIL ? lane_f32(rb.y, l) : 0.f;
+                oc.b_i = lane_f32(r.z, pos); oc.b_j = lane_f32(r.w, pos);
+                oc.bp_i = TRAIL ? lane_f32(r.x, pos + 1) : 0.f;
+                oc.bp_j = TRAIL ? lane_f32(r.y, pos + 1) : 0.f;
+                if constexpr (C == 1) {
+                    v2f a = *(const v2f *)(lds + oi), b = *(const v2f *)(lds + oj);
+                    float xi_ = a.x, xti = a.y, xj = b.x, xtj = b.y;
+                    gossip_jump<TRAIL>(xi_, xti, xj, xtj, oc, alpha, alpha_t, PRE);
+                    a.x = xi_; a.y = xti; b.x = xj; b.y = xtj;
+                    *(v2f *)(lds + oi) = a;
+                    *(v2f *)(lds + oj) = b;
+                } else {
+                    v4f a[C / 2], b[C / 2];              // all reads first: one LDS round trip per operation
 #pragma unroll
-                for (int c = 0; c < C; ++c) {
-                    gossip_jump<TRAIL>(vi.p[c].x, vi.p[c].xt, vj.p[c].x, vj.p[c].xt, oc, alpha, alpha_t, PRE);
+                    for (int h = 0; h < C / 2; ++h) {
+                        a[h] = *(const v4f *)(lds + oi + h * 1024);
+                        b[h] = *(const v4f *)(lds + oj + h * 1024);
+                    }
+#pragma unroll
+                    for (int h = 0; h < C / 2; ++h) {
+                        float i0 = a[h].x, it0 = a[h].y, i1 = a[h].z, it1 = a[h].w;
+                        float j0 = b[h].x, jt0 = b[h].y, j1 = b[h].z, jt1 = b[h].w;
+                        gossip_jump<TRAIL>(i0, it0, j0, jt0, oc, alpha, alpha_t, PRE);
+                        gossip_jump<TRAIL>(i1, it1, j1, jt1, oc, alpha, alpha_t, PRE);
+                        const v4f na = {i0, it0, i1, it1}, nb = {j0, jt0, j1, jt1};
+                        a[h] = na; b[h] = nb;
+                    }
+#pragma unroll
+                    for (int h = 0; h < C / 2; ++h) {
+                        *(v4f *)(lds + oi + h * 1024) = a[h];
+                        *(v4f *)(lds + oj + h * 1024) = b[h];
+                    }
                 }
-                *pj = vj;
-            } else {                                     // a gradient event
-                const StageCell<C> in = gstage[(lane_u32(ra.y, l) % kStage) * 64 + lane];
-                OpCoef oc;
-                oc.b_i = b_i; oc.bp_i = TRAIL ? lane_f32(rb.x, l) : 0.f;
-                oc.gamma = lane_f32(rb.z, l); oc.gscale = lane_f32(rb.w, l);
-#pragma unroll
-                for (int c = 0; c < C; ++c)
-                    gradient_jump<TRAIL>(vi.p[c].x, vi.p[c].xt, in.xi[c], in.c[c], in.h[c], oc, PRE);
             }
-            *pi = vi;
+            for (int32_t t = 0; t < n_grad; ++t, pos += 2) {
+                const uint32_t oi = lane_u32(r.x, pos) + lane_off;
+                OpCoef oc;
+                oc.b_i = lane_f32(r.y, pos); oc.gamma = lane_f32(r.z, pos); oc.gscale = lane_f32(r.w, pos);
+                oc.bp_i = TRAIL ? lane_f32(r.y, pos + 1) : 0.f;
+                if constexpr (C == 1) {
+                    v2f a = *(const v2f *)(lds + oi);
+                    float xi_ = a.x, xti = a.y;
+                    gradient_jump<TRAIL>(xi_, xti, gx[0], gc[0], gh[0], oc, PRE);
+                    a.x = xi_; a.y = xti;
+                    *(v2f *)(lds + oi) = a;
+                } else {
+                    v4f a[C / 2];
+#pragma unroll
+                    for (int h = 0; h < C / 2; ++h) a[h] = *(const v4f *)(lds + oi + h * 1024);
+#pragma unroll
+                    for (int h = 0; h < C / 2; ++h) {
+                        float i0 = a[h].x, it0 = a[h].y, i1 = a[h].z, it1 = a[h].w;
+                        gradient_jump<TRAIL>(i0, it0, gx[2 * h], gc[2 * h], gh[2 * h], oc, PRE);
+                        gradient_jump<TRAIL>(i1, it1, gx[2 * h + 1], gc[2 * h + 1], gh[2 * h + 1], oc, PRE);
+                        const v4f na = {i0, it0, i1, it1};
+                        a[h] = na;
+                    }
+#pragma unroll
+                    for (int h = 0; h < C / 2; ++h) *(v4f *)(lds + oi + h * 1024) = a[h];
+                }
+                const uint32_t next = lane_u32(r.x, pos + 1);
+                if (next != kResNone)
+                    res_request<C, HC, HH>(gx, gc, gh, lane_u32(r.z, pos + 1), lane_u32(r.w, pos + 1), gin, next, col0,
+                                          lane_c, d, whole);
+            }
         }
-    }
+    };
+#pragma unroll
+    for (int k = 0; k < kSets; ++k)
+        if (run_set(set[k])) break;                      // the last set always ends the programme
     __syncthreads();
 
     if (valid) {
         for (int32_t s = wave; s < n_rows; s += W) {
-            const TileCell<C> v = tile[s * 64 + lane];
-            const int64_t off = (int64_t)rows[s] * ld;
             Cols<C> a, at;
-#pragma unroll
-            for (int c = 0; c < C; ++c) { a.v[c] = v.p[c].x; at.v[c] = v.p[c].xt; }
+            res_get<C>(lds, (uint32_t)s * kRow + lane_off, a, at);
+            const int64_t off = (int64_t)rows[s] * ld;
             store_cols<C>(x + off, col, d, a);
             store_cols<C>(xt + off, col, d, at);
         }

@@ -354,7 +354,12 @@ def test_observables_at_full_size_against_library_reductions():
 @pytest.mark.parametrize("name,d,events,batch,group,cols", [
     ("C1", 1000, 3000, 512, 4, 1), ("C2", 64 * 37 + 5, 3000, 1000, 1, 1), ("C3", 9001, 3000, 1024, 2, 1),
     ("C4", 12345, 4000, 1024, 8, 1), ("C5", 8191, 4000, 700, 4, 2), ("C4", 12347, 3000, 1024, 8, 2),
-    ("C2", 9001, 3000, 1024, 16, 4), ("C2", 1027, 3000, 1000, 8, 4), ("C1", 3, 500, 100, 16, 2)])
+    ("C2", 9001, 3000, 1024, 16, 4), ("C2", 1027, 3000, 1000, 8, 4), ("C1", 3, 500, 100, 16, 2),
+    ("C3", 2 * 128 * 3 + 1, 3000, 1024, 16, 2), ("C5", 4099, 3000, 1024, 16, 1), ("C2", 777, 2000, 600, 2, 4),
+    ("C2", 1234, 2000, 4096, 4, 4), ("C1", 130, 2000, 1000, 2, 2),
+    # group 0: the library chooses the shape for every batch
+    ("C1", 1000, 3000, 512, 0, 1), ("C2", 5003, 3000, 1000, 0, 1), ("C3", 9001, 3000, 1024, 0, 1),
+    ("C4", 12345, 3000, 1024, 0, 1), ("C5", 8191, 3000, 4096, 0, 1)])
 def test_resident_kernel_matches_oracle(name, d, events, batch, group, cols):
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=events)
     _say(f"resident {name} d={d} group={group} cols={cols}")
@@ -483,7 +488,7 @@ def test_extreme_worker_counts(n, topology, d, events, mode):
 
 def test_resident_mode_is_refused_beyond_its_lds_capacity():
     from paper_2306_08289_amd import A2cidError, binding
-    w = wl.Workload(_custom_workload(128, "ring", 64), batch_events=100)
+    w = wl.Workload(_custom_workload(384, "ring", 64), batch_events=100)
     with pytest.raises(A2cidError) as e:
         w.engine.set_tuning(1, 0, 256, 2)
     assert e.value.code == binding.EINVAL
