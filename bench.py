@@ -48,9 +48,9 @@ MEASURED_TRAFFIC = {
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
-             2: "resident_kernel (the library's choice for 32 to 112 workers): every touched row stays in LDS for the "
+             2: "resident_kernel (the library's choice for up to 112 workers): every touched row stays in LDS for the "
                 "whole batch (state read and written once per batch)",
-             3: "chain_kernel (the library's choice for fewer than 32 or more than 112 workers): events re-ordered so "
+             3: "chain_kernel (the library's choice for more than 112 workers): events re-ordered so "
                 "that a worker's columns are found in registers or parked in LDS as often as possible"}
 
 
@@ -288,7 +288,7 @@ def main():
         if not launches:
             return None
         achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
-        bound = "hbm" if kernel_name != "resident_kernel" else "instruction issue and LDS latency (not HBM: see frac)"
+        bound = "hbm" if kernel_name != "resident_kernel" else "instruction issue and level barriers (not HBM: see frac)"
         traffic, source = MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name), (None, None)) \
             if default_shape else (None, None)
         return {"bound": bound, "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,

@@ -262,6 +262,36 @@ typedef struct a2cid_chain_step {
 int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t lds_slots, a2cid_chain_step *steps,
                      int64_t capacity, int64_t *n_steps, double *bytes_per_column);
 
+/* The programmes the resident kernel (a2cid_set_tuning, mode 2) runs for one launch, as a pure host
+ * function.  waves wavefronts share a tile of 64 * cols columns that stays in LDS for the whole launch;
+ * the operations of a level touch disjoint workers, so they are dealt to the waves, and a workgroup
+ * barrier separates levels.  Every wave gets its own linear programme of 16-byte slots, typed by
+ * position (fp32 values as their bit patterns):
+ *   control:  x = gossip operations | gradient operations << 8 that follow, after a barrier (a level);
+ *             or 0x10000: continue with the next set of 64 slots; or 0x20000: the end.  In the first slot
+ *             of a programme also y = ordinal of the wave's first gradient event (0xffffffff: none),
+ *             z, w = low and high word of that event's xi;
+ *   gossip:   x, y = LDS byte offsets of worker i's and j's row (512 * cols * position in rows),
+ *             z, w = mixing coefficients b_pre_i, b_pre_j; if any operation of the batch has a trailing
+ *             mix, a second slot follows with x, y = b_post_i, b_post_j;
+ *   gradient: two slots: x = LDS byte offset of the worker's row, y = b_pre_i, z = gamma, w = gscale;
+ *             then x = ordinal of the wave's next gradient event (0xffffffff: none), y = b_post_i,
+ *             z, w = that event's xi.  An xi of 1 stands for "no xi" (zeros).
+ * All programmes hold the same number of levels; a level never straddles a set of 64 slots; a
+ * programme has 256 (waves = 16) or 512 slots, end slots included, so one call takes as many whole
+ * levels (levels of more than 31 * waves operations in parts) from operation first_op on as fit, and
+ * *next_op is where the next launch starts (first_op must be the start of a level or a former
+ * *next_op).  Gradient events are numbered in the order of gradient_ops (their indices in the batch).
+ * *waves = 0 lets the library choose waves and cols from the batch (as a2cid_apply_events does) and
+ * returns the choice.  slots: *waves * (256 or 512) entries, wave after wave (8192 always suffice);
+ * rows: n entries; gradient_ops: n_ops entries.  coef: the batch's coefficients from a2cid_plan_batch. */
+typedef struct a2cid_resident_slot {
+    uint32_t x, y, z, w;
+} a2cid_resident_slot;
+int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int32_t *waves, int32_t *cols,
+                        int64_t first_op, a2cid_resident_slot *slots, int32_t *rows, int32_t *n_rows,
+                        int64_t *gradient_ops, int32_t *n_gradient_ops, int64_t *next_op);
+
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 
 /* Independent Poisson clocks (Assumption 3.1): one per worker (gradient events, rate
@@ -318,9 +348,8 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
  * workgroup size (64 ... 1024, a power of two), mode =
- *  -1: chosen by the library from the shape (default): 2 where its tile fits the LDS and a level holds
- *      enough operations to occupy its waves (32 ... 112 workers) and for rows of at most 4096
- *      parameters; 1 for such short rows otherwise; 3 for everything else;
+ *  -1: chosen by the library from the shape (default): 2 for up to 112 workers; beyond that 1 for rows
+ *      of at most 4096 parameters and 3 for everything else;
  *   0: one launch per level;
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
  *      own columns, each operation reading and writing its rows in device memory (32 d bytes per
@@ -329,8 +358,8 @@ void a2cid_sched_destroy(a2cid_sched *s);
  *      operations stays in registers and workers that come back soon are parked in LDS (16 d bytes
  *      for a gossip event that finds one worker there and leaves one there);
  *   2: as 1, but the workgroup keeps its columns of all touched rows in LDS for the whole batch, so
- *      the state is read and written once per batch instead of once per event (at most 112
- *      workers).
+ *      the state is read and written once per batch instead of once per event (at most 320
+ *      workers: 512 bytes of LDS per worker and column-per-lane).
  * Default: 1, 0, 256, -1 (tiles shrink automatically for short rows).  All modes compute the same
  * operations in the same per-worker order and give the same state bit for bit.  In every mode the
  * gradient inputs of a batch must hold their final values, in stream order, before

@@ -77,6 +77,8 @@ SIGNATURES = {
     "a2cid_destroy": (None, [C.c_void_p]),
     "a2cid_plan_chain": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_int32, C.c_void_p, C.c_int64,
                                    _P(C.c_int64), _P(C.c_double)]),
+    "a2cid_plan_resident": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, _P(C.c_int32), _P(C.c_int32), C.c_int64,
+                                      C.c_void_p, C.c_void_p, _P(C.c_int32), C.c_void_p, _P(C.c_int32), _P(C.c_int64)]),
     "a2cid_set_chain_slots": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
@@ -201,6 +203,29 @@ def a2cid_plan_chain(n, batch, lds_slots=5):
     _check(load().a2cid_plan_chain(int(n), C.byref(bs), int(lds_slots), steps.ctypes.data, len(steps),
                                    C.byref(count), C.byref(per_col)))
     return steps[:count.value], per_col.value
+
+
+SLOT_DTYPE = np.dtype([("x", "<u4"), ("y", "<u4"), ("z", "<u4"), ("w", "<u4")])
+RES_JUMP, RES_END, RES_NONE = 0x10000, 0x20000, 0xffffffff
+
+
+def a2cid_plan_resident(n, batch, coef, first_op=0, waves=0, cols=1):
+    """One launch of the resident kernel from operation first_op on.  Returns a dict: waves, cols (as used), slots
+    (waves x slots-per-wave SLOT_DTYPE array), rows (LDS row -> worker), gradient_ops (ordinal -> index in the batch),
+    next_op."""
+    slots = np.zeros(8192, SLOT_DTYPE)
+    rows = np.zeros(int(n), np.int32)
+    gops = np.zeros(max(1, len(batch.ops)), np.int64)
+    w, c = C.c_int32(int(waves)), C.c_int32(int(cols))
+    n_rows, n_g, nxt = C.c_int32(), C.c_int32(), C.c_int64()
+    bs = batch.struct()
+    coef = np.ascontiguousarray(coef, COEF_DTYPE)
+    _check(load().a2cid_plan_resident(int(n), C.byref(bs), coef.ctypes.data, C.byref(w), C.byref(c), int(first_op),
+                                      slots.ctypes.data, rows.ctypes.data, C.byref(n_rows), gops.ctypes.data,
+                                      C.byref(n_g), C.byref(nxt)))
+    per_wave = 256 if w.value >= 16 else 512
+    return {"waves": w.value, "cols": c.value, "slots": slots[:w.value * per_wave].reshape(w.value, per_wave).copy(),
+            "rows": rows[:n_rows.value].copy(), "gradient_ops": gops[:n_g.value].copy(), "next_op": nxt.value}
 
 
 class Scheduler:

@@ -90,13 +90,7 @@ struct a2cid_ctx {
     float *zero_dev = nullptr;          // a zero float and, behind it, a one: stand in for absent gradient inputs
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4) when group != 0
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
-    std::vector<int32_t> slot_of;       // resident kernel: LDS slot of each worker in the current launch
-    std::vector<std::vector<ResSlot>> programme; // resident kernel: the per-wave programmes being written
-    std::vector<int32_t> wave_slots;             // per wave: slots of the operations dealt to it in the current (sub-)level
-    std::vector<int64_t> last_grad_rec;          // per wave: index of its latest gradient record in programme (-1: none)
-    std::vector<int32_t> last_grad_level;        // per wave: (sub-)level of its latest gradient event
-    std::vector<int32_t> wave_load;              // per wave: operations dealt to it in the current (sub-)level
-    std::vector<int32_t> wave_of;                // per operation of the current (sub-)level: its wave
+    ResidentPlan resplan;               // resident kernel: the launch being planned
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     bool failed = false;                // an enqueueing step failed half-way: device state and time stamps disagree
     // observables scratch
@@ -382,152 +376,38 @@ int launch_resident(a2cid_ctx *c, const Slot *s, int32_t n_rows, bool trailing, 
     return A2CID_OK;
 }
 
-// One launch of resident_kernel: writes the per-wave programmes for the operations of the batch from operation *k
-// on (which lies in level *l), as many whole (sub-)levels as the programmes hold, uploads them and launches the kernel.
-// On return *l, *k name the first operation not included.  trailing: gossip operations take two slots.
+// One launch of resident_kernel: plans the per-wave programmes for the operations of the batch from operation *k on
+// (which lies in level *l), as many whole (sub-)levels as the programmes hold (plan_resident), uploads them and launches
+// the kernel.  On return *l, *k name the first operation not included.
 int enqueue_resident(a2cid_ctx *c, const a2cid_event_batch *batch, int32_t *l, int64_t *k, bool trailing) {
     Slot *s;
     if (int rc = acquire_slot(c, &s)) return rc;
     const int W = c->group_now;
-    const size_t n_slots = (size_t)resident_slots(W);      // of one wave's programme
-    const uint32_t row_bytes = resident_row_bytes(c->cols_now);
-    const uintptr_t zero = 1u, one = 3u;        // odd values: no pointer, a constant row
-    const int64_t sub_max = 31 * (int64_t)W;    // at most 31 operations (62 slots) per wave between two control slots
-    int32_t n_rows = 0, n_grad = 0, n_xi = 0, n_c = 0, n_h = 0;
-    c->slot_of.assign(c->n, -1);
-    c->programme.resize(W);
-    for (auto &prog : c->programme) prog.clear();
-    c->last_grad_rec.assign(W, -1);
-    c->last_grad_level.assign(W, -1);
-    c->wave_load.assign(W, 0);
-    c->wave_slots.assign(W, 0);
-    const ResSlot blank = {0u, 0u, 0u, 0u};
-    auto f2u = [](float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; };
-    const uint32_t gossip_slots = trailing ? 2u : 1u;
-    int32_t sub_index = 0;                      // running number of the (sub-)levels of this launch
-    bool full = false;
-    while (!full && *l < batch->n_levels) {
-        const int64_t hi = batch->level_off[*l + 1];
-        if (*k >= hi) { ++*l; continue; }
-        const int64_t sub = *k, end = std::min(hi, sub + sub_max);
-        // Deal the operations to the waves: gradient events first, each to the least loaded wave whose previous
-        // gradient event lies furthest back (its inputs are requested when that one is done); then the gossip
-        // events to the least loaded waves.
-        std::fill(c->wave_load.begin(), c->wave_load.end(), 0);
-        std::fill(c->wave_slots.begin(), c->wave_slots.end(), 0);
-        c->wave_of.assign((size_t)(end - sub), 0);
-        for (int pass = 0; pass < 2; ++pass)
-            for (int64_t q = sub; q < end; ++q) {
-                const bool is_grad = batch->ops[q].kind == A2CID_KIND_GRADIENT;
-                if (is_grad != (pass == 0)) continue;
-                int best = 0;
-                for (int w = 1; w < W; ++w) {
-                    if (c->wave_load[w] != c->wave_load[best]) {
-                        if (c->wave_load[w] < c->wave_load[best]) best = w;
-                    } else if (is_grad && c->last_grad_level[w] < c->last_grad_level[best]) {
-                        best = w;
-                    }
-                }
-                c->wave_of[(size_t)(q - sub)] = best;
-                ++c->wave_load[best];
-                c->wave_slots[best] += is_grad ? 2 : (int32_t)gossip_slots;
-                if (is_grad) c->last_grad_level[best] = sub_index;
-            }
-        // does every wave's programme take the (sub-)level (and still an end slot after it)?
-        for (int w = 0; w < W && !full; ++w) {
-            size_t at = c->programme[(size_t)w].size();
-            const size_t need = 1 + (size_t)c->wave_slots[w];
-            if ((at & 63) + need > 63) at = (at + 64) & ~(size_t)63;      // a jump slot, then the next set
-            if (at + need + 1 > n_slots) full = true;
-        }
-        if (full) break;
-        // per wave: control slot, gossip operations, gradient operations; never across a set of 64 slots
-        for (int w = 0; w < W; ++w) {
-            auto &prog = c->programme[(size_t)w];
-            const size_t need = 1 + (size_t)c->wave_slots[w];
-            if ((prog.size() & 63) + need > 63) {
-                ResSlot jump = blank;
-                jump.x = kResJump;
-                prog.push_back(jump);
-                ResSlot pad = blank;
-                pad.x = kResEnd;
-                while (prog.size() & 63) prog.push_back(pad);
-            }
-            ResSlot ctl = blank;
-            ctl.y = kResNone;
-            const size_t ctl_at = prog.size();
-            prog.push_back(ctl);
-            uint32_t n_gos_w = 0, n_grad_w = 0;
-            for (int pass = 0; pass < 2; ++pass)
-                for (int64_t q = sub; q < end; ++q) {
-                    if (c->wave_of[(size_t)(q - sub)] != w) continue;
-                    const a2cid_op &op = batch->ops[q];
-                    const a2cid_coef &cf = c->plan.coef[q];
-                    const bool is_grad = op.kind == A2CID_KIND_GRADIENT;
-                    if (is_grad != (pass == 1)) continue;
-                    const int32_t row_i = op.i, row_j = is_grad ? op.i : op.j;
-                    if (c->slot_of[row_i] < 0) { c->slot_of[row_i] = n_rows; s->rows_host[n_rows++] = row_i; }
-                    if (c->slot_of[row_j] < 0) { c->slot_of[row_j] = n_rows; s->rows_host[n_rows++] = row_j; }
-                    ResSlot r = blank;
-                    r.x = (uint32_t)c->slot_of[row_i] * row_bytes;
-                    if (!is_grad) {
-                        r.y = (uint32_t)c->slot_of[row_j] * row_bytes;
-                        r.z = f2u(cf.b_pre_i); r.w = f2u(cf.b_pre_j);
-                        prog.push_back(r);
-                        if (trailing) {
-                            ResSlot r2 = blank;
-                            r2.x = f2u(cf.b_post_i); r2.y = f2u(cf.b_post_j);
-                            prog.push_back(r2);
-                        }
-                        ++n_gos_w;
-                    } else {
-                        r.y = f2u(cf.b_pre_i); r.z = f2u(op.gamma); r.w = f2u(op.gscale);
-                        const bool use_c = op.c && op.gscale != 0.f, use_h = op.h && op.gscale != 0.f;
-                        const uintptr_t xi = op.xi ? (uintptr_t)op.xi : zero;
-                        s->gin_host[n_grad].xi = xi;
-                        s->gin_host[n_grad].c = use_c ? (uintptr_t)op.c : zero;
-                        s->gin_host[n_grad].h = use_h ? (uintptr_t)op.h : one;
-                        n_xi += op.xi != nullptr; n_c += use_c; n_h += use_h;
-                        // the slot that names this event: the second slot of the wave's previous gradient
-                        // operation, or the first slot of its programme
-                        ResSlot &from = c->last_grad_rec[w] < 0 ? prog[0] : prog[(size_t)c->last_grad_rec[w]];
-                        if (c->last_grad_rec[w] < 0) from.y = (uint32_t)n_grad;
-                        else from.x = (uint32_t)n_grad;
-                        from.z = (uint32_t)(xi & 0xffffffffu);
-                        from.w = (uint32_t)((uint64_t)xi >> 32);
-                        prog.push_back(r);
-                        ResSlot r2 = blank;
-                        r2.x = kResNone;
-                        r2.y = f2u(cf.b_post_i);
-                        c->last_grad_rec[w] = (int64_t)prog.size();
-                        prog.push_back(r2);
-                        ++n_grad;
-                        ++n_grad_w;
-                    }
-                }
-            prog[ctl_at].x = kResLevel | n_gos_w << 8 | n_grad_w << 16;
-        }
-        ++sub_index;
-        *k = end;
-    }
-    if (sub_index == 0) return fail(A2CID_EINVAL, "internal: a level does not fit an empty resident programme");
-    ResSlot end_slot = blank;
-    end_slot.x = kResEnd;
-    ResSlot *host = s->res_host;
-    for (int w = 0; w < W; ++w) {
-        ResSlot *dst = host + (size_t)w * n_slots;
-        const auto &prog = c->programme[(size_t)w];
-        if (prog.size() + 1 > n_slots) return fail(A2CID_EINVAL, "internal: resident programme of %zu slots", prog.size());
-        std::copy(prog.begin(), prog.end(), dst);
-        std::fill(dst + prog.size(), dst + n_slots, end_slot);
+    const int64_t k_before = *k;
+    plan_resident(c->n, batch, c->plan.coef.data(), W, c->cols_now, trailing, l, k, c->resplan);
+    if (*k == k_before) return fail(A2CID_EINVAL, "internal: a level does not fit an empty resident programme");
+    const ResidentPlan &rp = c->resplan;
+    const size_t per_wave = (size_t)resident_slots(W);
+    const int32_t n_rows = (int32_t)rp.rows.size(), n_grad = (int32_t)rp.grad_op.size();
+    if ((int64_t)(per_wave * (size_t)W) > kResRecords || n_rows > A2CID_MAX_WORKERS || n_grad > kSlotOps)
+        return fail(A2CID_EINVAL, "internal: resident plan exceeds its staging buffers");
+    for (int w = 0; w < W; ++w)
+        std::memcpy(s->res_host + (size_t)w * per_wave, rp.programme[(size_t)w].data(), per_wave * sizeof(ResSlot));
+    std::copy(rp.rows.begin(), rp.rows.end(), s->rows_host);
+    for (int32_t g = 0; g < n_grad; ++g) {
+        const a2cid_op &op = batch->ops[rp.grad_op[(size_t)g]];
+        const bool affine = op.gscale != 0.f;
+        s->gin_host[g].xi = op.xi ? (uintptr_t)op.xi : kResZeros;
+        s->gin_host[g].c = (op.c && affine) ? (uintptr_t)op.c : kResZeros;
+        s->gin_host[g].h = (op.h && affine) ? (uintptr_t)op.h : kResOnes;
     }
     A2CID_HIP(hipMemcpyAsync(s->rows_dev, s->rows_host, sizeof(int32_t) * (size_t)n_rows, hipMemcpyHostToDevice, c->stream));
-    A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * n_slots * (size_t)W, hipMemcpyHostToDevice,
+    A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * per_wave * (size_t)W, hipMemcpyHostToDevice,
                              c->stream));
     if (n_grad > 0)
         A2CID_HIP(hipMemcpyAsync(s->gin_dev, s->gin_host, sizeof(GradIn) * (size_t)n_grad, hipMemcpyHostToDevice, c->stream));
-    c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (n_xi + n_c + n_h));
-    if (int rc = launch_resident(c, s, n_rows, trailing, n_c > 0, n_h > 0)) return rc;
+    c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (rp.n_xi + rp.n_c + rp.n_h));
+    if (int rc = launch_resident(c, s, n_rows, trailing, rp.n_c > 0, rp.n_h > 0)) return rc;
     A2CID_HIP(hipEventRecord(s->done, c->stream));
     s->in_flight = true;
     return A2CID_OK;
@@ -671,15 +551,13 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 // of LDS per row and column-per-lane).
 constexpr int64_t kShortRow = 4096;
 constexpr int32_t kResidentAutoRows = 112;
-constexpr int32_t kResidentMaxRows = 320;
 static int event_mode(const a2cid_ctx *c) {
     if (c->walk >= 0) return c->walk;
     if (c->n <= kResidentAutoRows) return 2;
     return c->d <= kShortRow ? 1 : 3;
 }
-// Operations per launch: the chain programme of k operations has at most 3 k + slots steps (every spill makes room for
-// a parking); each of the resident kernel's W programmes holds at most k barrier records (a (sub-)level per operation
-// at worst), at most k operation records (all dealt to the same wave then) and an end record, in whole chunks of 64.
+// Operations per staging buffer: the chain programme of k operations has at most 3 k + slots steps (every spill makes
+// room for a parking); the resident kernel's launches are cut to the size of its programmes on the way.
 static int64_t piece_capacity(const a2cid_ctx *c) {
     switch (event_mode(c)) {
         case 3: return (kSlotOps - kChainMaxSlots) / 3;
@@ -690,27 +568,20 @@ static int64_t piece_capacity(const a2cid_ctx *c) {
 
 static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch);
 
-// Launch shape of the resident kernel for a batch, unless the caller has fixed it.  Waves per tile: the largest power
-// of two that does not exceed the average number of operations of a level (more waves than operations only add
-// waves that pass the barrier with nothing to do; fewer make a level as long as several operations).  Columns per
-// lane: as many as still let 32 / waves workgroups share a CU's 160 KiB of LDS (32 waves per CU is the hardware limit),
-// at 512 bytes per row and column-per-lane.  Measured on the 64-worker configurations (events per second, 1024 events
-// per batch): ring, 17.5 operations per level: 16 waves x 2 columns 108 k, 8 x 1 94 k; exponential graph, 11.5: 8 x 1
-// 46.8 k, 16 x 2 44.6 k; complete graph, 10.1: 8 x 1 44.8 k, 16 x 2 41.6 k; 16 workers on a ring, 5.7: 4 x 2 766 k,
-// 8 x 2 699 k.
-static void resident_shape(a2cid_ctx *c, const a2cid_event_batch *batch) {
+// Launch shape of the resident kernel for a batch, unless the caller has fixed it: resident_shape (a2cid_host.cpp).
+// Waves per tile: the smallest power of two with at most 1.6 operations of an average level per wave (more waves only
+// add waves that pass the barrier with nothing to do; fewer make a level as long as several operations).  Columns per lane: as many as still let 32 / waves workgroups share a CU's 160 KiB of LDS (32 waves per CU
+// is the hardware limit), at 512 bytes per row and column-per-lane.  Measured on the 64-worker configurations (events
+// per second, 1024 events per batch): ring, 17.5 operations per level: 16 waves x 2 columns 108 k, 8 x 1 94 k;
+// exponential graph, 11.5: 8 x 1 46.8 k, 16 x 2 44.6 k; complete graph, 10.1: 8 x 1 44.8 k, 16 x 2 41.6 k; 16 workers
+// on a ring, 5.7: 4 x 2 766 k, 8 x 2 699 k.
+static void choose_resident_shape(a2cid_ctx *c, const a2cid_event_batch *batch) {
     if (c->group != 0) {
         c->group_now = c->group;
         c->cols_now = c->resident_cols;
         return;
     }
-    const double per_level = batch->n_levels > 0 ? (double)batch->n_ops / (double)batch->n_levels : 1.0;
-    int waves = 2;
-    while (waves < 16 && 2 * waves <= per_level) waves *= 2;
-    int cols = 4;
-    while (cols > 1 && (size_t)c->n * 512 * cols * (32 / waves) > 160 * 1024) cols /= 2;
-    c->group_now = waves;
-    c->cols_now = cols;
+    resident_shape(c->n, batch, &c->group_now, &c->cols_now);
 }
 
 static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
@@ -752,7 +623,7 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
     const int64_t cap = piece_capacity(c);
     const int mode = event_mode(c);
     if (mode == 2) {
-        resident_shape(c, batch);
+        choose_resident_shape(c, batch);
         // as many launches as the programmes need (each holds resident_slots slots per wave)
         bool trailing = false;
         for (int64_t k = 0; k < batch->n_ops && !trailing; ++k)

@@ -610,6 +610,157 @@ void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots
     }
 }
 
+
+// ---- resident kernel: launch shape and per-wave programmes -------------------------------------------------
+
+void resident_shape(int32_t n, const a2cid_event_batch *batch, int *waves, int *cols) {
+    const double per_level = batch->n_levels > 0 ? (double)batch->n_ops / (double)batch->n_levels : 1.0;
+    int w = 2;
+    while (w < 16 && per_level > 1.6 * w) w *= 2;       // measured break-even between 8 and 16 waves: about 13
+    int c = 4;
+    while (c > 1 && (size_t)n * 512 * c * (32 / w) > 160 * 1024) c /= 2;
+    *waves = w;
+    *cols = c;
+}
+
+void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int waves, int cols,
+                   bool trailing, int32_t *l, int64_t *k, ResidentPlan &plan) {
+    const int W = waves;
+    const size_t n_slots = (size_t)resident_slots(W);
+    const uint32_t row_bytes = resident_row_bytes(cols);
+    const int64_t sub_max = (kResSetMax / 2) * (int64_t)W;  // at most 31 operations (62 slots) per wave and level
+    const uint32_t gossip_slots = trailing ? 2u : 1u;
+    plan.programme.resize(W);
+    for (auto &prog : plan.programme) prog.clear();
+    plan.rows.clear();
+    plan.grad_op.clear();
+    plan.n_xi = plan.n_c = plan.n_h = 0;
+    plan.slot_of.assign(n, -1);
+    plan.last_grad_slot.assign(W, -1);
+    plan.last_grad_level.assign(W, -1);
+    plan.wave_load.assign(W, 0);
+    plan.wave_slots.assign(W, 0);
+    const ResSlot blank = {0u, 0u, 0u, 0u};
+    auto f2u = [](float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; };
+    int32_t sub_index = 0;                      // running number of the (sub-)levels of this launch
+    while (*l < batch->n_levels) {
+        const int64_t hi = batch->level_off[*l + 1];
+        if (*k >= hi) { ++*l; continue; }
+        const int64_t sub = *k, end = std::min(hi, sub + sub_max);
+        // Deal the operations to the waves: gradient events first, each to the least loaded wave whose previous
+        // gradient event lies furthest back (its inputs are requested when that one is done); then the gossip
+        // events to the least loaded waves.
+        std::fill(plan.wave_load.begin(), plan.wave_load.end(), 0);
+        std::fill(plan.wave_slots.begin(), plan.wave_slots.end(), 0);
+        plan.wave_of.assign((size_t)(end - sub), 0);
+        for (int pass = 0; pass < 2; ++pass)
+            for (int64_t q = sub; q < end; ++q) {
+                const bool is_grad = batch->ops[q].kind == A2CID_KIND_GRADIENT;
+                if (is_grad != (pass == 0)) continue;
+                int best = 0;
+                for (int w = 1; w < W; ++w) {
+                    if (plan.wave_load[w] != plan.wave_load[best]) {
+                        if (plan.wave_load[w] < plan.wave_load[best]) best = w;
+                    } else if (is_grad && plan.last_grad_level[w] < plan.last_grad_level[best]) {
+                        best = w;
+                    }
+                }
+                plan.wave_of[(size_t)(q - sub)] = best;
+                ++plan.wave_load[best];
+                plan.wave_slots[best] += is_grad ? 2 : (int32_t)gossip_slots;
+                if (is_grad) plan.last_grad_level[best] = sub_index;
+            }
+        // does every wave's programme take the (sub-)level, and still an end slot after it?
+        bool full = false;
+        for (int w = 0; w < W && !full; ++w) {
+            size_t at = plan.programme[(size_t)w].size();
+            const size_t need = 1 + (size_t)plan.wave_slots[w];
+            if ((at & 63) + need > 63) at = (at + 64) & ~(size_t)63;      // a jump slot, then the next set
+            if (at + need + 1 > n_slots) full = true;
+        }
+        if (full) break;
+        // per wave: control slot, gossip operations, gradient operations; never across a set of 64 slots
+        for (int w = 0; w < W; ++w) {
+            auto &prog = plan.programme[(size_t)w];
+            const size_t need = 1 + (size_t)plan.wave_slots[w];
+            if ((prog.size() & 63) + need > 63) {
+                ResSlot jump = blank;
+                jump.x = kResJump;
+                prog.push_back(jump);
+                ResSlot pad = blank;
+                pad.x = kResEnd;
+                while (prog.size() & 63) prog.push_back(pad);
+            }
+            ResSlot ctl = blank;
+            ctl.y = kResNone;
+            const size_t ctl_at = prog.size();
+            prog.push_back(ctl);
+            uint32_t n_gos_w = 0, n_grad_w = 0;
+            for (int pass = 0; pass < 2; ++pass)
+                for (int64_t q = sub; q < end; ++q) {
+                    if (plan.wave_of[(size_t)(q - sub)] != w) continue;
+                    const a2cid_op &op = batch->ops[q];
+                    const a2cid_coef &cf = coef[q];
+                    const bool is_grad = op.kind == A2CID_KIND_GRADIENT;
+                    if (is_grad != (pass == 1)) continue;
+                    const int32_t row_i = op.i, row_j = is_grad ? op.i : op.j;
+                    if (plan.slot_of[row_i] < 0) { plan.slot_of[row_i] = (int32_t)plan.rows.size(); plan.rows.push_back(row_i); }
+                    if (plan.slot_of[row_j] < 0) { plan.slot_of[row_j] = (int32_t)plan.rows.size(); plan.rows.push_back(row_j); }
+                    ResSlot r = blank;
+                    r.x = (uint32_t)plan.slot_of[row_i] * row_bytes;
+                    if (!is_grad) {
+                        r.y = (uint32_t)plan.slot_of[row_j] * row_bytes;
+                        r.z = f2u(cf.b_pre_i); r.w = f2u(cf.b_pre_j);
+                        prog.push_back(r);
+                        if (trailing) {
+                            ResSlot r2 = blank;
+                            r2.x = f2u(cf.b_post_i); r2.y = f2u(cf.b_post_j);
+                            prog.push_back(r2);
+                        }
+                        ++n_gos_w;
+                    } else {
+                        r.y = f2u(cf.b_pre_i); r.z = f2u(op.gamma); r.w = f2u(op.gscale);
+                        const uint32_t ordinal = (uint32_t)plan.grad_op.size();
+                        const uintptr_t xi = op.xi ? (uintptr_t)op.xi : kResZeros;
+                        plan.n_xi += op.xi != nullptr;
+                        plan.n_c += op.c && op.gscale != 0.f;
+                        plan.n_h += op.h && op.gscale != 0.f;
+                        // the slot that names this event: the second slot of the wave's previous gradient
+                        // operation, or the first slot of its programme
+                        if (plan.last_grad_slot[w] < 0) {
+                            prog[0].y = ordinal;
+                            prog[0].z = (uint32_t)(xi & 0xffffffffu);
+                            prog[0].w = (uint32_t)((uint64_t)xi >> 32);
+                        } else {
+                            ResSlot &from = prog[(size_t)plan.last_grad_slot[w]];
+                            from.x = ordinal;
+                            from.z = (uint32_t)(xi & 0xffffffffu);
+                            from.w = (uint32_t)((uint64_t)xi >> 32);
+                        }
+                        prog.push_back(r);
+                        ResSlot r2 = blank;
+                        r2.x = kResNone;
+                        r2.y = f2u(cf.b_post_i);
+                        plan.last_grad_slot[w] = (int64_t)prog.size();
+                        prog.push_back(r2);
+                        plan.grad_op.push_back(q);
+                        ++n_grad_w;
+                    }
+                }
+            prog[ctl_at].x = n_gos_w | n_grad_w << 8;
+        }
+        ++sub_index;
+        *k = end;
+    }
+    ResSlot end_slot = blank;
+    end_slot.x = kResEnd;
+    end_slot.y = kResNone;                      // also a valid first slot of an empty programme
+    for (auto &prog : plan.programme) {
+        prog.push_back(end_slot);
+        prog.resize(n_slots, end_slot);
+    }
+}
+
 }  // namespace a2cid
 
 extern "C" {
@@ -702,6 +853,56 @@ int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t lds_slot
                 return fail(A2CID_EINVAL, "%zu steps do not fit into %lld entries", plan.steps.size(), (long long)capacity);
             std::copy(plan.steps.begin(), plan.steps.end(), steps);
         }
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
+int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int32_t *waves, int32_t *cols,
+                        int64_t first_op, a2cid_resident_slot *slots, int32_t *rows, int32_t *n_rows,
+                        int64_t *gradient_ops, int32_t *n_gradient_ops, int64_t *next_op) {
+    clear_error();
+    if (n < 1 || n > A2CID_MAX_WORKERS) return fail(A2CID_EINVAL, "n = %d out of range", n);
+    if (!batch || batch->n_ops < 0 || (batch->n_ops > 0 && (!batch->ops || !batch->level_off)) || batch->n_levels < 0)
+        return fail(A2CID_EINVAL, "batch is NULL or malformed");
+    if (!coef || !waves || !cols || !slots || !rows || !n_rows || !gradient_ops || !n_gradient_ops || !next_op)
+        return fail(A2CID_EINVAL, "an output or coef is NULL");
+    if (first_op < 0 || first_op > batch->n_ops) return fail(A2CID_EINVAL, "first_op out of range");
+    for (int64_t k = 0; k < batch->n_ops; ++k) {
+        const a2cid_op &o = batch->ops[k];
+        const bool gossip = o.kind == A2CID_KIND_GOSSIP;
+        if ((!gossip && o.kind != A2CID_KIND_GRADIENT) || o.i < 0 || o.i >= n || (gossip && (o.j < 0 || o.j >= n || o.j == o.i)))
+            return fail(A2CID_EINVAL, "op %lld: bad kind or worker index", (long long)k);
+    }
+    int64_t at = 0;
+    for (int32_t l = 0; l < batch->n_levels; ++l) {
+        if (batch->level_off[l] != at || batch->level_off[l + 1] < at) return fail(A2CID_EMATCHING, "level table is not ascending");
+        at = batch->level_off[l + 1];
+    }
+    if (at != batch->n_ops) return fail(A2CID_EMATCHING, "level table does not cover the operations");
+    int w = *waves, c = *cols;
+    if (w == 0) resident_shape(n, batch, &w, &c);
+    if (w != 1 && w != 2 && w != 4 && w != 8 && w != 16) return fail(A2CID_EINVAL, "waves must be 0, 1, 2, 4, 8 or 16");
+    if (c != 1 && c != 2 && c != 4) return fail(A2CID_EINVAL, "cols must be 1, 2 or 4");
+    try {
+        bool trailing = false;
+        for (int64_t k = 0; k < batch->n_ops && !trailing; ++k) trailing = coef[k].b_post_i != 0.f || coef[k].b_post_j != 0.f;
+        int32_t l = 0;
+        while (l < batch->n_levels && batch->level_off[l + 1] <= first_op) ++l;
+        int64_t k = first_op;
+        ResidentPlan plan;
+        plan_resident(n, batch, coef, w, c, trailing, &l, &k, plan);
+        const size_t per_wave = (size_t)resident_slots(w);
+        for (int q = 0; q < w; ++q)
+            std::memcpy(slots + (size_t)q * per_wave, plan.programme[(size_t)q].data(), per_wave * sizeof(ResSlot));
+        std::copy(plan.rows.begin(), plan.rows.end(), rows);
+        *n_rows = (int32_t)plan.rows.size();
+        std::copy(plan.grad_op.begin(), plan.grad_op.end(), gradient_ops);
+        *n_gradient_ops = (int32_t)plan.grad_op.size();
+        *next_op = k;
+        *waves = w;
+        *cols = c;
     } catch (const std::bad_alloc &) {
         return fail(A2CID_ENOMEM, "out of host memory");
     }

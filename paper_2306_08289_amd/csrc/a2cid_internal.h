@@ -79,4 +79,54 @@ constexpr int32_t kChainMaxSlots = 16;
 // ops[0 .. count) must hold valid worker indices (0 <= i, j < n, i != j for gossip); 0 <= lds_slots <= kChainMaxSlots.
 void plan_chain(int32_t n, const a2cid_op *ops, int64_t count, int32_t lds_slots, ChainPlan &plan);
 
+// ---- The resident kernel's programme for one launch (planner: a2cid_host.cpp, kernel: a2cid_kernels.hip.h) ----
+// W waves share a tile of 64 * C columns that stays in LDS for the whole launch.  Each wave runs its own linear
+// programme of 16-byte slots, typed by position:
+//   control:   x = gossip operations | gradient operations << 8 that follow (a level: every wave passes a workgroup
+//              barrier first), or kResJump (continue with the next set of 64 slots), or kResEnd; in the first slot of
+//              a programme also y = ordinal of the wave's first gradient event (kResNone: it has none), z/w = that
+//              event's xi
+//   gossip:    x = LDS byte offset of row i, y = of row j, z = b_i, w = b_j (fp32 bits); with trailing mixes a second
+//              slot follows: x = bp_i, y = bp_j
+//   gradient:  two slots: x = LDS byte offset of the row, y = b_i, z = gamma, w = gscale; then x = ordinal of the
+//              wave's next gradient event or kResNone, y = bp_i, z/w = xi of that next event (low, high word)
+// A gradient input is a device pointer to the row, or an odd value, which is no pointer but stands for a constant
+// row: 1 for zeros, 3 for ones.  Every wave's programme has the same number of level slots, a level never straddles
+// a set of 64 slots, and a programme has at most resident_slots(W) slots including its end slot.
+struct ResSlot { uint32_t x, y, z, w; };
+static_assert(sizeof(ResSlot) == 16 && sizeof(ResSlot) == sizeof(a2cid_resident_slot), "ResSlot layout");
+struct GradIn { uintptr_t xi, c, h; };
+enum : uint32_t { kResJump = 0x10000u, kResEnd = 0x20000u };
+constexpr uint32_t kResNone = 0xffffffffu;
+constexpr uintptr_t kResZeros = 1u, kResOnes = 3u;
+constexpr int kResSetMax = 62;           // operation slots of one wave between two control slots
+// Slots of one wave's programme: sets of 64, one slot per lane and set.  Four sets (16 registers) when 16 waves share
+// the operations of a level, eight otherwise (a wave then has twice the operations, and registers to spare).
+constexpr int resident_sets(int waves) { return waves >= 16 ? 4 : 8; }
+constexpr int resident_slots(int waves) { return 64 * resident_sets(waves); }
+constexpr size_t resident_lds_bytes(int cols, int n_rows) { return (size_t)n_rows * 64 * 8 * (size_t)cols; }
+constexpr uint32_t resident_row_bytes(int cols) { return 64u * 8u * (uint32_t)cols; }
+constexpr int32_t kResidentMaxRows = 320;    // 512 bytes of the 160 KiB of LDS per row and column-per-lane
+
+struct ResidentPlan {
+    std::vector<std::vector<ResSlot>> programme;    // per wave
+    std::vector<int32_t> rows;                      // LDS row -> worker, in order of first use
+    std::vector<int64_t> grad_op;                   // gradient ordinal -> index of the event in the batch
+    int32_t n_xi = 0, n_c = 0, n_h = 0;             // gradient inputs the launch reads
+    // work arrays
+    std::vector<int32_t> slot_of;                   // per worker: its LDS row or -1
+    std::vector<int64_t> last_grad_slot;            // per wave: index of the second slot of its latest gradient operation
+    std::vector<int32_t> last_grad_level;           // per wave: (sub-)level of its latest gradient event
+    std::vector<int32_t> wave_load, wave_slots;     // per wave: operations / slots dealt to it in the current (sub-)level
+    std::vector<int32_t> wave_of;                   // per operation of the current (sub-)level: its wave
+};
+// Launch shape for a batch: waves per tile = the smallest power of two (2 ... 16) with at most 1.6 operations of an
+// average level per wave; columns per lane = as many (4, 2, 1) as still let 32 / waves workgroups share a CU's LDS.
+void resident_shape(int32_t n, const a2cid_event_batch *batch, int *waves, int *cols);
+// Writes the programmes of one launch: the operations of the batch from *k on (which lies in level *l), as many whole
+// (sub-)levels as the programmes hold.  On return *l, *k name the first operation not included.  coef: the batch's
+// coefficients (plan_batch); trailing: gossip operations take two slots.  The batch must be valid (plan_batch passed).
+void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int waves, int cols,
+                   bool trailing, int32_t *l, int64_t *k, ResidentPlan &plan);
+
 }  // namespace a2cid

@@ -459,10 +459,6 @@ __global__ __launch_bounds__(TPB) void chain_kernel(float *__restrict__ x, float
     }
 }
 
-// Gradient inputs of a launch's gradient events, in order: device pointers to the row (column k at pointer + k), or an
-// odd value, which is no pointer but stands for a constant row: 1 for zeros, 3 for ones.
-struct GradIn { uintptr_t xi, c, h; };
-
 typedef const __attribute__((address_space(1))) float *global_f32;
 
 __device__ __forceinline__ uint32_t lane_u32(uint32_t v, int l) { return (uint32_t)__builtin_amdgcn_readlane((int)v, l); }
@@ -537,26 +533,7 @@ __device__ __forceinline__ void store_cols(float *p, int64_t col, int64_t d, con
 // of the one-pass-per-event kernels: it is not bound by memory.
 // LDS: n_rows * 64 * 8 C bytes (C = 1: (x, xt) pairs; C = 2, 4: planes of 16-byte cells holding two columns).
 // ------------------------------------------------------------------------------------------
-enum : uint32_t { kResLevel = 1, kResJump = 2, kResEnd = 3 };
-constexpr uint32_t kResNone = 0xffffffffu;
-// Slots of one wave's programme: sets of 64, one slot per lane and set.  Four sets (16 registers) when 16 waves share
-// the operations of a level, eight otherwise (a wave then has twice the operations, and registers to spare).
-constexpr int resident_sets(int waves) { return waves >= 16 ? 4 : 8; }
-constexpr int resident_slots(int waves) { return 64 * resident_sets(waves); }
-constexpr int kResSetMax = 62;            // operation slots of one wave between two control slots
-
-// control:   x = kRes* | gossip operations << 8 | gradient operations << 16; in the first slot of a programme also
-//            y = ordinal of the wave's first gradient event (kResNone: it has none), z/w = that event's xi
-// gossip:    x = LDS offset of row i, y = of row j, z = b_i, w = b_j; with trailing mixes (TRAIL) a second slot
-//            follows: x = bp_i, y = bp_j
-// gradient:  two slots: x = LDS offset of the row, y = b_i, z = gamma, w = gscale; then x = ordinal of the wave's
-//            next gradient event or kResNone, y = bp_i, z/w = xi of that next event (low, high; an odd value is no
-//            pointer but stands for a constant row: 1 for zeros, 3 for ones; so are c and h in the gin table)
-struct ResSlot { uint32_t x, y, z, w; };
-static_assert(sizeof(ResSlot) == 16, "ResSlot layout");
-
-constexpr size_t resident_lds_bytes(int cols, int n_rows) { return (size_t)n_rows * 64 * 8 * (size_t)cols; }
-constexpr uint32_t resident_row_bytes(int cols) { return 64u * 8u * (uint32_t)cols; }
+// Slot layout, control codes and sizes: a2cid_internal.h (shared with the planner).
 
 typedef float v2f __attribute__((ext_vector_type(2)));
 
@@ -682,6 +659,10 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
             if (s < n_rows) res_put<C>(lds, (uint32_t)s * kRow + lane_off, a[q], at[q]);
         }
     }
+    // Every load issued so far (programme, rows, first gradient inputs) is waited for here, once: the compiler then
+    // knows that no register has a load pending when the operation loops begin, and puts no wait for vector
+    // memory into them except where requested gradient inputs are used (s_waitcnt vmcnt(0) expcnt(7) lgkmcnt(15)).
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     // no barrier here: every programme starts with a level slot, which brings one
 
     // The slots of one set, from its first to a jump slot (returns false) or to the end of the programme (true).
@@ -689,12 +670,40 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
         int32_t pos = 0;                                 // lane that holds the next slot
         for (;;) {
             const uint32_t w0 = lane_u32(r.x, pos);
-            const uint32_t kind = w0 & 7u;
-            if (kind != kResLevel) return kind != kResJump;
-            const int32_t n_gossip = (int32_t)((w0 >> 8) & 255u), n_grad = (int32_t)((w0 >> 16) & 255u);
+            if (w0 >= kResJump) return w0 != kResJump;
+            const int32_t n_gossip = (int32_t)(w0 & 255u), n_grad = (int32_t)(w0 >> 8);
             ++pos;
             __syncthreads();                             // the previous level is complete in LDS
-            for (int32_t t = 0; t < n_gossip; ++t, pos += TRAIL ? 2 : 1) {
+            int32_t t = 0;
+            if constexpr (C == 1) {
+                // two operations of the level at a time (they touch disjoint rows): one LDS round trip for both
+                constexpr int kStep = TRAIL ? 2 : 1;
+                for (; t + 2 <= n_gossip; t += 2, pos += 2 * kStep) {
+                    const int32_t p2 = pos + kStep;
+                    const uint32_t oi = lane_u32(r.x, pos) + lane_off, oj = lane_u32(r.y, pos) + lane_off;
+                    const uint32_t oi2 = lane_u32(r.x, p2) + lane_off, oj2 = lane_u32(r.y, p2) + lane_off;
+                    v2f a = *(const v2f *)(lds + oi), b = *(const v2f *)(lds + oj);
+                    v2f a2 = *(const v2f *)(lds + oi2), b2 = *(const v2f *)(lds + oj2);
+                    OpCoef oc, oc2;
+                    oc.b_i = lane_f32(r.z, pos); oc.b_j = lane_f32(r.w, pos);
+                    oc.bp_i = TRAIL ? lane_f32(r.x, pos + 1) : 0.f;
+                    oc.bp_j = TRAIL ? lane_f32(r.y, pos + 1) : 0.f;
+                    oc2.b_i = lane_f32(r.z, p2); oc2.b_j = lane_f32(r.w, p2);
+                    oc2.bp_i = TRAIL ? lane_f32(r.x, p2 + 1) : 0.f;
+                    oc2.bp_j = TRAIL ? lane_f32(r.y, p2 + 1) : 0.f;
+                    float xi_ = a.x, xti = a.y, xj = b.x, xtj = b.y;
+                    float xi2 = a2.x, xti2 = a2.y, xj2 = b2.x, xtj2 = b2.y;
+                    gossip_jump<TRAIL>(xi_, xti, xj, xtj, oc, alpha, alpha_t, PRE);
+                    gossip_jump<TRAIL>(xi2, xti2, xj2, xtj2, oc2, alpha, alpha_t, PRE);
+                    a.x = xi_; a.y = xti; b.x = xj; b.y = xtj;
+                    a2.x = xi2; a2.y = xti2; b2.x = xj2; b2.y = xtj2;
+                    *(v2f *)(lds + oi) = a;
+                    *(v2f *)(lds + oj) = b;
+                    *(v2f *)(lds + oi2) = a2;
+                    *(v2f *)(lds + oj2) = b2;
+                }
+            }
+            for (; t < n_gossip; ++t, pos += TRAIL ? 2 : 1) {
                 const uint32_t oi = lane_u32(r.x, pos) + lane_off, oj = lane_u32(r.y, pos) + lane_off;
                 OpCoef oc;
                 oc.b_i = lane_f32(r.z, pos); oc.b_j = lane_f32(r.w, pos);
@@ -759,7 +768,7 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
                 const uint32_t next = lane_u32(r.x, pos + 1);
                 if (next != kResNone)
                     res_request<C, HC, HH>(gx, gc, gh, lane_u32(r.z, pos + 1), lane_u32(r.w, pos + 1), gin, next, col0,
-                                          lane_c, d, whole);
+                                           lane_c, d, whole);
             }
         }
     };

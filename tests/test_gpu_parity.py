@@ -357,6 +357,8 @@ def test_observables_at_full_size_against_library_reductions():
     ("C2", 9001, 3000, 1024, 16, 4), ("C2", 1027, 3000, 1000, 8, 4), ("C1", 3, 500, 100, 16, 2),
     ("C3", 2 * 128 * 3 + 1, 3000, 1024, 16, 2), ("C5", 4099, 3000, 1024, 16, 1), ("C2", 777, 2000, 600, 2, 4),
     ("C2", 1234, 2000, 4096, 4, 4), ("C1", 130, 2000, 1000, 2, 2),
+    # one or two waves per tile on 64 workers: programmes overflow into further launches, wide levels come in parts
+    ("C5", 1000, 3000, 2048, 1, 1), ("C3", 1500, 3000, 2048, 2, 2),
     # group 0: the library chooses the shape for every batch
     ("C1", 1000, 3000, 512, 0, 1), ("C2", 5003, 3000, 1000, 0, 1), ("C3", 9001, 3000, 1024, 0, 1),
     ("C4", 12345, 3000, 1024, 0, 1), ("C5", 8191, 3000, 4096, 0, 1)])
@@ -463,7 +465,8 @@ def _custom_workload(n, topology, d, seed=0xA2C1D2 + 77, **kw):
 @pytest.mark.parametrize("n,topology,d,events,mode", [(2, "ring", 4099, 400, 1), (2, "ring", 5, 400, 2),
                                                       (1024, "ring", 261, 6000, 1), (1024, "ring", 133, 4000, 0),
                                                       (112, "exponential", 700, 3000, 2), (2, "ring", 1031, 400, 3),
-                                                      (1024, "ring", 259, 6000, 3)])
+                                                      (1024, "ring", 259, 6000, 3), (320, "ring", 200, 5000, 2),
+                                                      (128, "complete", 515, 4000, 2)])
 def test_extreme_worker_counts(n, topology, d, events, mode):
     # explicit eta, alpha_tilde: Proposition 3.2 gives alpha_tilde = 115 on a ring of 1024, where fp32 cancellation in
     # xt (terms of +-100 summing to O(1)) alone exceeds 1e-5 -- a property of fp32 state, not of the kernels

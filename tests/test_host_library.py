@@ -436,3 +436,248 @@ def test_chain_programme_on_arbitrary_small_batches():
         assert _run_chain_programme(n, ops, steps, slots) == per_col
 
     check()
+
+
+# ---- the resident kernel's programmes ---------------------------------------------------------------------------
+
+def _f32_bits(v):
+    return int(np.float32(v).view(np.uint32))
+
+
+def _run_resident_launch(n, batch, coef, plan, first_op, trailing):
+    """Walks the W programmes of one launch the way the kernel does and checks them against the batch: returns the
+    set of operations the launch applies.  Levels are executed in lock step (every wave passes the same number of
+    barriers); within a level the rows touched by all waves must be disjoint; per worker the operations must come
+    in batch order; every operation carries its own rows, coefficients and inputs; a gradient operation's inputs are
+    the ones its wave was told to request by its previous gradient operation (or by its first slot)."""
+    W, cols, slots = plan["waves"], plan["cols"], plan["slots"]
+    per_wave = slots.shape[1]
+    assert per_wave == (256 if W >= 16 else 512)
+    row_bytes = 512 * cols
+    rows = [int(r) for r in plan["rows"]]
+    assert len(set(rows)) == len(rows) and all(0 <= r < n for r in rows)
+    ops = batch.ops
+    level_of = np.zeros(len(ops), np.int64)
+    for l in range(len(batch.level_off) - 1):
+        level_of[batch.level_off[l]:batch.level_off[l + 1]] = l
+    gops = [int(g) for g in plan["gradient_ops"]]
+    # per wave: list of levels, each a list of (kind, op index)
+    per_wave_levels, requested = [], []
+    applied = {}
+    for w in range(W):
+        prog = slots[w]
+        pos, levels = 0, []
+        first = prog[0]
+        pending = None                                      # (ordinal, xi) the wave has been told to request
+        if first["x"] < binding.RES_JUMP or first["x"] == binding.RES_END:
+            if first["y"] != binding.RES_NONE:
+                pending = (int(first["y"]), int(first["z"]) | int(first["w"]) << 32)
+        seen_end = False
+        while not seen_end:
+            ctl = int(prog[pos]["x"])
+            if ctl == binding.RES_END:
+                seen_end = True
+                break
+            if ctl == binding.RES_JUMP:
+                pos = (pos // 64 + 1) * 64                  # the next set
+                assert pos < per_wave
+                continue
+            assert ctl < binding.RES_JUMP
+            n_gos, n_grad = ctl & 255, ctl >> 8
+            need = 1 + n_gos * (2 if trailing else 1) + 2 * n_grad
+            assert pos % 64 + need <= 63, "a level straddles a set (or leaves no room for the next control slot)"
+            pos += 1
+            this = []
+            for _ in range(n_gos):
+                sl = prog[pos]
+                ri, rj = int(sl["x"]), int(sl["y"])
+                assert ri % row_bytes == 0 and rj % row_bytes == 0
+                wi, wj = rows[ri // row_bytes], rows[rj // row_bytes]
+                this.append(("gossip", wi, wj, int(sl["z"]), int(sl["w"]),
+                             (int(prog[pos + 1]["x"]), int(prog[pos + 1]["y"])) if trailing else (0, 0)))
+                pos += 2 if trailing else 1
+            for _ in range(n_grad):
+                sl, sl2 = prog[pos], prog[pos + 1]
+                ri = int(sl["x"])
+                assert ri % row_bytes == 0
+                assert pending is not None, "a gradient operation whose inputs nobody requested"
+                this.append(("gradient", rows[ri // row_bytes], pending, int(sl["y"]), int(sl["z"]), int(sl["w"]), int(sl2["y"])))
+                pending = None if sl2["x"] == binding.RES_NONE else (int(sl2["x"]), int(sl2["z"]) | int(sl2["w"]) << 32)
+                pos += 2
+            levels.append(this)
+        assert pending is None, "a requested gradient input that no operation uses"
+        per_wave_levels.append(levels)
+    n_levels = len(per_wave_levels[0])
+    assert all(len(lv) == n_levels for lv in per_wave_levels), "waves pass different numbers of barriers"
+    last_op_of_worker = {}
+    # which operation is it?  match by (workers, level order): walk the batch from first_op in order per worker
+    next_of_worker = {}
+    for k in range(first_op, len(ops)):
+        for wkr in ([int(ops["i"][k]), int(ops["j"][k])] if ops["kind"][k] == binding.KIND_GOSSIP else [int(ops["i"][k])]):
+            next_of_worker.setdefault(wkr, []).append(k)
+    cursor = {wkr: 0 for wkr in next_of_worker}
+    for l in range(n_levels):
+        touched = set()
+        for w in range(W):
+            for rec in per_wave_levels[w][l]:
+                ws = [rec[1], rec[2]] if rec[0] == "gossip" else [rec[1]]
+                assert not (touched & set(ws)), "two operations of a level share a worker"
+                touched |= set(ws)
+                # the operation must be the next one of each of its workers
+                ks = {next_of_worker[wkr][cursor[wkr]] for wkr in ws}
+                assert len(ks) == 1, ("not the next operation of both workers", rec)
+                k = ks.pop()
+                for wkr in ws:
+                    cursor[wkr] += 1
+                assert k not in applied
+                applied[k] = (l, w)
+                op, cf = ops[k], coef[k]
+                if rec[0] == "gossip":
+                    assert op["kind"] == binding.KIND_GOSSIP and (rec[1], rec[2]) == (int(op["i"]), int(op["j"]))
+                    assert (rec[3], rec[4]) == (_f32_bits(cf["b_pre_i"]), _f32_bits(cf["b_pre_j"]))
+                    if trailing:
+                        assert rec[5] == (_f32_bits(cf["b_post_i"]), _f32_bits(cf["b_post_j"]))
+                else:
+                    assert op["kind"] == binding.KIND_GRADIENT and rec[1] == int(op["i"])
+                    ordinal, xi = rec[2]
+                    assert gops[ordinal] == k, "the requested inputs belong to another event"
+                    assert xi == (int(op["xi"]) if op["xi"] else 1)
+                    assert (rec[3], rec[4], rec[5]) == (_f32_bits(cf["b_pre_i"]), _f32_bits(op["gamma"]), _f32_bits(op["gscale"]))
+                    if trailing:
+                        assert rec[6] == _f32_bits(cf["b_post_i"])
+    ks = sorted(applied)
+    assert ks == list(range(first_op, plan["next_op"])), "the launch must apply a contiguous range of the batch"
+    assert sorted(set(rows)) == sorted({int(x) for k in ks for x in
+                                        ([ops["i"][k], ops["j"][k]] if ops["kind"][k] == binding.KIND_GOSSIP else [ops["i"][k]])})
+    assert sorted(gops) == [k for k in ks if ops["kind"][k] == binding.KIND_GRADIENT]
+    return ks
+
+
+def _resident_plans_cover(n, batch, coef, waves, cols):
+    trailing = bool(((coef["b_post_i"] != 0) | (coef["b_post_j"] != 0)).any())
+    k, launches = 0, 0
+    while k < len(batch.ops):
+        plan = binding.a2cid_plan_resident(n, batch, coef, first_op=k, waves=waves, cols=cols)
+        ks = _run_resident_launch(n, batch, coef, plan, k, trailing)
+        assert ks and plan["next_op"] > k
+        k = plan["next_op"]
+        launches += 1
+    return launches
+
+
+@pytest.mark.parametrize("topo,n,edge_rate", [("ring", 64, 2.0), ("exponential", 64, 1.0), ("complete", 64, 0.56),
+                                              ("ring", 16, 1.0), ("complete", 4, 1.0), ("ring", 320, 1.0)])
+@pytest.mark.parametrize("waves,cols", [(0, 1), (1, 1), (2, 4), (8, 1), (16, 2)])
+def test_resident_programmes_on_scheduler_batches(topo, n, edge_rate, waves, cols):
+    edges = getattr(graph, topo)(n)
+    u, v = _uv(edges)
+    s = binding.Scheduler(n, u, v, edge_rate, 1.0, 5)
+    t = np.zeros(n)
+    for size, sync in ((1, False), (300, False), (4096, False), (1024, True)):   # a trailing mix only in the last one
+        b = s.next(size)
+        b.ops["gamma"], b.ops["gscale"] = 0.1, 1.0
+        grad = b.ops["kind"] == binding.KIND_GRADIENT
+        b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))        # distinct, 16-byte aligned stand-ins
+        if sync:
+            b.t_sync = float(b.ops["t"].max()) + 0.5
+        t, coef = binding.a2cid_plan_batch(n, u, v, edge_rate, 0.7, t, b)
+        launches = _resident_plans_cover(n, b, coef, waves, cols)
+        if size <= 300:
+            assert launches <= 2
+    s.close()
+
+
+def test_resident_shape_follows_the_operations_per_level():
+    for topo, n, rate, want in (("ring", 64, 2.0, (16, 2)), ("exponential", 64, 1.0, (8, 1)), ("ring", 16, 1.0, (4, 2))):
+        u, v = _uv(getattr(graph, topo)(n))
+        s = binding.Scheduler(n, u, v, rate, 1.0, 5)
+        b = s.next(1024)
+        _, coef = binding.a2cid_plan_batch(n, u, v, rate, 0.5, np.zeros(n), b)
+        plan = binding.a2cid_plan_resident(n, b, coef)
+        assert (plan["waves"], plan["cols"]) == want
+        s.close()
+
+
+def test_resident_programme_of_wide_levels_is_cut_into_parts():
+    """A level with more operations than a wave may hold between two control slots (31) is applied in parts."""
+    n = 320
+    ops = np.zeros(160, binding.OP_DTYPE)
+    ops["kind"], ops["i"], ops["j"] = binding.KIND_GOSSIP, 2 * np.arange(160), 2 * np.arange(160) + 1
+    ops["t"] = 1.0
+    b = binding.Batch(ops, [0, 160])
+    u, v = list(range(0, 320, 2)), list(range(1, 320, 2))
+    _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.5, np.zeros(n), b)
+    for waves in (1, 2, 16):
+        plan = binding.a2cid_plan_resident(n, b, coef, waves=waves, cols=1)
+        assert _run_resident_launch(n, b, coef, plan, 0, False) == list(range(160))
+        prog, pos, levels = plan["slots"][0], 0, 0
+        while prog[pos]["x"] != binding.RES_END:
+            ctl = int(prog[pos]["x"])
+            if ctl == binding.RES_JUMP:
+                pos = (pos // 64 + 1) * 64
+            else:
+                levels += 1
+                pos += 1 + (ctl & 255) + 2 * (ctl >> 8)
+        assert levels == -(-160 // (31 * waves))
+
+
+def test_resident_planner_rejects_malformed_input():
+    ops = _random_ops(np.random.default_rng(0), 4, 20, 0.3)
+    coef = np.zeros(20, binding.COEF_DTYPE)
+    good = binding.Batch(ops, [0, 20])
+    for kwargs in ({"waves": 3}, {"waves": 8, "cols": 3}, {"first_op": 21}, {"first_op": -1}):
+        with pytest.raises(a2.A2cidError):
+            binding.a2cid_plan_resident(4, good, coef, **kwargs)
+    bad = ops.copy()
+    bad["i"][5] = 4
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_plan_resident(4, binding.Batch(bad, [0, 20]), coef)
+
+
+def test_resident_programme_checker_notices_planted_mistakes():
+    """The checker above is only worth something if a wrong programme fails it."""
+    n = 16
+    u, v = _uv(graph.ring(n))
+    s = binding.Scheduler(n, u, v, 1.0, 1.0, 3)
+    b = s.next(400)
+    b.ops["gamma"], b.ops["gscale"] = 0.1, 1.0
+    grad = b.ops["kind"] == binding.KIND_GRADIENT
+    b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))
+    _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
+    good = binding.a2cid_plan_resident(n, b, coef, waves=4, cols=2)
+    _run_resident_launch(n, b, coef, good, 0, False)
+
+    def first_slot(kind_wanted):
+        """(wave, position) of the first gossip / gradient operation slot of wave 1's programme."""
+        prog, pos = good["slots"][1], 0
+        while True:
+            ctl = int(prog[pos]["x"])
+            assert ctl != binding.RES_END
+            if ctl == binding.RES_JUMP:
+                pos = (pos // 64 + 1) * 64
+                continue
+            n_gos, n_grad = ctl & 255, ctl >> 8
+            if kind_wanted == "gossip" and n_gos:
+                return pos + 1
+            if kind_wanted == "gradient" and n_grad:
+                return pos + 1 + n_gos
+            pos += 1 + n_gos + 2 * n_grad
+
+    def mutated(change):
+        plan = dict(good)
+        plan["slots"] = good["slots"].copy()
+        change(plan["slots"])
+        return plan
+
+    g, d = first_slot("gossip"), first_slot("gradient")
+    mistakes = {
+        "wrong row": lambda sl: sl[1].__setitem__(g, (sl[1][g]["x"], sl[1][g]["x"] ^ 1024, sl[1][g]["z"], sl[1][g]["w"])),
+        "wrong coefficient": lambda sl: sl[1].__setitem__(g, (sl[1][g]["x"], sl[1][g]["y"], sl[1][g]["z"] ^ 1, sl[1][g]["w"])),
+        "wrong step size": lambda sl: sl[1].__setitem__(d, (sl[1][d]["x"], sl[1][d]["y"], sl[1][d]["z"] ^ 1, sl[1][d]["w"])),
+        "wrong next input": lambda sl: sl[1].__setitem__(d + 1, (sl[1][d + 1]["x"] ^ 1, sl[1][d + 1]["y"], sl[1][d + 1]["z"], sl[1][d + 1]["w"])),
+        "missing barrier": lambda sl: sl[2].__setitem__(0, (binding.RES_END, sl[2][0]["y"], 0, 0)),
+    }
+    for what, change in mistakes.items():
+        with pytest.raises((AssertionError, IndexError, KeyError)):
+            _run_resident_launch(n, b, coef, mutated(change), 0, False)
+    s.close()
