@@ -34,15 +34,15 @@ HBM_PEAK_GBS = 8000.0     # MI355X published HBM3E bandwidth
 # figure comes from.  Only valid for the workload, batch size, kernel and launch shape it names.  The counters sit
 # between the L2 and the fabric: bytes served by the 256 MB last-level cache behind it count as traffic here.
 MEASURED_TRAFFIC = {
-    ("C4", 1024, "walk_kernel"): (7.9189e11, "profiles/bench_C4_hbm_counters.md"),
-    ("C4", 1024, "chain_kernel"): (3.2501e11, "profiles/bench_C4_hbm_counters.md"),
-    ("C4", 1024, "resident_kernel"): (2.9906e10, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "walk_kernel"): (7.9188e11, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "chain_kernel"): (3.2503e11, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "resident_kernel"): (4.2497e10, "profiles/bench_C4_hbm_counters.md"),
     ("C3", 1024, "walk_kernel"): (3.3678e11, "profiles/bench_C3_hbm_counters.md"),
-    ("C3", 1024, "chain_kernel"): (7.2097e10, "profiles/bench_C3_hbm_counters.md"),
-    ("C3", 1024, "resident_kernel"): (1.3529e10, "profiles/bench_C3_hbm_counters.md"),
-    ("C5", 1024, "walk_kernel"): (8.2851e11, "profiles/bench_C5_hbm_counters.md"),
-    ("C5", 1024, "chain_kernel"): (3.7700e11, "profiles/bench_C5_hbm_counters.md"),
-    ("C5", 1024, "resident_kernel"): (3.6357e10, "profiles/bench_C5_hbm_counters.md"),
+    ("C3", 1024, "chain_kernel"): (7.2107e10, "profiles/bench_C3_hbm_counters.md"),
+    ("C3", 1024, "resident_kernel"): (2.6875e10, "profiles/bench_C3_hbm_counters.md"),
+    ("C5", 1024, "walk_kernel"): (8.2850e11, "profiles/bench_C5_hbm_counters.md"),
+    ("C5", 1024, "chain_kernel"): (3.7701e11, "profiles/bench_C5_hbm_counters.md"),
+    ("C5", 1024, "resident_kernel"): (3.7909e10, "profiles/bench_C5_hbm_counters.md"),
 }
 
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
@@ -190,8 +190,8 @@ def main():
     ap.add_argument("--threads", type=int, default=None)
     ap.add_argument("--walk", type=int, default=None,
                     help="event kernel of the headline line: 1 = walk, one full pass per event (default: the kernel "
-                         "whose traffic is the algorithmic byte count), 3 = chain (the library's default), "
-                         "0 = one launch per level, 2 = LDS-resident")
+                         "whose traffic is the algorithmic byte count), 3 = chain, 0 = one launch per level, "
+                         "2 = LDS-resident (the library's choice for up to 112 workers)")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--walk-occupancy", type=int, default=None, help="walk kernel: at most this many workgroups per CU")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup (default: chosen per batch)")
