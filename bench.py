@@ -48,9 +48,9 @@ MEASURED_TRAFFIC = {
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
-             2: "resident_kernel (the library's choice for up to 112 workers): every touched row stays in LDS for the "
+             2: "resident_kernel (the library's choice for up to 160 workers): every touched row stays in LDS for the "
                 "whole batch (state read and written once per batch)",
-             3: "chain_kernel (the library's choice for more than 112 workers): events re-ordered so "
+             3: "chain_kernel (the library's choice for more than 160 workers): events re-ordered so "
                 "that a worker's columns are found in registers or parked in LDS as often as possible"}
 
 
@@ -191,7 +191,7 @@ def main():
     ap.add_argument("--walk", type=int, default=None,
                     help="event kernel of the headline line: 1 = walk, one full pass per event (default: the kernel "
                          "whose traffic is the algorithmic byte count), 3 = chain, 0 = one launch per level, "
-                         "2 = LDS-resident (the library's choice for up to 112 workers)")
+                         "2 = LDS-resident (the library's choice for up to 160 workers)")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--walk-occupancy", type=int, default=None, help="walk kernel: at most this many workgroups per CU")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup (default: chosen per batch)")
@@ -366,7 +366,7 @@ def main():
     variants = []
     if not args.no_chain_leg and mode != 3:
         variants.append((3, "chain_variant"))
-    if not args.no_resident_leg and mode != 2 and cfg.n <= 112:
+    if not args.no_resident_leg and mode != 2 and cfg.n <= 160:
         variants.append((2, "resident_variant"))
     for v_mode, key in variants:
         w.engine.set_tuning(1, 0, 256, v_mode)

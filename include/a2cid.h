@@ -348,7 +348,7 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
  * workgroup size (64 ... 1024, a power of two), mode =
- *  -1: chosen by the library from the shape (default): 2 for up to 112 workers; beyond that 1 for rows
+ *  -1: chosen by the library from the shape (default): 2 for up to 160 workers; beyond that 1 for rows
  *      of at most 4096 parameters and 3 for everything else;
  *   0: one launch per level;
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its

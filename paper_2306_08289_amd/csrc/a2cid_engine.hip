@@ -543,14 +543,16 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
     return A2CID_OK;
 }
 
-// The event kernel of the next batch when the choice is left to the library, from measurements on the five
-// configurations (events per second, 1024 events per batch): the LDS-resident kernel for up to 112 workers (4 workers:
-// 2.2 times, 16: 1.25 times, 64: 1.7 to 2.6 times the chain kernel) and for rows so short (at most 4096 parameters) that
-// every other kernel launches a handful of workgroups; beyond that the chain kernel, or, for short rows, the walk kernel
-// (it needs no programme from the host).  The resident kernel itself takes up to kResidentMaxRows workers (512 bytes
-// of LDS per row and column-per-lane).
+// The event kernel of the next batch when the choice is left to the library, from measurements (events per second,
+// 1024 events per batch).  The LDS-resident kernel for up to 160 workers, the most for which two workgroups share a CU's
+// LDS: on the five configurations it is 2.2 (4 workers), 1.3 (16) and 1.8 to 2.6 (64 workers) times the chain kernel;
+// with rows of 4 M parameters, ring / exponential graph: 96 workers 1.4, 112: 2.3, 128: 1.4 / 2.4, 160: 1.3 times; from
+// 192 workers on it depends on the graph (192 exponential 1.4, 256 ring 0.8, 256 exponential 1.4, 320 ring 0.8, 320
+// complete 1.5 times), so beyond 160 workers the chain kernel runs, or, for rows of at most 4096 parameters, the walk
+// kernel (it needs no programme from the host).  Asked for explicitly, the resident kernel takes up to kResidentMaxRows
+// workers.
 constexpr int64_t kShortRow = 4096;
-constexpr int32_t kResidentAutoRows = 112;
+constexpr int32_t kResidentAutoRows = 160;
 static int event_mode(const a2cid_ctx *c) {
     if (c->walk >= 0) return c->walk;
     if (c->n <= kResidentAutoRows) return 2;
