@@ -48,6 +48,12 @@ void a2o_mix_row(double *x, double *xt, int64_t d, double eta, double tau)
 }
 
 /* ------------------------------------------------------------------------- */
+/* Worker clocks (section "Practical implementation of the dynamic": time is     */
+/* normalised by a running average of the durations of the previous gradient    */
+/* steps, read per worker): rate_i is the speed of worker i's own clock against */
+/* the clock of the event times, so the mixing of worker i from its last event  */
+/* to te lasts rate_i * (te - t_i).  rate_i = 1 is the plain dynamic.           */
+/* ------------------------------------------------------------------------- */
 /* Gradient jump of Eq. (1) / gradient thread of Algorithm 1 for worker i at    */
 /* time te: mix to te, g = gscale * h .* (x_i - c) + xi, then the SAME          */
 /* gamma * g is subtracted from x_i and from xt_i.  This g is the gradient of   */
@@ -64,11 +70,11 @@ static double a2o_local_gradient(double x, int64_t k, double gscale,
     return g;
 }
 
-void a2o_gradient_event(double *x_i, double *xt_i, double *t_i, int64_t d,
+void a2o_gradient_event(double *x_i, double *xt_i, double *t_i, double rate_i, int64_t d,
                         double eta, double te, double gamma, double gscale,
                         const double *c, const double *xi, const double *h)
 {
-    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    a2o_mix_row(x_i, xt_i, d, eta, rate_i * (te - *t_i));
     *t_i = te;
     for (int64_t k = 0; k < d; ++k) {
         const double g = a2o_local_gradient(x_i[k], k, gscale, c, xi, h);
@@ -82,13 +88,13 @@ void a2o_gradient_event(double *x_i, double *xt_i, double *t_i, int64_t d,
 /* at time te: both workers mix to te, m = x_i - x_j from the mixed values,     */
 /* x_i -= alpha m, x_j += alpha m, xt_i -= alpha_t m, xt_j += alpha_t m.        */
 /* ------------------------------------------------------------------------- */
-void a2o_gossip_event(double *x_i, double *xt_i, double *t_i,
-                      double *x_j, double *xt_j, double *t_j, int64_t d,
+void a2o_gossip_event(double *x_i, double *xt_i, double *t_i, double rate_i,
+                      double *x_j, double *xt_j, double *t_j, double rate_j, int64_t d,
                       double eta, double te, double alpha, double alpha_t)
 {
-    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    a2o_mix_row(x_i, xt_i, d, eta, rate_i * (te - *t_i));
     *t_i = te;
-    a2o_mix_row(x_j, xt_j, d, eta, te - *t_j);
+    a2o_mix_row(x_j, xt_j, d, eta, rate_j * (te - *t_j));
     *t_j = te;
     for (int64_t k = 0; k < d; ++k) {
         const double m = x_i[k] - x_j[k];
@@ -106,13 +112,13 @@ void a2o_gossip_event(double *x_i, double *xt_i, double *t_i,
 /* a real system g takes a whole forward/backward pass and is stale in exactly   */
 /* this way.  Kept as a variant; the default reading is the one above.           */
 /* ------------------------------------------------------------------------- */
-void a2o_gradient_event_listing(double *x_i, double *xt_i, double *t_i, int64_t d,
+void a2o_gradient_event_listing(double *x_i, double *xt_i, double *t_i, double rate_i, int64_t d,
                                 double eta, double te, double gamma, double gscale,
                                 const double *c, const double *xi, const double *h)
 {
     double *g = (double *)malloc(sizeof(double) * (size_t)d);
     for (int64_t k = 0; k < d; ++k) g[k] = a2o_local_gradient(x_i[k], k, gscale, c, xi, h);
-    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    a2o_mix_row(x_i, xt_i, d, eta, rate_i * (te - *t_i));
     *t_i = te;
     for (int64_t k = 0; k < d; ++k) {
         x_i[k] -= gamma * g[k];
@@ -121,15 +127,15 @@ void a2o_gradient_event_listing(double *x_i, double *xt_i, double *t_i, int64_t 
     free(g);
 }
 
-void a2o_gossip_event_listing(double *x_i, double *xt_i, double *t_i,
-                              double *x_j, double *xt_j, double *t_j, int64_t d,
+void a2o_gossip_event_listing(double *x_i, double *xt_i, double *t_i, double rate_i,
+                              double *x_j, double *xt_j, double *t_j, double rate_j, int64_t d,
                               double eta, double te, double alpha, double alpha_t)
 {
     double *m = (double *)malloc(sizeof(double) * (size_t)d);
     for (int64_t k = 0; k < d; ++k) m[k] = x_i[k] - x_j[k];
-    a2o_mix_row(x_i, xt_i, d, eta, te - *t_i);
+    a2o_mix_row(x_i, xt_i, d, eta, rate_i * (te - *t_i));
     *t_i = te;
-    a2o_mix_row(x_j, xt_j, d, eta, te - *t_j);
+    a2o_mix_row(x_j, xt_j, d, eta, rate_j * (te - *t_j));
     *t_j = te;
     for (int64_t k = 0; k < d; ++k) {
         x_i[k] -= alpha * m[k];
@@ -147,6 +153,9 @@ void a2o_gossip_event_listing(double *x_i, double *xt_i, double *t_i,
 /* (or -1: none; the row arrays themselves may be NULL).                        */
 /* order 0: jumps evaluated after the mixing (Eq. (1)); order 1: Algorithm 1's    */
 /* listing order (see above).                                                   */
+/* rate (n entries, may be NULL: all 1): the speed of every worker's clock, read */
+/* and updated; speed[e] > 0 on a gradient event sets its worker's rate after   */
+/* the event (speed may be NULL).                                               */
 /* Returns 0, or -(e+1) for the first malformed event (nothing after it runs).  */
 /* ------------------------------------------------------------------------- */
 int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
@@ -156,25 +165,29 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
                          const double *gamma, const double *gscale,
                          const int64_t *xi_row, const double *xi,
                          const int64_t *c_row, const double *c,
-                         const int64_t *h_row, const double *h, int32_t order)
+                         const int64_t *h_row, const double *h, int32_t order,
+                         double *rate, const double *speed)
 {
     for (int64_t e = 0; e < n_events; ++e) {
         const int32_t i = wi[e];
         if (i < 0 || i >= n) return -(e + 1);
+        const double rate_i = rate ? rate[i] : 1.0;
         if (kind[e] == 0) {
             if (te[e] < t[i]) return -(e + 1);
             const double *ce = (c_row && c_row[e] >= 0) ? c + c_row[e] * d : NULL;
             const double *xe = (xi_row && xi_row[e] >= 0) ? xi + xi_row[e] * d : NULL;
             const double *he = (h_row && h_row[e] >= 0) ? h + h_row[e] * d : NULL;
             (order ? a2o_gradient_event_listing : a2o_gradient_event)(
-                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, d, eta, te[e], gamma[e], gscale[e], ce, xe, he);
+                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, rate_i, d, eta, te[e], gamma[e], gscale[e], ce, xe, he);
+            /* the finished gradient step sets the speed of the worker's clock from here on */
+            if (rate && speed && speed[e] > 0.0) rate[i] = speed[e];
         } else if (kind[e] == 1) {
             const int32_t j = wj[e];
             if (j < 0 || j >= n || j == i) return -(e + 1);
             if (te[e] < t[i] || te[e] < t[j]) return -(e + 1);
             (order ? a2o_gossip_event_listing : a2o_gossip_event)(
-                x + (int64_t)i * d, xt + (int64_t)i * d, t + i,
-                x + (int64_t)j * d, xt + (int64_t)j * d, t + j, d, eta, te[e], alpha, alpha_t);
+                x + (int64_t)i * d, xt + (int64_t)i * d, t + i, rate_i,
+                x + (int64_t)j * d, xt + (int64_t)j * d, t + j, rate ? rate[j] : 1.0, d, eta, te[e], alpha, alpha_t);
         } else {
             return -(e + 1);
         }
@@ -190,7 +203,7 @@ int64_t a2o_apply_events(int32_t n, int64_t d, double *x, double *xt, double *t,
 /* ------------------------------------------------------------------------- */
 int a2o_stats(int32_t n, int64_t d, const double *x, const double *xt, const double *t,
               double eta, double t_now,
-              double *consensus_x, double *consensus_xt, double *sum_x, double *sum_xt)
+              double *consensus_x, double *consensus_xt, double *sum_x, double *sum_xt, const double *rate)
 {
     double *mx = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
     double *mxt = (double *)malloc(sizeof(double) * (size_t)n * (size_t)d);
@@ -198,7 +211,7 @@ int a2o_stats(int32_t n, int64_t d, const double *x, const double *xt, const dou
     memcpy(mx, x, sizeof(double) * (size_t)n * (size_t)d);
     memcpy(mxt, xt, sizeof(double) * (size_t)n * (size_t)d);
     for (int32_t i = 0; i < n; ++i)
-        a2o_mix_row(mx + (int64_t)i * d, mxt + (int64_t)i * d, d, eta, t_now - t[i]);
+        a2o_mix_row(mx + (int64_t)i * d, mxt + (int64_t)i * d, d, eta, (rate ? rate[i] : 1.0) * (t_now - t[i]));
 
     double cx = 0.0, cxt = 0.0;
     for (int64_t k = 0; k < d; ++k) {

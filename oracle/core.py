@@ -25,10 +25,10 @@ def lib():
         _lib.a2o_apply_events.argtypes = [
             C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double, C.c_double,
             C.c_int64, d_p, i32_p, i32_p, i32_p, d_p, d_p,
-            i64_p, C.c_void_p, i64_p, C.c_void_p, i64_p, C.c_void_p, C.c_int32]
+            i64_p, C.c_void_p, i64_p, C.c_void_p, i64_p, C.c_void_p, C.c_int32, d_p, C.c_void_p]
         _lib.a2o_apply_events.restype = C.c_int64
         _lib.a2o_stats.argtypes = [C.c_int32, C.c_int64, d_p, d_p, d_p, C.c_double, C.c_double,
-                                   C.POINTER(C.c_double), C.POINTER(C.c_double), d_p, d_p]
+                                   C.POINTER(C.c_double), C.POINTER(C.c_double), d_p, d_p, d_p]
         _lib.a2o_stats.restype = C.c_int
         _lib.a2o_philox4x32_10.argtypes = [u32_p, u32_p, u32_p]
         _lib.a2o_philox4x32_10.restype = None
@@ -48,19 +48,22 @@ def philox4x32_10(counter, key):
 class Events:
     """A serial event stream: parallel arrays, one entry per event, in time order."""
 
-    def __init__(self, t, kind, i, j, clock=None):
+    def __init__(self, t, kind, i, j, clock=None, speed=None):
+        """clock: which clock fired (worker, or n + edge index).  speed: per event, > 0 on a gradient event sets the
+        speed of that worker's own clock from the event on (0 / None: unchanged)."""
         self.t = np.ascontiguousarray(t, np.float64)
         self.kind = np.ascontiguousarray(kind, np.int32)
         self.i = np.ascontiguousarray(i, np.int32)
         self.j = np.ascontiguousarray(j, np.int32)
         self.clock = None if clock is None else np.ascontiguousarray(clock, np.int32)
+        self.speed = None if speed is None else np.ascontiguousarray(speed, np.float64)
 
     def __len__(self):
         return len(self.t)
 
     def __getitem__(self, s):
         return Events(self.t[s], self.kind[s], self.i[s], self.j[s],
-                      None if self.clock is None else self.clock[s])
+                      None if self.clock is None else self.clock[s], None if self.speed is None else self.speed[s])
 
 
 def generate_events(n, edges_u, edges_v, node_rate, edge_rate, seed, n_events):
@@ -96,6 +99,7 @@ class State:
         self.t = np.zeros(self.n, np.float64)
         self.eta, self.alpha, self.alpha_t = float(eta), float(alpha), float(alpha_t)
         self.order = int(order)      # 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
+        self.rate = np.ones(self.n, np.float64)   # speed of every worker's own clock against the event times
 
     def apply(self, ev, gamma=None, gscale=None, xi=None, xi_row=None, c=None, c_row=None, h=None, h_row=None):
         """Run the serial event loop over ev.
@@ -124,7 +128,8 @@ class State:
         rc = lib().a2o_apply_events(self.n, self.d, self.x, self.xt, self.t,
                                     self.eta, self.alpha, self.alpha_t, m,
                                     ev.t, ev.kind, ev.i, ev.j, gamma, gscale,
-                                    xi_r, xi_p, c_r, c_p, h_r, h_p, self.order)
+                                    xi_r, xi_p, c_r, c_p, h_r, h_p, self.order, self.rate,
+                                    None if ev.speed is None else ev.speed.ctypes.data_as(C.c_void_p))
         if rc != 0:
             raise ValueError(f"malformed event at position {-rc - 1}")
         return self
@@ -133,14 +138,14 @@ class State:
         cx, cxt = C.c_double(), C.c_double()
         sx = np.zeros(self.n); sxt = np.zeros(self.n)
         rc = lib().a2o_stats(self.n, self.d, self.x, self.xt, self.t, self.eta, float(t_now),
-                             C.byref(cx), C.byref(cxt), sx, sxt)
+                             C.byref(cx), C.byref(cxt), sx, sxt, self.rate)
         assert rc == 0
         return {"consensus_x": cx.value, "consensus_xt": cxt.value, "sum_x": sx, "sum_xt": sxt}
 
     def mix_workers(self, workers, t_now):
         """Applies the mixing flow up to t_now to the listed workers in place (and moves their time stamps)."""
         for i in workers:
-            lib().a2o_mix_row(self.x[i], self.xt[i], self.d, self.eta, float(t_now) - self.t[i])
+            lib().a2o_mix_row(self.x[i], self.xt[i], self.d, self.eta, self.rate[i] * (float(t_now) - self.t[i]))
             self.t[i] = float(t_now)
         return self
 
@@ -156,7 +161,7 @@ class State:
         """Copy of (x, xt) with every worker mixed up to t_now (what Algorithm 1 returns at T)."""
         x = self.x.copy(); xt = self.xt.copy()
         for i in range(self.n):
-            lib().a2o_mix_row(x[i], xt[i], self.d, self.eta, float(t_now) - self.t[i])
+            lib().a2o_mix_row(x[i], xt[i], self.d, self.eta, self.rate[i] * (float(t_now) - self.t[i]))
         return x, xt
 
 

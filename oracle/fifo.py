@@ -21,6 +21,14 @@ Reading used (the paper describes the mechanism in prose only):
     completed so far, by any worker); before the first completion the average is the mean of 1 / rate_i.  A
     step's duration enters the average after the events of its own completion are stamped.  Durations and
     communication times stay in real time; only the stamps change.
+  * normalize="worker": the same sentence read per worker.  Every worker normalises its own clock by the running
+    average of the durations of its OWN previous gradient steps (before its first completion: 1 / rate_i).  Events
+    keep their real-time stamps, which order them; what changes is how much time elapses for the mixing of worker
+    i between two of its events: (real time elapsed) / (worker i's average).  The stream carries this as the field
+    `speed` of a gradient event: the speed of that worker's clock from the event on, 1 / (average duration of the
+    worker's steps completed so far, the one just finished included), rounded to fp32, the precision in which the
+    engine receives it.  As above, a step's duration counts only after the events of its own completion.  The
+    initial speeds are the rates rate_i (core.State.rate has to be set to them).
 
 Random numbers: Philox4x32-10, key = (seed_lo, seed_hi), counter = (draw_lo, draw_hi, worker, tag) with
 tag 0x0A2C1D21 for step durations and 0x0A2C1D22 for the Poisson counts; a uniform is the 53-bit value
@@ -60,7 +68,11 @@ def _poisson(stream, mean):
 
 
 def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_events, normalize=False):
-    """Returns core.Events (clock = worker for gradient events, n + edge index for gossip events)."""
+    """Returns core.Events (clock = worker for gradient events, n + edge index for gossip events; speed: see
+    normalize="worker", else None)."""
+    per_worker = normalize == "worker"
+    if per_worker:
+        normalize = False
     edge_index = {}
     for e, (a, b) in enumerate(edges):
         edge_index[(a, b)] = e
@@ -76,7 +88,8 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
         if node_rate[i] > 0:
             running[i] = (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0))
             heapq.heappush(heap, (running[i], 1, i))
-    out_t, out_kind, out_i, out_j, out_clock = [], [], [], [], []
+    out_t, out_kind, out_i, out_j, out_clock, out_speed = [], [], [], [], [], []
+    own_sum, own_n = [0.0] * n, [0] * n          # per worker: durations of its completed gradient steps
     active = [1.0 / node_rate[i] for i in range(n) if node_rate[i] > 0]
     unit = sum(active) / len(active) if active else 1.0      # average gradient-step duration so far
     dur_sum, dur_n = 0.0, 0
@@ -104,6 +117,7 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
             e = edge_index[(a, b)]
             out_t.append(stamp(t)); out_kind.append(1); out_i.append(edges[e][0]); out_j.append(edges[e][1])
             out_clock.append(n + e)
+            out_speed.append(0.0)
             for w in (a, b):
                 todo[w] -= 1
                 busy[w] = True
@@ -122,6 +136,9 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
             out_t.append(stamp(t)); out_kind.append(0); out_i.append(i); out_j.append(-1); out_clock.append(i)
             todo[i] += _poisson(cnt[i], comm_per_grad)
             finished = running[i]
+            own_sum[i] += finished
+            own_n[i] += 1
+            out_speed.append(float(np.float32(1.0 / (own_sum[i] / own_n[i]))))
             running[i] = (1.0 / node_rate[i]) * (1.0 + jitter * (2.0 * dur[i].next() - 1.0))
             heapq.heappush(heap, (t + running[i], 1, i))
         join(i)
@@ -131,4 +148,5 @@ def generate(n, edges, node_rate, comm_per_grad, comm_time, jitter, seed, n_even
             dur_n += 1
             unit = dur_sum / dur_n
     return core.Events(np.array(out_t), np.array(out_kind, np.int32), np.array(out_i, np.int32),
-                       np.array(out_j, np.int32), np.array(out_clock, np.int32))
+                       np.array(out_j, np.int32), np.array(out_clock, np.int32),
+                       np.array(out_speed) if per_worker else None)

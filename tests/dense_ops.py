@@ -38,9 +38,11 @@ def gradient(n, i, gamma, s, c_k, xi_k):
     return m
 
 
-def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, order=0, h=None):
+def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, order=0, h=None, flow_time=None):
     """events: list of (t, kind, i, j).  c: (n, d) or None.  xi: list (per event) of d-vectors or None.
     h: (n, d) per-worker, per-coordinate curvatures or None.
+    flow_time: None, or a function (event index or None for the final flush, worker, t_from, t_to) -> duration of the
+    flow of that worker between the two times (worker clocks that do not run at the speed of the event times).
     order 0: v <- J F v (flow, then the jump evaluated at the flowed state, Eq. (1));
     order 1: v <- F v + (J - I) v (the jump evaluated at the stored state, Algorithm 1's listing order).
     Returns (x, xt) after the events, every worker flowed to t_final if given."""
@@ -54,7 +56,7 @@ def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, ord
             ws = [i] if kind == 0 else [i, j]
             f = np.eye(2 * n + 1)
             for w in ws:
-                f = flow(n, w, eta, te - t[w]) @ f
+                f = flow(n, w, eta, te - t[w] if flow_time is None else flow_time(e, w, t[w], te)) @ f
                 t[w] = te
             if kind == 0:
                 ck = 0.0 if c is None else c[i, k]
@@ -67,7 +69,7 @@ def run(x0, xt0, eta, alpha, alpha_t, events, gamma, s, c, xi, t_final=None, ord
             total = step @ total
         if t_final is not None:
             for w in range(n):
-                total = flow(n, w, eta, t_final - t[w]) @ total
+                total = flow(n, w, eta, t_final - t[w] if flow_time is None else flow_time(None, w, t[w], t_final)) @ total
         v = total @ v
         x[:, k], xt[:, k] = v[:n], v[n:2 * n]
     return x, xt

@@ -444,3 +444,66 @@ def test_accelerated_parameters_reach_a_tighter_neighbourhood_of_the_optimum_on_
         assert dist[0] < 0.5 * np.sqrt(((x0 - x_star) ** 2).sum(1).mean())     # the transient is over early
         level[label] = np.mean(dist[2:])
     assert level["accelerated"] < 0.8 * level["baseline"]
+
+
+# ---------------------------------------------------------------- worker clocks (time normalised per worker)
+
+def test_worker_clocks_equal_dense_operators_with_flows_of_the_workers_own_durations():
+    """Every worker's flow between two of its events lasts (speed of its clock) x (difference of the event times); a
+    gradient event may set a new speed, which counts from that event on.  The speeds are tracked here by hand and
+    handed to the dense operators as flow durations."""
+    rng = np.random.default_rng(5)
+    n, d = 4, 6
+    edges = graph.ring(n)
+    ev = _events(n, edges, 1.0, 1.3, 321, 160)
+    m = len(ev)
+    is_grad = ev.kind == 0
+    speed = np.where(is_grad & (rng.random(m) < 0.7), rng.uniform(0.3, 2.5, m), 0.0)
+    ev = core.Events(ev.t, ev.kind, ev.i, ev.j, ev.clock, speed)
+    rate0 = rng.uniform(0.5, 2.0, n)
+    eta, alpha, alpha_t = 0.6, 0.5, 1.2
+    x0 = rng.normal(size=(n, d)); xt0 = rng.normal(size=(n, d))
+    gamma = rng.uniform(0.01, 0.2, m); s = rng.uniform(0.0, 1.5, m)
+    c = rng.normal(size=(n, d))
+    c_row = np.where(is_grad, ev.i, -1).astype(np.int64)
+    for order in (0, 1):
+        st = core.State(x0, xt0, eta, alpha, alpha_t, order=order)
+        st.rate[:] = rate0
+        st.apply(ev, gamma, s, None, None, c, c_row)
+        T = ev.t[-1] + 0.4
+        ox, oxt = st.flushed(T)
+        # by hand: the speed in force for worker w when event e (or the final flush) mixes it
+        in_force = np.zeros((m + 1, n))
+        cur = rate0.copy()
+        for e in range(m):
+            in_force[e] = cur
+            if is_grad[e] and speed[e] > 0:
+                cur[ev.i[e]] = speed[e]
+        in_force[m] = cur
+        assert np.array_equal(st.rate, cur)
+        bx, bxt = dense_ops.run(x0, xt0, eta, alpha, alpha_t, list(zip(ev.t, ev.kind, ev.i, ev.j)), gamma, s, c,
+                                [None] * m, t_final=T, order=order,
+                                flow_time=lambda e, w, a, b: in_force[m if e is None else e, w] * (b - a))
+        assert np.allclose(ox, bx, rtol=1e-10, atol=1e-12) and np.allclose(oxt, bxt, rtol=1e-10, atol=1e-12)
+        assert not np.allclose(ox, core.State(x0, xt0, eta, alpha, alpha_t, order=order).apply(
+            core.Events(ev.t, ev.kind, ev.i, ev.j), gamma, s, None, None, c, c_row).flushed(T)[0], rtol=1e-3)
+
+
+def test_one_common_clock_speed_is_a_change_of_eta():
+    """All clocks at the same constant speed s: eta only ever multiplies an elapsed time, so the run equals the plain
+    dynamic with eta s; and the observables, which mix every worker to a common time, follow."""
+    rng = np.random.default_rng(8)
+    n, d = 5, 7
+    ev = _events(n, graph.complete(n), 1.0, 0.8, 77, 300)
+    x0 = rng.normal(size=(n, d))
+    a = core.State(x0, None, 0.4, 0.5, 0.9)
+    a.rate[:] = 1.75
+    a.apply(ev, 0.05, 1.0)
+    b = core.State(x0, None, 0.4 * 1.75, 0.5, 0.9).apply(ev, 0.05, 1.0)
+    assert np.allclose(a.x, b.x, rtol=1e-12, atol=1e-14) and np.allclose(a.xt, b.xt, rtol=1e-12, atol=1e-14)
+    T = ev.t[-1] + 1.0
+    sa, sb = a.stats(T), b.stats(T)
+    assert np.isclose(sa["consensus_xt"], sb["consensus_xt"], rtol=1e-11)
+    assert np.allclose(sa["sum_x"], sb["sum_x"], rtol=1e-11)
+    a.average(T); b.average(T)
+    assert np.allclose(a.x, b.x, rtol=1e-12, atol=1e-14)

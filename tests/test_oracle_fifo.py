@@ -2,7 +2,7 @@
 import numpy as np
 from scipy import stats
 
-from oracle import fifo, graph
+from oracle import core, fifo, graph
 
 
 def _run(n, topo, rate, rho, comm_time, jitter, seed, m):
@@ -129,3 +129,60 @@ def test_normalised_clock_with_unequal_workers():
             # averaging ends between events move the clock too but never change the unit, so applying the new unit
             # from this event on is the same thing
             unit = np.mean(done)
+
+
+# ---- the same normalisation read per worker: every worker's clock runs on its own gradient steps --------------
+
+def test_per_worker_clock_speeds_are_the_running_averages_of_the_workers_own_steps():
+    n, edges = 6, graph.ring(6)
+    rate = np.array([0.4, 1.0, 2.5, 1.0, 0.7, 1.6])
+    real = fifo.generate(n, edges, rate, 1.2, 0.02, 0.3, 4, 4000)
+    per = fifo.generate(n, edges, rate, 1.2, 0.02, 0.3, 4, 4000, normalize="worker")
+    # the events and their real-time stamps do not change; only gradient events carry a speed
+    assert np.array_equal(real.t, per.t) and np.array_equal(real.kind, per.kind) and np.array_equal(real.i, per.i)
+    assert np.all(per.speed[per.kind == 1] == 0) and np.all(per.speed[per.kind == 0] > 0)
+    for w in range(n):
+        ends = per.t[(per.kind == 0) & (per.i == w)]
+        durations = np.diff(np.concatenate([[0.0], ends]))                 # steps run back to back from time 0
+        want = 1.0 / (np.cumsum(durations) / np.arange(1, len(durations) + 1))
+        got = per.speed[(per.kind == 0) & (per.i == w)]
+        assert np.allclose(got, want, rtol=2e-7)                           # rounded to fp32
+        assert np.array_equal(got, got.astype(np.float32).astype(np.float64))
+        # on its own clock a worker completes one gradient step per unit of time in the long run: the time that
+        # elapses for it during step k is duration_k x (speed before the step's completion)
+        before = np.concatenate([[rate[w]], got[:-1]])
+        assert abs((durations * before).sum() / len(durations) - 1.0) < 0.02
+
+
+def test_per_worker_clocks_of_identical_workers_are_the_common_normalised_clock():
+    """Identical workers, no jitter: every step of every worker lasts 1 / r, so every worker's own average is the
+    global one and the dynamic driven by the per-worker speeds equals the one driven by the normalised stamps."""
+    n, edges, r = 8, graph.ring(8), 2.0
+    glob = fifo.generate(n, edges, np.full(n, r), 1.5, 0.005, 0.0, 3, 2500, normalize=True)
+    per = fifo.generate(n, edges, np.full(n, r), 1.5, 0.005, 0.0, 3, 2500, normalize="worker")
+    assert np.array_equal(glob.kind, per.kind) and np.array_equal(glob.i, per.i) and np.array_equal(glob.j, per.j)
+    assert np.allclose(per.speed[per.kind == 0], r, rtol=1e-7)
+    rng = np.random.default_rng(2)
+    x0 = rng.normal(size=(n, 5))
+    a = core.State(x0, None, 0.8, 0.5, 1.1).apply(glob, 0.05, 1.0)
+    b = core.State(x0, None, 0.8, 0.5, 1.1)
+    b.rate[:] = r
+    b.apply(per, 0.05, 1.0)
+    assert np.allclose(a.x, b.x, rtol=1e-9, atol=1e-12) and np.allclose(a.xt, b.xt, rtol=1e-9, atol=1e-12)
+
+
+def test_per_worker_clocks_do_not_depend_on_the_unit_of_time():
+    n, edges = 10, graph.exponential(10)
+    rate = np.array([0.5, 0.8, 1.0, 1.0, 1.2, 2.0, 2.2, 3.0, 0.9, 1.4])
+    rng = np.random.default_rng(6)
+    x0 = rng.normal(size=(n, 4))
+    out = []
+    for k in (1.0, 8.0):                                   # k times faster machines, k times shorter exchanges
+        ev = fifo.generate(n, edges, k * rate, 1.0, 0.02 / k, 0.3, 9, 3000, normalize="worker")
+        st = core.State(x0, None, 0.5, 0.5, 0.9)
+        st.rate[:] = k * rate
+        st.apply(ev, 0.05, 1.0)
+        out.append((ev, st))
+    (ea, sa), (eb, sb) = out
+    assert np.array_equal(ea.kind, eb.kind) and np.array_equal(ea.i, eb.i) and np.allclose(ea.t, 8.0 * eb.t, rtol=1e-12)
+    assert np.allclose(sa.x, sb.x, rtol=1e-5, atol=1e-7)   # the speeds are rounded to fp32 on both sides
