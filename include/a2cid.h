@@ -96,6 +96,15 @@ typedef struct {
  *   xi, c, h  device pointers to d floats, 16-byte aligned, or NULL (xi, c: zeros; h: ones).
  *           Read when the stream reaches the operation; the caller keeps them alive until
  *           then.  c and h are not read when gscale = 0.
+ *   clock_rate  gradient events only; 0: nothing changes.  > 0: from this event on worker i's own
+ *           clock runs at this speed against the clock of the event times, i.e. the mixing of
+ *           worker i between two of its events (or up to t_sync, or up to the t_now of a2cid_stats,
+ *           a2cid_flush, a2cid_average) lasts clock_rate times the difference of the two times.
+ *           This is the time normalisation of the section "Practical implementation of the
+ *           dynamic" (a running average of the durations of the previous gradient steps) read per
+ *           worker: the caller passes 1 / (average duration of worker i's steps so far).  The
+ *           mixing up to this event itself still uses the previous speed.  Every worker starts at
+ *           speed 1 (a2cid_set_clock_rates changes that).
  *   id      opaque to the library (the scheduler stores the serial event index here). */
 typedef struct {
     double t;
@@ -104,7 +113,7 @@ typedef struct {
     int32_t j;
     float gamma;
     float gscale;
-    int32_t reserved;
+    float clock_rate;
     const float *xi;
     const float *c;
     const float *h;
@@ -222,6 +231,11 @@ int a2cid_get_times(const a2cid_ctx *ctx, double *t);
 /* Replaces the n time stamps (resuming from a saved state). */
 int a2cid_set_times(a2cid_ctx *ctx, const double *t);
 
+/* The speeds of the n workers' own clocks (a2cid_op.clock_rate): get, and set (finite, > 0; e.g. the
+ * nominal step rates before any gradient step has been measured, or a saved state). */
+int a2cid_get_clock_rates(const a2cid_ctx *ctx, double *rate);
+int a2cid_set_clock_rates(a2cid_ctx *ctx, const double *rate);
+
 /* Waits until everything enqueued so far has finished. */
 int a2cid_synchronize(a2cid_ctx *ctx);
 
@@ -234,6 +248,11 @@ void a2cid_destroy(a2cid_ctx *ctx);
  * Same error codes as a2cid_apply_events. */
 int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
                      const a2cid_event_batch *batch, a2cid_coef *coef);
+/* The same with worker clocks: rate (n doubles, the speed of every worker's own clock, see
+ * a2cid_op.clock_rate) is read and, on success, updated by the batch's gradient events.
+ * a2cid_plan_batch is this function with every speed 1 at the start of the batch. */
+int a2cid_plan_batch_clocks(int32_t n, const a2cid_graph *graph, double eta, double *t, double *rate,
+                            const a2cid_event_batch *batch, a2cid_coef *coef);
 
 /* The programme the chain kernel (a2cid_set_tuning, mode 3) runs for a batch, as a pure host
  * function.  Eq. (1) lets operations on disjoint workers commute, so any order that keeps every
@@ -315,12 +334,16 @@ int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
  * Simultaneous completions are ordered (time, averaging-end before step-end, worker).  The graph's
  * rates are ignored.  Streams: Philox4x32-10 as for a2cid_sched_create with counter tags
  * 0x0A2C1D21 (durations) and 0x0A2C1D22 (Poisson counts, product-of-uniforms method).
- * normalize != 0 stamps the events with normalised time instead of real time, as the same section
+ * normalize = 1 stamps the events with normalised time instead of real time, as the same section
  * describes (a running average of the duration of the previous gradient steps normalises time, so
  * that a gradient step takes one unit as the analysis assumes): the stamp advances by (real time
  * elapsed) / (average duration of all gradient steps completed so far, by any worker; before the
  * first completion: the mean of 1 / node_rate[i]); a step's duration enters the average after the
- * events of its own completion are stamped.  Durations and comm_time stay in real time.  The
+ * events of its own completion are stamped.  Durations and comm_time stay in real time.
+ * normalize = 2 reads the same sentence per worker: the stamps stay in real time, and every gradient
+ * event carries in clock_rate the speed of its worker's own clock from then on, 1 / (average duration
+ * of that worker's steps completed so far, the one just finished included), as a float; the context
+ * that consumes the stream should start from a2cid_set_clock_rates(node_rate).  The
  * returned scheduler is used with a2cid_sched_next / skip / counts / destroy like any other. */
 int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *graph, const double *node_rate,
                            double comm_per_grad, double comm_time, double jitter, int32_t normalize,

@@ -37,12 +37,12 @@ class a2cid_buffers(C.Structure):
 
 class a2cid_op(C.Structure):
     _fields_ = [("t", C.c_double), ("kind", C.c_int32), ("i", C.c_int32), ("j", C.c_int32),
-                ("gamma", C.c_float), ("gscale", C.c_float), ("reserved", C.c_int32),
+                ("gamma", C.c_float), ("gscale", C.c_float), ("clock_rate", C.c_float),
                 ("xi", C.c_void_p), ("c", C.c_void_p), ("h", C.c_void_p), ("id", C.c_int64)]
 
 
 OP_DTYPE = np.dtype([("t", "<f8"), ("kind", "<i4"), ("i", "<i4"), ("j", "<i4"), ("gamma", "<f4"),
-                     ("gscale", "<f4"), ("reserved", "<i4"), ("xi", "<u8"), ("c", "<u8"), ("h", "<u8"), ("id", "<i8")])
+                     ("gscale", "<f4"), ("clock_rate", "<f4"), ("xi", "<u8"), ("c", "<u8"), ("h", "<u8"), ("id", "<i8")])
 assert OP_DTYPE.itemsize == C.sizeof(a2cid_op) == 64
 
 
@@ -73,6 +73,10 @@ SIGNATURES = {
     "a2cid_average": (C.c_int, [C.c_void_p, C.c_double]),
     "a2cid_get_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
     "a2cid_set_times": (C.c_int, [C.c_void_p, _P(C.c_double)]),
+    "a2cid_get_clock_rates": (C.c_int, [C.c_void_p, _P(C.c_double)]),
+    "a2cid_set_clock_rates": (C.c_int, [C.c_void_p, _P(C.c_double)]),
+    "a2cid_plan_batch_clocks": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double), _P(C.c_double),
+                                          _P(a2cid_event_batch), C.c_void_p]),
     "a2cid_synchronize": (C.c_int, [C.c_void_p]),
     "a2cid_destroy": (None, [C.c_void_p]),
     "a2cid_plan_chain": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_int32, C.c_void_p, C.c_int64,
@@ -179,14 +183,20 @@ def a2cid_graph_params(n, u, v, rate):
             "alpha_tilde": out[3].value}
 
 
-def a2cid_plan_batch(n, u, v, rate, eta, t, batch):
-    """Returns (t_after, coefficients); t is not modified."""
+def a2cid_plan_batch(n, u, v, rate, eta, t, batch, clock_rates=None):
+    """Returns (t_after, coefficients), or with clock_rates (the speeds of the workers' own clocks) (t_after,
+    coefficients, clock_rates_after); the arguments are not modified."""
     g = _GraphArg(u, v, rate)
     t = np.array(t, np.float64)
     coef = np.zeros(len(batch.ops), COEF_DTYPE)
     bs = batch.struct()
-    _check(load().a2cid_plan_batch(n, C.byref(g.struct), float(eta), _dptr(t), C.byref(bs), coef.ctypes.data))
-    return t, coef
+    if clock_rates is None:
+        _check(load().a2cid_plan_batch(n, C.byref(g.struct), float(eta), _dptr(t), C.byref(bs), coef.ctypes.data))
+        return t, coef
+    cr = np.array(clock_rates, np.float64)
+    _check(load().a2cid_plan_batch_clocks(n, C.byref(g.struct), float(eta), _dptr(t), _dptr(cr), C.byref(bs),
+                                          coef.ctypes.data))
+    return t, coef, cr
 
 
 STEP_DTYPE = np.dtype([("op", "<i4"), ("row_i", "<i4"), ("row_j", "<i4"), ("src_i", "u1"), ("src_j", "u1"),
@@ -244,7 +254,7 @@ class Scheduler:
         else:
             _check(load().a2cid_sched_create_fifo(C.byref(self._h), n, C.byref(self._g.struct), _dptr(nr),
                                                   float(fifo["comm_per_grad"]), float(fifo["comm_time"]),
-                                                  float(fifo["jitter"]), int(bool(fifo.get("normalize", False))),
+                                                  float(fifo["jitter"]), {False: 0, True: 1, "worker": 2}[fifo.get("normalize", False)],
                                                   int(seed)))
 
     def next(self, max_events):
@@ -338,6 +348,15 @@ class Engine:
         t = np.zeros(self.n)
         _check(load().a2cid_get_times(self._h, _dptr(t)))
         return t
+
+    def clock_rates(self):
+        r = np.zeros(self.n, np.float64)
+        _check(load().a2cid_get_clock_rates(self._h, _dptr(r)))
+        return r
+
+    def set_clock_rates(self, rate):
+        r = np.ascontiguousarray(np.broadcast_to(rate, (self.n,)), np.float64)
+        _check(load().a2cid_set_clock_rates(self._h, _dptr(r)))
 
     def set_times(self, t):
         t = np.ascontiguousarray(t, np.float64)

@@ -75,6 +75,7 @@ struct a2cid_ctx {
     std::vector<DevSpan> known;         // device allocations that passed check_device_span (a cache)
     double eta = 0, alpha = 0, alpha_t = 0;
     std::vector<double> t;
+    std::vector<double> rate;           // speed of every worker's own clock against the event times (default 1)
     Plan plan;
     PlanScratch scratch;
     Slot slots[kSlots];
@@ -492,6 +493,7 @@ static int create_impl(a2cid_ctx *c, int32_t n, int64_t d, const a2cid_graph *gr
     c->stream = (hipStream_t)buf->hip_stream;
     c->eta = eta; c->alpha = alpha; c->alpha_t = alpha_tilde;
     c->t.assign(n, 0.0);
+    c->rate.assign(n, 1.0);
     for (Slot &s : c->slots) {
         A2CID_HIP(hipHostMalloc((void **)&s.host, sizeof(DevOp) * kSlotOps, hipHostMallocDefault));
         A2CID_HIP(hipMalloc((void **)&s.dev, sizeof(DevOp) * kSlotOps));
@@ -590,7 +592,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
     if (int rc = enter(c)) return rc;
     if (int rc = unusable(c)) return rc;
     // ---- validation: nothing is enqueued and no time stamp moves before all of it has passed ----
-    if (int rc = plan_batch(c->g, c->eta, c->t.data(), batch, c->plan, c->scratch)) return rc;
+    if (int rc = plan_batch(c->g, c->eta, c->t.data(), c->rate.data(), batch, c->plan, c->scratch)) return rc;
     // gradient inputs the kernels will read: d floats each, inside one device allocation
     c->known.clear();
     for (int64_t k = 0; k < batch->n_ops; ++k) {
@@ -614,6 +616,7 @@ static int apply_impl(a2cid_ctx *c, const a2cid_event_batch *batch) {
         return rc;
     }
     c->t = c->plan.t_after;
+    c->rate = c->plan.rate_after;
     c->n_gossip += c->plan.n_gossip;
     c->n_grad += c->plan.n_grad;
     c->alg_bytes += (double)c->d * (32.0 * c->plan.n_gossip + 16.0 * c->plan.n_grad +
@@ -752,7 +755,7 @@ static int check_common_time(const a2cid_ctx *c, double t_now) {
 static int upload_coefficients(a2cid_ctx *c, double t_now) {
     CoefStage *cs;
     if (int rc = acquire_coef_stage(c, &cs)) return rc;
-    for (int32_t i = 0; i < c->n; ++i) cs->host[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+    for (int32_t i = 0; i < c->n; ++i) cs->host[i] = (float)mix_coefficient(c->eta, c->rate[i] * (t_now - c->t[i]));
     A2CID_HIP(hipMemcpyAsync(c->b_dev, cs->host, sizeof(float) * c->n, hipMemcpyHostToDevice, c->stream));
     A2CID_HIP(hipEventRecord(cs->done, c->stream));
     cs->in_flight = true;
@@ -765,7 +768,7 @@ int a2cid_flush(a2cid_ctx *c, double t_now) {
     if (int rc = check_common_time(c, t_now)) return rc;
     try {
         std::vector<float> b(c->n);
-        for (int32_t i = 0; i < c->n; ++i) b[i] = (float)mix_coefficient(c->eta, t_now - c->t[i]);
+        for (int32_t i = 0; i < c->n; ++i) b[i] = (float)mix_coefficient(c->eta, c->rate[i] * (t_now - c->t[i]));
         if (int rc = enqueue_mix_all(c, b)) {
             c->failed = true;
             return rc;
@@ -867,7 +870,7 @@ int a2cid_stats_static(a2cid_ctx *c, double t_now, double *out) {
     if (int rc = static_scratch(c->device, &partials)) return rc;
     MixArgs args;
     for (int32_t i = 0; i < kMixArgsMax; ++i)
-        args.b[i] = i < c->n ? (float)mix_coefficient(c->eta, t_now - c->t[i]) : 0.f;
+        args.b[i] = i < c->n ? (float)mix_coefficient(c->eta, c->rate[i] * (t_now - c->t[i])) : 0.f;
     const int32_t max_blocks = (int32_t)std::min<size_t>((size_t)c->stats_blocks, kStaticDoubles / (size_t)m);
     if (int rc = launch_stats(c, nullptr, &args, partials, max_blocks, out)) {
         c->failed = true;
@@ -903,6 +906,22 @@ int a2cid_get_times(const a2cid_ctx *c, double *t) {
     clear_error();
     if (!c || !t) return fail(A2CID_EINVAL, "context / t is NULL");
     std::copy(c->t.begin(), c->t.end(), t);
+    return A2CID_OK;
+}
+
+int a2cid_get_clock_rates(const a2cid_ctx *c, double *rate) {
+    clear_error();
+    if (!c || !rate) return fail(A2CID_EINVAL, "context / rate is NULL");
+    std::copy(c->rate.begin(), c->rate.end(), rate);
+    return A2CID_OK;
+}
+
+int a2cid_set_clock_rates(a2cid_ctx *c, const double *rate) {
+    clear_error();
+    if (!c || !rate) return fail(A2CID_EINVAL, "context / rate is NULL");
+    for (int32_t i = 0; i < c->n; ++i)
+        if (!(rate[i] > 0.0) || !std::isfinite(rate[i])) return fail(A2CID_EINVAL, "rate[%d] must be finite and > 0", i);
+    c->rate.assign(rate, rate + c->n);
     return A2CID_OK;
 }
 

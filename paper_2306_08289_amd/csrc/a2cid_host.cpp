@@ -200,7 +200,7 @@ static bool connected(const Graph &g) {
 // ------------------------------------------------------------------------------------------
 // Batch planner
 // ------------------------------------------------------------------------------------------
-int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
+int plan_batch(const Graph &g, double eta, const double *t_now, const double *rate_now, const a2cid_event_batch *batch,
                Plan &plan, PlanScratch &scratch) {
     if (!batch) return fail(A2CID_EINVAL, "batch is NULL");
     if (batch->n_ops < 0 || batch->n_levels < 0) return fail(A2CID_EINVAL, "negative batch size");
@@ -211,6 +211,8 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
     const int32_t n = g.n;
     plan.coef.assign((size_t)batch->n_ops, a2cid_coef{0.f, 0.f, 0.f, 0.f});
     plan.t_after.assign(t_now, t_now + n);
+    if (rate_now) plan.rate_after.assign(rate_now, rate_now + n);
+    else plan.rate_after.assign(n, 1.0);
     plan.n_gossip = plan.n_grad = plan.n_grad_xi = plan.n_grad_c = plan.n_grad_h = 0;
     scratch.level_stamp.assign(n, 0);
     scratch.last_op.assign(n, -1);
@@ -237,6 +239,8 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
                     return fail(A2CID_EINVAL, "op %lld: gamma / gscale not finite", (long long)k);
                 if (((uintptr_t)op.xi | (uintptr_t)op.c | (uintptr_t)op.h) & 15u)
                     return fail(A2CID_EALIGN, "op %lld: xi / c / h must be 16-byte aligned", (long long)k);
+                if (!(op.clock_rate >= 0.f) || !std::isfinite(op.clock_rate))
+                    return fail(A2CID_EINVAL, "op %lld: clock_rate must be finite and >= 0", (long long)k);
                 ++plan.n_grad;
                 if (op.xi) ++plan.n_grad_xi;
                 if (op.c && op.gscale != 0.f) ++plan.n_grad_c;
@@ -257,17 +261,19 @@ int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_even
                 if (tau < 0.0)
                     return fail(A2CID_EORDER, "op %lld: time %.17g is before worker %d's time %.17g",
                                 (long long)k, op.t, w, plan.t_after[w]);
-                *b_pre[s] = (float)mix_coefficient(eta, tau);
+                *b_pre[s] = (float)mix_coefficient(eta, plan.rate_after[w] * tau);
                 plan.t_after[w] = op.t;
                 scratch.last_op[w] = k;
             }
+            // the finished gradient step sets the speed of the worker's clock from here on
+            if (op.kind == A2CID_KIND_GRADIENT && op.clock_rate > 0.f) plan.rate_after[op.i] = (double)op.clock_rate;
         }
     }
     if (sync) {
         for (int32_t w = 0; w < n; ++w) {
             const int64_t k = scratch.last_op[w];
             if (k < 0) continue;
-            const float b = (float)mix_coefficient(eta, batch->t_sync - plan.t_after[w]);
+            const float b = (float)mix_coefficient(eta, plan.rate_after[w] * (batch->t_sync - plan.t_after[w]));
             if (batch->ops[k].i == w) plan.coef[k].b_post_i = b; else plan.coef[k].b_post_j = b;
             plan.t_after[w] = batch->t_sync;
         }
@@ -329,6 +335,11 @@ struct a2cid_sched {
     bool normalize = false;
     double unit = 1.0, dur_sum = 0.0, t_norm = 0.0, real_last = 0.0;
     int64_t dur_n = 0;
+    // the same per worker: stamps stay in real time, every gradient event carries the speed of its worker's own clock,
+    // 1 / (average duration of that worker's completed steps)
+    bool per_worker = false;
+    std::vector<double> own_sum;
+    std::vector<int64_t> own_n;
     std::vector<double> running;                 // duration of the gradient step each worker is in
 
     double uniform(uint64_t k, uint32_t stream, uint32_t tag) const {
@@ -361,10 +372,11 @@ struct a2cid_sched {
         return k - 1;
     }
 
-    void emit(double t, int32_t kind, int32_t i, int32_t j, int32_t clock) {
+    void emit(double t, int32_t kind, int32_t i, int32_t j, int32_t clock, float clock_rate = 0.f) {
         a2cid_op op;
         std::memset(&op, 0, sizeof(op));
         op.t = t; op.kind = kind; op.i = i; op.j = j;
+        op.clock_rate = clock_rate;
         op.id = serial++;
         ++fired[clock];
         emitted.push_back(op);
@@ -382,9 +394,15 @@ struct a2cid_sched {
         if (what == 0) {
             busy[w] = 0;
         } else {
-            emit(stamp, A2CID_KIND_GRADIENT, w, -1, w);
-            todo[w] += comm_count(w);
             finished = running[w];
+            float speed = 0.f;
+            if (per_worker) {
+                own_sum[w] += finished;
+                ++own_n[w];
+                speed = (float)(1.0 / (own_sum[w] / (double)own_n[w]));
+            }
+            emit(stamp, A2CID_KIND_GRADIENT, w, -1, w, speed);
+            todo[w] += comm_count(w);
             running[w] = step_time(w);
             completions.emplace(t + running[w], 1, w);
         }
@@ -810,23 +828,32 @@ int a2cid_graph_params(const a2cid_graph *graph, int32_t n, double *chi1, double
     return A2CID_OK;
 }
 
-int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
-                     const a2cid_event_batch *batch, a2cid_coef *coef) {
+int a2cid_plan_batch_clocks(int32_t n, const a2cid_graph *graph, double eta, double *t, double *rate,
+                            const a2cid_event_batch *batch, a2cid_coef *coef) {
     clear_error();
     if (!t) return fail(A2CID_EINVAL, "t is NULL");
     if (!(eta >= 0.0) || !std::isfinite(eta)) return fail(A2CID_EINVAL, "eta = %g must be finite and >= 0", eta);
+    if (rate)
+        for (int32_t i = 0; i < n; ++i)
+            if (!(rate[i] > 0.0) || !std::isfinite(rate[i])) return fail(A2CID_EINVAL, "rate[%d] must be finite and > 0", i);
     try {
         Graph g;
         if (int rc = load_graph(g, n, graph)) return rc;
         Plan plan;
         PlanScratch scratch;
-        if (int rc = plan_batch(g, eta, t, batch, plan, scratch)) return rc;
+        if (int rc = plan_batch(g, eta, t, rate, batch, plan, scratch)) return rc;
         if (coef && batch->n_ops > 0) std::memcpy(coef, plan.coef.data(), sizeof(a2cid_coef) * (size_t)batch->n_ops);
         std::copy(plan.t_after.begin(), plan.t_after.end(), t);
+        if (rate) std::copy(plan.rate_after.begin(), plan.rate_after.end(), rate);
     } catch (const std::bad_alloc &) {
         return fail(A2CID_ENOMEM, "out of host memory");
     }
     return A2CID_OK;
+}
+
+int a2cid_plan_batch(int32_t n, const a2cid_graph *graph, double eta, double *t,
+                     const a2cid_event_batch *batch, a2cid_coef *coef) {
+    return a2cid_plan_batch_clocks(n, graph, eta, t, nullptr, batch, coef);
 }
 
 int a2cid_plan_chain(int32_t n, const a2cid_event_batch *batch, int32_t lds_slots, a2cid_chain_step *steps,
@@ -951,6 +978,7 @@ int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *gra
         return fail(A2CID_EINVAL, "comm_per_grad = %g must be in [0, 700]", comm_per_grad);
     if (!(comm_time >= 0.0) || !std::isfinite(comm_time)) return fail(A2CID_EINVAL, "comm_time = %g must be >= 0", comm_time);
     if (!(jitter >= 0.0) || jitter >= 1.0) return fail(A2CID_EINVAL, "jitter = %g must be in [0, 1)", jitter);
+    if (normalize < 0 || normalize > 2) return fail(A2CID_EINVAL, "normalize must be 0, 1 or 2");
     a2cid_sched *s = new (std::nothrow) a2cid_sched;
     if (!s) return fail(A2CID_ENOMEM, "out of host memory");
     try {
@@ -979,7 +1007,10 @@ int a2cid_sched_create_fifo(a2cid_sched **out, int32_t n, const a2cid_graph *gra
             s->edge_of[(size_t)s->g.u[e] * n + s->g.v[e]] = (int32_t)e;
             s->edge_of[(size_t)s->g.v[e] * n + s->g.u[e]] = (int32_t)e;
         }
-        s->normalize = normalize != 0;
+        s->normalize = normalize == 1;
+        s->per_worker = normalize == 2;
+        s->own_sum.assign(n, 0.0);
+        s->own_n.assign(n, 0);
         s->running.assign(n, 0.0);
         double nominal = 0.0;
         int32_t active = 0;

@@ -36,6 +36,7 @@ double mix_coefficient(double eta, double tau);
 struct Plan {
     std::vector<a2cid_coef> coef;   // one per op
     std::vector<double> t_after;    // n time stamps after the batch
+    std::vector<double> rate_after; // n clock speeds after the batch
     int64_t n_gossip = 0, n_grad = 0, n_grad_xi = 0, n_grad_c = 0, n_grad_h = 0;
 };
 
@@ -45,7 +46,8 @@ struct PlanScratch {
     std::vector<int64_t> level_stamp;   // per worker: 1 + index of the last level that touched it
     std::vector<int64_t> last_op;       // per worker: index of its last op in the batch, or -1
 };
-int plan_batch(const Graph &g, double eta, const double *t_now, const a2cid_event_batch *batch,
+// rate_now: the speed of every worker's own clock (a2cid_op.clock_rate), or NULL for all 1.
+int plan_batch(const Graph &g, double eta, const double *t_now, const double *rate_now, const a2cid_event_batch *batch,
                Plan &plan, PlanScratch &scratch);
 
 // The chain kernel's programme for one launch: the order in which the operations are applied and where every

@@ -54,7 +54,7 @@ class Workload:
     """Device-side instance of a config: state, gradient inputs, scheduler and engine."""
 
     def __init__(self, cfg, device="cuda:0", batch_events=1024, xi_slots=None, reuse_xi=False, fifo=None, ld_pad=0):
-        """fifo = dict(comm_per_grad, comm_time, jitter) replaces the Poisson clocks by the first-in-first-out
+        """fifo = dict(comm_per_grad, comm_time, jitter[, normalize]) replaces the Poisson clocks by the first-in-first-out
         pairing source; the edge rate that enters chi_1, chi_2 is then comm_per_grad spread evenly over the edges
         (uniform pairing among neighbours, as the paper assumes when it computes them)."""
         import torch
@@ -115,6 +115,9 @@ class Workload:
             self.engine = binding.Engine(self.x, self.xt, d, self.u, self.v, self.edge_rate, self.eta,
                                          self.alpha, self.alpha_tilde)
         self.sched = binding.Scheduler(n, self.u, self.v, self.edge_rate, self.node_rate, cfg.seed, fifo=fifo)
+        if fifo is not None and fifo.get("normalize") == "worker":
+            # every worker's clock starts at its nominal step rate and then follows its own measured steps
+            self.engine.set_clock_rates(self.node_rate)
         self.events_done = 0
         self.t_last = 0.0
 

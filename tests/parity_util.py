@@ -57,6 +57,8 @@ class OracleStream:
             if cfg.curvature else None
         self.events = None
         self.done = 0
+        if fifo is not None and fifo.get("normalize") == "worker":
+            self.state.rate[:] = node_rate                  # the workers' own clocks start at their nominal step rates
 
     def generate(self, n_events):
         """The first n_events events of the stream (the oracle's own clock code, from time 0)."""
@@ -64,7 +66,7 @@ class OracleStream:
             from oracle import fifo as fifo_source
             self.events = fifo_source.generate(self.cfg.n, self.edges, self.node_rate, self.fifo["comm_per_grad"],
                                                self.fifo["comm_time"], self.fifo["jitter"], self.cfg.seed, n_events,
-                                               normalize=bool(self.fifo.get("normalize", False)))
+                                               normalize=self.fifo.get("normalize", False))
             return self.events
         self.events = core.generate_events(self.cfg.n, [e[0] for e in self.edges], [e[1] for e in self.edges],
                                            self.node_rate, np.full(len(self.edges), self.edge_rate), self.cfg.seed,

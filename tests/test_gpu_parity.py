@@ -435,13 +435,17 @@ def test_average_matches_oracle(name, d):
     w.close()
 
 
-@pytest.mark.parametrize("name,d,mode", [("C3", 6001, 1), ("C4", 5000, 2), ("C5", 4099, 1), ("C4", 4100, 3)])
-def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode):
-    # the paper's practical event source: Poisson count per gradient step + first-in-first-out pairing
-    fifo = dict(comm_per_grad=2.0 if name == "C3" else 1.0, comm_time=0.03, jitter=0.25,
-                normalize=name in ("C4", "C5"))          # C4, C5: events stamped with the normalised clock
+@pytest.mark.parametrize("name,d,mode,normalize", [("C3", 6001, 1, False), ("C4", 5000, 2, True), ("C5", 4099, 1, True),
+                                                   ("C4", 4100, 3, True), ("C5", 4099, 2, "worker"),
+                                                   ("C3", 3001, 3, "worker"), ("C5", 2050, 1, "worker"),
+                                                   ("C2", 5000, 0, "worker")])
+def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode, normalize):
+    # the paper's practical event source: Poisson count per gradient step + first-in-first-out pairing; events stamped
+    # in real time (False), with the common normalised clock (True), or in real time with every worker's own clock
+    # normalised by its own gradient steps ("worker": C5 has straggling workers, rates ~ LogNormal(0, 0.5))
+    fifo = dict(comm_per_grad=2.0 if name == "C3" else 1.0, comm_time=0.03, jitter=0.25, normalize=normalize)
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=3000)
-    _say(f"fifo source {name} d={d} mode={mode}")
+    _say(f"fifo source {name} d={d} mode={mode} normalize={normalize}")
     w = wl.Workload(cfg, batch_events=750, fifo=fifo)
     w.engine.set_tuning(1, 0, 256, mode)
     w.run(3000)
@@ -449,9 +453,14 @@ def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode):
     gx, gxt = w.columns(cols)
     st, ev = pu.oracle_run(cfg, cols, 3000, fifo=fifo)
     assert np.array_equal(w.engine.times(), st.t)
+    assert np.array_equal(w.engine.clock_rates(), st.rate)
+    if normalize == "worker":
+        assert len(np.unique(st.rate)) == cfg.n                # every worker ends up on a clock of its own
     assert pu.rel_err(gx, st.x) <= pu.TOL and pu.rel_err(gxt, st.xt) <= pu.TOL
     counts = w.sched.counts()
     assert counts.sum() == 3000 and np.array_equal(counts, np.bincount(ev.clock, minlength=len(counts)))
+    # the observables and the flush bring every worker to a common time of the shared clock, each at its own speed
+    pu.check_observables(w, st, float(ev.t[-1]) + 0.3, cols)
     w.close()
 
 

@@ -204,7 +204,7 @@ def test_empty_batch_is_fine():
 
 
 # ------------------------------------------------------------------ first-in-first-out pairing source
-@pytest.mark.parametrize("normalize", [False, True])
+@pytest.mark.parametrize("normalize", [False, True, "worker"])
 @pytest.mark.parametrize("topo,n,rho,comm_time,jitter,seed", [
     ("ring", 16, 1.0, 0.05, 0.2, 3), ("exponential", 64, 1.0, 0.02, 0.1, (5 << 32) + 1),
     ("complete", 8, 2.0, 0.0, 0.0, 7), ("ring", 64, 2.0, 0.01, 0.5, 11)])
@@ -226,7 +226,45 @@ def test_fifo_schedule_is_bit_identical_to_the_oracle_stream(topo, n, rho, comm_
         assert np.array_equal(b.ops["t"], ref.t[order])
         assert np.array_equal(b.ops["kind"], ref.kind[order])
         assert np.array_equal(b.ops["i"], ref.i[order]) and np.array_equal(b.ops["j"], ref.j[order])
+        # the speeds of the workers' own clocks: bit-equal fp32 values on gradient events, 0 elsewhere
+        want = ref.speed[order] if normalize == "worker" else np.zeros(len(order))
+        assert np.array_equal(b.ops["clock_rate"].astype(np.float64), want)
     assert np.array_equal(s.counts(), np.bincount(ref.clock, minlength=n + len(edges)))
+
+
+def test_plan_batch_with_worker_clocks_scales_every_workers_elapsed_time_by_its_own_speed():
+    n = 4
+    u, v = _uv(graph.ring(n))
+    eta = 0.8
+    ops = np.zeros(5, binding.OP_DTYPE)
+    ops["kind"] = [binding.KIND_GRADIENT, binding.KIND_GOSSIP, binding.KIND_GRADIENT, binding.KIND_GOSSIP, binding.KIND_GRADIENT]
+    ops["i"], ops["j"] = [0, 0, 2, 1, 0], [-1, 1, -1, 2, -1]
+    ops["t"] = [0.5, 0.9, 1.0, 1.6, 2.0]
+    ops["clock_rate"] = [2.5, 0.0, 0.0, 0.0, 0.25]        # worker 0 changes speed twice, worker 2 keeps its own
+    b = binding.Batch(ops, [0, 1, 2, 3, 4, 5], t_sync=3.0)
+    rate0 = np.array([0.5, 1.0, 3.0, 1.0])
+    t1, coef, rate1 = a2.a2cid_plan_batch(n, u, v, 1.0, eta, np.zeros(n), b, clock_rates=rate0)
+    bcoef = lambda tau: np.float32(0.5 * -np.expm1(-2.0 * eta * tau))
+    # worker 0: 0.5 elapsed at speed 0.5 (the new speed counts after the event), then 0.4 at 2.5, then 1.1 at 2.5, then
+    # the trailing mix of 1.0 at 0.25; worker 1: speed 1 throughout; worker 2: speed 3 throughout
+    assert coef["b_pre_i"][0] == bcoef(0.5 * 0.5)
+    assert coef["b_pre_i"][1] == bcoef(2.5 * 0.4) and coef["b_pre_j"][1] == bcoef(1.0 * 0.9)
+    assert coef["b_pre_i"][2] == bcoef(3.0 * 1.0)
+    assert coef["b_pre_i"][3] == bcoef(1.0 * 0.7) and coef["b_pre_j"][3] == bcoef(3.0 * 0.6)
+    assert coef["b_pre_i"][4] == bcoef(2.5 * 1.1)
+    assert coef["b_post_i"][4] == bcoef(0.25 * 1.0)
+    assert coef["b_post_i"][3] == bcoef(1.0 * 1.4) and coef["b_post_j"][3] == bcoef(3.0 * 1.4)
+    assert np.array_equal(rate1, [0.25, 1.0, 3.0, 1.0]) and np.all(t1[:3] == 3.0) and t1[3] == 0.0
+    # without speeds given every clock runs at 1, and changes made by the batch still count inside it
+    _, plain = a2.a2cid_plan_batch(n, u, v, 1.0, eta, np.zeros(n), b)
+    assert plain["b_pre_i"][0] == bcoef(0.5) and plain["b_pre_i"][1] == bcoef(2.5 * 0.4)
+    for bad in (-1.0, float("nan"), float("inf")):
+        wrong = ops.copy()
+        wrong["clock_rate"][2] = bad
+        with pytest.raises(a2.A2cidError):
+            a2.a2cid_plan_batch(n, u, v, 1.0, eta, np.zeros(n), binding.Batch(wrong, [0, 1, 2, 3, 4, 5]))
+    with pytest.raises(a2.A2cidError):
+        a2.a2cid_plan_batch(n, u, v, 1.0, eta, np.zeros(n), b, clock_rates=[1.0, 0.0, 1.0, 1.0])
 
 
 def test_fifo_scheduler_rejects_bad_parameters():
