@@ -8,7 +8,7 @@ A stream is cut into segments, one test each, so that a hang or a failure names 
 for long; the segments of one stream share a module-level run and must execute in order (pytest's default).  After
 every segment: state on the sampled columns within TOL (norm-wise, per worker and buffer), time stamps bit-equal,
 consensus distance of the sampled columns against the oracle's.  After the last one: the flushed state, the
-observables kernel against fp64 library reductions of the whole final state, and a record under gpurun_out/.
+observables kernel against fp64 library reductions of the whole final state, and a JSON record under OUT_DIR.
 The consensus-distance trace of configuration 4's two arms (accelerated parameters against eta = 0, same events, same
 noise) is the deliverable that configuration names; it is asserted against the oracle at every check point.
 """
