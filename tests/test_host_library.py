@@ -300,6 +300,8 @@ def test_engine_entry_points_fail_cleanly_without_touching_memory():
     assert lib.a2cid_stats_static(None, 0.0, None) == binding.EINVAL
     assert lib.a2cid_inplace_probe(None, 2, 8, None) == binding.EINVAL
     assert lib.a2cid_set_walk_occupancy(None, 4) == binding.EINVAL
+    assert lib.a2cid_set_resident_group(None, 8, 1) == binding.EINVAL
+    assert lib.a2cid_set_clock_rates(None, None) == binding.EINVAL and lib.a2cid_get_clock_rates(None, None) == binding.EINVAL
     assert lib.a2cid_profile_read_stats(None, None, None) == binding.EINVAL
     assert lib.a2cid_stream_probe(None, None, 16, None) == binding.EINVAL
     assert lib.a2cid_stream_probe(0x1000, 0x2000, 18, None) == binding.EINVAL
