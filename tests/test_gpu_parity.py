@@ -461,6 +461,13 @@ def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode, no
     assert counts.sum() == 3000 and np.array_equal(counts, np.bincount(ev.clock, minlength=len(counts)))
     # the observables and the flush bring every worker to a common time of the shared clock, each at its own speed
     pu.check_observables(w, st, float(ev.t[-1]) + 0.3, cols)
+    if normalize == "worker":
+        # so does the consensus step; one more stretch of mixing at the workers' own speeds comes before it
+        t_avg = float(ev.t[-1]) + 0.8
+        w.engine.average(t_avg)
+        st.average(t_avg)
+        ax, axt = w.columns(cols)
+        assert pu.rel_err(ax, st.x) <= pu.TOL and pu.rel_err(axt, st.xt) <= pu.TOL
     w.close()
 
 
