@@ -8,7 +8,9 @@
  * was last brought up to date.  Three kinds of update exist:
  *
  *   mixing flow  (x_i, xt_i) <- exp((t - t_i) [[-eta, eta], [eta, -eta]]) (x_i, xt_i)
- *                applied to a worker right before any jump that touches it (Algorithm 1);
+ *                applied to a worker right before any jump that touches it (Algorithm 1); the
+ *                elapsed time t - t_i is multiplied by the speed of worker i's own clock, which
+ *                is 1 unless the caller sets it (a2cid_op.clock_rate);
  *   gradient     x_i -= gamma g,  xt_i -= gamma g                  (Eq. (1), dN^i term)
  *                with g = gscale * h .* (x_i - c) + xi evaluated AFTER the mixing;
  *   gossip       m = x_i - x_j;  x_i -= alpha m;  x_j += alpha m;
