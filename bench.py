@@ -45,6 +45,14 @@ MEASURED_TRAFFIC = {
     ("C5", 1024, "resident_kernel"): (3.7909e10, "profiles/bench_C5_hbm_counters.md"),
 }
 
+# The resident kernel is bound by vector-ALU issue, not by memory: its roofline is the chip's fp32 vector rate.
+# Arithmetic of the method per column (one fused multiply-add = 2 flop): a gossip event mixes two workers (a subtraction
+# and two fused multiply-adds each), forms m (a subtraction) and applies four fused multiply-adds: 19 flop; a gradient
+# event mixes one worker (5), forms g = s (x - c) + xi (3) and applies two fused multiply-adds (4): 12 flop.
+# Peak: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 flop = 78.6 TFLOP/s with one fp32 operation per lane and cycle, twice
+# that (the published 157.3 TFLOP/s) only with packed two-wide fp32 instructions, which this build does not emit.
+FLOP_PER_COLUMN = {"gossip": 19.0, "gradient": 12.0}
+FP32_VECTOR_PEAK_TFLOPS = 157.3
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
@@ -288,11 +296,21 @@ def main():
         if not launches:
             return None
         achieved = cnt["moved_bytes"] / (kernel_ms * 1e-3) / 1e9
-        bound = "hbm" if kernel_name != "resident_kernel" else "instruction issue and level barriers (not HBM: see frac)"
         traffic, source = MEASURED_TRAFFIC.get((args.workload, args.batch, kernel_name), (None, None)) \
             if default_shape else (None, None)
-        return {"bound": bound, "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        head = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS}
+        if kernel_name == "resident_kernel":
+            # vector-ALU issue and the level barriers bound this kernel (SQ counters: profiles/): its HBM figures follow
+            # as hbm_GBs / frac_of_hbm_peak
+            flop = cfg.d * (FLOP_PER_COLUMN["gossip"] * cnt["gossip"] + FLOP_PER_COLUMN["gradient"] * cnt["gradient"])
+            tflops = flop / (kernel_ms * 1e-3) / 1e12
+            head = {"bound": "alu", "kernel": kernel_name, "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS,
+                    "unit": "TFLOP/s", "frac": tflops / FP32_VECTOR_PEAK_TFLOPS,
+                    "frac_of_unpacked_fp32_peak": tflops / (FP32_VECTOR_PEAK_TFLOPS / 2),
+                    "alg_flop_per_launch": flop / launches,
+                    "hbm_GBs": achieved, "frac_of_hbm_peak": achieved / HBM_PEAK_GBS}
+        return {**head,
                 "traffic": traffic,
                 "traffic_source": None if traffic is None else
                 f"{source}: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command, scaled by the "
