@@ -244,16 +244,22 @@ def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit(name, d
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=900)
     cols = np.arange(cfg.d)
     results = []
-    for batch, tuning, slots in [(900, None, None), (128, (1, 0, 256, 3), None), (512, (1, 0, 256, 1), None),
-                                 (300, (4, 1, 64, 0), None), (77, (2, 0, 128, 1), None), (450, (1, 0, 256, 2), None),
-                                 (900, (1, 0, 256, 3), 0), (211, (2, 0, 64, 3), 5), (640, (1, 0, 128, 3), 1),
-                                 (333, (1, 0, 256, 2), None)]:
-        _say(f"{name} batching {batch} tuning {tuning} slots {slots}")
+    # (events per batch, a2cid_set_tuning arguments, chain slots, resident shape (waves, columns per lane))
+    for batch, tuning, slots, shape in [(900, None, None, None), (128, (1, 0, 256, 3), None, None),
+                                        (512, (1, 0, 256, 1), None, None), (300, (4, 1, 64, 0), None, None),
+                                        (77, (2, 0, 128, 1), None, None), (450, (1, 0, 256, 2), None, None),
+                                        (900, (1, 0, 256, 3), 0, None), (211, (2, 0, 64, 3), 5, None),
+                                        (640, (1, 0, 128, 3), 1, None), (333, (1, 0, 256, 2), None, (8, 1)),
+                                        (900, (1, 0, 256, 2), None, (16, 2)), (250, (1, 0, 256, 2), None, (4, 4)),
+                                        (600, (1, 0, 256, 2), None, (2, 1)), (450, (1, 0, 256, 2), None, (16, 4))]:
+        _say(f"{name} batching {batch} tuning {tuning} slots {slots} shape {shape}")
         w = wl.Workload(cfg, batch_events=batch)
         if tuning:
             w.engine.set_tuning(*tuning)
         if slots is not None:
             w.engine.set_chain_slots(slots)
+        if shape is not None:
+            w.engine.set_resident_group(*shape)
         w.run(900)
         results.append(w.columns(cols) + (w.engine.times(),))
         w.close()

@@ -721,3 +721,45 @@ def test_resident_programme_checker_notices_planted_mistakes():
         with pytest.raises((AssertionError, IndexError, KeyError)):
             _run_resident_launch(n, b, coef, mutated(change), 0, False)
     s.close()
+
+
+def test_resident_programmes_on_arbitrary_small_batches():
+    """Property test: whatever the batch and the launch shape, the launches together apply every operation once, in an
+    order the checker accepts."""
+    hyp = pytest.importorskip("hypothesis")
+    from hypothesis import strategies as st
+
+    @st.composite
+    def cases(draw):
+        n = draw(st.integers(2, 9))
+        m = draw(st.integers(1, 60))
+        rng = np.random.default_rng(draw(st.integers(0, 2 ** 20)))
+        ops = _random_ops(rng, n, m, draw(st.sampled_from([0.0, 0.3, 1.0])))
+        ops["gamma"], ops["t"] = 0.1, np.sort(rng.uniform(0.0, 5.0, m))
+        ops["xi"] = np.where(ops["kind"] == binding.KIND_GRADIENT, 4096 * (1 + np.arange(m)), 0)
+        ops["c"] = ops["h"] = 0
+        # levels: greedy, as the scheduler packs them
+        level, last = np.zeros(m, np.int64), {}
+        for k in range(m):
+            ws = [int(ops["i"][k])] + ([int(ops["j"][k])] if ops["kind"][k] == binding.KIND_GOSSIP else [])
+            level[k] = 1 + max([last.get(w, -1) for w in ws])
+            for w in ws:
+                last[w] = level[k]
+        order = np.argsort(level, kind="stable")
+        ops = ops[order]
+        off = np.concatenate([[0], np.cumsum(np.bincount(level))])
+        sync = draw(st.booleans())
+        return n, ops, off, sync, draw(st.sampled_from([1, 2, 4, 8, 16])), draw(st.sampled_from([1, 2, 4]))
+
+    @hyp.settings(max_examples=150, deadline=None)
+    @hyp.given(cases())
+    def check(case):
+        n, ops, off, sync, waves, cols = case
+        if waves == 1:
+            cols = 1
+        b = binding.Batch(ops, off, t_sync=6.0 if sync else float("nan"))
+        u, v = _uv(graph.complete(n))
+        _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
+        _resident_plans_cover(n, b, coef, waves, cols)
+
+    check()
