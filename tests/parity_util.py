@@ -128,6 +128,10 @@ class SlicedOracle:
     def t(self):
         return self.parts[0].state.t
 
+    @property
+    def rate(self):
+        return self.parts[0].state.rate
+
     def rows(self):
         """(x, xt) on all sampled columns, as stored (each worker at its own time stamp)."""
         return (np.concatenate([o.state.x for o in self.parts], axis=1),

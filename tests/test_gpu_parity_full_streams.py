@@ -36,8 +36,22 @@ OUT_DIR = os.path.join(ROOT, "gpurun_out", "full_streams")
 # configuration 4, which takes the chain kernel so that both kernels are followed over 10^6 events at 64 workers.  The kernels give the same
 # state bit for bit (test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit), so the two arms of
 # configuration 4 remain comparable.
-PLAN = [("C2", 2, 50_000), ("C3", 2, 100_000), ("C4", 2, 100_000), ("C4-baseline", 3, 100_000), ("C5", 2, 200_000)]
+PLAN = [("C2", 2, 50_000), ("C3", 2, 100_000), ("C4", 2, 100_000), ("C4-baseline", 3, 100_000), ("C5", 2, 200_000),
+        ("C5-fifo", 2, 100_000)]
 BATCH = 1024                # events per a2cid_apply_events call: the launch configuration bench.py times
+
+# One more stream at full size: configuration 5's straggling workers (gradient rates ~ LogNormal(0, 0.5)) driven by the
+# paper's practical event source instead of the Poisson clocks -- gradient steps back to back, a Poisson number of
+# averagings per step, first-in-first-out pairing -- with every worker's clock normalised by its own gradient steps.
+FIFO_RUNS = {"C5-fifo": ("C5", 300_000, dict(comm_per_grad=1.0, comm_time=0.02, jitter=0.25, normalize="worker"))}
+
+
+def _config(name):
+    """(configuration, number of events, options of the first-in-first-out source or None) of a PLAN entry."""
+    if name in FIFO_RUNS:
+        base, events, fifo = FIFO_RUNS[name]
+        return wl.scaled(wl.CONFIGS[base], events=events), events, fifo
+    return wl.CONFIGS[name], wl.CONFIGS[name].events, None
 
 
 def _say(msg):
@@ -47,13 +61,14 @@ def _say(msg):
 class Run:
     def __init__(self, name, mode):
         self.name, self.mode = name, mode
-        self.cfg = cfg = wl.CONFIGS[name]
+        self.cfg, _, self.fifo = _config(name)
+        cfg = self.cfg
         self.cols = pu.sample_columns(cfg.d, 4096, seed=7)
         t0 = time.perf_counter()
-        self.oracle = pu.SlicedOracle(cfg, self.cols, threads=4)
+        self.oracle = pu.SlicedOracle(cfg, self.cols, threads=4, fifo=self.fifo)
         self.ev = self.oracle.generate(cfg.events)
         assert len(self.ev) == cfg.events
-        self.w = wl.Workload(cfg, batch_events=BATCH)
+        self.w = wl.Workload(cfg, batch_events=BATCH, fifo=self.fifo)
         self.w.engine.set_tuning(1, 0, 256, mode)
         self.done = 0
         self.failed = False
@@ -93,6 +108,7 @@ class Run:
         t_now = float(self.ev.t[upto - 1])
         got = core.State(gx, gxt, eta=w.eta)
         got.t[:] = times
+        got.rate[:] = w.engine.clock_rates()
         mgx, mgxt = got.flushed(t_now)
         mox, moxt = self.oracle.flushed(t_now)
         return {"t_now": t_now, "times": times, "rows": (gx, gxt, ox, oxt), "mixed": (mgx, mgxt, mox, moxt),
@@ -135,6 +151,7 @@ class Run:
              f"sampled consensus x {cg:.9g} (oracle {co:.9g}, rel {abs(cg - co) / co:.1e})  whole state "
              f"{gs['consensus_x']:.6g}  gpu {self.gpu_seconds:.1f} s")
         assert check["times_equal"]
+        assert np.array_equal(w.engine.clock_rates(), self.oracle.rate)       # all 1 unless the source sets them
         assert ex <= pu.TOL and ext <= pu.TOL
         pu.assert_consensus(cg, co, mgx, mox, "x, sampled columns")
         pu.assert_consensus(cgt, cot, mgxt, moxt, "xt, sampled columns")
@@ -207,7 +224,7 @@ def _run_for(name, mode):
 def _params():
     out = []
     for name, mode, seg in PLAN:
-        total = wl.CONFIGS[name].events
+        total = _config(name)[1]
         for upto in range(seg, total + 1, seg):
             out.append(pytest.param(name, mode, upto, id=f"{name}-{upto:07d}"))
         out.append(pytest.param(name, mode, -1, id=f"{name}-end"))
@@ -219,7 +236,7 @@ def test_whole_stream_follows_the_oracle(name, mode, upto):
     run = _run_for(name, mode)
     if run.failed:
         pytest.skip("an earlier segment of this stream failed")
-    expected_done = wl.CONFIGS[name].events if upto < 0 else upto - dict((p[0], p[2]) for p in PLAN)[name]
+    expected_done = _config(name)[1] if upto < 0 else upto - dict((p[0], p[2]) for p in PLAN)[name]
     if run.done != expected_done:
         pytest.skip(f"the segments of a stream run in order ({run.done} events done, {expected_done} expected)")
     try:
