@@ -53,13 +53,15 @@ MEASURED_TRAFFIC = {
 # that (the published 157.3 TFLOP/s) only with packed two-wide fp32 instructions, which this build does not emit.
 FLOP_PER_COLUMN = {"gossip": 19.0, "gradient": 12.0}
 FP32_VECTOR_PEAK_TFLOPS = 157.3
-MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel"}
+MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel", 4: "regfile_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
              2: "resident_kernel (the library's choice for up to 160 workers): every touched row stays in LDS for the "
                 "whole batch (state read and written once per batch)",
              3: "chain_kernel (the library's choice for more than 160 workers): events re-ordered so "
-                "that a worker's columns are found in registers or parked in LDS as often as possible"}
+                "that a worker's columns are found in registers or parked in LDS as often as possible",
+             4: "regfile_kernel (up to 64 workers): a wave keeps its 64 columns of every worker's x and xt in vector "
+                "registers for the whole batch (state read and written once per batch, no LDS, no barrier)"}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -300,7 +302,7 @@ def main():
             if default_shape else (None, None)
         head = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS}
-        if kernel_name == "resident_kernel":
+        if kernel_name in ("resident_kernel", "regfile_kernel"):
             # vector-ALU issue and the level barriers bound this kernel (SQ counters: profiles/): its HBM figures follow
             # as hbm_GBs / frac_of_hbm_peak
             flop = cfg.d * (FLOP_PER_COLUMN["gossip"] * cnt["gossip"] + FLOP_PER_COLUMN["gradient"] * cnt["gradient"])

@@ -92,6 +92,7 @@ struct a2cid_ctx {
     int resident_cols = 1;              // resident kernel: columns per lane (1, 2 or 4) when group != 0
     int order = 0;                      // 0: jumps after the mixing (Eq. (1)); 1: Algorithm 1's listing order
     ResidentPlan resplan;               // resident kernel: the launch being planned
+    RegPlan regplan;                    // register-file kernel: the launch being planned
     int stats_v = 2, stats_r = 2, stats_blocks = 2048, stats_nt = 1;   // launch shape of the observables kernel
     bool failed = false;                // an enqueueing step failed half-way: device state and time stamps disagree
     // observables scratch
@@ -414,6 +415,75 @@ int enqueue_resident(a2cid_ctx *c, const a2cid_event_batch *batch, int32_t *l, i
     return A2CID_OK;
 }
 
+// One launch of regfile_kernel: writes the programme for the operations of the batch from operation *k on, as many as
+// a staging buffer holds (plan_regfile), uploads it and launches the kernel.  On return *k names the first operation
+// not included.
+int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, int64_t *k) {
+    Slot *s;
+    if (int rc = acquire_slot(c, &s)) return rc;
+    const int64_t k_before = *k;
+    plan_regfile(c->n, batch, c->plan.coef.data(), kResRecords, k, c->regplan);
+    if (*k == k_before) return fail(A2CID_EINVAL, "internal: an operation does not fit an empty register-file programme");
+    const RegPlan &rp = c->regplan;
+    const int32_t n_grad = (int32_t)rp.grad_op.size();
+    if ((int64_t)rp.programme.size() > kResRecords || n_grad > kSlotOps)
+        return fail(A2CID_EINVAL, "internal: register-file plan exceeds its staging buffers");
+    std::memcpy(s->res_host, rp.programme.data(), rp.programme.size() * sizeof(ResSlot));
+    // The input table: per chunk of kRegChunk gradient events 8 pointers each for xi, c and h, and one chunk more than
+    // the events fill (the kernel requests two chunks ahead).  Absent inputs and the ordinals past the last event:
+    // the address of the context's zero (or one) with bit 0 set, read by every lane alike.
+    const uint64_t zeros = (uint64_t)(uintptr_t)c->zero_dev | 1u, ones = (uint64_t)(uintptr_t)(c->zero_dev + 1) | 1u;
+    const int32_t n_chunks = (n_grad + kRegChunk - 1) / kRegChunk + 1;
+    uint64_t *table = reinterpret_cast<uint64_t *>(s->gin_host);
+    static_assert(sizeof(GradIn) == 3 * sizeof(uint64_t), "the chunk table reuses the GradIn staging buffer");
+    if ((int64_t)n_chunks * 3 * kRegChunk > kSlotOps * 3)
+        return fail(A2CID_EINVAL, "internal: register-file input table exceeds its staging buffer");
+    for (int32_t g = 0; g < n_chunks * kRegChunk; ++g) {
+        uint64_t *at = table + (size_t)(g / kRegChunk) * 3 * kRegChunk + g % kRegChunk;
+        at[0] = zeros; at[kRegChunk] = zeros; at[2 * kRegChunk] = ones;
+        if (g >= n_grad) continue;
+        const a2cid_op &op = batch->ops[rp.grad_op[(size_t)g]];
+        const bool affine = op.gscale != 0.f;
+        if (op.xi) at[0] = (uint64_t)(uintptr_t)op.xi;
+        if (op.c && affine) at[kRegChunk] = (uint64_t)(uintptr_t)op.c;
+        if (op.h && affine) at[2 * kRegChunk] = (uint64_t)(uintptr_t)op.h;
+    }
+    A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * rp.programme.size(), hipMemcpyHostToDevice,
+                             c->stream));
+    A2CID_HIP(hipMemcpyAsync(s->gin_dev, table, sizeof(uint64_t) * 3 * kRegChunk * (size_t)n_chunks, hipMemcpyHostToDevice,
+                             c->stream));
+    const int n_rows = __builtin_popcountll(rp.touched);
+    c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (rp.n_xi + rp.n_c + rp.n_h));
+    TimedLaunch tl{};
+    if (c->profiling) {
+        if (int rc = get_event(c, &tl.start)) return rc;
+        if (int rc = get_event(c, &tl.stop)) return rc;
+        A2CID_HIP(hipEventRecord(tl.start, c->stream));
+    }
+    const unsigned blocks = (unsigned)((c->d + 63) / 64);
+#define A2CID_REG(PRE, FULL)                                                                                            \
+    hipLaunchKernelGGL((regfile_kernel<PRE, FULL>), dim3(blocks), dim3(64), 0, c->stream, c->x, c->xt, c->ld, c->d,    \
+                       s->res_dev, (uint32_t)(rp.programme.size() * sizeof(ResSlot)),                                   \
+                       reinterpret_cast<const uint64_t *>(s->gin_dev), (uint32_t)(n_chunks - 1), rp.touched,           \
+                       (float)c->alpha, (float)c->alpha_t)
+    switch ((c->order != 0 ? 2 : 0) | ((rp.n_c > 0 || rp.n_h > 0) ? 1 : 0)) {
+        case 0: A2CID_REG(false, false); break;
+        case 1: A2CID_REG(false, true); break;
+        case 2: A2CID_REG(true, false); break;
+        default: A2CID_REG(true, true); break;
+    }
+#undef A2CID_REG
+    A2CID_HIP(hipGetLastError());
+    if (c->profiling) {
+        A2CID_HIP(hipEventRecord(tl.stop, c->stream));
+        c->timed.push_back(tl);
+    }
+    ++c->n_launch;
+    A2CID_HIP(hipEventRecord(s->done, c->stream));
+    s->in_flight = true;
+    return A2CID_OK;
+}
+
 // Mixing every worker whose coefficient is non-zero, as one level of mix-only operations.
 int enqueue_mix_all(a2cid_ctx *c, const std::vector<float> &b) {
     int32_t done = 0;
@@ -639,6 +709,12 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
             if (k >= batch->level_off[l + 1]) { ++l; continue; }
             if (int rc = enqueue_resident(c, batch, &l, &k, trailing)) return rc;
         }
+        return A2CID_OK;
+    }
+    if (mode == 4) {
+        int64_t k = 0;
+        while (k < batch->n_ops)
+            if (int rc = enqueue_regfile(c, batch, &k)) return rc;
         return A2CID_OK;
     }
     int32_t l = 0;
@@ -947,8 +1023,10 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     if (unroll != 1 && unroll != 2 && unroll != 4) return fail(A2CID_EINVAL, "unroll must be 1, 2 or 4");
     if (threads != 64 && threads != 128 && threads != 256 && threads != 512 && threads != 1024)
         return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
-    if (mode < -1 || mode > 3)
-        return fail(A2CID_EINVAL, "mode must be -1 (automatic), 0 (levels), 1 (walk), 2 (resident) or 3 (chain)");
+    if (mode < -1 || mode > 4)
+        return fail(A2CID_EINVAL, "mode must be -1 (automatic), 0 (levels), 1 (walk), 2 (resident), 3 (chain) or 4 (register file)");
+    if (mode == 4 && (c->n > kRegMaxRows || c->d > ((int64_t)1 << 30)))
+        return fail(A2CID_EINVAL, "the register-file kernel holds at most %d workers of at most 2^30 parameters", kRegMaxRows);
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
     if ((mode == 3 || mode == -1) && (size_t)c->chain_slots * unroll * threads * 32 > 160 * 1024)

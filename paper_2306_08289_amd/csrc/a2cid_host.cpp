@@ -779,6 +779,57 @@ void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *
     }
 }
 
+void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, int64_t *k,
+                  RegPlan &plan) {
+    (void)n;
+    plan.programme.clear();
+    plan.grad_op.clear();
+    plan.touched = 0;
+    plan.n_xi = plan.n_c = plan.n_h = 0;
+    auto f2u = [](float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; };
+    const ResSlot filler = {kRegControl << 8, 0u, 0u, 0u};
+    auto whole_blocks = [](size_t slots) { return (slots + kRegBlock - 1) / kRegBlock * kRegBlock; };
+    auto &prog = plan.programme;
+    for (; *k < batch->n_ops; ++*k) {
+        const a2cid_op &op = batch->ops[*k];
+        const a2cid_coef &cf = coef[*k];
+        const bool is_grad = op.kind == A2CID_KIND_GRADIENT;
+        // a gradient event that opens a chunk of inputs (not the first) comes after a switch slot, in a new block
+        const bool opens = is_grad && !plan.grad_op.empty() && plan.grad_op.size() % kRegChunk == 0;
+        const size_t at = opens ? whole_blocks(prog.size() + 1) : prog.size();
+        const size_t need = 1 + (cf.b_post_i != 0.f) + (!is_grad && cf.b_post_j != 0.f);
+        if ((int64_t)whole_blocks(at + need + 1) > max_slots) break;        // the end slot still has to fit
+        if (opens) {
+            ResSlot sw = filler;
+            sw.y = kRegSwitch;
+            prog.push_back(sw);
+            prog.resize(at, filler);
+        }
+        ResSlot r = {0u, 0u, 0u, 0u};
+        plan.touched |= (uint64_t)1 << op.i;
+        if (!is_grad) {
+            plan.touched |= (uint64_t)1 << op.j;
+            r.x = (uint32_t)op.i | kRegGossip << 8;
+            r.y = (uint32_t)op.j;
+            r.z = f2u(cf.b_pre_i); r.w = f2u(cf.b_pre_j);
+        } else {
+            r.x = (uint32_t)op.i | kRegGradient << 8;
+            r.y = f2u(cf.b_pre_i); r.z = f2u(op.gamma); r.w = f2u(op.gscale);
+            plan.n_xi += op.xi != nullptr;
+            plan.n_c += op.c && op.gscale != 0.f;
+            plan.n_h += op.h && op.gscale != 0.f;
+            plan.grad_op.push_back(*k);
+        }
+        prog.push_back(r);
+        if (cf.b_post_i != 0.f) prog.push_back(ResSlot{(uint32_t)op.i | kRegMix << 8, f2u(cf.b_post_i), 0u, 0u});
+        if (!is_grad && cf.b_post_j != 0.f) prog.push_back(ResSlot{(uint32_t)op.j | kRegMix << 8, f2u(cf.b_post_j), 0u, 0u});
+    }
+    ResSlot end_slot = filler;
+    end_slot.y = kRegEnd;
+    prog.push_back(end_slot);
+    prog.resize(whole_blocks(prog.size()), filler);
+}
+
 }  // namespace a2cid
 
 extern "C" {

@@ -131,4 +131,35 @@ void resident_shape(int32_t n, const a2cid_event_batch *batch, int *waves, int *
 void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int waves, int cols,
                    bool trailing, int32_t *l, int64_t *k, ResidentPlan &plan);
 
+// ---- The register-file kernel's programme for one launch (planner: a2cid_host.cpp, kernel: a2cid_kernels.hip.h) ----
+// One wave owns 64 columns and keeps its column of every worker's x and xt in vector registers for the whole launch
+// (worker r in register r and 64 + r: at most kRegMaxRows workers).  All waves run the same linear programme of
+// 16-byte slots, fetched with scalar loads in blocks of kRegBlock slots; a slot's kind is x >> 8:
+//   gossip:    x = i, y = j, z = b_i, w = b_j (fp32 bits)
+//   gradient:  x = i | kRegGradient << 8, y = b_i, z = gamma, w = gscale; its inputs are entry (ordinal % kRegChunk)
+//              of the current chunk of gradient inputs (the launch's gradient events in programme order, kRegChunk
+//              to a chunk, named by the GradIn table)
+//   mix:       x = i | kRegMix << 8, y = b (a trailing mix, right after its operation)
+//   control:   x = kRegControl << 8, y = kRegSwitch (the next gradient event opens the next chunk; the rest of the
+//              block is skipped), kRegEnd (end of the programme) or 0 (filler)
+// Every slot is applied in order; any order that keeps each worker's own operations in sequence gives the same
+// bits, and the planner keeps the batch's.
+enum : uint32_t { kRegGossip = 0, kRegGradient = 1, kRegMix = 2, kRegControl = 3 };
+enum : uint32_t { kRegSwitch = 1, kRegEnd = 2 };
+constexpr int kRegBlock = 8;             // slots per scalar fetch
+constexpr int kRegChunk = 8;             // gradient events per chunk of inputs (two chunks are held in registers)
+constexpr int32_t kRegMaxRows = 64;
+
+struct RegPlan {
+    std::vector<ResSlot> programme;
+    std::vector<int64_t> grad_op;       // gradient ordinal -> index of the event in the batch
+    uint64_t touched = 0;               // bit r: worker r is read and written by the launch
+    int32_t n_xi = 0, n_c = 0, n_h = 0; // gradient inputs the launch reads
+};
+// Writes the programme for the operations of the batch from *k on, as many as max_slots slots hold (at least one
+// block more than the longest single operation needs).  On return *k names the first operation not included.
+// The batch must be valid (plan_batch passed) and n <= kRegMaxRows.
+void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, int64_t *k,
+                  RegPlan &plan);
+
 }  // namespace a2cid

@@ -789,6 +789,276 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 }
 
 // ------------------------------------------------------------------------------------------
+// Register-file kernel: grid = tiles of 64 columns, one wave per workgroup, one launch per batch (or piece of one).
+// The ownership argument taken to its end: with at most 64 workers a lane can hold its column of EVERY worker's x
+// and xt in vector registers (worker r: v[r] and v[64 + r]), so a wave loads its 64 columns of the touched rows once,
+// applies the whole programme to registers and stores the rows back: no LDS, no barrier, nothing shared between waves
+// but the (read-only) programme.  Which register an operation touches is only known at run time, so the operations
+// address the register file relatively: S_SET_GPR_IDX_ON adds a scalar index (the low 8 bits of its operand) to
+// chosen operands of the vector instructions that follow, here to the operands written as v0 (x), v64 (xt) and
+// v128 / v144 / v160 (gradient inputs).  Only s_set_gpr_idx_on / s_set_gpr_idx_off bracket the indexed instructions,
+// the forms the compiler itself emits for dynamically indexed vectors.
+//
+// The operation loop is one asm statement with a fixed register map, because the register allocator cannot be made
+// to keep four 32-register blocks in place across compiler-visible control flow:
+//   v[0:63] x, v[64:127] xt of the 64 workers (the statement's in/out operands, pinned by their constraints)
+//   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
+//   FULL only: v[144:151], v[152:159] the sets of centres c, v[160:167], v[168:175] of curvatures h
+//   v[TB .. TB+10]           temporaries (TB = 144, FULL: 176)
+//   s[40:71] the current block of 8 slots, s[72:87] eight input pointers, s88 byte position in the programme,
+//   s89, s93 scratch, s90 index of the next gradient event's inputs (set offset included), s91 offset of the set in
+//   use (0 or 8), s92 the chunk to request next
+// Programme (layout: a2cid_internal.h): every slot is applied in order; a gossip slot (the common case) falls
+// through its kind test, the other kinds are handled out of line.  The loop ends at the end slot, and in any case
+// when the position reaches the programme's length.
+// Gradient inputs: chunk k of kRegChunk events uses set k % 2.  A switch slot precedes the first event of every chunk
+// but the first: the wave waits for the other set (requested a whole chunk ago; nothing else is in flight), requests
+// chunk k + 2 into the set just used up, and goes on with the next block (the planner leaves the rest of the block
+// empty).  The input table holds, per chunk, 8 pointers each for xi, c and h (192 bytes); a pointer with bit 0 set
+// is the address of one float that stands for every column (absent input); ordinals past the last event repeat a
+// valid entry, and the chunk index is clamped to the table's last.
+// The arithmetic is the shared sequence of individually rounded operations (mix, gossip_jump, gradient_jump: the
+// same subtractions and fused multiply-adds in the same order), so results agree bit for bit with the other kernels.
+// Valid only while every gradient input of the batch is final when the batch is submitted, like the resident kernel.
+// ------------------------------------------------------------------------------------------
+typedef float v32f __attribute__((ext_vector_type(32)));
+typedef __attribute__((address_space(1))) float *global_out_f32;
+
+// A uniform address as the compiler must take it: a scalar base, to which a lane adds its 32-bit offset in the
+// load or store instruction itself (left to itself the compiler folds the lane's offset in first and then keeps
+// one 64-bit address per row in vector registers, 256 of them).
+__device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
+    const uintptr_t v = (uintptr_t)p;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (uintptr_t)lo | (uintptr_t)hi << 32;
+}
+
+#define A2R_T(TB, k) "v[" TB "+" #k "]"
+#define A2R_ON(idx, mode) "s_set_gpr_idx_on " idx ", gpr_idx(" mode ")\n\t"
+#define A2R_OFF "s_set_gpr_idx_off\n\t"
+// temporaries: 0 di, 1 dj, 2 xi, 3 ti, 4 xj, 5 tj, 6 m, 7 g, 8 u / stored x, 9 slope, 10 lane offset of a request
+
+// mix of workers X (i) and Y (j) to the event time, difference m, the four jumps; Z = b_i, W = b_j
+#define A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                              \
+    A2R_ON(X, "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                                \
+    A2R_ON(Y, "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 1) ", v64, v0\n\t"                                                \
+    A2R_ON(X, "SRC2") "v_fma_f32 " A2R_T(TB, 2) ", " Z ", " A2R_T(TB, 0) ", v0\n\t"                                 \
+                      "v_fma_f32 " A2R_T(TB, 3) ", -" Z ", " A2R_T(TB, 0) ", v64\n\t"                               \
+    A2R_ON(Y, "SRC2") "v_fma_f32 " A2R_T(TB, 4) ", " W ", " A2R_T(TB, 1) ", v0\n\t"                                 \
+                      "v_fma_f32 " A2R_T(TB, 5) ", -" W ", " A2R_T(TB, 1) ", v64\n\t"
+#define A2R_GOSSIP_JUMP(TB, X, Y)                                                                                   \
+    A2R_ON(X, "DST") "v_fma_f32 v0, %[nal], " A2R_T(TB, 6) ", " A2R_T(TB, 2) "\n\t"                                 \
+                     "v_fma_f32 v64, %[nalt], " A2R_T(TB, 6) ", " A2R_T(TB, 3) "\n\t"                               \
+    A2R_ON(Y, "DST") "v_fma_f32 v0, %[al], " A2R_T(TB, 6) ", " A2R_T(TB, 4) "\n\t"                                  \
+                     "v_fma_f32 v64, %[alt], " A2R_T(TB, 6) ", " A2R_T(TB, 5) "\n\t"                                \
+    A2R_OFF
+// m after the mixing (Eq. (1)): a two-operand instruction, untouched by the SRC2 mode still in force
+#define A2R_GOSSIP_0(TB, X, Y, Z, W)                                                                                \
+    A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                                  \
+    "v_sub_f32 " A2R_T(TB, 6) ", " A2R_T(TB, 2) ", " A2R_T(TB, 4) "\n\t"                                            \
+    A2R_GOSSIP_JUMP(TB, X, Y)
+// m from the stored values (Algorithm 1 as listed)
+#define A2R_GOSSIP_1(TB, X, Y, Z, W)                                                                                \
+    A2R_ON(Y, "SRC0") "v_mov_b32 " A2R_T(TB, 6) ", v0\n\t"                                                          \
+    A2R_ON(X, "SRC0") "v_sub_f32 " A2R_T(TB, 6) ", v0, " A2R_T(TB, 6) "\n\t"                                        \
+    A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                                  \
+    A2R_GOSSIP_JUMP(TB, X, Y)
+
+// gradient event of worker s93 (index), Y = b_i, Z = gamma, W = gscale; inputs at index s90
+#define A2R_STORED_2(TB)
+#define A2R_STORED_8(TB) A2R_ON("s93", "SRC0") "v_mov_b32 " A2R_T(TB, 8) ", v0\n\t"
+#define A2R_GRAD_HEAD(TB, Y, AT)                                                                                    \
+    A2R_ON("s93", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
+    A2R_STORED_##AT(TB)                                                                                             \
+    A2R_ON("s93", "SRC2") "v_fma_f32 " A2R_T(TB, 2) ", " Y ", " A2R_T(TB, 0) ", v0\n\t"                             \
+                          "v_fma_f32 " A2R_T(TB, 3) ", -" Y ", " A2R_T(TB, 0) ", v64\n\t"
+#define A2R_GRAD_TAIL(TB, Z)                                                                                        \
+    A2R_ON("s93", "DST") "v_fma_f32 v0, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 2) "\n\t"                             \
+                         "v_fma_f32 v64, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 3) "\n\t"                            \
+    A2R_OFF "s_add_u32 s90, s90, 1\n\t"
+// g = gscale x + xi (no centre, no curvature); AT = 2: at the mixed point, 8: at the stored point
+#define A2R_GRAD_PLAIN(TB, Y, Z, W, AT)                                                                             \
+    A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
+    A2R_ON("s90", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " W ", " A2R_T(TB, AT) ", v128\n\t"                          \
+    A2R_GRAD_TAIL(TB, Z)
+// g = (gscale h) (x - c) + xi
+#define A2R_GRAD_FULL(TB, Y, Z, W, AT)                                                                              \
+    A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
+    A2R_ON("s90", "SRC1") "v_sub_f32 " A2R_T(TB, 8) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
+                          "v_mul_f32 " A2R_T(TB, 9) ", " W ", v160\n\t"                                             \
+    A2R_ON("s90", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " A2R_T(TB, 9) ", " A2R_T(TB, 8) ", v128\n\t"                \
+    A2R_GRAD_TAIL(TB, Z)
+#define A2R_MIX(TB, Y)                                                                                              \
+    A2R_ON("s93", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
+    A2R_ON("s93", "SRC2,DST") "v_fma_f32 v0, " Y ", " A2R_T(TB, 0) ", v0\n\t"                                       \
+                              "v_fma_f32 v64, -" Y ", " A2R_T(TB, 0) ", v64\n\t"                                    \
+    A2R_OFF
+
+// one slot in line: a gossip operation falls through
+#define A2R_SLOT(TB, GOSSIP, id, X, Y, Z, W)                                                                        \
+    "s_cmp_lt_u32 " X ", 0x100\n\t"                                                                                 \
+    "s_cbranch_scc0 L_o" id "_%=\n\t"                                                                               \
+    GOSSIP(TB, X, Y, Z, W)                                                                                          \
+    "\nL_d" id "_%=:\n\t"
+// the other kinds of the same slot, out of line
+#define A2R_OTHER(TB, GRAD, AT, id, X, Y, Z, W)                                                                     \
+    "\nL_o" id "_%=:\n\t"                                                                                           \
+    "s_lshr_b32 s89, " X ", 8\n\t"                                                                                  \
+    "s_and_b32 s93, " X ", 0xff\n\t"                                                                                \
+    "s_cmp_eq_u32 s89, 1\n\t"                                                                                       \
+    "s_cbranch_scc0 L_p" id "_%=\n\t"                                                                               \
+    GRAD(TB, Y, Z, W, AT)                                                                                           \
+    "s_branch L_d" id "_%=\n"                                                                                       \
+    "L_p" id "_%=:\n\t"                                                                                             \
+    "s_cmp_eq_u32 s89, 2\n\t"                                                                                       \
+    "s_cbranch_scc0 L_c" id "_%=\n\t"                                                                               \
+    A2R_MIX(TB, Y)                                                                                                  \
+    "s_branch L_d" id "_%=\n"                                                                                       \
+    "L_c" id "_%=:\n\t"                                                                                             \
+    "s_cmp_eq_u32 " Y ", 1\n\t"                                                                                     \
+    "s_cbranch_scc1 L_switch_%=\n\t"                                                                                \
+    "s_cmp_eq_u32 " Y ", 2\n\t"                                                                                     \
+    "s_cbranch_scc1 L_end_%=\n\t"                                                                                   \
+    "s_branch L_d" id "_%=\n\t"
+#define A2R_SLOTS(M, ...)                                                                                           \
+    M(__VA_ARGS__, "0", "s40", "s41", "s42", "s43") M(__VA_ARGS__, "1", "s44", "s45", "s46", "s47")                 \
+    M(__VA_ARGS__, "2", "s48", "s49", "s50", "s51") M(__VA_ARGS__, "3", "s52", "s53", "s54", "s55")                 \
+    M(__VA_ARGS__, "4", "s56", "s57", "s58", "s59") M(__VA_ARGS__, "5", "s60", "s61", "s62", "s63")                 \
+    M(__VA_ARGS__, "6", "s64", "s65", "s66", "s67") M(__VA_ARGS__, "7", "s68", "s69", "s70", "s71")
+
+// one input: pointer pair LO:HI of the batch in s[72:87], destination register DST
+#define A2R_REQ1(TB, DST, LO, PAIR)                                                                                 \
+    "s_bitcmp1_b32 " LO ", 0\n\t"                                                                                   \
+    "s_cselect_b64 vcc, -1, 0\n\t"                                                                                  \
+    "v_cndmask_b32_e64 " A2R_T(TB, 10) ", %[voff], 0, vcc\n\t"                                                      \
+    "s_and_b32 " LO ", " LO ", -4\n\t"                                                                              \
+    "global_load_dword " DST ", " A2R_T(TB, 10) ", " PAIR " nt\n\t"
+// eight inputs of one kind: the pointers at byte offset OFF of the table, destinations v[B .. B+7]
+#define A2R_REQ8(TB, OFF, B)                                                                                        \
+    "s_load_dwordx16 s[72:87], %[gin], " OFF "\n\t"                                                                 \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
+    A2R_REQ1(TB, "v[" B "+0]", "s72", "s[72:73]") A2R_REQ1(TB, "v[" B "+1]", "s74", "s[74:75]")                     \
+    A2R_REQ1(TB, "v[" B "+2]", "s76", "s[76:77]") A2R_REQ1(TB, "v[" B "+3]", "s78", "s[78:79]")                     \
+    A2R_REQ1(TB, "v[" B "+4]", "s80", "s[80:81]") A2R_REQ1(TB, "v[" B "+5]", "s82", "s[82:83]")                     \
+    A2R_REQ1(TB, "v[" B "+6]", "s84", "s[84:85]") A2R_REQ1(TB, "v[" B "+7]", "s86", "s[86:87]")
+// a whole chunk (table byte offset in s89) into set SET ("0" or "8")
+#define A2R_REQ_PLAIN(TB, SET) A2R_REQ8(TB, "s89", "128+" SET)
+#define A2R_REQ_FULL(TB, SET)                                                                                       \
+    A2R_REQ8(TB, "s89", "128+" SET)                                                                                 \
+    "s_add_u32 s93, s89, 64\n\t" A2R_REQ8(TB, "s93", "144+" SET)                                                    \
+    "s_add_u32 s93, s89, 128\n\t" A2R_REQ8(TB, "s93", "160+" SET)
+
+#define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, REQ)                                                                    \
+    "s_mov_b32 s88, 0\n\t"                                                                                          \
+    "s_mov_b32 s90, 0\n\t"                                                                                          \
+    "s_mov_b32 s91, 0\n\t"                                                                                          \
+    "s_mov_b32 s92, 2\n\t"                                                                                          \
+    "s_mov_b32 s89, 0\n\t"                                                                                          \
+    REQ(TB, "0")                                                                                                    \
+    "s_min_u32 s89, %[last], 1\n\t"                                                                                 \
+    "s_mul_i32 s89, s89, 192\n\t"                                                                                   \
+    REQ(TB, "8")                                                                                                    \
+    "s_waitcnt vmcnt(0)\n"                                                                                          \
+    "L_blk_%=:\n\t"                                                                                                 \
+    "s_cmp_lt_u32 s88, %[nbytes]\n\t"                                                                               \
+    "s_cbranch_scc0 L_end_%=\n\t"                                                                                   \
+    "s_load_dwordx16 s[40:55], %[prog], s88\n\t"                                                                    \
+    "s_add_u32 s89, s88, 64\n\t"                                                                                    \
+    "s_load_dwordx16 s[56:71], %[prog], s89\n\t"                                                                    \
+    "s_add_u32 s88, s88, 128\n\t"                                                                                   \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
+    A2R_SLOTS(A2R_SLOT, TB, GOSSIP)                                                                                 \
+    "s_branch L_blk_%=\n\t"                                                                                         \
+    A2R_SLOTS(A2R_OTHER, TB, GRAD, AT)                                                                              \
+    "\nL_switch_%=:\n\t"                                                                                            \
+    "s_waitcnt vmcnt(0)\n\t"                                                                                        \
+    "s_min_u32 s89, s92, %[last]\n\t"                                                                               \
+    "s_mul_i32 s89, s89, 192\n\t"                                                                                   \
+    "s_add_u32 s92, s92, 1\n\t"                                                                                     \
+    "s_cmp_eq_u32 s91, 0\n\t"                                                                                       \
+    "s_cbranch_scc0 L_setb_%=\n\t"                                                                                  \
+    REQ(TB, "0")                                                                                                    \
+    "s_mov_b32 s91, 8\n\t"                                                                                          \
+    "s_mov_b32 s90, 8\n\t"                                                                                          \
+    "s_branch L_blk_%=\n"                                                                                           \
+    "L_setb_%=:\n\t"                                                                                                \
+    REQ(TB, "8")                                                                                                    \
+    "s_mov_b32 s91, 0\n\t"                                                                                          \
+    "s_mov_b32 s90, 0\n\t"                                                                                          \
+    "s_branch L_blk_%=\n"                                                                                           \
+    "L_end_%=:\n\t"                                                                                                 \
+    "s_waitcnt vmcnt(0)"
+
+#define A2R_CLOBBER_S                                                                                               \
+    "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55", \
+    "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", \
+    "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", \
+    "s88", "s89", "s90", "s91", "s92", "s93", "vcc", "scc", "memory"
+#define A2R_V10(a) "v" #a "0", "v" #a "1", "v" #a "2", "v" #a "3", "v" #a "4", "v" #a "5", "v" #a "6", "v" #a "7", "v" #a "8", "v" #a "9"
+#define A2R_CLOBBER_PLAIN "v128", "v129", A2R_V10(13), A2R_V10(14), "v150", "v151", "v152", "v153", "v154"
+#define A2R_CLOBBER_FULL                                                                                            \
+    "v128", "v129", A2R_V10(13), A2R_V10(14), A2R_V10(15), A2R_V10(16), A2R_V10(17), "v180", "v181", "v182", "v183", \
+    "v184", "v185", "v186"
+
+template <bool PRE, bool FULL>
+__global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
+                                                     int64_t d, const ResSlot *__restrict__ recs, uint32_t n_bytes,
+                                                     const uint64_t *__restrict__ gin, uint32_t last_chunk,
+                                                     uint64_t touched, float alpha, float alpha_t) {
+    const uint32_t lane = threadIdx.x;
+    const int64_t col0 = (int64_t)blockIdx.x * 64;
+    const bool valid = col0 + lane < d;
+    const uint32_t lane_in = valid ? lane : 0u;             // loads of lanes past the end read the tile's first column
+    const uint32_t voff = (uint32_t)(col0 + lane_in) * 4u;  // byte offset of the lane's column in a row (d < 2^30)
+
+    // Every register is loaded, the untouched workers' from the first touched row (never used, never stored):
+    // straight-line code, so that the four blocks are built in place.
+    v32f X0, X1, T0, T1;
+    {
+        const int64_t r0 = touched ? __builtin_ctzll(touched) : 0;
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            const int64_t row = ((touched >> r) & 1) ? r : r0;
+            const float a = __builtin_nontemporal_load((global_f32)reg_uniform(x + row * ld + col0) + lane_in);
+            const float b = __builtin_nontemporal_load((global_f32)reg_uniform(xt + row * ld + col0) + lane_in);
+            if (r < 32) { X0[r] = a; T0[r] = b; } else { X1[r - 32] = a; T1[r - 32] = b; }
+        }
+    }
+    const float neg_alpha = -alpha, neg_alpha_t = -alpha_t;
+#define A2R_OPERANDS                                                                                                \
+    : "+{v[0:31]}"(X0), "+{v[32:63]}"(X1), "+{v[64:95]}"(T0), "+{v[96:127]}"(T1)                                    \
+    : [prog] "s"(recs), [nbytes] "s"(n_bytes), [gin] "s"(gin), [last] "s"(last_chunk), [voff] "v"(voff),            \
+      [al] "s"(alpha), [nal] "s"(neg_alpha), [alt] "s"(alpha_t), [nalt] "s"(neg_alpha_t)
+    if constexpr (!FULL) {
+        if constexpr (!PRE)
+            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_0, A2R_GRAD_PLAIN, 2, A2R_REQ_PLAIN) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
+        else
+            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_1, A2R_GRAD_PLAIN, 8, A2R_REQ_PLAIN) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
+    } else {
+        if constexpr (!PRE)
+            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_0, A2R_GRAD_FULL, 2, A2R_REQ_FULL) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
+        else
+            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_1, A2R_GRAD_FULL, 8, A2R_REQ_FULL) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
+    }
+#undef A2R_OPERANDS
+
+    if (valid) {
+#pragma unroll
+        for (int r = 0; r < 64; ++r) {
+            if ((touched >> r) & 1) {
+                __builtin_nontemporal_store(r < 32 ? X0[r] : X1[r - 32], (global_out_f32)reg_uniform(x + r * ld + col0) + lane);
+                __builtin_nontemporal_store(r < 32 ? T0[r] : T1[r - 32], (global_out_f32)reg_uniform(xt + r * ld + col0) + lane);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Plain device copy of n4 float4 pieces with the event kernels' access shape (4 pieces per lane,
 // 256 lanes, non-temporal).  A measurement aid: it moves a known number of bytes, which gives
 // the practical streaming ceiling of the machine at hand and the scale of the HBM counters.
