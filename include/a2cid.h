@@ -313,6 +313,29 @@ int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_c
                         int64_t first_op, a2cid_resident_slot *slots, int32_t *rows, int32_t *n_rows,
                         int64_t *gradient_ops, int32_t *n_gradient_ops, int64_t *next_op);
 
+/* The programme the register-file kernel (a2cid_set_tuning, mode 4; n <= 64) runs for one launch, as a
+ * pure host function.  A wavefront keeps its 64 columns of every worker's x and xt in vector registers
+ * for the whole launch, so all wavefronts run the same linear programme, the batch's operations in the
+ * batch's order from first_op on, as 16-byte slots whose kind is x >> 8 (fp32 values as bit patterns):
+ *   0 gossip:   x = i, y = j, z, w = b_pre_i, b_pre_j;
+ *   1 gradient: x = i | 1 << 8, y = b_pre_i, z = gamma, w = gscale; gradient events are numbered in the
+ *               order of gradient_ops (their indices in the batch), and their inputs are read in chunks
+ *               of 8 events, two chunks ahead of their use;
+ *   2 mix:      x = worker | 2 << 8, y = b_post: a trailing mix, directly after its operation (one slot
+ *               per worker with b_post != 0);
+ *   3 control:  x = 3 << 8, y = 1: the next gradient event is the first of a chunk (the kernel turns to
+ *               the other set of inputs and skips the rest of the block of 8 slots, which holds filler);
+ *               y = 2: the end; y = 0: filler.
+ * The programme is fetched in blocks of 8 slots, ends with an end slot and is padded to a whole block.
+ * One call takes as many operations as fit into max_slots slots (a multiple of 8, at least 16; the
+ * library uses 8192); *next_op is where the next launch starts.  touched: bit r set iff worker r is used.
+ * slots: max_slots entries; gradient_ops: n_ops entries.  coef: the batch's coefficients from
+ * a2cid_plan_batch.  The batch's level table is not read: any order that keeps every worker's own
+ * operations in sequence gives the same bits (Eq. (1) couples no other), and the batch's order does. */
+int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t first_op,
+                         int64_t max_slots, a2cid_resident_slot *slots, int64_t *n_slots, int64_t *gradient_ops,
+                         int32_t *n_gradient_ops, uint64_t *touched, int64_t *next_op);
+
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 
 /* Independent Poisson clocks (Assumption 3.1): one per worker (gradient events, rate
@@ -373,8 +396,8 @@ void a2cid_sched_destroy(a2cid_sched *s);
 /* Launch shape of the event kernels: unroll = 16-byte pieces per lane and row (1, 2 or 4),
  * nontemporal != 0 selects non-temporal loads and stores of the state (modes 0 and 1), threads =
  * workgroup size (64 ... 1024, a power of two), mode =
- *  -1: chosen by the library from the shape (default): 2 for up to 160 workers; beyond that 1 for rows
- *      of at most 4096 parameters and 3 for everything else;
+ *  -1: chosen by the library from the shape (default): 4 for up to 64 workers, 2 for up to 160; beyond
+ *      that 1 for rows of at most 4096 parameters and 3 for everything else;
  *   0: one launch per level;
  *   1: one launch per batch in which every workgroup walks all operations, in level order, for its
  *      own columns, each operation reading and writing its rows in device memory (32 d bytes per
@@ -384,7 +407,10 @@ void a2cid_sched_destroy(a2cid_sched *s);
  *      for a gossip event that finds one worker there and leaves one there);
  *   2: as 1, but the workgroup keeps its columns of all touched rows in LDS for the whole batch, so
  *      the state is read and written once per batch instead of once per event (at most 320
- *      workers: 512 bytes of LDS per worker and column-per-lane).
+ *      workers: 512 bytes of LDS per worker and column-per-lane);
+ *   4: as 2, but every wavefront keeps its 64 columns of all workers in its vector registers and
+ *      runs the whole programme of a2cid_plan_registers on them, with no LDS and no barrier (at most
+ *      64 workers, rows of at most 2^30 parameters).
  * Default: 1, 0, 256, -1 (tiles shrink automatically for short rows).  All modes compute the same
  * operations in the same per-worker order and give the same state bit for bit.  In every mode the
  * gradient inputs of a batch must hold their final values, in stream order, before
@@ -446,7 +472,7 @@ int a2cid_inplace_probe(a2cid_ctx *ctx, int32_t rows_per_op, int32_t n_ops, doub
  * 4 d for each of xi, c and h that it reads; 16 d per worker mixed by a2cid_flush; 16 n d for
  * a2cid_average), and the bytes the launched kernels move by construction: the same for modes 0
  * and 1; for mode 3, 8 d for every row read from or written to memory (a2cid_plan_chain) plus the
- * gradient inputs; for mode 2, 16 d
+ * gradient inputs; for modes 2 and 4, 16 d
  * per touched row and launch plus the gradient inputs.  Any output pointer may be NULL. */
 int a2cid_counters(a2cid_ctx *ctx, int64_t *n_gossip, int64_t *n_gradient, int64_t *n_launches,
                    double *one_pass_bytes, double *moved_bytes, int32_t reset);

@@ -83,6 +83,8 @@ SIGNATURES = {
                                    _P(C.c_int64), _P(C.c_double)]),
     "a2cid_plan_resident": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, _P(C.c_int32), _P(C.c_int32), C.c_int64,
                                       C.c_void_p, C.c_void_p, _P(C.c_int32), C.c_void_p, _P(C.c_int32), _P(C.c_int64)]),
+    "a2cid_plan_registers": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
+                                       _P(C.c_int64), C.c_void_p, _P(C.c_int32), _P(C.c_uint64), _P(C.c_int64)]),
     "a2cid_set_chain_slots": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
@@ -236,6 +238,26 @@ def a2cid_plan_resident(n, batch, coef, first_op=0, waves=0, cols=1):
     per_wave = 256 if w.value >= 16 else 512
     return {"waves": w.value, "cols": c.value, "slots": slots[:w.value * per_wave].reshape(w.value, per_wave).copy(),
             "rows": rows[:n_rows.value].copy(), "gradient_ops": gops[:n_g.value].copy(), "next_op": nxt.value}
+
+
+REG_GOSSIP, REG_GRADIENT, REG_MIX, REG_CONTROL = 0, 1, 2, 3      # kind of a register-file slot: x >> 8
+REG_SWITCH, REG_END = 1, 2                                      # y of a control slot
+REG_BLOCK, REG_CHUNK = 8, 8
+
+
+def a2cid_plan_registers(n, batch, coef, first_op=0, max_slots=8192):
+    """One launch of the register-file kernel from operation first_op on.  Returns a dict: slots (SLOT_DTYPE array),
+    gradient_ops (ordinal -> index in the batch), touched (bit mask of workers), next_op."""
+    slots = np.zeros(max(int(max_slots), 1), SLOT_DTYPE)
+    gops = np.zeros(max(1, len(batch.ops)), np.int64)
+    n_slots, n_g, touched, nxt = C.c_int64(), C.c_int32(), C.c_uint64(), C.c_int64()
+    bs = batch.struct()
+    coef = np.ascontiguousarray(coef, COEF_DTYPE)
+    _check(load().a2cid_plan_registers(int(n), C.byref(bs), coef.ctypes.data, int(first_op), int(max_slots),
+                                       slots.ctypes.data, C.byref(n_slots), gops.ctypes.data, C.byref(n_g),
+                                       C.byref(touched), C.byref(nxt)))
+    return {"slots": slots[:n_slots.value].copy(), "gradient_ops": gops[:n_g.value].copy(), "touched": touched.value,
+            "next_op": nxt.value}
 
 
 class Scheduler:

@@ -616,17 +616,19 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 }
 
 // The event kernel of the next batch when the choice is left to the library, from measurements (events per second,
-// 1024 events per batch).  The LDS-resident kernel for up to 160 workers, the most for which two workgroups share a CU's
-// LDS: on the five configurations it is 2.2 (4 workers), 1.3 (16) and 1.8 to 2.6 (64 workers) times the chain kernel;
-// with rows of 4 M parameters, ring / exponential graph: 96 workers 1.4, 112: 2.3, 128: 1.4 / 2.4, 160: 1.3 times; from
-// 192 workers on it depends on the graph (192 exponential 1.4, 256 ring 0.8, 256 exponential 1.4, 320 ring 0.8, 320
-// complete 1.5 times), so beyond 160 workers the chain kernel runs, or, for rows of at most 4096 parameters, the walk
-// kernel (it needs no programme from the host).  Asked for explicitly, the resident kernel takes up to kResidentMaxRows
-// workers.
+// 1024 events per batch).  Up to 64 workers the register-file kernel: 1.3 to 1.7 times the LDS-resident kernel on
+// the 64-worker configurations.  The LDS-resident kernel for up to 160 workers, the most for which two workgroups
+// share a CU's LDS: with rows of 4 M parameters, ring / exponential graph, it is, against the chain kernel: 96 workers
+// 1.4, 112: 2.3, 128: 1.4 / 2.4, 160: 1.3 times; from 192 workers on it depends on the graph (192 exponential 1.4,
+// 256 ring 0.8, 256 exponential 1.4, 320 ring 0.8, 320 complete 1.5 times), so beyond 160 workers the chain kernel
+// runs, or, for rows of at most 4096 parameters, the walk kernel (it needs no programme from the host).  Asked for
+// explicitly, the resident kernel takes up to kResidentMaxRows workers.
 constexpr int64_t kShortRow = 4096;
 constexpr int32_t kResidentAutoRows = 160;
+constexpr int64_t kRegMaxColumns = (int64_t)1 << 30;    // a lane's byte offset into a row is a 32-bit number
 static int event_mode(const a2cid_ctx *c) {
     if (c->walk >= 0) return c->walk;
+    if (c->n <= kRegMaxRows && c->d <= kRegMaxColumns) return 4;
     if (c->n <= kResidentAutoRows) return 2;
     return c->d <= kShortRow ? 1 : 3;
 }
@@ -1025,7 +1027,7 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
         return fail(A2CID_EINVAL, "threads must be 64, 128, 256, 512 or 1024");
     if (mode < -1 || mode > 4)
         return fail(A2CID_EINVAL, "mode must be -1 (automatic), 0 (levels), 1 (walk), 2 (resident), 3 (chain) or 4 (register file)");
-    if (mode == 4 && (c->n > kRegMaxRows || c->d > ((int64_t)1 << 30)))
+    if (mode == 4 && (c->n > kRegMaxRows || c->d > kRegMaxColumns))
         return fail(A2CID_EINVAL, "the register-file kernel holds at most %d workers of at most 2^30 parameters", kRegMaxRows);
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);

@@ -987,6 +987,40 @@ int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_c
     return A2CID_OK;
 }
 
+int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t first_op,
+                         int64_t max_slots, a2cid_resident_slot *slots, int64_t *n_slots, int64_t *gradient_ops,
+                         int32_t *n_gradient_ops, uint64_t *touched, int64_t *next_op) {
+    clear_error();
+    if (n < 1 || n > kRegMaxRows) return fail(A2CID_EINVAL, "n = %d out of range (1 ... %d)", n, kRegMaxRows);
+    if (!batch || batch->n_ops < 0 || (batch->n_ops > 0 && !batch->ops))
+        return fail(A2CID_EINVAL, "batch is NULL or malformed");
+    if (!coef || !slots || !n_slots || !gradient_ops || !n_gradient_ops || !touched || !next_op)
+        return fail(A2CID_EINVAL, "an output or coef is NULL");
+    if (first_op < 0 || first_op > batch->n_ops) return fail(A2CID_EINVAL, "first_op out of range");
+    if (max_slots < 2 * kRegBlock || max_slots % kRegBlock)
+        return fail(A2CID_EINVAL, "max_slots must be a multiple of %d and at least %d", kRegBlock, 2 * kRegBlock);
+    for (int64_t k = 0; k < batch->n_ops; ++k) {
+        const a2cid_op &o = batch->ops[k];
+        const bool gossip = o.kind == A2CID_KIND_GOSSIP;
+        if ((!gossip && o.kind != A2CID_KIND_GRADIENT) || o.i < 0 || o.i >= n || (gossip && (o.j < 0 || o.j >= n || o.j == o.i)))
+            return fail(A2CID_EINVAL, "op %lld: bad kind or worker index", (long long)k);
+    }
+    try {
+        RegPlan plan;
+        int64_t k = first_op;
+        plan_regfile(n, batch, coef, max_slots, &k, plan);
+        std::memcpy(slots, plan.programme.data(), plan.programme.size() * sizeof(ResSlot));
+        *n_slots = (int64_t)plan.programme.size();
+        std::copy(plan.grad_op.begin(), plan.grad_op.end(), gradient_ops);
+        *n_gradient_ops = (int32_t)plan.grad_op.size();
+        *touched = plan.touched;
+        *next_op = k;
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
 int a2cid_sched_create(a2cid_sched **out, int32_t n, const a2cid_graph *graph,
                        const double *node_rate, uint64_t seed) {
     clear_error();

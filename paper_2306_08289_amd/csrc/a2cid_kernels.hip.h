@@ -805,9 +805,9 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 //   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
 //   FULL only: v[144:151], v[152:159] the sets of centres c, v[160:167], v[168:175] of curvatures h
 //   v[TB .. TB+10]           temporaries (TB = 144, FULL: 176)
-//   s[40:71] the current block of 8 slots, s[72:87] eight input pointers, s88 byte position in the programme,
-//   s89, s93 scratch, s90 index of the next gradient event's inputs (set offset included), s91 offset of the set in
-//   use (0 or 8), s92 the chunk to request next
+//   s[36:67], s[68:99] two blocks of 8 slots (one applied, one being fetched); s[68:83] also the eight input pointers
+//   of a request; s26 byte position of the next fetch, s27, s31 scratch, s28 index of the next gradient event's
+//   inputs (set offset included), s29 offset of the set in use (0 or 8), s30 the chunk to request next
 // Programme (layout: a2cid_internal.h): every slot is applied in order; a gossip slot (the common case) falls
 // through its kind test, the other kinds are handled out of line.  The loop ends at the end slot, and in any case
 // when the position reaches the programme's length.
@@ -838,6 +838,9 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 #define A2R_ON(idx, mode) "s_set_gpr_idx_on " idx ", gpr_idx(" mode ")\n\t"
 #define A2R_OFF "s_set_gpr_idx_off\n\t"
 // temporaries: 0 di, 1 dj, 2 xi, 3 ti, 4 xj, 5 tj, 6 m, 7 g, 8 u / stored x, 9 slope, 10 lane offset of a request
+// Index mode stays on from one operation to the next (every vector instruction of an operation comes after the
+// operation's own s_set_gpr_idx_on); it is switched off before the only other vector instructions, those of a
+// request, and at the end.
 
 // mix of workers X (i) and Y (j) to the event time, difference m, the four jumps; Z = b_i, W = b_j
 #define A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                              \
@@ -851,8 +854,7 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     A2R_ON(X, "DST") "v_fma_f32 v0, %[nal], " A2R_T(TB, 6) ", " A2R_T(TB, 2) "\n\t"                                 \
                      "v_fma_f32 v64, %[nalt], " A2R_T(TB, 6) ", " A2R_T(TB, 3) "\n\t"                               \
     A2R_ON(Y, "DST") "v_fma_f32 v0, %[al], " A2R_T(TB, 6) ", " A2R_T(TB, 4) "\n\t"                                  \
-                     "v_fma_f32 v64, %[alt], " A2R_T(TB, 6) ", " A2R_T(TB, 5) "\n\t"                                \
-    A2R_OFF
+                     "v_fma_f32 v64, %[alt], " A2R_T(TB, 6) ", " A2R_T(TB, 5) "\n\t"
 // m after the mixing (Eq. (1)): a two-operand instruction, untouched by the SRC2 mode still in force
 #define A2R_GOSSIP_0(TB, X, Y, Z, W)                                                                                \
     A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                                  \
@@ -865,35 +867,34 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     A2R_GOSSIP_MIX(TB, X, Y, Z, W)                                                                                  \
     A2R_GOSSIP_JUMP(TB, X, Y)
 
-// gradient event of worker s93 (index), Y = b_i, Z = gamma, W = gscale; inputs at index s90
+// gradient event of worker s31 (index), Y = b_i, Z = gamma, W = gscale; inputs at index s28
 #define A2R_STORED_2(TB)
-#define A2R_STORED_8(TB) A2R_ON("s93", "SRC0") "v_mov_b32 " A2R_T(TB, 8) ", v0\n\t"
+#define A2R_STORED_8(TB) A2R_ON("s31", "SRC0") "v_mov_b32 " A2R_T(TB, 8) ", v0\n\t"
 #define A2R_GRAD_HEAD(TB, Y, AT)                                                                                    \
-    A2R_ON("s93", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
+    A2R_ON("s31", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
     A2R_STORED_##AT(TB)                                                                                             \
-    A2R_ON("s93", "SRC2") "v_fma_f32 " A2R_T(TB, 2) ", " Y ", " A2R_T(TB, 0) ", v0\n\t"                             \
+    A2R_ON("s31", "SRC2") "v_fma_f32 " A2R_T(TB, 2) ", " Y ", " A2R_T(TB, 0) ", v0\n\t"                             \
                           "v_fma_f32 " A2R_T(TB, 3) ", -" Y ", " A2R_T(TB, 0) ", v64\n\t"
 #define A2R_GRAD_TAIL(TB, Z)                                                                                        \
-    A2R_ON("s93", "DST") "v_fma_f32 v0, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 2) "\n\t"                             \
+    A2R_ON("s31", "DST") "v_fma_f32 v0, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 2) "\n\t"                             \
                          "v_fma_f32 v64, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 3) "\n\t"                            \
-    A2R_OFF "s_add_u32 s90, s90, 1\n\t"
+    "s_add_u32 s28, s28, 1\n\t"
 // g = gscale x + xi (no centre, no curvature); AT = 2: at the mixed point, 8: at the stored point
 #define A2R_GRAD_PLAIN(TB, Y, Z, W, AT)                                                                             \
     A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
-    A2R_ON("s90", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " W ", " A2R_T(TB, AT) ", v128\n\t"                          \
+    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " W ", " A2R_T(TB, AT) ", v128\n\t"                          \
     A2R_GRAD_TAIL(TB, Z)
 // g = (gscale h) (x - c) + xi
 #define A2R_GRAD_FULL(TB, Y, Z, W, AT)                                                                              \
     A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
-    A2R_ON("s90", "SRC1") "v_sub_f32 " A2R_T(TB, 8) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
+    A2R_ON("s28", "SRC1") "v_sub_f32 " A2R_T(TB, 8) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
                           "v_mul_f32 " A2R_T(TB, 9) ", " W ", v160\n\t"                                             \
-    A2R_ON("s90", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " A2R_T(TB, 9) ", " A2R_T(TB, 8) ", v128\n\t"                \
+    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " A2R_T(TB, 9) ", " A2R_T(TB, 8) ", v128\n\t"                \
     A2R_GRAD_TAIL(TB, Z)
 #define A2R_MIX(TB, Y)                                                                                              \
-    A2R_ON("s93", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
-    A2R_ON("s93", "SRC2,DST") "v_fma_f32 v0, " Y ", " A2R_T(TB, 0) ", v0\n\t"                                       \
-                              "v_fma_f32 v64, -" Y ", " A2R_T(TB, 0) ", v64\n\t"                                    \
-    A2R_OFF
+    A2R_ON("s31", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
+    A2R_ON("s31", "SRC2,DST") "v_fma_f32 v0, " Y ", " A2R_T(TB, 0) ", v0\n\t"                                       \
+                              "v_fma_f32 v64, -" Y ", " A2R_T(TB, 0) ", v64\n\t"
 
 // one slot in line: a gossip operation falls through
 #define A2R_SLOT(TB, GOSSIP, id, X, Y, Z, W)                                                                        \
@@ -904,14 +905,14 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 // the other kinds of the same slot, out of line
 #define A2R_OTHER(TB, GRAD, AT, id, X, Y, Z, W)                                                                     \
     "\nL_o" id "_%=:\n\t"                                                                                           \
-    "s_lshr_b32 s89, " X ", 8\n\t"                                                                                  \
-    "s_and_b32 s93, " X ", 0xff\n\t"                                                                                \
-    "s_cmp_eq_u32 s89, 1\n\t"                                                                                       \
+    "s_lshr_b32 s27, " X ", 8\n\t"                                                                                  \
+    "s_and_b32 s31, " X ", 0xff\n\t"                                                                                \
+    "s_cmp_eq_u32 s27, 1\n\t"                                                                                       \
     "s_cbranch_scc0 L_p" id "_%=\n\t"                                                                               \
     GRAD(TB, Y, Z, W, AT)                                                                                           \
     "s_branch L_d" id "_%=\n"                                                                                       \
     "L_p" id "_%=:\n\t"                                                                                             \
-    "s_cmp_eq_u32 s89, 2\n\t"                                                                                       \
+    "s_cmp_eq_u32 s27, 2\n\t"                                                                                       \
     "s_cbranch_scc0 L_c" id "_%=\n\t"                                                                               \
     A2R_MIX(TB, Y)                                                                                                  \
     "s_branch L_d" id "_%=\n"                                                                                       \
@@ -921,13 +922,19 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_cmp_eq_u32 " Y ", 2\n\t"                                                                                     \
     "s_cbranch_scc1 L_end_%=\n\t"                                                                                   \
     "s_branch L_d" id "_%=\n\t"
-#define A2R_SLOTS(M, ...)                                                                                           \
-    M(__VA_ARGS__, "0", "s40", "s41", "s42", "s43") M(__VA_ARGS__, "1", "s44", "s45", "s46", "s47")                 \
-    M(__VA_ARGS__, "2", "s48", "s49", "s50", "s51") M(__VA_ARGS__, "3", "s52", "s53", "s54", "s55")                 \
-    M(__VA_ARGS__, "4", "s56", "s57", "s58", "s59") M(__VA_ARGS__, "5", "s60", "s61", "s62", "s63")                 \
-    M(__VA_ARGS__, "6", "s64", "s65", "s66", "s67") M(__VA_ARGS__, "7", "s68", "s69", "s70", "s71")
+// the eight slots of block A (s[36:67]) and of block B (s[68:99])
+#define A2R_SLOTS_A(M, ...)                                                                                         \
+    M(__VA_ARGS__, "a0", "s36", "s37", "s38", "s39") M(__VA_ARGS__, "a1", "s40", "s41", "s42", "s43")               \
+    M(__VA_ARGS__, "a2", "s44", "s45", "s46", "s47") M(__VA_ARGS__, "a3", "s48", "s49", "s50", "s51")               \
+    M(__VA_ARGS__, "a4", "s52", "s53", "s54", "s55") M(__VA_ARGS__, "a5", "s56", "s57", "s58", "s59")               \
+    M(__VA_ARGS__, "a6", "s60", "s61", "s62", "s63") M(__VA_ARGS__, "a7", "s64", "s65", "s66", "s67")
+#define A2R_SLOTS_B(M, ...)                                                                                         \
+    M(__VA_ARGS__, "b0", "s68", "s69", "s70", "s71") M(__VA_ARGS__, "b1", "s72", "s73", "s74", "s75")               \
+    M(__VA_ARGS__, "b2", "s76", "s77", "s78", "s79") M(__VA_ARGS__, "b3", "s80", "s81", "s82", "s83")               \
+    M(__VA_ARGS__, "b4", "s84", "s85", "s86", "s87") M(__VA_ARGS__, "b5", "s88", "s89", "s90", "s91")               \
+    M(__VA_ARGS__, "b6", "s92", "s93", "s94", "s95") M(__VA_ARGS__, "b7", "s96", "s97", "s98", "s99")
 
-// one input: pointer pair LO:HI of the batch in s[72:87], destination register DST
+// one input: pointer pair LO:HI of the batch in s[68:83], destination register DST
 #define A2R_REQ1(TB, DST, LO, PAIR)                                                                                 \
     "s_bitcmp1_b32 " LO ", 0\n\t"                                                                                   \
     "s_cselect_b64 vcc, -1, 0\n\t"                                                                                  \
@@ -936,65 +943,89 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "global_load_dword " DST ", " A2R_T(TB, 10) ", " PAIR " nt\n\t"
 // eight inputs of one kind: the pointers at byte offset OFF of the table, destinations v[B .. B+7]
 #define A2R_REQ8(TB, OFF, B)                                                                                        \
-    "s_load_dwordx16 s[72:87], %[gin], " OFF "\n\t"                                                                 \
+    "s_load_dwordx16 s[68:83], %[gin], " OFF "\n\t"                                                                 \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
-    A2R_REQ1(TB, "v[" B "+0]", "s72", "s[72:73]") A2R_REQ1(TB, "v[" B "+1]", "s74", "s[74:75]")                     \
-    A2R_REQ1(TB, "v[" B "+2]", "s76", "s[76:77]") A2R_REQ1(TB, "v[" B "+3]", "s78", "s[78:79]")                     \
-    A2R_REQ1(TB, "v[" B "+4]", "s80", "s[80:81]") A2R_REQ1(TB, "v[" B "+5]", "s82", "s[82:83]")                     \
-    A2R_REQ1(TB, "v[" B "+6]", "s84", "s[84:85]") A2R_REQ1(TB, "v[" B "+7]", "s86", "s[86:87]")
-// a whole chunk (table byte offset in s89) into set SET ("0" or "8")
-#define A2R_REQ_PLAIN(TB, SET) A2R_REQ8(TB, "s89", "128+" SET)
+    A2R_REQ1(TB, "v[" B "+0]", "s68", "s[68:69]") A2R_REQ1(TB, "v[" B "+1]", "s70", "s[70:71]")                     \
+    A2R_REQ1(TB, "v[" B "+2]", "s72", "s[72:73]") A2R_REQ1(TB, "v[" B "+3]", "s74", "s[74:75]")                     \
+    A2R_REQ1(TB, "v[" B "+4]", "s76", "s[76:77]") A2R_REQ1(TB, "v[" B "+5]", "s78", "s[78:79]")                     \
+    A2R_REQ1(TB, "v[" B "+6]", "s80", "s[80:81]") A2R_REQ1(TB, "v[" B "+7]", "s82", "s[82:83]")
+// a whole chunk (table byte offset in s27) into set SET ("0" or "8")
+#define A2R_REQ_PLAIN(TB, SET) A2R_REQ8(TB, "s27", "128+" SET)
 #define A2R_REQ_FULL(TB, SET)                                                                                       \
-    A2R_REQ8(TB, "s89", "128+" SET)                                                                                 \
-    "s_add_u32 s93, s89, 64\n\t" A2R_REQ8(TB, "s93", "144+" SET)                                                    \
-    "s_add_u32 s93, s89, 128\n\t" A2R_REQ8(TB, "s93", "160+" SET)
+    A2R_REQ8(TB, "s27", "128+" SET)                                                                                 \
+    "s_add_u32 s31, s27, 64\n\t" A2R_REQ8(TB, "s31", "144+" SET)                                                    \
+    "s_add_u32 s31, s27, 128\n\t" A2R_REQ8(TB, "s31", "160+" SET)
 
+// s26: byte offset of the next block to fetch.  Block A is fetched while block B is being applied and the other
+// way round; scalar loads return in no fixed order, so the wait for a block comes before the next fetch is issued.
 #define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, REQ)                                                                    \
-    "s_mov_b32 s88, 0\n\t"                                                                                          \
-    "s_mov_b32 s90, 0\n\t"                                                                                          \
-    "s_mov_b32 s91, 0\n\t"                                                                                          \
-    "s_mov_b32 s92, 2\n\t"                                                                                          \
-    "s_mov_b32 s89, 0\n\t"                                                                                          \
+    "s_mov_b32 s26, 0\n\t"                                                                                          \
+    "s_mov_b32 s28, 0\n\t"                                                                                          \
+    "s_mov_b32 s29, 0\n\t"                                                                                          \
+    "s_mov_b32 s30, 2\n\t"                                                                                          \
+    "s_mov_b32 s27, 0\n\t"                                                                                          \
     REQ(TB, "0")                                                                                                    \
-    "s_min_u32 s89, %[last], 1\n\t"                                                                                 \
-    "s_mul_i32 s89, s89, 192\n\t"                                                                                   \
+    "s_min_u32 s27, %[last], 1\n\t"                                                                                 \
+    "s_mul_i32 s27, s27, 192\n\t"                                                                                   \
     REQ(TB, "8")                                                                                                    \
     "s_waitcnt vmcnt(0)\n"                                                                                          \
-    "L_blk_%=:\n\t"                                                                                                 \
-    "s_cmp_lt_u32 s88, %[nbytes]\n\t"                                                                               \
+    "L_fetch_%=:\n\t"                                                                                               \
+    "s_cmp_lt_u32 s26, %[nbytes]\n\t"                                                                               \
     "s_cbranch_scc0 L_end_%=\n\t"                                                                                   \
-    "s_load_dwordx16 s[40:55], %[prog], s88\n\t"                                                                    \
-    "s_add_u32 s89, s88, 64\n\t"                                                                                    \
-    "s_load_dwordx16 s[56:71], %[prog], s89\n\t"                                                                    \
-    "s_add_u32 s88, s88, 128\n\t"                                                                                   \
+    "s_load_dwordx16 s[36:51], %[prog], s26\n\t"                                                                    \
+    "s_add_u32 s27, s26, 64\n\t"                                                                                    \
+    "s_load_dwordx16 s[52:67], %[prog], s27\n\t"                                                                    \
+    "s_add_u32 s26, s26, 128\n"                                                                                     \
+    "L_blka_%=:\n\t"                                                                                                \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
-    A2R_SLOTS(A2R_SLOT, TB, GOSSIP)                                                                                 \
-    "s_branch L_blk_%=\n\t"                                                                                         \
-    A2R_SLOTS(A2R_OTHER, TB, GRAD, AT)                                                                              \
+    "s_cmp_lt_u32 s26, %[nbytes]\n\t"                                                                               \
+    "s_cbranch_scc0 L_nob_%=\n\t"                                                                                   \
+    "s_load_dwordx16 s[68:83], %[prog], s26\n\t"                                                                    \
+    "s_add_u32 s27, s26, 64\n\t"                                                                                    \
+    "s_load_dwordx16 s[84:99], %[prog], s27\n"                                                                      \
+    "L_nob_%=:\n\t"                                                                                                 \
+    "s_add_u32 s26, s26, 128\n\t"                                                                                   \
+    A2R_SLOTS_A(A2R_SLOT, TB, GOSSIP)                                                                               \
+    "s_cmp_le_u32 s26, %[nbytes]\n\t"                                                                               \
+    "s_cbranch_scc0 L_end_%=\n\t"                                                                                   \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
+    "s_cmp_lt_u32 s26, %[nbytes]\n\t"                                                                               \
+    "s_cbranch_scc0 L_noa_%=\n\t"                                                                                   \
+    "s_load_dwordx16 s[36:51], %[prog], s26\n\t"                                                                    \
+    "s_add_u32 s27, s26, 64\n\t"                                                                                    \
+    "s_load_dwordx16 s[52:67], %[prog], s27\n"                                                                      \
+    "L_noa_%=:\n\t"                                                                                                 \
+    "s_add_u32 s26, s26, 128\n\t"                                                                                   \
+    A2R_SLOTS_B(A2R_SLOT, TB, GOSSIP)                                                                               \
+    "s_cmp_le_u32 s26, %[nbytes]\n\t"                                                                               \
+    "s_cbranch_scc1 L_blka_%=\n\t"                                                                                  \
+    "s_branch L_end_%=\n\t"                                                                                         \
+    A2R_SLOTS_A(A2R_OTHER, TB, GRAD, AT)                                                                            \
+    A2R_SLOTS_B(A2R_OTHER, TB, GRAD, AT)                                                                            \
     "\nL_switch_%=:\n\t"                                                                                            \
-    "s_waitcnt vmcnt(0)\n\t"                                                                                        \
-    "s_min_u32 s89, s92, %[last]\n\t"                                                                               \
-    "s_mul_i32 s89, s89, 192\n\t"                                                                                   \
-    "s_add_u32 s92, s92, 1\n\t"                                                                                     \
-    "s_cmp_eq_u32 s91, 0\n\t"                                                                                       \
+    A2R_OFF                                                                                                         \
+    "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"                                                                             \
+    "s_sub_u32 s26, s26, 128\n\t"                                                                                   \
+    "s_min_u32 s27, s30, %[last]\n\t"                                                                               \
+    "s_mul_i32 s27, s27, 192\n\t"                                                                                   \
+    "s_add_u32 s30, s30, 1\n\t"                                                                                     \
+    "s_cmp_eq_u32 s29, 0\n\t"                                                                                       \
     "s_cbranch_scc0 L_setb_%=\n\t"                                                                                  \
     REQ(TB, "0")                                                                                                    \
-    "s_mov_b32 s91, 8\n\t"                                                                                          \
-    "s_mov_b32 s90, 8\n\t"                                                                                          \
-    "s_branch L_blk_%=\n"                                                                                           \
+    "s_mov_b32 s29, 8\n\t"                                                                                          \
+    "s_mov_b32 s28, 8\n\t"                                                                                          \
+    "s_branch L_fetch_%=\n"                                                                                         \
     "L_setb_%=:\n\t"                                                                                                \
     REQ(TB, "8")                                                                                                    \
-    "s_mov_b32 s91, 0\n\t"                                                                                          \
-    "s_mov_b32 s90, 0\n\t"                                                                                          \
-    "s_branch L_blk_%=\n"                                                                                           \
+    "s_mov_b32 s29, 0\n\t"                                                                                          \
+    "s_mov_b32 s28, 0\n\t"                                                                                          \
+    "s_branch L_fetch_%=\n"                                                                                         \
     "L_end_%=:\n\t"                                                                                                 \
-    "s_waitcnt vmcnt(0)"
+    A2R_OFF                                                                                                         \
+    "s_waitcnt vmcnt(0) lgkmcnt(0)"
 
-#define A2R_CLOBBER_S                                                                                               \
-    "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "s48", "s49", "s50", "s51", "s52", "s53", "s54", "s55", \
-    "s56", "s57", "s58", "s59", "s60", "s61", "s62", "s63", "s64", "s65", "s66", "s67", "s68", "s69", "s70", "s71", \
-    "s72", "s73", "s74", "s75", "s76", "s77", "s78", "s79", "s80", "s81", "s82", "s83", "s84", "s85", "s86", "s87", \
-    "s88", "s89", "s90", "s91", "s92", "s93", "vcc", "scc", "memory"
+#define A2R_S10(a) "s" #a "0", "s" #a "1", "s" #a "2", "s" #a "3", "s" #a "4", "s" #a "5", "s" #a "6", "s" #a "7", "s" #a "8", "s" #a "9"
+#define A2R_CLOBBER_S "s26", "s27", "s28", "s29", "s30", "s31", "s36", "s37", "s38", "s39", A2R_S10(4), A2R_S10(5), A2R_S10(6), A2R_S10(7), A2R_S10(8), A2R_S10(9), "vcc", "scc", "memory"
 #define A2R_V10(a) "v" #a "0", "v" #a "1", "v" #a "2", "v" #a "3", "v" #a "4", "v" #a "5", "v" #a "6", "v" #a "7", "v" #a "8", "v" #a "9"
 #define A2R_CLOBBER_PLAIN "v128", "v129", A2R_V10(13), A2R_V10(14), "v150", "v151", "v152", "v153", "v154"
 #define A2R_CLOBBER_FULL                                                                                            \

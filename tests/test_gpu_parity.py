@@ -70,7 +70,8 @@ def test_small_configs_match_oracle_everywhere(name, d, events, batch):
 @pytest.mark.parametrize("unroll,nt,threads,walk", [(1, 0, 64, 0), (2, 1, 128, 0), (4, 1, 256, 1), (4, 0, 64, 0),
                                                    (2, 0, 512, 1), (1, 1, 128, 1), (4, 1, 64, 0),
                                                    (1, 0, 1024, 1), (2, 1, 1024, 0), (1, 0, 256, 2),
-                                                   (1, 0, 256, 3), (2, 0, 128, 3), (4, 0, 64, 3), (1, 0, 1024, 3)])
+                                                   (1, 0, 256, 3), (2, 0, 128, 3), (4, 0, 64, 3), (1, 0, 1024, 3),
+                                                   (1, 0, 256, 4)])
 def test_launch_shapes_give_the_same_answer(unroll, nt, threads, walk):
     # rows long enough that the engine keeps the requested unroll (it shrinks tiles for short rows)
     cfg = wl.scaled(wl.CONFIGS["C2"], d=2048 * 1024 * 4 * 4 + 517, events=600)
@@ -119,9 +120,11 @@ def test_chain_slots_beyond_the_lds_are_refused():
 
 @pytest.mark.parametrize("name,events,batch,mode", [("C2", 3000, 1024, 3), ("C3", 600, 512, 3), ("C4", 400, 400, 3),
                                                     ("C5", 400, 400, 3), ("C4", 2048, 1024, 1), ("C4", 2048, 1024, 3),
-                                                    ("C3", 1024, 1024, 1)])
+                                                    ("C3", 1024, 1024, 1), ("C4", 2048, 1024, 4), ("C3", 1024, 1024, 4),
+                                                    ("C5", 2048, 1024, 4), ("C2", 3000, 1024, 4)])
 def test_full_size_configs_on_sampled_columns(name, events, batch, mode):
-    # the launch shapes the benchmark times: 1024 events per batch, walk (mode 1) and chain (mode 3) kernels
+    # the launch shapes the benchmark times: 1024 events per batch, walk (mode 1), chain (mode 3) and register-file
+    # (mode 4) kernels
     cfg = wl.scaled(wl.CONFIGS[name], events=events)
     _compare(cfg, events, batch, cols=pu.sample_columns(cfg.d, 4096, seed=1), tuning=(1, 0, 256, mode))
 
@@ -251,7 +254,8 @@ def test_result_does_not_depend_on_batching_or_kernel_choice_bit_for_bit(name, d
                                         (900, (1, 0, 256, 3), 0, None), (211, (2, 0, 64, 3), 5, None),
                                         (640, (1, 0, 128, 3), 1, None), (333, (1, 0, 256, 2), None, (8, 1)),
                                         (900, (1, 0, 256, 2), None, (16, 2)), (250, (1, 0, 256, 2), None, (4, 4)),
-                                        (600, (1, 0, 256, 2), None, (2, 1)), (450, (1, 0, 256, 2), None, (16, 4))]:
+                                        (600, (1, 0, 256, 2), None, (2, 1)), (450, (1, 0, 256, 2), None, (16, 4)),
+                                        (900, (1, 0, 256, 4), None, None), (97, (1, 0, 256, 4), None, None)]:
         _say(f"{name} batching {batch} tuning {tuning} slots {slots} shape {shape}")
         w = wl.Workload(cfg, batch_events=batch)
         if tuning:
@@ -400,7 +404,8 @@ def test_resident_kernel_at_full_size_on_sampled_columns():
 
 
 @pytest.mark.parametrize("name,d,mode", [("C2", 4 * 1024 + 7, 1), ("C4", 9001, 0), ("C5", 5003, 2), ("C3", 3333, 1),
-                                         ("C4", 4 * 256 * 2 + 3, 3), ("C3", 2049, 3)])
+                                         ("C4", 4 * 256 * 2 + 3, 3), ("C3", 2049, 3), ("C4", 64 * 5 + 9, 4),
+                                         ("C5", 1000, 4), ("C2", 130, 4)])
 def test_listing_order_variant_matches_oracle(name, d, mode):
     # Algorithm 1 as listed: g and m from the stored values, then the mixing, then the jump
     cfg = wl.scaled(wl.CONFIGS[name], d=d, events=2500)
@@ -444,7 +449,8 @@ def test_average_matches_oracle(name, d):
 @pytest.mark.parametrize("name,d,mode,normalize", [("C3", 6001, 1, False), ("C4", 5000, 2, True), ("C5", 4099, 1, True),
                                                    ("C4", 4100, 3, True), ("C5", 4099, 2, "worker"),
                                                    ("C3", 3001, 3, "worker"), ("C5", 2050, 1, "worker"),
-                                                   ("C2", 5000, 0, "worker")])
+                                                   ("C2", 5000, 0, "worker"), ("C5", 3000, 4, "worker"),
+                                                   ("C4", 2000, 4, True)])
 def test_fifo_pairing_source_drives_the_engine_like_the_oracle(name, d, mode, normalize):
     # the paper's practical event source: Poisson count per gradient step + first-in-first-out pairing; events stamped
     # in real time (False), with the common normalised clock (True), or in real time with every worker's own clock
@@ -488,7 +494,8 @@ def _custom_workload(n, topology, d, seed=0xA2C1D2 + 77, **kw):
                                                       (1024, "ring", 261, 6000, 1), (1024, "ring", 133, 4000, 0),
                                                       (112, "exponential", 700, 3000, 2), (2, "ring", 1031, 400, 3),
                                                       (1024, "ring", 259, 6000, 3), (320, "ring", 200, 5000, 2),
-                                                      (128, "complete", 515, 4000, 2)])
+                                                      (128, "complete", 515, 4000, 2), (2, "ring", 67, 400, 4),
+                                                      (64, "complete", 130, 3000, 4), (33, "ring", 5, 2000, 4)])
 def test_extreme_worker_counts(n, topology, d, events, mode):
     # explicit eta, alpha_tilde: Proposition 3.2 gives alpha_tilde = 115 on a ring of 1024, where fp32 cancellation in
     # xt (terms of +-100 summing to O(1)) alone exceeds 1e-5 -- a property of fp32 state, not of the kernels
@@ -520,7 +527,17 @@ def test_resident_mode_is_refused_beyond_its_lds_capacity():
     w.close()
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2, 3])
+def test_register_file_mode_is_refused_beyond_its_registers():
+    from paper_2306_08289_amd import A2cidError, binding
+    w = wl.Workload(_custom_workload(65, "ring", 64), batch_events=100)
+    with pytest.raises(A2cidError) as e:
+        w.engine.set_tuning(1, 0, 256, 4)
+    assert e.value.code == binding.EINVAL
+    w.run(100)                                           # the automatic choice goes on with another kernel
+    w.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1, 2, 3, 4])
 def test_batches_larger_than_a_staging_buffer_and_empty_batches(mode):
     # 40 000 events in one batch: the library splits it over several operation-table uploads
     cfg = wl.scaled(wl.CONFIGS["C4"], d=150, events=40000)
@@ -541,7 +558,7 @@ def test_batches_larger_than_a_staging_buffer_and_empty_batches(mode):
     w.close()
 
 
-@pytest.mark.parametrize("mode", [0, 1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 4])
 def test_trailing_mix_in_the_other_kernels(mode):
     cfg = wl.scaled(wl.CONFIGS["C3"], d=777, events=60)
     w = wl.Workload(cfg, batch_events=60)
@@ -597,7 +614,9 @@ def test_curvature_inputs_device_equals_host():
 
 @pytest.mark.parametrize("name,d,mode,order", [("C2", 4 * 1024 * 2 + 1027, 3, 0), ("C2", 4 * 256 * 3 + 2, 1, 0),
                                                ("C5", 5003, 0, 0), ("C5", 64 * 21 + 5, 2, 0), ("C1", 3, 3, 0),
-                                               ("C2", 4 * 256 * 2 + 1, 3, 1), ("C5", 777, 2, 1), ("C2", 2049, 1, 1)])
+                                               ("C2", 4 * 256 * 2 + 1, 3, 1), ("C5", 777, 2, 1), ("C2", 2049, 1, 1),
+                                               ("C5", 64 * 7 + 3, 4, 0), ("C2", 1000, 4, 0), ("C5", 500, 4, 1),
+                                               ("C1", 3, 4, 1)])
 def test_strongly_convex_objectives_match_oracle(name, d, mode, order):
     from dataclasses import replace
     cfg = replace(wl.scaled(wl.CONFIGS[name], d=d, events=3000), curvature=True)
@@ -625,7 +644,7 @@ def test_strongly_convex_objectives_match_oracle(name, d, mode, order):
     w.close()
 
 
-@pytest.mark.parametrize("mode", [1, 3])
+@pytest.mark.parametrize("mode", [1, 3, 4])
 def test_strongly_convex_objectives_at_full_size_on_sampled_columns(mode):
     from dataclasses import replace
     cfg = replace(wl.scaled(wl.CONFIGS["C5"], events=1024), curvature=True)

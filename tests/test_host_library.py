@@ -763,3 +763,197 @@ def test_resident_programmes_on_arbitrary_small_batches():
         _resident_plans_cover(n, b, coef, waves, cols)
 
     check()
+
+
+# ---- the register-file kernel's programme ------------------------------------------------------------------------
+
+def _run_register_launch(n, batch, coef, plan, first_op, max_slots):
+    """Interprets one launch the way regfile_kernel does and checks it against the batch: blocks of 8 slots, two sets of
+    gradient inputs of 8 events each (set = chunk % 2), a switch slot before the first event of every later chunk, after
+    which the rest of the block is skipped.  Returns the indices of the operations applied, in order."""
+    ops, slots, gops = batch.ops, plan["slots"], [int(k) for k in plan["gradient_ops"]]
+    B, K = binding.REG_BLOCK, binding.REG_CHUNK
+    assert len(slots) % B == 0 and 0 < len(slots) <= max_slots
+    applied, touched = [], 0
+    k = first_op                       # the next operation of the batch
+    pending_mix = []                   # trailing mixes the last operation still owes: (worker, bits)
+    sets = {0: 0, 8: 1}                # set offset -> the chunk whose inputs it holds (requested two chunks ahead)
+    sel, q, gnext, pos, ended = 0, 0, 2, 0, False
+    while pos < len(slots) and not ended:
+        block, pos = slots[pos:pos + B], pos + B
+        for s in block:
+            kind, x, y = int(s["x"]) >> 8, int(s["x"]), int(s["y"])
+            if kind != binding.REG_MIX:
+                assert not pending_mix, "a trailing mix is missing"
+            if kind == binding.REG_GOSSIP:
+                op, cf = ops[k], coef[k]
+                assert op["kind"] == binding.KIND_GOSSIP and (x, y) == (int(op["i"]), int(op["j"]))
+                assert (int(s["z"]), int(s["w"])) == (_f32_bits(cf["b_pre_i"]), _f32_bits(cf["b_pre_j"]))
+                pending_mix = [(int(op[e]), _f32_bits(cf[b])) for e, b in (("i", "b_post_i"), ("j", "b_post_j")) if cf[b] != 0]
+                touched |= 1 << x | 1 << y
+                applied.append(k); k += 1
+            elif kind == binding.REG_GRADIENT:
+                op, cf = ops[k], coef[k]
+                assert op["kind"] == binding.KIND_GRADIENT and (x & 255) == int(op["i"])
+                assert (y, int(s["z"]), int(s["w"])) == (_f32_bits(cf["b_pre_i"]), _f32_bits(op["gamma"]), _f32_bits(op["gscale"]))
+                assert q - sel < K, "more gradient events than a set of inputs holds"
+                assert gops[sets[sel] * K + (q - sel)] == k, "the inputs in the registers belong to another event"
+                q += 1
+                pending_mix = [(int(op["i"]), _f32_bits(cf["b_post_i"]))] if cf["b_post_i"] != 0 else []
+                touched |= 1 << (x & 255)
+                applied.append(k); k += 1
+            elif kind == binding.REG_MIX:
+                assert pending_mix and pending_mix.pop(0) == (x & 255, y), "a trailing mix nobody owes"
+            else:
+                assert kind == binding.REG_CONTROL and (x & 255) == 0
+                if y == binding.REG_SWITCH:
+                    sets[sel] = gnext                  # the set just used up receives the chunk after the next
+                    gnext += 1
+                    sel = 8 - sel
+                    q = sel
+                    break                              # the rest of the block is skipped
+                if y == binding.REG_END:
+                    ended = True
+                    break
+                assert y == 0
+    assert ended and not pending_mix, "the programme has no end slot"
+    assert pos == len(slots), "blocks after the end"
+    assert k == plan["next_op"] and applied == list(range(first_op, k))
+    assert gops == [j for j in applied if ops["kind"][j] == binding.KIND_GRADIENT]
+    assert touched == plan["touched"]
+    return applied
+
+
+def _register_plans_cover(n, batch, coef, max_slots=8192):
+    k, launches = 0, 0
+    while k < len(batch.ops):
+        plan = binding.a2cid_plan_registers(n, batch, coef, first_op=k, max_slots=max_slots)
+        assert _run_register_launch(n, batch, coef, plan, k, max_slots), "a launch must take at least one operation"
+        k = plan["next_op"]
+        launches += 1
+    return launches
+
+
+@pytest.mark.parametrize("topo,n,edge_rate", [("ring", 64, 2.0), ("exponential", 64, 1.0), ("complete", 64, 0.56),
+                                              ("ring", 16, 1.0), ("complete", 4, 1.0)])
+def test_register_programmes_on_scheduler_batches(topo, n, edge_rate):
+    u, v = _uv(getattr(graph, topo)(n))
+    s = binding.Scheduler(n, u, v, edge_rate, 1.0, 5)
+    t = np.zeros(n)
+    for size, sync in ((1, False), (300, False), (4096, False), (12000, False), (1024, True)):   # the sync batch last
+        b = s.next(size)
+        b.ops["gamma"], b.ops["gscale"] = 0.1, 1.0
+        grad = b.ops["kind"] == binding.KIND_GRADIENT
+        b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))
+        if sync:
+            b.t_sync = float(b.ops["t"].max()) + 0.5
+        t, coef = binding.a2cid_plan_batch(n, u, v, edge_rate, 0.7, t, b)
+        launches = _register_plans_cover(n, b, coef)
+        assert launches == (1 if size <= 4096 else 2)
+        assert _register_plans_cover(n, b, coef, max_slots=64) >= size // 64     # short programmes: many launches
+        assert _register_plans_cover(n, b, coef, max_slots=16) >= size // 16
+    s.close()
+
+
+def test_register_programme_of_an_empty_range_and_of_gradient_events_only():
+    n = 8
+    ops = np.zeros(40, binding.OP_DTYPE)
+    ops["kind"], ops["i"], ops["j"], ops["t"] = binding.KIND_GRADIENT, np.arange(40) % n, -1, 1.0 + np.arange(40) // n
+    ops["gamma"], ops["xi"] = 0.1, 4096 * (1 + np.arange(40))
+    b = binding.Batch(ops, list(range(0, 41, 8)))
+    u, v = _uv(graph.ring(n))
+    _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.5, np.zeros(n), b)
+    plan = binding.a2cid_plan_registers(n, b, coef)
+    assert _run_register_launch(n, b, coef, plan, 0, 8192) == list(range(40))
+    # 40 events: chunks of 8, a switch slot before events 8, 16, 24, 32, each followed by filler to the end of its block
+    kinds = [int(x) >> 8 for x in plan["slots"]["x"]]
+    assert sum(1 for s in plan["slots"] if int(s["x"]) >> 8 == binding.REG_CONTROL and int(s["y"]) == binding.REG_SWITCH) == 4
+    assert kinds.count(binding.REG_GRADIENT) == 40 and len(kinds) == 10 * 8
+    empty = binding.a2cid_plan_registers(n, b, coef, first_op=40)
+    assert empty["next_op"] == 40 and empty["touched"] == 0 and len(empty["slots"]) == 8
+    assert (int(empty["slots"][0]["x"]) >> 8, int(empty["slots"][0]["y"])) == (binding.REG_CONTROL, binding.REG_END)
+
+
+def test_register_planner_rejects_malformed_input():
+    ops = _random_ops(np.random.default_rng(0), 4, 20, 0.3)
+    coef = np.zeros(20, binding.COEF_DTYPE)
+    good = binding.Batch(ops, [0, 20])
+    for kwargs in ({"first_op": 21}, {"first_op": -1}, {"max_slots": 8}, {"max_slots": 20}, {"max_slots": 0}):
+        with pytest.raises(a2.A2cidError):
+            binding.a2cid_plan_registers(4, good, coef, **kwargs)
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_plan_registers(65, good, coef)                 # more workers than registers
+    bad = ops.copy()
+    bad["i"][5] = 4
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_plan_registers(4, binding.Batch(bad, [0, 20]), coef)
+
+
+def test_register_programme_checker_notices_planted_mistakes():
+    n = 16
+    u, v = _uv(graph.ring(n))
+    s = binding.Scheduler(n, u, v, 1.0, 1.0, 3)
+    b = s.next(400)
+    b.ops["gamma"], b.ops["gscale"] = 0.1, 1.0
+    grad = b.ops["kind"] == binding.KIND_GRADIENT
+    b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))
+    b.t_sync = float(b.ops["t"].max()) + 0.5
+    _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
+    good = binding.a2cid_plan_registers(n, b, coef)
+    _run_register_launch(n, b, coef, good, 0, 8192)
+    kinds = good["slots"]["x"] >> 8
+    ctl = (kinds == binding.REG_CONTROL)
+    g = int(np.flatnonzero(kinds == binding.REG_GOSSIP)[3])
+    d = int(np.flatnonzero(kinds == binding.REG_GRADIENT)[9])
+    m = int(np.flatnonzero(kinds == binding.REG_MIX)[0])
+    sw = int(np.flatnonzero(ctl & (good["slots"]["y"] == binding.REG_SWITCH))[0])
+
+    def mutated(change):
+        plan = dict(good)
+        plan["slots"] = good["slots"].copy()
+        change(plan["slots"])
+        return plan
+
+    def swap(sl, a, b):
+        sl[[a, b]] = sl[[b, a]]
+
+    mistakes = {
+        "wrong worker": lambda sl: sl["y"].__setitem__(g, sl["y"][g] ^ 1),
+        "wrong coefficient": lambda sl: sl["z"].__setitem__(g, sl["z"][g] ^ 1),
+        "wrong step size": lambda sl: sl["z"].__setitem__(d, sl["z"][d] ^ 1),
+        "missing switch": lambda sl: sl["y"].__setitem__(sw, 0),
+        "dropped trailing mix": lambda sl: sl.__setitem__(m, (binding.REG_CONTROL << 8, 0, 0, 0)),
+        "operations exchanged": lambda sl: swap(sl, g, d),
+        "no end": lambda sl: sl["y"].__setitem__(np.flatnonzero(ctl & (sl["y"] == binding.REG_END)), 0),
+    }
+    for what, change in mistakes.items():
+        with pytest.raises((AssertionError, IndexError, KeyError)):
+            _run_register_launch(n, b, coef, mutated(change), 0, 8192)
+    s.close()
+
+
+def test_register_programmes_on_arbitrary_small_batches():
+    """Property test: whatever the batch and the programme length, the launches together apply every operation once,
+    in the batch's order, with the inputs of the right gradient event in the registers."""
+    hyp = pytest.importorskip("hypothesis")
+    from hypothesis import strategies as st
+
+    @st.composite
+    def cases(draw):
+        n = draw(st.integers(2, 9))
+        m = draw(st.integers(1, 120))
+        rng = np.random.default_rng(draw(st.integers(0, 2 ** 20)))
+        ops = _random_ops(rng, n, m, draw(st.sampled_from([0.0, 0.3, 0.8, 1.0])))
+        ops["gamma"], ops["t"] = 0.1, np.sort(rng.uniform(0.0, 5.0, m))
+        return n, ops, draw(st.booleans()), draw(st.sampled_from([16, 24, 64, 8192]))
+
+    @hyp.settings(max_examples=150, deadline=None)
+    @hyp.given(cases())
+    def check(case):
+        n, ops, sync, max_slots = case
+        b = binding.Batch(ops, list(range(len(ops) + 1)), t_sync=6.0 if sync else float("nan"))   # one operation per level
+        u, v = _uv(graph.complete(n))
+        _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
+        _register_plans_cover(n, b, coef, max_slots)
+
+    check()
