@@ -11,9 +11,9 @@ Prints ONE JSON line.  The headline figures (value, roofline) belong to the walk
 makes one full pass over the touched rows per event, so that its traffic IS the algorithmic byte
 count of the method: 32 d per gossip event, 16 d + 4 d per gradient input per gradient event
 (+ 8 n d per observables call in `value`).  The kernels that keep workers on the chip between
-events -- the chain kernel and the LDS-resident kernel, between which the library chooses by shape -- move
-fewer bytes for the same events; they are timed on the same steps and reported as separate lines
-(`chain_variant`, `resident_variant`: events/s up, HBM GB/s down, with the bytes they move by
+events -- the chain kernel, the LDS-resident kernel and the register-file kernel, between which the library chooses
+by shape -- move fewer bytes for the same events; they are timed on the same steps and reported as separate lines
+(`chain_variant`, `resident_variant`, `regfile_variant`: events/s up, HBM GB/s down, with the bytes they move by
 construction and the same work priced at one pass per event).  Also: the copy ceiling of the
 machine, and the CPU oracle timed on a bounded sample on this machine's host cores.
 """
@@ -45,7 +45,8 @@ MEASURED_TRAFFIC = {
     ("C5", 1024, "resident_kernel"): (3.7909e10, "profiles/bench_C5_hbm_counters.md"),
 }
 
-# The resident kernel is bound by vector-ALU issue, not by memory: its roofline is the chip's fp32 vector rate.
+# The resident and register-file kernels are bound by instruction issue, not by memory: their roofline is the chip's
+# fp32 vector rate.
 # Arithmetic of the method per column (one fused multiply-add = 2 flop): a gossip event mixes two workers (a subtraction
 # and two fused multiply-adds each), forms m (a subtraction) and applies four fused multiply-adds: 19 flop; a gradient
 # event mixes one worker (5), forms g = s (x - c) + xi (3) and applies two fused multiply-adds (4): 12 flop.
@@ -56,12 +57,13 @@ FP32_VECTOR_PEAK_TFLOPS = 157.3
 MODE_NAMES = {0: "level_kernel", 1: "walk_kernel", 2: "resident_kernel", 3: "chain_kernel", 4: "regfile_kernel"}
 MODE_WHAT = {0: "level_kernel: one launch per level, one full pass over the touched rows per event",
              1: "walk_kernel: one launch per batch, one full pass over the touched rows per event",
-             2: "resident_kernel (the library's choice for up to 160 workers): every touched row stays in LDS for the "
+             2: "resident_kernel (the library's choice for 65 to 160 workers): every touched row stays in LDS for the "
                 "whole batch (state read and written once per batch)",
              3: "chain_kernel (the library's choice for more than 160 workers): events re-ordered so "
                 "that a worker's columns are found in registers or parked in LDS as often as possible",
-             4: "regfile_kernel (up to 64 workers): a wave keeps its 64 columns of every worker's x and xt in vector "
-                "registers for the whole batch (state read and written once per batch, no LDS, no barrier)"}
+             4: "regfile_kernel (the library's choice for up to 64 workers): a wave keeps its 64 columns of every worker's "
+                "x and xt in vector registers for the whole batch (state read and written once per batch, no LDS, no "
+                "barrier)"}
 
 
 def cpu_baseline(cfg, seconds_budget=20.0):
@@ -110,7 +112,7 @@ def cpu_baseline(cfg, seconds_budget=20.0):
 
 
 def short_run(name, batch, steps=6, warmup=2):
-    """A few steps of one configuration with the walk, chain and LDS-resident kernels."""
+    """A few steps of one configuration with the walk, chain, LDS-resident and register-file kernels."""
     import torch
     from paper_2306_08289_amd import workloads as wl
     cfg = wl.CONFIGS[name]
@@ -119,7 +121,7 @@ def short_run(name, batch, steps=6, warmup=2):
     res = {"workload": name, "n": cfg.n, "topology": cfg.topology, "d": cfg.d, "events_per_step": batch,
            "state_bytes": 8.0 * cfg.n * cfg.d,
            "note": "state fits the 256 MB last-level cache: not an HBM figure" if 8.0 * cfg.n * cfg.d < 3e8 else ""}
-    for mode, key in ((1, "walk"), (3, "chain"), (2, "resident")):
+    for mode, key in ((1, "walk"), (3, "chain"), (2, "resident"), (4, "regfile")):
         w.engine.set_tuning(1, 0, 256, mode)
         for _ in range(warmup):
             w.step(); w.engine.stats(w.t_last)
@@ -201,12 +203,14 @@ def main():
     ap.add_argument("--walk", type=int, default=None,
                     help="event kernel of the headline line: 1 = walk, one full pass per event (default: the kernel "
                          "whose traffic is the algorithmic byte count), 3 = chain, 0 = one launch per level, "
-                         "2 = LDS-resident (the library's choice for up to 160 workers)")
+                         "2 = LDS-resident (the library's choice for 65 to 160 workers), 4 = register file (the "
+                         "library's choice for up to 64 workers)")
     ap.add_argument("--slots", type=int, default=None, help="chain kernel: LDS slots for parked workers (default 5)")
     ap.add_argument("--walk-occupancy", type=int, default=None, help="walk kernel: at most this many workgroups per CU")
     ap.add_argument("--group", type=int, default=None, help="resident kernel: waves per workgroup (default: chosen per batch)")
     ap.add_argument("--cols", type=int, default=None, help="resident kernel: columns per lane")
     ap.add_argument("--no-resident-leg", action="store_true", help="skip the separate LDS-resident measurement")
+    ap.add_argument("--no-regfile-leg", action="store_true", help="skip the separate register-file measurement")
     ap.add_argument("--no-chain-leg", action="store_true", help="skip the separate chain-kernel measurement")
     ap.add_argument("--ld-pad", type=int, default=0, help="extra row pitch in units of 4 floats (layout experiments)")
     ap.add_argument("--all-configs", action="store_true",
@@ -303,8 +307,8 @@ def main():
         head = {"bound": "hbm", "kernel": kernel_name, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS}
         if kernel_name in ("resident_kernel", "regfile_kernel"):
-            # vector-ALU issue and the level barriers bound this kernel (SQ counters: profiles/): its HBM figures follow
-            # as hbm_GBs / frac_of_hbm_peak
+            # instruction issue (and, for the resident kernel, the level barriers) bound these kernels (SQ counters:
+            # profiles/): their HBM figures follow as hbm_GBs / frac_of_hbm_peak
             flop = cfg.d * (FLOP_PER_COLUMN["gossip"] * cnt["gossip"] + FLOP_PER_COLUMN["gradient"] * cnt["gradient"])
             tflops = flop / (kernel_ms * 1e-3) / 1e12
             head = {"bound": "alu", "kernel": kernel_name, "achieved": tflops, "peak": FP32_VECTOR_PEAK_TFLOPS,
@@ -388,6 +392,8 @@ def main():
         variants.append((3, "chain_variant"))
     if not args.no_resident_leg and mode != 2 and cfg.n <= 160:
         variants.append((2, "resident_variant"))
+    if not args.no_regfile_leg and mode != 4 and cfg.n <= 64:
+        variants.append((4, "regfile_variant"))
     for v_mode, key in variants:
         w.engine.set_tuning(1, 0, 256, v_mode)
         for _ in range(2):

@@ -319,22 +319,31 @@ int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_c
  * batch's order from first_op on, as 16-byte slots whose kind is x >> 8 (fp32 values as bit patterns):
  *   0 gossip:   x = i, y = j, z, w = b_pre_i, b_pre_j;
  *   1 gradient: x = i | 1 << 8, y = b_pre_i, z = gamma, w = gscale; gradient events are numbered in the
- *               order of gradient_ops (their indices in the batch), and their inputs are read in chunks
- *               of 8 events, two chunks ahead of their use;
+ *               order of gradient_ops (their indices in the batch), 8 to a chunk;
  *   2 mix:      x = worker | 2 << 8, y = b_post: a trailing mix, directly after its operation (one slot
  *               per worker with b_post != 0);
- *   3 control:  x = 3 << 8, y = 1: the next gradient event is the first of a chunk (the kernel turns to
- *               the other set of inputs and skips the rest of the block of 8 slots, which holds filler);
- *               y = 2: the end; y = 0: filler.
- * The programme is fetched in blocks of 8 slots, ends with an end slot and is padded to a whole block.
- * One call takes as many operations as fit into max_slots slots (a multiple of 8, at least 16; the
- * library uses 8192); *next_op is where the next launch starts.  touched: bit r set iff worker r is used.
+ *   3 control:  x = 3 << 8, y = 2: the end; y = 0: filler; y = 1 or 3, in the first slot of a block of 8
+ *               slots only: a request block.
+ * Request block q (in programme order) names the inputs of chunk q: its slots 1-4 hold the 8 xi pointers
+ * (two to a slot: x, y = low and high word of the first, z, w of the second), the rest is filler; if
+ * full != 0 a second block follows with the c pointers in slots 0-3 and the h pointers in slots 4-7.  A
+ * pointer with bit 0 set is the address of one float that stands for every column: zero_one for an
+ * absent xi or c and for events past the last, zero_one + 1 for an absent h (zero_one: device address
+ * of a float 0 followed by a float 1; only recorded here).  The programme begins with request blocks 0
+ * and 1 (y = 3); request block k + 1 (y = 1) stands before the first gradient event of chunk k >= 1,
+ * where the kernel waits for chunk k's inputs, requests chunk k + 1 into the registers chunk k - 1 used,
+ * and turns to chunk k.  The programme is fetched in blocks of 8 slots, ends with an end slot and is
+ * padded to a whole block.
+ * One call takes as many operations as fit into max_slots slots (a multiple of 8, at least 32, with full
+ * 48; the library uses 8192); *next_op is where the next launch starts.  touched: bit r set iff worker
+ * r is used.  full must be set if any gradient event of the batch has a c or an h and gscale != 0.
  * slots: max_slots entries; gradient_ops: n_ops entries.  coef: the batch's coefficients from
  * a2cid_plan_batch.  The batch's level table is not read: any order that keeps every worker's own
  * operations in sequence gives the same bits (Eq. (1) couples no other), and the batch's order does. */
 int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t first_op,
-                         int64_t max_slots, a2cid_resident_slot *slots, int64_t *n_slots, int64_t *gradient_ops,
-                         int32_t *n_gradient_ops, uint64_t *touched, int64_t *next_op);
+                         int64_t max_slots, int32_t full, const float *zero_one, a2cid_resident_slot *slots,
+                         int64_t *n_slots, int64_t *gradient_ops, int32_t *n_gradient_ops, uint64_t *touched,
+                         int64_t *next_op);
 
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 

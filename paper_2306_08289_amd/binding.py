@@ -83,8 +83,9 @@ SIGNATURES = {
                                    _P(C.c_int64), _P(C.c_double)]),
     "a2cid_plan_resident": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, _P(C.c_int32), _P(C.c_int32), C.c_int64,
                                       C.c_void_p, C.c_void_p, _P(C.c_int32), C.c_void_p, _P(C.c_int32), _P(C.c_int64)]),
-    "a2cid_plan_registers": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
-                                       _P(C.c_int64), C.c_void_p, _P(C.c_int32), _P(C.c_uint64), _P(C.c_int64)]),
+    "a2cid_plan_registers": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, C.c_int64, C.c_int64, C.c_int32,
+                                       C.c_void_p, C.c_void_p, _P(C.c_int64), C.c_void_p, _P(C.c_int32), _P(C.c_uint64),
+                                       _P(C.c_int64)]),
     "a2cid_set_chain_slots": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
@@ -241,11 +242,11 @@ def a2cid_plan_resident(n, batch, coef, first_op=0, waves=0, cols=1):
 
 
 REG_GOSSIP, REG_GRADIENT, REG_MIX, REG_CONTROL = 0, 1, 2, 3      # kind of a register-file slot: x >> 8
-REG_SWITCH, REG_END = 1, 2                                      # y of a control slot
+REG_SWITCH, REG_END, REG_REQUEST = 1, 2, 3                      # y of a control slot
 REG_BLOCK, REG_CHUNK = 8, 8
 
 
-def a2cid_plan_registers(n, batch, coef, first_op=0, max_slots=8192):
+def a2cid_plan_registers(n, batch, coef, first_op=0, max_slots=8192, full=False, zero_one=0x1000):
     """One launch of the register-file kernel from operation first_op on.  Returns a dict: slots (SLOT_DTYPE array),
     gradient_ops (ordinal -> index in the batch), touched (bit mask of workers), next_op."""
     slots = np.zeros(max(int(max_slots), 1), SLOT_DTYPE)
@@ -254,8 +255,8 @@ def a2cid_plan_registers(n, batch, coef, first_op=0, max_slots=8192):
     bs = batch.struct()
     coef = np.ascontiguousarray(coef, COEF_DTYPE)
     _check(load().a2cid_plan_registers(int(n), C.byref(bs), coef.ctypes.data, int(first_op), int(max_slots),
-                                       slots.ctypes.data, C.byref(n_slots), gops.ctypes.data, C.byref(n_g),
-                                       C.byref(touched), C.byref(nxt)))
+                                       int(bool(full)), C.c_void_p(int(zero_one)), slots.ctypes.data, C.byref(n_slots),
+                                       gops.ctypes.data, C.byref(n_g), C.byref(touched), C.byref(nxt)))
     return {"slots": slots[:n_slots.value].copy(), "gradient_ops": gops[:n_g.value].copy(), "touched": touched.value,
             "next_op": nxt.value}
 

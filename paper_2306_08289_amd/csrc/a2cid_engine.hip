@@ -417,40 +417,19 @@ int enqueue_resident(a2cid_ctx *c, const a2cid_event_batch *batch, int32_t *l, i
 
 // One launch of regfile_kernel: writes the programme for the operations of the batch from operation *k on, as many as
 // a staging buffer holds (plan_regfile), uploads it and launches the kernel.  On return *k names the first operation
-// not included.
-int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, int64_t *k) {
+// not included.  full: some gradient event of the batch has a centre or a curvature.
+int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, bool full, int64_t *k) {
     Slot *s;
     if (int rc = acquire_slot(c, &s)) return rc;
     const int64_t k_before = *k;
-    plan_regfile(c->n, batch, c->plan.coef.data(), kResRecords, k, c->regplan);
+    plan_regfile(c->n, batch, c->plan.coef.data(), kResRecords, full, (uintptr_t)c->zero_dev, k, c->regplan);
     if (*k == k_before) return fail(A2CID_EINVAL, "internal: an operation does not fit an empty register-file programme");
     const RegPlan &rp = c->regplan;
-    const int32_t n_grad = (int32_t)rp.grad_op.size();
-    if ((int64_t)rp.programme.size() > kResRecords || n_grad > kSlotOps)
-        return fail(A2CID_EINVAL, "internal: register-file plan exceeds its staging buffers");
+    if ((int64_t)rp.programme.size() > kResRecords || rp.programme.size() % kRegBlock != 0 ||
+        rp.programme.size() < (size_t)(full ? 5 : 3) * kRegBlock)
+        return fail(A2CID_EINVAL, "internal: register-file programme of %zu slots", rp.programme.size());
     std::memcpy(s->res_host, rp.programme.data(), rp.programme.size() * sizeof(ResSlot));
-    // The input table: per chunk of kRegChunk gradient events 8 pointers each for xi, c and h, and one chunk more than
-    // the events fill (the kernel requests two chunks ahead).  Absent inputs and the ordinals past the last event:
-    // the address of the context's zero (or one) with bit 0 set, read by every lane alike.
-    const uint64_t zeros = (uint64_t)(uintptr_t)c->zero_dev | 1u, ones = (uint64_t)(uintptr_t)(c->zero_dev + 1) | 1u;
-    const int32_t n_chunks = (n_grad + kRegChunk - 1) / kRegChunk + 1;
-    uint64_t *table = reinterpret_cast<uint64_t *>(s->gin_host);
-    static_assert(sizeof(GradIn) == 3 * sizeof(uint64_t), "the chunk table reuses the GradIn staging buffer");
-    if ((int64_t)n_chunks * 3 * kRegChunk > kSlotOps * 3)
-        return fail(A2CID_EINVAL, "internal: register-file input table exceeds its staging buffer");
-    for (int32_t g = 0; g < n_chunks * kRegChunk; ++g) {
-        uint64_t *at = table + (size_t)(g / kRegChunk) * 3 * kRegChunk + g % kRegChunk;
-        at[0] = zeros; at[kRegChunk] = zeros; at[2 * kRegChunk] = ones;
-        if (g >= n_grad) continue;
-        const a2cid_op &op = batch->ops[rp.grad_op[(size_t)g]];
-        const bool affine = op.gscale != 0.f;
-        if (op.xi) at[0] = (uint64_t)(uintptr_t)op.xi;
-        if (op.c && affine) at[kRegChunk] = (uint64_t)(uintptr_t)op.c;
-        if (op.h && affine) at[2 * kRegChunk] = (uint64_t)(uintptr_t)op.h;
-    }
     A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * rp.programme.size(), hipMemcpyHostToDevice,
-                             c->stream));
-    A2CID_HIP(hipMemcpyAsync(s->gin_dev, table, sizeof(uint64_t) * 3 * kRegChunk * (size_t)n_chunks, hipMemcpyHostToDevice,
                              c->stream));
     const int n_rows = __builtin_popcountll(rp.touched);
     c->moved_bytes += (double)c->d * (16.0 * n_rows + 4.0 * (rp.n_xi + rp.n_c + rp.n_h));
@@ -463,10 +442,9 @@ int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, int64_t *k) {
     const unsigned blocks = (unsigned)((c->d + 63) / 64);
 #define A2CID_REG(PRE, FULL)                                                                                            \
     hipLaunchKernelGGL((regfile_kernel<PRE, FULL>), dim3(blocks), dim3(64), 0, c->stream, c->x, c->xt, c->ld, c->d,    \
-                       s->res_dev, (uint32_t)(rp.programme.size() * sizeof(ResSlot)),                                   \
-                       reinterpret_cast<const uint64_t *>(s->gin_dev), (uint32_t)(n_chunks - 1), rp.touched,           \
-                       (float)c->alpha, (float)c->alpha_t)
-    switch ((c->order != 0 ? 2 : 0) | ((rp.n_c > 0 || rp.n_h > 0) ? 1 : 0)) {
+                       s->res_dev, (uint32_t)(rp.programme.size() * sizeof(ResSlot)), rp.touched, (float)c->alpha,      \
+                       (float)c->alpha_t)
+    switch ((c->order != 0 ? 2 : 0) | (full ? 1 : 0)) {
         case 0: A2CID_REG(false, false); break;
         case 1: A2CID_REG(false, true); break;
         case 2: A2CID_REG(true, false); break;
@@ -714,9 +692,14 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
         return A2CID_OK;
     }
     if (mode == 4) {
+        bool full = false;
+        for (int64_t q = 0; q < batch->n_ops && !full; ++q) {
+            const a2cid_op &op = batch->ops[q];
+            full = op.kind == A2CID_KIND_GRADIENT && op.gscale != 0.f && (op.c || op.h);
+        }
         int64_t k = 0;
         while (k < batch->n_ops)
-            if (int rc = enqueue_regfile(c, batch, &k)) return rc;
+            if (int rc = enqueue_regfile(c, batch, full, &k)) return rc;
         return A2CID_OK;
     }
     int32_t l = 0;

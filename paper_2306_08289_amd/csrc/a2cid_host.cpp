@@ -779,32 +779,40 @@ void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *
     }
 }
 
-void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, int64_t *k,
-                  RegPlan &plan) {
+void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, bool full,
+                  uintptr_t zero_one, int64_t *k, RegPlan &plan) {
     (void)n;
     plan.programme.clear();
     plan.grad_op.clear();
     plan.touched = 0;
     plan.n_xi = plan.n_c = plan.n_h = 0;
+    plan.request_at.clear();
     auto f2u = [](float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; };
     const ResSlot filler = {kRegControl << 8, 0u, 0u, 0u};
+    const size_t request_slots = full ? 2 * kRegBlock : kRegBlock;
     auto whole_blocks = [](size_t slots) { return (slots + kRegBlock - 1) / kRegBlock * kRegBlock; };
     auto &prog = plan.programme;
+    // a request block for the next chunk of inputs (its pointers are filled in at the end), in a block of its own
+    auto request = [&](uint32_t code) {
+        prog.resize(whole_blocks(prog.size()), filler);
+        plan.request_at.push_back(prog.size());
+        ResSlot ctl = filler;
+        ctl.y = code;
+        prog.push_back(ctl);
+        prog.resize(prog.size() - 1 + request_slots, filler);
+    };
+    request(kRegRequest);                       // chunk 0
+    request(kRegRequest);                       // chunk 1
     for (; *k < batch->n_ops; ++*k) {
         const a2cid_op &op = batch->ops[*k];
         const a2cid_coef &cf = coef[*k];
         const bool is_grad = op.kind == A2CID_KIND_GRADIENT;
-        // a gradient event that opens a chunk of inputs (not the first) comes after a switch slot, in a new block
+        // a gradient event that opens a chunk of inputs (not the first chunk) comes after a switch block
         const bool opens = is_grad && !plan.grad_op.empty() && plan.grad_op.size() % kRegChunk == 0;
-        const size_t at = opens ? whole_blocks(prog.size() + 1) : prog.size();
+        const size_t at = opens ? whole_blocks(prog.size()) + request_slots : prog.size();
         const size_t need = 1 + (cf.b_post_i != 0.f) + (!is_grad && cf.b_post_j != 0.f);
         if ((int64_t)whole_blocks(at + need + 1) > max_slots) break;        // the end slot still has to fit
-        if (opens) {
-            ResSlot sw = filler;
-            sw.y = kRegSwitch;
-            prog.push_back(sw);
-            prog.resize(at, filler);
-        }
+        if (opens) request(kRegSwitch);
         ResSlot r = {0u, 0u, 0u, 0u};
         plan.touched |= (uint64_t)1 << op.i;
         if (!is_grad) {
@@ -828,6 +836,33 @@ void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *c
     end_slot.y = kRegEnd;
     prog.push_back(end_slot);
     prog.resize(whole_blocks(prog.size()), filler);
+    // The pointers: request block q (in programme order) names chunk q, i.e. gradient events 8 q ... 8 q + 7 of the
+    // launch; absent inputs and events past the last one: the address of a zero (or one) with bit 0 set.
+    const uint64_t zeros = (uint64_t)zero_one | 1u, ones = (uint64_t)(zero_one + sizeof(float)) | 1u;
+    auto put = [&](size_t slot, int e, uint64_t p) {         // pointer e (0 ... 7) of the four slots from `slot` on
+        ResSlot &r = prog[slot + (size_t)e / 2];
+        if (e % 2 == 0) { r.x = (uint32_t)p; r.y = (uint32_t)(p >> 32); }
+        else { r.z = (uint32_t)p; r.w = (uint32_t)(p >> 32); }
+    };
+    for (size_t q = 0; q < plan.request_at.size(); ++q) {
+        const size_t base = plan.request_at[q];
+        for (int e = 0; e < kRegChunk; ++e) {
+            const size_t g = q * kRegChunk + (size_t)e;
+            uint64_t xi = zeros, c = zeros, h = ones;
+            if (g < plan.grad_op.size()) {
+                const a2cid_op &op = batch->ops[plan.grad_op[g]];
+                const bool affine = op.gscale != 0.f;
+                if (op.xi) xi = (uint64_t)(uintptr_t)op.xi;
+                if (op.c && affine) c = (uint64_t)(uintptr_t)op.c;
+                if (op.h && affine) h = (uint64_t)(uintptr_t)op.h;
+            }
+            put(base + 1, e, xi);
+            if (full) {
+                put(base + kRegBlock, e, c);
+                put(base + kRegBlock + 4, e, h);
+            }
+        }
+    }
 }
 
 }  // namespace a2cid
@@ -988,8 +1023,9 @@ int a2cid_plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_c
 }
 
 int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t first_op,
-                         int64_t max_slots, a2cid_resident_slot *slots, int64_t *n_slots, int64_t *gradient_ops,
-                         int32_t *n_gradient_ops, uint64_t *touched, int64_t *next_op) {
+                         int64_t max_slots, int32_t full, const float *zero_one, a2cid_resident_slot *slots,
+                         int64_t *n_slots, int64_t *gradient_ops, int32_t *n_gradient_ops, uint64_t *touched,
+                         int64_t *next_op) {
     clear_error();
     if (n < 1 || n > kRegMaxRows) return fail(A2CID_EINVAL, "n = %d out of range (1 ... %d)", n, kRegMaxRows);
     if (!batch || batch->n_ops < 0 || (batch->n_ops > 0 && !batch->ops))
@@ -997,18 +1033,26 @@ int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_
     if (!coef || !slots || !n_slots || !gradient_ops || !n_gradient_ops || !touched || !next_op)
         return fail(A2CID_EINVAL, "an output or coef is NULL");
     if (first_op < 0 || first_op > batch->n_ops) return fail(A2CID_EINVAL, "first_op out of range");
-    if (max_slots < 2 * kRegBlock || max_slots % kRegBlock)
-        return fail(A2CID_EINVAL, "max_slots must be a multiple of %d and at least %d", kRegBlock, 2 * kRegBlock);
+    const int64_t least = (full ? 5 : 3) * kRegBlock;       // the two first requests and a block for the end slot
+    if (max_slots < least + kRegBlock || max_slots % kRegBlock)
+        return fail(A2CID_EINVAL, "max_slots must be a multiple of %d and at least %lld", kRegBlock,
+                    (long long)(least + kRegBlock));
+    if (((uintptr_t)zero_one & 3) != 0) return fail(A2CID_EINVAL, "zero_one must be 4-byte aligned");
+    bool needs_full = false;
     for (int64_t k = 0; k < batch->n_ops; ++k) {
         const a2cid_op &o = batch->ops[k];
         const bool gossip = o.kind == A2CID_KIND_GOSSIP;
         if ((!gossip && o.kind != A2CID_KIND_GRADIENT) || o.i < 0 || o.i >= n || (gossip && (o.j < 0 || o.j >= n || o.j == o.i)))
             return fail(A2CID_EINVAL, "op %lld: bad kind or worker index", (long long)k);
+        if (!gossip && o.gscale != 0.f && (o.c || o.h)) needs_full = true;
+        if (!gossip && ((((uintptr_t)o.xi | (uintptr_t)o.c | (uintptr_t)o.h) & 3) != 0))
+            return fail(A2CID_EINVAL, "op %lld: gradient inputs must be 4-byte aligned", (long long)k);
     }
+    if (needs_full && !full) return fail(A2CID_EINVAL, "the batch has centres or curvatures: full must be set");
     try {
         RegPlan plan;
         int64_t k = first_op;
-        plan_regfile(n, batch, coef, max_slots, &k, plan);
+        plan_regfile(n, batch, coef, max_slots, full != 0, (uintptr_t)zero_one, &k, plan);
         std::memcpy(slots, plan.programme.data(), plan.programme.size() * sizeof(ResSlot));
         *n_slots = (int64_t)plan.programme.size();
         std::copy(plan.grad_op.begin(), plan.grad_op.end(), gradient_ops);

@@ -137,15 +137,22 @@ void plan_resident(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *
 // 16-byte slots, fetched with scalar loads in blocks of kRegBlock slots; a slot's kind is x >> 8:
 //   gossip:    x = i, y = j, z = b_i, w = b_j (fp32 bits)
 //   gradient:  x = i | kRegGradient << 8, y = b_i, z = gamma, w = gscale; its inputs are entry (ordinal % kRegChunk)
-//              of the current chunk of gradient inputs (the launch's gradient events in programme order, kRegChunk
-//              to a chunk, named by the GradIn table)
+//              of the chunk of gradient inputs in use (the launch's gradient events in programme order, kRegChunk to
+//              a chunk)
 //   mix:       x = i | kRegMix << 8, y = b (a trailing mix, right after its operation)
-//   control:   x = kRegControl << 8, y = kRegSwitch (the next gradient event opens the next chunk; the rest of the
-//              block is skipped), kRegEnd (end of the programme) or 0 (filler)
-// Every slot is applied in order; any order that keeps each worker's own operations in sequence gives the same
-// bits, and the planner keeps the batch's.
+//   control:   x = kRegControl << 8, y = kRegEnd (end of the programme), 0 (filler), or, in the first slot of a block
+//              only, kRegSwitch / kRegRequest: a request block
+// A request block names the inputs of one chunk: slots 1-4 hold the 8 xi pointers (two to a slot: x, y = low and high
+// word of the first, z, w of the second), the rest is filler; with centres and curvatures (`full`) a second block
+// follows with the c pointers in slots 0-3 and the h pointers in slots 4-7.  A pointer with bit 0 set is the address
+// of one float that stands for every column (absent input, or an event past the last).  The programme begins with the
+// request blocks of chunks 0 and 1 (kRegRequest); before the first gradient event of chunk k >= 1 comes the request
+// block of chunk k + 1 (kRegSwitch): the kernel waits for chunk k's inputs, requests chunk k + 1 into the registers
+// chunk k - 1 used, and turns to chunk k.
+// Every operation slot is applied in order; any order that keeps each worker's own operations in sequence gives the
+// same bits, and the planner keeps the batch's.
 enum : uint32_t { kRegGossip = 0, kRegGradient = 1, kRegMix = 2, kRegControl = 3 };
-enum : uint32_t { kRegSwitch = 1, kRegEnd = 2 };
+enum : uint32_t { kRegSwitch = 1, kRegEnd = 2, kRegRequest = 3 };
 constexpr int kRegBlock = 8;             // slots per scalar fetch
 constexpr int kRegChunk = 8;             // gradient events per chunk of inputs (two chunks are held in registers)
 constexpr int32_t kRegMaxRows = 64;
@@ -155,11 +162,14 @@ struct RegPlan {
     std::vector<int64_t> grad_op;       // gradient ordinal -> index of the event in the batch
     uint64_t touched = 0;               // bit r: worker r is read and written by the launch
     int32_t n_xi = 0, n_c = 0, n_h = 0; // gradient inputs the launch reads
+    std::vector<size_t> request_at;     // work array: first slot of request block q
 };
-// Writes the programme for the operations of the batch from *k on, as many as max_slots slots hold (at least one
-// block more than the longest single operation needs).  On return *k names the first operation not included.
-// The batch must be valid (plan_batch passed) and n <= kRegMaxRows.
-void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, int64_t *k,
-                  RegPlan &plan);
+// Writes the programme for the operations of the batch from *k on, as many as max_slots slots hold (a multiple of
+// kRegBlock; at least one block more than the first requests and the longest single operation need).  On return *k
+// names the first operation not included.  full: request blocks carry c and h pointers (needed as soon as one event
+// of the launch has a centre or a curvature with gscale != 0); zero_one: device address of a float 0 followed by a
+// float 1.  The batch must be valid (plan_batch passed) and n <= kRegMaxRows.
+void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, bool full,
+                  uintptr_t zero_one, int64_t *k, RegPlan &plan);
 
 }  // namespace a2cid

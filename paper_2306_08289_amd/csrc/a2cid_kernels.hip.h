@@ -805,18 +805,19 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 //   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
 //   FULL only: v[144:151], v[152:159] the sets of centres c, v[160:167], v[168:175] of curvatures h
 //   v[TB .. TB+10]           temporaries (TB = 144, FULL: 176)
-//   s[36:67], s[68:99] two blocks of 8 slots (one applied, one being fetched); s[68:83] also the eight input pointers
-//   of a request; s26 byte position of the next fetch, s27, s31 scratch, s28 index of the next gradient event's
-//   inputs (set offset included), s29 offset of the set in use (0 or 8), s30 the chunk to request next
+//   s[36:67], s[68:99] two blocks of 8 slots (one applied, one being fetched), s26 byte position of the next fetch,
+//   s27, s31 scratch, s28 index of the next gradient event's inputs (set offset included), s29 offset of the set in
+//   use (0 or 8), s30 (FULL) set while the block of c and h pointers after a request is to be passed over
 // Programme (layout: a2cid_internal.h): every slot is applied in order; a gossip slot (the common case) falls
 // through its kind test, the other kinds are handled out of line.  The loop ends at the end slot, and in any case
 // when the position reaches the programme's length.
-// Gradient inputs: chunk k of kRegChunk events uses set k % 2.  A switch slot precedes the first event of every chunk
-// but the first: the wave waits for the other set (requested a whole chunk ago; nothing else is in flight), requests
-// chunk k + 2 into the set just used up, and goes on with the next block (the planner leaves the rest of the block
-// empty).  The input table holds, per chunk, 8 pointers each for xi, c and h (192 bytes); a pointer with bit 0 set
-// is the address of one float that stands for every column (absent input); ordinals past the last event repeat a
-// valid entry, and the chunk index is clamped to the table's last.
+// Gradient inputs: chunk k of kRegChunk events uses set k % 2.  The pointers travel in the programme itself, in
+// request blocks (8 xi pointers in slots 1-4; FULL: the block after it holds 8 c and 8 h pointers), so they arrive
+// with the block prefetch.  The programme begins with the request blocks of chunks 0 and 1.  The request block of
+// chunk k + 1 precedes the first event of chunk k >= 1; its first slot is a switch slot: the wave waits for chunk k's
+// set (requested a whole chunk ago; nothing else is in flight), requests chunk k + 1 into the set chunk k - 1 used,
+// turns to chunk k's set and goes on with the next block.  A pointer with bit 0 set is the address of one float
+// that stands for every column (an absent input, or an event past the last).
 // The arithmetic is the shared sequence of individually rounded operations (mix, gossip_jump, gradient_jump: the
 // same subtractions and fused multiply-adds in the same order), so results agree bit for bit with the other kernels.
 // Valid only while every gradient input of the batch is final when the batch is submitted, like the resident kernel.
@@ -902,8 +903,8 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_cbranch_scc0 L_o" id "_%=\n\t"                                                                               \
     GOSSIP(TB, X, Y, Z, W)                                                                                          \
     "\nL_d" id "_%=:\n\t"
-// the other kinds of the same slot, out of line
-#define A2R_OTHER(TB, GRAD, AT, id, X, Y, Z, W)                                                                     \
+// the other kinds of the same slot, out of line, up to the control slots
+#define A2R_OTHER_HEAD(TB, GRAD, AT, id, X, Y, Z, W)                                                                \
     "\nL_o" id "_%=:\n\t"                                                                                           \
     "s_lshr_b32 s27, " X ", 8\n\t"                                                                                  \
     "s_and_b32 s31, " X ", 0xff\n\t"                                                                                \
@@ -916,60 +917,114 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_cbranch_scc0 L_c" id "_%=\n\t"                                                                               \
     A2R_MIX(TB, Y)                                                                                                  \
     "s_branch L_d" id "_%=\n"                                                                                       \
-    "L_c" id "_%=:\n\t"                                                                                             \
-    "s_cmp_eq_u32 " Y ", 1\n\t"                                                                                     \
-    "s_cbranch_scc1 L_switch_%=\n\t"                                                                                \
+    "L_c" id "_%=:\n\t"
+// a control slot: the end, or filler; in the first slot of a block (FIRST) also a switch
+#define A2R_OTHER(TB, GRAD, AT, PH, id, X, Y, Z, W)                                                                 \
+    A2R_OTHER_HEAD(TB, GRAD, AT, id, X, Y, Z, W)                                                                    \
     "s_cmp_eq_u32 " Y ", 2\n\t"                                                                                     \
     "s_cbranch_scc1 L_end_%=\n\t"                                                                                   \
     "s_branch L_d" id "_%=\n\t"
-// the eight slots of block A (s[36:67]) and of block B (s[68:99])
-#define A2R_SLOTS_A(M, ...)                                                                                         \
-    M(__VA_ARGS__, "a0", "s36", "s37", "s38", "s39") M(__VA_ARGS__, "a1", "s40", "s41", "s42", "s43")               \
+#define A2R_OTHER_FIRST(TB, GRAD, AT, PH, id, X, Y, Z, W)                                                           \
+    A2R_OTHER_HEAD(TB, GRAD, AT, id, X, Y, Z, W)                                                                    \
+    "s_cmp_eq_u32 " Y ", 1\n\t"                                                                                     \
+    "s_cbranch_scc1 L_sw" PH "_%=\n\t"                                                                              \
+    "s_cmp_eq_u32 " Y ", 2\n\t"                                                                                     \
+    "s_cbranch_scc1 L_end_%=\n\t"                                                                                   \
+    "s_branch L_d" id "_%=\n\t"
+// the eight slots of block A (s[36:67]) and of block B (s[68:99]); M0 for the first slot, M for the others
+#define A2R_SLOTS_A(M0, M, ...)                                                                                     \
+    M0(__VA_ARGS__, "a0", "s36", "s37", "s38", "s39") M(__VA_ARGS__, "a1", "s40", "s41", "s42", "s43")              \
     M(__VA_ARGS__, "a2", "s44", "s45", "s46", "s47") M(__VA_ARGS__, "a3", "s48", "s49", "s50", "s51")               \
     M(__VA_ARGS__, "a4", "s52", "s53", "s54", "s55") M(__VA_ARGS__, "a5", "s56", "s57", "s58", "s59")               \
     M(__VA_ARGS__, "a6", "s60", "s61", "s62", "s63") M(__VA_ARGS__, "a7", "s64", "s65", "s66", "s67")
-#define A2R_SLOTS_B(M, ...)                                                                                         \
-    M(__VA_ARGS__, "b0", "s68", "s69", "s70", "s71") M(__VA_ARGS__, "b1", "s72", "s73", "s74", "s75")               \
+#define A2R_SLOTS_B(M0, M, ...)                                                                                     \
+    M0(__VA_ARGS__, "b0", "s68", "s69", "s70", "s71") M(__VA_ARGS__, "b1", "s72", "s73", "s74", "s75")              \
     M(__VA_ARGS__, "b2", "s76", "s77", "s78", "s79") M(__VA_ARGS__, "b3", "s80", "s81", "s82", "s83")               \
     M(__VA_ARGS__, "b4", "s84", "s85", "s86", "s87") M(__VA_ARGS__, "b5", "s88", "s89", "s90", "s91")               \
     M(__VA_ARGS__, "b6", "s92", "s93", "s94", "s95") M(__VA_ARGS__, "b7", "s96", "s97", "s98", "s99")
 
-// one input: pointer pair LO:HI of the batch in s[68:83], destination register DST
-#define A2R_REQ1(TB, DST, LO, PAIR)                                                                                 \
-    "s_bitcmp1_b32 " LO ", 0\n\t"                                                                                   \
+// one input: its pointer in s[P+2k : P+2k+1] (bit 0: one float for every column), destination v[B+k]
+#define A2R_REQ1(TB, B, P, k)                                                                                       \
+    "s_bitcmp1_b32 s[" P "+2*" #k "], 0\n\t"                                                                        \
     "s_cselect_b64 vcc, -1, 0\n\t"                                                                                  \
     "v_cndmask_b32_e64 " A2R_T(TB, 10) ", %[voff], 0, vcc\n\t"                                                      \
-    "s_and_b32 " LO ", " LO ", -4\n\t"                                                                              \
-    "global_load_dword " DST ", " A2R_T(TB, 10) ", " PAIR " nt\n\t"
-// eight inputs of one kind: the pointers at byte offset OFF of the table, destinations v[B .. B+7]
-#define A2R_REQ8(TB, OFF, B)                                                                                        \
-    "s_load_dwordx16 s[68:83], %[gin], " OFF "\n\t"                                                                 \
+    "s_and_b32 s[" P "+2*" #k "], s[" P "+2*" #k "], -4\n\t"                                                        \
+    "global_load_dword v[" B "+" #k "], " A2R_T(TB, 10) ", s[" P "+2*" #k ":" P "+2*" #k "+1] nt\n\t"
+// eight inputs of one kind: pointers in s[P : P+15], destinations v[B : B+7]
+#define A2R_REQ8(TB, B, P)                                                                                          \
+    A2R_REQ1(TB, B, P, 0) A2R_REQ1(TB, B, P, 1) A2R_REQ1(TB, B, P, 2) A2R_REQ1(TB, B, P, 3)                         \
+    A2R_REQ1(TB, B, P, 4) A2R_REQ1(TB, B, P, 5) A2R_REQ1(TB, B, P, 6) A2R_REQ1(TB, B, P, 7)
+// A request block: slot 0 a control slot, slots 1-4 the xi pointers of a chunk.  With centres and curvatures (FULL)
+// the block after it holds the c pointers (slots 0-3) and the h pointers (slots 4-7).  XI: first SGPR of slot 1 of
+// the request block, C / H: first SGPR of slots 0 / 4 of the other block; SET: "0" or "8".
+#define A2R_REQ_PLAIN(TB, SET, XI, C, H) A2R_REQ8(TB, "128+" SET, XI)
+#define A2R_REQ_FULL(TB, SET, XI, C, H)                                                                             \
+    A2R_REQ8(TB, "128+" SET, XI) A2R_REQ8(TB, "144+" SET, C) A2R_REQ8(TB, "160+" SET, H)
+// After a request with centres and curvatures the block of c and h pointers is passed over (s30 = 1: skip a block).
+#define A2R_SKIP_SET_PLAIN
+#define A2R_SKIP_SET_FULL "s_mov_b32 s30, 1\n\t"
+#define A2R_SKIP_TEST_PLAIN(PH)
+#define A2R_SKIP_TEST_FULL(PH)                                                                                      \
+    "s_cmp_eq_u32 s30, 0\n\t"                                                                                       \
+    "s_cbranch_scc1 L_go" PH "_%=\n\t"                                                                              \
+    "s_mov_b32 s30, 0\n\t"                                                                                          \
+    "s_branch L_end" PH "_%=\n"                                                                                     \
+    "L_go" PH "_%=:\n\t"
+// A switch slot (first slot of a block, phase PH): the wave waits for the set of inputs requested a chunk ago
+// (nothing else is in flight; with centres and curvatures also for the block of their pointers, being fetched),
+// requests the pointers of this block into the set just used up, turns to the other set and goes on with the
+// next block.
+#define A2R_SWITCH(TB, PH, REQ, VARIANT, XI, C, H)                                                                  \
+    "\nL_sw" PH "_%=:\n\t"                                                                                          \
+    A2R_OFF                                                                                                         \
+    "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"                                                                             \
+    "s_cmp_eq_u32 s29, 0\n\t"                                                                                       \
+    "s_cbranch_scc0 L_sw" PH "b_%=\n\t"                                                                             \
+    REQ(TB, "0", XI, C, H)                                                                                          \
+    "s_mov_b32 s29, 8\n\t"                                                                                          \
+    "s_mov_b32 s28, 8\n\t"                                                                                          \
+    A2R_SKIP_SET_##VARIANT                                                                                          \
+    "s_branch L_end" PH "_%=\n"                                                                                     \
+    "L_sw" PH "b_%=:\n\t"                                                                                           \
+    REQ(TB, "8", XI, C, H)                                                                                          \
+    "s_mov_b32 s29, 0\n\t"                                                                                          \
+    "s_mov_b32 s28, 0\n\t"                                                                                          \
+    A2R_SKIP_SET_##VARIANT                                                                                          \
+    "s_branch L_end" PH "_%=\n\t"
+
+// The first blocks of a programme are the request blocks of chunks 0 and 1 (2 blocks; 4 with centres and curvatures).
+#define A2R_FIRST_PLAIN(TB)                                                                                         \
+    "s_load_dwordx16 s[36:51], %[prog], 0x0\n\t"                                                                    \
+    "s_load_dwordx16 s[52:67], %[prog], 0x40\n\t"                                                                   \
+    "s_load_dwordx16 s[68:83], %[prog], 0x80\n\t"                                                                   \
+    "s_load_dwordx16 s[84:99], %[prog], 0xc0\n\t"                                                                   \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
-    A2R_REQ1(TB, "v[" B "+0]", "s68", "s[68:69]") A2R_REQ1(TB, "v[" B "+1]", "s70", "s[70:71]")                     \
-    A2R_REQ1(TB, "v[" B "+2]", "s72", "s[72:73]") A2R_REQ1(TB, "v[" B "+3]", "s74", "s[74:75]")                     \
-    A2R_REQ1(TB, "v[" B "+4]", "s76", "s[76:77]") A2R_REQ1(TB, "v[" B "+5]", "s78", "s[78:79]")                     \
-    A2R_REQ1(TB, "v[" B "+6]", "s80", "s[80:81]") A2R_REQ1(TB, "v[" B "+7]", "s82", "s[82:83]")
-// a whole chunk (table byte offset in s27) into set SET ("0" or "8")
-#define A2R_REQ_PLAIN(TB, SET) A2R_REQ8(TB, "s27", "128+" SET)
-#define A2R_REQ_FULL(TB, SET)                                                                                       \
-    A2R_REQ8(TB, "s27", "128+" SET)                                                                                 \
-    "s_add_u32 s31, s27, 64\n\t" A2R_REQ8(TB, "s31", "144+" SET)                                                    \
-    "s_add_u32 s31, s27, 128\n\t" A2R_REQ8(TB, "s31", "160+" SET)
+    A2R_REQ_PLAIN(TB, "0", "40", "0", "0") A2R_REQ_PLAIN(TB, "8", "72", "0", "0")                                   \
+    "s_mov_b32 s26, 0x100\n\t"
+#define A2R_FIRST_FULL(TB)                                                                                          \
+    "s_load_dwordx16 s[36:51], %[prog], 0x0\n\t"                                                                    \
+    "s_load_dwordx16 s[52:67], %[prog], 0x40\n\t"                                                                   \
+    "s_load_dwordx16 s[68:83], %[prog], 0x80\n\t"                                                                   \
+    "s_load_dwordx16 s[84:99], %[prog], 0xc0\n\t"                                                                   \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
+    A2R_REQ_FULL(TB, "0", "40", "68", "84")                                                                         \
+    "s_load_dwordx16 s[36:51], %[prog], 0x100\n\t"                                                                  \
+    "s_load_dwordx16 s[52:67], %[prog], 0x140\n\t"                                                                  \
+    "s_load_dwordx16 s[68:83], %[prog], 0x180\n\t"                                                                  \
+    "s_load_dwordx16 s[84:99], %[prog], 0x1c0\n\t"                                                                  \
+    "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
+    A2R_REQ_FULL(TB, "8", "40", "68", "84")                                                                         \
+    "s_mov_b32 s26, 0x200\n\t"
 
 // s26: byte offset of the next block to fetch.  Block A is fetched while block B is being applied and the other
 // way round; scalar loads return in no fixed order, so the wait for a block comes before the next fetch is issued.
-#define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, REQ)                                                                    \
-    "s_mov_b32 s26, 0\n\t"                                                                                          \
+// VARIANT: PLAIN or FULL (pasted into macro names).
+#define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, VARIANT)                                                                \
     "s_mov_b32 s28, 0\n\t"                                                                                          \
     "s_mov_b32 s29, 0\n\t"                                                                                          \
-    "s_mov_b32 s30, 2\n\t"                                                                                          \
-    "s_mov_b32 s27, 0\n\t"                                                                                          \
-    REQ(TB, "0")                                                                                                    \
-    "s_min_u32 s27, %[last], 1\n\t"                                                                                 \
-    "s_mul_i32 s27, s27, 192\n\t"                                                                                   \
-    REQ(TB, "8")                                                                                                    \
-    "s_waitcnt vmcnt(0)\n"                                                                                          \
-    "L_fetch_%=:\n\t"                                                                                               \
+    "s_mov_b32 s30, 0\n\t"                                                                                          \
+    A2R_FIRST_##VARIANT(TB)                                                                                         \
+    "s_waitcnt vmcnt(0)\n\t"                                                                                        \
     "s_cmp_lt_u32 s26, %[nbytes]\n\t"                                                                               \
     "s_cbranch_scc0 L_end_%=\n\t"                                                                                   \
     "s_load_dwordx16 s[36:51], %[prog], s26\n\t"                                                                    \
@@ -985,7 +1040,9 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_load_dwordx16 s[84:99], %[prog], s27\n"                                                                      \
     "L_nob_%=:\n\t"                                                                                                 \
     "s_add_u32 s26, s26, 128\n\t"                                                                                   \
-    A2R_SLOTS_A(A2R_SLOT, TB, GOSSIP)                                                                               \
+    A2R_SKIP_TEST_##VARIANT("a")                                                                                    \
+    A2R_SLOTS_A(A2R_SLOT, A2R_SLOT, TB, GOSSIP)                                                                     \
+    "\nL_enda_%=:\n\t"                                                                                              \
     "s_cmp_le_u32 s26, %[nbytes]\n\t"                                                                               \
     "s_cbranch_scc0 L_end_%=\n\t"                                                                                   \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
@@ -996,31 +1053,17 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_load_dwordx16 s[52:67], %[prog], s27\n"                                                                      \
     "L_noa_%=:\n\t"                                                                                                 \
     "s_add_u32 s26, s26, 128\n\t"                                                                                   \
-    A2R_SLOTS_B(A2R_SLOT, TB, GOSSIP)                                                                               \
+    A2R_SKIP_TEST_##VARIANT("b")                                                                                    \
+    A2R_SLOTS_B(A2R_SLOT, A2R_SLOT, TB, GOSSIP)                                                                     \
+    "\nL_endb_%=:\n\t"                                                                                              \
     "s_cmp_le_u32 s26, %[nbytes]\n\t"                                                                               \
     "s_cbranch_scc1 L_blka_%=\n\t"                                                                                  \
     "s_branch L_end_%=\n\t"                                                                                         \
-    A2R_SLOTS_A(A2R_OTHER, TB, GRAD, AT)                                                                            \
-    A2R_SLOTS_B(A2R_OTHER, TB, GRAD, AT)                                                                            \
-    "\nL_switch_%=:\n\t"                                                                                            \
-    A2R_OFF                                                                                                         \
-    "s_waitcnt vmcnt(0) lgkmcnt(0)\n\t"                                                                             \
-    "s_sub_u32 s26, s26, 128\n\t"                                                                                   \
-    "s_min_u32 s27, s30, %[last]\n\t"                                                                               \
-    "s_mul_i32 s27, s27, 192\n\t"                                                                                   \
-    "s_add_u32 s30, s30, 1\n\t"                                                                                     \
-    "s_cmp_eq_u32 s29, 0\n\t"                                                                                       \
-    "s_cbranch_scc0 L_setb_%=\n\t"                                                                                  \
-    REQ(TB, "0")                                                                                                    \
-    "s_mov_b32 s29, 8\n\t"                                                                                          \
-    "s_mov_b32 s28, 8\n\t"                                                                                          \
-    "s_branch L_fetch_%=\n"                                                                                         \
-    "L_setb_%=:\n\t"                                                                                                \
-    REQ(TB, "8")                                                                                                    \
-    "s_mov_b32 s29, 0\n\t"                                                                                          \
-    "s_mov_b32 s28, 0\n\t"                                                                                          \
-    "s_branch L_fetch_%=\n"                                                                                         \
-    "L_end_%=:\n\t"                                                                                                 \
+    A2R_SLOTS_A(A2R_OTHER_FIRST, A2R_OTHER, TB, GRAD, AT, "a")                                                      \
+    A2R_SLOTS_B(A2R_OTHER_FIRST, A2R_OTHER, TB, GRAD, AT, "b")                                                      \
+    A2R_SWITCH(TB, "a", A2R_REQ_##VARIANT, VARIANT, "40", "68", "84")                                               \
+    A2R_SWITCH(TB, "b", A2R_REQ_##VARIANT, VARIANT, "72", "36", "52")                                               \
+    "\nL_end_%=:\n\t"                                                                                               \
     A2R_OFF                                                                                                         \
     "s_waitcnt vmcnt(0) lgkmcnt(0)"
 
@@ -1035,7 +1078,6 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 template <bool PRE, bool FULL>
 __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
                                                      int64_t d, const ResSlot *__restrict__ recs, uint32_t n_bytes,
-                                                     const uint64_t *__restrict__ gin, uint32_t last_chunk,
                                                      uint64_t touched, float alpha, float alpha_t) {
     const uint32_t lane = threadIdx.x;
     const int64_t col0 = (int64_t)blockIdx.x * 64;
@@ -1059,21 +1101,21 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
     const float neg_alpha = -alpha, neg_alpha_t = -alpha_t;
 #define A2R_OPERANDS                                                                                                \
     : "+{v[0:31]}"(X0), "+{v[32:63]}"(X1), "+{v[64:95]}"(T0), "+{v[96:127]}"(T1)                                    \
-    : [prog] "s"(recs), [nbytes] "s"(n_bytes), [gin] "s"(gin), [last] "s"(last_chunk), [voff] "v"(voff),            \
+    : [prog] "s"(recs), [nbytes] "s"(n_bytes), [voff] "v"(voff),                                                    \
       [al] "s"(alpha), [nal] "s"(neg_alpha), [alt] "s"(alpha_t), [nalt] "s"(neg_alpha_t)
     if constexpr (!FULL) {
         if constexpr (!PRE)
-            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_0, A2R_GRAD_PLAIN, 2, A2R_REQ_PLAIN) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_0, A2R_GRAD_PLAIN, 2, PLAIN) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
         else
-            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_1, A2R_GRAD_PLAIN, 8, A2R_REQ_PLAIN) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_1, A2R_GRAD_PLAIN, 8, PLAIN) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
     } else {
         if constexpr (!PRE)
-            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_0, A2R_GRAD_FULL, 2, A2R_REQ_FULL) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_0, A2R_GRAD_FULL, 2, FULL) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
         else
-            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_1, A2R_GRAD_FULL, 8, A2R_REQ_FULL) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_1, A2R_GRAD_FULL, 8, FULL) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
     }
 #undef A2R_OPERANDS

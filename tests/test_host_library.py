@@ -767,21 +767,51 @@ def test_resident_programmes_on_arbitrary_small_batches():
 
 # ---- the register-file kernel's programme ------------------------------------------------------------------------
 
-def _run_register_launch(n, batch, coef, plan, first_op, max_slots):
-    """Interprets one launch the way regfile_kernel does and checks it against the batch: blocks of 8 slots, two sets of
-    gradient inputs of 8 events each (set = chunk % 2), a switch slot before the first event of every later chunk, after
-    which the rest of the block is skipped.  Returns the indices of the operations applied, in order."""
+REG_ZERO_ONE = 0x7000                   # stand-in for the device address of the constants 0.0 and 1.0
+
+
+def _run_register_launch(n, batch, coef, plan, first_op, max_slots, full=False):
+    """Interprets one launch the way regfile_kernel does and checks it against the batch.  The programme starts with
+    the request blocks of chunks 0 and 1 (8 gradient events to a chunk; set of registers = chunk % 2); a switch block
+    (first slot of a block) precedes the first event of every later chunk: the kernel requests its pointers into the
+    set just used up and turns to the other set; nothing else of a request block (nor, with centres and curvatures,
+    of the block after it) is executed.  Returns the indices of the operations applied, in order."""
     ops, slots, gops = batch.ops, plan["slots"], [int(k) for k in plan["gradient_ops"]]
     B, K = binding.REG_BLOCK, binding.REG_CHUNK
+    per_request = 2 * B if full else B
     assert len(slots) % B == 0 and 0 < len(slots) <= max_slots
+
+    def pointers(at):
+        """The three lists of 8 pointers a request block at slot `at` names."""
+        def eight(first):
+            out = []
+            for s in slots[first:first + 4]:
+                out += [int(s["x"]) | int(s["y"]) << 32, int(s["z"]) | int(s["w"]) << 32]
+            return out
+        none = [None] * K
+        return eight(at + 1), eight(at + B) if full else none, eight(at + B + 4) if full else none
+
+    def expected(k_op):
+        """What the registers must hold for gradient event k_op: (xi, c, h) as the kernel reads them."""
+        op = ops[k_op]
+        affine = op["gscale"] != 0
+        want = (int(op["xi"]) if op["xi"] else REG_ZERO_ONE | 1,
+                int(op["c"]) if op["c"] and affine else REG_ZERO_ONE | 1,
+                int(op["h"]) if op["h"] and affine else (REG_ZERO_ONE + 4) | 1)
+        return want if full else (want[0], None, None)
+
+    for q in (0, 1):                                   # the two first requests
+        ctl = slots[q * per_request]
+        assert (int(ctl["x"]) >> 8, int(ctl["y"])) == (binding.REG_CONTROL, binding.REG_REQUEST)
+    sets = {0: pointers(0), 8: pointers(per_request)}  # set offset -> the pointers it was filled from
     applied, touched = [], 0
-    k = first_op                       # the next operation of the batch
-    pending_mix = []                   # trailing mixes the last operation still owes: (worker, bits)
-    sets = {0: 0, 8: 1}                # set offset -> the chunk whose inputs it holds (requested two chunks ahead)
-    sel, q, gnext, pos, ended = 0, 0, 2, 0, False
+    k = first_op                                       # the next operation of the batch
+    pending_mix = []                                   # trailing mixes the last operation still owes: (worker, bits)
+    sel, q, n_grad, ended = 0, 0, 0, False
+    pos = 2 * per_request
     while pos < len(slots) and not ended:
-        block, pos = slots[pos:pos + B], pos + B
-        for s in block:
+        block, at, pos = slots[pos:pos + B], pos, pos + B
+        for j, s in enumerate(block):
             kind, x, y = int(s["x"]) >> 8, int(s["x"]), int(s["y"])
             if kind != binding.REG_MIX:
                 assert not pending_mix, "a trailing mix is missing"
@@ -797,8 +827,10 @@ def _run_register_launch(n, batch, coef, plan, first_op, max_slots):
                 assert op["kind"] == binding.KIND_GRADIENT and (x & 255) == int(op["i"])
                 assert (y, int(s["z"]), int(s["w"])) == (_f32_bits(cf["b_pre_i"]), _f32_bits(op["gamma"]), _f32_bits(op["gscale"]))
                 assert q - sel < K, "more gradient events than a set of inputs holds"
-                assert gops[sets[sel] * K + (q - sel)] == k, "the inputs in the registers belong to another event"
-                q += 1
+                have = tuple(p[q - sel] for p in sets[sel])
+                assert have == expected(k), "the inputs in the registers belong to another event"
+                assert gops[n_grad] == k
+                q += 1; n_grad += 1
                 pending_mix = [(int(op["i"]), _f32_bits(cf["b_post_i"]))] if cf["b_post_i"] != 0 else []
                 touched |= 1 << (x & 255)
                 applied.append(k); k += 1
@@ -807,11 +839,13 @@ def _run_register_launch(n, batch, coef, plan, first_op, max_slots):
             else:
                 assert kind == binding.REG_CONTROL and (x & 255) == 0
                 if y == binding.REG_SWITCH:
-                    sets[sel] = gnext                  # the set just used up receives the chunk after the next
-                    gnext += 1
+                    assert j == 0, "a switch slot anywhere but at the head of a block is not acted on"
+                    sets[sel] = pointers(at)           # the set just used up receives the pointers of this block
                     sel = 8 - sel
                     q = sel
-                    break                              # the rest of the block is skipped
+                    if full:
+                        pos += B                       # the block of c and h pointers is passed over
+                    break                              # and so is the rest of this one
                 if y == binding.REG_END:
                     ended = True
                     break
@@ -824,11 +858,12 @@ def _run_register_launch(n, batch, coef, plan, first_op, max_slots):
     return applied
 
 
-def _register_plans_cover(n, batch, coef, max_slots=8192):
+def _register_plans_cover(n, batch, coef, max_slots=8192, full=False):
     k, launches = 0, 0
     while k < len(batch.ops):
-        plan = binding.a2cid_plan_registers(n, batch, coef, first_op=k, max_slots=max_slots)
-        assert _run_register_launch(n, batch, coef, plan, k, max_slots), "a launch must take at least one operation"
+        plan = binding.a2cid_plan_registers(n, batch, coef, first_op=k, max_slots=max_slots, full=full,
+                                            zero_one=REG_ZERO_ONE)
+        assert _run_register_launch(n, batch, coef, plan, k, max_slots, full), "a launch must take at least one operation"
         k = plan["next_op"]
         launches += 1
     return launches
@@ -849,9 +884,17 @@ def test_register_programmes_on_scheduler_batches(topo, n, edge_rate):
             b.t_sync = float(b.ops["t"].max()) + 0.5
         t, coef = binding.a2cid_plan_batch(n, u, v, edge_rate, 0.7, t, b)
         launches = _register_plans_cover(n, b, coef)
-        assert launches == (1 if size <= 4096 else 2)
+        assert launches == 1 if size <= 4096 else launches in (2, 3)
         assert _register_plans_cover(n, b, coef, max_slots=64) >= size // 64     # short programmes: many launches
-        assert _register_plans_cover(n, b, coef, max_slots=16) >= size // 16
+        assert _register_plans_cover(n, b, coef, max_slots=32) >= size // 32
+        # with centres and curvatures on some events: request blocks of two blocks
+        b.ops["c"][grad] = np.where(np.arange(int(grad.sum())) % 3 == 0, 0, (1 << 40) + 16 * np.arange(int(grad.sum())))
+        b.ops["h"][grad] = np.where(np.arange(int(grad.sum())) % 2 == 0, 0, (1 << 41) + 16 * np.arange(int(grad.sum())))
+        _register_plans_cover(n, b, coef, full=True)
+        _register_plans_cover(n, b, coef, max_slots=48, full=True)
+        if grad.any() and size > 1:
+            with pytest.raises(a2.A2cidError):                                    # centres need the two-block requests
+                binding.a2cid_plan_registers(n, b, coef)
     s.close()
 
 
@@ -860,33 +903,51 @@ def test_register_programme_of_an_empty_range_and_of_gradient_events_only():
     ops = np.zeros(40, binding.OP_DTYPE)
     ops["kind"], ops["i"], ops["j"], ops["t"] = binding.KIND_GRADIENT, np.arange(40) % n, -1, 1.0 + np.arange(40) // n
     ops["gamma"], ops["xi"] = 0.1, 4096 * (1 + np.arange(40))
+    ops["xi"][5] = 0                                                 # an event without xi
     b = binding.Batch(ops, list(range(0, 41, 8)))
     u, v = _uv(graph.ring(n))
     _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.5, np.zeros(n), b)
-    plan = binding.a2cid_plan_registers(n, b, coef)
+    plan = binding.a2cid_plan_registers(n, b, coef, zero_one=REG_ZERO_ONE)
     assert _run_register_launch(n, b, coef, plan, 0, 8192) == list(range(40))
-    # 40 events: chunks of 8, a switch slot before events 8, 16, 24, 32, each followed by filler to the end of its block
-    kinds = [int(x) >> 8 for x in plan["slots"]["x"]]
-    assert sum(1 for s in plan["slots"] if int(s["x"]) >> 8 == binding.REG_CONTROL and int(s["y"]) == binding.REG_SWITCH) == 4
-    assert kinds.count(binding.REG_GRADIENT) == 40 and len(kinds) == 10 * 8
+    # 40 events in chunks of 8: two first request blocks, then a switch block (requesting chunks 2, 3, 4, 5) before
+    # events 8, 16, 24, 32, each block of 8 events in a block of its own, the end slot in the last
+    sl = plan["slots"]
+    kinds = [int(x) >> 8 for x in sl["x"]]
+    heads = [(kinds[at], int(sl["y"][at])) for at in range(0, len(sl), 8)]
+    req, sw, ctl = binding.REG_REQUEST, binding.REG_SWITCH, binding.REG_CONTROL
+    assert heads == [(ctl, req), (ctl, req), (1, heads[2][1]), (ctl, sw), (1, heads[4][1]), (ctl, sw), (1, heads[6][1]),
+                     (ctl, sw), (1, heads[8][1]), (ctl, sw), (1, heads[10][1]), (ctl, binding.REG_END)]
+    assert kinds.count(binding.REG_GRADIENT) == 40
+    xi_of_chunk_0 = [int(s["x"]) | int(s["y"]) << 32 for s in sl[1:5]] + [int(s["z"]) | int(s["w"]) << 32 for s in sl[1:5]]
+    assert sorted(xi_of_chunk_0) == sorted([4096 * (1 + g) for g in range(8) if g != 5] + [REG_ZERO_ONE | 1])
+    last_request = 9 * 8                                             # chunk 5: no such events
+    assert all(int(s["x"]) == REG_ZERO_ONE | 1 and int(s["z"]) == REG_ZERO_ONE | 1 for s in sl[last_request + 1:last_request + 5])
     empty = binding.a2cid_plan_registers(n, b, coef, first_op=40)
-    assert empty["next_op"] == 40 and empty["touched"] == 0 and len(empty["slots"]) == 8
-    assert (int(empty["slots"][0]["x"]) >> 8, int(empty["slots"][0]["y"])) == (binding.REG_CONTROL, binding.REG_END)
+    assert empty["next_op"] == 40 and empty["touched"] == 0 and len(empty["slots"]) == 24
+    assert (int(empty["slots"][16]["x"]) >> 8, int(empty["slots"][16]["y"])) == (binding.REG_CONTROL, binding.REG_END)
 
 
 def test_register_planner_rejects_malformed_input():
     ops = _random_ops(np.random.default_rng(0), 4, 20, 0.3)
+    ops["c"] = ops["h"] = 0
     coef = np.zeros(20, binding.COEF_DTYPE)
     good = binding.Batch(ops, [0, 20])
-    for kwargs in ({"first_op": 21}, {"first_op": -1}, {"max_slots": 8}, {"max_slots": 20}, {"max_slots": 0}):
+    for kwargs in ({"first_op": 21}, {"first_op": -1}, {"max_slots": 24}, {"max_slots": 36}, {"max_slots": 0},
+                   {"max_slots": 40, "full": True}, {"zero_one": 0x1002}):
         with pytest.raises(a2.A2cidError):
             binding.a2cid_plan_registers(4, good, coef, **kwargs)
+    binding.a2cid_plan_registers(4, good, coef, max_slots=32)
+    binding.a2cid_plan_registers(4, good, coef, max_slots=48, full=True)
     with pytest.raises(a2.A2cidError):
         binding.a2cid_plan_registers(65, good, coef)                 # more workers than registers
     bad = ops.copy()
     bad["i"][5] = 4
     with pytest.raises(a2.A2cidError):
         binding.a2cid_plan_registers(4, binding.Batch(bad, [0, 20]), coef)
+    odd = ops.copy()
+    odd["xi"][np.flatnonzero(odd["kind"] == binding.KIND_GRADIENT)[0]] = 4097      # bit 0 is the library's own mark
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_plan_registers(4, binding.Batch(odd, [0, 20]), coef)
 
 
 def test_register_programme_checker_notices_planted_mistakes():
@@ -899,14 +960,15 @@ def test_register_programme_checker_notices_planted_mistakes():
     b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))
     b.t_sync = float(b.ops["t"].max()) + 0.5
     _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
-    good = binding.a2cid_plan_registers(n, b, coef)
+    good = binding.a2cid_plan_registers(n, b, coef, zero_one=REG_ZERO_ONE)
     _run_register_launch(n, b, coef, good, 0, 8192)
     kinds = good["slots"]["x"] >> 8
-    ctl = (kinds == binding.REG_CONTROL)
+    ctl = (kinds == binding.REG_CONTROL) & (np.arange(len(kinds)) % 8 == 0)
     g = int(np.flatnonzero(kinds == binding.REG_GOSSIP)[3])
     d = int(np.flatnonzero(kinds == binding.REG_GRADIENT)[9])
     m = int(np.flatnonzero(kinds == binding.REG_MIX)[0])
     sw = int(np.flatnonzero(ctl & (good["slots"]["y"] == binding.REG_SWITCH))[0])
+    end = int(np.flatnonzero((kinds == binding.REG_CONTROL) & (good["slots"]["y"] == binding.REG_END))[-1])
 
     def mutated(change):
         plan = dict(good)
@@ -922,9 +984,11 @@ def test_register_programme_checker_notices_planted_mistakes():
         "wrong coefficient": lambda sl: sl["z"].__setitem__(g, sl["z"][g] ^ 1),
         "wrong step size": lambda sl: sl["z"].__setitem__(d, sl["z"][d] ^ 1),
         "missing switch": lambda sl: sl["y"].__setitem__(sw, 0),
+        "wrong pointer in a request": lambda sl: sl["z"].__setitem__(sw + 2, sl["z"][sw + 2] ^ 64),
+        "pointers of two events exchanged": lambda sl: swap(sl, 1, 2),
         "dropped trailing mix": lambda sl: sl.__setitem__(m, (binding.REG_CONTROL << 8, 0, 0, 0)),
         "operations exchanged": lambda sl: swap(sl, g, d),
-        "no end": lambda sl: sl["y"].__setitem__(np.flatnonzero(ctl & (sl["y"] == binding.REG_END)), 0),
+        "no end": lambda sl: sl["y"].__setitem__(end, 0),
     }
     for what, change in mistakes.items():
         with pytest.raises((AssertionError, IndexError, KeyError)):
@@ -945,15 +1009,21 @@ def test_register_programmes_on_arbitrary_small_batches():
         rng = np.random.default_rng(draw(st.integers(0, 2 ** 20)))
         ops = _random_ops(rng, n, m, draw(st.sampled_from([0.0, 0.3, 0.8, 1.0])))
         ops["gamma"], ops["t"] = 0.1, np.sort(rng.uniform(0.0, 5.0, m))
-        return n, ops, draw(st.booleans()), draw(st.sampled_from([16, 24, 64, 8192]))
+        grad = ops["kind"] == binding.KIND_GRADIENT
+        for name, base in (("xi", 1 << 20), ("c", 2 << 20), ("h", 3 << 20)):     # distinct addresses where the event has the input
+            ops[name] = np.where(grad & (ops[name] != 0), base + 16 * np.arange(m), 0)
+        full = draw(st.booleans())
+        if not full:
+            ops["c"] = ops["h"] = 0
+        return n, ops, draw(st.booleans()), draw(st.sampled_from([48, 56, 64, 8192])), full
 
-    @hyp.settings(max_examples=150, deadline=None)
+    @hyp.settings(max_examples=200, deadline=None)
     @hyp.given(cases())
     def check(case):
-        n, ops, sync, max_slots = case
+        n, ops, sync, max_slots, full = case
         b = binding.Batch(ops, list(range(len(ops) + 1)), t_sync=6.0 if sync else float("nan"))   # one operation per level
         u, v = _uv(graph.complete(n))
         _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
-        _register_plans_cover(n, b, coef, max_slots)
+        _register_plans_cover(n, b, coef, max_slots, full)
 
     check()
