@@ -903,17 +903,17 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_cbranch_scc0 L_o" id "_%=\n\t"                                                                               \
     GOSSIP(TB, X, Y, Z, W)                                                                                          \
     "\nL_d" id "_%=:\n\t"
-// the other kinds of the same slot, out of line, up to the control slots
+// the other kinds of the same slot (x >> 8 = 1 gradient, 2 mix, 3 control: told apart by bits 9 and 8), out of line,
+// up to the control slots
 #define A2R_OTHER_HEAD(TB, GRAD, AT, id, X, Y, Z, W)                                                                \
     "\nL_o" id "_%=:\n\t"                                                                                           \
-    "s_lshr_b32 s27, " X ", 8\n\t"                                                                                  \
     "s_and_b32 s31, " X ", 0xff\n\t"                                                                                \
-    "s_cmp_eq_u32 s27, 1\n\t"                                                                                       \
+    "s_bitcmp0_b32 " X ", 9\n\t"                                                                                    \
     "s_cbranch_scc0 L_p" id "_%=\n\t"                                                                               \
     GRAD(TB, Y, Z, W, AT)                                                                                           \
     "s_branch L_d" id "_%=\n"                                                                                       \
     "L_p" id "_%=:\n\t"                                                                                             \
-    "s_cmp_eq_u32 s27, 2\n\t"                                                                                       \
+    "s_bitcmp0_b32 " X ", 8\n\t"                                                                                    \
     "s_cbranch_scc0 L_c" id "_%=\n\t"                                                                               \
     A2R_MIX(TB, Y)                                                                                                  \
     "s_branch L_d" id "_%=\n"                                                                                       \
