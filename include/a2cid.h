@@ -419,7 +419,7 @@ void a2cid_sched_destroy(a2cid_sched *s);
  *      workers: 512 bytes of LDS per worker and column-per-lane);
  *   4: as 2, but every wavefront keeps its 64 columns of all workers in its vector registers and
  *      runs the whole programme of a2cid_plan_registers on them, with no LDS and no barrier (at most
- *      64 workers, rows of at most 2^30 parameters).
+ *      64 workers, rows of at most 2^29 parameters).
  * Default: 1, 0, 256, -1 (tiles shrink automatically for short rows).  All modes compute the same
  * operations in the same per-worker order and give the same state bit for bit.  In every mode the
  * gradient inputs of a batch must hold their final values, in stream order, before

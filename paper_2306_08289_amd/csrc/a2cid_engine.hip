@@ -603,7 +603,7 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 // explicitly, the resident kernel takes up to kResidentMaxRows workers.
 constexpr int64_t kShortRow = 4096;
 constexpr int32_t kResidentAutoRows = 160;
-constexpr int64_t kRegMaxColumns = (int64_t)1 << 30;    // a lane's byte offset into a row is a 32-bit number
+constexpr int64_t kRegMaxColumns = (int64_t)1 << 29;    // a lane's byte offset into a row stays below 2^31
 static int event_mode(const a2cid_ctx *c) {
     if (c->walk >= 0) return c->walk;
     if (c->n <= kRegMaxRows && c->d <= kRegMaxColumns) return 4;
@@ -1011,7 +1011,7 @@ int a2cid_set_tuning(a2cid_ctx *c, int32_t unroll, int32_t nontemporal, int32_t 
     if (mode < -1 || mode > 4)
         return fail(A2CID_EINVAL, "mode must be -1 (automatic), 0 (levels), 1 (walk), 2 (resident), 3 (chain) or 4 (register file)");
     if (mode == 4 && (c->n > kRegMaxRows || c->d > kRegMaxColumns))
-        return fail(A2CID_EINVAL, "the register-file kernel holds at most %d workers of at most 2^30 parameters", kRegMaxRows);
+        return fail(A2CID_EINVAL, "the register-file kernel holds at most %d workers of at most 2^29 parameters", kRegMaxRows);
     if (mode == 2 && c->n > kResidentMaxRows)
         return fail(A2CID_EINVAL, "the resident kernel holds at most %d workers in LDS", kResidentMaxRows);
     if ((mode == 3 || mode == -1) && (size_t)c->chain_slots * unroll * threads * 32 > 160 * 1024)

@@ -1083,7 +1083,7 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
     const int64_t col0 = (int64_t)blockIdx.x * 64;
     const bool valid = col0 + lane < d;
     const uint32_t lane_in = valid ? lane : 0u;             // loads of lanes past the end read the tile's first column
-    const uint32_t voff = (uint32_t)(col0 + lane_in) * 4u;  // byte offset of the lane's column in a row (d < 2^30)
+    const uint32_t voff = (uint32_t)(col0 + lane_in) * 4u;  // byte offset of the lane's column in a row (d <= 2^29)
 
     // Every register is loaded, the untouched workers' from the first touched row (never used, never stored):
     // straight-line code, so that the four blocks are built in place.
