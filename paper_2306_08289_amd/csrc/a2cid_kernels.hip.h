@@ -800,7 +800,8 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 // the forms the compiler itself emits for dynamically indexed vectors.
 //
 // The operation loop is one asm statement with a fixed register map, because the register allocator cannot be made
-// to keep four 32-register blocks in place across compiler-visible control flow:
+// to keep four 32-register blocks in place across compiler-visible control flow (the row loads before it and the row
+// stores after it are two more statements on the same pinned registers):
 //   v[0:63] x, v[64:127] xt of the 64 workers (the statement's in/out operands, pinned by their constraints)
 //   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
 //   FULL only: v[144:151], v[152:159] the sets of centres c, v[160:167], v[168:175] of curvatures h
@@ -1067,6 +1068,37 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     A2R_OFF                                                                                                         \
     "s_waitcnt vmcnt(0) lgkmcnt(0)"
 
+// The rows of the tile into the state registers and back, 64 unrolled steps with running row addresses in scalar
+// registers (written in C++, the compiler forms all 128 row addresses first and parks them in spare vector lanes).
+// s[40:41], s[42:43]: address of the current row of x and of xt (the lane adds the byte offset of its column); an untouched worker's registers
+// are loaded from the first touched row (never used, never stored), so every register is defined.
+#define A2R_LD1(b, k)                                                                                               \
+    "s_bitcmp1_b64 %[touched], " #b "+" #k "\n\t"                                                                   \
+    "s_cselect_b64 s[44:45], s[40:41], %[p0]\n\t"                                                                   \
+    "s_cselect_b64 s[46:47], s[42:43], %[q0]\n\t"                                                                   \
+    "global_load_dword v[" #b "+" #k "], %[voff], s[44:45] nt\n\t"                                                  \
+    "global_load_dword v[64+" #b "+" #k "], %[voff], s[46:47] nt\n\t"                                               \
+    "s_add_u32 s40, s40, %[slo]\n\t"                                                                                \
+    "s_addc_u32 s41, s41, %[shi]\n\t"                                                                               \
+    "s_add_u32 s42, s42, %[slo]\n\t"                                                                                \
+    "s_addc_u32 s43, s43, %[shi]\n\t"
+#define A2R_ST1(b, k)                                                                                               \
+    "s_bitcmp1_b64 %[touched], " #b "+" #k "\n\t"                                                                   \
+    "s_cbranch_scc0 L_st" #b "_" #k "_%=\n\t"                                                                       \
+    "global_store_dword %[voff], v[" #b "+" #k "], s[40:41] nt\n\t"                                                 \
+    "global_store_dword %[voff], v[64+" #b "+" #k "], s[42:43] nt\n"                                                \
+    "L_st" #b "_" #k "_%=:\n\t"                                                                                     \
+    "s_add_u32 s40, s40, %[slo]\n\t"                                                                                \
+    "s_addc_u32 s41, s41, %[shi]\n\t"                                                                               \
+    "s_add_u32 s42, s42, %[slo]\n\t"                                                                                \
+    "s_addc_u32 s43, s43, %[shi]\n\t"
+#define A2R_ROWS8(M, b) M(b, 0) M(b, 1) M(b, 2) M(b, 3) M(b, 4) M(b, 5) M(b, 6) M(b, 7)
+#define A2R_ROWS(M)                                                                                                 \
+    "s_mov_b64 s[40:41], %[xb]\n\t"                                                                                 \
+    "s_mov_b64 s[42:43], %[tb]\n\t"                                                                                 \
+    A2R_ROWS8(M, 0) A2R_ROWS8(M, 8) A2R_ROWS8(M, 16) A2R_ROWS8(M, 24)                                               \
+    A2R_ROWS8(M, 32) A2R_ROWS8(M, 40) A2R_ROWS8(M, 48) A2R_ROWS8(M, 56)
+
 #define A2R_S10(a) "s" #a "0", "s" #a "1", "s" #a "2", "s" #a "3", "s" #a "4", "s" #a "5", "s" #a "6", "s" #a "7", "s" #a "8", "s" #a "9"
 #define A2R_CLOBBER_S "s26", "s27", "s28", "s29", "s30", "s31", "s36", "s37", "s38", "s39", A2R_S10(4), A2R_S10(5), A2R_S10(6), A2R_S10(7), A2R_S10(8), A2R_S10(9), "vcc", "scc", "memory"
 #define A2R_V10(a) "v" #a "0", "v" #a "1", "v" #a "2", "v" #a "3", "v" #a "4", "v" #a "5", "v" #a "6", "v" #a "7", "v" #a "8", "v" #a "9"
@@ -1085,18 +1117,20 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
     const uint32_t lane_in = valid ? lane : 0u;             // loads of lanes past the end read the tile's first column
     const uint32_t voff = (uint32_t)(col0 + lane_in) * 4u;  // byte offset of the lane's column in a row (d <= 2^29)
 
-    // Every register is loaded, the untouched workers' from the first touched row (never used, never stored):
-    // straight-line code, so that the four blocks are built in place.
+    // The loads of this statement are not waited for here: the operation loop below issues its first requests and
+    // then waits for everything (nothing but these four values, pinned to the same registers there, reads them).
     v32f X0, X1, T0, T1;
+    const uintptr_t xb = reg_uniform(x), tb = reg_uniform(xt);     // the lane's offset counts from the start of a row
+    const uint64_t step = (uint64_t)ld * 4u;
+    const uint32_t step_lo = (uint32_t)step, step_hi = (uint32_t)(step >> 32);
     {
-        const int64_t r0 = touched ? __builtin_ctzll(touched) : 0;
-#pragma unroll
-        for (int r = 0; r < 64; ++r) {
-            const int64_t row = ((touched >> r) & 1) ? r : r0;
-            const float a = __builtin_nontemporal_load((global_f32)reg_uniform(x + row * ld + col0) + lane_in);
-            const float b = __builtin_nontemporal_load((global_f32)reg_uniform(xt + row * ld + col0) + lane_in);
-            if (r < 32) { X0[r] = a; T0[r] = b; } else { X1[r - 32] = a; T1[r - 32] = b; }
-        }
+        const uint64_t first = (uint64_t)(touched ? __builtin_ctzll(touched) : 0) * step;
+        const uintptr_t p0 = xb + first, q0 = tb + first;
+        asm volatile(A2R_ROWS(A2R_LD1)
+                     : "=&{v[0:31]}"(X0), "=&{v[32:63]}"(X1), "=&{v[64:95]}"(T0), "=&{v[96:127]}"(T1)
+                     : [xb] "s"(xb), [tb] "s"(tb), [p0] "s"(p0), [q0] "s"(q0), [slo] "s"(step_lo), [shi] "s"(step_hi),
+                       [touched] "s"(touched), [voff] "v"(voff)
+                     : "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "scc", "memory");
     }
     const float neg_alpha = -alpha, neg_alpha_t = -alpha_t;
 #define A2R_OPERANDS                                                                                                \
@@ -1121,13 +1155,11 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
 #undef A2R_OPERANDS
 
     if (valid) {
-#pragma unroll
-        for (int r = 0; r < 64; ++r) {
-            if ((touched >> r) & 1) {
-                __builtin_nontemporal_store(r < 32 ? X0[r] : X1[r - 32], (global_out_f32)reg_uniform(x + r * ld + col0) + lane);
-                __builtin_nontemporal_store(r < 32 ? T0[r] : T1[r - 32], (global_out_f32)reg_uniform(xt + r * ld + col0) + lane);
-            }
-        }
+        asm volatile(A2R_ROWS(A2R_ST1)
+                     :
+                     : "{v[0:31]}"(X0), "{v[32:63]}"(X1), "{v[64:95]}"(T0), "{v[96:127]}"(T1), [xb] "s"(xb), [tb] "s"(tb),
+                       [slo] "s"(step_lo), [shi] "s"(step_hi), [touched] "s"(touched), [voff] "v"(voff)
+                     : "s40", "s41", "s42", "s43", "scc", "memory");
     }
 }
 
