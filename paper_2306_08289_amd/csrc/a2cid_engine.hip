@@ -417,8 +417,8 @@ int enqueue_resident(a2cid_ctx *c, const a2cid_event_batch *batch, int32_t *l, i
 
 // One launch of regfile_kernel: writes the programme for the operations of the batch from operation *k on, as many as
 // a staging buffer holds (plan_regfile), uploads it and launches the kernel.  On return *k names the first operation
-// not included.  full: some gradient event of the batch has a centre or a curvature.
-int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, bool full, int64_t *k) {
+// not included.  full: some gradient event of the batch has a centre or a curvature; curvatures: some has a curvature.
+int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, bool full, bool curvatures, int64_t *k) {
     Slot *s;
     if (int rc = acquire_slot(c, &s)) return rc;
     const int64_t k_before = *k;
@@ -440,15 +440,19 @@ int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, bool full, int
         A2CID_HIP(hipEventRecord(tl.start, c->stream));
     }
     const unsigned blocks = (unsigned)((c->d + 63) / 64);
-#define A2CID_REG(PRE, FULL)                                                                                            \
-    hipLaunchKernelGGL((regfile_kernel<PRE, FULL>), dim3(blocks), dim3(64), 0, c->stream, c->x, c->xt, c->ld, c->d,    \
+#define A2CID_REG(PRE, VARIANT)                                                                                         \
+    hipLaunchKernelGGL((regfile_kernel<PRE, VARIANT>), dim3(blocks), dim3(64), 0, c->stream, c->x, c->xt, c->ld, c->d, \
                        s->res_dev, (uint32_t)(rp.programme.size() * sizeof(ResSlot)), rp.touched, (float)c->alpha,      \
                        (float)c->alpha_t)
-    switch ((c->order != 0 ? 2 : 0) | (full ? 1 : 0)) {
-        case 0: A2CID_REG(false, false); break;
-        case 1: A2CID_REG(false, true); break;
-        case 2: A2CID_REG(true, false); break;
-        default: A2CID_REG(true, true); break;
+    // centres only (two blocks per request, the curvature pointers unused) leave room for three waves per SIMD
+    const int variant = !full ? 0 : curvatures ? 2 : 1;
+    switch ((c->order != 0 ? 3 : 0) + variant) {
+        case 0: A2CID_REG(false, 0); break;
+        case 1: A2CID_REG(false, 1); break;
+        case 2: A2CID_REG(false, 2); break;
+        case 3: A2CID_REG(true, 0); break;
+        case 4: A2CID_REG(true, 1); break;
+        default: A2CID_REG(true, 2); break;
     }
 #undef A2CID_REG
     A2CID_HIP(hipGetLastError());
@@ -692,14 +696,16 @@ static int enqueue_batch(a2cid_ctx *c, const a2cid_event_batch *batch) {
         return A2CID_OK;
     }
     if (mode == 4) {
-        bool full = false;
-        for (int64_t q = 0; q < batch->n_ops && !full; ++q) {
+        bool full = false, curvatures = false;
+        for (int64_t q = 0; q < batch->n_ops && !curvatures; ++q) {
             const a2cid_op &op = batch->ops[q];
-            full = op.kind == A2CID_KIND_GRADIENT && op.gscale != 0.f && (op.c || op.h);
+            if (op.kind != A2CID_KIND_GRADIENT || op.gscale == 0.f) continue;
+            full = full || op.c || op.h;
+            curvatures = op.h != nullptr;
         }
         int64_t k = 0;
         while (k < batch->n_ops)
-            if (int rc = enqueue_regfile(c, batch, full, &k)) return rc;
+            if (int rc = enqueue_regfile(c, batch, full, curvatures, &k)) return rc;
         return A2CID_OK;
     }
     int32_t l = 0;

@@ -804,8 +804,8 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 // stores after it are two more statements on the same pinned registers):
 //   v[0:63] x, v[64:127] xt of the 64 workers (the statement's in/out operands, pinned by their constraints)
 //   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
-//   FULL only: v[144:151], v[152:159] the sets of centres c, v[160:167], v[168:175] of curvatures h
-//   v[TB .. TB+10]           temporaries (TB = 144, FULL: 176)
+//   with centres: v[144:151], v[152:159] the sets of centres c; with curvatures also v[160:167], v[168:175] for h
+//   v[TB .. TB+6]            temporaries (TB = 144, with centres 160, with curvatures 176)
 //   s[36:67], s[68:99] two blocks of 8 slots (one applied, one being fetched), s26 byte position of the next fetch,
 //   s27, s31 scratch, s28 index of the next gradient event's inputs (set offset included), s29 offset of the set in
 //   use (0 or 8), s30 (FULL) set while the block of c and h pointers after a request is to be passed over
@@ -839,7 +839,8 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 #define A2R_T(TB, k) "v[" TB "+" #k "]"
 #define A2R_ON(idx, mode) "s_set_gpr_idx_on " idx ", gpr_idx(" mode ")\n\t"
 #define A2R_OFF "s_set_gpr_idx_off\n\t"
-// temporaries: 0 di, 1 dj, 2 xi, 3 ti, 4 xj, 5 tj, 6 m, 7 g, 8 u / stored x, 9 slope, 10 lane offset of a request
+// temporaries: 0 di, 1 dj (gradient: g), 2 xi, 3 ti, 4 xj (gradient: u / stored x), 5 tj (gradient: slope), 6 m (request:
+// the lane's offset)
 // Index mode stays on from one operation to the next (every vector instruction of an operation comes after the
 // operation's own s_set_gpr_idx_on); it is switched off before the only other vector instructions, those of a
 // request, and at the end.
@@ -871,27 +872,33 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 
 // gradient event of worker s31 (index), Y = b_i, Z = gamma, W = gscale; inputs at index s28
 #define A2R_STORED_2(TB)
-#define A2R_STORED_8(TB) A2R_ON("s31", "SRC0") "v_mov_b32 " A2R_T(TB, 8) ", v0\n\t"
+#define A2R_STORED_4(TB) A2R_ON("s31", "SRC0") "v_mov_b32 " A2R_T(TB, 4) ", v0\n\t"
 #define A2R_GRAD_HEAD(TB, Y, AT)                                                                                    \
     A2R_ON("s31", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
     A2R_STORED_##AT(TB)                                                                                             \
     A2R_ON("s31", "SRC2") "v_fma_f32 " A2R_T(TB, 2) ", " Y ", " A2R_T(TB, 0) ", v0\n\t"                             \
                           "v_fma_f32 " A2R_T(TB, 3) ", -" Y ", " A2R_T(TB, 0) ", v64\n\t"
 #define A2R_GRAD_TAIL(TB, Z)                                                                                        \
-    A2R_ON("s31", "DST") "v_fma_f32 v0, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 2) "\n\t"                             \
-                         "v_fma_f32 v64, -" Z ", " A2R_T(TB, 7) ", " A2R_T(TB, 3) "\n\t"                            \
+    A2R_ON("s31", "DST") "v_fma_f32 v0, -" Z ", " A2R_T(TB, 1) ", " A2R_T(TB, 2) "\n\t"                             \
+                         "v_fma_f32 v64, -" Z ", " A2R_T(TB, 1) ", " A2R_T(TB, 3) "\n\t"                            \
     "s_add_u32 s28, s28, 1\n\t"
-// g = gscale x + xi (no centre, no curvature); AT = 2: at the mixed point, 8: at the stored point
+// g = gscale x + xi (no centre, no curvature); AT = 2: at the mixed point, 4: at the stored point
 #define A2R_GRAD_PLAIN(TB, Y, Z, W, AT)                                                                             \
     A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
-    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " W ", " A2R_T(TB, AT) ", v128\n\t"                          \
+    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 1) ", " W ", " A2R_T(TB, AT) ", v128\n\t"                          \
     A2R_GRAD_TAIL(TB, Z)
 // g = (gscale h) (x - c) + xi
 #define A2R_GRAD_FULL(TB, Y, Z, W, AT)                                                                              \
     A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
-    A2R_ON("s28", "SRC1") "v_sub_f32 " A2R_T(TB, 8) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
-                          "v_mul_f32 " A2R_T(TB, 9) ", " W ", v160\n\t"                                             \
-    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 7) ", " A2R_T(TB, 9) ", " A2R_T(TB, 8) ", v128\n\t"                \
+    A2R_ON("s28", "SRC1") "v_sub_f32 " A2R_T(TB, 4) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
+                          "v_mul_f32 " A2R_T(TB, 5) ", " W ", v160\n\t"                                             \
+    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 1) ", " A2R_T(TB, 5) ", " A2R_T(TB, 4) ", v128\n\t"                \
+    A2R_GRAD_TAIL(TB, Z)
+// g = gscale (x - c) + xi (centres, no curvature)
+#define A2R_GRAD_HC(TB, Y, Z, W, AT)                                                                                \
+    A2R_GRAD_HEAD(TB, Y, AT)                                                                                        \
+    A2R_ON("s28", "SRC1") "v_sub_f32 " A2R_T(TB, 4) ", " A2R_T(TB, AT) ", v144\n\t"                                 \
+    A2R_ON("s28", "SRC2") "v_fma_f32 " A2R_T(TB, 1) ", " W ", " A2R_T(TB, 4) ", v128\n\t"                           \
     A2R_GRAD_TAIL(TB, Z)
 #define A2R_MIX(TB, Y)                                                                                              \
     A2R_ON("s31", "SRC0,SRC1") "v_sub_f32 " A2R_T(TB, 0) ", v64, v0\n\t"                                            \
@@ -948,9 +955,9 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 #define A2R_REQ1(TB, B, P, k)                                                                                       \
     "s_bitcmp1_b32 s[" P "+2*" #k "], 0\n\t"                                                                        \
     "s_cselect_b64 vcc, -1, 0\n\t"                                                                                  \
-    "v_cndmask_b32_e64 " A2R_T(TB, 10) ", %[voff], 0, vcc\n\t"                                                      \
+    "v_cndmask_b32_e64 " A2R_T(TB, 6) ", %[voff], 0, vcc\n\t"                                                      \
     "s_and_b32 s[" P "+2*" #k "], s[" P "+2*" #k "], -4\n\t"                                                        \
-    "global_load_dword v[" B "+" #k "], " A2R_T(TB, 10) ", s[" P "+2*" #k ":" P "+2*" #k "+1] nt\n\t"
+    "global_load_dword v[" B "+" #k "], " A2R_T(TB, 6) ", s[" P "+2*" #k ":" P "+2*" #k "+1] nt\n\t"
 // eight inputs of one kind: pointers in s[P : P+15], destinations v[B : B+7]
 #define A2R_REQ8(TB, B, P)                                                                                          \
     A2R_REQ1(TB, B, P, 0) A2R_REQ1(TB, B, P, 1) A2R_REQ1(TB, B, P, 2) A2R_REQ1(TB, B, P, 3)                         \
@@ -959,11 +966,13 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 // the block after it holds the c pointers (slots 0-3) and the h pointers (slots 4-7).  XI: first SGPR of slot 1 of
 // the request block, C / H: first SGPR of slots 0 / 4 of the other block; SET: "0" or "8".
 #define A2R_REQ_PLAIN(TB, SET, XI, C, H) A2R_REQ8(TB, "128+" SET, XI)
+#define A2R_REQ_HC(TB, SET, XI, C, H) A2R_REQ8(TB, "128+" SET, XI) A2R_REQ8(TB, "144+" SET, C)
 #define A2R_REQ_FULL(TB, SET, XI, C, H)                                                                             \
     A2R_REQ8(TB, "128+" SET, XI) A2R_REQ8(TB, "144+" SET, C) A2R_REQ8(TB, "160+" SET, H)
 // After a request with centres and curvatures the block of c and h pointers is passed over (s30 = 1: skip a block).
 #define A2R_SKIP_SET_PLAIN
 #define A2R_SKIP_SET_FULL "s_mov_b32 s30, 1\n\t"
+#define A2R_SKIP_SET_HC A2R_SKIP_SET_FULL
 #define A2R_SKIP_TEST_PLAIN(PH)
 #define A2R_SKIP_TEST_FULL(PH)                                                                                      \
     "s_cmp_eq_u32 s30, 0\n\t"                                                                                       \
@@ -971,6 +980,7 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_mov_b32 s30, 0\n\t"                                                                                          \
     "s_branch L_end" PH "_%=\n"                                                                                     \
     "L_go" PH "_%=:\n\t"
+#define A2R_SKIP_TEST_HC(PH) A2R_SKIP_TEST_FULL(PH)
 // A switch slot (first slot of a block, phase PH): the wave waits for the set of inputs requested a chunk ago
 // (nothing else is in flight; with centres and curvatures also for the block of their pointers, being fetched),
 // requests the pointers of this block into the set just used up, turns to the other set and goes on with the
@@ -1002,24 +1012,26 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
     A2R_REQ_PLAIN(TB, "0", "40", "0", "0") A2R_REQ_PLAIN(TB, "8", "72", "0", "0")                                   \
     "s_mov_b32 s26, 0x100\n\t"
-#define A2R_FIRST_FULL(TB)                                                                                          \
+#define A2R_FIRST_TWO(TB, REQ)                                                                                      \
     "s_load_dwordx16 s[36:51], %[prog], 0x0\n\t"                                                                    \
     "s_load_dwordx16 s[52:67], %[prog], 0x40\n\t"                                                                   \
     "s_load_dwordx16 s[68:83], %[prog], 0x80\n\t"                                                                   \
     "s_load_dwordx16 s[84:99], %[prog], 0xc0\n\t"                                                                   \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
-    A2R_REQ_FULL(TB, "0", "40", "68", "84")                                                                         \
+    REQ(TB, "0", "40", "68", "84")                                                                                  \
     "s_load_dwordx16 s[36:51], %[prog], 0x100\n\t"                                                                  \
     "s_load_dwordx16 s[52:67], %[prog], 0x140\n\t"                                                                  \
     "s_load_dwordx16 s[68:83], %[prog], 0x180\n\t"                                                                  \
     "s_load_dwordx16 s[84:99], %[prog], 0x1c0\n\t"                                                                  \
     "s_waitcnt lgkmcnt(0)\n\t"                                                                                      \
-    A2R_REQ_FULL(TB, "8", "40", "68", "84")                                                                         \
+    REQ(TB, "8", "40", "68", "84")                                                                                  \
     "s_mov_b32 s26, 0x200\n\t"
+#define A2R_FIRST_FULL(TB) A2R_FIRST_TWO(TB, A2R_REQ_FULL)
+#define A2R_FIRST_HC(TB) A2R_FIRST_TWO(TB, A2R_REQ_HC)
 
 // s26: byte offset of the next block to fetch.  Block A is fetched while block B is being applied and the other
 // way round; scalar loads return in no fixed order, so the wait for a block comes before the next fetch is issued.
-// VARIANT: PLAIN or FULL (pasted into macro names).
+// VARIANT: PLAIN, HC or FULL (pasted into macro names).
 #define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, VARIANT)                                                                \
     "s_mov_b32 s28, 0\n\t"                                                                                          \
     "s_mov_b32 s29, 0\n\t"                                                                                          \
@@ -1102,12 +1114,13 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 #define A2R_S10(a) "s" #a "0", "s" #a "1", "s" #a "2", "s" #a "3", "s" #a "4", "s" #a "5", "s" #a "6", "s" #a "7", "s" #a "8", "s" #a "9"
 #define A2R_CLOBBER_S "s26", "s27", "s28", "s29", "s30", "s31", "s36", "s37", "s38", "s39", A2R_S10(4), A2R_S10(5), A2R_S10(6), A2R_S10(7), A2R_S10(8), A2R_S10(9), "vcc", "scc", "memory"
 #define A2R_V10(a) "v" #a "0", "v" #a "1", "v" #a "2", "v" #a "3", "v" #a "4", "v" #a "5", "v" #a "6", "v" #a "7", "v" #a "8", "v" #a "9"
-#define A2R_CLOBBER_PLAIN "v128", "v129", A2R_V10(13), A2R_V10(14), "v150", "v151", "v152", "v153", "v154"
+#define A2R_CLOBBER_PLAIN "v128", "v129", A2R_V10(13), A2R_V10(14), "v150"
+#define A2R_CLOBBER_HC "v128", "v129", A2R_V10(13), A2R_V10(14), A2R_V10(15), "v160", "v161", "v162", "v163", "v164", "v165", "v166"
 #define A2R_CLOBBER_FULL                                                                                            \
-    "v128", "v129", A2R_V10(13), A2R_V10(14), A2R_V10(15), A2R_V10(16), A2R_V10(17), "v180", "v181", "v182", "v183", \
-    "v184", "v185", "v186"
+    "v128", "v129", A2R_V10(13), A2R_V10(14), A2R_V10(15), A2R_V10(16), A2R_V10(17), "v180", "v181", "v182"
 
-template <bool PRE, bool FULL>
+// VARIANT: 0 no centres and no curvatures, 1 centres only, 2 both.
+template <bool PRE, int VARIANT>
 __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, float *__restrict__ xt, int64_t ld,
                                                      int64_t d, const ResSlot *__restrict__ recs, uint32_t n_bytes,
                                                      uint64_t touched, float alpha, float alpha_t) {
@@ -1137,19 +1150,26 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
     : "+{v[0:31]}"(X0), "+{v[32:63]}"(X1), "+{v[64:95]}"(T0), "+{v[96:127]}"(T1)                                    \
     : [prog] "s"(recs), [nbytes] "s"(n_bytes), [voff] "v"(voff),                                                    \
       [al] "s"(alpha), [nal] "s"(neg_alpha), [alt] "s"(alpha_t), [nalt] "s"(neg_alpha_t)
-    if constexpr (!FULL) {
+    if constexpr (VARIANT == 0) {
         if constexpr (!PRE)
             asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_0, A2R_GRAD_PLAIN, 2, PLAIN) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
         else
-            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_1, A2R_GRAD_PLAIN, 8, PLAIN) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_1, A2R_GRAD_PLAIN, 4, PLAIN) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_PLAIN);
+    } else if constexpr (VARIANT == 1) {
+        if constexpr (!PRE)
+            asm volatile(A2R_PROGRAMME("160", A2R_GOSSIP_0, A2R_GRAD_HC, 2, HC) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_HC);
+        else
+            asm volatile(A2R_PROGRAMME("160", A2R_GOSSIP_1, A2R_GRAD_HC, 4, HC) A2R_OPERANDS
+                         : A2R_CLOBBER_S, A2R_CLOBBER_HC);
     } else {
         if constexpr (!PRE)
             asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_0, A2R_GRAD_FULL, 2, FULL) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
         else
-            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_1, A2R_GRAD_FULL, 8, FULL) A2R_OPERANDS
+            asm volatile(A2R_PROGRAMME("176", A2R_GOSSIP_1, A2R_GRAD_FULL, 4, FULL) A2R_OPERANDS
                          : A2R_CLOBBER_S, A2R_CLOBBER_FULL);
     }
 #undef A2R_OPERANDS
