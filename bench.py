@@ -37,15 +37,15 @@ MEASURED_TRAFFIC = {
     ("C4", 1024, "walk_kernel"): (7.9190e11, "profiles/bench_C4_hbm_counters.md"),
     ("C4", 1024, "chain_kernel"): (3.2498e11, "profiles/bench_C4_hbm_counters.md"),
     ("C4", 1024, "resident_kernel"): (4.2486e10, "profiles/bench_C4_hbm_counters.md"),
-    ("C4", 1024, "regfile_kernel"): (4.2737e10, "profiles/bench_C4_hbm_counters.md"),
+    ("C4", 1024, "regfile_kernel"): (4.2788e10, "profiles/bench_C4_hbm_counters.md"),
     ("C3", 1024, "walk_kernel"): (3.3678e11, "profiles/bench_C3_hbm_counters.md"),
     ("C3", 1024, "chain_kernel"): (7.2111e10, "profiles/bench_C3_hbm_counters.md"),
     ("C3", 1024, "resident_kernel"): (2.6894e10, "profiles/bench_C3_hbm_counters.md"),
-    ("C3", 1024, "regfile_kernel"): (2.6509e10, "profiles/bench_C3_hbm_counters.md"),
+    ("C3", 1024, "regfile_kernel"): (2.6515e10, "profiles/bench_C3_hbm_counters.md"),
     ("C5", 1024, "walk_kernel"): (8.2851e11, "profiles/bench_C5_hbm_counters.md"),
     ("C5", 1024, "chain_kernel"): (3.7700e11, "profiles/bench_C5_hbm_counters.md"),
     ("C5", 1024, "resident_kernel"): (3.7917e10, "profiles/bench_C5_hbm_counters.md"),
-    ("C5", 1024, "regfile_kernel"): (3.8687e10, "profiles/bench_C5_hbm_counters.md"),
+    ("C5", 1024, "regfile_kernel"): (3.8749e10, "profiles/bench_C5_hbm_counters.md"),
 }
 
 # The resident and register-file kernels are bound by instruction issue, not by memory: their roofline is the chip's

@@ -598,7 +598,7 @@ int a2cid_create(a2cid_ctx **out, int32_t n, int64_t d, const a2cid_graph *graph
 }
 
 // The event kernel of the next batch when the choice is left to the library, from measurements (events per second,
-// 1024 events per batch).  Up to 64 workers the register-file kernel: 1.3 to 1.7 times the LDS-resident kernel on
+// 1024 events per batch).  Up to 64 workers the register-file kernel: 1.4 to 2.0 times the LDS-resident kernel on
 // the 64-worker configurations.  The LDS-resident kernel for up to 160 workers, the most for which two workgroups
 // share a CU's LDS: with rows of 4 M parameters, ring / exponential graph, it is, against the chain kernel: 96 workers
 // 1.4, 112: 2.3, 128: 1.4 / 2.4, 160: 1.3 times; from 192 workers on it depends on the graph (192 exponential 1.4,
