@@ -808,12 +808,12 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 //   v[TB .. TB+6]            temporaries (TB = 144, with centres 160, with curvatures 176)
 //   s[36:67], s[68:99] two blocks of 8 slots (one applied, one being fetched), s26 byte position of the next fetch,
 //   s27, s31 scratch, s28 index of the next gradient event's inputs (set offset included), s29 offset of the set in
-//   use (0 or 8), s30 (FULL) set while the block of c and h pointers after a request is to be passed over
+//   use (0 or 8), s30 (with centres) set while the block of c and h pointers after a request is to be passed over
 // Programme (layout: a2cid_internal.h): every slot is applied in order; a gossip slot (the common case) falls
 // through its kind test, the other kinds are handled out of line.  The loop ends at the end slot, and in any case
 // when the position reaches the programme's length.
 // Gradient inputs: chunk k of kRegChunk events uses set k % 2.  The pointers travel in the programme itself, in
-// request blocks (8 xi pointers in slots 1-4; FULL: the block after it holds 8 c and 8 h pointers), so they arrive
+// request blocks (8 xi pointers in slots 1-4; with centres the block after it holds 8 c and 8 h pointers), so they arrive
 // with the block prefetch.  The programme begins with the request blocks of chunks 0 and 1.  The request block of
 // chunk k + 1 precedes the first event of chunk k >= 1; its first slot is a switch slot: the wave waits for chunk k's
 // set (requested a whole chunk ago; nothing else is in flight), requests chunk k + 1 into the set chunk k - 1 used,
@@ -826,9 +826,7 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 typedef float v32f __attribute__((ext_vector_type(32)));
 typedef __attribute__((address_space(1))) float *global_out_f32;
 
-// A uniform address as the compiler must take it: a scalar base, to which a lane adds its 32-bit offset in the
-// load or store instruction itself (left to itself the compiler folds the lane's offset in first and then keeps
-// one 64-bit address per row in vector registers, 256 of them).
+// A uniform address as the compiler must take it: a value in scalar registers.
 __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
     const uintptr_t v = (uintptr_t)p;
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
