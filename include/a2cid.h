@@ -345,6 +345,13 @@ int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_
                          int64_t *n_slots, int64_t *gradient_ops, int32_t *n_gradient_ops, uint64_t *touched,
                          int64_t *next_op);
 
+/* The check every register-file programme passes before it is launched (the kernel adds worker indices
+ * to register numbers and trusts the block structure, so a malformed programme must never reach it):
+ * whole blocks of 8 slots, the two first request blocks, worker indices below n <= 64, at most 8
+ * gradient events between two switch slots, switch slots only at the head of a block and followed by
+ * their pointer block(s), an end slot in the last block.  A2CID_OK or A2CID_EINVAL.  Host only. */
+int a2cid_check_registers(int32_t n, int32_t full, const a2cid_resident_slot *slots, int64_t n_slots);
+
 /* ---- event scheduler (host only) ------------------------------------------------------- */
 
 /* Independent Poisson clocks (Assumption 3.1): one per worker (gradient events, rate

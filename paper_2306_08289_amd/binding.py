@@ -86,6 +86,7 @@ SIGNATURES = {
     "a2cid_plan_registers": (C.c_int, [C.c_int32, _P(a2cid_event_batch), C.c_void_p, C.c_int64, C.c_int64, C.c_int32,
                                        C.c_void_p, C.c_void_p, _P(C.c_int64), C.c_void_p, _P(C.c_int32), _P(C.c_uint64),
                                        _P(C.c_int64)]),
+    "a2cid_check_registers": (C.c_int, [C.c_int32, C.c_int32, C.c_void_p, C.c_int64]),
     "a2cid_set_chain_slots": (C.c_int, [C.c_void_p, C.c_int32]),
     "a2cid_plan_batch": (C.c_int, [C.c_int32, _P(a2cid_graph), C.c_double, _P(C.c_double),
                                    _P(a2cid_event_batch), C.c_void_p]),
@@ -259,6 +260,12 @@ def a2cid_plan_registers(n, batch, coef, first_op=0, max_slots=8192, full=False,
                                        gops.ctypes.data, C.byref(n_g), C.byref(touched), C.byref(nxt)))
     return {"slots": slots[:n_slots.value].copy(), "gradient_ops": gops[:n_g.value].copy(), "touched": touched.value,
             "next_op": nxt.value}
+
+
+def a2cid_check_registers(n, slots, full=False):
+    """Raises A2cidError unless slots is a programme the register-file kernel may run for n workers."""
+    slots = np.ascontiguousarray(slots, SLOT_DTYPE)
+    _check(load().a2cid_check_registers(int(n), int(bool(full)), slots.ctypes.data, len(slots)))
 
 
 class Scheduler:

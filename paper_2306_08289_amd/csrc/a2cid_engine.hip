@@ -425,9 +425,8 @@ int enqueue_regfile(a2cid_ctx *c, const a2cid_event_batch *batch, bool full, boo
     plan_regfile(c->n, batch, c->plan.coef.data(), kResRecords, full, (uintptr_t)c->zero_dev, k, c->regplan);
     if (*k == k_before) return fail(A2CID_EINVAL, "internal: an operation does not fit an empty register-file programme");
     const RegPlan &rp = c->regplan;
-    if ((int64_t)rp.programme.size() > kResRecords || rp.programme.size() % kRegBlock != 0 ||
-        rp.programme.size() < (size_t)(full ? 5 : 3) * kRegBlock)
-        return fail(A2CID_EINVAL, "internal: register-file programme of %zu slots", rp.programme.size());
+    if ((int64_t)rp.programme.size() > kResRecords || !regfile_programme_ok(rp.programme, c->n, full))
+        return fail(A2CID_EINVAL, "internal: register-file programme of %zu slots fails its check", rp.programme.size());
     std::memcpy(s->res_host, rp.programme.data(), rp.programme.size() * sizeof(ResSlot));
     A2CID_HIP(hipMemcpyAsync(s->res_dev, s->res_host, sizeof(ResSlot) * rp.programme.size(), hipMemcpyHostToDevice,
                              c->stream));

@@ -865,6 +865,46 @@ void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *c
     }
 }
 
+// Walks a register-file programme the way the kernel does and checks everything the kernel relies on without
+// testing it: whole blocks, the first request blocks, an end slot, worker indices below n (the kernel adds them to a
+// register number: an index past the wave's registers is not harmless), at most kRegChunk gradient events between two
+// switch slots, switch slots only at the head of a block and followed by their pointer block(s).
+bool regfile_programme_ok(const std::vector<ResSlot> &prog, int32_t n, bool full) {
+    const size_t request_slots = full ? 2 * kRegBlock : kRegBlock;
+    if (prog.empty() || prog.size() % kRegBlock != 0 || prog.size() < 2 * request_slots + kRegBlock) return false;
+    if (n < 1 || n > kRegMaxRows) return false;
+    for (size_t q = 0; q < 2; ++q) {
+        const ResSlot &ctl = prog[q * request_slots];
+        if (ctl.x != kRegControl << 8 || ctl.y != kRegRequest) return false;
+    }
+    int in_chunk = 0;
+    for (size_t at = 2 * request_slots; at < prog.size(); at += kRegBlock) {
+        for (int j = 0; j < kRegBlock; ++j) {
+            const ResSlot &r = prog[at + (size_t)j];
+            const uint32_t kind = r.x >> 8, worker = r.x & 255u;
+            if (kind == kRegGossip) {
+                if (worker >= (uint32_t)n || r.y >= (uint32_t)n) return false;
+            } else if (kind == kRegGradient) {
+                if (worker >= (uint32_t)n || ++in_chunk > kRegChunk) return false;
+            } else if (kind == kRegMix) {
+                if (worker >= (uint32_t)n) return false;
+            } else if (kind == kRegControl) {
+                if (r.y == kRegEnd) return at + kRegBlock == prog.size();       // nothing after the end slot's block
+                if (r.y == kRegSwitch) {
+                    if (j != 0 || at + request_slots >= prog.size()) return false;
+                    in_chunk = 0;
+                    at += request_slots - kRegBlock;                            // the pointers are not operations
+                    break;
+                }
+                if (r.y != 0) return false;
+            } else {
+                return false;
+            }
+        }
+    }
+    return false;                                                               // no end slot
+}
+
 }  // namespace a2cid
 
 extern "C" {
@@ -1053,12 +1093,28 @@ int a2cid_plan_registers(int32_t n, const a2cid_event_batch *batch, const a2cid_
         RegPlan plan;
         int64_t k = first_op;
         plan_regfile(n, batch, coef, max_slots, full != 0, (uintptr_t)zero_one, &k, plan);
+        if (!regfile_programme_ok(plan.programme, n, full != 0))
+            return fail(A2CID_EINVAL, "internal: the register-file programme fails its own check");
         std::memcpy(slots, plan.programme.data(), plan.programme.size() * sizeof(ResSlot));
         *n_slots = (int64_t)plan.programme.size();
         std::copy(plan.grad_op.begin(), plan.grad_op.end(), gradient_ops);
         *n_gradient_ops = (int32_t)plan.grad_op.size();
         *touched = plan.touched;
         *next_op = k;
+    } catch (const std::bad_alloc &) {
+        return fail(A2CID_ENOMEM, "out of host memory");
+    }
+    return A2CID_OK;
+}
+
+int a2cid_check_registers(int32_t n, int32_t full, const a2cid_resident_slot *slots, int64_t n_slots) {
+    clear_error();
+    if (!slots || n_slots < 0) return fail(A2CID_EINVAL, "slots is NULL or n_slots negative");
+    try {
+        std::vector<ResSlot> prog((size_t)n_slots);
+        std::memcpy(prog.data(), slots, (size_t)n_slots * sizeof(ResSlot));
+        if (!regfile_programme_ok(prog, n, full != 0))
+            return fail(A2CID_EINVAL, "not a programme the register-file kernel may run");
     } catch (const std::bad_alloc &) {
         return fail(A2CID_ENOMEM, "out of host memory");
     }

@@ -171,5 +171,8 @@ struct RegPlan {
 // float 1.  The batch must be valid (plan_batch passed) and n <= kRegMaxRows.
 void plan_regfile(int32_t n, const a2cid_event_batch *batch, const a2cid_coef *coef, int64_t max_slots, bool full,
                   uintptr_t zero_one, int64_t *k, RegPlan &plan);
+// What the kernel relies on without testing it (indices below n, chunk sizes, block structure): checked before
+// every launch, so that a planner mistake becomes an error instead of a wave addressing registers it does not own.
+bool regfile_programme_ok(const std::vector<ResSlot> &prog, int32_t n, bool full);
 
 }  // namespace a2cid

@@ -996,6 +996,71 @@ def test_register_programme_checker_notices_planted_mistakes():
     s.close()
 
 
+def test_register_programme_check_refuses_what_the_kernel_could_not_run():
+    """The kernel adds worker indices to register numbers and trusts the block structure; the library checks every
+    programme before launching it, and this is that check."""
+    n = 16
+    u, v = _uv(graph.ring(n))
+    s = binding.Scheduler(n, u, v, 1.0, 1.0, 3)
+    b = s.next(400)
+    b.ops["gamma"], b.ops["gscale"] = 0.1, 1.0
+    grad = b.ops["kind"] == binding.KIND_GRADIENT
+    b.ops["xi"][grad] = 4096 * (1 + np.arange(int(grad.sum())))
+    _, coef = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), b)
+    for full in (False, True):
+        good = binding.a2cid_plan_registers(n, b, coef, full=full)["slots"]
+        binding.a2cid_check_registers(n, good, full)
+        binding.a2cid_check_registers(64, good, full)
+        kinds = good["x"] >> 8
+        heads = np.arange(len(good)) % 8 == 0
+        g = int(np.flatnonzero(kinds == binding.REG_GOSSIP)[5])
+        d = int(np.flatnonzero(kinds == binding.REG_GRADIENT)[3])
+        sw = int(np.flatnonzero((kinds == binding.REG_CONTROL) & heads & (good["y"] == binding.REG_SWITCH))[0])
+        end = int(np.flatnonzero((kinds == binding.REG_CONTROL) & (good["y"] == binding.REG_END))[-1])
+        filler = (binding.REG_CONTROL << 8, 0, 0, 0)
+
+        def bad(change, workers=n):
+            sl = good.copy()
+            sl = change(sl)
+            with pytest.raises(a2.A2cidError):
+                binding.a2cid_check_registers(workers, sl, full)
+
+        def put(sl, at, field, value):
+            sl[field][at] = value
+            return sl
+
+        bad(lambda sl: put(sl, g, "x", n))                                      # worker i out of range
+        bad(lambda sl: put(sl, g, "y", 200))                                    # worker j out of range
+        bad(lambda sl: put(sl, d, "x", (binding.REG_GRADIENT << 8) | 77))
+        bad(lambda sl: sl, workers=int(max(good["x"][kinds == 0].max(), good["y"][kinds == 0].max())))  # n too small
+        bad(lambda sl: sl, workers=65)
+        bad(lambda sl: put(sl, sw, "y", 0))                                     # the pointers would run as operations
+        bad(lambda sl: put(sl, end, "y", 0))                                    # no end
+        bad(lambda sl: sl[:-8])                                                 # the end slot's block is gone
+        bad(lambda sl: sl[:-3])                                                 # not whole blocks
+        bad(lambda sl: np.concatenate([sl, np.array([filler] * 8, binding.SLOT_DTYPE)]))   # blocks after the end
+        bad(lambda sl: put(sl, 0, "y", binding.REG_SWITCH))                     # the first requests are missing
+        bad(lambda sl: put(sl, g, "x", 9 << 8))                                 # no such kind
+        moved = good.copy()                                                     # a switch slot away from a block's head
+        moved[[sw, sw + 1]] = moved[[sw + 1, sw]]
+        bad(lambda sl: moved)
+    bad_full = binding.a2cid_plan_registers(n, b, coef, full=False)["slots"]
+    with pytest.raises(a2.A2cidError):                                          # read with the other block layout
+        binding.a2cid_check_registers(n, bad_full, True)
+    # nine gradient events in one chunk: index 8 of a set of 8 registers
+    ops = np.zeros(9, binding.OP_DTYPE)
+    ops["kind"], ops["i"], ops["j"], ops["t"], ops["gamma"] = binding.KIND_GRADIENT, np.arange(9), -1, 1.0, 0.1
+    nine = binding.Batch(ops, [0, 9])
+    _, c9 = binding.a2cid_plan_batch(n, u, v, 1.0, 0.7, np.zeros(n), nine)
+    sl = binding.a2cid_plan_registers(n, nine, c9)["slots"]
+    binding.a2cid_check_registers(n, sl)
+    assert len(sl) == 40                   # two requests, eight events, the switch block, the ninth event and the end
+    merged = np.concatenate([sl[:24], sl[32:]])                                 # ... without the switch block
+    with pytest.raises(a2.A2cidError):
+        binding.a2cid_check_registers(n, merged)
+    s.close()
+
+
 def test_register_programmes_on_arbitrary_small_batches():
     """Property test: whatever the batch and the programme length, the launches together apply every operation once,
     in the batch's order, with the inputs of the right gradient event in the registers."""
