@@ -701,3 +701,67 @@ def test_accelerated_parameters_reach_a_tighter_neighbourhood_of_the_optimum_on_
         level[label] = float(np.mean(dist[2:]))
         w.close()
     assert level["accelerated"] < 0.8 * level["baseline"]
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_register_file_kernel_on_hand_made_batches_bit_for_bit(order):
+    """Batches the schedulers never produce: gossip only, gradient events only (several chunks of inputs), every
+    combination of present and absent xi, c, h with zero and non-zero slope, a trailing mix; the register-file kernel
+    (all three forms: no centres, centres, centres and curvatures) against the walk kernel, bit for bit."""
+    from paper_2306_08289_amd import binding
+    n, d = 12, 64 * 3 + 17
+    ld = (d + 3) // 4 * 4
+    u = [i for i in range(n) for j in range(i + 1, n)]
+    v = [j for i in range(n) for j in range(i + 1, n)]
+    rng = np.random.default_rng(20 + order)
+    dev = torch.device("cuda:0")
+    x0 = torch.tensor(rng.standard_normal((n, ld)), dtype=torch.float32, device=dev)
+    xt0 = torch.tensor(rng.standard_normal((n, ld)), dtype=torch.float32, device=dev)
+    pool = torch.tensor(rng.standard_normal((6, ld)), dtype=torch.float32, device=dev)      # rows to use as xi, c
+    hpool = torch.tensor(0.25 + rng.random((3, ld)), dtype=torch.float32, device=dev)       # rows to use as h
+
+    def gossip_level(t):
+        perm = rng.permutation(n)
+        return [dict(t=t, kind=binding.KIND_GOSSIP, i=int(min(a, b)), j=int(max(a, b))) for a, b in zip(perm[0::2], perm[1::2])]
+
+    def gradient_level(t, combos):
+        ops = []
+        for w, (has_xi, has_c, has_h, slope) in zip(rng.permutation(n), combos):
+            ops.append(dict(t=t, kind=binding.KIND_GRADIENT, i=int(w), j=-1, gamma=0.05, gscale=slope,
+                            xi=pool[int(rng.integers(3))].data_ptr() if has_xi else 0,
+                            c=pool[3 + int(rng.integers(3))].data_ptr() if has_c else 0,
+                            h=hpool[int(rng.integers(3))].data_ptr() if has_h else 0))
+        return ops
+
+    every = [(a, b, c, s) for a in (0, 1) for b in (0, 1) for c in (0, 1) for s in (0.0, 0.7)]
+    plans = {
+        "gossip only": [gossip_level(0.1 * (k + 1)) for k in range(30)],
+        "gradient events only, no centres": [gradient_level(0.1 * (k + 1), [(k % 2, 0, 0, 0.3)] * 10) for k in range(5)],
+        "centres, no curvatures": [gradient_level(0.2, [(1, 1, 0, 0.7)] * 9), gossip_level(0.3),
+                                   gradient_level(0.4, [(0, 1, 0, 0.7), (1, 0, 0, 0.7), (1, 1, 0, 0.0)] * 4)],
+        "every combination": [gradient_level(0.1, every[:12]), gossip_level(0.2), gradient_level(0.3, every[4:]),
+                              gossip_level(0.35), gradient_level(0.4, every[:8])],
+    }
+    for what, levels in plans.items():
+        _say(f"hand-made batch: {what}, order {order}")
+        ops = np.zeros(sum(len(l) for l in levels), binding.OP_DTYPE)
+        off, k = [0], 0
+        for level in levels:
+            for op in level:
+                for name, value in op.items():
+                    ops[name][k] = value
+                k += 1
+            off.append(k)
+        results = []
+        for mode in (1, 4):
+            x, xt = x0.clone(), xt0.clone()
+            eng = binding.Engine(x, xt, d, u, v, 1.0, 0.4, 0.5, 0.8)
+            eng.set_tuning(1, 0, 256, mode)
+            eng.set_order(order)
+            eng.apply_events(binding.Batch(ops.copy(), off, t_sync=float(ops["t"].max()) + 0.5))
+            torch.cuda.synchronize()
+            results.append((x.cpu().numpy().view(np.uint32), xt.cpu().numpy().view(np.uint32), eng.times()))
+            eng.close()
+        for a, b in zip(*results):
+            assert np.array_equal(a, b), what
+        assert not np.array_equal(results[0][0][:, :d], x0.cpu().numpy().view(np.uint32)[:, :d])     # something happened
