@@ -800,8 +800,8 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 // the forms the compiler itself emits for dynamically indexed vectors.
 //
 // The operation loop is one asm statement with a fixed register map, because the register allocator cannot be made
-// to keep four 32-register blocks in place across compiler-visible control flow (the row loads before it and the row
-// stores after it are two more statements on the same pinned registers):
+// to keep four 32-register blocks in place across compiler-visible control flow (it begins with the row loads; the
+// row stores after it are a second statement on the same pinned registers):
 //   v[0:63] x, v[64:127] xt of the 64 workers (the statement's in/out operands, pinned by their constraints)
 //   v[128:135], v[136:143]   the two sets of gradient inputs xi (kRegChunk events each)
 //   with centres: v[144:151], v[152:159] the sets of centres c; with curvatures also v[160:167], v[168:175] for h
@@ -1031,6 +1031,7 @@ __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
 // way round; scalar loads return in no fixed order, so the wait for a block comes before the next fetch is issued.
 // VARIANT: PLAIN, HC or FULL (pasted into macro names).
 #define A2R_PROGRAMME(TB, GOSSIP, GRAD, AT, VARIANT)                                                                \
+    A2R_ROWS(A2R_LD1)                                                                                               \
     "s_mov_b32 s28, 0\n\t"                                                                                          \
     "s_mov_b32 s29, 0\n\t"                                                                                          \
     "s_mov_b32 s30, 0\n\t"                                                                                          \
@@ -1128,26 +1129,21 @@ __global__ __launch_bounds__(64) void regfile_kernel(float *__restrict__ x, floa
     const uint32_t lane_in = valid ? lane : 0u;             // loads of lanes past the end read the tile's first column
     const uint32_t voff = (uint32_t)(col0 + lane_in) * 4u;  // byte offset of the lane's column in a row (d <= 2^29)
 
-    // The loads of this statement are not waited for here: the operation loop below issues its first requests and
-    // then waits for everything (nothing but these four values, pinned to the same registers there, reads them).
+    // The statement below loads the rows of the tile (A2R_ROWS), issues the first requests of gradient inputs, waits
+    // for all of it and runs the programme; the four values it defines are the state registers.
     v32f X0, X1, T0, T1;
     const uintptr_t xb = reg_uniform(x), tb = reg_uniform(xt);     // the lane's offset counts from the start of a row
     const uint64_t step = (uint64_t)ld * 4u;
     const uint32_t step_lo = (uint32_t)step, step_hi = (uint32_t)(step >> 32);
-    {
-        const uint64_t first = (uint64_t)(touched ? __builtin_ctzll(touched) : 0) * step;
-        const uintptr_t p0 = xb + first, q0 = tb + first;
-        asm volatile(A2R_ROWS(A2R_LD1)
-                     : "=&{v[0:31]}"(X0), "=&{v[32:63]}"(X1), "=&{v[64:95]}"(T0), "=&{v[96:127]}"(T1)
-                     : [xb] "s"(xb), [tb] "s"(tb), [p0] "s"(p0), [q0] "s"(q0), [slo] "s"(step_lo), [shi] "s"(step_hi),
-                       [touched] "s"(touched), [voff] "v"(voff)
-                     : "s40", "s41", "s42", "s43", "s44", "s45", "s46", "s47", "scc", "memory");
-    }
+    const uint64_t first = (uint64_t)(touched ? __builtin_ctzll(touched) : 0) * step;
+    const uintptr_t p0 = xb + first, q0 = tb + first;
     const float neg_alpha = -alpha, neg_alpha_t = -alpha_t;
 #define A2R_OPERANDS                                                                                                \
-    : "+{v[0:31]}"(X0), "+{v[32:63]}"(X1), "+{v[64:95]}"(T0), "+{v[96:127]}"(T1)                                    \
+    : "=&{v[0:31]}"(X0), "=&{v[32:63]}"(X1), "=&{v[64:95]}"(T0), "=&{v[96:127]}"(T1)                                \
     : [prog] "s"(recs), [nbytes] "s"(n_bytes), [voff] "v"(voff),                                                    \
-      [al] "s"(alpha), [nal] "s"(neg_alpha), [alt] "s"(alpha_t), [nalt] "s"(neg_alpha_t)
+      [al] "s"(alpha), [nal] "s"(neg_alpha), [alt] "s"(alpha_t), [nalt] "s"(neg_alpha_t),                           \
+      [xb] "s"(xb), [tb] "s"(tb), [p0] "s"(p0), [q0] "s"(q0), [slo] "s"(step_lo), [shi] "s"(step_hi),               \
+      [touched] "s"(touched)
     if constexpr (VARIANT == 0) {
         if constexpr (!PRE)
             asm volatile(A2R_PROGRAMME("144", A2R_GOSSIP_0, A2R_GRAD_PLAIN, 2, PLAIN) A2R_OPERANDS
