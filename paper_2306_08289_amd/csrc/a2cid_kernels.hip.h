@@ -824,7 +824,6 @@ __global__ __launch_bounds__(64 * W) void resident_kernel(float *__restrict__ x,
 // Valid only while every gradient input of the batch is final when the batch is submitted, like the resident kernel.
 // ------------------------------------------------------------------------------------------
 typedef float v32f __attribute__((ext_vector_type(32)));
-typedef __attribute__((address_space(1))) float *global_out_f32;
 
 // A uniform address as the compiler must take it: a value in scalar registers.
 __device__ __forceinline__ uintptr_t reg_uniform(const float *p) {
